@@ -1,0 +1,178 @@
+/*
+ * TEST INFRASTRUCTURE -- not part of the product path.
+ *
+ * Plain CPU evaluation of the weighted critical path of a data-flow DAG under
+ * candidate device partitions.  It is the definition written out: one partition
+ * at a time, one vertex at a time, int64 throughout, partition-major arrays.
+ * It shares no code, header, table or constant with the GPU library; only the
+ * tests, the smoke check and the benchmark's CPU-baseline leg may call it.
+ *
+ * What is computed (paper, section 2 for the model; section 4.1 and its
+ * equation for PCT; section 3.2 and its two rank equations; section 2's
+ * remark on the artificial final sink):
+ *
+ *   w(v)  = ceil( c(v) / s[p(v)] )                     execution time of v on its device
+ *   x(e)  = 0                      if p(u) == p(v)      transfer time along e = (u -> v)
+ *         = ceil( t(e) / B[p(u)][p(v)] )  otherwise
+ *   b(v)  = w(v) + max over out-edges e=(v->u) of ( x(e) + b(u) ),  empty max = 0
+ *           -- the paper's PCT: a sink's value is its own execution time
+ *   tl(v) = max over in-edges e=(u->v) of ( tl(u) + w(u) + x(e) ),  empty max = 0
+ *           -- the downward rank without the vertex's own term
+ *   CP    = max_v b(v)   (= start time of the zero-cost final sink joined to all sinks)
+ *   mask(v) = [ tl(v) + b(v) == CP ]
+ *
+ * Integer ticks: each term is rounded up on its own, ceil(a/d) = (a + d - 1) div d
+ * for a >= 0, d >= 1.
+ *
+ * The vertex order comes from Kahn's algorithm on the successor lists; the
+ * level index used by the GPU path is never consulted.  tl is pushed along
+ * out-edges, so the predecessor arrays are not consulted either.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int64_t cp_oracle_ceil_div(int64_t a, int64_t d) { return (a + d - 1) / d; }
+
+/* section 2: execution time = complexity / speed of the device */
+int64_t cp_oracle_vertex_cost(int64_t c, int64_t s) { return cp_oracle_ceil_div(c, s); }
+
+/* section 4.1: transfer time is 0 on one device, else volume / rate between the two;
+ * bandwidth is k x k, row = device of the edge's source vertex */
+int64_t cp_oracle_edge_cost(int64_t t, int pu, int pv, const int64_t *bandwidth, int k)
+{
+    if (pu == pv) return 0;
+    return cp_oracle_ceil_div(t, bandwidth[(size_t)pu * k + pv]);
+}
+
+/* Kahn's algorithm on successor lists.  order[n] receives the vertices, sources
+ * first.  Returns 0, or -1 if the graph has a cycle. */
+int cp_oracle_topo_order(int32_t n, const int32_t *succ_ptr, const int32_t *succ_idx, int32_t *order)
+{
+    int32_t *indeg = (int32_t *)calloc((size_t)n + 1, sizeof(int32_t));
+    if (!indeg) return -2;
+    for (int32_t v = 0; v < n; ++v)
+        for (int32_t e = succ_ptr[v]; e < succ_ptr[v + 1]; ++e) indeg[succ_idx[e]]++;
+    int32_t head = 0, tail = 0;
+    for (int32_t v = 0; v < n; ++v)
+        if (indeg[v] == 0) order[tail++] = v;
+    while (head < tail) {
+        int32_t v = order[head++];
+        for (int32_t e = succ_ptr[v]; e < succ_ptr[v + 1]; ++e) {
+            int32_t u = succ_idx[e];
+            if (--indeg[u] == 0) order[tail++] = u;
+        }
+    }
+    free(indeg);
+    return tail == n ? 0 : -1;
+}
+
+/* One partition.  p[n] device of each vertex; outputs b[n], tl[n], mask[n] (any may
+ * be NULL except that b and tl are needed internally, so scratch is used). */
+static int64_t eval_one(int32_t n, const int32_t *succ_ptr, const int32_t *succ_idx,
+                        const int64_t *succ_t, const int64_t *c, int k, const int64_t *speeds,
+                        const int64_t *bandwidth, const int32_t *order, const uint8_t *p,
+                        int64_t *w, int64_t *b, int64_t *tl, uint8_t *mask)
+{
+    for (int32_t v = 0; v < n; ++v) w[v] = cp_oracle_vertex_cost(c[v], speeds[p[v]]);
+
+    /* b-level: sinks first */
+    for (int32_t i = n - 1; i >= 0; --i) {
+        int32_t v = order[i];
+        int64_t best = 0;
+        for (int32_t e = succ_ptr[v]; e < succ_ptr[v + 1]; ++e) {
+            int32_t u = succ_idx[e];
+            int64_t cand = cp_oracle_edge_cost(succ_t[e], p[v], p[u], bandwidth, k) + b[u];
+            if (cand > best) best = cand;
+        }
+        b[v] = w[v] + best;
+    }
+
+    /* t-level: sources first, pushed along out-edges */
+    for (int32_t v = 0; v < n; ++v) tl[v] = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        int32_t v = order[i];
+        for (int32_t e = succ_ptr[v]; e < succ_ptr[v + 1]; ++e) {
+            int32_t u = succ_idx[e];
+            int64_t cand = tl[v] + w[v] + cp_oracle_edge_cost(succ_t[e], p[v], p[u], bandwidth, k);
+            if (cand > tl[u]) tl[u] = cand;
+        }
+    }
+
+    int64_t cp = 0;
+    for (int32_t v = 0; v < n; ++v)
+        if (b[v] > cp) cp = b[v];
+    if (mask)
+        for (int32_t v = 0; v < n; ++v) mask[v] = (uint8_t)(tl[v] + b[v] == cp);
+    return cp;
+}
+
+/*
+ * All partitions.  assignments is [P][n]; cp_out [P]; b_out, tl_out [P][n] int64;
+ * mask_out [P][n] bytes (0/1).  b_out, tl_out, mask_out may be NULL.
+ * threads <= 0 means one thread.  Returns 0; -1 cycle; -2 out of memory;
+ * -3 bad argument (device id >= k, speed < 1, off-diagonal bandwidth < 1, negative weight).
+ * *threads_used (may be NULL) receives the number of threads that ran.
+ */
+int cp_oracle_eval(int32_t n, const int32_t *succ_ptr, const int32_t *succ_idx,
+                   const int64_t *succ_t, const int64_t *c, int k, const int64_t *speeds,
+                   const int64_t *bandwidth, int32_t P, const uint8_t *assignments,
+                   int64_t *cp_out, int64_t *b_out, int64_t *tl_out, uint8_t *mask_out,
+                   int threads, int *threads_used)
+{
+    if (n < 0 || P < 0 || k < 1 || k > 256) return -3;
+    for (int i = 0; i < k; ++i) {
+        if (speeds[i] < 1) return -3;
+        for (int j = 0; j < k; ++j)
+            if (i != j && bandwidth[(size_t)i * k + j] < 1) return -3;
+    }
+    int64_t m = n ? succ_ptr[n] : 0;
+    for (int32_t v = 0; v < n; ++v) if (c[v] < 0) return -3;
+    for (int64_t e = 0; e < m; ++e) if (succ_t[e] < 0) return -3;
+    for (int64_t i = 0; i < (int64_t)P * n; ++i) if (assignments[i] >= k) return -3;
+
+    int32_t *order = (int32_t *)malloc(((size_t)n + 1) * sizeof(int32_t));
+    if (!order) return -2;
+    int rc = cp_oracle_topo_order(n, succ_ptr, succ_idx, order);
+    if (rc) { free(order); return rc; }
+
+    if (threads < 1) threads = 1;
+    int used = 1, failed = 0;
+#ifdef _OPENMP
+#pragma omp parallel num_threads(threads)
+#endif
+    {
+#ifdef _OPENMP
+#pragma omp single
+        used = omp_get_num_threads();
+#endif
+        int64_t *w = (int64_t *)malloc(((size_t)n + 1) * sizeof(int64_t));
+        int64_t *bs = b_out ? NULL : (int64_t *)malloc(((size_t)n + 1) * sizeof(int64_t));
+        int64_t *ts = tl_out ? NULL : (int64_t *)malloc(((size_t)n + 1) * sizeof(int64_t));
+        if (!w || (!b_out && !bs) || (!tl_out && !ts)) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
+            failed = 1;
+        }
+#ifdef _OPENMP
+#pragma omp barrier
+#pragma omp for schedule(dynamic, 1)
+#endif
+        for (int32_t j = 0; j < P; ++j) {
+            if (failed) continue;
+            int64_t *b = b_out ? b_out + (size_t)j * n : bs;
+            int64_t *tl = tl_out ? tl_out + (size_t)j * n : ts;
+            uint8_t *mk = mask_out ? mask_out + (size_t)j * n : NULL;
+            cp_out[j] = eval_one(n, succ_ptr, succ_idx, succ_t, c, k, speeds, bandwidth, order,
+                                 assignments + (size_t)j * n, w, b, tl, mk);
+        }
+        free(w); free(bs); free(ts);
+    }
+    free(order);
+    if (threads_used) *threads_used = used;
+    return failed ? -2 : 0;
+}

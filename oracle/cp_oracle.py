@@ -1,0 +1,119 @@
+"""TEST INFRASTRUCTURE: ctypes access to the C oracle (``cp_oracle.c``).
+
+The arithmetic lives in the C file; this module only marshals numpy arrays.
+"""
+from __future__ import annotations
+
+import ctypes as C
+
+import numpy as np
+
+from .build import build_oracle
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = C.CDLL(build_oracle(force=False))
+        i64p, i32p, u8p = C.POINTER(C.c_int64), C.POINTER(C.c_int32), C.POINTER(C.c_uint8)
+        lib.cp_oracle_ceil_div.restype = C.c_int64
+        lib.cp_oracle_ceil_div.argtypes = [C.c_int64, C.c_int64]
+        lib.cp_oracle_vertex_cost.restype = C.c_int64
+        lib.cp_oracle_vertex_cost.argtypes = [C.c_int64, C.c_int64]
+        lib.cp_oracle_edge_cost.restype = C.c_int64
+        lib.cp_oracle_edge_cost.argtypes = [C.c_int64, C.c_int, C.c_int, i64p, C.c_int]
+        lib.cp_oracle_topo_order.restype = C.c_int
+        lib.cp_oracle_topo_order.argtypes = [C.c_int32, i32p, i32p, i32p]
+        lib.cp_oracle_eval.restype = C.c_int
+        lib.cp_oracle_eval.argtypes = [C.c_int32, i32p, i32p, i64p, i64p, C.c_int, i64p, i64p,
+                                       C.c_int32, u8p, i64p, i64p, i64p, u8p, C.c_int,
+                                       C.POINTER(C.c_int)]
+        _lib = lib
+    return _lib
+
+
+def _ptr(a, ctype):
+    return a.ctypes.data_as(C.POINTER(ctype))
+
+
+def vertex_cost(c: int, s: int) -> int:
+    return int(_load().cp_oracle_vertex_cost(int(c), int(s)))
+
+
+def edge_cost(t: int, pu: int, pv: int, bandwidth) -> int:
+    bw = np.ascontiguousarray(bandwidth, dtype=np.int64)
+    return int(_load().cp_oracle_edge_cost(int(t), int(pu), int(pv), _ptr(bw, C.c_int64), bw.shape[0]))
+
+
+def topo_order(n, succ_ptr, succ_idx):
+    sp = np.ascontiguousarray(succ_ptr, dtype=np.int32)
+    si = np.ascontiguousarray(succ_idx, dtype=np.int32)
+    if si.size == 0:
+        si = np.zeros(1, dtype=np.int32)
+    order = np.empty(n + 1, dtype=np.int32)
+    rc = _load().cp_oracle_topo_order(n, _ptr(sp, C.c_int32), _ptr(si, C.c_int32), _ptr(order, C.c_int32))
+    if rc:
+        raise ValueError("graph has a cycle")
+    return order[:n]
+
+
+def evaluate(n, succ_ptr, succ_idx, succ_t, c, speeds, bandwidth, assignments,
+             want=("cp", "b", "tl", "mask"), threads=1):
+    """Evaluate every row of ``assignments[P][n]``.
+
+    Returns a dict with ``cp`` int64 [P] and, if asked for, ``b``, ``tl`` int64
+    [P][n] and ``mask`` bool [P][n] (partition-major), plus ``threads`` = the
+    number of threads that ran.
+    """
+    lib = _load()
+    sp = np.ascontiguousarray(succ_ptr, dtype=np.int32)
+    si = np.ascontiguousarray(succ_idx, dtype=np.int32)
+    st = np.ascontiguousarray(succ_t, dtype=np.int64)
+    if si.size == 0:  # keep the pointers valid for m = 0
+        si = np.zeros(1, dtype=np.int32)
+        st = np.zeros(1, dtype=np.int64)
+    cc = np.ascontiguousarray(c, dtype=np.int64)
+    s = np.ascontiguousarray(speeds, dtype=np.int64)
+    bw = np.ascontiguousarray(bandwidth, dtype=np.int64)
+    a = np.ascontiguousarray(assignments, dtype=np.uint8)
+    k = int(s.shape[0])
+    assert bw.shape == (k, k), "bandwidth must be k x k"
+    assert a.ndim == 2 and a.shape[1] == n, "assignments must be [P][n]"
+    assert sp.shape[0] == n + 1
+    P = int(a.shape[0])
+    cp = np.zeros(P, dtype=np.int64)
+    b = np.zeros((P, n), dtype=np.int64) if "b" in want else None
+    tl = np.zeros((P, n), dtype=np.int64) if "tl" in want else None
+    mask = np.zeros((P, n), dtype=np.uint8) if "mask" in want else None
+    used = C.c_int(0)
+    null64 = C.POINTER(C.c_int64)()
+    null8 = C.POINTER(C.c_uint8)()
+    rc = lib.cp_oracle_eval(
+        n, _ptr(sp, C.c_int32), _ptr(si, C.c_int32), _ptr(st, C.c_int64), _ptr(cc, C.c_int64),
+        k, _ptr(s, C.c_int64), _ptr(bw, C.c_int64), P, _ptr(a, C.c_uint8), _ptr(cp, C.c_int64),
+        _ptr(b, C.c_int64) if b is not None else null64,
+        _ptr(tl, C.c_int64) if tl is not None else null64,
+        _ptr(mask, C.c_uint8) if mask is not None else null8,
+        int(threads), C.byref(used))
+    if rc == -1:
+        raise ValueError("graph has a cycle")
+    if rc == -3:
+        raise ValueError("bad argument (device id >= k, speed < 1, bandwidth < 1 or negative weight)")
+    if rc:
+        raise MemoryError("oracle ran out of memory")
+    out = {"cp": cp, "threads": int(used.value)}
+    if b is not None:
+        out["b"] = b
+    if tl is not None:
+        out["tl"] = tl
+    if mask is not None:
+        out["mask"] = mask.astype(bool)
+    return out
+
+
+def evaluate_workload(w, want=("cp", "b", "tl", "mask"), threads=1, partitions=None):
+    a = w.assignments if partitions is None else w.assignments[partitions]
+    return evaluate(w.n, w.succ_ptr, w.succ_idx, w.succ_t, w.c, w.speeds, w.bandwidth, a,
+                    want=want, threads=threads)
