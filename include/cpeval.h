@@ -1,0 +1,202 @@
+/*
+ * cpeval -- batched evaluation of the weighted critical path of a data-flow DAG
+ * under many candidate device partitions, on one AMD MI355X (gfx950).
+ *
+ * Model (paper, section 2): a DAG G=(V,E) with n vertices and m edges, vertex
+ * complexity c(v) >= 0, edge volume t(e) >= 0, k devices of speed s[i] >= 1 and a
+ * k x k bandwidth matrix B (row = device of the edge's source vertex, column =
+ * device of its target; the diagonal is never read).  A partition p: V -> D is
+ * one row of `assignments`.  Costs are integer ticks, each term rounded up on
+ * its own:
+ *
+ *   w(v)  = ceil(c(v) / s[p(v)])                             (section 2: time = complexity / speed)
+ *   x(e)  = 0 if p(u) == p(v), else ceil(t(e) / B[p(u)][p(v)])   for e = (u -> v)   (section 4.1)
+ *   b(v)  = w(v) + max over out-edges (x(e) + b(head)), empty max = 0
+ *           (section 4.1, the PCT equation; a sink's value is its own execution time)
+ *   tl(v) = max over in-edges (tl(tail) + w(tail) + x(e)), empty max = 0
+ *           (section 3.2, the downward rank without the vertex's own term)
+ *   CP    = max_v b(v)     (section 2: the start time of a zero-cost final sink
+ *                           joined to every sink by zero-cost edges)
+ *   mask(v) = [tl(v) + b(v) == CP]    (the union of all critical paths, section 3.2.2)
+ *
+ * Multi-edges are allowed (the costlier one decides), c = 0 and t = 0 are allowed,
+ * m = 0 is allowed.  B need not be symmetric.
+ *
+ * Calling convention: plain C, no exceptions, no aborts.  Every function returns
+ * CP_OK (0) or a negative CP_ERR_* code.  "host" pointers are ordinary memory that
+ * is only read during the call; "device" pointers are HIP device memory owned by
+ * the caller.  The library never allocates or frees device memory.  `stream` is
+ * a hipStream_t passed as void* (NULL = the default stream).
+ */
+#ifndef CPEVAL_H
+#define CPEVAL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- error codes (return values) ---- */
+#define CP_OK              0
+#define CP_ERR_NULL       (-1)   /* a required pointer is NULL */
+#define CP_ERR_SIZE       (-2)   /* n < 1, m < 0, L < 1, batch < 1, k < 1 or k > 255 */
+#define CP_ERR_CSR        (-3)   /* non-monotone ptr, index out of range, succ/pred mismatch */
+#define CP_ERR_LEVELS     (-4)   /* level index is not a partition of V, or an edge does not go to a higher level */
+#define CP_ERR_NEGATIVE   (-5)   /* c(v) < 0 or t(e) < 0 */
+#define CP_ERR_SPEED      (-6)   /* s[i] < 1 */
+#define CP_ERR_BANDWIDTH  (-7)   /* off-diagonal B[i][j] < 1 */
+#define CP_ERR_OVERFLOW   (-8)   /* longest raw path >= 2^62, or 32-bit ticks asked for but not provably safe */
+#define CP_ERR_WORKSPACE  (-9)   /* workspace or blob too small or misaligned */
+#define CP_ERR_HIP        (-10)  /* a HIP runtime call failed */
+#define CP_ERR_STATE      (-11)  /* graph not uploaded yet, or profile slot out of range */
+#define CP_ERR_ARG        (-12)  /* unknown enum value, or an output requested without the outputs it depends on */
+#define CP_ERR_ALLOC      (-13)  /* host allocation failed */
+
+/* ---- value written to *status_out by the device ---- */
+#define CP_STATUS_OK             0
+#define CP_STATUS_BAD_DEVICE_ID  1   /* some assignments entry is >= k (it was treated as device 0) */
+
+/* ---- enums ---- */
+#define CP_TICK_I32  4   /* b-level / t-level stored as int32 (only if the graph's bound allows) */
+#define CP_TICK_I64  8   /* stored as int64 */
+
+#define CP_ASSIGN_PARTITION_MAJOR 0   /* assignments[batch][n] */
+#define CP_ASSIGN_VERTEX_MAJOR    1   /* assignments[n][batch] */
+
+#define CP_PLAN_AUTO             0
+#define CP_PLAN_WAVE_COLUMN      1   /* one wavefront = one vertex x 64 partitions; one launch per level */
+#define CP_PLAN_RESIDENT_WINDOW  2   /* one workgroup = one partition; recent levels kept in LDS; one launch per sweep */
+
+/* stages of one cp_eval call, in the order they run; also the index into cp_profile_read's output */
+#define CP_STAGE_PREP    0   /* clear outputs, cost tables, assignment transpose */
+#define CP_STAGE_BLEVEL  1   /* b-level sweep, last level to first */
+#define CP_STAGE_CP      2   /* critical-path length per partition */
+#define CP_STAGE_TLEVEL  3   /* t-level sweep, first level to last */
+#define CP_STAGE_MASK    4   /* critical-vertex mask */
+#define CP_NUM_STAGES    5
+
+typedef struct cp_graph cp_graph;
+typedef struct cp_profile cp_profile;
+
+typedef struct cp_graph_info {
+    int32_t n, L;
+    int64_t m;
+    int32_t max_out_degree, max_in_degree, max_level_width;
+    int32_t num_sources, num_sinks;
+    int64_t max_c, max_t;
+    int64_t raw_path_bound;      /* U0: longest path with w = c and x = t; every tick value is <= U0 */
+    int32_t min_tick_bytes;      /* 4 if U0 < 2^31, else 8 */
+    int32_t window_ok;           /* 1 if the resident-window plan can run this graph */
+    int32_t window_slots_b;      /* LDS slots the b-level sweep needs under that plan */
+    int32_t window_slots_t;      /* ... and the t-level sweep */
+    int32_t auto_plan;           /* plan CP_PLAN_AUTO resolves to */
+    int32_t uploaded;            /* 1 after cp_graph_upload */
+    uint64_t blob_bytes;
+} cp_graph_info;
+
+/*
+ * Validate a graph and pack it (host work only; no GPU is touched).
+ *
+ *   succ_ptr[n+1], succ_idx[m], succ_t[m]   successor CSR: out-edges of v are
+ *       succ_ptr[v] .. succ_ptr[v+1]-1, succ_idx = head vertex, succ_t = t(e)
+ *   pred_ptr[n+1], pred_idx[m], pred_eid[m] predecessor CSR: pred_idx = tail vertex,
+ *       pred_eid = position of the same edge in the successor arrays
+ *   c[n]                                    vertex complexity
+ *   level_ptr[L+1], level_vtx[n]            vertices grouped by topological level;
+ *       any grouping in which every edge goes to a strictly higher level is accepted
+ *
+ * All arrays are host memory, borrowed for the call.  succ_idx, succ_t, pred_idx,
+ * pred_eid may be NULL when m == 0.  On success *out owns a host object to be
+ * released with cp_graph_destroy.
+ * Errors: CP_ERR_NULL, CP_ERR_SIZE, CP_ERR_CSR, CP_ERR_LEVELS, CP_ERR_NEGATIVE,
+ * CP_ERR_OVERFLOW (longest raw path >= 2^62), CP_ERR_ALLOC.
+ */
+int cp_graph_create(int32_t n, int64_t m, int32_t L,
+                    const int32_t *succ_ptr, const int32_t *succ_idx, const int64_t *succ_t,
+                    const int32_t *pred_ptr, const int32_t *pred_idx, const int32_t *pred_eid,
+                    const int64_t *c,
+                    const int32_t *level_ptr, const int32_t *level_vtx,
+                    cp_graph **out);
+
+/* Facts about a created graph. */
+int cp_graph_get_info(const cp_graph *g, cp_graph_info *out);
+
+/*
+ * Copy the packed graph into caller-owned device memory (>= info.blob_bytes bytes,
+ * 256-byte aligned) and wait for the copy.  The memory must stay valid and
+ * unmodified until cp_graph_destroy.  Errors: CP_ERR_NULL, CP_ERR_WORKSPACE, CP_ERR_HIP.
+ */
+int cp_graph_upload(cp_graph *g, void *device_blob, size_t blob_bytes, void *stream);
+
+/* Release the host object (the device blob stays the caller's).  NULL is accepted. */
+void cp_graph_destroy(cp_graph *g);
+
+/*
+ * Bytes of device workspace cp_eval needs for this batch size, device count,
+ * assignment layout and plan (CP_PLAN_AUTO allowed).
+ */
+int cp_eval_workspace_bytes(const cp_graph *g, int32_t batch, int32_t k, int assign_layout,
+                            int plan, size_t *out_bytes);
+
+/*
+ * Evaluate `batch` partitions.  Only enqueues work on `stream`; it does not wait.
+ *
+ *   assignments   device, uint8, [batch][n] or [n][batch] per assign_layout; entries < k
+ *   speeds        host, int64 [k], each >= 1
+ *   bandwidth     host, int64 [k][k], row = source vertex's device; off-diagonal >= 1
+ *   workspace     device, >= cp_eval_workspace_bytes, 256-byte aligned; contents are scratch.
+ *                 Two calls that may overlap in time need distinct workspaces.
+ *   cp_out        device int64 [batch], or NULL
+ *   blevel_out    device ticks [n][batch] (vertex-major: partition j of vertex v at v*batch + j), or NULL
+ *   tlevel_out    device ticks [n][batch], or NULL
+ *   mask_out      device uint64 [n][ceil(batch/64)]; bit i of word q of row v is partition 64q+i; or NULL
+ *   tick_dtype    CP_TICK_I32 or CP_TICK_I64: element type of blevel_out / tlevel_out
+ *   plan          CP_PLAN_AUTO, or force one (CP_ERR_ARG if it cannot run this graph / cost model)
+ *   status_out    device int32, required: CP_STATUS_* after the stream has drained
+ *   profile       NULL, or a profile whose next slot receives this call's stage timestamps
+ *
+ * Dependencies between outputs: cp_out needs blevel_out; mask_out needs cp_out,
+ * blevel_out and tlevel_out (CP_ERR_ARG otherwise).
+ * Errors: CP_ERR_NULL, CP_ERR_SIZE, CP_ERR_SPEED, CP_ERR_BANDWIDTH, CP_ERR_OVERFLOW
+ * (CP_TICK_I32 with a bound >= 2^31), CP_ERR_WORKSPACE, CP_ERR_STATE, CP_ERR_ARG, CP_ERR_HIP.
+ */
+int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
+            const uint8_t *assignments, int assign_layout,
+            const int64_t *speeds, const int64_t *bandwidth,
+            void *workspace, size_t workspace_bytes, void *stream,
+            int64_t *cp_out, void *blevel_out, void *tlevel_out, uint64_t *mask_out,
+            int tick_dtype, int plan, int32_t *status_out, cp_profile *profile);
+
+/*
+ * Stage timing with HIP events recorded on the stream the kernels run on.
+ * A profile holds `slots` sets of CP_NUM_STAGES+1 events; every cp_eval call that
+ * is given the profile fills the next slot (CP_ERR_STATE when full).
+ */
+int cp_profile_create(int32_t slots, cp_profile **out);
+int cp_profile_reset(cp_profile *p);                       /* next call fills slot 0 again */
+int cp_profile_count(const cp_profile *p, int32_t *out);   /* slots filled so far */
+/* Milliseconds per stage for one filled slot; the stream must have drained.
+ * sweep_launches[0], [1] (may be NULL) receive the number of kernel launches the
+ * b-level and t-level stages made. */
+int cp_profile_read(const cp_profile *p, int32_t slot, float ms_out[CP_NUM_STAGES],
+                    int32_t sweep_launches[2]);
+void cp_profile_destroy(cp_profile *p);
+
+/*
+ * Diagnostic: the 32-bit multiply-shift constants the kernels would use for
+ * ceil(a / divisor) with 0 <= a <= max_dividend:
+ *     ceil(a / divisor) == ((a + *dm1) * (uint64)*mul + (a + *dm1)) >> 32.
+ * Returns 1 and fills mul, dm1 if that form is exact over the whole range, 0 if it
+ * is not (the kernels then divide plainly), or a negative CP_ERR_* code.
+ */
+int cp_cost_magic(int64_t divisor, int64_t max_dividend, uint32_t *mul, uint32_t *dm1);
+
+/* Human-readable text for a CP_ERR_* code (static storage). */
+const char *cp_error_string(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CPEVAL_H */

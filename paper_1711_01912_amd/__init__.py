@@ -1,0 +1,18 @@
+"""Batched critical-path evaluation of data-flow DAGs on AMD MI355X.
+
+The work is done by ``libcpeval.so`` (hand-written HIP for gfx950, C ABI in
+``include/cpeval.h``).  This package is the thin binding: argument marshalling
+with ctypes, PyTorch tensors for device memory and streams.
+"""
+from .binding import (  # noqa: F401
+    CpError,
+    CpGraph,
+    CpProfile,
+    PLAN_AUTO,
+    PLAN_RESIDENT_WINDOW,
+    PLAN_WAVE_COLUMN,
+    cost_magic,
+    cp_eval,
+    error_string,
+    load_library,
+)

@@ -1,0 +1,319 @@
+"""ctypes binding of the C ABI in ``include/cpeval.h``.
+
+Names follow the C entry points.  Nothing is computed here: tensors are
+allocated with torch, pointers and sizes are handed to the library, and every
+step of the evaluation runs in the library's kernels.  If the shared library is
+missing the import of this module still works (so that the build can be checked
+without a GPU), but any call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libcpeval.so")
+
+TICK_I32, TICK_I64 = 4, 8
+ASSIGN_PARTITION_MAJOR, ASSIGN_VERTEX_MAJOR = 0, 1
+PLAN_AUTO, PLAN_WAVE_COLUMN, PLAN_RESIDENT_WINDOW = 0, 1, 2
+NUM_STAGES = 5
+STAGE_NAMES = ("prep", "blevel", "cp", "tlevel", "mask")
+STATUS_BAD_DEVICE_ID = 1
+
+EXPORTS = (
+    "cp_graph_create", "cp_graph_get_info", "cp_graph_upload", "cp_graph_destroy",
+    "cp_eval_workspace_bytes", "cp_eval", "cp_profile_create", "cp_profile_reset",
+    "cp_profile_count", "cp_profile_read", "cp_profile_destroy", "cp_cost_magic",
+    "cp_error_string",
+)
+
+
+class GraphInfo(C.Structure):
+    _fields_ = [
+        ("n", C.c_int32), ("L", C.c_int32), ("m", C.c_int64),
+        ("max_out_degree", C.c_int32), ("max_in_degree", C.c_int32), ("max_level_width", C.c_int32),
+        ("num_sources", C.c_int32), ("num_sinks", C.c_int32),
+        ("max_c", C.c_int64), ("max_t", C.c_int64), ("raw_path_bound", C.c_int64),
+        ("min_tick_bytes", C.c_int32), ("window_ok", C.c_int32),
+        ("window_slots_b", C.c_int32), ("window_slots_t", C.c_int32),
+        ("auto_plan", C.c_int32), ("uploaded", C.c_int32), ("blob_bytes", C.c_uint64),
+    ]
+
+    def as_dict(self):
+        return {name: int(getattr(self, name)) for name, _ in self._fields_}
+
+
+class CpError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = int(code)
+        super().__init__(f"{where}: {error_string(code)} (code {code})")
+
+
+_lib = None
+
+
+def load_library():
+    """Load ``libcpeval.so`` from the package directory; fails loudly if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    lib = C.CDLL(LIB_PATH)
+    i32p, i64p, u8p = C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_uint8)
+    vp = C.c_void_p
+    lib.cp_graph_create.restype = C.c_int
+    lib.cp_graph_create.argtypes = [C.c_int32, C.c_int64, C.c_int32, i32p, i32p, i64p, i32p, i32p,
+                                    i32p, i64p, i32p, i32p, C.POINTER(vp)]
+    lib.cp_graph_get_info.restype = C.c_int
+    lib.cp_graph_get_info.argtypes = [vp, C.POINTER(GraphInfo)]
+    lib.cp_graph_upload.restype = C.c_int
+    lib.cp_graph_upload.argtypes = [vp, vp, C.c_size_t, vp]
+    lib.cp_graph_destroy.restype = None
+    lib.cp_graph_destroy.argtypes = [vp]
+    lib.cp_eval_workspace_bytes.restype = C.c_int
+    lib.cp_eval_workspace_bytes.argtypes = [vp, C.c_int32, C.c_int32, C.c_int, C.c_int,
+                                            C.POINTER(C.c_size_t)]
+    lib.cp_eval.restype = C.c_int
+    lib.cp_eval.argtypes = [vp, C.c_int32, C.c_int32, vp, C.c_int, i64p, i64p, vp, C.c_size_t, vp,
+                            vp, vp, vp, vp, C.c_int, C.c_int, vp, vp]
+    lib.cp_profile_create.restype = C.c_int
+    lib.cp_profile_create.argtypes = [C.c_int32, C.POINTER(vp)]
+    lib.cp_profile_reset.restype = C.c_int
+    lib.cp_profile_reset.argtypes = [vp]
+    lib.cp_profile_count.restype = C.c_int
+    lib.cp_profile_count.argtypes = [vp, i32p]
+    lib.cp_profile_read.restype = C.c_int
+    lib.cp_profile_read.argtypes = [vp, C.c_int32, C.POINTER(C.c_float), i32p]
+    lib.cp_profile_destroy.restype = None
+    lib.cp_profile_destroy.argtypes = [vp]
+    lib.cp_cost_magic.restype = C.c_int
+    lib.cp_cost_magic.argtypes = [C.c_int64, C.c_int64, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
+    lib.cp_error_string.restype = C.c_char_p
+    lib.cp_error_string.argtypes = [C.c_int]
+    _lib = lib
+    return lib
+
+
+def error_string(code: int) -> str:
+    return load_library().cp_error_string(int(code)).decode()
+
+
+def cost_magic(divisor: int, max_dividend: int):
+    """(mul, dm1) of the exact multiply-shift form, or None if there is none."""
+    mul, dm1 = C.c_uint32(0), C.c_uint32(0)
+    rc = load_library().cp_cost_magic(int(divisor), int(max_dividend), C.byref(mul), C.byref(dm1))
+    if rc < 0:
+        raise CpError(rc, "cp_cost_magic")
+    return (int(mul.value), int(dm1.value)) if rc == 1 else None
+
+
+def _np_ptr(a, ctype):
+    if a is None:
+        return C.POINTER(ctype)()
+    return a.ctypes.data_as(C.POINTER(ctype))
+
+
+def _stream_ptr(stream):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(int(s.cuda_stream))
+
+
+class CpGraph:
+    """cp_graph_create (+ cp_graph_upload when a device is given)."""
+
+    def __init__(self, n, succ_ptr, succ_idx, succ_t, pred_ptr, pred_idx, pred_eid, c,
+                 level_ptr, level_vtx, device=None, m=None, L=None):
+        lib = load_library()
+        self._lib = lib
+        self._handle = C.c_void_p()
+        self.blob = None
+        a32 = lambda x: None if x is None else np.ascontiguousarray(x, dtype=np.int32)
+        a64 = lambda x: None if x is None else np.ascontiguousarray(x, dtype=np.int64)
+        sp, si, st = a32(succ_ptr), a32(succ_idx), a64(succ_t)
+        pp, pi, pe = a32(pred_ptr), a32(pred_idx), a32(pred_eid)
+        cc, lp, lv = a64(c), a32(level_ptr), a32(level_vtx)
+        if m is None:
+            m = 0 if si is None else int(si.shape[0])
+        if L is None:
+            L = int(lp.shape[0]) - 1
+        rc = lib.cp_graph_create(int(n), int(m), int(L), _np_ptr(sp, C.c_int32), _np_ptr(si, C.c_int32),
+                                 _np_ptr(st, C.c_int64), _np_ptr(pp, C.c_int32), _np_ptr(pi, C.c_int32),
+                                 _np_ptr(pe, C.c_int32), _np_ptr(cc, C.c_int64), _np_ptr(lp, C.c_int32),
+                                 _np_ptr(lv, C.c_int32), C.byref(self._handle))
+        if rc:
+            self._handle = C.c_void_p()
+            raise CpError(rc, "cp_graph_create")
+        if device is not None:
+            self.upload(device)
+
+    @classmethod
+    def from_workload(cls, w, device=None):
+        return cls(w.n, w.succ_ptr, w.succ_idx, w.succ_t, w.pred_ptr, w.pred_idx, w.pred_eid,
+                   w.c, w.level_ptr, w.level_vtx, device=device)
+
+    @property
+    def info(self) -> dict:
+        gi = GraphInfo()
+        rc = self._lib.cp_graph_get_info(self._handle, C.byref(gi))
+        if rc:
+            raise CpError(rc, "cp_graph_get_info")
+        return gi.as_dict()
+
+    def upload(self, device="cuda:0", stream=None):
+        import torch
+        nbytes = self.info["blob_bytes"]
+        self.blob = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+        rc = self._lib.cp_graph_upload(self._handle, C.c_void_p(self.blob.data_ptr()),
+                                       C.c_size_t(self.blob.numel()), _stream_ptr(stream))
+        if rc:
+            raise CpError(rc, "cp_graph_upload")
+        return self
+
+    def close(self):
+        if getattr(self, "_handle", None) is not None and self._handle:
+            self._lib.cp_graph_destroy(self._handle)
+            self._handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class CpProfile:
+    """cp_profile_*: per-stage HIP-event timing of cp_eval calls."""
+
+    def __init__(self, slots: int):
+        self._lib = load_library()
+        self._handle = C.c_void_p()
+        rc = self._lib.cp_profile_create(int(slots), C.byref(self._handle))
+        if rc:
+            raise CpError(rc, "cp_profile_create")
+
+    def reset(self):
+        rc = self._lib.cp_profile_reset(self._handle)
+        if rc:
+            raise CpError(rc, "cp_profile_reset")
+
+    def count(self) -> int:
+        out = C.c_int32(0)
+        rc = self._lib.cp_profile_count(self._handle, C.byref(out))
+        if rc:
+            raise CpError(rc, "cp_profile_count")
+        return int(out.value)
+
+    def read(self, slot: int):
+        """(ms per stage as a dict, (b-level launches, t-level launches)); synchronise first."""
+        ms = (C.c_float * NUM_STAGES)()
+        launches = (C.c_int32 * 2)()
+        rc = self._lib.cp_profile_read(self._handle, int(slot), ms, launches)
+        if rc:
+            raise CpError(rc, "cp_profile_read")
+        return {STAGE_NAMES[i]: float(ms[i]) for i in range(NUM_STAGES)}, (int(launches[0]), int(launches[1]))
+
+    def close(self):
+        if getattr(self, "_handle", None) is not None and self._handle:
+            self._lib.cp_profile_destroy(self._handle)
+            self._handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def workspace_bytes(graph: CpGraph, batch: int, k: int, assign_layout=ASSIGN_PARTITION_MAJOR,
+                    plan=PLAN_AUTO) -> int:
+    out = C.c_size_t(0)
+    rc = load_library().cp_eval_workspace_bytes(graph._handle, int(batch), int(k), int(assign_layout),
+                                                int(plan), C.byref(out))
+    if rc:
+        raise CpError(rc, "cp_eval_workspace_bytes")
+    return int(out.value)
+
+
+def cp_eval(graph: CpGraph, assignments, speeds, bandwidth, *, want=("cp", "b", "tl", "mask"),
+            tick_bytes=None, plan=PLAN_AUTO, assign_layout=ASSIGN_PARTITION_MAJOR,
+            out=None, workspace=None, profile: CpProfile | None = None, stream=None,
+            check_status=True):
+    """cp_eval on torch tensors.
+
+    ``assignments``: uint8 CUDA tensor, [batch][n] (or [n][batch] with
+    ``assign_layout=ASSIGN_VERTEX_MAJOR``).  Returns a dict with the requested
+    tensors: ``cp`` int64 [batch]; ``b``, ``tl`` int32/int64 [n][batch];
+    ``mask`` uint64-as-int64 words [n][ceil(batch/64)]; plus ``status`` (int32
+    tensor).  ``out`` may carry preallocated tensors under the same keys and
+    ``workspace`` a preallocated uint8 tensor.  With ``check_status`` the stream
+    is synchronised and a bad device id raises.
+    """
+    import torch
+    lib = load_library()
+    info = graph.info
+    n = info["n"]
+    assert assignments.is_cuda and assignments.dtype == torch.uint8 and assignments.is_contiguous()
+    if assign_layout == ASSIGN_PARTITION_MAJOR:
+        batch = int(assignments.shape[0])
+        assert int(assignments.shape[1]) == n
+    else:
+        batch = int(assignments.shape[1])
+        assert int(assignments.shape[0]) == n
+    s = np.ascontiguousarray(speeds, dtype=np.int64)
+    bw = np.ascontiguousarray(bandwidth, dtype=np.int64)
+    k = int(s.shape[0])
+    assert bw.shape == (k, k)
+    if tick_bytes is None:
+        tick_bytes = info["min_tick_bytes"]
+    tdt = torch.int32 if tick_bytes == 4 else torch.int64
+    dev = assignments.device
+    out = dict(out) if out else {}
+    want = set(want)
+    if "mask" in want:
+        want |= {"cp", "b", "tl"}
+    if "cp" in want:
+        want.add("b")
+    ncol = (batch + 63) // 64
+    if "cp" in want and "cp" not in out:
+        out["cp"] = torch.empty(batch, dtype=torch.int64, device=dev)
+    if "b" in want and "b" not in out:
+        out["b"] = torch.empty((n, batch), dtype=tdt, device=dev)
+    if "tl" in want and "tl" not in out:
+        out["tl"] = torch.empty((n, batch), dtype=tdt, device=dev)
+    if "mask" in want and "mask" not in out:
+        out["mask"] = torch.empty((n, ncol), dtype=torch.int64, device=dev)
+    if "status" not in out:
+        out["status"] = torch.empty(1, dtype=torch.int32, device=dev)
+    if workspace is None:
+        workspace = torch.empty(workspace_bytes(graph, batch, k, assign_layout, plan),
+                                dtype=torch.uint8, device=dev)
+    ptr = lambda key: C.c_void_p(out[key].data_ptr()) if key in want else C.c_void_p()
+    rc = lib.cp_eval(graph._handle, batch, k, C.c_void_p(assignments.data_ptr()), int(assign_layout),
+                     _np_ptr(s, C.c_int64), _np_ptr(bw, C.c_int64),
+                     C.c_void_p(workspace.data_ptr()), C.c_size_t(workspace.numel()), _stream_ptr(stream),
+                     ptr("cp"), ptr("b"), ptr("tl"), ptr("mask"), int(tick_bytes), int(plan),
+                     C.c_void_p(out["status"].data_ptr()),
+                     C.c_void_p(profile._handle.value) if profile is not None else C.c_void_p())
+    if rc:
+        raise CpError(rc, "cp_eval")
+    out["_workspace"] = workspace  # keep it alive until the caller drops the result
+    if check_status:
+        torch.cuda.synchronize(dev)
+        st = int(out["status"].item())
+        if st == STATUS_BAD_DEVICE_ID:
+            raise ValueError("assignments holds a device id >= k")
+    return out
+
+
+def mask_to_bool(mask_words, batch: int) -> np.ndarray:
+    """Unpack mask words [n][ceil(batch/64)] (host numpy or torch) into bool [n][batch]."""
+    a = mask_words.cpu().numpy() if hasattr(mask_words, "cpu") else np.asarray(mask_words)
+    a = np.ascontiguousarray(a).view(np.uint64)
+    bits = np.unpackbits(a.view(np.uint8).reshape(a.shape[0], -1), axis=1, bitorder="little")
+    return bits[:, :batch].astype(bool)

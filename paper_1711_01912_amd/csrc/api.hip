@@ -1,0 +1,375 @@
+// The C ABI declared in include/cpeval.h: argument checks, plan selection,
+// cost-table upload and the order in which the stages are enqueued.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <mutex>
+#include <new>
+
+#include "launch.hpp"
+
+using namespace cpeval;
+
+struct cp_profile {
+    int32_t slots = 0, count = 0;
+    std::vector<hipEvent_t> ev;          // slots * (CP_NUM_STAGES + 1)
+    std::vector<int32_t> launches;       // slots * 2
+};
+
+namespace {
+
+// Pinned staging slots for the per-call cost tables, reused round-robin; a slot is
+// only rewritten after the copy that last read it has finished.
+struct StageSlot {
+    void *host = nullptr;
+    size_t cap = 0;
+    hipEvent_t done = nullptr;
+    bool pending = false;
+};
+constexpr int kStageSlots = 8;
+StageSlot g_stage[kStageSlots];
+int g_stage_next = 0;
+std::mutex g_stage_mu;
+
+int stage_and_copy(const void *src, size_t bytes, void *dst, hipStream_t st) {
+    std::lock_guard<std::mutex> lock(g_stage_mu);
+    StageSlot &s = g_stage[g_stage_next];
+    g_stage_next = (g_stage_next + 1) % kStageSlots;
+    if (s.pending) {
+        if (hipEventSynchronize(s.done) != hipSuccess) return CP_ERR_HIP;
+        s.pending = false;
+    }
+    if (!s.done && hipEventCreateWithFlags(&s.done, hipEventDisableTiming) != hipSuccess)
+        return CP_ERR_HIP;
+    if (s.cap < bytes) {
+        if (s.host) (void)hipHostFree(s.host);
+        s.host = nullptr;
+        s.cap = 0;
+        size_t cap = std::max<size_t>(bytes, 4096);
+        if (hipHostMalloc(&s.host, cap, hipHostMallocDefault) != hipSuccess) return CP_ERR_HIP;
+        s.cap = cap;
+    }
+    std::memcpy(s.host, src, bytes);
+    if (hipMemcpyAsync(dst, s.host, bytes, hipMemcpyHostToDevice, st) != hipSuccess) return CP_ERR_HIP;
+    if (hipEventRecord(s.done, st) != hipSuccess) return CP_ERR_HIP;
+    s.pending = true;
+    return CP_OK;
+}
+
+constexpr size_t kWindowLdsLimit = kLdsBudget - 256;   // room for the kernel's static LDS
+
+bool window_fits(const Packed &p, int32_t k, size_t tick_bytes) {
+    if (!p.have_window || k > kMagicMaxK) return false;
+    return window_lds_bytes(k, p.win_b.slots, tick_bytes) <= kWindowLdsLimit &&
+           window_lds_bytes(k, p.win_t.slots, tick_bytes) <= kWindowLdsLimit;
+}
+
+// The resident-window plan pays the graph stream once per partition and wins when
+// levels are narrow and many; wide levels and hub rows go to the wave-column plan.
+bool window_preferred(const Packed &p) {
+    return p.info.max_level_width <= 2048 && p.info.max_out_degree < kHubDegree &&
+           p.info.max_in_degree < kHubDegree;
+}
+
+size_t tables_bytes(int32_t k) { return align_up(table_entries(k) * 8); }
+
+int check_eval_sizes(const cp_graph *g, int32_t batch, int32_t k, int assign_layout, int plan) {
+    if (!g) return CP_ERR_NULL;
+    if (batch < 1 || k < 1 || k > 255) return CP_ERR_SIZE;
+    if (assign_layout != CP_ASSIGN_PARTITION_MAJOR && assign_layout != CP_ASSIGN_VERTEX_MAJOR)
+        return CP_ERR_ARG;
+    if (plan != CP_PLAN_AUTO && plan != CP_PLAN_WAVE_COLUMN && plan != CP_PLAN_RESIDENT_WINDOW)
+        return CP_ERR_ARG;
+    return CP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int cp_graph_create(int32_t n, int64_t m, int32_t L,
+                    const int32_t *succ_ptr, const int32_t *succ_idx, const int64_t *succ_t,
+                    const int32_t *pred_ptr, const int32_t *pred_idx, const int32_t *pred_eid,
+                    const int64_t *c, const int32_t *level_ptr, const int32_t *level_vtx,
+                    cp_graph **out) {
+    if (!out) return CP_ERR_NULL;
+    *out = nullptr;
+    cp_graph *g = new (std::nothrow) cp_graph;
+    if (!g) return CP_ERR_ALLOC;
+    int rc;
+    try {
+        rc = pack_graph(n, m, L, succ_ptr, succ_idx, succ_t, pred_ptr, pred_idx, pred_eid, c,
+                        level_ptr, level_vtx, g->packed);
+    } catch (const std::bad_alloc &) {
+        rc = CP_ERR_ALLOC;
+    }
+    if (rc != CP_OK) {
+        delete g;
+        return rc;
+    }
+    cp_graph_info &info = g->packed.info;
+    info.window_ok = window_fits(g->packed, 1, (size_t)info.min_tick_bytes) ? 1 : 0;
+    info.auto_plan = info.window_ok && window_preferred(g->packed) ? CP_PLAN_RESIDENT_WINDOW
+                                                                   : CP_PLAN_WAVE_COLUMN;
+    *out = g;
+    return CP_OK;
+}
+
+int cp_graph_get_info(const cp_graph *g, cp_graph_info *out) {
+    if (!g || !out) return CP_ERR_NULL;
+    *out = g->packed.info;
+    out->uploaded = g->device_blob ? 1 : 0;
+    return CP_OK;
+}
+
+int cp_graph_upload(cp_graph *g, void *device_blob, size_t blob_bytes, void *stream) {
+    if (!g || !device_blob) return CP_ERR_NULL;
+    if (blob_bytes < g->packed.blob.size() || ((uintptr_t)device_blob % kAlign) != 0)
+        return CP_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    if (hipMemcpyAsync(device_blob, g->packed.blob.data(), g->packed.blob.size(),
+                       hipMemcpyHostToDevice, st) != hipSuccess)
+        return CP_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return CP_ERR_HIP;
+    g->device_blob = device_blob;
+    return CP_OK;
+}
+
+void cp_graph_destroy(cp_graph *g) { delete g; }
+
+int cp_eval_workspace_bytes(const cp_graph *g, int32_t batch, int32_t k, int assign_layout,
+                            int plan, size_t *out_bytes) {
+    if (!out_bytes) return CP_ERR_NULL;
+    int rc = check_eval_sizes(g, batch, k, assign_layout, plan);
+    if (rc) return rc;
+    size_t bytes = tables_bytes(k);
+    // the wave-column plan reads device ids vertex-major; under CP_PLAN_AUTO it may be
+    // the one that runs, whatever the graph prefers, if the cost model rules the other out
+    if (assign_layout == CP_ASSIGN_PARTITION_MAJOR && plan != CP_PLAN_RESIDENT_WINDOW)
+        bytes += align_up((size_t)g->packed.n * (size_t)batch);
+    *out_bytes = bytes;
+    return CP_OK;
+}
+
+int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
+            const uint8_t *assignments, int assign_layout,
+            const int64_t *speeds, const int64_t *bandwidth,
+            void *workspace, size_t workspace_bytes, void *stream,
+            int64_t *cp_out, void *blevel_out, void *tlevel_out, uint64_t *mask_out,
+            int tick_dtype, int plan, int32_t *status_out, cp_profile *profile) {
+    int rc = check_eval_sizes(g, batch, k, assign_layout, plan);
+    if (rc) return rc;
+    if (!assignments || !speeds || !bandwidth || !workspace || !status_out) return CP_ERR_NULL;
+    if (tick_dtype != CP_TICK_I32 && tick_dtype != CP_TICK_I64) return CP_ERR_ARG;
+    if (cp_out && !blevel_out) return CP_ERR_ARG;
+    if (mask_out && (!cp_out || !blevel_out || !tlevel_out)) return CP_ERR_ARG;
+    if (!g->device_blob) return CP_ERR_STATE;
+    const Packed &p = g->packed;
+    if (tick_dtype == CP_TICK_I32 && p.info.min_tick_bytes > 4) return CP_ERR_OVERFLOW;
+    if (((uintptr_t)workspace % kAlign) != 0) return CP_ERR_WORKSPACE;
+    if (profile && profile->count >= profile->slots) return CP_ERR_STATE;
+
+    CostTables tabs;
+    try {
+        rc = build_cost_tables(k, speeds, bandwidth, p.narrow, p.info.max_c, p.info.max_t, tabs);
+    } catch (const std::bad_alloc &) {
+        rc = CP_ERR_ALLOC;
+    }
+    if (rc) return rc;
+
+    // plan
+    const bool can_window = tabs.magic_ok && window_fits(p, k, (size_t)tick_dtype);
+    int use = plan;
+    if (plan == CP_PLAN_AUTO)
+        use = can_window && window_preferred(p) ? CP_PLAN_RESIDENT_WINDOW : CP_PLAN_WAVE_COLUMN;
+    if (use == CP_PLAN_RESIDENT_WINDOW && !can_window) return CP_ERR_ARG;
+
+    // workspace
+    const bool need_pT = use == CP_PLAN_WAVE_COLUMN && assign_layout == CP_ASSIGN_PARTITION_MAJOR;
+    size_t need = tables_bytes(k) + (need_pT ? align_up((size_t)p.n * (size_t)batch) : 0);
+    if (workspace_bytes < need) return CP_ERR_WORKSPACE;
+    uint8_t *ws = (uint8_t *)workspace;
+    uint8_t *d_tab = ws;
+    uint8_t *d_pT = ws + tables_bytes(k);
+
+    hipStream_t st = (hipStream_t)stream;
+    hipEvent_t *ev = nullptr;
+    int32_t *launches = nullptr;
+    if (profile) {
+        ev = profile->ev.data() + (size_t)profile->count * (CP_NUM_STAGES + 1);
+        launches = profile->launches.data() + (size_t)profile->count * 2;
+        launches[0] = launches[1] = 0;
+        profile->count++;
+    }
+#define CP_MARK(i)                                                              \
+    do {                                                                        \
+        if (ev && hipEventRecord(ev[i], st) != hipSuccess) return CP_ERR_HIP;  \
+    } while (0)
+
+    // ---- stage: prep
+    CP_MARK(CP_STAGE_PREP);
+    rc = launch_clear(cp_out, batch, status_out, stream);
+    if (rc) return rc;
+    const void *tab_src = tabs.magic_ok ? (const void *)tabs.magic.data() : (const void *)tabs.divisor.data();
+    rc = stage_and_copy(tab_src, table_entries(k) * 8, d_tab, st);
+    if (rc) return rc;
+    const uint8_t *pT = assignments;
+    if (need_pT) {
+        rc = launch_transpose(assignments, d_pT, p.n, batch, stream);
+        if (rc) return rc;
+        pT = d_pT;
+    }
+    const size_t kk = (size_t)k * k;
+
+    SweepLaunch s;
+    s.blob = (const uint8_t *)g->device_blob;
+    s.c_off = p.c_off;
+    s.magic = tabs.magic_ok;
+    s.narrow = p.narrow;
+    s.tick_bytes = tick_dtype;
+    s.P = batch; s.k = k; s.L = p.L; s.max_width = p.max_width;
+    s.pT = pT;
+    s.assign = assignments;
+    if (assign_layout == CP_ASSIGN_PARTITION_MAJOR) { s.a_stride_p = p.n; s.a_stride_v = 1; }
+    else { s.a_stride_p = 1; s.a_stride_v = batch; }
+    s.vert_tab = d_tab + 2 * kk * 8;
+    s.status = status_out;
+
+    // ---- stage: b-level sweep
+    CP_MARK(CP_STAGE_BLEVEL);
+    if (blevel_out) {
+        s.tsweep = false;
+        s.dir = &p.col_b;
+        s.win = &p.win_b;
+        s.val = blevel_out;
+        s.edge_tab = d_tab;
+        s.cp_out = use == CP_PLAN_RESIDENT_WINDOW ? cp_out : nullptr;
+        rc = use == CP_PLAN_RESIDENT_WINDOW ? launch_window_sweep(s, stream, launches)
+                                            : launch_column_sweep(s, stream, launches);
+        if (rc) return rc;
+    }
+
+    // ---- stage: critical-path length
+    CP_MARK(CP_STAGE_CP);
+    if (cp_out && use == CP_PLAN_WAVE_COLUMN) {
+        rc = launch_cp_sources((const int32_t *)(s.blob + p.sources_off), p.info.num_sources,
+                               blevel_out, batch, tick_dtype, cp_out, stream);
+        if (rc) return rc;
+    }
+
+    // ---- stage: t-level sweep
+    CP_MARK(CP_STAGE_TLEVEL);
+    if (tlevel_out) {
+        s.tsweep = true;
+        s.dir = &p.col_t;
+        s.win = &p.win_t;
+        s.val = tlevel_out;
+        s.edge_tab = d_tab + kk * 8;
+        s.cp_out = nullptr;
+        rc = use == CP_PLAN_RESIDENT_WINDOW ? launch_window_sweep(s, stream, launches ? launches + 1 : nullptr)
+                                            : launch_column_sweep(s, stream, launches ? launches + 1 : nullptr);
+        if (rc) return rc;
+    }
+
+    // ---- stage: mask
+    CP_MARK(CP_STAGE_MASK);
+    if (mask_out) {
+        rc = launch_mask(blevel_out, tlevel_out, cp_out, p.n, batch, tick_dtype, mask_out, stream);
+        if (rc) return rc;
+    }
+    CP_MARK(CP_NUM_STAGES);
+#undef CP_MARK
+    return CP_OK;
+}
+
+int cp_profile_create(int32_t slots, cp_profile **out) {
+    if (!out) return CP_ERR_NULL;
+    *out = nullptr;
+    if (slots < 1 || slots > 65536) return CP_ERR_SIZE;
+    cp_profile *p = new (std::nothrow) cp_profile;
+    if (!p) return CP_ERR_ALLOC;
+    p->slots = slots;
+    try {
+        p->ev.assign((size_t)slots * (CP_NUM_STAGES + 1), nullptr);
+        p->launches.assign((size_t)slots * 2, 0);
+    } catch (const std::bad_alloc &) {
+        delete p;
+        return CP_ERR_ALLOC;
+    }
+    for (auto &e : p->ev)
+        if (hipEventCreate(&e) != hipSuccess) {
+            cp_profile_destroy(p);
+            return CP_ERR_HIP;
+        }
+    *out = p;
+    return CP_OK;
+}
+
+int cp_profile_reset(cp_profile *p) {
+    if (!p) return CP_ERR_NULL;
+    p->count = 0;
+    return CP_OK;
+}
+
+int cp_profile_count(const cp_profile *p, int32_t *out) {
+    if (!p || !out) return CP_ERR_NULL;
+    *out = p->count;
+    return CP_OK;
+}
+
+int cp_profile_read(const cp_profile *p, int32_t slot, float ms_out[CP_NUM_STAGES],
+                    int32_t sweep_launches[2]) {
+    if (!p || !ms_out) return CP_ERR_NULL;
+    if (slot < 0 || slot >= p->count) return CP_ERR_STATE;
+    const hipEvent_t *ev = p->ev.data() + (size_t)slot * (CP_NUM_STAGES + 1);
+    for (int i = 0; i < CP_NUM_STAGES; ++i)
+        if (hipEventElapsedTime(&ms_out[i], ev[i], ev[i + 1]) != hipSuccess) return CP_ERR_HIP;
+    if (sweep_launches) {
+        sweep_launches[0] = p->launches[(size_t)slot * 2];
+        sweep_launches[1] = p->launches[(size_t)slot * 2 + 1];
+    }
+    return CP_OK;
+}
+
+void cp_profile_destroy(cp_profile *p) {
+    if (!p) return;
+    for (auto e : p->ev)
+        if (e) (void)hipEventDestroy(e);
+    delete p;
+}
+
+int cp_cost_magic(int64_t divisor, int64_t max_dividend, uint32_t *mul, uint32_t *dm1) {
+    if (!mul || !dm1) return CP_ERR_NULL;
+    if (divisor < 1 || max_dividend < 0) return CP_ERR_SIZE;
+    int64_t s = divisor, b[1] = {1};
+    CostTables t;
+    // one device of speed `divisor`: the vertex entry carries the constants
+    int rc = build_cost_tables(1, &s, b, true, max_dividend, 0, t);
+    if (rc) return rc;
+    if (!t.magic_ok) return 0;
+    *mul = t.magic[2].mul;
+    *dm1 = t.magic[2].dm1;
+    return 1;
+}
+
+const char *cp_error_string(int code) {
+    switch (code) {
+        case CP_OK: return "ok";
+        case CP_ERR_NULL: return "a required pointer is NULL";
+        case CP_ERR_SIZE: return "size out of range (n, m, L, batch or k)";
+        case CP_ERR_CSR: return "malformed CSR arrays, or successor and predecessor arrays disagree";
+        case CP_ERR_LEVELS: return "level index is not a partition of the vertices, or an edge does not go to a higher level";
+        case CP_ERR_NEGATIVE: return "negative vertex complexity or edge volume";
+        case CP_ERR_SPEED: return "device speed < 1";
+        case CP_ERR_BANDWIDTH: return "off-diagonal bandwidth < 1";
+        case CP_ERR_OVERFLOW: return "longest raw path too large for the requested tick type";
+        case CP_ERR_WORKSPACE: return "workspace or blob too small or misaligned";
+        case CP_ERR_HIP: return "a HIP runtime call failed";
+        case CP_ERR_STATE: return "graph not uploaded, or profile full / slot not filled";
+        case CP_ERR_ARG: return "bad enum value, output dependency not met, or plan not runnable";
+        case CP_ERR_ALLOC: return "host allocation failed";
+        default: return "unknown error code";
+    }
+}
+
+}  // extern "C"

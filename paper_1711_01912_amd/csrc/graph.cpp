@@ -1,0 +1,309 @@
+// Host side of cp_graph_create: validation of the caller's arrays and packing
+// into the device image used by the two kernel families.  No GPU call here.
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <numeric>
+
+#include "cpeval_internal.hpp"
+
+namespace cpeval {
+namespace {
+
+struct BlobWriter {
+    std::vector<uint8_t> &buf;
+    explicit BlobWriter(std::vector<uint8_t> &b) : buf(b) {}
+    size_t reserve(size_t bytes) {
+        size_t off = align_up(buf.size());
+        buf.resize(off + bytes, 0);
+        return off;
+    }
+    template <typename T> T *at(size_t off) { return reinterpret_cast<T *>(buf.data() + off); }
+};
+
+struct Csr {
+    const int32_t *ptr;
+    const int32_t *idx;
+    std::vector<int64_t> wt;  // t(e) in this CSR's order
+};
+
+int check_csr(int32_t n, int64_t m, const int32_t *ptr, const int32_t *idx) {
+    if (ptr[0] != 0 || (int64_t)ptr[n] != m) return CP_ERR_CSR;
+    for (int32_t v = 0; v < n; ++v)
+        if (ptr[v + 1] < ptr[v]) return CP_ERR_CSR;
+    for (int64_t e = 0; e < m; ++e)
+        if (idx[e] < 0 || idx[e] >= n) return CP_ERR_CSR;
+    return CP_OK;
+}
+
+// Vertices in sweep order: levels first-to-last (forward) or last-to-first, and
+// inside a level the longest rows first, so that hubs lead and rows of similar
+// length share a wavefront.
+void sweep_order(int32_t n, int32_t L, const int32_t *level_ptr, const int32_t *level_vtx,
+                 const int32_t *ptr, bool forward, std::vector<int32_t> &order, ColumnDir &dir) {
+    order.resize(n);
+    dir.lvl_begin.assign(L, 0);
+    dir.lvl_hubs.assign(L, 0);
+    dir.lvl_count.assign(L, 0);
+    int32_t pos = 0;
+    for (int32_t s = 0; s < L; ++s) {
+        int32_t l = forward ? s : L - 1 - s;
+        int32_t a = level_ptr[l], b = level_ptr[l + 1];
+        std::copy(level_vtx + a, level_vtx + b, order.begin() + pos);
+        std::stable_sort(order.begin() + pos, order.begin() + pos + (b - a),
+                         [&](int32_t x, int32_t y) {
+                             return ptr[x + 1] - ptr[x] > ptr[y + 1] - ptr[y];
+                         });
+        int32_t hubs = 0;
+        while (hubs < b - a) {
+            int32_t v = order[pos + hubs];
+            if (ptr[v + 1] - ptr[v] < kHubDegree) break;
+            ++hubs;
+        }
+        dir.lvl_begin[s] = pos;
+        dir.lvl_hubs[s] = hubs;
+        dir.lvl_count[s] = b - a;
+        pos += b - a;
+    }
+}
+
+void pack_column_dir(BlobWriter &w, int32_t n, int64_t m, bool narrow, const Csr &csr,
+                     const std::vector<int32_t> &order, ColumnDir &dir) {
+    dir.ptr_off = w.reserve(sizeof(int32_t) * ((size_t)n + 1));
+    std::memcpy(w.at<int32_t>(dir.ptr_off), csr.ptr, sizeof(int32_t) * ((size_t)n + 1));
+    dir.idx_off = w.reserve(sizeof(int32_t) * (size_t)std::max<int64_t>(m, 1));
+    if (m) std::memcpy(w.at<int32_t>(dir.idx_off), csr.idx, sizeof(int32_t) * (size_t)m);
+    if (narrow) {
+        dir.wt_off = w.reserve(sizeof(uint32_t) * (size_t)std::max<int64_t>(m, 1));
+        uint32_t *p = w.at<uint32_t>(dir.wt_off);
+        for (int64_t e = 0; e < m; ++e) p[e] = (uint32_t)csr.wt[e];
+    } else {
+        dir.wt_off = w.reserve(sizeof(int64_t) * (size_t)std::max<int64_t>(m, 1));
+        if (m) std::memcpy(w.at<int64_t>(dir.wt_off), csr.wt.data(), sizeof(int64_t) * (size_t)m);
+    }
+    dir.order_off = w.reserve(sizeof(int32_t) * (size_t)n);
+    std::memcpy(w.at<int32_t>(dir.order_off), order.data(), sizeof(int32_t) * (size_t)n);
+}
+
+// Resident-window packing for one direction.  Returns false if the entry count
+// does not fit the 32-bit slice offsets.
+bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, const Csr &csr,
+                     const std::vector<int32_t> &order, const ColumnDir &col, WindowDir &dir) {
+    std::vector<int32_t> pos(n);
+    for (int32_t i = 0; i < n; ++i) pos[order[i]] = i;
+
+    // ring capacity: while a level [a, b) is being written, every position from the
+    // earliest one it reads up to b-1 must own a distinct slot
+    int64_t need = 1;
+    for (int32_t s = 0; s < L; ++s) {
+        int32_t a = col.lvl_begin[s], b = a + col.lvl_count[s];
+        int32_t jmin = a;
+        for (int32_t i = a; i < b; ++i) {
+            int32_t v = order[i];
+            for (int32_t e = csr.ptr[v]; e < csr.ptr[v + 1]; ++e) jmin = std::min(jmin, pos[csr.idx[e]]);
+        }
+        need = std::max<int64_t>(need, (int64_t)b - jmin);
+    }
+    dir.slots = (int32_t)need;
+
+    // slices
+    std::vector<uint32_t> slice_off;
+    std::vector<int32_t> lvl(2 * ((size_t)L + 1));
+    uint64_t entries = 0;
+    for (int32_t s = 0; s < L; ++s) {
+        int32_t a = col.lvl_begin[s], b = a + col.lvl_count[s];
+        lvl[2 * s] = a;
+        lvl[2 * s + 1] = (int32_t)slice_off.size();
+        for (int32_t p0 = a; p0 < b; p0 += kWave) {
+            int32_t v0 = order[p0];
+            uint32_t width = (uint32_t)(csr.ptr[v0 + 1] - csr.ptr[v0]);  // longest row leads
+            slice_off.push_back((uint32_t)entries);
+            entries += (uint64_t)width * kWave;
+            if (entries >= (1ull << 32)) return false;
+        }
+    }
+    lvl[2 * L] = n;
+    lvl[2 * L + 1] = (int32_t)slice_off.size();
+    slice_off.push_back((uint32_t)entries);
+    dir.slices = (int32_t)slice_off.size() - 1;
+    dir.entries = (int64_t)entries;
+
+    dir.vtx_off = w.reserve(sizeof(int32_t) * (size_t)n);
+    std::memcpy(w.at<int32_t>(dir.vtx_off), order.data(), sizeof(int32_t) * (size_t)n);
+    dir.c_off = w.reserve(sizeof(uint32_t) * (size_t)n);
+    dir.deg_off = w.reserve(sizeof(int32_t) * (size_t)n);
+    dir.lvl_off = w.reserve(sizeof(int32_t) * lvl.size());
+    std::memcpy(w.at<int32_t>(dir.lvl_off), lvl.data(), sizeof(int32_t) * lvl.size());
+    dir.slice_off = w.reserve(sizeof(uint32_t) * slice_off.size());
+    std::memcpy(w.at<uint32_t>(dir.slice_off), slice_off.data(), sizeof(uint32_t) * slice_off.size());
+    dir.ent_off = w.reserve(sizeof(uint32_t) * 2 * (size_t)std::max<uint64_t>(entries, 1));
+
+    uint32_t *cp = w.at<uint32_t>(dir.c_off);
+    int32_t *dg = w.at<int32_t>(dir.deg_off);
+    uint32_t *ent = w.at<uint32_t>(dir.ent_off);
+    int32_t slice = 0;
+    for (int32_t s = 0; s < L; ++s) {
+        int32_t a = col.lvl_begin[s], b = a + col.lvl_count[s];
+        for (int32_t p0 = a; p0 < b; p0 += kWave, ++slice) {
+            uint64_t base = slice_off[slice];
+            for (int32_t i = p0; i < std::min(b, p0 + kWave); ++i) {
+                int32_t v = order[i];
+                int32_t d = csr.ptr[v + 1] - csr.ptr[v];
+                cp[i] = (uint32_t)c[v];
+                dg[i] = d;
+                for (int32_t j = 0; j < d; ++j) {
+                    int64_t e = (int64_t)csr.ptr[v] + j;
+                    uint64_t at = base + (uint64_t)j * kWave + (uint32_t)(i - p0);
+                    ent[2 * at] = (uint32_t)(pos[csr.idx[e]] % dir.slots);
+                    ent[2 * at + 1] = (uint32_t)csr.wt[e];
+                }
+            }
+        }
+    }
+    return true;
+}
+
+}  // namespace
+
+int pack_graph(int32_t n, int64_t m, int32_t L,
+               const int32_t *succ_ptr, const int32_t *succ_idx, const int64_t *succ_t,
+               const int32_t *pred_ptr, const int32_t *pred_idx, const int32_t *pred_eid,
+               const int64_t *c, const int32_t *level_ptr, const int32_t *level_vtx,
+               Packed &out) {
+    if (n < 1 || m < 0 || L < 1 || m >= (int64_t)0x7fffffff) return CP_ERR_SIZE;
+    if (!succ_ptr || !pred_ptr || !c || !level_ptr || !level_vtx) return CP_ERR_NULL;
+    if (m > 0 && (!succ_idx || !succ_t || !pred_idx || !pred_eid)) return CP_ERR_NULL;
+
+    int rc = check_csr(n, m, succ_ptr, succ_idx);
+    if (rc) return rc;
+    rc = check_csr(n, m, pred_ptr, pred_idx);
+    if (rc) return rc;
+
+    // both CSRs must describe the same multiset of edges
+    std::vector<int32_t> edge_src((size_t)m);
+    for (int32_t v = 0; v < n; ++v)
+        for (int32_t e = succ_ptr[v]; e < succ_ptr[v + 1]; ++e) edge_src[e] = v;
+    {
+        std::vector<uint8_t> seen((size_t)m, 0);
+        for (int32_t v = 0; v < n; ++v)
+            for (int32_t j = pred_ptr[v]; j < pred_ptr[v + 1]; ++j) {
+                int32_t e = pred_eid[j];
+                if (e < 0 || e >= m || seen[e]) return CP_ERR_CSR;
+                seen[e] = 1;
+                if (succ_idx[e] != v || edge_src[e] != pred_idx[j]) return CP_ERR_CSR;
+            }
+    }
+
+    // level index: a partition of V in which every edge climbs
+    if (level_ptr[0] != 0 || level_ptr[L] != n) return CP_ERR_LEVELS;
+    std::vector<int32_t> level((size_t)n, -1);
+    for (int32_t l = 0; l < L; ++l) {
+        if (level_ptr[l + 1] < level_ptr[l]) return CP_ERR_LEVELS;
+        for (int32_t i = level_ptr[l]; i < level_ptr[l + 1]; ++i) {
+            int32_t v = level_vtx[i];
+            if (v < 0 || v >= n || level[v] >= 0) return CP_ERR_LEVELS;
+            level[v] = l;
+        }
+    }
+    for (int64_t e = 0; e < m; ++e)
+        if (level[edge_src[e]] >= level[succ_idx[e]]) return CP_ERR_LEVELS;
+
+    int64_t max_c = 0, max_t = 0;
+    for (int32_t v = 0; v < n; ++v) {
+        if (c[v] < 0) return CP_ERR_NEGATIVE;
+        max_c = std::max(max_c, c[v]);
+    }
+    for (int64_t e = 0; e < m; ++e) {
+        if (succ_t[e] < 0) return CP_ERR_NEGATIVE;
+        max_t = std::max(max_t, succ_t[e]);
+    }
+
+    // U0: longest path with w = c and x = t bounds every tick value for every s, B >= 1
+    const uint64_t kLimit = 1ull << 62;
+    uint64_t u0 = 0;
+    {
+        std::vector<uint64_t> b0((size_t)n, 0);
+        for (int32_t l = L - 1; l >= 0; --l)
+            for (int32_t i = level_ptr[l]; i < level_ptr[l + 1]; ++i) {
+                int32_t v = level_vtx[i];
+                uint64_t best = 0;
+                for (int32_t e = succ_ptr[v]; e < succ_ptr[v + 1]; ++e) {
+                    uint64_t cand = (uint64_t)succ_t[e] + b0[succ_idx[e]];  // each term < 2^63
+                    best = std::max(best, cand);
+                }
+                if (best >= kLimit || (uint64_t)c[v] >= kLimit) return CP_ERR_OVERFLOW;
+                uint64_t val = best + (uint64_t)c[v];
+                if (val >= kLimit) return CP_ERR_OVERFLOW;
+                b0[v] = val;
+                u0 = std::max(u0, val);
+            }
+    }
+
+    Packed &P = out;
+    P.n = n; P.m = m; P.L = L;
+    P.narrow = (uint64_t)max_c < (1ull << 32) && (uint64_t)max_t < (1ull << 32);
+
+    cp_graph_info &info = P.info;
+    info = cp_graph_info{};
+    info.n = n; info.L = L; info.m = m;
+    info.max_c = max_c; info.max_t = max_t;
+    info.raw_path_bound = (int64_t)u0;
+    info.min_tick_bytes = u0 < (1ull << 31) ? 4 : 8;
+    std::vector<int32_t> sources;
+    for (int32_t v = 0; v < n; ++v) {
+        int32_t od = succ_ptr[v + 1] - succ_ptr[v], id = pred_ptr[v + 1] - pred_ptr[v];
+        info.max_out_degree = std::max(info.max_out_degree, od);
+        info.max_in_degree = std::max(info.max_in_degree, id);
+        if (od == 0) info.num_sinks++;
+        if (id == 0) sources.push_back(v);
+    }
+    info.num_sources = (int32_t)sources.size();
+    for (int32_t l = 0; l < L; ++l)
+        info.max_level_width = std::max(info.max_level_width, level_ptr[l + 1] - level_ptr[l]);
+    P.max_width = info.max_level_width;
+
+    Csr succ{succ_ptr, succ_idx, {}}, pred{pred_ptr, pred_idx, {}};
+    succ.wt.assign(succ_t, succ_t + m);
+    pred.wt.resize((size_t)m);
+    for (int64_t j = 0; j < m; ++j) pred.wt[j] = succ_t[pred_eid[j]];
+
+    std::vector<int32_t> order_b, order_t;
+    sweep_order(n, L, level_ptr, level_vtx, succ_ptr, /*forward=*/false, order_b, P.col_b);
+    sweep_order(n, L, level_ptr, level_vtx, pred_ptr, /*forward=*/true, order_t, P.col_t);
+
+    try {
+        P.blob.clear();
+        BlobWriter w(P.blob);
+        pack_column_dir(w, n, m, P.narrow, succ, order_b, P.col_b);
+        pack_column_dir(w, n, m, P.narrow, pred, order_t, P.col_t);
+        if (P.narrow) {
+            P.c_off = w.reserve(sizeof(uint32_t) * (size_t)n);
+            uint32_t *cp = w.at<uint32_t>(P.c_off);
+            for (int32_t v = 0; v < n; ++v) cp[v] = (uint32_t)c[v];
+        } else {
+            P.c_off = w.reserve(sizeof(int64_t) * (size_t)n);
+            std::memcpy(w.at<int64_t>(P.c_off), c, sizeof(int64_t) * (size_t)n);
+        }
+        P.sources_off = w.reserve(sizeof(int32_t) * sources.size());
+        std::memcpy(w.at<int32_t>(P.sources_off), sources.data(), sizeof(int32_t) * sources.size());
+
+        P.have_window = false;
+        if (P.narrow) {
+            size_t mark = P.blob.size();
+            bool ok = pack_window_dir(w, n, L, c, succ, order_b, P.col_b, P.win_b) &&
+                      pack_window_dir(w, n, L, c, pred, order_t, P.col_t, P.win_t);
+            if (ok) P.have_window = true;
+            else P.blob.resize(mark);
+        }
+        P.blob.resize(align_up(P.blob.size()));
+    } catch (const std::bad_alloc &) {
+        return CP_ERR_ALLOC;
+    }
+
+    info.window_slots_b = P.have_window ? P.win_b.slots : 0;
+    info.window_slots_t = P.have_window ? P.win_t.slots : 0;
+    info.blob_bytes = P.blob.size();
+    return CP_OK;
+}
+
+}  // namespace cpeval

@@ -1,0 +1,247 @@
+"""GPU parity: the HIP library, called through the C ABI, against the CPU oracle,
+element by element and bit-exact (integer ticks), on the same seeded inputs."""
+import numpy as np
+import pytest
+
+from workloads import build_csr, make_workload, random_layered_dag
+from workloads.dags import Workload, _finish
+
+pytestmark = pytest.mark.gpu
+
+COLUMN, WINDOW = 1, 2
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_1711_01912_amd as cpe
+    cpe.load_library()
+    return cpe
+
+
+def _oracle(oracle, w, **kw):
+    return oracle.evaluate_workload(w, threads=16, **kw)
+
+
+def _check(gpu, oracle, w, plans=(COLUMN, WINDOW), ticks=(None,), layouts=(0,), what=None):
+    from gpu_util import assert_equal_to_oracle, run_gpu
+    ref = _oracle(oracle, w)
+    g = gpu.CpGraph.from_workload(w, device="cuda:0")
+    for plan in plans:
+        for tb in ticks:
+            for layout in layouts:
+                res = run_gpu(w, plan, tick_bytes=tb, layout=layout, graph=g)
+                assert_equal_to_oracle(res, ref, what=f"{what or w.name} plan={plan} ticks={tb} layout={layout}")
+    g.close()
+    return ref
+
+
+def _custom(name, n, src, dst, t, c, speeds, bandwidth, assignments, level=None):
+    csr = build_csr(n, src, dst, t, level)
+    return _finish(name, csr, c, len(speeds), speeds, bandwidth, assignments)
+
+
+# ------------------------------------------------------------------ the five workloads
+
+def test_tiny_all_variants(gpu, oracle):
+    w = make_workload("tiny")
+    _check(gpu, oracle, w, ticks=(4, 8), layouts=(0, 1))
+
+
+def test_mlp_full(gpu, oracle):
+    _check(gpu, oracle, make_workload("mlp"))
+
+
+def test_mlp_literal_single_shard(gpu, oracle):
+    _check(gpu, oracle, make_workload("mlp", shards=1, P=130))
+
+
+def test_inception_full(gpu, oracle):
+    _check(gpu, oracle, make_workload("inception"))
+
+
+def test_large_sparse_full(gpu, oracle):
+    """The benchmark workload at full size, all columns, in both plans."""
+    _check(gpu, oracle, make_workload("large_sparse"))
+
+
+def test_comm_heavy_full(gpu, oracle):
+    w = make_workload("comm_heavy")
+    _check(gpu, oracle, w, plans=(COLUMN,))
+
+
+def test_comm_heavy_scaled_both_plans(gpu, oracle):
+    # hub rows (300 >= the hub threshold) and levels wider than one workgroup
+    w = make_workload("comm_heavy", P=70, levels=5, width=3000, hub_degree=300)
+    _check(gpu, oracle, w)
+
+
+# ------------------------------------------------------------------ edge cases
+
+@pytest.mark.parametrize("P", [1, 2, 63, 64, 65, 127, 130])
+def test_ragged_batches(gpu, oracle, P):
+    w = make_workload("large_sparse", P=P, levels=40, width=70)
+    _check(gpu, oracle, w, what=f"ragged P={P}")
+
+
+def test_single_vertex_and_edgeless(gpu, oracle):
+    a = np.array([[0], [1], [1]], dtype=np.uint8)
+    w = _custom("one", 1, [], [], [], [7], [2, 3], [[1, 5], [4, 1]], a)
+    _check(gpu, oracle, w)
+    rng = np.random.default_rng(0)
+    a = rng.integers(0, 3, size=(5, 200), dtype=np.uint8)
+    w = _custom("antichain", 200, [], [], [], rng.integers(0, 50, size=200), [1, 2, 5],
+                rng.integers(1, 9, size=(3, 3)), a)
+    _check(gpu, oracle, w)
+
+
+def test_zero_costs_and_multi_edges(gpu, oracle):
+    rng = np.random.default_rng(1)
+    n, level, src, dst = random_layered_dag(rng, [9] * 12, 1, 4, 3)
+    # duplicate a third of the edges with other volumes
+    dup = rng.random(len(src)) < 0.33
+    src = np.concatenate([src, src[dup]])
+    dst = np.concatenate([dst, dst[dup]])
+    t = rng.integers(0, 3, size=len(src)) * rng.integers(0, 1000, size=len(src))
+    c = rng.integers(0, 2, size=n) * rng.integers(0, 100, size=n)
+    a = rng.integers(0, 4, size=(37, n), dtype=np.uint8)
+    B = rng.integers(1, 30, size=(4, 4))
+    w = _custom("zeros-multi", n, src, dst, t, c, [1, 2, 3, 4], B, a, level)
+    _check(gpu, oracle, w)
+
+
+def test_asymmetric_bandwidth(gpu, oracle):
+    w = make_workload("inception", P=100, modules=5, groups=3)
+    rng = np.random.default_rng(2)
+    w.bandwidth = rng.integers(1, 100, size=(w.k, w.k)).astype(np.int64)
+    assert not np.array_equal(w.bandwidth, w.bandwidth.T)
+    _check(gpu, oracle, w)
+
+
+def test_paper_parameter_ranges_fifty_devices(gpu, oracle):
+    """50 devices with the simulation's ranges (section 5.1)."""
+    rng = np.random.default_rng(3)
+    n, level, src, dst = random_layered_dag(rng, [7] * 50, 1, 2, 3)
+    k = 50
+    w = _custom("paper-ranges", n, src, dst, rng.integers(1, 101, size=len(src)),
+                rng.integers(1, 101, size=n), rng.integers(10, 101, size=k),
+                rng.integers(10, 61, size=(k, k)), rng.integers(0, k, size=(96, n), dtype=np.uint8), level)
+    _check(gpu, oracle, w)
+
+
+def test_many_devices_take_the_plain_division_path(gpu, oracle):
+    """k = 200 exceeds the LDS-table limit: plain divisors from global memory."""
+    rng = np.random.default_rng(4)
+    n, level, src, dst = random_layered_dag(rng, [11] * 14, 1, 3, 2)
+    k = 200
+    w = _custom("k200", n, src, dst, rng.integers(1, 10**4, size=len(src)),
+                rng.integers(1, 10**3, size=n), rng.integers(1, 40, size=k),
+                rng.integers(1, 90, size=(k, k)), rng.integers(0, k, size=(70, n), dtype=np.uint8), level)
+    _check(gpu, oracle, w, plans=(COLUMN,))
+    with pytest.raises(gpu.CpError) as e:
+        from gpu_util import run_gpu
+        run_gpu(w, WINDOW)
+    assert e.value.code == -12
+
+
+def test_wide_weights_take_the_64_bit_path(gpu, oracle):
+    """Volumes above 2^32 and a path bound above 2^31: int64 ticks, plain division."""
+    rng = np.random.default_rng(5)
+    n, level, src, dst = random_layered_dag(rng, [8] * 10, 1, 3, 2)
+    t = rng.integers(1, 2**45, size=len(src))
+    c = rng.integers(1, 2**40, size=n)
+    B = rng.integers(1, 2**20, size=(3, 3))
+    a = rng.integers(0, 3, size=(66, n), dtype=np.uint8)
+    w = _custom("wide", n, src, dst, t, c, [1, 3, 2**33], B, a, level)
+    g = gpu.CpGraph.from_workload(w)
+    assert g.info["min_tick_bytes"] == 8
+    g.close()
+    _check(gpu, oracle, w, plans=(COLUMN,))
+
+
+def test_narrow_weights_with_inexact_constants_fall_back(gpu, oracle):
+    """Weights fit 32 bits but a divisor does not admit the exact 32-bit form."""
+    rng = np.random.default_rng(6)
+    n, level, src, dst = random_layered_dag(rng, [8] * 10, 1, 3, 2)
+    t = rng.integers(2**31, 2**32, size=len(src))
+    c = rng.integers(1, 1000, size=n)
+    B = np.array([[1, 3, 7], [11, 1, 641], [6700417, 5, 1]])
+    assert gpu.cost_magic(3, int(t.max())) is None
+    a = rng.integers(0, 3, size=(40, n), dtype=np.uint8)
+    w = _custom("inexact", n, src, dst, t, c, [1, 2, 3], B, a, level)
+    _check(gpu, oracle, w, plans=(COLUMN,), ticks=(8,))
+
+
+def test_tick_width_request_is_checked(gpu, oracle):
+    import torch
+    w = make_workload("tiny")
+    w.c = w.c * 2**26            # pushes the raw path bound past 2^31
+    g = gpu.CpGraph.from_workload(w, device="cuda:0")
+    assert g.info["min_tick_bytes"] == 8
+    a = torch.from_numpy(w.assignments).to("cuda:0")
+    with pytest.raises(gpu.CpError) as e:
+        gpu.cp_eval(g, a, w.speeds, w.bandwidth, tick_bytes=4)
+    assert e.value.code == -8
+    g.close()
+    _check(gpu, oracle, w, ticks=(8,))
+
+
+def test_bad_device_id_is_reported_not_fatal(gpu):
+    import torch
+    w = make_workload("tiny")
+    g = gpu.CpGraph.from_workload(w, device="cuda:0")
+    bad = w.assignments.copy()
+    bad[3, 10] = 9
+    a = torch.from_numpy(bad).to("cuda:0")
+    for plan in (COLUMN, WINDOW):
+        with pytest.raises(ValueError):
+            gpu.cp_eval(g, a, w.speeds, w.bandwidth, plan=plan)
+    # a good call afterwards clears the status word
+    out = gpu.cp_eval(g, torch.from_numpy(w.assignments).to("cuda:0"), w.speeds, w.bandwidth)
+    assert int(out["status"].item()) == 0
+    g.close()
+
+
+def test_rejected_cost_models(gpu):
+    import torch
+    w = make_workload("tiny")
+    g = gpu.CpGraph.from_workload(w, device="cuda:0")
+    a = torch.from_numpy(w.assignments).to("cuda:0")
+    with pytest.raises(gpu.CpError) as e:
+        gpu.cp_eval(g, a, [1, 0], w.bandwidth)
+    assert e.value.code == -6
+    with pytest.raises(gpu.CpError) as e:
+        gpu.cp_eval(g, a, w.speeds, [[0, 0], [3, 0]])
+    assert e.value.code == -7
+    gpu.cp_eval(g, a, w.speeds, [[0, 1], [3, -5]])   # the diagonal is never read
+    g.close()
+
+
+def test_partial_outputs_and_determinism(gpu, oracle):
+    from gpu_util import run_gpu
+    w = make_workload("large_sparse", P=100, levels=60, width=90)
+    ref = _oracle(oracle, w)
+    for plan in (COLUMN, WINDOW):
+        r1 = run_gpu(w, plan, want=("b",))
+        assert np.array_equal(r1["b"].T, ref["b"]) and "tl" not in r1
+        r2 = run_gpu(w, plan, want=("cp",))
+        assert np.array_equal(r2["cp"], ref["cp"])
+        r3 = run_gpu(w, plan, want=("tl",))
+        assert np.array_equal(r3["tl"].T, ref["tl"])
+        r4 = run_gpu(w, plan)
+        r5 = run_gpu(w, plan)
+        for key in ("cp", "b", "tl", "mask"):
+            assert np.array_equal(r4[key], r5[key])
+
+
+def test_one_column_equals_its_column_in_a_batch(gpu):
+    from gpu_util import run_gpu
+    w = make_workload("mlp", P=200, layers=8, shards=3)
+    full = run_gpu(w, WINDOW)
+    for plan in (COLUMN, WINDOW):
+        one = run_gpu(w, plan, assignments=w.assignments[77:78])
+        assert np.array_equal(one["b"][:, 0], full["b"][:, 77])
+        assert np.array_equal(one["tl"][:, 0], full["tl"][:, 77])
+        assert one["cp"][0] == full["cp"][77]

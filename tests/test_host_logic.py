@@ -1,0 +1,234 @@
+"""CPU-only checks of the library's host side: it loads, exports what the header
+declares, validates graphs, reports graph facts, and builds exact division
+constants.  No kernel is launched."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_1711_01912_amd as cpe
+from paper_1711_01912_amd import binding
+from workloads import build_csr, make_workload, random_layered_dag
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_1711_01912_amd.build import build_library
+    build_library(force=False)
+    return cpe.load_library()
+
+
+def test_library_exports_every_declared_symbol(lib):
+    text = open(os.path.join(ROOT, "include", "cpeval.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(cp_[a-z_]+)\s*\(", text))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_error_strings(lib):
+    seen = set()
+    for code in range(0, -14, -1):
+        s = cpe.error_string(code)
+        assert s and s != "unknown error code"
+        seen.add(s)
+    assert len(seen) == 14
+    assert cpe.error_string(-99) == "unknown error code"
+
+
+def _graph_args(w):
+    return dict(n=w.n, succ_ptr=w.succ_ptr.copy(), succ_idx=w.succ_idx.copy(), succ_t=w.succ_t.copy(),
+                pred_ptr=w.pred_ptr.copy(), pred_idx=w.pred_idx.copy(), pred_eid=w.pred_eid.copy(),
+                c=w.c.copy(), level_ptr=w.level_ptr.copy(), level_vtx=w.level_vtx.copy())
+
+
+def _create_rc(**a):
+    try:
+        cpe.CpGraph(**a).close()
+        return 0
+    except cpe.CpError as e:
+        return e.code
+
+
+def test_create_accepts_every_workload_recipe(lib):
+    for name, kw in [("tiny", {}), ("mlp", dict(P=4, layers=4, shards=2)),
+                     ("inception", dict(P=4, modules=3, groups=2)),
+                     ("large_sparse", dict(P=4, levels=30, width=20)),
+                     ("comm_heavy", dict(P=4, levels=4, width=400, hub_degree=300))]:
+        w = make_workload(name, **kw)
+        g = cpe.CpGraph.from_workload(w)
+        info = g.info
+        assert (info["n"], info["m"], info["L"]) == (w.n, w.m, w.L)
+        assert info["max_out_degree"] == int(np.diff(w.succ_ptr).max())
+        assert info["max_in_degree"] == int(np.diff(w.pred_ptr).max())
+        assert info["max_level_width"] == int(np.diff(w.level_ptr).max())
+        assert info["num_sources"] == int((np.diff(w.pred_ptr) == 0).sum())
+        assert info["num_sinks"] == int((np.diff(w.succ_ptr) == 0).sum())
+        assert info["max_c"] == int(w.c.max()) and info["max_t"] == int(w.succ_t.max())
+        assert info["uploaded"] == 0 and info["blob_bytes"] % 256 == 0
+        g.close()
+
+
+def test_raw_path_bound_is_the_unit_speed_critical_path(lib, oracle):
+    """U0 is the critical path with w = c and x = t: one device per vertex pair
+    cannot be arranged in general, so compare on a chain-free bound instead: it
+    must dominate CP for any speeds/bandwidth >= 1 and equal the longest raw path."""
+    w = make_workload("large_sparse", P=6, levels=25, width=12)
+    g = cpe.CpGraph.from_workload(w)
+    u0 = g.info["raw_path_bound"]
+    # longest raw path by plain DP in level order
+    best = np.zeros(w.n, dtype=np.int64)
+    for l in range(w.L - 1, -1, -1):
+        for v in w.level_vtx[w.level_ptr[l]:w.level_ptr[l + 1]]:
+            e0, e1 = w.succ_ptr[v], w.succ_ptr[v + 1]
+            m = 0 if e0 == e1 else int((w.succ_t[e0:e1] + best[w.succ_idx[e0:e1]]).max())
+            best[v] = w.c[v] + m
+    assert u0 == int(best.max())
+    out = oracle.evaluate_workload(w)
+    assert (out["cp"] <= u0).all()
+    assert g.info["min_tick_bytes"] == 4
+
+
+def test_create_rejects_bad_graphs(lib):
+    w = make_workload("tiny")
+    base = _graph_args(w)
+    assert _create_rc(**base) == 0
+
+    a = dict(base); a["succ_ptr"] = base["succ_ptr"].copy(); a["succ_ptr"][3] = a["succ_ptr"][4] + 1
+    assert _create_rc(**a) == -3                       # non-monotone ptr
+    a = dict(base); a["succ_idx"] = base["succ_idx"].copy(); a["succ_idx"][0] = w.n
+    assert _create_rc(**a) == -3                       # index out of range
+    a = dict(base); a["pred_eid"] = base["pred_eid"].copy(); a["pred_eid"][0] = a["pred_eid"][1]
+    assert _create_rc(**a) == -3                       # eid not a permutation
+    a = dict(base); a["pred_idx"] = base["pred_idx"].copy()
+    a["pred_idx"][0] = (a["pred_idx"][0] + 1) % w.n
+    assert _create_rc(**a) == -3                       # pred disagrees with succ
+    a = dict(base); a["level_vtx"] = base["level_vtx"].copy(); a["level_vtx"][0] = a["level_vtx"][1]
+    assert _create_rc(**a) == -4                       # not a permutation
+    a = dict(base); a["level_vtx"] = base["level_vtx"][::-1].copy()
+    assert _create_rc(**a) == -4                       # edges go down
+    a = dict(base); a["c"] = base["c"].copy(); a["c"][5] = -1
+    assert _create_rc(**a) == -5
+    a = dict(base); a["succ_t"] = base["succ_t"].copy(); a["succ_t"][7] = -3
+    assert _create_rc(**a) == -5
+    a = dict(base); a["c"] = base["c"].copy(); a["c"][:] = 2**61
+    assert _create_rc(**a) == -8                       # raw path bound >= 2^62
+    a = dict(base); a["n"] = 0
+    assert _create_rc(**a) == -2
+    a = dict(base); a["c"] = None
+    assert _create_rc(**a) == -1
+
+
+def test_cycle_is_rejected_through_the_level_check(lib):
+    # 0 -> 1 -> 0 cannot be levelled
+    csr = dict(n=2, succ_ptr=[0, 1, 2], succ_idx=[1, 0], succ_t=[1, 1],
+               pred_ptr=[0, 1, 2], pred_idx=[1, 0], pred_eid=[1, 0], c=[1, 1],
+               level_ptr=[0, 1, 2], level_vtx=[0, 1])
+    assert _create_rc(**csr) == -4
+
+
+def test_edgeless_and_wide_tick_graphs(lib):
+    g = cpe.CpGraph(5, [0] * 6, None, None, [0] * 6, None, None, [3, 1, 4, 1, 5], [0, 5], [0, 1, 2, 3, 4])
+    assert g.info["m"] == 0 and g.info["num_sources"] == 5 and g.info["raw_path_bound"] == 5
+    g.close()
+    csr = build_csr(3, [0, 1], [1, 2], [2**40, 5])
+    g = cpe.CpGraph(3, csr["succ_ptr"], csr["succ_idx"], csr["succ_t"], csr["pred_ptr"],
+                    csr["pred_idx"], csr["pred_eid"], [1, 1, 1], csr["level_ptr"], csr["level_vtx"])
+    assert g.info["min_tick_bytes"] == 8 and g.info["window_ok"] == 0
+    assert g.info["auto_plan"] == cpe.PLAN_WAVE_COLUMN
+    g.close()
+
+
+def test_plan_selection_facts(lib):
+    w = make_workload("large_sparse", P=4, levels=40, width=30)
+    g = cpe.CpGraph.from_workload(w)
+    info = g.info
+    assert info["window_ok"] == 1 and info["auto_plan"] == cpe.PLAN_RESIDENT_WINDOW
+    # the ring must cover at least one level plus the longest edge span (10 levels here)
+    assert 30 <= info["window_slots_b"] <= 11 * 30
+    assert 30 <= info["window_slots_t"] <= 11 * 30
+    g.close()
+    w = make_workload("comm_heavy", P=4, levels=4, width=400, hub_degree=300)
+    g = cpe.CpGraph.from_workload(w)
+    assert g.info["auto_plan"] == cpe.PLAN_WAVE_COLUMN   # hub rows
+    g.close()
+
+
+def test_workspace_bytes_and_eval_argument_errors(lib):
+    w = make_workload("tiny")
+    g = cpe.CpGraph.from_workload(w)
+    assert binding.workspace_bytes(g, 16, 2, plan=cpe.PLAN_RESIDENT_WINDOW) == 256
+    assert binding.workspace_bytes(g, 16, 2, plan=cpe.PLAN_WAVE_COLUMN) == 256 + 1024
+    assert binding.workspace_bytes(g, 16, 2, assign_layout=binding.ASSIGN_VERTEX_MAJOR) == 256
+    with pytest.raises(cpe.CpError) as e:
+        binding.workspace_bytes(g, 0, 2)
+    assert e.value.code == -2
+    with pytest.raises(cpe.CpError) as e:
+        binding.workspace_bytes(g, 4, 256)
+    assert e.value.code == -2
+
+    s = np.array([1, 2], dtype=np.int64)
+    B = np.array([[1, 10], [10, 1]], dtype=np.int64)
+    dummy = C.c_void_p(256)   # never dereferenced: every call below fails before any use
+    i64p = C.POINTER(C.c_int64)
+
+    def call(batch=4, k=2, assign=dummy, layout=0, sp=s, bw=B, ws=dummy, cp=dummy, b=dummy, tl=dummy,
+             mask=dummy, tick=4, plan=0, status=dummy):
+        return lib.cp_eval(g._handle, batch, k, assign, layout, sp.ctypes.data_as(i64p),
+                           bw.ctypes.data_as(i64p), ws, 1 << 20, None, cp, b, tl, mask, tick, plan,
+                           status, None)
+
+    assert call(batch=0) == -2
+    assert call(k=0) == -2
+    assert call(layout=7) == -12
+    assert call(plan=9) == -12
+    assert call(tick=2) == -12
+    assert call(assign=C.c_void_p()) == -1
+    assert call(status=C.c_void_p()) == -1
+    assert call(b=C.c_void_p()) == -12            # cp needs b
+    assert call(tl=C.c_void_p()) == -12           # mask needs tl
+    assert call() == -11                          # everything fine, but the graph was never uploaded
+    g.close()
+
+
+@pytest.mark.parametrize("amax", [0, 1, 999, 10**4, 10**7, 2**31, 2**32 - 1])
+def test_multiply_shift_constants_are_exact(lib, amax):
+    rng = np.random.default_rng(amax % 1000)
+    divisors = list(range(1, 70)) + [100, 255, 256, 257, 1000, 4095, 4096, 65535, 65536, 65537,
+                                     10**6, 2**31 - 1, 2**31, 2**32 - 1]
+    divisors += [int(x) for x in rng.integers(1, 2**32, size=40)]
+    found = 0
+    for d in divisors:
+        mg = cpe.cost_magic(d, amax)
+        if mg is None:
+            continue
+        found += 1
+        mul, dm1 = mg
+        assert dm1 == d - 1
+        # dividends around every multiple boundary near the ends, plus random ones
+        cands = {0, 1, amax, max(0, amax - 1)}
+        for q in (1, 2, 3, amax // d, max(0, amax // d - 1)):
+            for delta in (-1, 0, 1):
+                cands.add(q * d + delta)
+        cands |= {int(x) for x in rng.integers(0, amax + 1, size=200)}
+        for a in cands:
+            if 0 <= a <= amax:
+                n_ = a + dm1
+                assert n_ < 2**32
+                assert (n_ * mul + n_) >> 32 == -(-a // d), (a, d)
+    if amax <= 10**7:
+        assert found >= 69   # every small divisor must take the fast path for small weights
+
+
+def test_multiply_shift_exhaustive_small_range(lib):
+    for d in range(1, 130):
+        mul, dm1 = cpe.cost_magic(d, 5000)
+        a = np.arange(0, 5001, dtype=np.uint64)
+        n_ = a + np.uint64(dm1)
+        got = (n_ * np.uint64(mul) + n_) >> np.uint64(32)
+        assert (got == (a + np.uint64(d - 1)) // np.uint64(d)).all()
