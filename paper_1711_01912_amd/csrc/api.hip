@@ -58,10 +58,20 @@ int stage_and_copy(const void *src, size_t bytes, void *dst, hipStream_t st) {
 
 constexpr size_t kWindowLdsLimit = kLdsBudget - 256;   // room for the kernel's static LDS
 
-bool window_fits(const Packed &p, int32_t k, size_t tick_bytes) {
+bool window_fits(const Packed &p, int32_t k, size_t tick_bytes, size_t limit = kWindowLdsLimit) {
     if (!p.have_window || k > kMagicMaxK) return false;
-    return window_lds_bytes(k, p.win_b.slots, tick_bytes) <= kWindowLdsLimit &&
-           window_lds_bytes(k, p.win_t.slots, tick_bytes) <= kWindowLdsLimit;
+    return window_lds_bytes(k, p.win_b.slots, tick_bytes) <= limit &&
+           window_lds_bytes(k, p.win_t.slots, tick_bytes) <= limit;
+}
+
+// LDS one workgroup may use on the current device, minus the kernel's static part.
+size_t device_window_lds_limit() {
+    int dev = 0, bytes = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&bytes, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess)
+        return 0;
+    size_t lim = std::min<size_t>((size_t)std::max(bytes, 0), kLdsBudget);
+    return lim > 256 ? lim - 256 : 0;
 }
 
 // The resident-window plan pays the graph stream once per partition and wins when
@@ -178,7 +188,7 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
     if (rc) return rc;
 
     // plan
-    const bool can_window = tabs.magic_ok && window_fits(p, k, (size_t)tick_dtype);
+    const bool can_window = tabs.magic_ok && window_fits(p, k, (size_t)tick_dtype, device_window_lds_limit());
     int use = plan;
     if (plan == CP_PLAN_AUTO)
         use = can_window && window_preferred(p) ? CP_PLAN_RESIDENT_WINDOW : CP_PLAN_WAVE_COLUMN;

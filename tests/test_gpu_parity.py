@@ -185,7 +185,7 @@ def test_tick_width_request_is_checked(gpu, oracle):
         gpu.cp_eval(g, a, w.speeds, w.bandwidth, tick_bytes=4)
     assert e.value.code == -8
     g.close()
-    _check(gpu, oracle, w, ticks=(8,))
+    _check(gpu, oracle, w, plans=(COLUMN,), ticks=(8,))
 
 
 def test_bad_device_id_is_reported_not_fatal(gpu):
