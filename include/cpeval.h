@@ -91,6 +91,8 @@ typedef struct cp_graph_info {
     int32_t window_ok;           /* 1 if the resident-window plan can run this graph */
     int32_t window_slots_b;      /* LDS slots the b-level sweep needs under that plan */
     int32_t window_slots_t;      /* ... and the t-level sweep */
+    int32_t window_packet_bytes_b;   /* largest per-level packet of that plan, b-level sweep */
+    int32_t window_packet_bytes_t;   /* ... and t-level sweep */
     int32_t auto_plan;           /* plan CP_PLAN_AUTO resolves to */
     int32_t uploaded;            /* 1 after cp_graph_upload */
     uint64_t blob_bytes;

@@ -39,6 +39,7 @@ class GraphInfo(C.Structure):
         ("max_c", C.c_int64), ("max_t", C.c_int64), ("raw_path_bound", C.c_int64),
         ("min_tick_bytes", C.c_int32), ("window_ok", C.c_int32),
         ("window_slots_b", C.c_int32), ("window_slots_t", C.c_int32),
+        ("window_packet_bytes_b", C.c_int32), ("window_packet_bytes_t", C.c_int32),
         ("auto_plan", C.c_int32), ("uploaded", C.c_int32), ("blob_bytes", C.c_uint64),
     ]
 

@@ -58,10 +58,19 @@ int stage_and_copy(const void *src, size_t bytes, void *dst, hipStream_t st) {
 
 constexpr size_t kWindowLdsLimit = kLdsBudget - 256;   // room for the kernel's static LDS
 
-bool window_fits(const Packed &p, int32_t k, size_t tick_bytes, size_t limit = kWindowLdsLimit) {
+bool window_fits(const Packed &p, int32_t k, size_t tick_bytes, size_t limit = kWindowLdsLimit,
+                 WindowCfg *cfg_b = nullptr, WindowCfg *cfg_t = nullptr) {
     if (!p.have_window || k > kMagicMaxK) return false;
-    return window_lds_bytes(k, p.win_b.slots, tick_bytes) <= limit &&
-           window_lds_bytes(k, p.win_t.slots, tick_bytes) <= limit;
+    WindowCfg b, t;
+    if (!window_config(p.win_b, k, tick_bytes, limit, b)) return false;
+    if (!window_config(p.win_t, k, tick_bytes, limit, t)) return false;
+    if (cfg_b) *cfg_b = b;
+    if (cfg_t) *cfg_t = t;
+    return true;
+}
+
+size_t pperm_bytes(const Packed &p, const WindowDir &d, int32_t batch) {
+    return align_up((size_t)batch * (size_t)p.L * (size_t)d.wpad);
 }
 
 // LDS one workgroup may use on the current device, minus the kernel's static part.
@@ -155,9 +164,13 @@ int cp_eval_workspace_bytes(const cp_graph *g, int32_t batch, int32_t k, int ass
     size_t bytes = tables_bytes(k);
     // the wave-column plan reads device ids vertex-major; under CP_PLAN_AUTO it may be
     // the one that runs, whatever the graph prefers, if the cost model rules the other out
+    size_t column = 0, window = 0;
     if (assign_layout == CP_ASSIGN_PARTITION_MAJOR && plan != CP_PLAN_RESIDENT_WINDOW)
-        bytes += align_up((size_t)g->packed.n * (size_t)batch);
-    *out_bytes = bytes;
+        column = align_up((size_t)g->packed.n * (size_t)batch);
+    // the resident-window plan gathers the device ids into sweep order, once per direction
+    if (plan != CP_PLAN_WAVE_COLUMN && g->packed.have_window)
+        window = pperm_bytes(g->packed, g->packed.win_b, batch) + pperm_bytes(g->packed, g->packed.win_t, batch);
+    *out_bytes = bytes + std::max(column, window);
     return CP_OK;
 }
 
@@ -188,7 +201,9 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
     if (rc) return rc;
 
     // plan
-    const bool can_window = tabs.magic_ok && window_fits(p, k, (size_t)tick_dtype, device_window_lds_limit());
+    WindowCfg cfg_b, cfg_t;
+    const bool can_window = tabs.magic_ok && window_fits(p, k, (size_t)tick_dtype,
+                                                         device_window_lds_limit(), &cfg_b, &cfg_t);
     int use = plan;
     if (plan == CP_PLAN_AUTO)
         use = can_window && window_preferred(p) ? CP_PLAN_RESIDENT_WINDOW : CP_PLAN_WAVE_COLUMN;
@@ -197,10 +212,14 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
     // workspace
     const bool need_pT = use == CP_PLAN_WAVE_COLUMN && assign_layout == CP_ASSIGN_PARTITION_MAJOR;
     size_t need = tables_bytes(k) + (need_pT ? align_up((size_t)p.n * (size_t)batch) : 0);
+    if (use == CP_PLAN_RESIDENT_WINDOW)
+        need += pperm_bytes(p, p.win_b, batch) + pperm_bytes(p, p.win_t, batch);
     if (workspace_bytes < need) return CP_ERR_WORKSPACE;
     uint8_t *ws = (uint8_t *)workspace;
     uint8_t *d_tab = ws;
     uint8_t *d_pT = ws + tables_bytes(k);
+    uint8_t *d_pperm_b = ws + tables_bytes(k);
+    uint8_t *d_pperm_t = d_pperm_b + pperm_bytes(p, p.win_b, batch);
 
     hipStream_t st = (hipStream_t)stream;
     hipEvent_t *ev = nullptr;
@@ -244,6 +263,18 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
     else { s.a_stride_p = 1; s.a_stride_v = batch; }
     s.vert_tab = d_tab + 2 * kk * 8;
     s.status = status_out;
+    if (use == CP_PLAN_RESIDENT_WINDOW) {   // device ids into sweep order, per direction
+        if (blevel_out) {
+            s.win = &p.win_b;
+            rc = launch_gather_assign(s, d_pperm_b, stream);
+            if (rc) return rc;
+        }
+        if (tlevel_out) {
+            s.win = &p.win_t;
+            rc = launch_gather_assign(s, d_pperm_t, stream);
+            if (rc) return rc;
+        }
+    }
 
     // ---- stage: b-level sweep
     CP_MARK(CP_STAGE_BLEVEL);
@@ -254,7 +285,8 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
         s.val = blevel_out;
         s.edge_tab = d_tab;
         s.cp_out = use == CP_PLAN_RESIDENT_WINDOW ? cp_out : nullptr;
-        rc = use == CP_PLAN_RESIDENT_WINDOW ? launch_window_sweep(s, stream, launches)
+        s.pperm = d_pperm_b;
+        rc = use == CP_PLAN_RESIDENT_WINDOW ? launch_window_sweep(s, cfg_b, stream, launches)
                                             : launch_column_sweep(s, stream, launches);
         if (rc) return rc;
     }
@@ -276,7 +308,8 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
         s.val = tlevel_out;
         s.edge_tab = d_tab + kk * 8;
         s.cp_out = nullptr;
-        rc = use == CP_PLAN_RESIDENT_WINDOW ? launch_window_sweep(s, stream, launches ? launches + 1 : nullptr)
+        s.pperm = d_pperm_t;
+        rc = use == CP_PLAN_RESIDENT_WINDOW ? launch_window_sweep(s, cfg_t, stream, launches ? launches + 1 : nullptr)
                                             : launch_column_sweep(s, stream, launches ? launches + 1 : nullptr);
         if (rc) return rc;
     }

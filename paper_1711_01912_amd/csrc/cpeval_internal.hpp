@@ -16,7 +16,7 @@ constexpr int kHubWaves = 16;          // ... of this many wavefronts
 constexpr int kMagicMaxK = 64;         // multiply-shift tables are staged in LDS up to this many devices
 constexpr size_t kAlign = 256;
 constexpr size_t kLdsBudget = 160 * 1024;   // LDS per workgroup on gfx950
-constexpr int kWindowMaxThreads = 1024;
+constexpr int kWindowMaxWaves = 16;      // wavefronts per workgroup (compute + loader)
 
 inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
 
@@ -31,18 +31,28 @@ struct ColumnDir {
 };
 
 // One sweep direction of the resident-window plan.  Vertices are renumbered by
-// position in sweep order; rows are packed in slices of 64 positions (one per
-// wavefront), entry j of lane l of a slice at slice_off + j*64 + l.
+// position in sweep order.  Everything a level needs is one contiguous "packet"
+// of 16-byte chunks, so that loader wavefronts can stream it into LDS ahead of
+// the compute wavefronts:
+//   [ 0,16)  header  {npos, nslices, ring_base = first position mod slots, 0}
+//   [16, ..) slice table, nslices x {entry base, width | log2(lanes per row) << 24}
+//            (padded to 16 bytes); a slice of at most 32 rows gives each row 2..64
+//            lanes that share its edges and fold their maxima at the end
+//            records, nslices*64 x {original vertex id (0xffffffff = padding), c}
+//            entries, per slice width x 64 x {ring slot of the neighbour, t(e)};
+//            entry j of lane l of a slice sits at base + j*64 + l, padding entries
+//            are {slots, 0}: ring slot `slots` holds the constant 0.  An entry is
+//            two uint32, or one uint32 (slot | t << 16) when both fit 16 bits (ent4)
 struct WindowDir {
-    size_t vtx_off = 0;     // int32 [n]        original id at each position
-    size_t c_off = 0;       // uint32 [n]       c at each position
-    size_t deg_off = 0;     // int32 [n]        row length at each position
-    size_t lvl_off = 0;     // int32 [L+1][2]   per level in sweep order: {first position, first slice}
-    size_t slice_off = 0;   // uint32 [slices+1] entry offset of each slice
-    size_t ent_off = 0;     // uint2 [entries]  {LDS slot of the neighbour, t(e)}
-    int64_t entries = 0;
-    int32_t slices = 0;
-    int32_t slots = 0;      // ring capacity R: slot of position i is i mod R
+    size_t stream_off = 0;   // uint4 [total_chunks]
+    size_t pkt_off = 0;      // uint32 [L+1] first chunk of each packet, in sweep order
+    size_t gmap_off = 0;     // int32 [L*wpad] original id per padded position, -1 = padding
+    int64_t total_chunks = 0;
+    int32_t max_chunks = 0;  // largest packet
+    int32_t wpad = 0;        // level width rounded up to whole slices of 64
+    int32_t smax = 0;        // slices of the widest level
+    int32_t slots = 0;       // ring capacity R: slot of position i is i mod R
+    bool ent4 = false;       // 4-byte entries
 };
 
 struct Packed {

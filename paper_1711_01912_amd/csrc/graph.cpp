@@ -85,16 +85,26 @@ void pack_column_dir(BlobWriter &w, int32_t n, int64_t m, bool narrow, const Csr
     std::memcpy(w.at<int32_t>(dir.order_off), order.data(), sizeof(int32_t) * (size_t)n);
 }
 
-// Resident-window packing for one direction.  Returns false if the entry count
-// does not fit the 32-bit slice offsets.
-bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, const Csr &csr,
-                     const std::vector<int32_t> &order, const ColumnDir &col, WindowDir &dir) {
+// A slice with few rows spreads each row over several lanes: log2 of the lanes
+// per row for a slice of `rows` vertices.
+int lanes_per_row_log2(int rows) {
+    int sh = 0;
+    while ((rows << (sh + 1)) <= kWave) ++sh;
+    return sh;
+}
+
+// Resident-window packing for one direction (layout: see WindowDir).  Returns
+// false if the packets would be unreasonably large.
+bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int64_t max_t,
+                     const Csr &csr, const std::vector<int32_t> &order, const ColumnDir &col,
+                     WindowDir &dir) {
     std::vector<int32_t> pos(n);
     for (int32_t i = 0; i < n; ++i) pos[order[i]] = i;
 
     // ring capacity: while a level [a, b) is being written, every position from the
     // earliest one it reads up to b-1 must own a distinct slot
     int64_t need = 1;
+    int32_t wmax = 1;
     for (int32_t s = 0; s < L; ++s) {
         int32_t a = col.lvl_begin[s], b = a + col.lvl_count[s];
         int32_t jmin = a;
@@ -103,61 +113,102 @@ bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, cons
             for (int32_t e = csr.ptr[v]; e < csr.ptr[v + 1]; ++e) jmin = std::min(jmin, pos[csr.idx[e]]);
         }
         need = std::max<int64_t>(need, (int64_t)b - jmin);
+        wmax = std::max(wmax, b - a);
     }
     dir.slots = (int32_t)need;
+    dir.ent4 = need < 65536 && max_t < 65536;
+    const uint64_t esz = dir.ent4 ? 4 : 8;
+    dir.smax = (wmax + kWave - 1) / kWave;
+    dir.wpad = dir.smax * kWave;
 
-    // slices
-    std::vector<uint32_t> slice_off;
-    std::vector<int32_t> lvl(2 * ((size_t)L + 1));
-    uint64_t entries = 0;
+    // packet sizes
+    std::vector<uint32_t> pkt_off((size_t)L + 1);
+    uint64_t total = 0;
+    uint32_t max_chunks = 1;
     for (int32_t s = 0; s < L; ++s) {
         int32_t a = col.lvl_begin[s], b = a + col.lvl_count[s];
-        lvl[2 * s] = a;
-        lvl[2 * s + 1] = (int32_t)slice_off.size();
+        uint64_t nsl = (uint64_t)(b - a + kWave - 1) / kWave;
+        uint64_t entries = 0;
         for (int32_t p0 = a; p0 < b; p0 += kWave) {
             int32_t v0 = order[p0];
-            uint32_t width = (uint32_t)(csr.ptr[v0 + 1] - csr.ptr[v0]);  // longest row leads
-            slice_off.push_back((uint32_t)entries);
-            entries += (uint64_t)width * kWave;
-            if (entries >= (1ull << 32)) return false;
+            int64_t deg0 = csr.ptr[v0 + 1] - csr.ptr[v0];                 // longest row leads
+            int sh = lanes_per_row_log2(std::min(kWave, b - p0));
+            entries += (uint64_t)((deg0 + (1 << sh) - 1) >> sh) * kWave;
         }
+        uint64_t bytes = 16 + align_up(8 * nsl, 16) + 8 * kWave * nsl + esz * entries;
+        uint64_t chunks = bytes / 16;
+        if (chunks > (1u << 20)) return false;      // a 16 MB level never fits LDS anyway
+        pkt_off[s] = (uint32_t)total;
+        total += chunks;
+        if (total >= (1ull << 31)) return false;
+        max_chunks = std::max<uint32_t>(max_chunks, (uint32_t)chunks);
     }
-    lvl[2 * L] = n;
-    lvl[2 * L + 1] = (int32_t)slice_off.size();
-    slice_off.push_back((uint32_t)entries);
-    dir.slices = (int32_t)slice_off.size() - 1;
-    dir.entries = (int64_t)entries;
+    pkt_off[L] = (uint32_t)total;
+    dir.total_chunks = (int64_t)total;
+    dir.max_chunks = (int32_t)max_chunks;
 
-    dir.vtx_off = w.reserve(sizeof(int32_t) * (size_t)n);
-    std::memcpy(w.at<int32_t>(dir.vtx_off), order.data(), sizeof(int32_t) * (size_t)n);
-    dir.c_off = w.reserve(sizeof(uint32_t) * (size_t)n);
-    dir.deg_off = w.reserve(sizeof(int32_t) * (size_t)n);
-    dir.lvl_off = w.reserve(sizeof(int32_t) * lvl.size());
-    std::memcpy(w.at<int32_t>(dir.lvl_off), lvl.data(), sizeof(int32_t) * lvl.size());
-    dir.slice_off = w.reserve(sizeof(uint32_t) * slice_off.size());
-    std::memcpy(w.at<uint32_t>(dir.slice_off), slice_off.data(), sizeof(uint32_t) * slice_off.size());
-    dir.ent_off = w.reserve(sizeof(uint32_t) * 2 * (size_t)std::max<uint64_t>(entries, 1));
+    dir.stream_off = w.reserve(16 * (size_t)std::max<uint64_t>(total, 1));
+    dir.pkt_off = w.reserve(sizeof(uint32_t) * pkt_off.size());
+    std::memcpy(w.at<uint32_t>(dir.pkt_off), pkt_off.data(), sizeof(uint32_t) * pkt_off.size());
+    dir.gmap_off = w.reserve(sizeof(int32_t) * (size_t)L * dir.wpad);
+    int32_t *gmap = w.at<int32_t>(dir.gmap_off);
+    std::fill(gmap, gmap + (size_t)L * dir.wpad, -1);
 
-    uint32_t *cp = w.at<uint32_t>(dir.c_off);
-    int32_t *dg = w.at<int32_t>(dir.deg_off);
-    uint32_t *ent = w.at<uint32_t>(dir.ent_off);
-    int32_t slice = 0;
     for (int32_t s = 0; s < L; ++s) {
         int32_t a = col.lvl_begin[s], b = a + col.lvl_count[s];
-        for (int32_t p0 = a; p0 < b; p0 += kWave, ++slice) {
-            uint64_t base = slice_off[slice];
-            for (int32_t i = p0; i < std::min(b, p0 + kWave); ++i) {
-                int32_t v = order[i];
-                int32_t d = csr.ptr[v + 1] - csr.ptr[v];
-                cp[i] = (uint32_t)c[v];
-                dg[i] = d;
-                for (int32_t j = 0; j < d; ++j) {
-                    int64_t e = (int64_t)csr.ptr[v] + j;
-                    uint64_t at = base + (uint64_t)j * kWave + (uint32_t)(i - p0);
-                    ent[2 * at] = (uint32_t)(pos[csr.idx[e]] % dir.slots);
-                    ent[2 * at + 1] = (uint32_t)csr.wt[e];
+        uint32_t nsl = (uint32_t)(b - a + kWave - 1) / kWave;
+        uint32_t *pk = w.at<uint32_t>(dir.stream_off + 16 * (size_t)pkt_off[s]);
+        pk[0] = (uint32_t)(b - a);
+        pk[1] = nsl;
+        pk[2] = (uint32_t)(a % dir.slots);
+        pk[3] = 0;
+        uint32_t *slice_tab = pk + 4;
+        uint32_t *rec = slice_tab + align_up(8 * (size_t)nsl, 16) / 4;
+        uint32_t *ent = rec + 2 * (size_t)kWave * nsl;
+        uint32_t ebase = 0;
+        for (uint32_t j = 0; j < nsl; ++j) {
+            int32_t p0 = a + (int32_t)j * kWave;
+            int32_t rows = std::min(kWave, b - p0);
+            int32_t v0 = order[p0];
+            int sh = lanes_per_row_log2(rows);
+            int32_t lpr = 1 << sh;
+            uint32_t width = (uint32_t)((csr.ptr[v0 + 1] - csr.ptr[v0] + lpr - 1) >> sh);
+            slice_tab[2 * j] = ebase;
+            slice_tab[2 * j + 1] = width | ((uint32_t)sh << 24);
+            for (int32_t r = 0; r < kWave; ++r) {       // records: one per row
+                uint32_t *rc = rec + 2 * ((size_t)j * kWave + r);
+                if (r < rows) {
+                    int32_t v = order[p0 + r];
+                    rc[0] = (uint32_t)v;
+                    rc[1] = (uint32_t)c[v];
+                    gmap[(size_t)s * dir.wpad + (size_t)j * kWave + r] = v;
+                } else {
+                    rc[0] = 0xffffffffu;
+                    rc[1] = 0;
                 }
             }
+            for (int32_t l = 0; l < kWave; ++l) {       // entries: lane l serves row l >> sh
+                int32_t r = l >> sh, sub = l & (lpr - 1);
+                int32_t v = r < rows ? order[p0 + r] : -1;
+                int32_t d = v >= 0 ? csr.ptr[v + 1] - csr.ptr[v] : 0;
+                for (uint32_t jj = 0; jj < width; ++jj) {
+                    const size_t at = (size_t)ebase + (size_t)jj * kWave + l;
+                    int64_t ei = (int64_t)jj * lpr + sub;
+                    uint32_t slot = (uint32_t)dir.slots, te = 0;    // padding: the constant-zero slot
+                    if (ei < d) {
+                        int64_t e = (int64_t)csr.ptr[v] + ei;
+                        slot = (uint32_t)(pos[csr.idx[e]] % dir.slots);
+                        te = (uint32_t)csr.wt[e];
+                    }
+                    if (dir.ent4) {
+                        ent[at] = slot | (te << 16);
+                    } else {
+                        ent[2 * at] = slot;
+                        ent[2 * at + 1] = te;
+                    }
+                }
+            }
+            ebase += width * kWave;
         }
     }
     return true;
@@ -290,8 +341,8 @@ int pack_graph(int32_t n, int64_t m, int32_t L,
         P.have_window = false;
         if (P.narrow) {
             size_t mark = P.blob.size();
-            bool ok = pack_window_dir(w, n, L, c, succ, order_b, P.col_b, P.win_b) &&
-                      pack_window_dir(w, n, L, c, pred, order_t, P.col_t, P.win_t);
+            bool ok = pack_window_dir(w, n, L, c, max_t, succ, order_b, P.col_b, P.win_b) &&
+                      pack_window_dir(w, n, L, c, max_t, pred, order_t, P.col_t, P.win_t);
             if (ok) P.have_window = true;
             else P.blob.resize(mark);
         }
@@ -302,6 +353,8 @@ int pack_graph(int32_t n, int64_t m, int32_t L,
 
     info.window_slots_b = P.have_window ? P.win_b.slots : 0;
     info.window_slots_t = P.have_window ? P.win_t.slots : 0;
+    info.window_packet_bytes_b = P.have_window ? 16 * P.win_b.max_chunks : 0;
+    info.window_packet_bytes_t = P.have_window ? 16 * P.win_t.max_chunks : 0;
     info.blob_bytes = P.blob.size();
     return CP_OK;
 }

@@ -15,6 +15,8 @@
 //    dependency never leaves the compute unit.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "launch.hpp"
 
 namespace cpeval {
@@ -225,85 +227,232 @@ __global__ __launch_bounds__(256) void mask_kernel(const Tick *__restrict__ b,
 
 // ---------------------------------------------------------------- resident-window sweep
 
+// Barrier that orders LDS traffic only: global loads issued by the loader
+// wavefronts stay in flight across it.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Device ids gathered into sweep order, one padded row of L*wpad bytes per
+// partition, so that the sweep kernel streams them like the graph packets.
+// Ids >= k are reported and replaced by 0.
+__global__ __launch_bounds__(256) void gather_assign_kernel(const int32_t *__restrict__ gmap,
+                                                            int64_t row_len,
+                                                            const uint8_t *__restrict__ assign,
+                                                            int64_t a_stride_p, int64_t a_stride_v,
+                                                            int32_t k, uint8_t *__restrict__ out,
+                                                            int32_t *status) {
+    const int64_t i4 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;   // row_len is a multiple of 64
+    if (i4 >= row_len) return;
+    const int64_t q = blockIdx.y;
+    const int4 v = *(const int4 *)(gmap + i4);
+    const uint8_t *row = assign + q * a_stride_p;
+    uint32_t p0 = v.x >= 0 ? row[(int64_t)v.x * a_stride_v] : 0;
+    uint32_t p1 = v.y >= 0 ? row[(int64_t)v.y * a_stride_v] : 0;
+    uint32_t p2 = v.z >= 0 ? row[(int64_t)v.z * a_stride_v] : 0;
+    uint32_t p3 = v.w >= 0 ? row[(int64_t)v.w * a_stride_v] : 0;
+    if (max(max(p0, p1), max(p2, p3)) >= (uint32_t)k) {
+        *status = CP_STATUS_BAD_DEVICE_ID;
+        if (p0 >= (uint32_t)k) p0 = 0;
+        if (p1 >= (uint32_t)k) p1 = 0;
+        if (p2 >= (uint32_t)k) p2 = 0;
+        if (p3 >= (uint32_t)k) p3 = 0;
+    }
+    *(uint32_t *)(out + q * row_len + i4) = p0 | (p1 << 8) | (p2 << 16) | (p3 << 24);
+}
+
 struct WindowArgs {
-    const int32_t *vtx;        // [n] original id per position
-    const uint32_t *c;         // [n]
-    const int32_t *deg;        // [n]
-    const int32_t *lvl;        // [L+1][2]
-    const uint32_t *slice_off; // [slices+1]
-    const uint2 *ent;          // {slot, t}
-    const uint8_t *assign;     // [P][n] or [n][P]
-    int64_t a_stride_p, a_stride_v;   // element strides of `assign`
+    const uint4 *stream;       // level packets
+    const uint32_t *pkt_off;   // [L+1] first chunk of each packet
+    const uint8_t *pperm;      // [P][L*wpad] device ids in sweep order
     void *out;                 // [n][P] ticks, or NULL
-    int64_t *cp_out;           // [P] or NULL: receives max of the values written to the ring
+    int64_t *cp_out;           // [P] or NULL: receives the maximum of b over the partition
     const Magic *edge_tab;
     const Magic *vert_tab;
-    int32_t *status;
-    int32_t P, L, k, slots;
+    int32_t P, L, k, slots, wpad;
+    int32_t nc, nlw;           // compute and loader wavefronts per workgroup
+    int32_t pgroups;           // partitions per XCD-sized group (blockIdx -> partition map)
 };
 
-template <typename Tick, bool TSWEEP>
-__global__ __launch_bounds__(kWindowMaxThreads) void window_sweep_kernel(WindowArgs a) {
-    extern __shared__ uint64_t lds[];
+template <typename Tick, bool PACKED> struct Ring;
+
+// {value, device id} in one 8-byte element: one LDS read per relaxation
+template <> struct Ring<int32_t, true> {
+    uint2 *e;
+    __device__ void init(uint8_t *base, int) { e = (uint2 *)base; }
+    __device__ void put(int slot, int32_t val, uint32_t p) { e[slot] = make_uint2((uint32_t)val, p); }
+    __device__ void get(int slot, int32_t &val, uint32_t &p) const {
+        const uint2 x = e[slot];
+        val = (int32_t)x.x;
+        p = x.y;
+    }
+};
+// separate arrays: 5 (or 9) bytes per slot when the window is large
+template <typename Tick> struct Ring<Tick, false> {
+    Tick *v;
+    uint8_t *d;
+    __device__ void init(uint8_t *base, int slots) {
+        v = (Tick *)base;
+        d = base + sizeof(Tick) * ((size_t)slots + 1);
+    }
+    __device__ void put(int slot, Tick val, uint32_t p) { v[slot] = val; d[slot] = (uint8_t)p; }
+    __device__ void get(int slot, Tick &val, uint32_t &p) const { val = v[slot]; p = d[slot]; }
+};
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // stays in registers when indexed statically
+typedef const uint32_t __attribute__((address_space(4))) *const_u32_ptr;   // uniform reads become scalar loads
+
+// LDS layout: [tables][ring][stage slot 0][stage slot 1]; a stage slot is
+// [wpad bytes of device ids][packet], NL*nlw*1024 bytes in all.
+//
+// Wavefronts 0..nc-1 compute, wavefronts nc..nc+nlw-1 load.  Tick t: after the
+// barrier the compute wavefronts relax level t out of stage slot t&1 while the
+// loaders copy packet t+1 (which they requested DR ticks earlier and hold in
+// registers) into the other slot and request packet t+1+DR.  The only traffic on
+// the level-to-level dependency is LDS.
+template <typename Tick, bool TSWEEP, bool PACKED, bool ENT4, int NL, int DR>
+__global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(WindowArgs a) {
+    extern __shared__ uint4 lds16[];
+    __shared__ long long red[kWindowMaxWaves];
+    uint8_t *lds = (uint8_t *)lds16;
     const int tid = threadIdx.x, lane = tid & 63, nt = blockDim.x;
-    const int k = a.k;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int k = a.k, L = a.L;
+
+    // blockIdx -> partition: blocks are dealt round-robin to the 8 XCDs; give each
+    // XCD a run of consecutive partitions so that the 4-byte stores of one output
+    // line meet in one L2
+    const int32_t q = (int32_t)(blockIdx.x % 8) * a.pgroups + (int32_t)(blockIdx.x / 8);
+    if (q >= a.P) return;      // whole workgroup: no barrier has been reached yet
+
     Magic *etab = (Magic *)lds;
     Magic *vtab = etab + k * k;
-    Tick *ring = (Tick *)(vtab + k);                    // 8-byte aligned: a table entry is 8 bytes
-    uint8_t *pdev = (uint8_t *)(ring + a.slots);
+    const size_t tab_bytes = (sizeof(Magic) * ((size_t)k * k + k) + 15) & ~(size_t)15;
+    const size_t ring_bytes = (((size_t)a.slots + 1) * (PACKED ? 8 : sizeof(Tick) + 1) + 15) & ~(size_t)15;
+    Ring<Tick, PACKED> ring;
+    ring.init(lds + tab_bytes, a.slots);
+    const int slot_chunks = NL * a.nlw * 64;
+    uint4 *stage = (uint4 *)(lds + tab_bytes + ring_bytes);
     {
         const uint64_t *e = (const uint64_t *)a.edge_tab, *v = (const uint64_t *)a.vert_tab;
-        for (int i = tid; i < k * k; i += nt) lds[i] = e[i];
-        for (int i = tid; i < k; i += nt) lds[k * k + i] = v[i];
+        uint64_t *t64 = (uint64_t *)lds;
+        for (int i = tid; i < k * k; i += nt) t64[i] = e[i];
+        for (int i = tid; i < k; i += nt) t64[k * k + i] = v[i];
+        if (tid == 0) ring.put(a.slots, 0, 0);     // the constant-zero slot padding entries point at
     }
-    __syncthreads();
 
-    // partition of this workgroup; neighbours in a 128-byte output line share an XCD
-    const int32_t q = blockIdx.x;
-    const uint8_t *assign = a.assign + (int64_t)q * a.a_stride_p;
-    Tick *out = a.out ? (Tick *)a.out + q : nullptr;
-    const int32_t R = a.slots, P = a.P;
+    const int Lpad = (L + DR - 1) / DR * DR;
+    const int wp16 = a.wpad / 16;
     long long best = 0;
 
-    for (int32_t s = 0; s < a.L; ++s) {
-        const int32_t pa = a.lvl[2 * s], sl0 = a.lvl[2 * s + 1], pb = a.lvl[2 * s + 2];
-        for (int32_t i0 = pa; i0 < pb; i0 += nt) {
-            const int32_t i = i0 + tid;
-            if (i < pb) {
-                const int32_t v = a.vtx[i];
-                uint32_t pv = assign[(int64_t)v * a.a_stride_v];
-                if (pv >= (uint32_t)k) { *a.status = CP_STATUS_BAD_DEVICE_ID; pv = 0; }
-                const int32_t dg = a.deg[i];
-                const uint32_t cv = a.c[i];
-                const uint32_t slice = sl0 + ((i - pa) >> 6);
-                const uint2 *ent = a.ent + a.slice_off[slice] + lane;
-                Tick acc = 0;
-                for (int32_t j = 0; j < dg; ++j) {
-                    const uint2 en = ent[(size_t)j * 64];
-                    const uint32_t pu = pdev[en.x];
-                    const Tick vu = ring[en.x];
-                    const Tick x = (Tick)magic_div(en.y, etab[pv * k + pu]);
-                    acc = max(acc, (Tick)(vu + x));
-                }
-                const Tick w = (Tick)magic_div(cv, vtab[pv]);
-                const Tick fin = acc + w;             // b(v), or tl(v) + w(v)
-                const int32_t slot = i % R;
-                ring[slot] = fin;
-                pdev[slot] = (uint8_t)pv;
-                if (out) out[(size_t)v * P] = TSWEEP ? acc : fin;
-                best = max(best, (long long)fin);
+    if (wave >= a.nc) {
+        // ------------------------------------------------ loader wavefronts
+        const int lw = wave - a.nc;
+        const uint4 *pp = (const uint4 *)(a.pperm + (size_t)q * L * a.wpad);
+        const_u32_ptr pkt_off = (const_u32_ptr)a.pkt_off;
+        u32x4 buf[DR][NL];
+        // every lane always loads: chunks past the packet's end re-read its last chunk
+#define CP_ISSUE(R, S)                                                                          \
+    do {                                                                                        \
+        const int s_ = min((S), L - 1);                                                         \
+        const uint32_t o0_ = pkt_off[s_], o1_ = pkt_off[s_ + 1];                                \
+        const int nchunks_ = wp16 + (int)(o1_ - o0_);                                           \
+        _Pragma("unroll") for (int i_ = 0; i_ < NL; ++i_) {                                     \
+            const int c_ = min((i_ * a.nlw + lw) * 64 + lane, nchunks_ - 1);                    \
+            const uint4 *src_ = c_ < wp16 ? pp + (size_t)s_ * wp16 + c_                         \
+                                          : a.stream + (size_t)o0_ + (c_ - wp16);               \
+            buf[R][i_] = *(const u32x4 *)src_;                                                  \
+        }                                                                                       \
+    } while (0)
+#define CP_STORE(R, SLOT)                                                                       \
+    do {                                                                                        \
+        u32x4 *dst_ = (u32x4 *)(stage + (size_t)(SLOT) * slot_chunks);                          \
+        _Pragma("unroll") for (int i_ = 0; i_ < NL; ++i_)                                       \
+            dst_[(i_ * a.nlw + lw) * 64 + lane] = buf[R][i_];                                   \
+    } while (0)
+#pragma unroll
+        for (int r = 0; r < DR; ++r) CP_ISSUE(r, r);
+        CP_STORE(0, 0);
+        CP_ISSUE(0, DR);
+        for (int t0 = 0; t0 < Lpad; t0 += DR) {
+#pragma unroll
+            for (int r = 0; r < DR; ++r) {
+                const int t = t0 + r;
+                lds_barrier();
+                CP_STORE((r + 1) % DR, (t + 1) & 1);
+                CP_ISSUE((r + 1) % DR, t + 1 + DR);
             }
         }
-        __syncthreads();
+#undef CP_ISSUE
+#undef CP_STORE
+    } else {
+        // ------------------------------------------------ compute wavefronts
+        typedef typename std::conditional<ENT4, uint32_t, uint2>::type Ent;
+        Tick *out = a.out ? (Tick *)a.out + q : nullptr;
+        const int32_t P = a.P, R = a.slots;
+        for (int t = 0; t < Lpad; ++t) {
+            lds_barrier();
+            if (t >= L) continue;
+            const uint8_t *st = (const uint8_t *)(stage + (size_t)(t & 1) * slot_chunks);
+            const uint8_t *pk = st + a.wpad;
+            const uint4 hdr = *(const uint4 *)pk;
+            const int npos = __builtin_amdgcn_readfirstlane((int)hdr.x);
+            const int nsl = __builtin_amdgcn_readfirstlane((int)hdr.y);
+            const int rbase = __builtin_amdgcn_readfirstlane((int)hdr.z);
+            const uint2 *slice_tab = (const uint2 *)(pk + 16);
+            const uint2 *rec = (const uint2 *)(pk + 16 + ((8 * nsl + 15) & ~15));
+            const Ent *ent_all = (const Ent *)(rec + (size_t)64 * nsl);
+            for (int j = wave; j < nsl; j += a.nc) {
+                const uint2 sl = slice_tab[j];
+                const int ebase = __builtin_amdgcn_readfirstlane((int)sl.x);
+                const int width = __builtin_amdgcn_readfirstlane((int)(sl.y & 0xffffffu));
+                const int lsh = __builtin_amdgcn_readfirstlane((int)(sl.y >> 24));   // log2 lanes per row
+                const int p = j * 64 + (lane >> lsh);
+                const uint2 rc = rec[p];
+                const uint32_t pv = st[p];
+                const Ent *ent = ent_all + ebase + lane;
+                const Magic *erow = etab + pv * k;
+                Tick acc = 0;
+#pragma unroll 4
+                for (int jj = 0; jj < width; ++jj) {
+                    uint32_t slot, te;
+                    if constexpr (ENT4) {
+                        const uint32_t en = ent[jj * 64];
+                        slot = en & 0xffffu;
+                        te = en >> 16;
+                    } else {
+                        const uint2 en = ent[jj * 64];
+                        slot = en.x;
+                        te = en.y;
+                    }
+                    Tick vu;
+                    uint32_t pu;
+                    ring.get((int)slot, vu, pu);
+                    const Tick x = (Tick)magic_div(te, erow[pu]);
+                    acc = max(acc, (Tick)(vu + x));
+                }
+                for (int off = (1 << lsh) >> 1; off > 0; off >>= 1)   // fold the lanes of a row
+                    acc = max(acc, __shfl_xor(acc, off));
+                if (p < npos && (lane & ((1 << lsh) - 1)) == 0) {
+                    const Tick fin = acc + (Tick)magic_div(rc.y, vtab[pv]);   // b(v), or tl(v) + w(v)
+                    int rs = rbase + p;
+                    if (rs >= R) rs -= R;
+                    ring.put(rs, fin, pv);
+                    if (out) out[(size_t)rc.x * P] = TSWEEP ? acc : fin;
+                    best = max(best, (long long)fin);
+                }
+            }
+        }
     }
 
-    if (a.cp_out) {   // workgroup maximum of everything written
-        __shared__ long long red[kWindowMaxThreads / 64];
+    if (a.cp_out) {   // workgroup maximum
         for (int off = 32; off > 0; off >>= 1) best = max(best, __shfl_xor(best, off));
-        if (lane == 0) red[tid >> 6] = best;
-        __syncthreads();
+        if (lane == 0) red[wave] = best;
+        lds_barrier();
         if (tid == 0) {
-            for (int w2 = 1; w2 < (nt + 63) / 64; ++w2) best = max(best, red[w2]);
+            for (int w2 = 1; w2 < a.nc; ++w2) best = max(best, red[w2]);
             a.cp_out[q] = best;
         }
     }
@@ -356,43 +505,96 @@ int launch_column_sweep_t(const SweepLaunch &s, hipStream_t st, int32_t *launche
     return hip_ok(hipGetLastError());
 }
 
-template <typename Tick, bool TSWEEP>
-int launch_window_sweep_t(const SweepLaunch &s, hipStream_t st, int32_t *launches) {
+template <typename Tick, bool TSWEEP, bool PACKED, bool ENT4, int NL, int DR>
+int launch_window_sweep_k(const SweepLaunch &s, const WindowCfg &cfg, hipStream_t st) {
     const WindowDir &dir = *s.win;
     WindowArgs a{};
-    a.vtx = (const int32_t *)(s.blob + dir.vtx_off);
-    a.c = (const uint32_t *)(s.blob + dir.c_off);
-    a.deg = (const int32_t *)(s.blob + dir.deg_off);
-    a.lvl = (const int32_t *)(s.blob + dir.lvl_off);
-    a.slice_off = (const uint32_t *)(s.blob + dir.slice_off);
-    a.ent = (const uint2 *)(s.blob + dir.ent_off);
-    a.assign = s.assign;
-    a.a_stride_p = s.a_stride_p;
-    a.a_stride_v = s.a_stride_v;
+    a.stream = (const uint4 *)(s.blob + dir.stream_off);
+    a.pkt_off = (const uint32_t *)(s.blob + dir.pkt_off);
+    a.pperm = s.pperm;
     a.out = s.val;
     a.cp_out = s.cp_out;
     a.edge_tab = (const Magic *)s.edge_tab;
     a.vert_tab = (const Magic *)s.vert_tab;
-    a.status = s.status;
-    a.P = s.P; a.L = s.L; a.k = s.k; a.slots = dir.slots;
-    const size_t lds_bytes = window_lds_bytes(s.k, dir.slots, sizeof(Tick));
-    auto kern = window_sweep_kernel<Tick, TSWEEP>;
-    if (lds_bytes > 64 * 1024) {
+    a.P = s.P; a.L = s.L; a.k = s.k; a.slots = dir.slots; a.wpad = dir.wpad;
+    a.nc = cfg.nc; a.nlw = cfg.nlw;
+    a.pgroups = (s.P + 7) / 8;
+    auto kern = window_sweep_kernel<Tick, TSWEEP, PACKED, ENT4, NL, DR>;
+    if (cfg.lds_bytes > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)cfg.lds_bytes);
         if (e != hipSuccess) return CP_ERR_HIP;
     }
-    int threads = std::min<int>(kWindowMaxThreads, (s.max_width + 63) / 64 * 64);
-    hipLaunchKernelGGL(kern, dim3((unsigned)s.P), dim3(threads), lds_bytes, st, a);
-    if (launches) *launches = 1;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(8 * a.pgroups)), dim3((cfg.nc + cfg.nlw) * 64),
+                       cfg.lds_bytes, st, a);
     return hip_ok(hipGetLastError());
+}
+
+template <typename Tick, bool TSWEEP, bool PACKED, bool ENT4>
+int launch_window_sweep_e(const SweepLaunch &s, const WindowCfg &cfg, hipStream_t st) {
+    switch (cfg.nl) {   // loads per loader lane per level x levels in flight: 64 registers at most
+        case 1: return launch_window_sweep_k<Tick, TSWEEP, PACKED, ENT4, 1, 8>(s, cfg, st);
+        case 2: return launch_window_sweep_k<Tick, TSWEEP, PACKED, ENT4, 2, 8>(s, cfg, st);
+        case 4: return launch_window_sweep_k<Tick, TSWEEP, PACKED, ENT4, 4, 4>(s, cfg, st);
+        case 8: return launch_window_sweep_k<Tick, TSWEEP, PACKED, ENT4, 8, 2>(s, cfg, st);
+        default: return CP_ERR_ARG;
+    }
+}
+
+template <typename Tick, bool TSWEEP, bool PACKED>
+int launch_window_sweep_p(const SweepLaunch &s, const WindowCfg &cfg, hipStream_t st) {
+    return s.win->ent4 ? launch_window_sweep_e<Tick, TSWEEP, PACKED, true>(s, cfg, st)
+                       : launch_window_sweep_e<Tick, TSWEEP, PACKED, false>(s, cfg, st);
+}
+
+template <bool TSWEEP>
+int launch_window_sweep_d(const SweepLaunch &s, const WindowCfg &cfg, hipStream_t st) {
+    if (s.tick_bytes == 4)
+        return cfg.packed ? launch_window_sweep_p<int32_t, TSWEEP, true>(s, cfg, st)
+                          : launch_window_sweep_p<int32_t, TSWEEP, false>(s, cfg, st);
+    return launch_window_sweep_p<int64_t, TSWEEP, false>(s, cfg, st);
 }
 
 }  // namespace
 
-size_t window_lds_bytes(int32_t k, int32_t slots, size_t tick_bytes) {
-    size_t tab = sizeof(Magic) * ((size_t)k * k + k);
-    return align_up(tab + (tick_bytes + 1) * (size_t)slots, 16);
+bool window_config(const WindowDir &d, int32_t k, size_t tick_bytes, size_t lds_limit, WindowCfg &out) {
+    const int64_t need = d.wpad / 16 + (int64_t)d.max_chunks;     // 16-byte chunks per stage slot
+    const size_t tab = (sizeof(Magic) * ((size_t)k * k + k) + 15) & ~(size_t)15;
+    static const int kNl[4] = {1, 2, 4, 8};
+    for (int nl : kNl) {
+        const int64_t nlw = (need + 64 * nl - 1) / (64 * nl);
+        if (nlw > 8) continue;
+        out.nl = nl;
+        out.nlw = (int)nlw;
+        out.dr = nl <= 2 ? 8 : (nl == 4 ? 4 : 2);
+        out.nc = std::max(1, std::min(d.smax, kWindowMaxWaves - (int)nlw));
+        const size_t stage = (size_t)2 * nl * nlw * 1024;
+        const size_t packed = (8 * ((size_t)d.slots + 1) + 15) & ~(size_t)15;
+        const size_t split = ((tick_bytes + 1) * ((size_t)d.slots + 1) + 15) & ~(size_t)15;
+        if (tick_bytes == 4 && tab + packed + stage <= lds_limit) {
+            out.packed = true;
+            out.lds_bytes = tab + packed + stage;
+            return true;
+        }
+        if (tab + split + stage <= lds_limit) {
+            out.packed = false;
+            out.lds_bytes = tab + split + stage;
+            return true;
+        }
+        return false;
+    }
+    return false;
+}
+
+int launch_gather_assign(const SweepLaunch &s, uint8_t *out, void *stream) {
+    const WindowDir &dir = *s.win;
+    const int64_t row_len = (int64_t)s.L * dir.wpad;
+    const int64_t chunks = (row_len + 1023) / 1024;
+    if (chunks > 65535) return CP_ERR_SIZE;
+    hipLaunchKernelGGL(gather_assign_kernel, dim3((unsigned)chunks, (unsigned)s.P), dim3(256), 0,
+                       (hipStream_t)stream, (const int32_t *)(s.blob + dir.gmap_off), row_len,
+                       s.assign, s.a_stride_p, s.a_stride_v, s.k, out, s.status);
+    return hip_ok(hipGetLastError());
 }
 
 int launch_clear(int64_t *cp_out, int32_t batch, int32_t *status, void *stream) {
@@ -424,13 +626,10 @@ int launch_column_sweep(const SweepLaunch &s, void *stream, int32_t *launches) {
 #undef CP_COL
 }
 
-int launch_window_sweep(const SweepLaunch &s, void *stream, int32_t *launches) {
-    hipStream_t st = (hipStream_t)stream;
-    if (s.tick_bytes == 4)
-        return s.tsweep ? launch_window_sweep_t<int32_t, true>(s, st, launches)
-                        : launch_window_sweep_t<int32_t, false>(s, st, launches);
-    return s.tsweep ? launch_window_sweep_t<int64_t, true>(s, st, launches)
-                    : launch_window_sweep_t<int64_t, false>(s, st, launches);
+int launch_window_sweep(const SweepLaunch &s, const WindowCfg &cfg, void *stream, int32_t *launches) {
+    if (launches) *launches = 1;
+    return s.tsweep ? launch_window_sweep_d<true>(s, cfg, (hipStream_t)stream)
+                    : launch_window_sweep_d<false>(s, cfg, (hipStream_t)stream);
 }
 
 int launch_cp_sources(const int32_t *sources, int32_t nsrc, const void *b, int32_t P,

@@ -18,7 +18,8 @@ struct SweepLaunch {
     int tick_bytes = 4;
     int32_t P = 0, k = 0, L = 0, max_width = 0;
     const uint8_t *pT = nullptr;        // [n][P] device ids (wave-column)
-    const uint8_t *assign = nullptr;    // caller's assignments (resident-window)
+    const uint8_t *assign = nullptr;    // caller's assignments (resident-window: input of the gather)
+    const uint8_t *pperm = nullptr;     // [P][L*wpad] device ids in sweep order (resident-window)
     int64_t a_stride_p = 0, a_stride_v = 0;
     void *val = nullptr;                // [n][P] ticks
     int64_t *cp_out = nullptr;          // resident-window b sweep only
@@ -27,12 +28,24 @@ struct SweepLaunch {
     int32_t *status = nullptr;
 };
 
-size_t window_lds_bytes(int32_t k, int32_t slots, size_t tick_bytes);
+// Launch shape of the resident-window kernel for one sweep direction.
+struct WindowCfg {
+    int nl = 0;        // 16-byte loads per loader lane per level
+    int nlw = 0;       // loader wavefronts
+    int nc = 0;        // compute wavefronts
+    int dr = 0;        // levels a loader runs ahead in registers
+    bool packed = false;   // ring holds {value, device} pairs (one LDS read per relaxation)
+    size_t lds_bytes = 0;
+};
+
+// False if the direction cannot run under `lds_limit` bytes of LDS.
+bool window_config(const WindowDir &d, int32_t k, size_t tick_bytes, size_t lds_limit, WindowCfg &out);
+int launch_gather_assign(const SweepLaunch &s, uint8_t *out, void *stream);
 
 int launch_clear(int64_t *cp_out, int32_t batch, int32_t *status, void *stream);
 int launch_transpose(const uint8_t *in, uint8_t *out, int32_t n, int32_t P, void *stream);
 int launch_column_sweep(const SweepLaunch &s, void *stream, int32_t *launches);
-int launch_window_sweep(const SweepLaunch &s, void *stream, int32_t *launches);
+int launch_window_sweep(const SweepLaunch &s, const WindowCfg &cfg, void *stream, int32_t *launches);
 int launch_cp_sources(const int32_t *sources, int32_t nsrc, const void *b, int32_t P,
                       int tick_bytes, int64_t *cp_out, void *stream);
 int launch_mask(const void *b, const void *tl, const int64_t *cp, int32_t n, int32_t P,

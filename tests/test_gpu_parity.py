@@ -72,9 +72,34 @@ def test_comm_heavy_full(gpu, oracle):
     _check(gpu, oracle, w, plans=(COLUMN,))
 
 
-def test_comm_heavy_scaled_both_plans(gpu, oracle):
-    # hub rows (300 >= the hub threshold) and levels wider than one workgroup
+def test_comm_heavy_scaled_hub_rows(gpu, oracle):
+    # hub rows (300 >= the hub threshold) take a whole workgroup in the wave-column plan;
+    # levels this wide do not fit the other plan's LDS stage, which must say so
+    from gpu_util import run_gpu
     w = make_workload("comm_heavy", P=70, levels=5, width=3000, hub_degree=300)
+    _check(gpu, oracle, w, plans=(COLUMN,))
+    with pytest.raises(gpu.CpError) as e:
+        run_gpu(w, WINDOW)
+    assert e.value.code == -12
+
+
+def test_comm_heavy_scaled_both_plans(gpu, oracle):
+    # rows of 40 edges next to rows of 2-4, 8-byte entries (volumes up to 1e7)
+    w = make_workload("comm_heavy", P=70, levels=5, width=600, hub_degree=40)
+    _check(gpu, oracle, w)
+
+
+def test_levels_wider_than_the_compute_wavefronts(gpu, oracle):
+    # 19 slices of 64 vertices per level against at most 8 compute wavefronts
+    rng = np.random.default_rng(7)
+    n, level, src, dst = random_layered_dag(rng, [1200] * 9, 1, 3, 2)
+    k = 5
+    w = _custom("wide-levels", n, src, dst, rng.integers(1, 10**4, size=len(src)),
+                rng.integers(1, 10**3, size=n), rng.integers(1, 9, size=k),
+                rng.integers(1, 50, size=(k, k)), rng.integers(0, k, size=(70, n), dtype=np.uint8), level)
+    g = gpu.CpGraph.from_workload(w)
+    assert g.info["window_ok"] == 1 and g.info["max_level_width"] == 1200
+    g.close()
     _check(gpu, oracle, w)
 
 

@@ -162,9 +162,11 @@ def test_plan_selection_facts(lib):
 def test_workspace_bytes_and_eval_argument_errors(lib):
     w = make_workload("tiny")
     g = cpe.CpGraph.from_workload(w)
-    assert binding.workspace_bytes(g, 16, 2, plan=cpe.PLAN_RESIDENT_WINDOW) == 256
+    # cost tables, then either the transposed ids (wave-column) or the ids gathered into
+    # sweep order for each direction (resident-window: 8 levels padded to 64 positions)
+    assert binding.workspace_bytes(g, 16, 2, plan=cpe.PLAN_RESIDENT_WINDOW) == 256 + 2 * 16 * 8 * 64
     assert binding.workspace_bytes(g, 16, 2, plan=cpe.PLAN_WAVE_COLUMN) == 256 + 1024
-    assert binding.workspace_bytes(g, 16, 2, assign_layout=binding.ASSIGN_VERTEX_MAJOR) == 256
+    assert binding.workspace_bytes(g, 16, 2) == 256 + 2 * 16 * 8 * 64
     with pytest.raises(cpe.CpError) as e:
         binding.workspace_bytes(g, 0, 2)
     assert e.value.code == -2
