@@ -256,7 +256,7 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
     s.magic = tabs.magic_ok;
     s.narrow = p.narrow;
     s.tick_bytes = tick_dtype;
-    s.P = batch; s.k = k; s.L = p.L; s.max_width = p.max_width;
+    s.n = p.n; s.P = batch; s.k = k; s.L = p.L; s.max_width = p.max_width;
     s.pT = pT;
     s.assign = assignments;
     if (assign_layout == CP_ASSIGN_PARTITION_MAJOR) { s.a_stride_p = p.n; s.a_stride_v = 1; }

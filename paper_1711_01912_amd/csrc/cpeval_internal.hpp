@@ -33,16 +33,20 @@ struct ColumnDir {
 // One sweep direction of the resident-window plan.  Vertices are renumbered by
 // position in sweep order.  Everything a level needs is one contiguous "packet"
 // of 16-byte chunks, so that loader wavefronts can stream it into LDS ahead of
-// the compute wavefronts:
-//   [ 0,16)  header  {npos, nslices, ring_base = first position mod slots, 0}
-//   [16, ..) slice table, nslices x {entry base, width | log2(lanes per row) << 24}
-//            (padded to 16 bytes); a slice of at most 32 rows gives each row 2..64
-//            lanes that share its edges and fold their maxima at the end
-//            records, nslices*64 x {original vertex id (0xffffffff = padding), c}
-//            entries, per slice width x 64 x {ring slot of the neighbour, t(e)};
-//            entry j of lane l of a slice sits at base + j*64 + l, padding entries
-//            are {slots, 0}: ring slot `slots` holds the constant 0.  An entry is
-//            two uint32, or one uint32 (slot | t << 16) when both fit 16 bits (ent4)
+// the compute wavefronts.  A level is cut into slices of 64 rows (vertices), one
+// per compute wavefront; a slice of at most 32 rows gives each row 2..64 lanes
+// that share its edges and fold their maxima at the end.
+//   descriptors  smax x {byte offset of the slice's entries in the packet,
+//                        width | log2(lanes per row) << 24, rows, ring slot of row 0}
+//                (rows = 0 for slices this level does not have), followed by a copy
+//                of the NEXT level's descriptors (zeros after the last level)
+//   records      per slice 64 x {original vertex id (0xffffffff = padding), c}
+//   entries      per slice width x 64 x {ring field of the neighbour, t(e)}: entry j
+//                of lane l of a slice sits at base + j*64 + l.  The ring field is the
+//                neighbour's slot (times 8 when the ring holds {value, device}
+//                pairs: a byte offset); padding entries point at slot `slots`,
+//                which holds the constant 0, with t = 0.  An entry is two uint32, or
+//                one uint32 (field | t << 16) when both fit 16 bits (ent4).
 struct WindowDir {
     size_t stream_off = 0;   // uint4 [total_chunks]
     size_t pkt_off = 0;      // uint32 [L+1] first chunk of each packet, in sweep order
@@ -52,6 +56,7 @@ struct WindowDir {
     int32_t wpad = 0;        // level width rounded up to whole slices of 64
     int32_t smax = 0;        // slices of the widest level
     int32_t slots = 0;       // ring capacity R: slot of position i is i mod R
+    bool packed = false;     // ring of {value, device} pairs (32-bit ticks only)
     bool ent4 = false;       // 4-byte entries
 };
 

@@ -96,8 +96,8 @@ int lanes_per_row_log2(int rows) {
 // Resident-window packing for one direction (layout: see WindowDir).  Returns
 // false if the packets would be unreasonably large.
 bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int64_t max_t,
-                     const Csr &csr, const std::vector<int32_t> &order, const ColumnDir &col,
-                     WindowDir &dir) {
+                     bool ticks32, const Csr &csr, const std::vector<int32_t> &order,
+                     const ColumnDir &col, WindowDir &dir) {
     std::vector<int32_t> pos(n);
     for (int32_t i = 0; i < n; ++i) pos[order[i]] = i;
 
@@ -116,28 +116,42 @@ bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int6
         wmax = std::max(wmax, b - a);
     }
     dir.slots = (int32_t)need;
-    dir.ent4 = need < 65536 && max_t < 65536;
-    const uint64_t esz = dir.ent4 ? 4 : 8;
     dir.smax = (wmax + kWave - 1) / kWave;
     dir.wpad = dir.smax * kWave;
+    if (dir.smax > 64) return false;        // levels this wide belong to the wave-column plan
 
-    // packet sizes
+    // entry counts per level
+    std::vector<uint64_t> lvl_entries(L, 0);
+    uint64_t emax = 0;
+    for (int32_t s = 0; s < L; ++s) {
+        int32_t a = col.lvl_begin[s], b = a + col.lvl_count[s];
+        for (int32_t p0 = a; p0 < b; p0 += kWave) {
+            int32_t v0 = order[p0];
+            int64_t deg0 = csr.ptr[v0 + 1] - csr.ptr[v0];                 // longest row leads
+            int sh = lanes_per_row_log2(std::min(kWave, b - p0));
+            lvl_entries[s] += (uint64_t)((deg0 + (1 << sh) - 1) >> sh) * kWave;
+        }
+        emax = std::max(emax, lvl_entries[s]);
+    }
+    // ring layout: {value, device} pairs if that leaves room for three stage slots
+    // and small cost tables, else separate arrays; it fixes what an entry stores
+    {
+        const uint64_t slot_est = align_up(dir.wpad + 32 * (uint64_t)dir.smax + 8 * (uint64_t)dir.wpad + 4 * emax, 1024);
+        dir.packed = ticks32 && 8 * ((uint64_t)need + 1) + 3 * slot_est + 4096 <= kLdsBudget - 512;
+    }
+    const uint64_t field_max = dir.packed ? 8 * (uint64_t)need : (uint64_t)need;
+    dir.ent4 = field_max < 65536 && max_t < 65536;
+    const uint64_t esz = dir.ent4 ? 4 : 8;
+
     std::vector<uint32_t> pkt_off((size_t)L + 1);
     uint64_t total = 0;
     uint32_t max_chunks = 1;
     for (int32_t s = 0; s < L; ++s) {
         int32_t a = col.lvl_begin[s], b = a + col.lvl_count[s];
         uint64_t nsl = (uint64_t)(b - a + kWave - 1) / kWave;
-        uint64_t entries = 0;
-        for (int32_t p0 = a; p0 < b; p0 += kWave) {
-            int32_t v0 = order[p0];
-            int64_t deg0 = csr.ptr[v0 + 1] - csr.ptr[v0];                 // longest row leads
-            int sh = lanes_per_row_log2(std::min(kWave, b - p0));
-            entries += (uint64_t)((deg0 + (1 << sh) - 1) >> sh) * kWave;
-        }
-        uint64_t bytes = 16 + align_up(8 * nsl, 16) + 8 * kWave * nsl + esz * entries;
-        uint64_t chunks = bytes / 16;
-        if (chunks > (1u << 20)) return false;      // a 16 MB level never fits LDS anyway
+        uint64_t bytes = 32 * (uint64_t)dir.smax + 8 * kWave * nsl + esz * lvl_entries[s];
+        uint64_t chunks = (bytes + 15) / 16;
+        if (chunks > (1u << 16)) return false;      // a 1 MB level never fits LDS
         pkt_off[s] = (uint32_t)total;
         total += chunks;
         if (total >= (1ull << 31)) return false;
@@ -154,18 +168,16 @@ bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int6
     int32_t *gmap = w.at<int32_t>(dir.gmap_off);
     std::fill(gmap, gmap + (size_t)L * dir.wpad, -1);
 
+    const uint32_t pad_field = (uint32_t)(dir.packed ? 8 * (uint64_t)dir.slots : (uint64_t)dir.slots);
     for (int32_t s = 0; s < L; ++s) {
         int32_t a = col.lvl_begin[s], b = a + col.lvl_count[s];
         uint32_t nsl = (uint32_t)(b - a + kWave - 1) / kWave;
-        uint32_t *pk = w.at<uint32_t>(dir.stream_off + 16 * (size_t)pkt_off[s]);
-        pk[0] = (uint32_t)(b - a);
-        pk[1] = nsl;
-        pk[2] = (uint32_t)(a % dir.slots);
-        pk[3] = 0;
-        uint32_t *slice_tab = pk + 4;
-        uint32_t *rec = slice_tab + align_up(8 * (size_t)nsl, 16) / 4;
-        uint32_t *ent = rec + 2 * (size_t)kWave * nsl;
-        uint32_t ebase = 0;
+        uint8_t *pk = w.at<uint8_t>(dir.stream_off + 16 * (size_t)pkt_off[s]);
+        uint32_t *desc = (uint32_t *)pk;                                  // smax x {ent byte offset, width|lsh<<24, rows, ring slot of row 0}
+        uint32_t *rec = (uint32_t *)(pk + 32 * (size_t)dir.smax);         // nsl*64 x {v, c}
+        const uint32_t ent_start = 32 * (uint32_t)dir.smax + 8 * kWave * nsl;
+        uint32_t *ent = (uint32_t *)(pk + ent_start);
+        uint32_t ebase = 0;                                               // in entries
         for (uint32_t j = 0; j < nsl; ++j) {
             int32_t p0 = a + (int32_t)j * kWave;
             int32_t rows = std::min(kWave, b - p0);
@@ -173,8 +185,10 @@ bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int6
             int sh = lanes_per_row_log2(rows);
             int32_t lpr = 1 << sh;
             uint32_t width = (uint32_t)((csr.ptr[v0 + 1] - csr.ptr[v0] + lpr - 1) >> sh);
-            slice_tab[2 * j] = ebase;
-            slice_tab[2 * j + 1] = width | ((uint32_t)sh << 24);
+            desc[4 * j] = ent_start + (uint32_t)esz * ebase;
+            desc[4 * j + 1] = width | ((uint32_t)sh << 24);
+            desc[4 * j + 2] = (uint32_t)rows;
+            desc[4 * j + 3] = (uint32_t)(p0 % dir.slots);
             for (int32_t r = 0; r < kWave; ++r) {       // records: one per row
                 uint32_t *rc = rec + 2 * ((size_t)j * kWave + r);
                 if (r < rows) {
@@ -194,21 +208,28 @@ bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int6
                 for (uint32_t jj = 0; jj < width; ++jj) {
                     const size_t at = (size_t)ebase + (size_t)jj * kWave + l;
                     int64_t ei = (int64_t)jj * lpr + sub;
-                    uint32_t slot = (uint32_t)dir.slots, te = 0;    // padding: the constant-zero slot
+                    uint32_t field = pad_field, te = 0;    // padding: the constant-zero slot
                     if (ei < d) {
                         int64_t e = (int64_t)csr.ptr[v] + ei;
-                        slot = (uint32_t)(pos[csr.idx[e]] % dir.slots);
+                        uint32_t slot = (uint32_t)(pos[csr.idx[e]] % dir.slots);
+                        field = dir.packed ? 8 * slot : slot;
                         te = (uint32_t)csr.wt[e];
                     }
                     if (dir.ent4) {
-                        ent[at] = slot | (te << 16);
+                        ent[at] = field | (te << 16);
                     } else {
-                        ent[2 * at] = slot;
+                        ent[2 * at] = field;
                         ent[2 * at + 1] = te;
                     }
                 }
             }
             ebase += width * kWave;
+        }
+        // the previous packet also carries these descriptors, so that a wavefront can
+        // address this level's entries one level ahead
+        if (s > 0) {
+            uint8_t *prev = w.at<uint8_t>(dir.stream_off + 16 * (size_t)pkt_off[s - 1]);
+            std::memcpy(prev + 16 * (size_t)dir.smax, pk, 16 * (size_t)dir.smax);
         }
     }
     return true;
@@ -341,8 +362,8 @@ int pack_graph(int32_t n, int64_t m, int32_t L,
         P.have_window = false;
         if (P.narrow) {
             size_t mark = P.blob.size();
-            bool ok = pack_window_dir(w, n, L, c, max_t, succ, order_b, P.col_b, P.win_b) &&
-                      pack_window_dir(w, n, L, c, max_t, pred, order_t, P.col_t, P.win_t);
+            bool ok = pack_window_dir(w, n, L, c, max_t, info.min_tick_bytes == 4, succ, order_b, P.col_b, P.win_b) &&
+                      pack_window_dir(w, n, L, c, max_t, info.min_tick_bytes == 4, pred, order_t, P.col_t, P.win_t);
             if (ok) P.have_window = true;
             else P.blob.resize(mark);
         }

@@ -271,47 +271,26 @@ struct WindowArgs {
     int64_t *cp_out;           // [P] or NULL: receives the maximum of b over the partition
     const Magic *edge_tab;
     const Magic *vert_tab;
-    int32_t P, L, k, slots, wpad;
+    int32_t P, L, k, slots, wpad, smax;
     int32_t nc, nlw;           // compute and loader wavefronts per workgroup
     int32_t pgroups;           // partitions per XCD-sized group (blockIdx -> partition map)
-};
-
-template <typename Tick, bool PACKED> struct Ring;
-
-// {value, device id} in one 8-byte element: one LDS read per relaxation
-template <> struct Ring<int32_t, true> {
-    uint2 *e;
-    __device__ void init(uint8_t *base, int) { e = (uint2 *)base; }
-    __device__ void put(int slot, int32_t val, uint32_t p) { e[slot] = make_uint2((uint32_t)val, p); }
-    __device__ void get(int slot, int32_t &val, uint32_t &p) const {
-        const uint2 x = e[slot];
-        val = (int32_t)x.x;
-        p = x.y;
-    }
-};
-// separate arrays: 5 (or 9) bytes per slot when the window is large
-template <typename Tick> struct Ring<Tick, false> {
-    Tick *v;
-    uint8_t *d;
-    __device__ void init(uint8_t *base, int slots) {
-        v = (Tick *)base;
-        d = base + sizeof(Tick) * ((size_t)slots + 1);
-    }
-    __device__ void put(int slot, Tick val, uint32_t p) { v[slot] = val; d[slot] = (uint8_t)p; }
-    __device__ void get(int slot, Tick &val, uint32_t &p) const { val = v[slot]; p = d[slot]; }
+    int32_t out32;             // 1 if every output index fits 32 bits
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // stays in registers when indexed statically
 typedef const uint32_t __attribute__((address_space(4))) *const_u32_ptr;   // uniform reads become scalar loads
 
-// LDS layout: [tables][ring][stage slot 0][stage slot 1]; a stage slot is
-// [wpad bytes of device ids][packet], NL*nlw*1024 bytes in all.
+// LDS layout: [ring][cost tables][3 stage slots]; a stage slot is
+// [wpad bytes of device ids][packet], NL*nlw*1024 bytes in all.  The ring is
+// either (slots+1) x {value, device*8} (PACKED: one 8-byte read per relaxation, and
+// an entry's ring field is the byte offset itself) or (slots+1) values followed by
+// (slots+1) device bytes.
 //
 // Wavefronts 0..nc-1 compute, wavefronts nc..nc+nlw-1 load.  Tick t: after the
-// barrier the compute wavefronts relax level t out of stage slot t&1 while the
-// loaders copy packet t+1 (which they requested DR ticks earlier and hold in
-// registers) into the other slot and request packet t+1+DR.  The only traffic on
-// the level-to-level dependency is LDS.
+// barrier the compute wavefronts relax level t out of its stage slot while the
+// loaders copy packet t+2 (requested DR ticks earlier, held in registers) into
+// the slot that level t-1 has just left and request packet t+2+DR.  Nothing on the
+// level-to-level dependency touches memory beyond LDS.
 template <typename Tick, bool TSWEEP, bool PACKED, bool ENT4, int NL, int DR>
 __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(WindowArgs a) {
     extern __shared__ uint4 lds16[];
@@ -319,7 +298,7 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
     uint8_t *lds = (uint8_t *)lds16;
     const int tid = threadIdx.x, lane = tid & 63, nt = blockDim.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int k = a.k, L = a.L;
+    const int k = a.k, L = a.L, R = a.slots;
 
     // blockIdx -> partition: blocks are dealt round-robin to the 8 XCDs; give each
     // XCD a run of consecutive partitions so that the 4-byte stores of one output
@@ -327,62 +306,82 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
     const int32_t q = (int32_t)(blockIdx.x % 8) * a.pgroups + (int32_t)(blockIdx.x / 8);
     if (q >= a.P) return;      // whole workgroup: no barrier has been reached yet
 
-    Magic *etab = (Magic *)lds;
-    Magic *vtab = etab + k * k;
-    const size_t tab_bytes = (sizeof(Magic) * ((size_t)k * k + k) + 15) & ~(size_t)15;
-    const size_t ring_bytes = (((size_t)a.slots + 1) * (PACKED ? 8 : sizeof(Tick) + 1) + 15) & ~(size_t)15;
-    Ring<Tick, PACKED> ring;
-    ring.init(lds + tab_bytes, a.slots);
-    const int slot_chunks = NL * a.nlw * 64;
-    uint4 *stage = (uint4 *)(lds + tab_bytes + ring_bytes);
+    const uint32_t ring_bytes = (uint32_t)((((size_t)R + 1) * (PACKED ? 8 : sizeof(Tick) + 1) + 15) & ~(size_t)15);
+    const uint32_t tab_bytes = (uint32_t)((sizeof(Magic) * ((size_t)k * k + k) + 15) & ~(size_t)15);
+    Tick *ring_val = (Tick *)lds;                                  // split layout
+    uint8_t *ring_dev = lds + sizeof(Tick) * ((size_t)R + 1);
+    const uint32_t etab_off = ring_bytes;                          // byte offsets inside LDS
+    const uint32_t vtab_off = etab_off + 8u * (uint32_t)(k * k);
+    const int slot_bytes = NL * a.nlw * 1024;
+    uint8_t *stage = lds + ring_bytes + tab_bytes;
     {
         const uint64_t *e = (const uint64_t *)a.edge_tab, *v = (const uint64_t *)a.vert_tab;
-        uint64_t *t64 = (uint64_t *)lds;
+        uint64_t *t64 = (uint64_t *)(lds + etab_off);
         for (int i = tid; i < k * k; i += nt) t64[i] = e[i];
         for (int i = tid; i < k; i += nt) t64[k * k + i] = v[i];
-        if (tid == 0) ring.put(a.slots, 0, 0);     // the constant-zero slot padding entries point at
+        if (tid == 0) {                      // the constant-zero slot padding entries point at
+            if (PACKED) {
+                ((uint2 *)lds)[R] = make_uint2(0, 0);
+            } else {
+                ring_val[R] = 0;
+                ring_dev[R] = 0;
+            }
+        }
     }
 
     const int Lpad = (L + DR - 1) / DR * DR;
     const int wp16 = a.wpad / 16;
-    long long best = 0;
+    Tick best = 0;
 
     if (wave >= a.nc) {
         // ------------------------------------------------ loader wavefronts
         const int lw = wave - a.nc;
-        const uint4 *pp = (const uint4 *)(a.pperm + (size_t)q * L * a.wpad);
         const_u32_ptr pkt_off = (const_u32_ptr)a.pkt_off;
+        // chunk ids of this lane are fixed; whether one is a device-id chunk (the first
+        // wp16 of a slot) or a packet chunk is therefore fixed too
+        int cid[NL];
+        const uint4 *base[NL];
+        bool is_id[NL];
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            cid[i] = (i * a.nlw + lw) * 64 + lane;
+            is_id[i] = cid[i] < wp16;
+            base[i] = is_id[i] ? (const uint4 *)(a.pperm + (size_t)q * L * a.wpad) : a.stream;
+        }
         u32x4 buf[DR][NL];
         // every lane always loads: chunks past the packet's end re-read its last chunk
-#define CP_ISSUE(R, S)                                                                          \
+#define CP_ISSUE(R_, S_)                                                                        \
     do {                                                                                        \
-        const int s_ = min((S), L - 1);                                                         \
+        const int s_ = min((S_), L - 1);                                                        \
         const uint32_t o0_ = pkt_off[s_], o1_ = pkt_off[s_ + 1];                                \
-        const int nchunks_ = wp16 + (int)(o1_ - o0_);                                           \
+        const int last_ = wp16 + (int)(o1_ - o0_) - 1;                                          \
+        const int off_id_ = s_ * wp16, off_pk_ = (int)o0_ - wp16;                               \
         _Pragma("unroll") for (int i_ = 0; i_ < NL; ++i_) {                                     \
-            const int c_ = min((i_ * a.nlw + lw) * 64 + lane, nchunks_ - 1);                    \
-            const uint4 *src_ = c_ < wp16 ? pp + (size_t)s_ * wp16 + c_                         \
-                                          : a.stream + (size_t)o0_ + (c_ - wp16);               \
-            buf[R][i_] = *(const u32x4 *)src_;                                                  \
+            const int c_ = min(cid[i_], last_) + (is_id[i_] ? off_id_ : off_pk_);               \
+            buf[R_][i_] = *(const u32x4 *)(base[i_] + c_);                                      \
         }                                                                                       \
     } while (0)
-#define CP_STORE(R, SLOT)                                                                       \
+#define CP_STORE(R_, SLOT_)                                                                     \
     do {                                                                                        \
-        u32x4 *dst_ = (u32x4 *)(stage + (size_t)(SLOT) * slot_chunks);                          \
-        _Pragma("unroll") for (int i_ = 0; i_ < NL; ++i_)                                       \
-            dst_[(i_ * a.nlw + lw) * 64 + lane] = buf[R][i_];                                   \
+        u32x4 *dst_ = (u32x4 *)(stage + (size_t)(SLOT_) * slot_bytes);                          \
+        _Pragma("unroll") for (int i_ = 0; i_ < NL; ++i_) dst_[cid[i_]] = buf[R_][i_];          \
     } while (0)
 #pragma unroll
         for (int r = 0; r < DR; ++r) CP_ISSUE(r, r);
         CP_STORE(0, 0);
         CP_ISSUE(0, DR);
+        CP_STORE(1 % DR, 1);
+        CP_ISSUE(1 % DR, DR + 1);
+        lds_barrier();                       // packets 0 and 1 are staged
+        int s_put = 2;                       // slot of packet t+2
         for (int t0 = 0; t0 < Lpad; t0 += DR) {
 #pragma unroll
             for (int r = 0; r < DR; ++r) {
                 const int t = t0 + r;
                 lds_barrier();
-                CP_STORE((r + 1) % DR, (t + 1) & 1);
-                CP_ISSUE((r + 1) % DR, t + 1 + DR);
+                CP_STORE((r + 2) % DR, s_put);
+                CP_ISSUE((r + 2) % DR, t + 2 + DR);
+                s_put = s_put == 2 ? 0 : s_put + 1;
             }
         }
 #undef CP_ISSUE
@@ -390,70 +389,201 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
     } else {
         // ------------------------------------------------ compute wavefronts
         typedef typename std::conditional<ENT4, uint32_t, uint2>::type Ent;
+        constexpr int PW = 8;                // entries per lane held in registers
         Tick *out = a.out ? (Tick *)a.out + q : nullptr;
-        const int32_t P = a.P, R = a.slots;
+        const uint32_t P = (uint32_t)a.P;
+        const uint32_t k8 = 8u * (uint32_t)k;
+        const uint32_t desc_next_off = (uint32_t)a.wpad + 16u * (uint32_t)a.smax;   // from the slot base
+        const uint32_t rec_off = (uint32_t)a.wpad + 32u * (uint32_t)a.smax;
+
+        auto ent_field = [](Ent e) -> uint32_t {
+            if constexpr (ENT4) return e & 0xffffu; else return e.x;
+        };
+        auto ent_t = [](Ent e) -> uint32_t {
+            if constexpr (ENT4) return e >> 16; else return e.y;
+        };
+        // value and 8 * device of the vertex behind ring field f
+        auto ring_get = [&](uint32_t f, Tick &vu, uint32_t &pu8) {
+            if constexpr (PACKED) {
+                const uint2 x = *(const uint2 *)(lds + f);
+                vu = (Tick)x.x;
+                pu8 = x.y;
+            } else {
+                vu = ring_val[f];
+                pu8 = 8u * ring_dev[f];
+            }
+        };
+        // fold the lanes of a row; afterwards the row's first lane holds the row's maximum
+        auto fold = [&](Tick acc, int lsh) -> Tick {
+            if (lsh >= 1) acc = max(acc, __shfl_xor(acc, 1));
+            if (lsh >= 2) acc = max(acc, __shfl_xor(acc, 2));
+            if (lsh >= 3) acc = max(acc, __shfl_xor(acc, 4));
+            if (lsh >= 4) acc = max(acc, __shfl_xor(acc, 8));
+            if (lsh >= 5) acc = max(acc, __shfl_xor(acc, 16));
+            if (lsh >= 6) acc = max(acc, __shfl_xor(acc, 32));
+            return acc;
+        };
+        // the row's first lane publishes the vertex: ring, output, running maximum
+        auto publish = [&](Tick acc, Tick w, int lsh, int rows, int rbase, uint32_t v, uint32_t pv) {
+            const int row = lane >> lsh;
+            if (row < rows && (lane & ((1 << lsh) - 1)) == 0) {
+                const Tick fin = acc + w;            // b(v), or tl(v) + w(v)
+                int rs = rbase + row;
+                if (rs >= R) rs -= R;
+                if constexpr (PACKED) {
+                    ((uint2 *)lds)[rs] = make_uint2((uint32_t)fin, 8u * pv);
+                } else {
+                    ring_val[rs] = fin;
+                    ring_dev[rs] = (uint8_t)pv;
+                }
+                if (out) {
+                    if (a.out32) out[__umul24(v, P)] = TSWEEP ? acc : fin;
+                    else out[(size_t)v * P] = TSWEEP ? acc : fin;
+                }
+                best = max(best, fin);
+            }
+        };
+        // a whole slice straight out of its stage slot (no register pipelining)
+        auto slice_direct = [&](const uint8_t *st, int j) {
+            const uint4 d = ((const uint4 *)(st + a.wpad))[j];
+            const uint32_t ent_off = __builtin_amdgcn_readfirstlane((int)d.x);
+            const int width = __builtin_amdgcn_readfirstlane((int)(d.y & 0xffffffu));
+            const int lsh = __builtin_amdgcn_readfirstlane((int)(d.y >> 24));
+            const int rows = __builtin_amdgcn_readfirstlane((int)d.z);
+            const int rbase = __builtin_amdgcn_readfirstlane((int)d.w);
+            if (rows == 0) return;
+            const int p = j * 64 + (lane >> lsh);
+            const uint2 rc = ((const uint2 *)(st + rec_off))[p];
+            const uint32_t pv = st[p];
+            const uint32_t erow = etab_off + pv * k8;
+            const Ent *ent = (const Ent *)(st + a.wpad + ent_off) + lane;
+            Tick acc = 0;
+#pragma unroll 4
+            for (int jj = 0; jj < width; ++jj) {
+                const Ent en = ent[jj * 64];
+                Tick vu;
+                uint32_t pu8;
+                ring_get(ent_field(en), vu, pu8);
+                const Magic mg = *(const Magic *)(lds + erow + pu8);
+                acc = max(acc, (Tick)(vu + (Tick)magic_div(ent_t(en), mg)));
+            }
+            acc = fold(acc, lsh);
+            const Magic mv = *(const Magic *)(lds + vtab_off + 8u * pv);
+            publish(acc, (Tick)magic_div(rc.y, mv), lsh, rows, rbase, rc.x, pv);
+        };
+
+        // Register pipeline for slice `wave`.  The c_ state describes the level about to
+        // be relaxed; its first PW entries E, record rc, device pv and vertex-cost
+        // constants mv were read from LDS one tick earlier, and nd is the descriptor of the
+        // level after it (each packet carries its successor's descriptors).  One tick is
+        // a straight-line block per slice width: ring reads (the only reads that depend
+        // on the previous level), then the reads for the next level, then the cost-table
+        // reads, so that a wavefront waits for two dependent LDS round trips per level.
+        uint32_t c_entoff = 0;
+        int c_width = 0, c_lsh = 0, c_rows = 0, c_rbase = 0;
+        Ent E[PW], E2[PW];
+        uint2 rc = make_uint2(0xffffffffu, 0), rc2 = rc;
+        uint32_t pv = 0, pv2 = 0;
+        Magic mv = {0, 0}, mv2 = {0, 0};
+        uint4 nd = make_uint4(0, 0, 0, 0), nd2 = nd;
+        uint32_t n_entoff = 0;
+        int n_width = 0, n_lsh = 0, n_rows = 0, n_rbase = 0;
+
+        // descriptor D (uniform, in a VGPR) to scalars; then that slice's record, device id,
+        // first PW entries and the descriptor after it, all out of stage slot SN
+#define CP_FETCH_NEXT(SN, D)                                                                    \
+    do {                                                                                        \
+        n_entoff = (uint32_t)__builtin_amdgcn_readfirstlane((int)(D).x);                        \
+        n_width = __builtin_amdgcn_readfirstlane((int)((D).y & 0xffffffu));                     \
+        n_lsh = __builtin_amdgcn_readfirstlane((int)((D).y >> 24));                             \
+        n_rows = __builtin_amdgcn_readfirstlane((int)(D).z);                                    \
+        n_rbase = __builtin_amdgcn_readfirstlane((int)(D).w);                                   \
+        const int p_ = wave * 64 + (lane >> n_lsh);                                             \
+        nd2 = ((const uint4 *)((SN) + desc_next_off))[wave];                                    \
+        rc2 = ((const uint2 *)((SN) + rec_off))[p_];                                            \
+        pv2 = (SN)[p_];                                                                         \
+        const Ent *ent_ = (const Ent *)((SN) + a.wpad + n_entoff) + lane;                       \
+        _Pragma("unroll") for (int jj_ = 0; jj_ < PW; ++jj_) E2[jj_] = ent_[jj_ * 64];          \
+    } while (0)
+
+        // N relaxations out of registers with the next level's reads in their shadow
+#define CP_TICK_CASE(N)                                                                         \
+    case N: {                                                                                   \
+        Tick vu_[N > 0 ? N : 1];                                                                \
+        uint32_t pu8_[N > 0 ? N : 1];                                                           \
+        Magic mg_[N > 0 ? N : 1];                                                               \
+        _Pragma("unroll") for (int jj_ = 0; jj_ < N; ++jj_) ring_get(ent_field(E[jj_]), vu_[jj_], pu8_[jj_]); \
+        CP_FETCH_NEXT(sn, nd);                                                                  \
+        _Pragma("unroll") for (int jj_ = 0; jj_ < N; ++jj_) mg_[jj_] = *(const Magic *)(lds + erow + pu8_[jj_]); \
+        mv2 = *(const Magic *)(lds + vtab_off + 8u * pv2);                                      \
+        _Pragma("unroll") for (int jj_ = 0; jj_ < N; ++jj_)                                     \
+            acc = max(acc, (Tick)(vu_[jj_] + (Tick)magic_div(ent_t(E[jj_]), mg_[jj_])));        \
+    } break;
+
+        lds_barrier();                       // packets 0 and 1 are staged
+        {   // level 0, not overlapped with anything
+            const uint8_t *st = stage;
+            const uint4 d = ((const uint4 *)(st + a.wpad))[wave];
+            CP_FETCH_NEXT(st, d);
+            mv2 = *(const Magic *)(lds + vtab_off + 8u * pv2);
+        }
+        int s_cur = 0;
         for (int t = 0; t < Lpad; ++t) {
+            // what was fetched during the previous tick becomes current
+            c_entoff = n_entoff; c_width = n_width; c_lsh = n_lsh; c_rows = n_rows; c_rbase = n_rbase;
+#pragma unroll
+            for (int jj = 0; jj < PW; ++jj) E[jj] = E2[jj];
+            rc = rc2; pv = pv2; mv = mv2; nd = nd2;
             lds_barrier();
             if (t >= L) continue;
-            const uint8_t *st = (const uint8_t *)(stage + (size_t)(t & 1) * slot_chunks);
-            const uint8_t *pk = st + a.wpad;
-            const uint4 hdr = *(const uint4 *)pk;
-            const int npos = __builtin_amdgcn_readfirstlane((int)hdr.x);
-            const int nsl = __builtin_amdgcn_readfirstlane((int)hdr.y);
-            const int rbase = __builtin_amdgcn_readfirstlane((int)hdr.z);
-            const uint2 *slice_tab = (const uint2 *)(pk + 16);
-            const uint2 *rec = (const uint2 *)(pk + 16 + ((8 * nsl + 15) & ~15));
-            const Ent *ent_all = (const Ent *)(rec + (size_t)64 * nsl);
-            for (int j = wave; j < nsl; j += a.nc) {
-                const uint2 sl = slice_tab[j];
-                const int ebase = __builtin_amdgcn_readfirstlane((int)sl.x);
-                const int width = __builtin_amdgcn_readfirstlane((int)(sl.y & 0xffffffu));
-                const int lsh = __builtin_amdgcn_readfirstlane((int)(sl.y >> 24));   // log2 lanes per row
-                const int p = j * 64 + (lane >> lsh);
-                const uint2 rc = rec[p];
-                const uint32_t pv = st[p];
-                const Ent *ent = ent_all + ebase + lane;
-                const Magic *erow = etab + pv * k;
-                Tick acc = 0;
-#pragma unroll 4
-                for (int jj = 0; jj < width; ++jj) {
-                    uint32_t slot, te;
-                    if constexpr (ENT4) {
-                        const uint32_t en = ent[jj * 64];
-                        slot = en & 0xffffu;
-                        te = en >> 16;
-                    } else {
-                        const uint2 en = ent[jj * 64];
-                        slot = en.x;
-                        te = en.y;
-                    }
-                    Tick vu;
-                    uint32_t pu;
-                    ring.get((int)slot, vu, pu);
-                    const Tick x = (Tick)magic_div(te, erow[pu]);
-                    acc = max(acc, (Tick)(vu + x));
-                }
-                for (int off = (1 << lsh) >> 1; off > 0; off >>= 1)   // fold the lanes of a row
-                    acc = max(acc, __shfl_xor(acc, off));
-                if (p < npos && (lane & ((1 << lsh) - 1)) == 0) {
-                    const Tick fin = acc + (Tick)magic_div(rc.y, vtab[pv]);   // b(v), or tl(v) + w(v)
-                    int rs = rbase + p;
-                    if (rs >= R) rs -= R;
-                    ring.put(rs, fin, pv);
-                    if (out) out[(size_t)rc.x * P] = TSWEEP ? acc : fin;
-                    best = max(best, (long long)fin);
+            const int s_nxt = s_cur == 2 ? 0 : s_cur + 1;
+            const uint8_t *st = stage + (size_t)s_cur * slot_bytes;
+            const uint8_t *sn = stage + (size_t)s_nxt * slot_bytes;   // level t+1, staged during tick t-1
+            const uint32_t erow = etab_off + pv * k8;
+            Tick acc = 0;
+            switch (min(c_width, PW)) {
+                CP_TICK_CASE(0)
+                CP_TICK_CASE(1)
+                CP_TICK_CASE(2)
+                CP_TICK_CASE(3)
+                CP_TICK_CASE(4)
+                CP_TICK_CASE(5)
+                CP_TICK_CASE(6)
+                CP_TICK_CASE(7)
+                default:
+                CP_TICK_CASE(8)
+            }
+            if (c_width > PW) {                  // rows longer than the register window
+                const Ent *ent = (const Ent *)(st + a.wpad + c_entoff) + lane;
+                for (int jj = PW; jj < c_width; ++jj) {
+                    const Ent en = ent[jj * 64];
+                    Tick v1;
+                    uint32_t p1;
+                    ring_get(ent_field(en), v1, p1);
+                    const Magic m1 = *(const Magic *)(lds + erow + p1);
+                    acc = max(acc, (Tick)(v1 + (Tick)magic_div(ent_t(en), m1)));
                 }
             }
+            if (c_rows > 0) {
+                acc = fold(acc, c_lsh);
+                publish(acc, (Tick)magic_div(rc.y, mv), c_lsh, c_rows, c_rbase, rc.x, pv);
+            }
+            // further slices of level t when it has more slices than compute wavefronts
+            for (int j = wave + a.nc; j < a.smax; j += a.nc) slice_direct(st, j);
+            s_cur = s_nxt;
         }
+#undef CP_FETCH_NEXT
+#undef CP_TICK_CASE
     }
 
     if (a.cp_out) {   // workgroup maximum
-        for (int off = 32; off > 0; off >>= 1) best = max(best, __shfl_xor(best, off));
-        if (lane == 0) red[wave] = best;
+        long long b64 = (long long)best;
+        for (int off = 32; off > 0; off >>= 1) b64 = max(b64, __shfl_xor(b64, off));
+        if (lane == 0) red[wave] = b64;
         lds_barrier();
         if (tid == 0) {
-            for (int w2 = 1; w2 < a.nc; ++w2) best = max(best, red[w2]);
-            a.cp_out[q] = best;
+            for (int w2 = 1; w2 < a.nc; ++w2) b64 = max(b64, red[w2]);
+            a.cp_out[q] = b64;
         }
     }
 }
@@ -516,8 +646,9 @@ int launch_window_sweep_k(const SweepLaunch &s, const WindowCfg &cfg, hipStream_
     a.cp_out = s.cp_out;
     a.edge_tab = (const Magic *)s.edge_tab;
     a.vert_tab = (const Magic *)s.vert_tab;
-    a.P = s.P; a.L = s.L; a.k = s.k; a.slots = dir.slots; a.wpad = dir.wpad;
+    a.P = s.P; a.L = s.L; a.k = s.k; a.slots = dir.slots; a.wpad = dir.wpad; a.smax = dir.smax;
     a.nc = cfg.nc; a.nlw = cfg.nlw;
+    a.out32 = s.n < (1 << 24) && s.P < (1 << 24) && (uint64_t)s.n * (uint64_t)s.P < (1ull << 31);
     a.pgroups = (s.P + 7) / 8;
     auto kern = window_sweep_kernel<Tick, TSWEEP, PACKED, ENT4, NL, DR>;
     if (cfg.lds_bytes > 64 * 1024) {
@@ -550,16 +681,19 @@ int launch_window_sweep_p(const SweepLaunch &s, const WindowCfg &cfg, hipStream_
 template <bool TSWEEP>
 int launch_window_sweep_d(const SweepLaunch &s, const WindowCfg &cfg, hipStream_t st) {
     if (s.tick_bytes == 4)
-        return cfg.packed ? launch_window_sweep_p<int32_t, TSWEEP, true>(s, cfg, st)
-                          : launch_window_sweep_p<int32_t, TSWEEP, false>(s, cfg, st);
+        return s.win->packed ? launch_window_sweep_p<int32_t, TSWEEP, true>(s, cfg, st)
+                             : launch_window_sweep_p<int32_t, TSWEEP, false>(s, cfg, st);
+    if (s.win->packed) return CP_ERR_ARG;      // packed rings hold 32-bit ticks only
     return launch_window_sweep_p<int64_t, TSWEEP, false>(s, cfg, st);
 }
 
 }  // namespace
 
 bool window_config(const WindowDir &d, int32_t k, size_t tick_bytes, size_t lds_limit, WindowCfg &out) {
+    if (d.packed && tick_bytes != 4) return false;
     const int64_t need = d.wpad / 16 + (int64_t)d.max_chunks;     // 16-byte chunks per stage slot
     const size_t tab = (sizeof(Magic) * ((size_t)k * k + k) + 15) & ~(size_t)15;
+    const size_t ring = (((size_t)d.slots + 1) * (d.packed ? 8 : tick_bytes + 1) + 15) & ~(size_t)15;
     static const int kNl[4] = {1, 2, 4, 8};
     for (int nl : kNl) {
         const int64_t nlw = (need + 64 * nl - 1) / (64 * nl);
@@ -568,20 +702,10 @@ bool window_config(const WindowDir &d, int32_t k, size_t tick_bytes, size_t lds_
         out.nlw = (int)nlw;
         out.dr = nl <= 2 ? 8 : (nl == 4 ? 4 : 2);
         out.nc = std::max(1, std::min(d.smax, kWindowMaxWaves - (int)nlw));
-        const size_t stage = (size_t)2 * nl * nlw * 1024;
-        const size_t packed = (8 * ((size_t)d.slots + 1) + 15) & ~(size_t)15;
-        const size_t split = ((tick_bytes + 1) * ((size_t)d.slots + 1) + 15) & ~(size_t)15;
-        if (tick_bytes == 4 && tab + packed + stage <= lds_limit) {
-            out.packed = true;
-            out.lds_bytes = tab + packed + stage;
-            return true;
-        }
-        if (tab + split + stage <= lds_limit) {
-            out.packed = false;
-            out.lds_bytes = tab + split + stage;
-            return true;
-        }
-        return false;
+        out.packed = d.packed;
+        // the register window reads up to 8 entries x 64 lanes x 8 bytes past a slice's start
+        out.lds_bytes = ring + tab + (size_t)3 * nl * nlw * 1024 + 4096;
+        return out.lds_bytes <= lds_limit;
     }
     return false;
 }

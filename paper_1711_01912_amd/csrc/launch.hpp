@@ -16,7 +16,7 @@ struct SweepLaunch {
     bool magic = false;                 // multiply-shift tables (else plain divisors)
     bool narrow = false;                // 32-bit weights in the blob
     int tick_bytes = 4;
-    int32_t P = 0, k = 0, L = 0, max_width = 0;
+    int32_t n = 0, P = 0, k = 0, L = 0, max_width = 0;
     const uint8_t *pT = nullptr;        // [n][P] device ids (wave-column)
     const uint8_t *assign = nullptr;    // caller's assignments (resident-window: input of the gather)
     const uint8_t *pperm = nullptr;     // [P][L*wpad] device ids in sweep order (resident-window)

@@ -46,8 +46,24 @@ def _custom(name, n, src, dst, t, c, speeds, bandwidth, assignments, level=None)
 # ------------------------------------------------------------------ the five workloads
 
 def test_tiny_all_variants(gpu, oracle):
+    from gpu_util import run_gpu
     w = make_workload("tiny")
-    _check(gpu, oracle, w, ticks=(4, 8), layouts=(0, 1))
+    _check(gpu, oracle, w, ticks=(4,), layouts=(0, 1))
+    _check(gpu, oracle, w, plans=(COLUMN,), ticks=(8,), layouts=(0, 1))
+    # this graph's window ring was packed for 32-bit ticks: 64-bit ticks must be refused there
+    with pytest.raises(gpu.CpError) as e:
+        run_gpu(w, WINDOW, tick_bytes=8)
+    assert e.value.code == -12
+
+
+def test_window_plan_with_64_bit_ticks(gpu, oracle):
+    """A raw path bound past 2^31 with 32-bit weights: the window plan runs on int64 ticks."""
+    w = make_workload("large_sparse", P=40, levels=300, width=40)
+    w.c = w.c * 2**18
+    g = gpu.CpGraph.from_workload(w)
+    assert g.info["min_tick_bytes"] == 8 and g.info["window_ok"] == 1
+    g.close()
+    _check(gpu, oracle, w, ticks=(8,))
 
 
 def test_mlp_full(gpu, oracle):
