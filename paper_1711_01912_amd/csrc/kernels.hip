@@ -201,7 +201,8 @@ __global__ __launch_bounds__(256) void cp_sources_kernel(const int32_t *__restri
     }
 }
 
-// mask[v][word] bit i = (tl + b == CP) for partition 64*word + i
+// mask[v][word] bit i = (tl + b == CP) for partition 64*word + i.  A wavefront
+// takes four (vertex, word) tasks per trip so that eight loads are in flight.
 template <typename Tick>
 __global__ __launch_bounds__(256) void mask_kernel(const Tick *__restrict__ b,
                                                    const Tick *__restrict__ tl,
@@ -211,17 +212,29 @@ __global__ __launch_bounds__(256) void mask_kernel(const Tick *__restrict__ b,
     const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
     const int64_t ntasks = (int64_t)n * ncol;
-    for (int64_t task = wave0; task < ntasks; task += nwaves) {
-        const int64_t v = task / ncol;
-        const int32_t col = (int32_t)(task % ncol);
-        const int32_t q = col * 64 + lane;
-        bool on = false;
-        if (q < P) {
-            const size_t at = (size_t)v * P + q;
-            on = (int64_t)tl[at] + (int64_t)b[at] == cp[q];
+    for (int64_t task0 = wave0 * 4; task0 < ntasks; task0 += nwaves * 4) {
+        Tick vb[4], vt[4];
+        int64_t c[4];
+        bool live[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t task = task0 + u;
+            const int64_t v = task / ncol;
+            const int32_t q = (int32_t)(task % ncol) * 64 + lane;
+            live[u] = task < ntasks && q < P;
+            vb[u] = 0; vt[u] = 0; c[u] = -1;
+            if (live[u]) {
+                const size_t at = (size_t)v * P + q;
+                vt[u] = tl[at];
+                vb[u] = b[at];
+                c[u] = cp[q];
+            }
         }
-        const uint64_t word = __ballot(on);
-        if (lane == 0) mask[task] = word;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint64_t word = __ballot(live[u] && (int64_t)vt[u] + (int64_t)vb[u] == c[u]);
+            if (lane == 0 && task0 + u < ntasks) mask[task0 + u] = word;
+        }
     }
 }
 
@@ -237,30 +250,40 @@ __device__ __forceinline__ void lds_barrier() {
 
 // Device ids gathered into sweep order, one padded row of L*wpad bytes per
 // partition, so that the sweep kernel streams them like the graph packets.
-// Ids >= k are reported and replaced by 0.
+// Ids >= k are reported and replaced by 0.  One thread fills 16 positions.
 __global__ __launch_bounds__(256) void gather_assign_kernel(const int32_t *__restrict__ gmap,
                                                             int64_t row_len,
                                                             const uint8_t *__restrict__ assign,
                                                             int64_t a_stride_p, int64_t a_stride_v,
                                                             int32_t k, uint8_t *__restrict__ out,
                                                             int32_t *status) {
-    const int64_t i4 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;   // row_len is a multiple of 64
-    if (i4 >= row_len) return;
-    const int64_t q = blockIdx.y;
-    const int4 v = *(const int4 *)(gmap + i4);
+    const int64_t i16 = ((int64_t)blockIdx.y * 256 + threadIdx.x) * 16;   // row_len is a multiple of 64
+    if (i16 >= row_len) return;
+    const int64_t q = blockIdx.x;
     const uint8_t *row = assign + q * a_stride_p;
-    uint32_t p0 = v.x >= 0 ? row[(int64_t)v.x * a_stride_v] : 0;
-    uint32_t p1 = v.y >= 0 ? row[(int64_t)v.y * a_stride_v] : 0;
-    uint32_t p2 = v.z >= 0 ? row[(int64_t)v.z * a_stride_v] : 0;
-    uint32_t p3 = v.w >= 0 ? row[(int64_t)v.w * a_stride_v] : 0;
-    if (max(max(p0, p1), max(p2, p3)) >= (uint32_t)k) {
-        *status = CP_STATUS_BAD_DEVICE_ID;
-        if (p0 >= (uint32_t)k) p0 = 0;
-        if (p1 >= (uint32_t)k) p1 = 0;
-        if (p2 >= (uint32_t)k) p2 = 0;
-        if (p3 >= (uint32_t)k) p3 = 0;
+    int4 v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = *(const int4 *)(gmap + i16 + 4 * j);
+    uint32_t w[4];
+    uint32_t worst = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        uint32_t p0 = v[j].x >= 0 ? row[(int64_t)v[j].x * a_stride_v] : 0;
+        uint32_t p1 = v[j].y >= 0 ? row[(int64_t)v[j].y * a_stride_v] : 0;
+        uint32_t p2 = v[j].z >= 0 ? row[(int64_t)v[j].z * a_stride_v] : 0;
+        uint32_t p3 = v[j].w >= 0 ? row[(int64_t)v[j].w * a_stride_v] : 0;
+        const uint32_t m = max(max(p0, p1), max(p2, p3));
+        if (m >= (uint32_t)k) {
+            if (p0 >= (uint32_t)k) p0 = 0;
+            if (p1 >= (uint32_t)k) p1 = 0;
+            if (p2 >= (uint32_t)k) p2 = 0;
+            if (p3 >= (uint32_t)k) p3 = 0;
+        }
+        worst = max(worst, m);
+        w[j] = p0 | (p1 << 8) | (p2 << 16) | (p3 << 24);
     }
-    *(uint32_t *)(out + q * row_len + i4) = p0 | (p1 << 8) | (p2 << 16) | (p3 << 24);
+    if (worst >= (uint32_t)k) *status = CP_STATUS_BAD_DEVICE_ID;
+    *(uint4 *)(out + q * row_len + i16) = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
 struct WindowArgs {
@@ -713,9 +736,9 @@ bool window_config(const WindowDir &d, int32_t k, size_t tick_bytes, size_t lds_
 int launch_gather_assign(const SweepLaunch &s, uint8_t *out, void *stream) {
     const WindowDir &dir = *s.win;
     const int64_t row_len = (int64_t)s.L * dir.wpad;
-    const int64_t chunks = (row_len + 1023) / 1024;
+    const int64_t chunks = (row_len + 4095) / 4096;
     if (chunks > 65535) return CP_ERR_SIZE;
-    hipLaunchKernelGGL(gather_assign_kernel, dim3((unsigned)chunks, (unsigned)s.P), dim3(256), 0,
+    hipLaunchKernelGGL(gather_assign_kernel, dim3((unsigned)s.P, (unsigned)chunks), dim3(256), 0,
                        (hipStream_t)stream, (const int32_t *)(s.blob + dir.gmap_off), row_len,
                        s.assign, s.a_stride_p, s.a_stride_v, s.k, out, s.status);
     return hip_ok(hipGetLastError());
@@ -774,7 +797,7 @@ int launch_mask(const void *b, const void *tl, const int64_t *cp, int32_t n, int
                 int tick_bytes, uint64_t *mask, void *stream) {
     const int ncol = (P + 63) / 64;
     const int64_t tasks = (int64_t)n * ncol;
-    const unsigned blocks = (unsigned)std::max<int64_t>(1, std::min<int64_t>((tasks + 3) / 4, 256 * 64));
+    const unsigned blocks = (unsigned)std::max<int64_t>(1, std::min<int64_t>((tasks + 15) / 16, 256 * 32));
     if (tick_bytes == 4)
         hipLaunchKernelGGL(mask_kernel<int32_t>, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
                            (const int32_t *)b, (const int32_t *)tl, cp, n, P, ncol, mask);
