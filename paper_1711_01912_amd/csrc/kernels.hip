@@ -303,17 +303,17 @@ struct WindowArgs {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // stays in registers when indexed statically
 typedef const uint32_t __attribute__((address_space(4))) *const_u32_ptr;   // uniform reads become scalar loads
 
-// LDS layout: [ring][cost tables][3 stage slots]; a stage slot is
+// LDS layout: [ring][cost tables][2 stage slots]; a stage slot is
 // [wpad bytes of device ids][packet], NL*nlw*1024 bytes in all.  The ring is
 // either (slots+1) x {value, device*8} (PACKED: one 8-byte read per relaxation, and
 // an entry's ring field is the byte offset itself) or (slots+1) values followed by
 // (slots+1) device bytes.
 //
 // Wavefronts 0..nc-1 compute, wavefronts nc..nc+nlw-1 load.  Tick t: after the
-// barrier the compute wavefronts relax level t out of its stage slot while the
-// loaders copy packet t+2 (requested DR ticks earlier, held in registers) into
-// the slot that level t-1 has just left and request packet t+2+DR.  Nothing on the
-// level-to-level dependency touches memory beyond LDS.
+// barrier the compute wavefronts relax level t out of stage slot t&1 while the
+// loaders copy packet t+1 (requested DR ticks earlier, held in registers) into
+// the other slot and request packet t+1+DR.  Nothing on the level-to-level
+// dependency touches memory beyond LDS.
 template <typename Tick, bool TSWEEP, bool PACKED, bool ENT4, int NL, int DR>
 __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(WindowArgs a) {
     extern __shared__ uint4 lds16[];
@@ -393,18 +393,15 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
         for (int r = 0; r < DR; ++r) CP_ISSUE(r, r);
         CP_STORE(0, 0);
         CP_ISSUE(0, DR);
-        CP_STORE(1 % DR, 1);
-        CP_ISSUE(1 % DR, DR + 1);
-        lds_barrier();                       // packets 0 and 1 are staged
-        int s_put = 2;                       // slot of packet t+2
+        lds_barrier();                       // packet 0 is staged
         for (int t0 = 0; t0 < Lpad; t0 += DR) {
 #pragma unroll
             for (int r = 0; r < DR; ++r) {
                 const int t = t0 + r;
                 lds_barrier();
-                CP_STORE((r + 2) % DR, s_put);
-                CP_ISSUE((r + 2) % DR, t + 2 + DR);
-                s_put = s_put == 2 ? 0 : s_put + 1;
+                // the compute wavefronts now read slot t&1, which packet t-1 has left
+                CP_STORE((r + 1) % DR, (t + 1) & 1);
+                CP_ISSUE((r + 1) % DR, t + 1 + DR);
             }
         }
 #undef CP_ISSUE
@@ -412,11 +409,9 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
     } else {
         // ------------------------------------------------ compute wavefronts
         typedef typename std::conditional<ENT4, uint32_t, uint2>::type Ent;
-        constexpr int PW = 8;                // entries per lane held in registers
         Tick *out = a.out ? (Tick *)a.out + q : nullptr;
         const uint32_t P = (uint32_t)a.P;
         const uint32_t k8 = 8u * (uint32_t)k;
-        const uint32_t desc_next_off = (uint32_t)a.wpad + 16u * (uint32_t)a.smax;   // from the slot base
         const uint32_t rec_off = (uint32_t)a.wpad + 32u * (uint32_t)a.smax;
 
         auto ent_field = [](Ent e) -> uint32_t {
@@ -466,7 +461,7 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
                 best = max(best, fin);
             }
         };
-        // a whole slice straight out of its stage slot (no register pipelining)
+        // one slice of the current level out of its stage slot
         auto slice_direct = [&](const uint8_t *st, int j) {
             const uint4 d = ((const uint4 *)(st + a.wpad))[j];
             const uint32_t ent_off = __builtin_amdgcn_readfirstlane((int)d.x);
@@ -481,122 +476,45 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
             const uint32_t erow = etab_off + pv * k8;
             const Ent *ent = (const Ent *)(st + a.wpad + ent_off) + lane;
             Tick acc = 0;
-#pragma unroll 4
-            for (int jj = 0; jj < width; ++jj) {
-                const Ent en = ent[jj * 64];
-                Tick vu;
-                uint32_t pu8;
-                ring_get(ent_field(en), vu, pu8);
-                const Magic mg = *(const Magic *)(lds + erow + pu8);
-                acc = max(acc, (Tick)(vu + (Tick)magic_div(ent_t(en), mg)));
+            // N relaxations as one straight-line block: N entry reads, N ring reads, N
+            // cost-table reads, then the arithmetic -- three LDS round trips whatever N is
+#define CP_BLOCK(N)                                                                             \
+    do {                                                                                        \
+        Ent en_[N];                                                                             \
+        Tick vu_[N];                                                                            \
+        uint32_t pu8_[N];                                                                       \
+        Magic mg_[N];                                                                           \
+        _Pragma("unroll") for (int i_ = 0; i_ < N; ++i_) en_[i_] = ent[(jj + i_) * 64];         \
+        _Pragma("unroll") for (int i_ = 0; i_ < N; ++i_) ring_get(ent_field(en_[i_]), vu_[i_], pu8_[i_]); \
+        _Pragma("unroll") for (int i_ = 0; i_ < N; ++i_) mg_[i_] = *(const Magic *)(lds + erow + pu8_[i_]); \
+        _Pragma("unroll") for (int i_ = 0; i_ < N; ++i_)                                        \
+            acc = max(acc, (Tick)(vu_[i_] + (Tick)magic_div(ent_t(en_[i_]), mg_[i_])));         \
+    } while (0)
+            int jj = 0;
+            for (; jj + 8 <= width; jj += 8) CP_BLOCK(8);
+            switch (width - jj) {
+                case 1: CP_BLOCK(1); break;
+                case 2: CP_BLOCK(2); break;
+                case 3: CP_BLOCK(3); break;
+                case 4: CP_BLOCK(4); break;
+                case 5: CP_BLOCK(5); break;
+                case 6: CP_BLOCK(6); break;
+                case 7: CP_BLOCK(7); break;
+                default: break;
             }
+#undef CP_BLOCK
             acc = fold(acc, lsh);
             const Magic mv = *(const Magic *)(lds + vtab_off + 8u * pv);
             publish(acc, (Tick)magic_div(rc.y, mv), lsh, rows, rbase, rc.x, pv);
         };
 
-        // Register pipeline for slice `wave`.  The c_ state describes the level about to
-        // be relaxed; its first PW entries E, record rc, device pv and vertex-cost
-        // constants mv were read from LDS one tick earlier, and nd is the descriptor of the
-        // level after it (each packet carries its successor's descriptors).  One tick is
-        // a straight-line block per slice width: ring reads (the only reads that depend
-        // on the previous level), then the reads for the next level, then the cost-table
-        // reads, so that a wavefront waits for two dependent LDS round trips per level.
-        uint32_t c_entoff = 0;
-        int c_width = 0, c_lsh = 0, c_rows = 0, c_rbase = 0;
-        Ent E[PW], E2[PW];
-        uint2 rc = make_uint2(0xffffffffu, 0), rc2 = rc;
-        uint32_t pv = 0, pv2 = 0;
-        Magic mv = {0, 0}, mv2 = {0, 0};
-        uint4 nd = make_uint4(0, 0, 0, 0), nd2 = nd;
-        uint32_t n_entoff = 0;
-        int n_width = 0, n_lsh = 0, n_rows = 0, n_rbase = 0;
-
-        // descriptor D (uniform, in a VGPR) to scalars; then that slice's record, device id,
-        // first PW entries and the descriptor after it, all out of stage slot SN
-#define CP_FETCH_NEXT(SN, D)                                                                    \
-    do {                                                                                        \
-        n_entoff = (uint32_t)__builtin_amdgcn_readfirstlane((int)(D).x);                        \
-        n_width = __builtin_amdgcn_readfirstlane((int)((D).y & 0xffffffu));                     \
-        n_lsh = __builtin_amdgcn_readfirstlane((int)((D).y >> 24));                             \
-        n_rows = __builtin_amdgcn_readfirstlane((int)(D).z);                                    \
-        n_rbase = __builtin_amdgcn_readfirstlane((int)(D).w);                                   \
-        const int p_ = wave * 64 + (lane >> n_lsh);                                             \
-        nd2 = ((const uint4 *)((SN) + desc_next_off))[wave];                                    \
-        rc2 = ((const uint2 *)((SN) + rec_off))[p_];                                            \
-        pv2 = (SN)[p_];                                                                         \
-        const Ent *ent_ = (const Ent *)((SN) + a.wpad + n_entoff) + lane;                       \
-        _Pragma("unroll") for (int jj_ = 0; jj_ < PW; ++jj_) E2[jj_] = ent_[jj_ * 64];          \
-    } while (0)
-
-        // N relaxations out of registers with the next level's reads in their shadow
-#define CP_TICK_CASE(N)                                                                         \
-    case N: {                                                                                   \
-        Tick vu_[N > 0 ? N : 1];                                                                \
-        uint32_t pu8_[N > 0 ? N : 1];                                                           \
-        Magic mg_[N > 0 ? N : 1];                                                               \
-        _Pragma("unroll") for (int jj_ = 0; jj_ < N; ++jj_) ring_get(ent_field(E[jj_]), vu_[jj_], pu8_[jj_]); \
-        CP_FETCH_NEXT(sn, nd);                                                                  \
-        _Pragma("unroll") for (int jj_ = 0; jj_ < N; ++jj_) mg_[jj_] = *(const Magic *)(lds + erow + pu8_[jj_]); \
-        mv2 = *(const Magic *)(lds + vtab_off + 8u * pv2);                                      \
-        _Pragma("unroll") for (int jj_ = 0; jj_ < N; ++jj_)                                     \
-            acc = max(acc, (Tick)(vu_[jj_] + (Tick)magic_div(ent_t(E[jj_]), mg_[jj_])));        \
-    } break;
-
-        lds_barrier();                       // packets 0 and 1 are staged
-        {   // level 0, not overlapped with anything
-            const uint8_t *st = stage;
-            const uint4 d = ((const uint4 *)(st + a.wpad))[wave];
-            CP_FETCH_NEXT(st, d);
-            mv2 = *(const Magic *)(lds + vtab_off + 8u * pv2);
-        }
-        int s_cur = 0;
+        lds_barrier();                       // packet 0 is staged
         for (int t = 0; t < Lpad; ++t) {
-            // what was fetched during the previous tick becomes current
-            c_entoff = n_entoff; c_width = n_width; c_lsh = n_lsh; c_rows = n_rows; c_rbase = n_rbase;
-#pragma unroll
-            for (int jj = 0; jj < PW; ++jj) E[jj] = E2[jj];
-            rc = rc2; pv = pv2; mv = mv2; nd = nd2;
             lds_barrier();
             if (t >= L) continue;
-            const int s_nxt = s_cur == 2 ? 0 : s_cur + 1;
-            const uint8_t *st = stage + (size_t)s_cur * slot_bytes;
-            const uint8_t *sn = stage + (size_t)s_nxt * slot_bytes;   // level t+1, staged during tick t-1
-            const uint32_t erow = etab_off + pv * k8;
-            Tick acc = 0;
-            switch (min(c_width, PW)) {
-                CP_TICK_CASE(0)
-                CP_TICK_CASE(1)
-                CP_TICK_CASE(2)
-                CP_TICK_CASE(3)
-                CP_TICK_CASE(4)
-                CP_TICK_CASE(5)
-                CP_TICK_CASE(6)
-                CP_TICK_CASE(7)
-                default:
-                CP_TICK_CASE(8)
-            }
-            if (c_width > PW) {                  // rows longer than the register window
-                const Ent *ent = (const Ent *)(st + a.wpad + c_entoff) + lane;
-                for (int jj = PW; jj < c_width; ++jj) {
-                    const Ent en = ent[jj * 64];
-                    Tick v1;
-                    uint32_t p1;
-                    ring_get(ent_field(en), v1, p1);
-                    const Magic m1 = *(const Magic *)(lds + erow + p1);
-                    acc = max(acc, (Tick)(v1 + (Tick)magic_div(ent_t(en), m1)));
-                }
-            }
-            if (c_rows > 0) {
-                acc = fold(acc, c_lsh);
-                publish(acc, (Tick)magic_div(rc.y, mv), c_lsh, c_rows, c_rbase, rc.x, pv);
-            }
-            // further slices of level t when it has more slices than compute wavefronts
-            for (int j = wave + a.nc; j < a.smax; j += a.nc) slice_direct(st, j);
-            s_cur = s_nxt;
+            const uint8_t *st = stage + (size_t)(t & 1) * slot_bytes;
+            for (int j = wave; j < a.smax; j += a.nc) slice_direct(st, j);
         }
-#undef CP_FETCH_NEXT
-#undef CP_TICK_CASE
     }
 
     if (a.cp_out) {   // workgroup maximum
@@ -726,8 +644,7 @@ bool window_config(const WindowDir &d, int32_t k, size_t tick_bytes, size_t lds_
         out.dr = nl <= 2 ? 8 : (nl == 4 ? 4 : 2);
         out.nc = std::max(1, std::min(d.smax, kWindowMaxWaves - (int)nlw));
         out.packed = d.packed;
-        // the register window reads up to 8 entries x 64 lanes x 8 bytes past a slice's start
-        out.lds_bytes = ring + tab + (size_t)3 * nl * nlw * 1024 + 4096;
+        out.lds_bytes = ring + tab + (size_t)2 * nl * nlw * 1024;
         return out.lds_bytes <= lds_limit;
     }
     return false;
