@@ -56,7 +56,8 @@ extern "C" {
 
 /* ---- value written to *status_out by the device ---- */
 #define CP_STATUS_OK             0
-#define CP_STATUS_BAD_DEVICE_ID  1   /* some assignments entry is >= k (it was treated as device 0) */
+#define CP_STATUS_BAD_DEVICE_ID  1   /* some assignments entry is >= k: the call's outputs are meaningless
+                                        (the entry was replaced by a valid device so that no access leaves its table) */
 
 /* ---- enums ---- */
 #define CP_TICK_I32  4   /* b-level / t-level stored as int32 (only if the graph's bound allows) */

@@ -70,7 +70,8 @@ bool window_fits(const Packed &p, int32_t k, size_t tick_bytes, size_t limit = k
 }
 
 size_t pperm_bytes(const Packed &p, const WindowDir &d, int32_t batch) {
-    return align_up((size_t)batch * (size_t)p.L * (size_t)d.wpad);
+    (void)p;
+    return align_up((size_t)batch * (size_t)d.ticks * (size_t)d.wpad);
 }
 
 // LDS one workgroup may use on the current device, minus the kernel's static part.
@@ -263,13 +264,19 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
     else { s.a_stride_p = 1; s.a_stride_v = batch; }
     s.vert_tab = d_tab + 2 * kk * 8;
     s.status = status_out;
-    if (use == CP_PLAN_RESIDENT_WINDOW) {   // device ids into sweep order, per direction
-        if (blevel_out) {
+    // Device ids reach the resident-window sweep either straight from the caller's rows
+    // (16-byte loads: the rows must be contiguous, and whole-buffer size and base must be
+    // multiples of 16 so that no load leaves the buffer) or gathered into sweep order first.
+    const bool rows_ok = assign_layout == CP_ASSIGN_PARTITION_MAJOR &&
+                         ((uint64_t)p.n * (uint64_t)batch) % 16 == 0 && ((uintptr_t)assignments % 16) == 0;
+    const bool direct_b = rows_ok && p.win_b.direct_ok, direct_t = rows_ok && p.win_t.direct_ok;
+    if (use == CP_PLAN_RESIDENT_WINDOW) {
+        if (blevel_out && !direct_b) {
             s.win = &p.win_b;
             rc = launch_gather_assign(s, d_pperm_b, stream);
             if (rc) return rc;
         }
-        if (tlevel_out) {
+        if (tlevel_out && !direct_t) {
             s.win = &p.win_t;
             rc = launch_gather_assign(s, d_pperm_t, stream);
             if (rc) return rc;
@@ -286,6 +293,7 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
         s.edge_tab = d_tab;
         s.cp_out = use == CP_PLAN_RESIDENT_WINDOW ? cp_out : nullptr;
         s.pperm = d_pperm_b;
+        s.direct_ids = direct_b;
         rc = use == CP_PLAN_RESIDENT_WINDOW ? launch_window_sweep(s, cfg_b, stream, launches)
                                             : launch_column_sweep(s, stream, launches);
         if (rc) return rc;
@@ -309,6 +317,7 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
         s.edge_tab = d_tab + kk * 8;
         s.cp_out = nullptr;
         s.pperm = d_pperm_t;
+        s.direct_ids = direct_t;
         rc = use == CP_PLAN_RESIDENT_WINDOW ? launch_window_sweep(s, cfg_t, stream, launches ? launches + 1 : nullptr)
                                             : launch_column_sweep(s, stream, launches ? launches + 1 : nullptr);
         if (rc) return rc;

@@ -17,6 +17,8 @@ constexpr int kMagicMaxK = 64;         // multiply-shift tables are staged in LD
 constexpr size_t kAlign = 256;
 constexpr size_t kLdsBudget = 160 * 1024;   // LDS per workgroup on gfx950
 constexpr int kWindowMaxWaves = 16;      // wavefronts per workgroup (compute + loader)
+constexpr int kWindowTickSlices = 8;     // slices (compute wavefronts) per tick
+constexpr uint64_t kWindowTickBytes = 15 * 1024;   // packet bytes per tick, unless one slice alone is larger
 
 inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
 
@@ -31,16 +33,18 @@ struct ColumnDir {
 };
 
 // One sweep direction of the resident-window plan.  Vertices are renumbered by
-// position in sweep order.  Everything a level needs is one contiguous "packet"
-// of 16-byte chunks, so that loader wavefronts can stream it into LDS ahead of
-// the compute wavefronts.  A level is cut into slices of 64 rows (vertices), one
-// per compute wavefront; a slice of at most 32 rows gives each row 2..64 lanes
-// that share its edges and fold their maxima at the end.
+// position in sweep order.  A level is cut into ticks (runs of at most
+// kWindowTickSlices slices and about kWindowTickBytes of packet), and everything
+// a tick needs is one contiguous "packet" of 16-byte chunks, so that loader
+// wavefronts can stream it into LDS ahead of the compute wavefronts.  A slice is
+// 64 rows (vertices), one per compute wavefront; a slice of at most 32 rows gives
+// each row 2..64 lanes that share its edges and fold their maxima at the end.
 //   descriptors  smax x {byte offset of the slice's entries in the packet,
-//                        width | log2(lanes per row) << 24, rows, ring slot of row 0}
-//                (rows = 0 for slices this level does not have), followed by a copy
-//                of the NEXT level's descriptors (zeros after the last level)
-//   records      per slice 64 x {original vertex id (0xffffffff = padding), c}
+//                        width | rows << 16 | log2(lanes per row) << 24,
+//                        lowest vertex id of the tick, ring slot of row 0}
+//                (rows = 0 for slices this tick does not have)
+//   records      per slice 64 x {original vertex id, c}; rows past `rows` are padding
+//                and carry the tick's lowest vertex id
 //   entries      per slice width x 64 x {ring field of the neighbour, t(e)}: entry j
 //                of lane l of a slice sits at base + j*64 + l.  The ring field is the
 //                neighbour's slot (times 8 when the ring holds {value, device}
@@ -49,13 +53,16 @@ struct ColumnDir {
 //                one uint32 (field | t << 16) when both fit 16 bits (ent4).
 struct WindowDir {
     size_t stream_off = 0;   // uint4 [total_chunks]
-    size_t pkt_off = 0;      // uint32 [L+1] first chunk of each packet, in sweep order
-    size_t gmap_off = 0;     // int32 [L*wpad] original id per padded position, -1 = padding
+    size_t tick_off = 0;     // uint32 [ticks+1][4] {first chunk, chunks, lowest id, id span}
+    size_t gmap_off = 0;     // int32 [ticks*wpad] original id per padded position, -1 = padding
     int64_t total_chunks = 0;
+    int32_t ticks = 0;
     int32_t max_chunks = 0;  // largest packet
-    int32_t wpad = 0;        // level width rounded up to whole slices of 64
-    int32_t smax = 0;        // slices of the widest level
+    int32_t wpad = 0;        // tick width rounded up to whole slices of 64
+    int32_t smax = 0;        // slices of the widest tick
     int32_t slots = 0;       // ring capacity R: slot of position i is i mod R
+    int32_t idpad = 0;       // bytes a stage slot reserves for device ids
+    bool direct_ok = false;  // every tick's vertices lie in a short id range
     bool packed = false;     // ring of {value, device} pairs (32-bit ticks only)
     bool ent4 = false;       // 4-byte entries
 };

@@ -94,88 +94,126 @@ int lanes_per_row_log2(int rows) {
 }
 
 // Resident-window packing for one direction (layout: see WindowDir).  Returns
-// false if the packets would be unreasonably large.
+// false if the graph does not suit that plan.
 bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int64_t max_t,
                      bool ticks32, const Csr &csr, const std::vector<int32_t> &order,
                      const ColumnDir &col, WindowDir &dir) {
     std::vector<int32_t> pos(n);
     for (int32_t i = 0; i < n; ++i) pos[order[i]] = i;
 
-    // ring capacity: while a level [a, b) is being written, every position from the
-    // earliest one it reads up to b-1 must own a distinct slot
-    int64_t need = 1;
-    int32_t wmax = 1;
-    for (int32_t s = 0; s < L; ++s) {
-        int32_t a = col.lvl_begin[s], b = a + col.lvl_count[s];
+    auto slice_entries = [&](int32_t p0, int32_t rows) -> uint64_t {
+        int32_t v0 = order[p0];
+        int64_t deg0 = csr.ptr[v0 + 1] - csr.ptr[v0];                 // longest row leads
+        int sh = lanes_per_row_log2(rows);
+        return (uint64_t)((deg0 + (1 << sh) - 1) >> sh) * kWave;
+    };
+    auto earliest_read = [&](int32_t a, int32_t b) -> int32_t {
         int32_t jmin = a;
         for (int32_t i = a; i < b; ++i) {
             int32_t v = order[i];
             for (int32_t e = csr.ptr[v]; e < csr.ptr[v + 1]; ++e) jmin = std::min(jmin, pos[csr.idx[e]]);
         }
-        need = std::max<int64_t>(need, (int64_t)b - jmin);
+        return jmin;
+    };
+
+    // An upper bound of the ring capacity (exact value below, once the ticks are known)
+    // fixes the entry format: the ring holds {value, device} pairs if that leaves room
+    // for two stage slots and small cost tables, else separate arrays.
+    int64_t need_ub = 1;
+    for (int32_t s = 0; s < L; ++s) {
+        int32_t a = col.lvl_begin[s], b = a + col.lvl_count[s];
+        need_ub = std::max<int64_t>(need_ub, (int64_t)b - earliest_read(a, b));
+    }
+    dir.packed = ticks32 && 8 * ((uint64_t)need_ub + 1) + 2 * (kWindowTickBytes + 1024) + 4096 <= kLdsBudget - 512;
+    const uint64_t field_max = dir.packed ? 8 * (uint64_t)need_ub : (uint64_t)need_ub;
+    dir.ent4 = field_max < 65536 && max_t < 65536;
+    const uint64_t esz = dir.ent4 ? 4 : 8;
+
+    // Ticks: a level is cut into runs of at most kWindowTickSlices slices and about
+    // kWindowTickBytes of packet, so that one typical packet size fits every tick
+    // (vertices of one level do not depend on each other, so any cut is valid).
+    std::vector<int32_t> tick_a, tick_b;
+    for (int32_t s = 0; s < L; ++s) {
+        int32_t a = col.lvl_begin[s], b = a + col.lvl_count[s];
+        if (a == b) continue;
+        int32_t start = a, nsl = 0;
+        uint64_t bytes = 0;
+        for (int32_t p0 = a; p0 < b; p0 += kWave) {
+            int32_t rows = std::min(kWave, b - p0);
+            uint64_t add = 8 * (uint64_t)kWave + esz * slice_entries(p0, rows);
+            if (nsl > 0 && (nsl == kWindowTickSlices || bytes + add > kWindowTickBytes)) {
+                tick_a.push_back(start);
+                tick_b.push_back(p0);
+                start = p0;
+                nsl = 0;
+                bytes = 0;
+            }
+            ++nsl;
+            bytes += add;
+        }
+        tick_a.push_back(start);
+        tick_b.push_back(b);
+    }
+    const int32_t T = (int32_t)tick_a.size();
+    dir.ticks = T;
+
+    int64_t need = 1;
+    int32_t wmax = 1;
+    int64_t idspan = 1;
+    std::vector<uint32_t> tick_tab(4 * ((size_t)T + 1), 0);   // {first chunk, chunks, lowest id, id span}
+    uint64_t total = 0;
+    uint32_t max_chunks = 1;
+    for (int32_t s = 0; s < T; ++s) {
+        int32_t a = tick_a[s], b = tick_b[s];
+        need = std::max<int64_t>(need, (int64_t)b - earliest_read(a, b));
         wmax = std::max(wmax, b - a);
+        int32_t lo = order[a], hi = order[a];
+        for (int32_t i = a; i < b; ++i) { lo = std::min(lo, order[i]); hi = std::max(hi, order[i]); }
+        idspan = std::max<int64_t>(idspan, (int64_t)hi - lo + 1);
+        tick_tab[4 * s + 2] = (uint32_t)lo;
+        tick_tab[4 * s + 3] = (uint32_t)(hi - lo + 1);
     }
     dir.slots = (int32_t)need;
     dir.smax = (wmax + kWave - 1) / kWave;
     dir.wpad = dir.smax * kWave;
-    if (dir.smax > 64) return false;        // levels this wide belong to the wave-column plan
+    if (dir.smax > kWindowMaxWaves - 1) return false;   // only when one slice alone exceeds every limit
+    // the device ids of a tick can be staged straight from the caller's row when its
+    // vertices occupy a short id range
+    dir.direct_ok = idspan + 15 <= 4 * (int64_t)dir.wpad;
+    dir.idpad = dir.direct_ok ? std::max<int32_t>(dir.wpad, (int32_t)((idspan + 15 + 15) / 16 * 16)) : dir.wpad;
 
-    // entry counts per level
-    std::vector<uint64_t> lvl_entries(L, 0);
-    uint64_t emax = 0;
-    for (int32_t s = 0; s < L; ++s) {
-        int32_t a = col.lvl_begin[s], b = a + col.lvl_count[s];
-        for (int32_t p0 = a; p0 < b; p0 += kWave) {
-            int32_t v0 = order[p0];
-            int64_t deg0 = csr.ptr[v0 + 1] - csr.ptr[v0];                 // longest row leads
-            int sh = lanes_per_row_log2(std::min(kWave, b - p0));
-            lvl_entries[s] += (uint64_t)((deg0 + (1 << sh) - 1) >> sh) * kWave;
-        }
-        emax = std::max(emax, lvl_entries[s]);
-    }
-    // ring layout: {value, device} pairs if that leaves room for three stage slots
-    // and small cost tables, else separate arrays; it fixes what an entry stores
-    {
-        const uint64_t slot_est = align_up(dir.wpad + 32 * (uint64_t)dir.smax + 8 * (uint64_t)dir.wpad + 4 * emax, 1024);
-        dir.packed = ticks32 && 8 * ((uint64_t)need + 1) + 3 * slot_est + 4096 <= kLdsBudget - 512;
-    }
-    const uint64_t field_max = dir.packed ? 8 * (uint64_t)need : (uint64_t)need;
-    dir.ent4 = field_max < 65536 && max_t < 65536;
-    const uint64_t esz = dir.ent4 ? 4 : 8;
-
-    std::vector<uint32_t> pkt_off((size_t)L + 1);
-    uint64_t total = 0;
-    uint32_t max_chunks = 1;
-    for (int32_t s = 0; s < L; ++s) {
-        int32_t a = col.lvl_begin[s], b = a + col.lvl_count[s];
-        uint64_t nsl = (uint64_t)(b - a + kWave - 1) / kWave;
-        uint64_t bytes = 32 * (uint64_t)dir.smax + 8 * kWave * nsl + esz * lvl_entries[s];
+    for (int32_t s = 0; s < T; ++s) {
+        int32_t a = tick_a[s], b = tick_b[s];
+        uint64_t nsl = (uint64_t)(b - a + kWave - 1) / kWave, entries = 0;
+        for (int32_t p0 = a; p0 < b; p0 += kWave) entries += slice_entries(p0, std::min(kWave, b - p0));
+        uint64_t bytes = 16 * (uint64_t)dir.smax + 8 * kWave * nsl + esz * entries;
         uint64_t chunks = (bytes + 15) / 16;
-        if (chunks > (1u << 16)) return false;      // a 1 MB level never fits LDS
-        pkt_off[s] = (uint32_t)total;
+        if (chunks > (1u << 16)) return false;      // a 1 MB tick never fits LDS
+        tick_tab[4 * s] = (uint32_t)total;
+        tick_tab[4 * s + 1] = (uint32_t)chunks;
         total += chunks;
         if (total >= (1ull << 31)) return false;
         max_chunks = std::max<uint32_t>(max_chunks, (uint32_t)chunks);
     }
-    pkt_off[L] = (uint32_t)total;
+    tick_tab[4 * (size_t)T] = (uint32_t)total;
     dir.total_chunks = (int64_t)total;
     dir.max_chunks = (int32_t)max_chunks;
 
     dir.stream_off = w.reserve(16 * (size_t)std::max<uint64_t>(total, 1));
-    dir.pkt_off = w.reserve(sizeof(uint32_t) * pkt_off.size());
-    std::memcpy(w.at<uint32_t>(dir.pkt_off), pkt_off.data(), sizeof(uint32_t) * pkt_off.size());
-    dir.gmap_off = w.reserve(sizeof(int32_t) * (size_t)L * dir.wpad);
+    dir.tick_off = w.reserve(sizeof(uint32_t) * tick_tab.size());
+    std::memcpy(w.at<uint32_t>(dir.tick_off), tick_tab.data(), sizeof(uint32_t) * tick_tab.size());
+    dir.gmap_off = w.reserve(sizeof(int32_t) * (size_t)std::max(T, 1) * dir.wpad);
     int32_t *gmap = w.at<int32_t>(dir.gmap_off);
-    std::fill(gmap, gmap + (size_t)L * dir.wpad, -1);
+    std::fill(gmap, gmap + (size_t)std::max(T, 1) * dir.wpad, -1);
 
     const uint32_t pad_field = (uint32_t)(dir.packed ? 8 * (uint64_t)dir.slots : (uint64_t)dir.slots);
-    for (int32_t s = 0; s < L; ++s) {
-        int32_t a = col.lvl_begin[s], b = a + col.lvl_count[s];
+    for (int32_t s = 0; s < T; ++s) {
+        int32_t a = tick_a[s], b = tick_b[s];
         uint32_t nsl = (uint32_t)(b - a + kWave - 1) / kWave;
-        uint8_t *pk = w.at<uint8_t>(dir.stream_off + 16 * (size_t)pkt_off[s]);
-        uint32_t *desc = (uint32_t *)pk;                                  // smax x {ent byte offset, width|lsh<<24, rows, ring slot of row 0}
-        uint32_t *rec = (uint32_t *)(pk + 32 * (size_t)dir.smax);         // nsl*64 x {v, c}
-        const uint32_t ent_start = 32 * (uint32_t)dir.smax + 8 * kWave * nsl;
+        uint8_t *pk = w.at<uint8_t>(dir.stream_off + 16 * (size_t)tick_tab[4 * s]);
+        uint32_t *desc = (uint32_t *)pk;
+        uint32_t *rec = (uint32_t *)(pk + 16 * (size_t)dir.smax);         // nsl*64 x {v, c}
+        const uint32_t ent_start = 16 * (uint32_t)dir.smax + 8 * kWave * nsl;
         uint32_t *ent = (uint32_t *)(pk + ent_start);
         uint32_t ebase = 0;                                               // in entries
         for (uint32_t j = 0; j < nsl; ++j) {
@@ -184,10 +222,11 @@ bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int6
             int32_t v0 = order[p0];
             int sh = lanes_per_row_log2(rows);
             int32_t lpr = 1 << sh;
-            uint32_t width = (uint32_t)((csr.ptr[v0 + 1] - csr.ptr[v0] + lpr - 1) >> sh);
+            uint64_t width = (uint64_t)((csr.ptr[v0 + 1] - csr.ptr[v0] + lpr - 1) >> sh);
+            if (width >= 65536) return false;
             desc[4 * j] = ent_start + (uint32_t)esz * ebase;
-            desc[4 * j + 1] = width | ((uint32_t)sh << 24);
-            desc[4 * j + 2] = (uint32_t)rows;
+            desc[4 * j + 1] = (uint32_t)width | ((uint32_t)rows << 16) | ((uint32_t)sh << 24);
+            desc[4 * j + 2] = tick_tab[4 * s + 2];
             desc[4 * j + 3] = (uint32_t)(p0 % dir.slots);
             for (int32_t r = 0; r < kWave; ++r) {       // records: one per row
                 uint32_t *rc = rec + 2 * ((size_t)j * kWave + r);
@@ -196,8 +235,8 @@ bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int6
                     rc[0] = (uint32_t)v;
                     rc[1] = (uint32_t)c[v];
                     gmap[(size_t)s * dir.wpad + (size_t)j * kWave + r] = v;
-                } else {
-                    rc[0] = 0xffffffffu;
+                } else {                                // padding row: never published
+                    rc[0] = tick_tab[4 * s + 2];
                     rc[1] = 0;
                 }
             }
@@ -205,7 +244,7 @@ bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int6
                 int32_t r = l >> sh, sub = l & (lpr - 1);
                 int32_t v = r < rows ? order[p0 + r] : -1;
                 int32_t d = v >= 0 ? csr.ptr[v + 1] - csr.ptr[v] : 0;
-                for (uint32_t jj = 0; jj < width; ++jj) {
+                for (uint32_t jj = 0; jj < (uint32_t)width; ++jj) {
                     const size_t at = (size_t)ebase + (size_t)jj * kWave + l;
                     int64_t ei = (int64_t)jj * lpr + sub;
                     uint32_t field = pad_field, te = 0;    // padding: the constant-zero slot
@@ -223,13 +262,7 @@ bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int6
                     }
                 }
             }
-            ebase += width * kWave;
-        }
-        // the previous packet also carries these descriptors, so that a wavefront can
-        // address this level's entries one level ahead
-        if (s > 0) {
-            uint8_t *prev = w.at<uint8_t>(dir.stream_off + 16 * (size_t)pkt_off[s - 1]);
-            std::memcpy(prev + 16 * (size_t)dir.smax, pk, 16 * (size_t)dir.smax);
+            ebase += (uint32_t)width * kWave;
         }
     }
     return true;

@@ -287,14 +287,18 @@ __global__ __launch_bounds__(256) void gather_assign_kernel(const int32_t *__res
 }
 
 struct WindowArgs {
-    const uint4 *stream;       // level packets
-    const uint32_t *pkt_off;   // [L+1] first chunk of each packet
-    const uint8_t *pperm;      // [P][L*wpad] device ids in sweep order
+    const uint4 *stream;       // tick packets
+    const uint32_t *tick_tab;  // [L+1][4] {first chunk, chunks, lowest vertex id, id span} per tick
+    const uint8_t *ids;        // direct: the caller's assignments[P][n]; else [P][L*wpad] ids in sweep order
+    int64_t ids_row;           // bytes from one partition's row of `ids` to the next
     void *out;                 // [n][P] ticks, or NULL
     int64_t *cp_out;           // [P] or NULL: receives the maximum of b over the partition
     const Magic *edge_tab;
     const Magic *vert_tab;
-    int32_t P, L, k, slots, wpad, smax;
+    int32_t P, L, k, slots, wpad, smax;   // L counts ticks
+    int32_t idpad;             // bytes of a stage slot set aside for device ids
+    int32_t direct;            // 1: ids are staged straight from the caller's rows
+    int32_t *status;
     int32_t nc, nlw;           // compute and loader wavefronts per workgroup
     int32_t pgroups;           // partitions per XCD-sized group (blockIdx -> partition map)
     int32_t out32;             // 1 if every output index fits 32 bits
@@ -353,34 +357,47 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
     }
 
     const int Lpad = (L + DR - 1) / DR * DR;
-    const int wp16 = a.wpad / 16;
+    const int id16 = a.idpad / 16;               // 16-byte chunks of a slot that hold device ids
     Tick best = 0;
 
     if (wave >= a.nc) {
         // ------------------------------------------------ loader wavefronts
         const int lw = wave - a.nc;
-        const_u32_ptr pkt_off = (const_u32_ptr)a.pkt_off;
+        const_u32_ptr tick_tab = (const_u32_ptr)a.tick_tab;
         // chunk ids of this lane are fixed; whether one is a device-id chunk (the first
-        // wp16 of a slot) or a packet chunk is therefore fixed too
+        // id16 of a slot) or a packet chunk is therefore fixed too
         int cid[NL];
         const uint4 *base[NL];
         bool is_id[NL];
+        const uint8_t *row = a.ids + (size_t)q * a.ids_row;
+        // direct staging starts at the 16-byte boundary below the tick's lowest id
+        const uint32_t row_mis = (uint32_t)((uintptr_t)row & 15);
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             cid[i] = (i * a.nlw + lw) * 64 + lane;
-            is_id[i] = cid[i] < wp16;
-            base[i] = is_id[i] ? (const uint4 *)(a.pperm + (size_t)q * L * a.wpad) : a.stream;
+            is_id[i] = cid[i] < id16;
+            base[i] = is_id[i] ? (const uint4 *)(row - row_mis) : a.stream;
         }
         u32x4 buf[DR][NL];
-        // every lane always loads: chunks past the packet's end re-read its last chunk
+        // every lane always loads: chunks past the end of the ids or of the packet re-read
+        // the last chunk of that part
 #define CP_ISSUE(R_, S_)                                                                        \
     do {                                                                                        \
         const int s_ = min((S_), L - 1);                                                        \
-        const uint32_t o0_ = pkt_off[s_], o1_ = pkt_off[s_ + 1];                                \
-        const int last_ = wp16 + (int)(o1_ - o0_) - 1;                                          \
-        const int off_id_ = s_ * wp16, off_pk_ = (int)o0_ - wp16;                               \
+        const u32x4 tt_ = *(const u32x4 __attribute__((address_space(4))) *)(tick_tab + 4 * s_); \
+        const uint32_t o0_ = tt_.x, oc_ = tt_.y, lo_ = tt_.z, span_ = tt_.w;                    \
+        int id_first_, id_last_;                                                                \
+        if (a.direct) {                                                                         \
+            id_first_ = (int)((row_mis + lo_) >> 4);                                            \
+            id_last_ = (int)((row_mis + lo_ + span_ - 1) >> 4) - id_first_;                     \
+        } else {                                                                                \
+            id_first_ = s_ * (a.wpad / 16);                                                     \
+            id_last_ = a.wpad / 16 - 1;                                                         \
+        }                                                                                       \
+        const int pk_last_ = id16 + (int)oc_ - 1, off_pk_ = (int)o0_ - id16;                    \
         _Pragma("unroll") for (int i_ = 0; i_ < NL; ++i_) {                                     \
-            const int c_ = min(cid[i_], last_) + (is_id[i_] ? off_id_ : off_pk_);               \
+            const int c_ = is_id[i_] ? min(cid[i_], id_last_) + id_first_                       \
+                                     : min(cid[i_], pk_last_) + off_pk_;                        \
             buf[R_][i_] = *(const u32x4 *)(base[i_] + c_);                                      \
         }                                                                                       \
     } while (0)
@@ -412,7 +429,9 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
         Tick *out = a.out ? (Tick *)a.out + q : nullptr;
         const uint32_t P = (uint32_t)a.P;
         const uint32_t k8 = 8u * (uint32_t)k;
-        const uint32_t rec_off = (uint32_t)a.wpad + 32u * (uint32_t)a.smax;
+        const uint32_t rec_off = (uint32_t)a.idpad + 16u * (uint32_t)a.smax;   // records, from the slot base
+        const uint32_t row_mis = (uint32_t)((uintptr_t)(a.ids + (size_t)q * a.ids_row) & 15);
+        uint32_t worst = 0;                  // largest device id seen
 
         auto ent_field = [](Ent e) -> uint32_t {
             if constexpr (ENT4) return e & 0xffffu; else return e.x;
@@ -463,18 +482,26 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
         };
         // one slice of the current level out of its stage slot
         auto slice_direct = [&](const uint8_t *st, int j) {
-            const uint4 d = ((const uint4 *)(st + a.wpad))[j];
-            const uint32_t ent_off = __builtin_amdgcn_readfirstlane((int)d.x);
-            const int width = __builtin_amdgcn_readfirstlane((int)(d.y & 0xffffffu));
+            // the descriptor is the same for all lanes; only what steers control flow
+            // (width, lanes per row) is moved to scalars, the rest stays in vector registers
+            const uint4 d = ((const uint4 *)(st + a.idpad))[j];
+            const uint32_t ent_off = d.x;
+            const int width = __builtin_amdgcn_readfirstlane((int)(d.y & 0xffffu));
             const int lsh = __builtin_amdgcn_readfirstlane((int)(d.y >> 24));
-            const int rows = __builtin_amdgcn_readfirstlane((int)d.z);
-            const int rbase = __builtin_amdgcn_readfirstlane((int)d.w);
-            if (rows == 0) return;
+            const int rows = (int)((d.y >> 16) & 0xffu);
+            const uint32_t lo = d.z;
+            const int rbase = (int)d.w;
+            if (width == 0 && lsh == 0 && __builtin_amdgcn_readfirstlane(rows) == 0) return;
             const int p = j * 64 + (lane >> lsh);
             const uint2 rc = ((const uint2 *)(st + rec_off))[p];
-            const uint32_t pv = st[p];
+            // device id: position p of the gathered row, or byte (v - lo) of the staged id
+            // range (padding rows carry v = lo, so every lane reads a byte that was staged)
+            const uint32_t idx = a.direct ? rc.x - lo + ((row_mis + lo) & 15u) : (uint32_t)p;
+            uint32_t pv = st[idx];
+            worst = max(worst, pv);              // checked against k once, after the sweep
+            pv = min(pv, (uint32_t)(k - 1));
             const uint32_t erow = etab_off + pv * k8;
-            const Ent *ent = (const Ent *)(st + a.wpad + ent_off) + lane;
+            const Ent *ent = (const Ent *)(st + a.idpad + ent_off) + lane;
             Tick acc = 0;
             // N relaxations as one straight-line block: N entry reads, N ring reads, N
             // cost-table reads, then the arithmetic -- three LDS round trips whatever N is
@@ -515,6 +542,7 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
             const uint8_t *st = stage + (size_t)(t & 1) * slot_bytes;
             for (int j = wave; j < a.smax; j += a.nc) slice_direct(st, j);
         }
+        if (worst >= (uint32_t)k) *a.status = CP_STATUS_BAD_DEVICE_ID;
     }
 
     if (a.cp_out) {   // workgroup maximum
@@ -581,13 +609,17 @@ int launch_window_sweep_k(const SweepLaunch &s, const WindowCfg &cfg, hipStream_
     const WindowDir &dir = *s.win;
     WindowArgs a{};
     a.stream = (const uint4 *)(s.blob + dir.stream_off);
-    a.pkt_off = (const uint32_t *)(s.blob + dir.pkt_off);
-    a.pperm = s.pperm;
+    a.tick_tab = (const uint32_t *)(s.blob + dir.tick_off);
+    a.direct = s.direct_ids ? 1 : 0;
+    a.ids = s.direct_ids ? s.assign : s.pperm;
+    a.ids_row = s.direct_ids ? s.a_stride_p : (int64_t)dir.ticks * dir.wpad;
+    a.idpad = dir.idpad;
+    a.status = s.status;
     a.out = s.val;
     a.cp_out = s.cp_out;
     a.edge_tab = (const Magic *)s.edge_tab;
     a.vert_tab = (const Magic *)s.vert_tab;
-    a.P = s.P; a.L = s.L; a.k = s.k; a.slots = dir.slots; a.wpad = dir.wpad; a.smax = dir.smax;
+    a.P = s.P; a.L = dir.ticks; a.k = s.k; a.slots = dir.slots; a.wpad = dir.wpad; a.smax = dir.smax;
     a.nc = cfg.nc; a.nlw = cfg.nlw;
     a.out32 = s.n < (1 << 24) && s.P < (1 << 24) && (uint64_t)s.n * (uint64_t)s.P < (1ull << 31);
     a.pgroups = (s.P + 7) / 8;
@@ -632,7 +664,7 @@ int launch_window_sweep_d(const SweepLaunch &s, const WindowCfg &cfg, hipStream_
 
 bool window_config(const WindowDir &d, int32_t k, size_t tick_bytes, size_t lds_limit, WindowCfg &out) {
     if (d.packed && tick_bytes != 4) return false;
-    const int64_t need = d.wpad / 16 + (int64_t)d.max_chunks;     // 16-byte chunks per stage slot
+    const int64_t need = d.idpad / 16 + (int64_t)d.max_chunks;    // 16-byte chunks per stage slot
     const size_t tab = (sizeof(Magic) * ((size_t)k * k + k) + 15) & ~(size_t)15;
     const size_t ring = (((size_t)d.slots + 1) * (d.packed ? 8 : tick_bytes + 1) + 15) & ~(size_t)15;
     static const int kNl[4] = {1, 2, 4, 8};
@@ -652,7 +684,7 @@ bool window_config(const WindowDir &d, int32_t k, size_t tick_bytes, size_t lds_
 
 int launch_gather_assign(const SweepLaunch &s, uint8_t *out, void *stream) {
     const WindowDir &dir = *s.win;
-    const int64_t row_len = (int64_t)s.L * dir.wpad;
+    const int64_t row_len = (int64_t)dir.ticks * dir.wpad;
     const int64_t chunks = (row_len + 4095) / 4096;
     if (chunks > 65535) return CP_ERR_SIZE;
     hipLaunchKernelGGL(gather_assign_kernel, dim3((unsigned)s.P, (unsigned)chunks), dim3(256), 0,

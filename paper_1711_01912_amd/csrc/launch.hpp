@@ -19,7 +19,8 @@ struct SweepLaunch {
     int32_t n = 0, P = 0, k = 0, L = 0, max_width = 0;
     const uint8_t *pT = nullptr;        // [n][P] device ids (wave-column)
     const uint8_t *assign = nullptr;    // caller's assignments (resident-window: input of the gather)
-    const uint8_t *pperm = nullptr;     // [P][L*wpad] device ids in sweep order (resident-window)
+    const uint8_t *pperm = nullptr;     // [P][ticks*wpad] device ids in sweep order (resident-window)
+    bool direct_ids = false;            // resident-window: stage ids straight from `assign`
     int64_t a_stride_p = 0, a_stride_v = 0;
     void *val = nullptr;                // [n][P] ticks
     int64_t *cp_out = nullptr;          // resident-window b sweep only
