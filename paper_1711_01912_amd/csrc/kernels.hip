@@ -452,6 +452,7 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
         };
         // fold the lanes of a row; afterwards the row's first lane holds the row's maximum
         auto fold = [&](Tick acc, int lsh) -> Tick {
+            if (lsh == 0) return acc;
             if (lsh >= 1) acc = max(acc, __shfl_xor(acc, 1));
             if (lsh >= 2) acc = max(acc, __shfl_xor(acc, 2));
             if (lsh >= 3) acc = max(acc, __shfl_xor(acc, 4));
@@ -463,7 +464,8 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
         // the row's first lane publishes the vertex: ring, output, running maximum
         auto publish = [&](Tick acc, Tick w, int lsh, int rows, int rbase, uint32_t v, uint32_t pv) {
             const int row = lane >> lsh;
-            if (row < rows && (lane & ((1 << lsh) - 1)) == 0) {
+            const bool first = lsh == 0 || (lane & ((1 << lsh) - 1)) == 0;
+            if (row < rows && first) {
                 const Tick fin = acc + w;            // b(v), or tl(v) + w(v)
                 int rs = rbase + row;
                 if (rs >= R) rs -= R;
@@ -500,7 +502,7 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
             uint32_t pv = st[idx];
             worst = max(worst, pv);              // checked against k once, after the sweep
             pv = min(pv, (uint32_t)(k - 1));
-            const uint32_t erow = etab_off + pv * k8;
+            const uint32_t erow = etab_off + __umul24(pv, k8);
             const Ent *ent = (const Ent *)(st + a.idpad + ent_off) + lane;
             Tick acc = 0;
             // N relaxations as one straight-line block: N entry reads, N ring reads, N
