@@ -43,6 +43,9 @@ def main():
     ap.add_argument("--plan", type=int, default=0, help="0 auto, 1 wave-column, 2 resident-window")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
     ap.add_argument("--cpu-sample", type=int, default=32, help="partitions the oracle is timed on (0 = skip)")
+    ap.add_argument("--calibrate-copy-mib", type=int, default=0,
+                    help="also run a plain device copy of this many MiB (a known-size kernel to scale "
+                         "hardware byte counters against)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the path has no multi-GPU part; run with --gpus 1", file=sys.stderr)
@@ -82,6 +85,13 @@ def main():
         cpe.cp_eval(g, a, w.speeds, w.bandwidth, out=out, workspace=ws, plan=args.plan,
                     profile=profile, check_status=False)
 
+    if args.calibrate_copy_mib > 0:
+        src = torch.empty(args.calibrate_copy_mib << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

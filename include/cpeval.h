@@ -94,7 +94,7 @@ typedef struct cp_graph_info {
     int32_t window_slots_t;      /* ... and the t-level sweep */
     int32_t window_packet_bytes_b;   /* largest per-level packet of that plan, b-level sweep */
     int32_t window_packet_bytes_t;   /* ... and t-level sweep */
-    int32_t auto_plan;           /* plan CP_PLAN_AUTO resolves to */
+    int32_t auto_plan;           /* plan CP_PLAN_AUTO resolves to for a batch of 256 (the choice is made per call) */
     int32_t uploaded;            /* 1 after cp_graph_upload */
     uint64_t blob_bytes;
 } cp_graph_info;

@@ -2,6 +2,7 @@
 // cost-table upload and the order in which the stages are enqueued.
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -84,11 +85,29 @@ size_t device_window_lds_limit() {
     return lim > 256 ? lim - 256 : 0;
 }
 
-// The resident-window plan pays the graph stream once per partition and wins when
-// levels are narrow and many; wide levels and hub rows go to the wave-column plan.
-bool window_preferred(const Packed &p) {
-    return p.info.max_level_width <= 2048 && p.info.max_out_degree < kHubDegree &&
-           p.info.max_in_degree < kHubDegree;
+// Which plan is cheaper for this batch, from measured unit costs on MI355X: the
+// resident-window plan walks every tick once per partition, 256 compute units times
+// as many workgroups as fit one unit's LDS at a time (about 0.6 us per tick plus
+// 0.045 us per slice); the wave-column plan pays about 6.3 us per level launch plus
+// its gathers at about 4 TB/s.
+bool window_preferred(const Packed &p, const WindowCfg &cb, const WindowCfg &ct, int32_t batch,
+                      size_t tick_bytes) {
+    const double cus = 256.0;
+    auto sweep_us = [&](const WindowDir &d, const WindowCfg &c) {
+        const double per_cu = std::max<double>(1.0, std::min<double>(
+            (double)(kLdsBudget / std::max<size_t>(c.lds_bytes, 1)), 32.0 / (c.nc + c.nlw)));
+        const double rounds = std::ceil((double)batch / (cus * std::floor(per_cu)));
+        return rounds * (double)d.ticks * (0.6 + 0.045 * d.smax);
+    };
+    const double window_us = sweep_us(p.win_b, cb) + sweep_us(p.win_t, ct);
+    auto column_us = [&](const ColumnDir &d) {
+        double launches = 0;
+        for (size_t l = 0; l < d.lvl_count.size(); ++l)
+            launches += (d.lvl_hubs[l] > 0) + (d.lvl_count[l] > d.lvl_hubs[l]);
+        const double bytes = ((double)p.n + (double)p.m) * batch * (1.0 + (double)tick_bytes);
+        return launches * 6.3 + bytes / 4.0e6;
+    };
+    return window_us <= column_us(p.col_b) + column_us(p.col_t);
 }
 
 size_t tables_bytes(int32_t k) { return align_up(table_entries(k) * 8); }
@@ -128,9 +147,11 @@ int cp_graph_create(int32_t n, int64_t m, int32_t L,
         return rc;
     }
     cp_graph_info &info = g->packed.info;
-    info.window_ok = window_fits(g->packed, 1, (size_t)info.min_tick_bytes) ? 1 : 0;
-    info.auto_plan = info.window_ok && window_preferred(g->packed) ? CP_PLAN_RESIDENT_WINDOW
-                                                                   : CP_PLAN_WAVE_COLUMN;
+    WindowCfg cb, ct;
+    info.window_ok = window_fits(g->packed, 1, (size_t)info.min_tick_bytes, kWindowLdsLimit, &cb, &ct) ? 1 : 0;
+    // the choice is made per call (it depends on the batch); this is the one for 256 partitions
+    info.auto_plan = info.window_ok && window_preferred(g->packed, cb, ct, 256, (size_t)info.min_tick_bytes)
+                         ? CP_PLAN_RESIDENT_WINDOW : CP_PLAN_WAVE_COLUMN;
     *out = g;
     return CP_OK;
 }
@@ -207,7 +228,8 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
                                                          device_window_lds_limit(), &cfg_b, &cfg_t);
     int use = plan;
     if (plan == CP_PLAN_AUTO)
-        use = can_window && window_preferred(p) ? CP_PLAN_RESIDENT_WINDOW : CP_PLAN_WAVE_COLUMN;
+        use = can_window && window_preferred(p, cfg_b, cfg_t, batch, (size_t)tick_dtype)
+                  ? CP_PLAN_RESIDENT_WINDOW : CP_PLAN_WAVE_COLUMN;
     if (use == CP_PLAN_RESIDENT_WINDOW && !can_window) return CP_ERR_ARG;
 
     // workspace
