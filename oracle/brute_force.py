@@ -64,3 +64,30 @@ def evaluate(n, edges, c, speeds, bandwidth, p, max_paths=2_000_000):
         tl[last] = max(tl[last], cost - _w(c, speeds, p, last))
         cp = max(cp, cost)
     return cp, b, tl
+
+
+def critical_paths(n, edges, c, speeds, bandwidth, p):
+    """Every source-to-sink path whose cost equals the largest path cost, as lists
+    of vertices (explicit enumeration)."""
+    has_pred = [False] * n
+    has_succ = [False] * n
+    for (u, v, _t) in edges:
+        has_pred[v] = True
+        has_succ[u] = True
+    best, found = -1, []
+    for path in all_paths(n, edges):
+        first, last = path[0][0], path[-1][0]
+        if has_pred[first] or has_succ[last]:
+            continue
+        cost = 0
+        for (v, ei) in path:
+            if ei is not None:
+                u_, v_, t_ = edges[ei]
+                cost += _x(t_, bandwidth, p, u_, v_)
+            cost += _w(c, speeds, p, v)
+        verts = [v for (v, _e) in path]
+        if cost > best:
+            best, found = cost, [verts]
+        elif cost == best:
+            found.append(verts)
+    return best, found

@@ -176,3 +176,58 @@ int cp_oracle_eval(int32_t n, const int32_t *succ_ptr, const int32_t *succ_idx,
     if (threads_used) *threads_used = used;
     return failed ? -2 : 0;
 }
+
+
+/*
+ * One critical path per partition (paper, section 3.2.2: "compute the critical
+ * path"; the paper walks back from the best sink and leaves ties open).  Reading
+ * taken here: among all source-to-sink paths whose cost equals CP, the one whose
+ * vertex sequence is lexicographically smallest.  It starts at the lowest-numbered
+ * vertex without predecessors whose b equals CP and always moves to the
+ * lowest-numbered successor u of v with b(v) = w(v) + x(v->u) + b(u); such a
+ * successor exists for every vertex that has successors, so the walk ends at a sink.
+ *
+ * path_out is [P][max_len] (unused tail = -1), len_out [P].  Returns 0; -1 cycle;
+ * -2 out of memory; -3 bad argument; -4 a path longer than max_len.
+ */
+int cp_oracle_critical_path(int32_t n, const int32_t *succ_ptr, const int32_t *succ_idx,
+                            const int64_t *succ_t, const int64_t *c, int k, const int64_t *speeds,
+                            const int64_t *bandwidth, int32_t P, const uint8_t *assignments,
+                            int32_t max_len, int32_t *path_out, int32_t *len_out)
+{
+    int64_t *cp = (int64_t *)malloc(((size_t)P + 1) * sizeof(int64_t));
+    int64_t *b = (int64_t *)malloc(((size_t)P * n + 1) * sizeof(int64_t));
+    uint8_t *has_pred = (uint8_t *)calloc((size_t)n + 1, 1);
+    if (!cp || !b || !has_pred) { free(cp); free(b); free(has_pred); return -2; }
+    int rc = cp_oracle_eval(n, succ_ptr, succ_idx, succ_t, c, k, speeds, bandwidth, P, assignments,
+                            cp, b, NULL, NULL, 1, NULL);
+    if (rc) { free(cp); free(b); free(has_pred); return rc; }
+    for (int32_t v = 0; v < n; ++v)
+        for (int32_t e = succ_ptr[v]; e < succ_ptr[v + 1]; ++e) has_pred[succ_idx[e]] = 1;
+    for (int32_t j = 0; j < P && rc == 0; ++j) {
+        const uint8_t *p = assignments + (size_t)j * n;
+        const int64_t *bj = b + (size_t)j * n;
+        int32_t *path = path_out + (size_t)j * max_len;
+        for (int32_t i = 0; i < max_len; ++i) path[i] = -1;
+        int32_t v = -1;
+        for (int32_t u = 0; u < n; ++u)
+            if (!has_pred[u] && bj[u] == cp[j]) { v = u; break; }
+        int32_t len = 0;
+        while (v >= 0) {
+            if (len >= max_len) { rc = -4; break; }
+            path[len++] = v;
+            int64_t rest = bj[v] - cp_oracle_vertex_cost(c[v], speeds[p[v]]);
+            int32_t next = -1;
+            for (int32_t e = succ_ptr[v]; e < succ_ptr[v + 1]; ++e) {
+                int32_t u = succ_idx[e];
+                if (cp_oracle_edge_cost(succ_t[e], p[v], p[u], bandwidth, k) + bj[u] == rest &&
+                    (next < 0 || u < next))
+                    next = u;
+            }
+            v = next;
+        }
+        len_out[j] = len;
+    }
+    free(cp); free(b); free(has_pred);
+    return rc;
+}

@@ -30,6 +30,9 @@ def _load():
         lib.cp_oracle_eval.argtypes = [C.c_int32, i32p, i32p, i64p, i64p, C.c_int, i64p, i64p,
                                        C.c_int32, u8p, i64p, i64p, i64p, u8p, C.c_int,
                                        C.POINTER(C.c_int)]
+        lib.cp_oracle_critical_path.restype = C.c_int
+        lib.cp_oracle_critical_path.argtypes = [C.c_int32, i32p, i32p, i64p, i64p, C.c_int, i64p, i64p,
+                                                C.c_int32, u8p, C.c_int32, i32p, i32p]
         _lib = lib
     return _lib
 
@@ -117,3 +120,30 @@ def evaluate_workload(w, want=("cp", "b", "tl", "mask"), threads=1, partitions=N
     a = w.assignments if partitions is None else w.assignments[partitions]
     return evaluate(w.n, w.succ_ptr, w.succ_idx, w.succ_t, w.c, w.speeds, w.bandwidth, a,
                     want=want, threads=threads)
+
+
+def critical_path(n, succ_ptr, succ_idx, succ_t, c, speeds, bandwidth, assignments, max_len):
+    """One critical path per row of ``assignments``: the lexicographically smallest
+    source-to-sink vertex sequence of cost CP.  Returns (paths int32 [P][max_len]
+    padded with -1, lengths int32 [P])."""
+    lib = _load()
+    sp = np.ascontiguousarray(succ_ptr, dtype=np.int32)
+    si = np.ascontiguousarray(succ_idx, dtype=np.int32)
+    st = np.ascontiguousarray(succ_t, dtype=np.int64)
+    if si.size == 0:
+        si = np.zeros(1, dtype=np.int32)
+        st = np.zeros(1, dtype=np.int64)
+    cc = np.ascontiguousarray(c, dtype=np.int64)
+    s = np.ascontiguousarray(speeds, dtype=np.int64)
+    bw = np.ascontiguousarray(bandwidth, dtype=np.int64)
+    a = np.ascontiguousarray(assignments, dtype=np.uint8)
+    P = int(a.shape[0])
+    paths = np.full((P, max_len), -1, dtype=np.int32)
+    lens = np.zeros(P, dtype=np.int32)
+    rc = lib.cp_oracle_critical_path(n, _ptr(sp, C.c_int32), _ptr(si, C.c_int32), _ptr(st, C.c_int64),
+                                     _ptr(cc, C.c_int64), int(s.shape[0]), _ptr(s, C.c_int64),
+                                     _ptr(bw, C.c_int64), P, _ptr(a, C.c_uint8), int(max_len),
+                                     _ptr(paths, C.c_int32), _ptr(lens, C.c_int32))
+    if rc:
+        raise ValueError(f"critical_path failed with code {rc}")
+    return paths, lens

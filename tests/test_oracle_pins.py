@@ -461,3 +461,44 @@ def test_rejects_cycles_and_bad_ids(oracle):
     ok = build_csr(2, [0], [1], [1])
     with pytest.raises(ValueError):
         _eval(oracle, ok, np.array([1, 1]), np.array([1]), np.array([[1]]), [[0, 1]])
+
+
+# ----------------------------------------------------------------- one critical path
+
+@pytest.mark.parametrize("seed", range(6))
+def test_critical_path_is_the_lexicographically_smallest_one(oracle, seed):
+    """Brute force lists every source-to-sink path of maximal cost; the oracle must
+    return the smallest vertex sequence among them (small weights force ties)."""
+    rng = np.random.default_rng(200 + seed)
+    n, level, src, dst = random_layered_dag(rng, [3] * 5, 1, 3, 2)
+    t = rng.integers(0, 3, size=len(src))
+    c = rng.integers(1, 3, size=n)
+    csr = build_csr(n, src, dst, t, level)
+    s = np.array([1, 2])
+    B = np.array([[1, 2], [1, 1]])
+    parts = rng.integers(0, 2, size=(10, n), dtype=np.uint8)
+    paths, lens = oracle.critical_path(n, csr["succ_ptr"], csr["succ_idx"], csr["succ_t"], c, s, B,
+                                       parts, max_len=csr["L"])
+    got = _eval(oracle, csr, c, s, B, parts)
+    edges = _edges(csr)
+    ties = 0
+    for j, p in enumerate(parts):
+        best, found = brute_force.critical_paths(n, edges, c, s, B, p)
+        assert best == got["cp"][j]
+        ties += len(found) > 1
+        assert paths[j, :lens[j]].tolist() == min(found)
+        assert (paths[j, lens[j]:] == -1).all()
+        assert got["mask"][j][paths[j, :lens[j]]].all()      # every vertex of it is critical
+    assert ties > 0
+
+
+def test_critical_path_of_a_chain_and_of_an_antichain(oracle):
+    csr = _chain(6, [1, 2, 3, 4, 5])
+    paths, lens = oracle.critical_path(6, csr["succ_ptr"], csr["succ_idx"], csr["succ_t"], np.ones(6),
+                                       np.array([1]), np.array([[1]]), np.zeros((1, 6), dtype=np.uint8), 6)
+    assert lens[0] == 6 and paths[0].tolist() == [0, 1, 2, 3, 4, 5]
+    csr = build_csr(4, [], [], [])
+    paths, lens = oracle.critical_path(4, csr["succ_ptr"], csr["succ_idx"], csr["succ_t"],
+                                       np.array([3, 9, 9, 1]), np.array([1]), np.array([[1]]),
+                                       np.zeros((1, 4), dtype=np.uint8), 2)
+    assert lens[0] == 1 and paths[0].tolist() == [1, -1]     # lowest id among the costliest
