@@ -173,6 +173,32 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
             int tick_dtype, int plan, int32_t *status_out, cp_profile *profile);
 
 /*
+ * One critical path per partition (paper, section 3.2.2 "compute the critical path";
+ * the paper leaves ties open).  Among all source-to-sink paths whose cost equals CP the
+ * one with the lexicographically smallest vertex sequence is returned: it starts at the
+ * lowest-numbered vertex without predecessors whose b-level equals CP and always moves
+ * to the lowest-numbered successor u of v with b(v) = w(v) + x(v->u) + b(u).
+ * Only enqueues work on `stream`.
+ *
+ *   assignments, assign_layout, speeds, bandwidth   as for cp_eval (same values as the
+ *                 call that produced blevel and cp)
+ *   blevel        device ticks [n][batch], cp device int64 [batch]: outputs of cp_eval
+ *   workspace     device, 256-byte aligned, >= cp_eval_workspace_bytes for this batch and k
+ *   max_len       row length of path_out, >= the graph's number of levels L
+ *   path_out      device int32 [batch][max_len]; unused tail = -1
+ *   len_out       device int32 [batch]: vertices on the path
+ *   status_out    device int32, as for cp_eval
+ * Errors: CP_ERR_NULL, CP_ERR_SIZE (also max_len < L), CP_ERR_ARG, CP_ERR_STATE,
+ * CP_ERR_OVERFLOW, CP_ERR_WORKSPACE, CP_ERR_SPEED, CP_ERR_BANDWIDTH, CP_ERR_HIP.
+ */
+int cp_critical_path(const cp_graph *g, int32_t batch, int32_t k,
+                     const uint8_t *assignments, int assign_layout,
+                     const int64_t *speeds, const int64_t *bandwidth,
+                     const void *blevel, const int64_t *cp, int tick_dtype,
+                     void *workspace, size_t workspace_bytes, void *stream,
+                     int32_t max_len, int32_t *path_out, int32_t *len_out, int32_t *status_out);
+
+/*
  * Stage timing with HIP events recorded on the stream the kernels run on.
  * A profile holds `slots` sets of CP_NUM_STAGES+1 events; every cp_eval call that
  * is given the profile fills the next slot (CP_ERR_STATE when full).

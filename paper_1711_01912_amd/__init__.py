@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     PLAN_RESIDENT_WINDOW,
     PLAN_WAVE_COLUMN,
     cost_magic,
+    cp_critical_path,
     cp_eval,
     error_string,
     load_library,

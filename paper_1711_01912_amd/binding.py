@@ -25,7 +25,7 @@ STATUS_BAD_DEVICE_ID = 1
 
 EXPORTS = (
     "cp_graph_create", "cp_graph_get_info", "cp_graph_upload", "cp_graph_destroy",
-    "cp_eval_workspace_bytes", "cp_eval", "cp_profile_create", "cp_profile_reset",
+    "cp_eval_workspace_bytes", "cp_eval", "cp_critical_path", "cp_profile_create", "cp_profile_reset",
     "cp_profile_count", "cp_profile_read", "cp_profile_destroy", "cp_cost_magic",
     "cp_error_string",
 )
@@ -82,6 +82,9 @@ def load_library():
     lib.cp_eval.restype = C.c_int
     lib.cp_eval.argtypes = [vp, C.c_int32, C.c_int32, vp, C.c_int, i64p, i64p, vp, C.c_size_t, vp,
                             vp, vp, vp, vp, C.c_int, C.c_int, vp, vp]
+    lib.cp_critical_path.restype = C.c_int
+    lib.cp_critical_path.argtypes = [vp, C.c_int32, C.c_int32, vp, C.c_int, i64p, i64p, vp, vp, C.c_int,
+                                     vp, C.c_size_t, vp, C.c_int32, vp, vp, vp]
     lib.cp_profile_create.restype = C.c_int
     lib.cp_profile_create.argtypes = [C.c_int32, C.POINTER(vp)]
     lib.cp_profile_reset.restype = C.c_int
@@ -310,6 +313,41 @@ def cp_eval(graph: CpGraph, assignments, speeds, bandwidth, *, want=("cp", "b", 
         if st == STATUS_BAD_DEVICE_ID:
             raise ValueError("assignments holds a device id >= k")
     return out
+
+
+def cp_critical_path(graph: CpGraph, assignments, speeds, bandwidth, b, cp, *,
+                     assign_layout=ASSIGN_PARTITION_MAJOR, workspace=None, stream=None, check_status=True):
+    """cp_critical_path on torch tensors: ``b`` and ``cp`` are outputs of cp_eval for the
+    same assignments and cost model.  Returns (paths int32 [batch][L] padded with -1,
+    lengths int32 [batch])."""
+    import torch
+    lib = load_library()
+    info = graph.info
+    s = np.ascontiguousarray(speeds, dtype=np.int64)
+    bw = np.ascontiguousarray(bandwidth, dtype=np.int64)
+    k = int(s.shape[0])
+    batch = int(cp.shape[0])
+    dev = assignments.device
+    max_len = info["L"]
+    paths = torch.empty((batch, max_len), dtype=torch.int32, device=dev)
+    lens = torch.empty(batch, dtype=torch.int32, device=dev)
+    status = torch.empty(1, dtype=torch.int32, device=dev)
+    if workspace is None:
+        workspace = torch.empty(workspace_bytes(graph, batch, k, assign_layout), dtype=torch.uint8, device=dev)
+    tick = 4 if b.dtype == torch.int32 else 8
+    rc = lib.cp_critical_path(graph._handle, batch, k, C.c_void_p(assignments.data_ptr()), int(assign_layout),
+                              _np_ptr(s, C.c_int64), _np_ptr(bw, C.c_int64), C.c_void_p(b.data_ptr()),
+                              C.c_void_p(cp.data_ptr()), tick, C.c_void_p(workspace.data_ptr()),
+                              C.c_size_t(workspace.numel()), _stream_ptr(stream), max_len,
+                              C.c_void_p(paths.data_ptr()), C.c_void_p(lens.data_ptr()),
+                              C.c_void_p(status.data_ptr()))
+    if rc:
+        raise CpError(rc, "cp_critical_path")
+    if check_status:
+        torch.cuda.synchronize(dev)
+        if int(status.item()) == STATUS_BAD_DEVICE_ID:
+            raise ValueError("assignments holds a device id >= k")
+    return paths, lens
 
 
 def mask_to_bool(mask_words, batch: int) -> np.ndarray:

@@ -356,6 +356,56 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
     return CP_OK;
 }
 
+int cp_critical_path(const cp_graph *g, int32_t batch, int32_t k,
+                     const uint8_t *assignments, int assign_layout,
+                     const int64_t *speeds, const int64_t *bandwidth,
+                     const void *blevel, const int64_t *cp, int tick_dtype,
+                     void *workspace, size_t workspace_bytes, void *stream,
+                     int32_t max_len, int32_t *path_out, int32_t *len_out, int32_t *status_out) {
+    int rc = check_eval_sizes(g, batch, k, assign_layout, CP_PLAN_AUTO);
+    if (rc) return rc;
+    if (!assignments || !speeds || !bandwidth || !blevel || !cp || !workspace || !path_out || !len_out ||
+        !status_out)
+        return CP_ERR_NULL;
+    if (tick_dtype != CP_TICK_I32 && tick_dtype != CP_TICK_I64) return CP_ERR_ARG;
+    if (!g->device_blob) return CP_ERR_STATE;
+    const Packed &p = g->packed;
+    if (tick_dtype == CP_TICK_I32 && p.info.min_tick_bytes > 4) return CP_ERR_OVERFLOW;
+    if (max_len < p.L) return CP_ERR_SIZE;      // a path has at most one vertex per level
+    if (((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < tables_bytes(k)) return CP_ERR_WORKSPACE;
+    CostTables tabs;
+    try {
+        rc = build_cost_tables(k, speeds, bandwidth, p.narrow, p.info.max_c, p.info.max_t, tabs);
+    } catch (const std::bad_alloc &) {
+        rc = CP_ERR_ALLOC;
+    }
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    rc = launch_clear(nullptr, 1, status_out, stream);
+    if (rc) return rc;
+    uint8_t *d_tab = (uint8_t *)workspace;
+    const void *tab_src = tabs.magic_ok ? (const void *)tabs.magic.data() : (const void *)tabs.divisor.data();
+    rc = stage_and_copy(tab_src, table_entries(k) * 8, d_tab, st);
+    if (rc) return rc;
+    SweepLaunch s;
+    s.blob = (const uint8_t *)g->device_blob;
+    s.dir = &p.col_b;
+    s.c_off = p.c_off;
+    s.magic = tabs.magic_ok;
+    s.narrow = p.narrow;
+    s.tick_bytes = tick_dtype;
+    s.n = p.n; s.P = batch; s.k = k; s.L = p.L;
+    s.assign = assignments;
+    if (assign_layout == CP_ASSIGN_PARTITION_MAJOR) { s.a_stride_p = p.n; s.a_stride_v = 1; }
+    else { s.a_stride_p = 1; s.a_stride_v = batch; }
+    s.val = const_cast<void *>(blevel);
+    s.edge_tab = d_tab;
+    s.vert_tab = d_tab + 2 * (size_t)k * k * 8;
+    s.status = status_out;
+    return launch_critical_path(s, (const int32_t *)(s.blob + p.sources_off), p.info.num_sources, cp,
+                                max_len, path_out, len_out, stream);
+}
+
 int cp_profile_create(int32_t slots, cp_profile **out) {
     if (!out) return CP_ERR_NULL;
     *out = nullptr;

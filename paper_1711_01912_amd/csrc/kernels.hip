@@ -238,6 +238,92 @@ __global__ __launch_bounds__(256) void mask_kernel(const Tick *__restrict__ b,
     }
 }
 
+// ---------------------------------------------------------------- one critical path
+
+struct PathArgs {
+    const int32_t *ptr;      // successor CSR over original ids
+    const int32_t *idx;
+    const void *wt;
+    const void *c;
+    const int32_t *sources;
+    int32_t nsrc;
+    const uint8_t *assign;
+    int64_t a_stride_p, a_stride_v;
+    const void *b;           // [n][P] ticks
+    const int64_t *cp;       // [P]
+    const void *edge_tab;    // b-sweep orientation: row = device of the edge's source vertex
+    const void *vert_tab;
+    int32_t *path;           // [P][max_len]
+    int32_t *len;            // [P]
+    int32_t *status;
+    int32_t P, k, max_len;
+};
+
+// One wavefront walks one partition's critical path (section 3.2.2, read as: the
+// lexicographically smallest source-to-sink vertex sequence of cost CP).  It starts at
+// the lowest-numbered source whose b equals CP; from v it moves to the lowest-numbered
+// successor u with b(v) = w(v) + x(v->u) + b(u), lanes across the successors.
+// With LDS_TAB the k*k + k table entries are staged in LDS first (one dependent
+// global load less per step of the walk).
+template <typename Tick, typename WT, bool MAGIC, bool LDS_TAB>
+__global__ __launch_bounds__(64) void critical_path_kernel(PathArgs a) {
+    extern __shared__ __align__(16) uint64_t path_lds[];
+    const int lane = threadIdx.x;
+    const int32_t q = blockIdx.x;
+    const int32_t P = a.P, k = a.k;
+    const Tick *b = (const Tick *)a.b + q;
+    const uint8_t *row = a.assign + (int64_t)q * a.a_stride_p;
+    const WT *wt = (const WT *)a.wt;
+    const WT *cw = (const WT *)a.c;
+    const void *etab = a.edge_tab, *vtab = a.vert_tab;
+    if (LDS_TAB) {
+        const uint64_t *ge = (const uint64_t *)a.edge_tab, *gv = (const uint64_t *)a.vert_tab;
+        for (int i = lane; i < k * k; i += 64) path_lds[i] = ge[i];
+        for (int i = lane; i < k; i += 64) path_lds[k * k + i] = gv[i];
+        __syncthreads();
+        etab = path_lds;
+        vtab = path_lds + k * k;
+    }
+    const Magic *etab_m = (const Magic *)etab, *vtab_m = (const Magic *)vtab;
+    const int64_t *etab_g = (const int64_t *)etab, *vtab_g = (const int64_t *)vtab;
+    int32_t *path = a.path + (int64_t)q * a.max_len;
+    for (int i = lane; i < a.max_len; i += 64) path[i] = -1;
+
+    const long long cpq = a.cp[q];
+    int32_t v = 0x7fffffff;
+    for (int32_t i = lane; i < a.nsrc; i += 64) {
+        const int32_t s = a.sources[i];
+        if ((long long)b[(size_t)s * P] == cpq) v = min(v, s);
+    }
+    for (int off = 32; off > 0; off >>= 1) v = min(v, __shfl_xor(v, off));
+
+    int32_t len = 0;
+    while (v != 0x7fffffff && len < a.max_len) {
+        if (lane == 0) path[len] = v;
+        ++len;
+        uint32_t pv = row[(int64_t)v * a.a_stride_v];
+        if (pv >= (uint32_t)k) { *a.status = CP_STATUS_BAD_DEVICE_ID; pv = 0; }
+        const WT cv = cw[v];
+        const Tick wv = MAGIC ? (Tick)magic_div((uint32_t)cv, vtab_m[pv])
+                              : (Tick)plain_div((uint64_t)cv, (uint64_t)vtab_g[pv]);
+        const Tick rest = b[(size_t)v * P] - wv;
+        const int32_t e0 = a.ptr[v], e1 = a.ptr[v + 1];
+        int32_t next = 0x7fffffff;
+        for (int32_t e = e0 + lane; e < e1; e += 64) {
+            const int32_t u = a.idx[e];
+            uint32_t pu = row[(int64_t)u * a.a_stride_v];
+            pu = min(pu, (uint32_t)(k - 1));
+            const WT te = wt[e];
+            const Tick x = MAGIC ? (Tick)magic_div((uint32_t)te, etab_m[pv * k + pu])
+                                 : (Tick)plain_div((uint64_t)te, (uint64_t)etab_g[pv * k + pu]);
+            if (x + b[(size_t)u * P] == rest) next = min(next, u);
+        }
+        for (int off = 32; off > 0; off >>= 1) next = min(next, __shfl_xor(next, off));
+        v = next;
+    }
+    if (lane == 0) a.len[q] = len;
+}
+
 // ---------------------------------------------------------------- resident-window sweep
 
 // Barrier that orders LDS traffic only: global loads issued by the loader
@@ -741,6 +827,52 @@ int launch_cp_sources(const int32_t *sources, int32_t nsrc, const void *b, int32
     else
         hipLaunchKernelGGL(cp_sources_kernel<int64_t>, grid, dim3(256), 0, (hipStream_t)stream,
                            sources, nsrc, (const int64_t *)b, P, cp_out);
+    return hip_ok(hipGetLastError());
+}
+
+int launch_critical_path(const SweepLaunch &s, const int32_t *sources, int32_t nsrc, const int64_t *cp,
+                         int32_t max_len, int32_t *path, int32_t *len, void *stream) {
+    const ColumnDir &dir = *s.dir;
+    PathArgs a{};
+    a.ptr = (const int32_t *)(s.blob + dir.ptr_off);
+    a.idx = (const int32_t *)(s.blob + dir.idx_off);
+    a.wt = s.blob + dir.wt_off;
+    a.c = s.blob + s.c_off;
+    a.sources = sources;
+    a.nsrc = nsrc;
+    a.assign = s.assign;
+    a.a_stride_p = s.a_stride_p;
+    a.a_stride_v = s.a_stride_v;
+    a.b = s.val;
+    a.cp = cp;
+    a.edge_tab = s.edge_tab;
+    a.vert_tab = s.vert_tab;
+    a.path = path;
+    a.len = len;
+    a.status = s.status;
+    a.P = s.P; a.k = s.k; a.max_len = max_len;
+    hipStream_t st = (hipStream_t)stream;
+    const bool lds_tab = s.k <= kMagicMaxK;
+    const size_t lds = lds_tab ? ((size_t)s.k * s.k + s.k) * 8 : 0;
+#define CP_PATH(TICK, WT, MAGIC)                                                                           \
+    do {                                                                                                   \
+        if (lds_tab)                                                                                       \
+            hipLaunchKernelGGL((critical_path_kernel<TICK, WT, MAGIC, true>), dim3((unsigned)s.P), dim3(64), \
+                               lds, st, a);                                                                \
+        else                                                                                               \
+            hipLaunchKernelGGL((critical_path_kernel<TICK, WT, MAGIC, false>), dim3((unsigned)s.P),        \
+                               dim3(64), 0, st, a);                                                        \
+    } while (0)
+    if (s.tick_bytes == 4) {
+        if (s.magic) CP_PATH(int32_t, uint32_t, true);
+        else if (s.narrow) CP_PATH(int32_t, uint32_t, false);
+        else CP_PATH(int32_t, int64_t, false);
+    } else {
+        if (s.magic) CP_PATH(int64_t, uint32_t, true);
+        else if (s.narrow) CP_PATH(int64_t, uint32_t, false);
+        else CP_PATH(int64_t, int64_t, false);
+    }
+#undef CP_PATH
     return hip_ok(hipGetLastError());
 }
 

@@ -286,3 +286,48 @@ def test_one_column_equals_its_column_in_a_batch(gpu):
         assert np.array_equal(one["b"][:, 0], full["b"][:, 77])
         assert np.array_equal(one["tl"][:, 0], full["tl"][:, 77])
         assert one["cp"][0] == full["cp"][77]
+
+
+# ------------------------------------------------------------------ one critical path per partition
+
+def _check_paths(gpu, oracle, w, layout=0):
+    import torch
+    g = gpu.CpGraph.from_workload(w, device="cuda:0")
+    a_host = w.assignments if layout == 0 else np.ascontiguousarray(w.assignments.T)
+    a = torch.from_numpy(a_host).to("cuda:0")
+    out = gpu.cp_eval(g, a, w.speeds, w.bandwidth, want=("cp", "b"), assign_layout=layout)
+    paths, lens = gpu.cp_critical_path(g, a, w.speeds, w.bandwidth, out["b"], out["cp"], assign_layout=layout)
+    ref_p, ref_l = oracle.critical_path(w.n, w.succ_ptr, w.succ_idx, w.succ_t, w.c, w.speeds, w.bandwidth,
+                                        w.assignments, max_len=w.L)
+    assert np.array_equal(lens.cpu().numpy(), ref_l)
+    assert np.array_equal(paths.cpu().numpy(), ref_p)
+    g.close()
+
+
+def test_critical_path_tiny_and_mlp(gpu, oracle):
+    _check_paths(gpu, oracle, make_workload("tiny"))
+    _check_paths(gpu, oracle, make_workload("tiny"), layout=1)
+    _check_paths(gpu, oracle, make_workload("mlp", P=96))
+
+
+def test_critical_path_with_ties_and_hubs(gpu, oracle):
+    rng = np.random.default_rng(21)
+    n, level, src, dst = random_layered_dag(rng, [6] * 12, 1, 4, 3)
+    w = _custom("ties", n, src, dst, rng.integers(0, 3, size=len(src)), rng.integers(1, 3, size=n),
+                [1, 2], [[1, 2], [1, 1]], rng.integers(0, 2, size=(70, n), dtype=np.uint8), level)
+    _check_paths(gpu, oracle, w)
+    # rows longer than one wavefront
+    _check_paths(gpu, oracle, make_workload("comm_heavy", P=12, levels=5, width=600, hub_degree=300))
+
+
+def test_critical_path_large_sparse_full(gpu, oracle):
+    _check_paths(gpu, oracle, make_workload("large_sparse"))
+
+
+def test_critical_path_64_bit_weights(gpu, oracle):
+    rng = np.random.default_rng(22)
+    n, level, src, dst = random_layered_dag(rng, [8] * 10, 1, 3, 2)
+    w = _custom("wide-path", n, src, dst, rng.integers(1, 2**45, size=len(src)), rng.integers(1, 2**40, size=n),
+                [1, 3, 2**33], rng.integers(1, 2**20, size=(3, 3)), rng.integers(0, 3, size=(20, n), dtype=np.uint8),
+                level)
+    _check_paths(gpu, oracle, w)
