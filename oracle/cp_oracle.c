@@ -231,3 +231,38 @@ int cp_oracle_critical_path(int32_t n, const int32_t *succ_ptr, const int32_t *s
     free(cp); free(b); free(has_pred);
     return rc;
 }
+
+/*
+ * Device-free ranks of section 3.2 (upward rank, downward rank and their sum, the
+ * total rank of section 3.2.1), written out from the two rank equations:
+ *   upRank(v)   = c(v) + max over successors u of upRank(u)      (c(v) alone for a sink)
+ *   downRank(v) = c(v) + max over predecessors u of downRank(u)  (c(v) alone for a source)
+ *   totalRank(v) = upRank(v) + downRank(v)
+ * Both equations add the vertex's own c, so the total counts c(v) twice.
+ * up, down, total are [n].  Returns 0; -1 cycle; -2 out of memory.
+ */
+int cp_oracle_ranks(int32_t n, const int32_t *succ_ptr, const int32_t *succ_idx, const int64_t *c,
+                    int64_t *up, int64_t *down, int64_t *total)
+{
+    int32_t *order = (int32_t *)malloc(((size_t)n + 1) * sizeof(int32_t));
+    if (!order) return -2;
+    int rc = cp_oracle_topo_order(n, succ_ptr, succ_idx, order);
+    if (rc) { free(order); return rc; }
+    for (int32_t i = n - 1; i >= 0; --i) {
+        int32_t v = order[i];
+        int64_t best = 0;
+        for (int32_t e = succ_ptr[v]; e < succ_ptr[v + 1]; ++e)
+            if (up[succ_idx[e]] > best) best = up[succ_idx[e]];
+        up[v] = best + c[v];
+    }
+    for (int32_t v = 0; v < n; ++v) down[v] = 0;
+    for (int32_t i = 0; i < n; ++i) {          /* down[v] holds the best predecessor rank so far */
+        int32_t v = order[i];
+        down[v] += c[v];
+        for (int32_t e = succ_ptr[v]; e < succ_ptr[v + 1]; ++e)
+            if (down[v] > down[succ_idx[e]]) down[succ_idx[e]] = down[v];
+    }
+    for (int32_t v = 0; v < n; ++v) total[v] = up[v] + down[v];
+    free(order);
+    return 0;
+}

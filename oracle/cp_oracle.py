@@ -33,6 +33,8 @@ def _load():
         lib.cp_oracle_critical_path.restype = C.c_int
         lib.cp_oracle_critical_path.argtypes = [C.c_int32, i32p, i32p, i64p, i64p, C.c_int, i64p, i64p,
                                                 C.c_int32, u8p, C.c_int32, i32p, i32p]
+        lib.cp_oracle_ranks.restype = C.c_int
+        lib.cp_oracle_ranks.argtypes = [C.c_int32, i32p, i32p, i64p, i64p, i64p, i64p]
         _lib = lib
     return _lib
 
@@ -147,3 +149,21 @@ def critical_path(n, succ_ptr, succ_idx, succ_t, c, speeds, bandwidth, assignmen
     if rc:
         raise ValueError(f"critical_path failed with code {rc}")
     return paths, lens
+
+
+def ranks(n, succ_ptr, succ_idx, c):
+    """upRank, downRank and totalRank of section 3.2 (each int64 [n])."""
+    lib = _load()
+    sp = np.ascontiguousarray(succ_ptr, dtype=np.int32)
+    si = np.ascontiguousarray(succ_idx, dtype=np.int32)
+    if si.size == 0:
+        si = np.zeros(1, dtype=np.int32)
+    cc = np.ascontiguousarray(c, dtype=np.int64)
+    up = np.zeros(n, dtype=np.int64)
+    down = np.zeros(n, dtype=np.int64)
+    total = np.zeros(n, dtype=np.int64)
+    rc = lib.cp_oracle_ranks(n, _ptr(sp, C.c_int32), _ptr(si, C.c_int32), _ptr(cc, C.c_int64),
+                             _ptr(up, C.c_int64), _ptr(down, C.c_int64), _ptr(total, C.c_int64))
+    if rc:
+        raise ValueError(f"ranks failed with code {rc}")
+    return up, down, total

@@ -502,3 +502,57 @@ def test_critical_path_of_a_chain_and_of_an_antichain(oracle):
                                        np.array([3, 9, 9, 1]), np.array([1]), np.array([[1]]),
                                        np.zeros((1, 4), dtype=np.uint8), 2)
     assert lens[0] == 1 and paths[0].tolist() == [1, -1]     # lowest id among the costliest
+
+
+# ------------------------------------------------------------------ ranks of section 3.2
+
+@pytest.mark.parametrize("seed", range(4))
+def test_ranks_against_path_enumeration(oracle, seed):
+    """upRank(v) is the largest sum of c over a path that starts at v, downRank(v) the
+    largest over a path that ends at v (both count v), by listing every path."""
+    rng = np.random.default_rng(300 + seed)
+    n, level, src, dst = random_layered_dag(rng, [3, 4, 2, 4, 3], 1, 3, 2)
+    c = rng.integers(1, 50, size=n)
+    csr = build_csr(n, src, dst, np.ones(len(src), dtype=np.int64), level)
+    up, down, total = oracle.ranks(n, csr["succ_ptr"], csr["succ_idx"], c)
+    exp_up = [0] * n
+    exp_down = [0] * n
+    for path in brute_force.all_paths(n, _edges(csr)):
+        cost = sum(int(c[v]) for v, _ in path)
+        exp_up[path[0][0]] = max(exp_up[path[0][0]], cost)
+        exp_down[path[-1][0]] = max(exp_down[path[-1][0]], cost)
+    assert up.tolist() == exp_up
+    assert down.tolist() == exp_down
+    assert total.tolist() == [a + b for a, b in zip(exp_up, exp_down)]
+
+
+def test_ranks_closed_forms(oracle):
+    # chain: suffix and prefix sums
+    c = np.array([5, 1, 7, 2, 3])
+    csr = _chain(5, [9, 9, 9, 9])
+    up, down, total = oracle.ranks(5, csr["succ_ptr"], csr["succ_idx"], c)
+    assert up.tolist() == np.cumsum(c[::-1])[::-1].tolist()
+    assert down.tolist() == np.cumsum(c).tolist()
+    assert total.tolist() == (c.sum() + c).tolist()       # every vertex lies on the one path; c counted twice
+    # diamond 0 -> {1, 2} -> 3 with a heavy and a light arm
+    csr = build_csr(4, [0, 0, 1, 2], [1, 2, 3, 3], [1, 1, 1, 1])
+    up, down, total = oracle.ranks(4, csr["succ_ptr"], csr["succ_idx"], np.array([1, 10, 2, 4]))
+    assert up.tolist() == [15, 14, 6, 4]
+    assert down.tolist() == [1, 11, 3, 15]
+    assert total.tolist() == [16, 25, 9, 19]
+    # no edges: both ranks are c
+    csr = build_csr(3, [], [], [])
+    up, down, total = oracle.ranks(3, csr["succ_ptr"], csr["succ_idx"], np.array([4, 0, 9]))
+    assert up.tolist() == [4, 0, 9] and down.tolist() == [4, 0, 9] and total.tolist() == [8, 0, 18]
+
+
+def test_ranks_are_the_one_device_unit_speed_evaluation(oracle):
+    """With one device of speed 1 nothing is transferred and w = c: upRank is the b-level,
+    downRank the t-level plus c (the rank equations add the vertex's own c)."""
+    w = make_workload("mlp", P=1)
+    up, down, total = oracle.ranks(w.n, w.succ_ptr, w.succ_idx, w.c)
+    got = oracle.evaluate(w.n, w.succ_ptr, w.succ_idx, w.succ_t, w.c, np.array([1]), np.array([[1]]),
+                          np.zeros((1, w.n), dtype=np.uint8))
+    assert np.array_equal(up, got["b"][0])
+    assert np.array_equal(down, got["tl"][0] + w.c)
+    assert up.max() == got["cp"][0] == down.max()
