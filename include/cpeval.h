@@ -199,6 +199,22 @@ int cp_critical_path(const cp_graph *g, int32_t batch, int32_t k,
                      int32_t max_len, int32_t *path_out, int32_t *len_out, int32_t *status_out);
 
 /*
+ * The device-free ranks of section 3.2: upRank (equation for the upward rank), downRank
+ * (equation for the downward rank) and totalRank = upRank + downRank (section 3.2.1).
+ * Both rank equations add the vertex's own c, so upRank is the b-level and downRank the
+ * t-level plus c of the evaluation with a single device of speed 1, which is how they
+ * are computed: one cp_eval with batch = 1, k = 1, then one elementwise kernel.
+ * Only enqueues work on `stream`.
+ *
+ *   workspace   device, 256-byte aligned, >= cp_ranks_workspace_bytes
+ *   up_out, down_out, total_out   device int64 [n] each; any may be NULL, not all
+ * Errors: CP_ERR_NULL, CP_ERR_STATE (graph not uploaded), CP_ERR_WORKSPACE, CP_ERR_HIP.
+ */
+int cp_ranks_workspace_bytes(const cp_graph *g, size_t *out_bytes);
+int cp_ranks(const cp_graph *g, void *workspace, size_t workspace_bytes, void *stream,
+             int64_t *up_out, int64_t *down_out, int64_t *total_out);
+
+/*
  * Stage timing with HIP events recorded on the stream the kernels run on.
  * A profile holds `slots` sets of CP_NUM_STAGES+1 events; every cp_eval call that
  * is given the profile fills the next slot (CP_ERR_STATE when full).

@@ -25,7 +25,8 @@ STATUS_BAD_DEVICE_ID = 1
 
 EXPORTS = (
     "cp_graph_create", "cp_graph_get_info", "cp_graph_upload", "cp_graph_destroy",
-    "cp_eval_workspace_bytes", "cp_eval", "cp_critical_path", "cp_profile_create", "cp_profile_reset",
+    "cp_eval_workspace_bytes", "cp_eval", "cp_critical_path", "cp_ranks_workspace_bytes", "cp_ranks",
+    "cp_profile_create", "cp_profile_reset",
     "cp_profile_count", "cp_profile_read", "cp_profile_destroy", "cp_cost_magic",
     "cp_error_string",
 )
@@ -85,6 +86,10 @@ def load_library():
     lib.cp_critical_path.restype = C.c_int
     lib.cp_critical_path.argtypes = [vp, C.c_int32, C.c_int32, vp, C.c_int, i64p, i64p, vp, vp, C.c_int,
                                      vp, C.c_size_t, vp, C.c_int32, vp, vp, vp]
+    lib.cp_ranks_workspace_bytes.restype = C.c_int
+    lib.cp_ranks_workspace_bytes.argtypes = [vp, C.POINTER(C.c_size_t)]
+    lib.cp_ranks.restype = C.c_int
+    lib.cp_ranks.argtypes = [vp, vp, C.c_size_t, vp, vp, vp, vp]
     lib.cp_profile_create.restype = C.c_int
     lib.cp_profile_create.argtypes = [C.c_int32, C.POINTER(vp)]
     lib.cp_profile_reset.restype = C.c_int
@@ -348,6 +353,26 @@ def cp_critical_path(graph: CpGraph, assignments, speeds, bandwidth, b, cp, *,
         if int(status.item()) == STATUS_BAD_DEVICE_ID:
             raise ValueError("assignments holds a device id >= k")
     return paths, lens
+
+
+def cp_ranks(graph: CpGraph, *, stream=None):
+    """cp_ranks on the graph's device: returns (upRank, downRank, totalRank), int64 [n] each."""
+    import torch
+    lib = load_library()
+    dev = graph.blob.device
+    n = graph.info["n"]
+    need = C.c_size_t(0)
+    rc = lib.cp_ranks_workspace_bytes(graph._handle, C.byref(need))
+    if rc:
+        raise CpError(rc, "cp_ranks_workspace_bytes")
+    ws = torch.empty(need.value, dtype=torch.uint8, device=dev)
+    up, down, total = (torch.empty(n, dtype=torch.int64, device=dev) for _ in range(3))
+    rc = lib.cp_ranks(graph._handle, C.c_void_p(ws.data_ptr()), C.c_size_t(ws.numel()), _stream_ptr(stream),
+                      C.c_void_p(up.data_ptr()), C.c_void_p(down.data_ptr()), C.c_void_p(total.data_ptr()))
+    if rc:
+        raise CpError(rc, "cp_ranks")
+    torch.cuda.synchronize(dev)      # the workspace is released on return
+    return up, down, total
 
 
 def mask_to_bool(mask_words, batch: int) -> np.ndarray:

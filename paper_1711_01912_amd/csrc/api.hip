@@ -406,6 +406,46 @@ int cp_critical_path(const cp_graph *g, int32_t batch, int32_t k,
                                 max_len, path_out, len_out, stream);
 }
 
+int cp_ranks_workspace_bytes(const cp_graph *g, size_t *out_bytes) {
+    if (!g || !out_bytes) return CP_ERR_NULL;
+    size_t eval = 0;
+    int rc = cp_eval_workspace_bytes(g, 1, 1, CP_ASSIGN_PARTITION_MAJOR, CP_PLAN_AUTO, &eval);
+    if (rc) return rc;
+    const size_t n = (size_t)g->packed.n, T = (size_t)g->packed.info.min_tick_bytes;
+    *out_bytes = align_up(eval) + align_up(n) + 2 * align_up(n * T) + 2 * kAlign;
+    return CP_OK;
+}
+
+int cp_ranks(const cp_graph *g, void *workspace, size_t workspace_bytes, void *stream,
+             int64_t *up_out, int64_t *down_out, int64_t *total_out) {
+    if (!g || !workspace) return CP_ERR_NULL;
+    if (!up_out && !down_out && !total_out) return CP_ERR_NULL;
+    if (!g->device_blob) return CP_ERR_STATE;
+    size_t need = 0, eval = 0;
+    int rc = cp_ranks_workspace_bytes(g, &need);
+    if (rc) return rc;
+    if (((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < need) return CP_ERR_WORKSPACE;
+    rc = cp_eval_workspace_bytes(g, 1, 1, CP_ASSIGN_PARTITION_MAJOR, CP_PLAN_AUTO, &eval);
+    if (rc) return rc;
+    const Packed &p = g->packed;
+    const size_t n = (size_t)p.n, T = (size_t)p.info.min_tick_bytes;
+    uint8_t *ws = (uint8_t *)workspace;
+    uint8_t *d_assign = ws + align_up(eval);
+    uint8_t *d_b = d_assign + align_up(n);
+    uint8_t *d_tl = d_b + align_up(n * T);
+    int64_t *d_cp = (int64_t *)(d_tl + align_up(n * T));
+    int32_t *d_status = (int32_t *)((uint8_t *)d_cp + kAlign);
+    rc = launch_zero_bytes(d_assign, (int64_t)n, stream);
+    if (rc) return rc;
+    // one device of speed 1: w(v) = c(v), nothing is ever transferred
+    const int64_t one = 1;
+    rc = cp_eval(g, 1, 1, d_assign, CP_ASSIGN_PARTITION_MAJOR, &one, &one, ws, align_up(eval), stream, d_cp,
+                 d_b, d_tl, nullptr, (int)T, CP_PLAN_AUTO, d_status, nullptr);
+    if (rc) return rc;
+    return launch_ranks(d_b, d_tl, (const uint8_t *)g->device_blob + p.c_off, p.narrow, (int)T, p.n, up_out,
+                        down_out, total_out, stream);
+}
+
 int cp_profile_create(int32_t slots, cp_profile **out) {
     if (!out) return CP_ERR_NULL;
     *out = nullptr;

@@ -59,6 +59,25 @@ __global__ void clear_kernel(int64_t *cp_out, int32_t batch, int32_t *status) {
     if (i == 0) *status = CP_STATUS_OK;
 }
 
+__global__ void zero_bytes_kernel(uint8_t *dst, int64_t bytes) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < bytes) dst[i] = 0;
+}
+
+// Ranks of section 3.2 from the one-device, unit-speed evaluation: upRank = b,
+// downRank = tl + c (the rank equation adds the vertex's own c), totalRank = their sum.
+template <typename Tick, typename WT>
+__global__ void ranks_kernel(const Tick *__restrict__ b, const Tick *__restrict__ tl,
+                             const WT *__restrict__ c, int32_t n, int64_t *__restrict__ up,
+                             int64_t *__restrict__ down, int64_t *__restrict__ total) {
+    int32_t v = blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= n) return;
+    const int64_t u = (int64_t)b[v], d = (int64_t)tl[v] + (int64_t)c[v];
+    if (up) up[v] = u;
+    if (down) down[v] = d;
+    if (total) total[v] = u + d;
+}
+
 // assignments[P][n] -> pT[n][P], 64 x 64 byte tiles through LDS
 __global__ __launch_bounds__(256) void transpose_kernel(const uint8_t *__restrict__ in,
                                                         uint8_t *__restrict__ out, int32_t n,
@@ -784,6 +803,29 @@ int launch_gather_assign(const SweepLaunch &s, uint8_t *out, void *stream) {
 int launch_clear(int64_t *cp_out, int32_t batch, int32_t *status, void *stream) {
     hipLaunchKernelGGL(clear_kernel, dim3((batch + 255) / 256), dim3(256), 0, (hipStream_t)stream,
                        cp_out, batch, status);
+    return hip_ok(hipGetLastError());
+}
+
+int launch_zero_bytes(uint8_t *dst, int64_t bytes, void *stream) {
+    if (bytes <= 0) return CP_OK;
+    hipLaunchKernelGGL(zero_bytes_kernel, dim3((unsigned)((bytes + 255) / 256)), dim3(256), 0,
+                       (hipStream_t)stream, dst, bytes);
+    return hip_ok(hipGetLastError());
+}
+
+int launch_ranks(const void *b, const void *tl, const void *c, bool narrow, int tick_bytes, int32_t n,
+                 int64_t *up, int64_t *down, int64_t *total, void *stream) {
+    const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+    hipStream_t st = (hipStream_t)stream;
+#define CP_RANKS(TICK, WT)                                                                         \
+    hipLaunchKernelGGL((ranks_kernel<TICK, WT>), grid, block, 0, st, (const TICK *)b, (const TICK *)tl, \
+                       (const WT *)c, n, up, down, total)
+    if (tick_bytes == 4) {
+        if (narrow) CP_RANKS(int32_t, uint32_t); else CP_RANKS(int32_t, int64_t);
+    } else {
+        if (narrow) CP_RANKS(int64_t, uint32_t); else CP_RANKS(int64_t, int64_t);
+    }
+#undef CP_RANKS
     return hip_ok(hipGetLastError());
 }
 

@@ -49,6 +49,9 @@ int launch_column_sweep(const SweepLaunch &s, void *stream, int32_t *launches);
 int launch_window_sweep(const SweepLaunch &s, const WindowCfg &cfg, void *stream, int32_t *launches);
 int launch_cp_sources(const int32_t *sources, int32_t nsrc, const void *b, int32_t P,
                       int tick_bytes, int64_t *cp_out, void *stream);
+int launch_zero_bytes(uint8_t *dst, int64_t bytes, void *stream);
+int launch_ranks(const void *b, const void *tl, const void *c, bool narrow, int tick_bytes, int32_t n,
+                 int64_t *up, int64_t *down, int64_t *total, void *stream);
 int launch_critical_path(const SweepLaunch &s, const int32_t *sources, int32_t nsrc, const int64_t *cp,
                          int32_t max_len, int32_t *path, int32_t *len, void *stream);
 int launch_mask(const void *b, const void *tl, const int64_t *cp, int32_t n, int32_t P,

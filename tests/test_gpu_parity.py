@@ -331,3 +331,31 @@ def test_critical_path_64_bit_weights(gpu, oracle):
                 [1, 3, 2**33], rng.integers(1, 2**20, size=(3, 3)), rng.integers(0, 3, size=(20, n), dtype=np.uint8),
                 level)
     _check_paths(gpu, oracle, w)
+
+
+# ------------------------------------------------------------------ ranks of section 3.2
+
+@pytest.mark.parametrize("name,kw", [("tiny", {}), ("mlp", {}), ("inception", {}), ("comm_heavy", {}),
+                                     ("large_sparse", {})])
+def test_ranks(gpu, oracle, name, kw):
+    w = make_workload(name, P=1, **kw)
+    g = gpu.CpGraph.from_workload(w, device="cuda:0")
+    up, down, total = gpu.cp_ranks(g)
+    ref = oracle.ranks(w.n, w.succ_ptr, w.succ_idx, w.c)
+    for got, exp, what in zip((up, down, total), ref, ("upRank", "downRank", "totalRank")):
+        assert np.array_equal(got.cpu().numpy(), exp), what
+    g.close()
+
+
+def test_ranks_with_wide_weights(gpu, oracle):
+    rng = np.random.default_rng(31)
+    n, level, src, dst = random_layered_dag(rng, [70] * 9, 1, 3, 2)
+    w = _custom("wide-ranks", n, src, dst, np.ones(len(src), dtype=np.int64), rng.integers(1, 2**40, size=n),
+                [1], [[1]], np.zeros((1, n), dtype=np.uint8), level)
+    g = gpu.CpGraph.from_workload(w, device="cuda:0")
+    assert g.info["min_tick_bytes"] == 8
+    got = gpu.cp_ranks(g)
+    ref = oracle.ranks(w.n, w.succ_ptr, w.succ_idx, w.c)
+    for a, b in zip(got, ref):
+        assert np.array_equal(a.cpu().numpy(), b)
+    g.close()
