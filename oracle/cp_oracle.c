@@ -266,3 +266,66 @@ int cp_oracle_ranks(int32_t n, const int32_t *succ_ptr, const int32_t *succ_idx,
     free(order);
     return 0;
 }
+
+/*
+ * PCT priority order (section 4.1: a device always runs the executable vertex with the
+ * highest PCT; PCT is computed once after partitioning and the schedule reused).  Per
+ * partition, the static priority list of every device: its vertices by descending
+ * PCT = b, equal values by ascending vertex number.  order_out[j] lists the vertices
+ * of device 0, then device 1, ...; seg_out[j][d] .. seg_out[j][d+1] is device d's range.
+ * Written as the definition: a comparison sort under the key (device, -b, vertex).
+ * assignments and b are [P][n], order_out [P][n], seg_out [P][k+1].
+ * Returns 0; -2 out of memory; -3 a device id >= k.
+ */
+typedef struct { int64_t b; int32_t v; int32_t dev; } pct_item;
+
+static int pct_before(const void *x, const void *y)
+{
+    const pct_item *a = (const pct_item *)x, *c = (const pct_item *)y;
+    if (a->dev != c->dev) return a->dev < c->dev ? -1 : 1;
+    if (a->b != c->b) return a->b > c->b ? -1 : 1;       /* higher PCT first */
+    if (a->v != c->v) return a->v < c->v ? -1 : 1;
+    return 0;
+}
+
+int cp_oracle_pct_order(int32_t n, int k, int32_t P, const uint8_t *assignments, const int64_t *b,
+                        int32_t *order_out, int32_t *seg_out, int threads)
+{
+    int rc = 0;
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+#else
+    (void)threads;
+#endif
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t j = 0; j < P; ++j) {
+        pct_item *it = (pct_item *)malloc(((size_t)n + 1) * sizeof(pct_item));
+        if (!it) {
+#pragma omp atomic write
+            rc = -2;
+            continue;
+        }
+        int32_t *seg = seg_out + (size_t)j * (k + 1);
+        for (int d = 0; d <= k; ++d) seg[d] = 0;
+        int bad = 0;
+        for (int32_t v = 0; v < n; ++v) {
+            int dev = assignments[(size_t)j * n + v];
+            if (dev >= k) { bad = 1; break; }
+            it[v].b = b[(size_t)j * n + v];
+            it[v].v = v;
+            it[v].dev = dev;
+            seg[dev + 1] += 1;
+        }
+        if (bad) {
+#pragma omp atomic write
+            rc = -3;
+            free(it);
+            continue;
+        }
+        qsort(it, (size_t)n, sizeof(pct_item), pct_before);
+        for (int32_t i = 0; i < n; ++i) order_out[(size_t)j * n + i] = it[i].v;
+        for (int d = 0; d < k; ++d) seg[d + 1] += seg[d];
+        free(it);
+    }
+    return rc;
+}

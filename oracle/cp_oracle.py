@@ -35,6 +35,8 @@ def _load():
                                                 C.c_int32, u8p, C.c_int32, i32p, i32p]
         lib.cp_oracle_ranks.restype = C.c_int
         lib.cp_oracle_ranks.argtypes = [C.c_int32, i32p, i32p, i64p, i64p, i64p, i64p]
+        lib.cp_oracle_pct_order.restype = C.c_int
+        lib.cp_oracle_pct_order.argtypes = [C.c_int32, C.c_int, C.c_int32, u8p, i64p, i32p, i32p, C.c_int]
         _lib = lib
     return _lib
 
@@ -167,3 +169,21 @@ def ranks(n, succ_ptr, succ_idx, c):
     if rc:
         raise ValueError(f"ranks failed with code {rc}")
     return up, down, total
+
+
+def pct_order(k, assignments, b, threads=0):
+    """PCT priority lists (section 4.1): per row of ``assignments`` [P][n] and ``b`` [P][n],
+    the vertices grouped by device and, inside a device, by descending b then ascending
+    vertex number.  Returns (order int32 [P][n], seg int32 [P][k+1])."""
+    lib = _load()
+    a = np.ascontiguousarray(assignments, dtype=np.uint8)
+    bb = np.ascontiguousarray(b, dtype=np.int64)
+    P, n = a.shape
+    assert bb.shape == (P, n)
+    order = np.zeros((P, n), dtype=np.int32)
+    seg = np.zeros((P, k + 1), dtype=np.int32)
+    rc = lib.cp_oracle_pct_order(n, int(k), P, _ptr(a, C.c_uint8), _ptr(bb, C.c_int64), _ptr(order, C.c_int32),
+                                 _ptr(seg, C.c_int32), int(threads))
+    if rc:
+        raise ValueError(f"pct_order failed with code {rc}")
+    return order, seg

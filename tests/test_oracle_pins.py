@@ -556,3 +556,54 @@ def test_ranks_are_the_one_device_unit_speed_evaluation(oracle):
     assert np.array_equal(up, got["b"][0])
     assert np.array_equal(down, got["tl"][0] + w.c)
     assert up.max() == got["cp"][0] == down.max()
+
+
+# ------------------------------------------------------------------ PCT priority order (section 4.1)
+
+def test_pct_order_hand_example(oracle):
+    # two devices; device 0 holds {0, 2, 3, 5}, device 1 holds {1, 4}
+    a = np.array([[0, 1, 0, 0, 1, 0]], dtype=np.uint8)
+    b = np.array([[7, 3, 9, 7, 3, 1]])
+    order, seg = oracle.pct_order(2, a, b)
+    assert order[0].tolist() == [2, 0, 3, 5, 1, 4]        # 9, then the two 7s by vertex number, then 1 | 3, 3
+    assert seg[0].tolist() == [0, 4, 6]
+    # an unused device has an empty range
+    order, seg = oracle.pct_order(3, np.array([[2, 0, 2]], dtype=np.uint8), np.array([[5, 5, 6]]))
+    assert order[0].tolist() == [1, 2, 0] and seg[0].tolist() == [0, 1, 1, 3]
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_pct_order_by_counting_ranks(oracle, seed):
+    """Position of v = number of vertices that must come before it (lower device, or the
+    same device and higher b, or the same b and lower number), counted pair by pair."""
+    rng = np.random.default_rng(400 + seed)
+    n, k, P = 60, 3, 5
+    a = rng.integers(0, k, size=(P, n), dtype=np.uint8)
+    b = rng.integers(0, 8, size=(P, n))                   # many ties
+    order, seg = oracle.pct_order(k, a, b)
+    for j in range(P):
+        pos = np.empty(n, dtype=np.int64)
+        pos[order[j]] = np.arange(n)
+        for v in range(n):
+            before = sum(1 for u in range(n) if u != v and (
+                a[j, u] < a[j, v] or (a[j, u] == a[j, v] and (b[j, u] > b[j, v] or (b[j, u] == b[j, v] and u < v)))))
+            assert pos[v] == before
+        assert seg[j].tolist() == [int((a[j] < d).sum()) for d in range(k + 1)]
+
+
+def test_pct_order_against_lexsort_and_precedence(oracle):
+    """numpy's lexsort under the same key; and since every vertex here costs at least one
+    tick, b strictly decreases along an edge, so a device's list never runs a vertex before
+    one of its predecessors on that device (requirement 4 of section 4)."""
+    w = make_workload("mlp", P=6)
+    got = oracle.evaluate_workload(w, want=("b",))
+    order, seg = oracle.pct_order(w.k, w.assignments, got["b"])
+    ids = np.arange(w.n)
+    src = np.repeat(ids, np.diff(w.succ_ptr))
+    for j in range(w.P):
+        assert np.array_equal(order[j], np.lexsort((ids, -got["b"][j], w.assignments[j])))
+        pos = np.empty(w.n, dtype=np.int64)
+        pos[order[j]] = ids
+        same = w.assignments[j][src] == w.assignments[j][w.succ_idx]
+        assert (pos[src][same] < pos[w.succ_idx][same]).all()
+        assert np.array_equal(np.diff(seg[j]), np.bincount(w.assignments[j], minlength=w.k))
