@@ -58,6 +58,8 @@ extern "C" {
 #define CP_STATUS_OK             0
 #define CP_STATUS_BAD_DEVICE_ID  1   /* some assignments entry is >= k: the call's outputs are meaningless
                                         (the entry was replaced by a valid device so that no access leaves its table) */
+#define CP_STATUS_B_OUT_OF_RANGE 2   /* cp_pct_order: some b lies outside [0, max_b]: the order is meaningless;
+                                        status values are bit flags and may be or-ed */
 
 /* ---- enums ---- */
 #define CP_TICK_I32  4   /* b-level / t-level stored as int32 (only if the graph's bound allows) */
@@ -197,6 +199,35 @@ int cp_critical_path(const cp_graph *g, int32_t batch, int32_t k,
                      const void *blevel, const int64_t *cp, int tick_dtype,
                      void *workspace, size_t workspace_bytes, void *stream,
                      int32_t max_len, int32_t *path_out, int32_t *len_out, int32_t *status_out);
+
+/*
+ * PCT priority lists (paper, section 4.1: every device runs, among its executable
+ * vertices, the one with the highest PCT; PCT is computed once after partitioning and
+ * the schedule is reused).  Per partition, the static priority list of every device:
+ * its vertices by descending PCT = b, equal values by ascending vertex number.
+ * order_out[j] lists the vertices of device 0, then of device 1, ...;
+ * seg_out[j][d] .. seg_out[j][d+1] is device d's range.  Only enqueues work on `stream`.
+ *
+ *   assignments, assign_layout   as for cp_eval
+ *   blevel      device ticks [n][batch]: output of cp_eval for these assignments
+ *   max_b       an upper bound on every b (for instance the largest CP of the batch); 0 = the
+ *               graph's raw path bound.  A tighter bound means fewer sorting passes.  A b
+ *               outside [0, max_b] sets CP_STATUS_B_OUT_OF_RANGE.
+ *   workspace   device, 256-byte aligned, >= cp_pct_order_workspace_bytes (same batch, k, max_b)
+ *   order_out   device int32 [batch][n]
+ *   seg_out     device int32 [batch][k+1]
+ *   status_out  device int32: CP_STATUS_* flags after the stream has drained
+ * Errors: CP_ERR_NULL, CP_ERR_SIZE (also batch * ceil(n / 4096) >= 2^31), CP_ERR_ARG
+ * (max_b < 0), CP_ERR_STATE, CP_ERR_OVERFLOW (device bits + bits of max_b > 64, or 32-bit
+ * ticks asked for a graph that needs 64), CP_ERR_WORKSPACE, CP_ERR_HIP.
+ */
+int cp_pct_order_workspace_bytes(const cp_graph *g, int32_t batch, int32_t k, int64_t max_b,
+                                 size_t *out_bytes);
+int cp_pct_order(const cp_graph *g, int32_t batch, int32_t k,
+                 const uint8_t *assignments, int assign_layout,
+                 const void *blevel, int tick_dtype, int64_t max_b,
+                 void *workspace, size_t workspace_bytes, void *stream,
+                 int32_t *order_out, int32_t *seg_out, int32_t *status_out);
 
 /*
  * The device-free ranks of section 3.2: upRank (equation for the upward rank), downRank

@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     PLAN_WAVE_COLUMN,
     cost_magic,
     cp_critical_path,
+    cp_pct_order,
     cp_ranks,
     cp_eval,
     error_string,

@@ -26,6 +26,7 @@ STATUS_BAD_DEVICE_ID = 1
 EXPORTS = (
     "cp_graph_create", "cp_graph_get_info", "cp_graph_upload", "cp_graph_destroy",
     "cp_eval_workspace_bytes", "cp_eval", "cp_critical_path", "cp_ranks_workspace_bytes", "cp_ranks",
+    "cp_pct_order_workspace_bytes", "cp_pct_order",
     "cp_profile_create", "cp_profile_reset",
     "cp_profile_count", "cp_profile_read", "cp_profile_destroy", "cp_cost_magic",
     "cp_error_string",
@@ -86,6 +87,11 @@ def load_library():
     lib.cp_critical_path.restype = C.c_int
     lib.cp_critical_path.argtypes = [vp, C.c_int32, C.c_int32, vp, C.c_int, i64p, i64p, vp, vp, C.c_int,
                                      vp, C.c_size_t, vp, C.c_int32, vp, vp, vp]
+    lib.cp_pct_order_workspace_bytes.restype = C.c_int
+    lib.cp_pct_order_workspace_bytes.argtypes = [vp, C.c_int32, C.c_int32, C.c_int64, C.POINTER(C.c_size_t)]
+    lib.cp_pct_order.restype = C.c_int
+    lib.cp_pct_order.argtypes = [vp, C.c_int32, C.c_int32, vp, C.c_int, vp, C.c_int, C.c_int64,
+                                 vp, C.c_size_t, vp, vp, vp, vp]
     lib.cp_ranks_workspace_bytes.restype = C.c_int
     lib.cp_ranks_workspace_bytes.argtypes = [vp, C.POINTER(C.c_size_t)]
     lib.cp_ranks.restype = C.c_int
@@ -353,6 +359,46 @@ def cp_critical_path(graph: CpGraph, assignments, speeds, bandwidth, b, cp, *,
         if int(status.item()) == STATUS_BAD_DEVICE_ID:
             raise ValueError("assignments holds a device id >= k")
     return paths, lens
+
+
+STATUS_B_OUT_OF_RANGE = 2
+
+
+def cp_pct_order(graph: CpGraph, assignments, k: int, b, *, max_b: int = 0,
+                 assign_layout=ASSIGN_PARTITION_MAJOR, workspace=None, out=None, stream=None,
+                 check_status=True):
+    """cp_pct_order on torch tensors: ``b`` is cp_eval's b-level output for the same
+    assignments.  Returns (order int32 [batch][n], seg int32 [batch][k+1])."""
+    import torch
+    lib = load_library()
+    n = graph.info["n"]
+    batch = int(b.shape[1])
+    dev = b.device
+    if workspace is None:
+        need = C.c_size_t(0)
+        rc = lib.cp_pct_order_workspace_bytes(graph._handle, batch, int(k), int(max_b), C.byref(need))
+        if rc:
+            raise CpError(rc, "cp_pct_order_workspace_bytes")
+        workspace = torch.empty(need.value, dtype=torch.uint8, device=dev)
+    if out is None:
+        out = {"order": torch.empty((batch, n), dtype=torch.int32, device=dev),
+               "seg": torch.empty((batch, int(k) + 1), dtype=torch.int32, device=dev),
+               "status": torch.empty(1, dtype=torch.int32, device=dev)}
+    tick = 4 if b.dtype == torch.int32 else 8
+    rc = lib.cp_pct_order(graph._handle, batch, int(k), C.c_void_p(assignments.data_ptr()), int(assign_layout),
+                          C.c_void_p(b.data_ptr()), tick, int(max_b), C.c_void_p(workspace.data_ptr()),
+                          C.c_size_t(workspace.numel()), _stream_ptr(stream), C.c_void_p(out["order"].data_ptr()),
+                          C.c_void_p(out["seg"].data_ptr()), C.c_void_p(out["status"].data_ptr()))
+    if rc:
+        raise CpError(rc, "cp_pct_order")
+    if check_status:
+        torch.cuda.synchronize(dev)
+        st = int(out["status"].item())
+        if st & STATUS_BAD_DEVICE_ID:
+            raise ValueError("assignments holds a device id >= k")
+        if st & STATUS_B_OUT_OF_RANGE:
+            raise ValueError("some b lies outside [0, max_b]")
+    return out["order"], out["seg"]
 
 
 def cp_ranks(graph: CpGraph, *, stream=None):

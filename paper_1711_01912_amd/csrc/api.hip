@@ -122,6 +122,38 @@ int check_eval_sizes(const cp_graph *g, int32_t batch, int32_t k, int assign_lay
     return CP_OK;
 }
 
+struct PctPlan {
+    int b_bits = 1, key_bits = 1, key_bytes = 4;
+    int64_t max_b = 0;
+    size_t keys_bytes = 0, vals_bytes = 0, counts_bytes = 0, total = 0;
+};
+
+int bit_length(uint64_t x) {
+    int b = 0;
+    while (x) { ++b; x >>= 1; }
+    return b;
+}
+
+int pct_plan(const cp_graph *g, int32_t batch, int32_t k, int64_t max_b, PctPlan &out) {
+    int rc = check_eval_sizes(g, batch, k, CP_ASSIGN_PARTITION_MAJOR, CP_PLAN_AUTO);
+    if (rc) return rc;
+    if (max_b < 0) return CP_ERR_ARG;
+    const Packed &p = g->packed;
+    out.max_b = max_b > 0 ? max_b : std::max<int64_t>(p.info.raw_path_bound, 1);
+    out.b_bits = std::max(1, bit_length((uint64_t)out.max_b));
+    out.key_bits = out.b_bits + bit_length((uint64_t)(k - 1));
+    if (out.key_bits > 64) return CP_ERR_OVERFLOW;
+    out.key_bytes = out.key_bits <= 32 ? 4 : 8;
+    const int64_t tiles = ((int64_t)p.n + 4095) / 4096;
+    if (tiles * (int64_t)batch >= (int64_t)1 << 31) return CP_ERR_SIZE;
+    const size_t items = (size_t)p.n * (size_t)batch;
+    out.keys_bytes = align_up(items * (size_t)out.key_bytes);
+    out.vals_bytes = align_up(items * sizeof(int32_t));
+    out.counts_bytes = pct_counts_bytes(p.n, batch);
+    out.total = 2 * out.keys_bytes + out.vals_bytes + out.counts_bytes;
+    return CP_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -404,6 +436,53 @@ int cp_critical_path(const cp_graph *g, int32_t batch, int32_t k,
     s.status = status_out;
     return launch_critical_path(s, (const int32_t *)(s.blob + p.sources_off), p.info.num_sources, cp,
                                 max_len, path_out, len_out, stream);
+}
+
+int cp_pct_order_workspace_bytes(const cp_graph *g, int32_t batch, int32_t k, int64_t max_b,
+                                 size_t *out_bytes) {
+    if (!out_bytes) return CP_ERR_NULL;
+    PctPlan plan;
+    int rc = pct_plan(g, batch, k, max_b, plan);
+    if (rc) return rc;
+    *out_bytes = plan.total;
+    return CP_OK;
+}
+
+int cp_pct_order(const cp_graph *g, int32_t batch, int32_t k,
+                 const uint8_t *assignments, int assign_layout,
+                 const void *blevel, int tick_dtype, int64_t max_b,
+                 void *workspace, size_t workspace_bytes, void *stream,
+                 int32_t *order_out, int32_t *seg_out, int32_t *status_out) {
+    PctPlan plan;
+    int rc = pct_plan(g, batch, k, max_b, plan);
+    if (rc) return rc;
+    if (assign_layout != CP_ASSIGN_PARTITION_MAJOR && assign_layout != CP_ASSIGN_VERTEX_MAJOR) return CP_ERR_ARG;
+    if (!assignments || !blevel || !workspace || !order_out || !seg_out || !status_out) return CP_ERR_NULL;
+    if (tick_dtype != CP_TICK_I32 && tick_dtype != CP_TICK_I64) return CP_ERR_ARG;
+    if (!g->device_blob) return CP_ERR_STATE;
+    const Packed &p = g->packed;
+    if (tick_dtype == CP_TICK_I32 && p.info.min_tick_bytes > 4) return CP_ERR_OVERFLOW;
+    if (((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < plan.total) return CP_ERR_WORKSPACE;
+    rc = launch_clear(nullptr, 1, status_out, stream);
+    if (rc) return rc;
+    uint8_t *ws = (uint8_t *)workspace;
+    PctOrderLaunch s;
+    s.n = p.n; s.P = batch; s.k = k;
+    s.b = blevel;
+    s.tick_bytes = tick_dtype;
+    s.assign = assignments;
+    if (assign_layout == CP_ASSIGN_PARTITION_MAJOR) { s.a_stride_p = p.n; s.a_stride_v = 1; }
+    else { s.a_stride_p = 1; s.a_stride_v = batch; }
+    s.max_b = plan.max_b;
+    s.b_bits = plan.b_bits; s.key_bits = plan.key_bits; s.key_bytes = plan.key_bytes;
+    s.keys_a = ws;
+    s.keys_b = ws + plan.keys_bytes;
+    s.vals_tmp = (int32_t *)(ws + 2 * plan.keys_bytes);
+    s.counts = (uint32_t *)(ws + 2 * plan.keys_bytes + plan.vals_bytes);
+    s.order_out = order_out;
+    s.seg_out = seg_out;
+    s.status = status_out;
+    return launch_pct_order(s, stream);
 }
 
 int cp_ranks_workspace_bytes(const cp_graph *g, size_t *out_bytes) {

@@ -49,6 +49,23 @@ int launch_column_sweep(const SweepLaunch &s, void *stream, int32_t *launches);
 int launch_window_sweep(const SweepLaunch &s, const WindowCfg &cfg, void *stream, int32_t *launches);
 int launch_cp_sources(const int32_t *sources, int32_t nsrc, const void *b, int32_t P,
                       int tick_bytes, int64_t *cp_out, void *stream);
+// One segmented radix sort per call: the PCT priority lists of section 4.1.
+struct PctOrderLaunch {
+    int32_t n = 0, P = 0, k = 0;
+    const void *b = nullptr;          // ticks [n][P]
+    int tick_bytes = 4;
+    const uint8_t *assign = nullptr;
+    int64_t a_stride_p = 0, a_stride_v = 0;
+    int64_t max_b = 0;                // every b lies in [0, max_b]
+    int b_bits = 1, key_bits = 1, key_bytes = 4;
+    void *keys_a = nullptr, *keys_b = nullptr;   // key [P][n] each
+    int32_t *vals_tmp = nullptr;      // [P][n]
+    uint32_t *counts = nullptr;       // pct_counts_bytes
+    int32_t *order_out = nullptr, *seg_out = nullptr, *status = nullptr;
+};
+size_t pct_counts_bytes(int32_t n, int32_t P);
+int launch_pct_order(const PctOrderLaunch &s, void *stream);
+
 int launch_zero_bytes(uint8_t *dst, int64_t bytes, void *stream);
 int launch_ranks(const void *b, const void *tl, const void *c, bool narrow, int tick_bytes, int32_t n,
                  int64_t *up, int64_t *down, int64_t *total, void *stream);

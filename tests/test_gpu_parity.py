@@ -359,3 +359,72 @@ def test_ranks_with_wide_weights(gpu, oracle):
     for a, b in zip(got, ref):
         assert np.array_equal(a.cpu().numpy(), b)
     g.close()
+
+
+# ------------------------------------------------------------------ PCT priority lists (section 4.1)
+
+def _check_pct_order(gpu, oracle, w, layout=0, max_b="cp", sample=None):
+    import torch
+    g = gpu.CpGraph.from_workload(w, device="cuda:0")
+    a_host = w.assignments if layout == 0 else np.ascontiguousarray(w.assignments.T)
+    a = torch.from_numpy(a_host).to("cuda:0")
+    out = gpu.cp_eval(g, a, w.speeds, w.bandwidth, want=("cp", "b"), assign_layout=layout)
+    bound = int(out["cp"].max().item()) if max_b == "cp" else max_b
+    order, seg = gpu.cp_pct_order(g, a, w.k, out["b"], max_b=bound, assign_layout=layout)
+    rows = slice(0, w.P) if sample is None else slice(0, sample)
+    b_host = np.ascontiguousarray(out["b"].cpu().numpy().T[rows]).astype(np.int64)
+    ref_b = oracle.evaluate_workload(w, want=("b",), threads=8, partitions=rows)["b"]
+    assert np.array_equal(b_host, ref_b)
+    ref_order, ref_seg = oracle.pct_order(w.k, w.assignments[rows], ref_b, threads=8)
+    assert np.array_equal(seg.cpu().numpy()[rows], ref_seg)
+    assert np.array_equal(order.cpu().numpy()[rows], ref_order)
+    g.close()
+
+
+def test_pct_order_small(gpu, oracle):
+    _check_pct_order(gpu, oracle, make_workload("tiny"))
+    _check_pct_order(gpu, oracle, make_workload("tiny"), layout=1)
+    _check_pct_order(gpu, oracle, make_workload("tiny"), max_b=0)            # the graph's own bound
+    _check_pct_order(gpu, oracle, make_workload("mlp", P=70))
+    _check_pct_order(gpu, oracle, make_workload("mlp", P=70), layout=1)
+
+
+def test_pct_order_several_tiles_and_a_ragged_tail(gpu, oracle):
+    _check_pct_order(gpu, oracle, make_workload("inception", P=33))          # 19,772 = 4 tiles + 3,388
+    _check_pct_order(gpu, oracle, make_workload("comm_heavy", P=9, levels=4, width=2049))
+
+
+def test_pct_order_many_ties_and_one_device(gpu, oracle):
+    rng = np.random.default_rng(41)
+    n, level, src, dst = random_layered_dag(rng, [700] * 8, 1, 3, 2)
+    w = _custom("ties", n, src, dst, np.zeros(len(src), dtype=np.int64), np.ones(n, dtype=np.int64), [1, 1, 1],
+                np.ones((3, 3), dtype=np.int64), rng.integers(0, 3, size=(5, n), dtype=np.uint8), level)
+    _check_pct_order(gpu, oracle, w)                                         # b takes 8 values only
+    w1 = _custom("one-device", n, src, dst, rng.integers(0, 50, size=len(src)), rng.integers(1, 50, size=n), [2],
+                 [[1]], np.zeros((3, n), dtype=np.uint8), level)
+    _check_pct_order(gpu, oracle, w1)
+
+
+def test_pct_order_64_bit_keys(gpu, oracle):
+    rng = np.random.default_rng(42)
+    n, level, src, dst = random_layered_dag(rng, [600] * 9, 1, 3, 2)
+    w = _custom("wide-order", n, src, dst, rng.integers(1, 2**45, size=len(src)), rng.integers(1, 2**40, size=n),
+                [1, 3, 2**33], rng.integers(1, 2**20, size=(3, 3)), rng.integers(0, 3, size=(7, n), dtype=np.uint8),
+                level)
+    _check_pct_order(gpu, oracle, w)
+    _check_pct_order(gpu, oracle, w, max_b=0)
+
+
+def test_pct_order_large_sparse_full(gpu, oracle):
+    _check_pct_order(gpu, oracle, make_workload("large_sparse"), sample=24)
+
+
+def test_pct_order_reports_a_bound_that_is_too_small(gpu):
+    import torch
+    w = make_workload("tiny")
+    g = gpu.CpGraph.from_workload(w, device="cuda:0")
+    a = torch.from_numpy(w.assignments).to("cuda:0")
+    out = gpu.cp_eval(g, a, w.speeds, w.bandwidth, want=("cp", "b"))
+    with pytest.raises(ValueError):
+        gpu.cp_pct_order(g, a, w.k, out["b"], max_b=int(out["cp"].max().item()) - 1)
+    g.close()
