@@ -42,6 +42,9 @@ def main():
     ap.add_argument("--workload", default="large_sparse")
     ap.add_argument("--plan", type=int, default=0, help="0 auto, 1 wave-column, 2 resident-window")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
+    ap.add_argument("--out-layout", default="native", choices=("native", "vertex", "partition"),
+                    help="layout of b, tl and the mask; native = the one the plan that runs produces directly "
+                         "(partition-major for the resident-window plan, vertex-major for wave-column)")
     ap.add_argument("--cpu-sample", type=int, default=32, help="partitions the oracle is timed on (0 = skip)")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB (a known-size kernel to scale "
@@ -71,18 +74,25 @@ def main():
     a = torch.from_numpy(w.assignments).to(dev)
     P, n, m = w.P, w.n, w.m
     tdt = torch.int32 if T == 4 else torch.int64
+    plan_used = args.plan if args.plan else binding.choose_plan(g, P, w.speeds, w.bandwidth, T)
+    if args.out_layout == "native":
+        out_layout = cpe.OUT_PARTITION_MAJOR if plan_used == cpe.PLAN_RESIDENT_WINDOW else cpe.OUT_VERTEX_MAJOR
+    else:
+        out_layout = cpe.OUT_PARTITION_MAJOR if args.out_layout == "partition" else cpe.OUT_VERTEX_MAJOR
+    rows, cols = (n, P) if out_layout == cpe.OUT_VERTEX_MAJOR else (P, n)
     out = {
         "cp": torch.empty(P, dtype=torch.int64, device=dev),
-        "b": torch.empty((n, P), dtype=tdt, device=dev),
-        "tl": torch.empty((n, P), dtype=tdt, device=dev),
-        "mask": torch.empty((n, (P + 63) // 64), dtype=torch.int64, device=dev),
+        "b": torch.empty((rows, cols), dtype=tdt, device=dev),
+        "tl": torch.empty((rows, cols), dtype=tdt, device=dev),
+        "mask": torch.empty((rows, (cols + 63) // 64), dtype=torch.int64, device=dev),
         "status": torch.empty(1, dtype=torch.int32, device=dev),
     }
-    ws = torch.empty(binding.workspace_bytes(g, P, w.k, plan=args.plan), dtype=torch.uint8, device=dev)
+    ws = torch.empty(binding.workspace_bytes(g, P, w.k, plan=args.plan, out_layout=out_layout, tick_bytes=T),
+                     dtype=torch.uint8, device=dev)
     prof = cpe.CpProfile(max(args.steps, 1))
 
     def step(profile=None):
-        cpe.cp_eval(g, a, w.speeds, w.bandwidth, out=out, workspace=ws, plan=args.plan,
+        cpe.cp_eval(g, a, w.speeds, w.bandwidth, out=out, workspace=ws, plan=args.plan, out_layout=out_layout,
                     profile=profile, check_status=False)
 
     if args.calibrate_copy_mib > 0:
@@ -136,7 +146,6 @@ def main():
                "kind": "oracle", "sample": f"first {sample} of {P} partitions of the same workload, "
                                            f"both sweeps, {c1 - c0:.2f} s"}
 
-    plan_used = args.plan if args.plan else info["auto_plan"]
     rec = {
         "metric": "edge-relaxations/sec (|E| x partitions) for batched critical-path eval",
         "value": 2.0 * m * P / (ms_per_step * 1e-3),
@@ -147,7 +156,8 @@ def main():
         "config": {"workload": args.workload, "n": n, "m": m, "L": w.L, "P": P, "k": w.k,
                    "tick_bytes": T, "max_out_degree": info["max_out_degree"],
                    "raw_path_bound": info["raw_path_bound"],
-                   "plan": {1: "wave-column", 2: "resident-window"}[plan_used]},
+                   "plan": {1: "wave-column", 2: "resident-window"}[plan_used],
+                   "out_layout": "vertex-major" if out_layout == cpe.OUT_VERTEX_MAJOR else "partition-major"},
         "stage_ms": stage_ms,
         "blevel_relaxations_per_s": m * P / (b_ms * 1e-3),
         "ns_per_level_blevel": b_ms * 1e6 / w.L,

@@ -68,6 +68,14 @@ extern "C" {
 #define CP_ASSIGN_PARTITION_MAJOR 0   /* assignments[batch][n] */
 #define CP_ASSIGN_VERTEX_MAJOR    1   /* assignments[n][batch] */
 
+/* Layout of the per-vertex outputs.  Vertex-major suits consumers that look at one
+ * vertex across partitions (and is what the wave-column plan produces natively);
+ * partition-major gives every partition one contiguous row (what the resident-window
+ * plan, the priority lists and the critical-path walk work on natively).  Every plan
+ * honours either choice. */
+#define CP_OUT_VERTEX_MAJOR       0   /* b, tl [n][batch]; mask [n][ceil(batch/64)], bit = partition */
+#define CP_OUT_PARTITION_MAJOR    1   /* b, tl [batch][n]; mask [batch][ceil(n/64)], bit = vertex */
+
 #define CP_PLAN_AUTO             0
 #define CP_PLAN_WAVE_COLUMN      1   /* one wavefront = one vertex x 64 partitions; one launch per level */
 #define CP_PLAN_RESIDENT_WINDOW  2   /* one workgroup = one partition; recent levels kept in LDS; one launch per sweep */
@@ -140,10 +148,18 @@ void cp_graph_destroy(cp_graph *g);
 
 /*
  * Bytes of device workspace cp_eval needs for this batch size, device count,
- * assignment layout and plan (CP_PLAN_AUTO allowed).
+ * assignment layout, plan (CP_PLAN_AUTO allowed), output layout and tick type.
  */
 int cp_eval_workspace_bytes(const cp_graph *g, int32_t batch, int32_t k, int assign_layout,
-                            int plan, size_t *out_bytes);
+                            int plan, int out_layout, int tick_dtype, size_t *out_bytes);
+
+/*
+ * The plan CP_PLAN_AUTO resolves to for this batch and cost model on the current
+ * device (a caller may want to know it to ask for the layout that plan produces
+ * directly).  Errors: as cp_eval's argument checks.
+ */
+int cp_eval_choose_plan(const cp_graph *g, int32_t batch, int32_t k, const int64_t *speeds,
+                        const int64_t *bandwidth, int tick_dtype, int *plan_out);
 
 /*
  * Evaluate `batch` partitions.  Only enqueues work on `stream`; it does not wait.
@@ -154,10 +170,14 @@ int cp_eval_workspace_bytes(const cp_graph *g, int32_t batch, int32_t k, int ass
  *   workspace     device, >= cp_eval_workspace_bytes, 256-byte aligned; contents are scratch.
  *                 Two calls that may overlap in time need distinct workspaces.
  *   cp_out        device int64 [batch], or NULL
- *   blevel_out    device ticks [n][batch] (vertex-major: partition j of vertex v at v*batch + j), or NULL
- *   tlevel_out    device ticks [n][batch], or NULL
- *   mask_out      device uint64 [n][ceil(batch/64)]; bit i of word q of row v is partition 64q+i; or NULL
+ *   blevel_out    device ticks, or NULL.  CP_OUT_VERTEX_MAJOR: [n][batch], partition j of vertex v at
+ *                 v*batch + j; CP_OUT_PARTITION_MAJOR: [batch][n], at j*n + v
+ *   tlevel_out    device ticks, same shape, or NULL
+ *   mask_out      device uint64, or NULL.  CP_OUT_VERTEX_MAJOR: [n][ceil(batch/64)], bit i of word w of
+ *                 row v is partition 64w+i; CP_OUT_PARTITION_MAJOR: [batch][ceil(n/64)], bit i of word w
+ *                 of row j is vertex 64w+i.  Bits past the last partition / vertex are 0.
  *   tick_dtype    CP_TICK_I32 or CP_TICK_I64: element type of blevel_out / tlevel_out
+ *   out_layout    CP_OUT_VERTEX_MAJOR or CP_OUT_PARTITION_MAJOR
  *   plan          CP_PLAN_AUTO, or force one (CP_ERR_ARG if it cannot run this graph / cost model)
  *   status_out    device int32, required: CP_STATUS_* after the stream has drained
  *   profile       NULL, or a profile whose next slot receives this call's stage timestamps
@@ -172,7 +192,7 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
             const int64_t *speeds, const int64_t *bandwidth,
             void *workspace, size_t workspace_bytes, void *stream,
             int64_t *cp_out, void *blevel_out, void *tlevel_out, uint64_t *mask_out,
-            int tick_dtype, int plan, int32_t *status_out, cp_profile *profile);
+            int tick_dtype, int out_layout, int plan, int32_t *status_out, cp_profile *profile);
 
 /*
  * One critical path per partition (paper, section 3.2.2 "compute the critical path";
@@ -184,7 +204,7 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
  *
  *   assignments, assign_layout, speeds, bandwidth   as for cp_eval (same values as the
  *                 call that produced blevel and cp)
- *   blevel        device ticks [n][batch], cp device int64 [batch]: outputs of cp_eval
+ *   blevel        device ticks laid out per b_layout (CP_OUT_*), cp device int64 [batch]: outputs of cp_eval
  *   workspace     device, 256-byte aligned, >= cp_eval_workspace_bytes for this batch and k
  *   max_len       row length of path_out, >= the graph's number of levels L
  *   path_out      device int32 [batch][max_len]; unused tail = -1
@@ -196,7 +216,7 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
 int cp_critical_path(const cp_graph *g, int32_t batch, int32_t k,
                      const uint8_t *assignments, int assign_layout,
                      const int64_t *speeds, const int64_t *bandwidth,
-                     const void *blevel, const int64_t *cp, int tick_dtype,
+                     const void *blevel, const int64_t *cp, int tick_dtype, int b_layout,
                      void *workspace, size_t workspace_bytes, void *stream,
                      int32_t max_len, int32_t *path_out, int32_t *len_out, int32_t *status_out);
 
@@ -209,7 +229,7 @@ int cp_critical_path(const cp_graph *g, int32_t batch, int32_t k,
  * seg_out[j][d] .. seg_out[j][d+1] is device d's range.  Only enqueues work on `stream`.
  *
  *   assignments, assign_layout   as for cp_eval
- *   blevel      device ticks [n][batch]: output of cp_eval for these assignments
+ *   blevel      device ticks laid out per b_layout (CP_OUT_*): output of cp_eval for these assignments
  *   max_b       an upper bound on every b (for instance the largest CP of the batch); 0 = the
  *               graph's raw path bound.  A tighter bound means fewer sorting passes.  A b
  *               outside [0, max_b] sets CP_STATUS_B_OUT_OF_RANGE.
@@ -225,7 +245,7 @@ int cp_pct_order_workspace_bytes(const cp_graph *g, int32_t batch, int32_t k, in
                                  size_t *out_bytes);
 int cp_pct_order(const cp_graph *g, int32_t batch, int32_t k,
                  const uint8_t *assignments, int assign_layout,
-                 const void *blevel, int tick_dtype, int64_t max_b,
+                 const void *blevel, int tick_dtype, int b_layout, int64_t max_b,
                  void *workspace, size_t workspace_bytes, void *stream,
                  int32_t *order_out, int32_t *seg_out, int32_t *status_out);
 

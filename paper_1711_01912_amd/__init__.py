@@ -8,6 +8,8 @@ from .binding import (  # noqa: F401
     CpError,
     CpGraph,
     CpProfile,
+    OUT_PARTITION_MAJOR,
+    OUT_VERTEX_MAJOR,
     PLAN_AUTO,
     PLAN_RESIDENT_WINDOW,
     PLAN_WAVE_COLUMN,

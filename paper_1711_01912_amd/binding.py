@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(HERE, "libcpeval.so")
 
 TICK_I32, TICK_I64 = 4, 8
 ASSIGN_PARTITION_MAJOR, ASSIGN_VERTEX_MAJOR = 0, 1
+OUT_VERTEX_MAJOR, OUT_PARTITION_MAJOR = 0, 1
 PLAN_AUTO, PLAN_WAVE_COLUMN, PLAN_RESIDENT_WINDOW = 0, 1, 2
 NUM_STAGES = 5
 STAGE_NAMES = ("prep", "blevel", "cp", "tlevel", "mask")
@@ -25,7 +26,7 @@ STATUS_BAD_DEVICE_ID = 1
 
 EXPORTS = (
     "cp_graph_create", "cp_graph_get_info", "cp_graph_upload", "cp_graph_destroy",
-    "cp_eval_workspace_bytes", "cp_eval", "cp_critical_path", "cp_ranks_workspace_bytes", "cp_ranks",
+    "cp_eval_workspace_bytes", "cp_eval_choose_plan", "cp_eval", "cp_critical_path", "cp_ranks_workspace_bytes", "cp_ranks",
     "cp_pct_order_workspace_bytes", "cp_pct_order",
     "cp_profile_create", "cp_profile_reset",
     "cp_profile_count", "cp_profile_read", "cp_profile_destroy", "cp_cost_magic",
@@ -79,18 +80,20 @@ def load_library():
     lib.cp_graph_destroy.restype = None
     lib.cp_graph_destroy.argtypes = [vp]
     lib.cp_eval_workspace_bytes.restype = C.c_int
-    lib.cp_eval_workspace_bytes.argtypes = [vp, C.c_int32, C.c_int32, C.c_int, C.c_int,
+    lib.cp_eval_workspace_bytes.argtypes = [vp, C.c_int32, C.c_int32, C.c_int, C.c_int, C.c_int, C.c_int,
                                             C.POINTER(C.c_size_t)]
+    lib.cp_eval_choose_plan.restype = C.c_int
+    lib.cp_eval_choose_plan.argtypes = [vp, C.c_int32, C.c_int32, i64p, i64p, C.c_int, C.POINTER(C.c_int)]
     lib.cp_eval.restype = C.c_int
     lib.cp_eval.argtypes = [vp, C.c_int32, C.c_int32, vp, C.c_int, i64p, i64p, vp, C.c_size_t, vp,
-                            vp, vp, vp, vp, C.c_int, C.c_int, vp, vp]
+                            vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, vp, vp]
     lib.cp_critical_path.restype = C.c_int
-    lib.cp_critical_path.argtypes = [vp, C.c_int32, C.c_int32, vp, C.c_int, i64p, i64p, vp, vp, C.c_int,
+    lib.cp_critical_path.argtypes = [vp, C.c_int32, C.c_int32, vp, C.c_int, i64p, i64p, vp, vp, C.c_int, C.c_int,
                                      vp, C.c_size_t, vp, C.c_int32, vp, vp, vp]
     lib.cp_pct_order_workspace_bytes.restype = C.c_int
     lib.cp_pct_order_workspace_bytes.argtypes = [vp, C.c_int32, C.c_int32, C.c_int64, C.POINTER(C.c_size_t)]
     lib.cp_pct_order.restype = C.c_int
-    lib.cp_pct_order.argtypes = [vp, C.c_int32, C.c_int32, vp, C.c_int, vp, C.c_int, C.c_int64,
+    lib.cp_pct_order.argtypes = [vp, C.c_int32, C.c_int32, vp, C.c_int, vp, C.c_int, C.c_int, C.c_int64,
                                  vp, C.c_size_t, vp, vp, vp, vp]
     lib.cp_ranks_workspace_bytes.restype = C.c_int
     lib.cp_ranks_workspace_bytes.argtypes = [vp, C.POINTER(C.c_size_t)]
@@ -246,26 +249,43 @@ class CpProfile:
 
 
 def workspace_bytes(graph: CpGraph, batch: int, k: int, assign_layout=ASSIGN_PARTITION_MAJOR,
-                    plan=PLAN_AUTO) -> int:
+                    plan=PLAN_AUTO, out_layout=OUT_VERTEX_MAJOR, tick_bytes=None) -> int:
     out = C.c_size_t(0)
+    if tick_bytes is None:
+        tick_bytes = graph.info["min_tick_bytes"]
     rc = load_library().cp_eval_workspace_bytes(graph._handle, int(batch), int(k), int(assign_layout),
-                                                int(plan), C.byref(out))
+                                                int(plan), int(out_layout), int(tick_bytes), C.byref(out))
     if rc:
         raise CpError(rc, "cp_eval_workspace_bytes")
     return int(out.value)
 
 
+def choose_plan(graph: CpGraph, batch: int, speeds, bandwidth, tick_bytes=None) -> int:
+    """The plan PLAN_AUTO resolves to for this batch and cost model on the current device."""
+    s = np.ascontiguousarray(speeds, dtype=np.int64)
+    bw = np.ascontiguousarray(bandwidth, dtype=np.int64)
+    if tick_bytes is None:
+        tick_bytes = graph.info["min_tick_bytes"]
+    plan = C.c_int(0)
+    rc = load_library().cp_eval_choose_plan(graph._handle, int(batch), int(s.shape[0]), _np_ptr(s, C.c_int64),
+                                            _np_ptr(bw, C.c_int64), int(tick_bytes), C.byref(plan))
+    if rc:
+        raise CpError(rc, "cp_eval_choose_plan")
+    return int(plan.value)
+
+
 def cp_eval(graph: CpGraph, assignments, speeds, bandwidth, *, want=("cp", "b", "tl", "mask"),
             tick_bytes=None, plan=PLAN_AUTO, assign_layout=ASSIGN_PARTITION_MAJOR,
-            out=None, workspace=None, profile: CpProfile | None = None, stream=None,
-            check_status=True):
+            out_layout=OUT_VERTEX_MAJOR, out=None, workspace=None, profile: CpProfile | None = None,
+            stream=None, check_status=True):
     """cp_eval on torch tensors.
 
     ``assignments``: uint8 CUDA tensor, [batch][n] (or [n][batch] with
     ``assign_layout=ASSIGN_VERTEX_MAJOR``).  Returns a dict with the requested
     tensors: ``cp`` int64 [batch]; ``b``, ``tl`` int32/int64 [n][batch];
-    ``mask`` uint64-as-int64 words [n][ceil(batch/64)]; plus ``status`` (int32
-    tensor).  ``out`` may carry preallocated tensors under the same keys and
+    ``mask`` uint64-as-int64 words [n][ceil(batch/64)] (with
+    ``out_layout=OUT_PARTITION_MAJOR``: [batch][n] and [batch][ceil(n/64)]); plus
+    ``status`` (int32 tensor).  ``out`` may carry preallocated tensors under the same keys and
     ``workspace`` a preallocated uint8 tensor.  With ``check_status`` the stream
     is synchronised and a bad device id raises.
     """
@@ -294,25 +314,25 @@ def cp_eval(graph: CpGraph, assignments, speeds, bandwidth, *, want=("cp", "b", 
         want |= {"cp", "b", "tl"}
     if "cp" in want:
         want.add("b")
-    ncol = (batch + 63) // 64
+    rows, cols = (n, batch) if out_layout == OUT_VERTEX_MAJOR else (batch, n)
     if "cp" in want and "cp" not in out:
         out["cp"] = torch.empty(batch, dtype=torch.int64, device=dev)
     if "b" in want and "b" not in out:
-        out["b"] = torch.empty((n, batch), dtype=tdt, device=dev)
+        out["b"] = torch.empty((rows, cols), dtype=tdt, device=dev)
     if "tl" in want and "tl" not in out:
-        out["tl"] = torch.empty((n, batch), dtype=tdt, device=dev)
+        out["tl"] = torch.empty((rows, cols), dtype=tdt, device=dev)
     if "mask" in want and "mask" not in out:
-        out["mask"] = torch.empty((n, ncol), dtype=torch.int64, device=dev)
+        out["mask"] = torch.empty((rows, (cols + 63) // 64), dtype=torch.int64, device=dev)
     if "status" not in out:
         out["status"] = torch.empty(1, dtype=torch.int32, device=dev)
     if workspace is None:
-        workspace = torch.empty(workspace_bytes(graph, batch, k, assign_layout, plan),
+        workspace = torch.empty(workspace_bytes(graph, batch, k, assign_layout, plan, out_layout, tick_bytes),
                                 dtype=torch.uint8, device=dev)
     ptr = lambda key: C.c_void_p(out[key].data_ptr()) if key in want else C.c_void_p()
     rc = lib.cp_eval(graph._handle, batch, k, C.c_void_p(assignments.data_ptr()), int(assign_layout),
                      _np_ptr(s, C.c_int64), _np_ptr(bw, C.c_int64),
                      C.c_void_p(workspace.data_ptr()), C.c_size_t(workspace.numel()), _stream_ptr(stream),
-                     ptr("cp"), ptr("b"), ptr("tl"), ptr("mask"), int(tick_bytes), int(plan),
+                     ptr("cp"), ptr("b"), ptr("tl"), ptr("mask"), int(tick_bytes), int(out_layout), int(plan),
                      C.c_void_p(out["status"].data_ptr()),
                      C.c_void_p(profile._handle.value) if profile is not None else C.c_void_p())
     if rc:
@@ -327,7 +347,8 @@ def cp_eval(graph: CpGraph, assignments, speeds, bandwidth, *, want=("cp", "b", 
 
 
 def cp_critical_path(graph: CpGraph, assignments, speeds, bandwidth, b, cp, *,
-                     assign_layout=ASSIGN_PARTITION_MAJOR, workspace=None, stream=None, check_status=True):
+                     assign_layout=ASSIGN_PARTITION_MAJOR, b_layout=OUT_VERTEX_MAJOR, workspace=None,
+                     stream=None, check_status=True):
     """cp_critical_path on torch tensors: ``b`` and ``cp`` are outputs of cp_eval for the
     same assignments and cost model.  Returns (paths int32 [batch][L] padded with -1,
     lengths int32 [batch])."""
@@ -348,7 +369,7 @@ def cp_critical_path(graph: CpGraph, assignments, speeds, bandwidth, b, cp, *,
     tick = 4 if b.dtype == torch.int32 else 8
     rc = lib.cp_critical_path(graph._handle, batch, k, C.c_void_p(assignments.data_ptr()), int(assign_layout),
                               _np_ptr(s, C.c_int64), _np_ptr(bw, C.c_int64), C.c_void_p(b.data_ptr()),
-                              C.c_void_p(cp.data_ptr()), tick, C.c_void_p(workspace.data_ptr()),
+                              C.c_void_p(cp.data_ptr()), tick, int(b_layout), C.c_void_p(workspace.data_ptr()),
                               C.c_size_t(workspace.numel()), _stream_ptr(stream), max_len,
                               C.c_void_p(paths.data_ptr()), C.c_void_p(lens.data_ptr()),
                               C.c_void_p(status.data_ptr()))
@@ -365,14 +386,14 @@ STATUS_B_OUT_OF_RANGE = 2
 
 
 def cp_pct_order(graph: CpGraph, assignments, k: int, b, *, max_b: int = 0,
-                 assign_layout=ASSIGN_PARTITION_MAJOR, workspace=None, out=None, stream=None,
-                 check_status=True):
+                 assign_layout=ASSIGN_PARTITION_MAJOR, b_layout=OUT_VERTEX_MAJOR, workspace=None, out=None,
+                 stream=None, check_status=True):
     """cp_pct_order on torch tensors: ``b`` is cp_eval's b-level output for the same
     assignments.  Returns (order int32 [batch][n], seg int32 [batch][k+1])."""
     import torch
     lib = load_library()
     n = graph.info["n"]
-    batch = int(b.shape[1])
+    batch = int(b.shape[1] if b_layout == OUT_VERTEX_MAJOR else b.shape[0])
     dev = b.device
     if workspace is None:
         need = C.c_size_t(0)
@@ -386,7 +407,8 @@ def cp_pct_order(graph: CpGraph, assignments, k: int, b, *, max_b: int = 0,
                "status": torch.empty(1, dtype=torch.int32, device=dev)}
     tick = 4 if b.dtype == torch.int32 else 8
     rc = lib.cp_pct_order(graph._handle, batch, int(k), C.c_void_p(assignments.data_ptr()), int(assign_layout),
-                          C.c_void_p(b.data_ptr()), tick, int(max_b), C.c_void_p(workspace.data_ptr()),
+                          C.c_void_p(b.data_ptr()), tick, int(b_layout), int(max_b),
+                          C.c_void_p(workspace.data_ptr()),
                           C.c_size_t(workspace.numel()), _stream_ptr(stream), C.c_void_p(out["order"].data_ptr()),
                           C.c_void_p(out["seg"].data_ptr()), C.c_void_p(out["status"].data_ptr()))
     if rc:

@@ -111,6 +111,9 @@ bool window_preferred(const Packed &p, const WindowCfg &cb, const WindowCfg &ct,
 }
 
 size_t tables_bytes(int32_t k) { return align_up(table_entries(k) * 8); }
+size_t column_scratch_bytes(const Packed &p, int32_t batch, int tick_bytes) {
+    return align_up((size_t)p.n * (size_t)batch * (size_t)tick_bytes);
+}
 
 int check_eval_sizes(const cp_graph *g, int32_t batch, int32_t k, int assign_layout, int plan) {
     if (!g) return CP_ERR_NULL;
@@ -211,20 +214,48 @@ int cp_graph_upload(cp_graph *g, void *device_blob, size_t blob_bytes, void *str
 void cp_graph_destroy(cp_graph *g) { delete g; }
 
 int cp_eval_workspace_bytes(const cp_graph *g, int32_t batch, int32_t k, int assign_layout,
-                            int plan, size_t *out_bytes) {
+                            int plan, int out_layout, int tick_dtype, size_t *out_bytes) {
     if (!out_bytes) return CP_ERR_NULL;
     int rc = check_eval_sizes(g, batch, k, assign_layout, plan);
     if (rc) return rc;
+    if (out_layout != CP_OUT_VERTEX_MAJOR && out_layout != CP_OUT_PARTITION_MAJOR) return CP_ERR_ARG;
+    if (tick_dtype != CP_TICK_I32 && tick_dtype != CP_TICK_I64) return CP_ERR_ARG;
     size_t bytes = tables_bytes(k);
     // the wave-column plan reads device ids vertex-major; under CP_PLAN_AUTO it may be
     // the one that runs, whatever the graph prefers, if the cost model rules the other out
     size_t column = 0, window = 0;
     if (assign_layout == CP_ASSIGN_PARTITION_MAJOR && plan != CP_PLAN_RESIDENT_WINDOW)
         column = align_up((size_t)g->packed.n * (size_t)batch);
+    // the wave-column plan sweeps vertex-major: partition-major outputs are transposed
+    // out of two scratch arrays
+    if (out_layout == CP_OUT_PARTITION_MAJOR && plan != CP_PLAN_RESIDENT_WINDOW)
+        column += 2 * column_scratch_bytes(g->packed, batch, tick_dtype);
     // the resident-window plan gathers the device ids into sweep order, once per direction
     if (plan != CP_PLAN_WAVE_COLUMN && g->packed.have_window)
         window = pperm_bytes(g->packed, g->packed.win_b, batch) + pperm_bytes(g->packed, g->packed.win_t, batch);
     *out_bytes = bytes + std::max(column, window);
+    return CP_OK;
+}
+
+int cp_eval_choose_plan(const cp_graph *g, int32_t batch, int32_t k, const int64_t *speeds,
+                        const int64_t *bandwidth, int tick_dtype, int *plan_out) {
+    int rc = check_eval_sizes(g, batch, k, CP_ASSIGN_PARTITION_MAJOR, CP_PLAN_AUTO);
+    if (rc) return rc;
+    if (!speeds || !bandwidth || !plan_out) return CP_ERR_NULL;
+    if (tick_dtype != CP_TICK_I32 && tick_dtype != CP_TICK_I64) return CP_ERR_ARG;
+    const Packed &p = g->packed;
+    CostTables tabs;
+    try {
+        rc = build_cost_tables(k, speeds, bandwidth, p.narrow, p.info.max_c, p.info.max_t, tabs);
+    } catch (const std::bad_alloc &) {
+        rc = CP_ERR_ALLOC;
+    }
+    if (rc) return rc;
+    WindowCfg cfg_b, cfg_t;
+    const bool can_window = tabs.magic_ok && window_fits(p, k, (size_t)tick_dtype, device_window_lds_limit(),
+                                                         &cfg_b, &cfg_t);
+    *plan_out = can_window && window_preferred(p, cfg_b, cfg_t, batch, (size_t)tick_dtype)
+                    ? CP_PLAN_RESIDENT_WINDOW : CP_PLAN_WAVE_COLUMN;
     return CP_OK;
 }
 
@@ -233,11 +264,12 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
             const int64_t *speeds, const int64_t *bandwidth,
             void *workspace, size_t workspace_bytes, void *stream,
             int64_t *cp_out, void *blevel_out, void *tlevel_out, uint64_t *mask_out,
-            int tick_dtype, int plan, int32_t *status_out, cp_profile *profile) {
+            int tick_dtype, int out_layout, int plan, int32_t *status_out, cp_profile *profile) {
     int rc = check_eval_sizes(g, batch, k, assign_layout, plan);
     if (rc) return rc;
     if (!assignments || !speeds || !bandwidth || !workspace || !status_out) return CP_ERR_NULL;
     if (tick_dtype != CP_TICK_I32 && tick_dtype != CP_TICK_I64) return CP_ERR_ARG;
+    if (out_layout != CP_OUT_VERTEX_MAJOR && out_layout != CP_OUT_PARTITION_MAJOR) return CP_ERR_ARG;
     if (cp_out && !blevel_out) return CP_ERR_ARG;
     if (mask_out && (!cp_out || !blevel_out || !tlevel_out)) return CP_ERR_ARG;
     if (!g->device_blob) return CP_ERR_STATE;
@@ -269,12 +301,20 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
     size_t need = tables_bytes(k) + (need_pT ? align_up((size_t)p.n * (size_t)batch) : 0);
     if (use == CP_PLAN_RESIDENT_WINDOW)
         need += pperm_bytes(p, p.win_b, batch) + pperm_bytes(p, p.win_t, batch);
+    const bool by_partition = out_layout == CP_OUT_PARTITION_MAJOR;
+    const bool via_scratch = by_partition && use == CP_PLAN_WAVE_COLUMN;
+    const size_t scratch_at = need;
+    if (via_scratch) need += 2 * column_scratch_bytes(p, batch, tick_dtype);
     if (workspace_bytes < need) return CP_ERR_WORKSPACE;
     uint8_t *ws = (uint8_t *)workspace;
     uint8_t *d_tab = ws;
     uint8_t *d_pT = ws + tables_bytes(k);
     uint8_t *d_pperm_b = ws + tables_bytes(k);
     uint8_t *d_pperm_t = d_pperm_b + pperm_bytes(p, p.win_b, batch);
+    // vertex-major sweep results of the wave-column plan when the caller wants rows per partition
+    void *col_b = via_scratch && blevel_out ? (void *)(ws + scratch_at) : blevel_out;
+    void *col_t = via_scratch && tlevel_out ? (void *)(ws + scratch_at + column_scratch_bytes(p, batch, tick_dtype))
+                                            : tlevel_out;
 
     hipStream_t st = (hipStream_t)stream;
     hipEvent_t *ev = nullptr;
@@ -318,6 +358,8 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
     else { s.a_stride_p = 1; s.a_stride_v = batch; }
     s.vert_tab = d_tab + 2 * kk * 8;
     s.status = status_out;
+    if (by_partition) { s.out_sv = 1; s.out_sq = p.n; }
+    else { s.out_sv = batch; s.out_sq = 1; }
     // Device ids reach the resident-window sweep either straight from the caller's rows
     // (16-byte loads: the rows must be contiguous, and whole-buffer size and base must be
     // multiples of 16 so that no load leaves the buffer) or gathered into sweep order first.
@@ -343,7 +385,7 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
         s.tsweep = false;
         s.dir = &p.col_b;
         s.win = &p.win_b;
-        s.val = blevel_out;
+        s.val = use == CP_PLAN_RESIDENT_WINDOW ? blevel_out : col_b;
         s.edge_tab = d_tab;
         s.cp_out = use == CP_PLAN_RESIDENT_WINDOW ? cp_out : nullptr;
         s.pperm = d_pperm_b;
@@ -357,7 +399,11 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
     CP_MARK(CP_STAGE_CP);
     if (cp_out && use == CP_PLAN_WAVE_COLUMN) {
         rc = launch_cp_sources((const int32_t *)(s.blob + p.sources_off), p.info.num_sources,
-                               blevel_out, batch, tick_dtype, cp_out, stream);
+                               col_b, batch, tick_dtype, cp_out, stream);
+        if (rc) return rc;
+    }
+    if (via_scratch && blevel_out) {
+        rc = launch_transpose_ticks(col_b, blevel_out, p.n, batch, tick_dtype, stream);
         if (rc) return rc;
     }
 
@@ -367,7 +413,7 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
         s.tsweep = true;
         s.dir = &p.col_t;
         s.win = &p.win_t;
-        s.val = tlevel_out;
+        s.val = use == CP_PLAN_RESIDENT_WINDOW ? tlevel_out : col_t;
         s.edge_tab = d_tab + kk * 8;
         s.cp_out = nullptr;
         s.pperm = d_pperm_t;
@@ -375,12 +421,16 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
         rc = use == CP_PLAN_RESIDENT_WINDOW ? launch_window_sweep(s, cfg_t, stream, launches ? launches + 1 : nullptr)
                                             : launch_column_sweep(s, stream, launches ? launches + 1 : nullptr);
         if (rc) return rc;
+        if (via_scratch) {
+            rc = launch_transpose_ticks(col_t, tlevel_out, p.n, batch, tick_dtype, stream);
+            if (rc) return rc;
+        }
     }
 
     // ---- stage: mask
     CP_MARK(CP_STAGE_MASK);
     if (mask_out) {
-        rc = launch_mask(blevel_out, tlevel_out, cp_out, p.n, batch, tick_dtype, mask_out, stream);
+        rc = launch_mask(blevel_out, tlevel_out, cp_out, p.n, batch, tick_dtype, by_partition, mask_out, stream);
         if (rc) return rc;
     }
     CP_MARK(CP_NUM_STAGES);
@@ -391,11 +441,12 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
 int cp_critical_path(const cp_graph *g, int32_t batch, int32_t k,
                      const uint8_t *assignments, int assign_layout,
                      const int64_t *speeds, const int64_t *bandwidth,
-                     const void *blevel, const int64_t *cp, int tick_dtype,
+                     const void *blevel, const int64_t *cp, int tick_dtype, int b_layout,
                      void *workspace, size_t workspace_bytes, void *stream,
                      int32_t max_len, int32_t *path_out, int32_t *len_out, int32_t *status_out) {
     int rc = check_eval_sizes(g, batch, k, assign_layout, CP_PLAN_AUTO);
     if (rc) return rc;
+    if (b_layout != CP_OUT_VERTEX_MAJOR && b_layout != CP_OUT_PARTITION_MAJOR) return CP_ERR_ARG;
     if (!assignments || !speeds || !bandwidth || !blevel || !cp || !workspace || !path_out || !len_out ||
         !status_out)
         return CP_ERR_NULL;
@@ -431,6 +482,8 @@ int cp_critical_path(const cp_graph *g, int32_t batch, int32_t k,
     if (assign_layout == CP_ASSIGN_PARTITION_MAJOR) { s.a_stride_p = p.n; s.a_stride_v = 1; }
     else { s.a_stride_p = 1; s.a_stride_v = batch; }
     s.val = const_cast<void *>(blevel);
+    if (b_layout == CP_OUT_PARTITION_MAJOR) { s.out_sv = 1; s.out_sq = p.n; }
+    else { s.out_sv = batch; s.out_sq = 1; }
     s.edge_tab = d_tab;
     s.vert_tab = d_tab + 2 * (size_t)k * k * 8;
     s.status = status_out;
@@ -450,10 +503,11 @@ int cp_pct_order_workspace_bytes(const cp_graph *g, int32_t batch, int32_t k, in
 
 int cp_pct_order(const cp_graph *g, int32_t batch, int32_t k,
                  const uint8_t *assignments, int assign_layout,
-                 const void *blevel, int tick_dtype, int64_t max_b,
+                 const void *blevel, int tick_dtype, int b_layout, int64_t max_b,
                  void *workspace, size_t workspace_bytes, void *stream,
                  int32_t *order_out, int32_t *seg_out, int32_t *status_out) {
     PctPlan plan;
+    if (b_layout != CP_OUT_VERTEX_MAJOR && b_layout != CP_OUT_PARTITION_MAJOR) return CP_ERR_ARG;
     int rc = pct_plan(g, batch, k, max_b, plan);
     if (rc) return rc;
     if (assign_layout != CP_ASSIGN_PARTITION_MAJOR && assign_layout != CP_ASSIGN_VERTEX_MAJOR) return CP_ERR_ARG;
@@ -469,6 +523,7 @@ int cp_pct_order(const cp_graph *g, int32_t batch, int32_t k,
     PctOrderLaunch s;
     s.n = p.n; s.P = batch; s.k = k;
     s.b = blevel;
+    s.b_by_partition = b_layout == CP_OUT_PARTITION_MAJOR;
     s.tick_bytes = tick_dtype;
     s.assign = assignments;
     if (assign_layout == CP_ASSIGN_PARTITION_MAJOR) { s.a_stride_p = p.n; s.a_stride_v = 1; }
@@ -488,7 +543,8 @@ int cp_pct_order(const cp_graph *g, int32_t batch, int32_t k,
 int cp_ranks_workspace_bytes(const cp_graph *g, size_t *out_bytes) {
     if (!g || !out_bytes) return CP_ERR_NULL;
     size_t eval = 0;
-    int rc = cp_eval_workspace_bytes(g, 1, 1, CP_ASSIGN_PARTITION_MAJOR, CP_PLAN_AUTO, &eval);
+    int rc = cp_eval_workspace_bytes(g, 1, 1, CP_ASSIGN_PARTITION_MAJOR, CP_PLAN_AUTO, CP_OUT_VERTEX_MAJOR,
+                                     g->packed.info.min_tick_bytes, &eval);
     if (rc) return rc;
     const size_t n = (size_t)g->packed.n, T = (size_t)g->packed.info.min_tick_bytes;
     *out_bytes = align_up(eval) + align_up(n) + 2 * align_up(n * T) + 2 * kAlign;
@@ -504,7 +560,8 @@ int cp_ranks(const cp_graph *g, void *workspace, size_t workspace_bytes, void *s
     int rc = cp_ranks_workspace_bytes(g, &need);
     if (rc) return rc;
     if (((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < need) return CP_ERR_WORKSPACE;
-    rc = cp_eval_workspace_bytes(g, 1, 1, CP_ASSIGN_PARTITION_MAJOR, CP_PLAN_AUTO, &eval);
+    rc = cp_eval_workspace_bytes(g, 1, 1, CP_ASSIGN_PARTITION_MAJOR, CP_PLAN_AUTO, CP_OUT_VERTEX_MAJOR,
+                                 g->packed.info.min_tick_bytes, &eval);
     if (rc) return rc;
     const Packed &p = g->packed;
     const size_t n = (size_t)p.n, T = (size_t)p.info.min_tick_bytes;
@@ -519,7 +576,7 @@ int cp_ranks(const cp_graph *g, void *workspace, size_t workspace_bytes, void *s
     // one device of speed 1: w(v) = c(v), nothing is ever transferred
     const int64_t one = 1;
     rc = cp_eval(g, 1, 1, d_assign, CP_ASSIGN_PARTITION_MAJOR, &one, &one, ws, align_up(eval), stream, d_cp,
-                 d_b, d_tl, nullptr, (int)T, CP_PLAN_AUTO, d_status, nullptr);
+                 d_b, d_tl, nullptr, (int)T, CP_OUT_VERTEX_MAJOR, CP_PLAN_AUTO, d_status, nullptr);
     if (rc) return rc;
     return launch_ranks(d_b, d_tl, (const uint8_t *)g->device_blob + p.c_off, p.narrow, (int)T, p.n, up_out,
                         down_out, total_out, stream);

@@ -93,7 +93,7 @@ int pack_graph(int32_t n, int64_t m, int32_t L,
 // Multiply-shift form of ceil(a/d) for a 32-bit dividend:
 //   ceil(a/d) = ((a + dm1) * mul + (a + dm1)) >> 32     with dm1 = d-1, mul = ceil(2^32/d) - 1.
 // A free transfer (same device) is the pair {0, 0}, which yields 0 for every a < 2^32.
-struct Magic { uint32_t mul, dm1; };
+struct alignas(8) Magic { uint32_t mul, dm1; };
 
 struct CostTables {
     int32_t k = 0;

@@ -220,17 +220,20 @@ __global__ __launch_bounds__(256) void cp_sources_kernel(const int32_t *__restri
     }
 }
 
-// mask[v][word] bit i = (tl + b == CP) for partition 64*word + i.  A wavefront
-// takes four (vertex, word) tasks per trip so that eight loads are in flight.
-template <typename Tick>
+// Vertex-major (BY_PARTITION = false): b, tl are [n][P] and mask[v][word] bit i =
+// (tl + b == CP) for partition 64*word + i.  Partition-major: b, tl are [P][n] and
+// mask[q][word] bit i belongs to vertex 64*word + i.  Either way rows x cols ticks are
+// read row by row; a wavefront takes four (row, word) tasks per trip so that eight
+// loads are in flight.
+template <typename Tick, bool BY_PARTITION>
 __global__ __launch_bounds__(256) void mask_kernel(const Tick *__restrict__ b,
                                                    const Tick *__restrict__ tl,
-                                                   const int64_t *__restrict__ cp, int32_t n,
-                                                   int32_t P, int32_t ncol, uint64_t *mask) {
+                                                   const int64_t *__restrict__ cp, int32_t rows,
+                                                   int32_t cols, int32_t ncol, uint64_t *mask) {
     const int lane = threadIdx.x & 63;
     const int64_t wave0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
-    const int64_t ntasks = (int64_t)n * ncol;
+    const int64_t ntasks = (int64_t)rows * ncol;
     for (int64_t task0 = wave0 * 4; task0 < ntasks; task0 += nwaves * 4) {
         Tick vb[4], vt[4];
         int64_t c[4];
@@ -238,15 +241,15 @@ __global__ __launch_bounds__(256) void mask_kernel(const Tick *__restrict__ b,
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int64_t task = task0 + u;
-            const int64_t v = task / ncol;
-            const int32_t q = (int32_t)(task % ncol) * 64 + lane;
-            live[u] = task < ntasks && q < P;
+            const int64_t r = task / ncol;
+            const int32_t i = (int32_t)(task % ncol) * 64 + lane;
+            live[u] = task < ntasks && i < cols;
             vb[u] = 0; vt[u] = 0; c[u] = -1;
             if (live[u]) {
-                const size_t at = (size_t)v * P + q;
+                const size_t at = (size_t)r * cols + i;
                 vt[u] = tl[at];
                 vb[u] = b[at];
-                c[u] = cp[q];
+                c[u] = cp[BY_PARTITION ? r : (int64_t)i];
             }
         }
 #pragma unroll
@@ -255,6 +258,20 @@ __global__ __launch_bounds__(256) void mask_kernel(const Tick *__restrict__ b,
             if (lane == 0 && task0 + u < ntasks) mask[task0 + u] = word;
         }
     }
+}
+
+// in[rows][cols] -> out[cols][rows], 64 x 64 tiles through LDS
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_ticks_kernel(const T *__restrict__ in, T *__restrict__ out,
+                                                              int32_t rows, int32_t cols) {
+    __shared__ T tile[64][65];
+    const int lane = threadIdx.x & 63, row0 = threadIdx.x >> 6;
+    const int64_t r0 = (int64_t)blockIdx.x * 64, c0 = (int64_t)blockIdx.y * 64;
+    for (int r = row0; r < 64; r += 4)
+        if (r0 + r < rows && c0 + lane < cols) tile[r][lane] = in[(r0 + r) * cols + c0 + lane];
+    __syncthreads();
+    for (int c = row0; c < 64; c += 4)
+        if (c0 + c < cols && r0 + lane < rows) out[(c0 + c) * rows + r0 + lane] = tile[lane][c];
 }
 
 // ---------------------------------------------------------------- one critical path
@@ -268,7 +285,8 @@ struct PathArgs {
     int32_t nsrc;
     const uint8_t *assign;
     int64_t a_stride_p, a_stride_v;
-    const void *b;           // [n][P] ticks
+    const void *b;           // ticks; b(v, q) sits at v * b_sv + q * b_sq
+    int64_t b_sv, b_sq;
     const int64_t *cp;       // [P]
     const void *edge_tab;    // b-sweep orientation: row = device of the edge's source vertex
     const void *vert_tab;
@@ -289,8 +307,9 @@ __global__ __launch_bounds__(64) void critical_path_kernel(PathArgs a) {
     extern __shared__ __align__(16) uint64_t path_lds[];
     const int lane = threadIdx.x;
     const int32_t q = blockIdx.x;
-    const int32_t P = a.P, k = a.k;
-    const Tick *b = (const Tick *)a.b + q;
+    const int32_t k = a.k;
+    const Tick *b = (const Tick *)a.b + (int64_t)q * a.b_sq;
+    const int64_t bsv = a.b_sv;
     const uint8_t *row = a.assign + (int64_t)q * a.a_stride_p;
     const WT *wt = (const WT *)a.wt;
     const WT *cw = (const WT *)a.c;
@@ -312,7 +331,7 @@ __global__ __launch_bounds__(64) void critical_path_kernel(PathArgs a) {
     int32_t v = 0x7fffffff;
     for (int32_t i = lane; i < a.nsrc; i += 64) {
         const int32_t s = a.sources[i];
-        if ((long long)b[(size_t)s * P] == cpq) v = min(v, s);
+        if ((long long)b[(int64_t)s * bsv] == cpq) v = min(v, s);
     }
     for (int off = 32; off > 0; off >>= 1) v = min(v, __shfl_xor(v, off));
 
@@ -325,7 +344,7 @@ __global__ __launch_bounds__(64) void critical_path_kernel(PathArgs a) {
         const WT cv = cw[v];
         const Tick wv = MAGIC ? (Tick)magic_div((uint32_t)cv, vtab_m[pv])
                               : (Tick)plain_div((uint64_t)cv, (uint64_t)vtab_g[pv]);
-        const Tick rest = b[(size_t)v * P] - wv;
+        const Tick rest = b[(int64_t)v * bsv] - wv;
         const int32_t e0 = a.ptr[v], e1 = a.ptr[v + 1];
         int32_t next = 0x7fffffff;
         for (int32_t e = e0 + lane; e < e1; e += 64) {
@@ -335,7 +354,7 @@ __global__ __launch_bounds__(64) void critical_path_kernel(PathArgs a) {
             const WT te = wt[e];
             const Tick x = MAGIC ? (Tick)magic_div((uint32_t)te, etab_m[pv * k + pu])
                                  : (Tick)plain_div((uint64_t)te, (uint64_t)etab_g[pv * k + pu]);
-            if (x + b[(size_t)u * P] == rest) next = min(next, u);
+            if (x + b[(int64_t)u * bsv] == rest) next = min(next, u);
         }
         for (int off = 32; off > 0; off >>= 1) next = min(next, __shfl_xor(next, off));
         v = next;
@@ -407,6 +426,8 @@ struct WindowArgs {
     int32_t nc, nlw;           // compute and loader wavefronts per workgroup
     int32_t pgroups;           // partitions per XCD-sized group (blockIdx -> partition map)
     int32_t out32;             // 1 if every output index fits 32 bits
+    int64_t out_sq;            // output index of (v, q) = v * out_sv + q * out_sq
+    uint32_t out_sv;
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // stays in registers when indexed statically
@@ -531,8 +552,8 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
     } else {
         // ------------------------------------------------ compute wavefronts
         typedef typename std::conditional<ENT4, uint32_t, uint2>::type Ent;
-        Tick *out = a.out ? (Tick *)a.out + q : nullptr;
-        const uint32_t P = (uint32_t)a.P;
+        Tick *out = a.out ? (Tick *)a.out + (size_t)q * (size_t)a.out_sq : nullptr;
+        const uint32_t out_sv = a.out_sv;
         const uint32_t k8 = 8u * (uint32_t)k;
         const uint32_t rec_off = (uint32_t)a.idpad + 16u * (uint32_t)a.smax;   // records, from the slot base
         const uint32_t row_mis = (uint32_t)((uintptr_t)(a.ids + (size_t)q * a.ids_row) & 15);
@@ -581,8 +602,8 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
                     ring_dev[rs] = (uint8_t)pv;
                 }
                 if (out) {
-                    if (a.out32) out[__umul24(v, P)] = TSWEEP ? acc : fin;
-                    else out[(size_t)v * P] = TSWEEP ? acc : fin;
+                    if (a.out32) out[__umul24(v, out_sv)] = TSWEEP ? acc : fin;
+                    else out[(size_t)v * out_sv] = TSWEEP ? acc : fin;
                 }
                 best = max(best, fin);
             }
@@ -600,18 +621,39 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
             const int rbase = (int)d.w;
             if (width == 0 && lsh == 0 && __builtin_amdgcn_readfirstlane(rows) == 0) return;
             const int p = j * 64 + (lane >> lsh);
-            const uint2 rc = ((const uint2 *)(st + rec_off))[p];
-            // device id: position p of the gathered row, or byte (v - lo) of the staged id
-            // range (padding rows carry v = lo, so every lane reads a byte that was staged)
-            const uint32_t idx = a.direct ? rc.x - lo + ((row_mis + lo) & 15u) : (uint32_t)p;
-            uint32_t pv = st[idx];
-            worst = max(worst, pv);              // checked against k once, after the sweep
-            pv = min(pv, (uint32_t)(k - 1));
-            const uint32_t erow = etab_off + __umul24(pv, k8);
+            const uint2 *rec = (const uint2 *)(st + rec_off) + p;
             const Ent *ent = (const Ent *)(st + a.idpad + ent_off) + lane;
+            const uint32_t id_bias = a.direct ? ((row_mis + lo) & 15u) - lo : 0u;
+            uint2 rc;
+            uint32_t pv;
+            Magic mv;
             Tick acc = 0;
-            // N relaxations as one straight-line block: N entry reads, N ring reads, N
-            // cost-table reads, then the arithmetic -- three LDS round trips whatever N is
+            // The vertex's own reads (record, then its device id, then its cost-table entry)
+            // and the first N relaxations (entries, then ring, then transfer-table entries)
+            // are two chains of three dependent LDS reads; issued side by side they cost
+            // three round trips together.  Device id: position p of the gathered row, or
+            // byte (v - lo) of the staged id range (padding rows carry v = lo, so every lane
+            // reads a byte that was staged); it is checked against k once, after the sweep.
+#define CP_HEAD(N)                                                                              \
+    do {                                                                                        \
+        Ent en_[N + 1];                                                                         \
+        Tick vu_[N + 1];                                                                        \
+        uint32_t pu8_[N + 1];                                                                   \
+        Magic mg_[N + 1];                                                                       \
+        rc = *rec;                                                                              \
+        _Pragma("unroll") for (int i_ = 0; i_ < N; ++i_) en_[i_] = ent[i_ * 64];                \
+        pv = st[a.direct ? rc.x + id_bias : (uint32_t)p];                                       \
+        _Pragma("unroll") for (int i_ = 0; i_ < N; ++i_) ring_get(ent_field(en_[i_]), vu_[i_], pu8_[i_]); \
+        worst = max(worst, pv);                                                                 \
+        pv = min(pv, (uint32_t)(k - 1));                                                        \
+        erow = etab_off + __umul24(pv, k8);                                                     \
+        mv = *(const Magic *)(lds + vtab_off + 8u * pv);                                        \
+        _Pragma("unroll") for (int i_ = 0; i_ < N; ++i_) mg_[i_] = *(const Magic *)(lds + erow + pu8_[i_]); \
+        _Pragma("unroll") for (int i_ = 0; i_ < N; ++i_)                                        \
+            acc = max(acc, (Tick)(vu_[i_] + (Tick)magic_div(ent_t(en_[i_]), mg_[i_])));         \
+    } while (0)
+            // N further relaxations as one straight-line block: N entry reads, N ring reads,
+            // N cost-table reads, then the arithmetic -- three LDS round trips whatever N is
 #define CP_BLOCK(N)                                                                             \
     do {                                                                                        \
         Ent en_[N];                                                                             \
@@ -624,7 +666,19 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
         _Pragma("unroll") for (int i_ = 0; i_ < N; ++i_)                                        \
             acc = max(acc, (Tick)(vu_[i_] + (Tick)magic_div(ent_t(en_[i_]), mg_[i_])));         \
     } while (0)
-            int jj = 0;
+            uint32_t erow;
+            switch (min(width, 8)) {
+                case 0: CP_HEAD(0); break;
+                case 1: CP_HEAD(1); break;
+                case 2: CP_HEAD(2); break;
+                case 3: CP_HEAD(3); break;
+                case 4: CP_HEAD(4); break;
+                case 5: CP_HEAD(5); break;
+                case 6: CP_HEAD(6); break;
+                case 7: CP_HEAD(7); break;
+                default: CP_HEAD(8); break;
+            }
+            int jj = 8;
             for (; jj + 8 <= width; jj += 8) CP_BLOCK(8);
             switch (width - jj) {
                 case 1: CP_BLOCK(1); break;
@@ -637,8 +691,8 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
                 default: break;
             }
 #undef CP_BLOCK
+#undef CP_HEAD
             acc = fold(acc, lsh);
-            const Magic mv = *(const Magic *)(lds + vtab_off + 8u * pv);
             publish(acc, (Tick)magic_div(rc.y, mv), lsh, rows, rbase, rc.x, pv);
         };
 
@@ -729,6 +783,8 @@ int launch_window_sweep_k(const SweepLaunch &s, const WindowCfg &cfg, hipStream_
     a.P = s.P; a.L = dir.ticks; a.k = s.k; a.slots = dir.slots; a.wpad = dir.wpad; a.smax = dir.smax;
     a.nc = cfg.nc; a.nlw = cfg.nlw;
     a.out32 = s.n < (1 << 24) && s.P < (1 << 24) && (uint64_t)s.n * (uint64_t)s.P < (1ull << 31);
+    a.out_sq = s.out_sq;
+    a.out_sv = (uint32_t)s.out_sv;
     a.pgroups = (s.P + 7) / 8;
     auto kern = window_sweep_kernel<Tick, TSWEEP, PACKED, ENT4, NL, DR>;
     if (cfg.lds_bytes > 64 * 1024) {
@@ -886,6 +942,8 @@ int launch_critical_path(const SweepLaunch &s, const int32_t *sources, int32_t n
     a.a_stride_p = s.a_stride_p;
     a.a_stride_v = s.a_stride_v;
     a.b = s.val;
+    a.b_sv = s.out_sv;
+    a.b_sq = s.out_sq;
     a.cp = cp;
     a.edge_tab = s.edge_tab;
     a.vert_tab = s.vert_tab;
@@ -919,16 +977,32 @@ int launch_critical_path(const SweepLaunch &s, const int32_t *sources, int32_t n
 }
 
 int launch_mask(const void *b, const void *tl, const int64_t *cp, int32_t n, int32_t P,
-                int tick_bytes, uint64_t *mask, void *stream) {
-    const int ncol = (P + 63) / 64;
-    const int64_t tasks = (int64_t)n * ncol;
-    const unsigned blocks = (unsigned)std::max<int64_t>(1, std::min<int64_t>((tasks + 15) / 16, 256 * 32));
+                int tick_bytes, bool by_partition, uint64_t *mask, void *stream) {
+    const int32_t rows = by_partition ? P : n, cols = by_partition ? n : P;
+    const int ncol = (cols + 63) / 64;
+    const int64_t tasks = (int64_t)rows * ncol;
+    const dim3 grid((unsigned)std::max<int64_t>(1, std::min<int64_t>((tasks + 15) / 16, 256 * 32))), block(256);
+    hipStream_t st = (hipStream_t)stream;
+#define CP_MASK(TICK, BYP)                                                                              \
+    hipLaunchKernelGGL((mask_kernel<TICK, BYP>), grid, block, 0, st, (const TICK *)b, (const TICK *)tl, cp, \
+                       rows, cols, ncol, mask)
+    if (tick_bytes == 4) {
+        if (by_partition) CP_MASK(int32_t, true); else CP_MASK(int32_t, false);
+    } else {
+        if (by_partition) CP_MASK(int64_t, true); else CP_MASK(int64_t, false);
+    }
+#undef CP_MASK
+    return hip_ok(hipGetLastError());
+}
+
+int launch_transpose_ticks(const void *in, void *out, int32_t rows, int32_t cols, int tick_bytes, void *stream) {
+    const dim3 grid((unsigned)((rows + 63) / 64), (unsigned)((cols + 63) / 64)), block(256);
     if (tick_bytes == 4)
-        hipLaunchKernelGGL(mask_kernel<int32_t>, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
-                           (const int32_t *)b, (const int32_t *)tl, cp, n, P, ncol, mask);
+        hipLaunchKernelGGL(transpose_ticks_kernel<int32_t>, grid, block, 0, (hipStream_t)stream,
+                           (const int32_t *)in, (int32_t *)out, rows, cols);
     else
-        hipLaunchKernelGGL(mask_kernel<int64_t>, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
-                           (const int64_t *)b, (const int64_t *)tl, cp, n, P, ncol, mask);
+        hipLaunchKernelGGL(transpose_ticks_kernel<int64_t>, grid, block, 0, (hipStream_t)stream,
+                           (const int64_t *)in, (int64_t *)out, rows, cols);
     return hip_ok(hipGetLastError());
 }
 

@@ -22,7 +22,9 @@ struct SweepLaunch {
     const uint8_t *pperm = nullptr;     // [P][ticks*wpad] device ids in sweep order (resident-window)
     bool direct_ids = false;            // resident-window: stage ids straight from `assign`
     int64_t a_stride_p = 0, a_stride_v = 0;
-    void *val = nullptr;                // [n][P] ticks
+    void *val = nullptr;                // ticks of (v, q) at v * out_sv + q * out_sq (resident-window sweep,
+                                        // critical-path walk); the wave-column sweep writes [n][P]
+    int64_t out_sv = 0, out_sq = 1;
     int64_t *cp_out = nullptr;          // resident-window b sweep only
     const void *edge_tab = nullptr;
     const void *vert_tab = nullptr;
@@ -52,7 +54,8 @@ int launch_cp_sources(const int32_t *sources, int32_t nsrc, const void *b, int32
 // One segmented radix sort per call: the PCT priority lists of section 4.1.
 struct PctOrderLaunch {
     int32_t n = 0, P = 0, k = 0;
-    const void *b = nullptr;          // ticks [n][P]
+    const void *b = nullptr;          // ticks [n][P], or [P][n] with b_by_partition
+    bool b_by_partition = false;
     int tick_bytes = 4;
     const uint8_t *assign = nullptr;
     int64_t a_stride_p = 0, a_stride_v = 0;
@@ -72,6 +75,7 @@ int launch_ranks(const void *b, const void *tl, const void *c, bool narrow, int 
 int launch_critical_path(const SweepLaunch &s, const int32_t *sources, int32_t nsrc, const int64_t *cp,
                          int32_t max_len, int32_t *path, int32_t *len, void *stream);
 int launch_mask(const void *b, const void *tl, const int64_t *cp, int32_t n, int32_t P,
-                int tick_bytes, uint64_t *mask, void *stream);
+                int tick_bytes, bool by_partition, uint64_t *mask, void *stream);
+int launch_transpose_ticks(const void *in, void *out, int32_t rows, int32_t cols, int tick_bytes, void *stream);
 
 }  // namespace cpeval

@@ -12,6 +12,7 @@
 // (digit, tile) order, and a stable scatter.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdint>
 
 #include "cpeval_internal.hpp"
@@ -80,6 +81,23 @@ __global__ __launch_bounds__(256) void pct_keys_kernel(KeyArgs a) {
             }
             keys[q * a.n + v] = key;
         }
+    }
+    if (bad_id) atomicOr(a.status, CP_STATUS_BAD_DEVICE_ID);
+    if (bad_b) atomicOr(a.status, CP_STATUS_B_OUT_OF_RANGE);
+}
+
+// The same from b laid out [P][n]: no transpose, one key per thread.
+template <typename Tick, typename Key>
+__global__ __launch_bounds__(256) void pct_keys_rows_kernel(KeyArgs a) {
+    const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= a.n) return;
+    bool bad_b = false, bad_id = false;
+    for (int64_t q = blockIdx.y; q < a.P; q += gridDim.y) {
+        long long bv = (long long)((const Tick *)a.b)[q * a.n + v];
+        if (bv < 0 || bv > a.max_b) { bad_b = true; bv = bv < 0 ? 0 : a.max_b; }
+        uint32_t dev = a.assign[q * a.a_stride_p + v * a.a_stride_v];
+        if (dev >= (uint32_t)a.k) { bad_id = true; dev = (uint32_t)a.k - 1; }
+        ((Key *)a.keys)[q * a.n + v] = (Key)(a.max_b - bv) | (Key)dev << a.bb;
     }
     if (bad_id) atomicOr(a.status, CP_STATUS_BAD_DEVICE_ID);
     if (bad_b) atomicOr(a.status, CP_STATUS_B_OUT_OF_RANGE);
@@ -320,14 +338,24 @@ int launch_pct_order(const PctOrderLaunch &s, void *stream) {
     a.status = s.status;
     a.max_b = s.max_b;
     a.n = s.n; a.P = s.P; a.k = s.k; a.bb = s.b_bits;
-    const dim3 kgrid((unsigned)((s.n + 63) / 64), (unsigned)((s.P + 63) / 64));
-    if (s.key_bytes == 4) {
-        if (s.tick_bytes == 4) hipLaunchKernelGGL((pct_keys_kernel<int32_t, uint32_t>), kgrid, dim3(256), 0, st, a);
-        else hipLaunchKernelGGL((pct_keys_kernel<int64_t, uint32_t>), kgrid, dim3(256), 0, st, a);
+#define CP_KEYS(KERNEL, GRID)                                                                         \
+    do {                                                                                              \
+        if (s.key_bytes == 4) {                                                                       \
+            if (s.tick_bytes == 4) hipLaunchKernelGGL((KERNEL<int32_t, uint32_t>), GRID, dim3(256), 0, st, a); \
+            else hipLaunchKernelGGL((KERNEL<int64_t, uint32_t>), GRID, dim3(256), 0, st, a);          \
+        } else {                                                                                      \
+            if (s.tick_bytes == 4) hipLaunchKernelGGL((KERNEL<int32_t, uint64_t>), GRID, dim3(256), 0, st, a); \
+            else hipLaunchKernelGGL((KERNEL<int64_t, uint64_t>), GRID, dim3(256), 0, st, a);          \
+        }                                                                                             \
+    } while (0)
+    if (s.b_by_partition) {
+        const dim3 kgrid((unsigned)((s.n + 255) / 256), (unsigned)std::min(s.P, 65535));
+        CP_KEYS(pct_keys_rows_kernel, kgrid);
     } else {
-        if (s.tick_bytes == 4) hipLaunchKernelGGL((pct_keys_kernel<int32_t, uint64_t>), kgrid, dim3(256), 0, st, a);
-        else hipLaunchKernelGGL((pct_keys_kernel<int64_t, uint64_t>), kgrid, dim3(256), 0, st, a);
+        const dim3 kgrid((unsigned)((s.n + 63) / 64), (unsigned)((s.P + 63) / 64));
+        CP_KEYS(pct_keys_kernel, kgrid);
     }
+#undef CP_KEYS
     if (hipGetLastError() != hipSuccess) return CP_ERR_HIP;
     int rc = s.key_bytes == 4 ? run_sort<uint32_t>(s, st) : run_sort<uint64_t>(s, st);
     if (rc) return rc;

@@ -4,7 +4,8 @@ import numpy as np
 
 
 def run_gpu(w, plan, tick_bytes=None, want=("cp", "b", "tl", "mask"), layout=0, graph=None,
-            speeds=None, bandwidth=None, assignments=None):
+            speeds=None, bandwidth=None, assignments=None, out_layout=0):
+    """Returns host arrays in the oracle's orientation ([P][n]) whatever the two layouts."""
     import torch
     import paper_1711_01912_amd as cpe
     from paper_1711_01912_amd import binding
@@ -14,28 +15,30 @@ def run_gpu(w, plan, tick_bytes=None, want=("cp", "b", "tl", "mask"), layout=0, 
     a = torch.from_numpy(np.ascontiguousarray(a_host if layout == 0 else a_host.T)).to("cuda:0")
     out = cpe.cp_eval(g, a, w.speeds if speeds is None else speeds,
                       w.bandwidth if bandwidth is None else bandwidth,
-                      want=want, plan=plan, tick_bytes=tick_bytes, assign_layout=layout)
+                      want=want, plan=plan, tick_bytes=tick_bytes, assign_layout=layout, out_layout=out_layout)
+    orient = (lambda x: x.T) if out_layout == 0 else (lambda x: x)
     res = {}
     if "cp" in out:
         res["cp"] = out["cp"].cpu().numpy()
     if "b" in out:
-        res["b"] = out["b"].cpu().numpy()
+        res["b"] = orient(out["b"].cpu().numpy())
+        assert res["b"].shape == (P, w.n)
     if "tl" in out:
-        res["tl"] = out["tl"].cpu().numpy()
+        res["tl"] = orient(out["tl"].cpu().numpy())
     if "mask" in out and "mask" in want:
-        res["mask"] = binding.mask_to_bool(out["mask"], P)
+        res["mask"] = orient(binding.mask_to_bool(out["mask"], P if out_layout == 0 else w.n))
     return res
 
 
 def assert_equal_to_oracle(res, ref, what=""):
-    """GPU arrays are [n][P]; the oracle's are [P][n]."""
+    """Both sides as [P][n]."""
     assert np.array_equal(res["cp"], ref["cp"]), f"{what}: CP differs"
     for key in ("b", "tl"):
         if key in res:
-            got = res[key].T
+            got = res[key]
             bad = np.nonzero(got != ref[key])
             assert bad[0].size == 0, (f"{what}: {key} differs at {bad[0].size} places, first "
                                       f"(partition {bad[0][0]}, vertex {bad[1][0]}): "
                                       f"{got[bad[0][0], bad[1][0]]} vs {ref[key][bad[0][0], bad[1][0]]}")
     if "mask" in res:
-        assert np.array_equal(res["mask"].T, ref["mask"]), f"{what}: mask differs"
+        assert np.array_equal(res["mask"], ref["mask"]), f"{what}: mask differs"

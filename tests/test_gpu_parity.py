@@ -25,15 +25,17 @@ def _oracle(oracle, w, **kw):
     return oracle.evaluate_workload(w, threads=16, **kw)
 
 
-def _check(gpu, oracle, w, plans=(COLUMN, WINDOW), ticks=(None,), layouts=(0,), what=None):
+def _check(gpu, oracle, w, plans=(COLUMN, WINDOW), ticks=(None,), layouts=(0,), out_layouts=(0, 1), what=None):
     from gpu_util import assert_equal_to_oracle, run_gpu
     ref = _oracle(oracle, w)
     g = gpu.CpGraph.from_workload(w, device="cuda:0")
     for plan in plans:
         for tb in ticks:
             for layout in layouts:
-                res = run_gpu(w, plan, tick_bytes=tb, layout=layout, graph=g)
-                assert_equal_to_oracle(res, ref, what=f"{what or w.name} plan={plan} ticks={tb} layout={layout}")
+                for ol in out_layouts:
+                    res = run_gpu(w, plan, tick_bytes=tb, layout=layout, graph=g, out_layout=ol)
+                    assert_equal_to_oracle(res, ref, what=f"{what or w.name} plan={plan} ticks={tb} "
+                                                          f"layout={layout} out_layout={ol}")
     g.close()
     return ref
 
@@ -266,11 +268,11 @@ def test_partial_outputs_and_determinism(gpu, oracle):
     ref = _oracle(oracle, w)
     for plan in (COLUMN, WINDOW):
         r1 = run_gpu(w, plan, want=("b",))
-        assert np.array_equal(r1["b"].T, ref["b"]) and "tl" not in r1
+        assert np.array_equal(r1["b"], ref["b"]) and "tl" not in r1
         r2 = run_gpu(w, plan, want=("cp",))
         assert np.array_equal(r2["cp"], ref["cp"])
         r3 = run_gpu(w, plan, want=("tl",))
-        assert np.array_equal(r3["tl"].T, ref["tl"])
+        assert np.array_equal(r3["tl"], ref["tl"])
         r4 = run_gpu(w, plan)
         r5 = run_gpu(w, plan)
         for key in ("cp", "b", "tl", "mask"):
@@ -283,8 +285,8 @@ def test_one_column_equals_its_column_in_a_batch(gpu):
     full = run_gpu(w, WINDOW)
     for plan in (COLUMN, WINDOW):
         one = run_gpu(w, plan, assignments=w.assignments[77:78])
-        assert np.array_equal(one["b"][:, 0], full["b"][:, 77])
-        assert np.array_equal(one["tl"][:, 0], full["tl"][:, 77])
+        assert np.array_equal(one["b"][0], full["b"][77])
+        assert np.array_equal(one["tl"][0], full["tl"][77])
         assert one["cp"][0] == full["cp"][77]
 
 
@@ -295,12 +297,14 @@ def _check_paths(gpu, oracle, w, layout=0):
     g = gpu.CpGraph.from_workload(w, device="cuda:0")
     a_host = w.assignments if layout == 0 else np.ascontiguousarray(w.assignments.T)
     a = torch.from_numpy(a_host).to("cuda:0")
-    out = gpu.cp_eval(g, a, w.speeds, w.bandwidth, want=("cp", "b"), assign_layout=layout)
-    paths, lens = gpu.cp_critical_path(g, a, w.speeds, w.bandwidth, out["b"], out["cp"], assign_layout=layout)
     ref_p, ref_l = oracle.critical_path(w.n, w.succ_ptr, w.succ_idx, w.succ_t, w.c, w.speeds, w.bandwidth,
                                         w.assignments, max_len=w.L)
-    assert np.array_equal(lens.cpu().numpy(), ref_l)
-    assert np.array_equal(paths.cpu().numpy(), ref_p)
+    for ol in (0, 1):
+        out = gpu.cp_eval(g, a, w.speeds, w.bandwidth, want=("cp", "b"), assign_layout=layout, out_layout=ol)
+        paths, lens = gpu.cp_critical_path(g, a, w.speeds, w.bandwidth, out["b"], out["cp"],
+                                           assign_layout=layout, b_layout=ol)
+        assert np.array_equal(lens.cpu().numpy(), ref_l)
+        assert np.array_equal(paths.cpu().numpy(), ref_p)
     g.close()
 
 
@@ -368,16 +372,18 @@ def _check_pct_order(gpu, oracle, w, layout=0, max_b="cp", sample=None):
     g = gpu.CpGraph.from_workload(w, device="cuda:0")
     a_host = w.assignments if layout == 0 else np.ascontiguousarray(w.assignments.T)
     a = torch.from_numpy(a_host).to("cuda:0")
-    out = gpu.cp_eval(g, a, w.speeds, w.bandwidth, want=("cp", "b"), assign_layout=layout)
-    bound = int(out["cp"].max().item()) if max_b == "cp" else max_b
-    order, seg = gpu.cp_pct_order(g, a, w.k, out["b"], max_b=bound, assign_layout=layout)
     rows = slice(0, w.P) if sample is None else slice(0, sample)
-    b_host = np.ascontiguousarray(out["b"].cpu().numpy().T[rows]).astype(np.int64)
     ref_b = oracle.evaluate_workload(w, want=("b",), threads=8, partitions=rows)["b"]
-    assert np.array_equal(b_host, ref_b)
     ref_order, ref_seg = oracle.pct_order(w.k, w.assignments[rows], ref_b, threads=8)
-    assert np.array_equal(seg.cpu().numpy()[rows], ref_seg)
-    assert np.array_equal(order.cpu().numpy()[rows], ref_order)
+    for ol in (0, 1):
+        out = gpu.cp_eval(g, a, w.speeds, w.bandwidth, want=("cp", "b"), assign_layout=layout, out_layout=ol)
+        bound = int(out["cp"].max().item()) if max_b == "cp" else max_b
+        order, seg = gpu.cp_pct_order(g, a, w.k, out["b"], max_b=bound, assign_layout=layout, b_layout=ol)
+        b_host = out["b"].cpu().numpy()
+        b_host = np.ascontiguousarray((b_host.T if ol == 0 else b_host)[rows]).astype(np.int64)
+        assert np.array_equal(b_host, ref_b)
+        assert np.array_equal(seg.cpu().numpy()[rows], ref_seg)
+        assert np.array_equal(order.cpu().numpy()[rows], ref_order)
     g.close()
 
 

@@ -167,6 +167,11 @@ def test_workspace_bytes_and_eval_argument_errors(lib):
     assert binding.workspace_bytes(g, 16, 2, plan=cpe.PLAN_RESIDENT_WINDOW) == 256 + 2 * 16 * 8 * 64
     assert binding.workspace_bytes(g, 16, 2, plan=cpe.PLAN_WAVE_COLUMN) == 256 + 1024
     assert binding.workspace_bytes(g, 16, 2) == 256 + 2 * 16 * 8 * 64
+    # partition-major outputs of the wave-column plan pass through two vertex-major scratch arrays
+    assert binding.workspace_bytes(g, 16, 2, plan=cpe.PLAN_WAVE_COLUMN, out_layout=cpe.OUT_PARTITION_MAJOR,
+                                   tick_bytes=4) == 256 + 1024 + 2 * 64 * 16 * 4
+    assert binding.workspace_bytes(g, 16, 2, plan=cpe.PLAN_RESIDENT_WINDOW, out_layout=cpe.OUT_PARTITION_MAJOR,
+                                   tick_bytes=4) == 256 + 2 * 16 * 8 * 64
     with pytest.raises(cpe.CpError) as e:
         binding.workspace_bytes(g, 0, 2)
     assert e.value.code == -2
@@ -180,9 +185,9 @@ def test_workspace_bytes_and_eval_argument_errors(lib):
     i64p = C.POINTER(C.c_int64)
 
     def call(batch=4, k=2, assign=dummy, layout=0, sp=s, bw=B, ws=dummy, cp=dummy, b=dummy, tl=dummy,
-             mask=dummy, tick=4, plan=0, status=dummy):
+             mask=dummy, tick=4, plan=0, status=dummy, out_layout=0):
         return lib.cp_eval(g._handle, batch, k, assign, layout, sp.ctypes.data_as(i64p),
-                           bw.ctypes.data_as(i64p), ws, 1 << 20, None, cp, b, tl, mask, tick, plan,
+                           bw.ctypes.data_as(i64p), ws, 1 << 20, None, cp, b, tl, mask, tick, out_layout, plan,
                            status, None)
 
     assert call(batch=0) == -2
@@ -190,6 +195,7 @@ def test_workspace_bytes_and_eval_argument_errors(lib):
     assert call(layout=7) == -12
     assert call(plan=9) == -12
     assert call(tick=2) == -12
+    assert call(out_layout=2) == -12
     assert call(assign=C.c_void_p()) == -1
     assert call(status=C.c_void_p()) == -1
     assert call(b=C.c_void_p()) == -12            # cp needs b
