@@ -69,6 +69,9 @@ def main():
                     help="layout of b, tl and the mask; native = the one the plan that runs produces directly "
                          "(partition-major for the resident-window plan, vertex-major for wave-column)")
     ap.add_argument("--cpu-sample", type=int, default=32, help="partitions the oracle is timed on (0 = skip)")
+    ap.add_argument("--extras", action="store_true",
+                    help="after the timed steps also time the consumers of the result (priority lists, one "
+                         "critical path per partition) and report them under 'extras'")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB (a known-size kernel to scale "
                          "hardware byte counters against)")
@@ -157,6 +160,30 @@ def main():
         "compulsory_frac": (n * P * (1 + T)) / (b_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
     }
 
+    extras = None
+    if args.extras:
+        extras = {}
+        b_layout = out_layout
+        max_b = int(out["cp"].max().item())
+
+        def timed(fn, reps=5):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+
+        ms = timed(lambda: cpe.cp_pct_order(g, a, w.k, out["b"], max_b=max_b, b_layout=b_layout, check_status=False))
+        extras["pct_order"] = {"ms": ms, "keys_per_s": n * P / (ms * 1e-3), "key_bits": max_b.bit_length()
+                               + (w.k - 1).bit_length()}
+        ms = timed(lambda: cpe.cp_critical_path(g, a, w.speeds, w.bandwidth, out["b"], out["cp"],
+                                                b_layout=b_layout, check_status=False))
+        extras["critical_path"] = {"ms": ms}
+
     cpu = None
     if args.cpu_sample > 0:
         from oracle import cp_oracle
@@ -188,6 +215,8 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
+    if extras is not None:
+        rec["extras"] = extras
     print(json.dumps(rec))
 
 

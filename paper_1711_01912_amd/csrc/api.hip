@@ -366,6 +366,13 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
     const bool rows_ok = assign_layout == CP_ASSIGN_PARTITION_MAJOR &&
                          ((uint64_t)p.n * (uint64_t)batch) % 16 == 0 && ((uintptr_t)assignments % 16) == 0;
     const bool direct_b = rows_ok && p.win_b.direct_ok, direct_t = rows_ok && p.win_t.direct_ok;
+    // With rows per partition the t sweep can write the mask as it goes: it needs the tick's b
+    // values staged like the device ids (16-byte loads that must stay inside the b array).
+    WindowCfg cfg_tm;
+    const bool fuse_mask = use == CP_PLAN_RESIDENT_WINDOW && by_partition && mask_out && direct_t &&
+                           tick_dtype == CP_TICK_I32 && ((uintptr_t)blevel_out % 16) == 0 &&
+                           ((uint64_t)p.n * (uint64_t)batch * 4) % 16 == 0 &&
+                           window_config(p.win_t, k, (size_t)tick_dtype, device_window_lds_limit(), cfg_tm, true);
     if (use == CP_PLAN_RESIDENT_WINDOW) {
         if (blevel_out && !direct_b) {
             s.win = &p.win_b;
@@ -418,8 +425,17 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
         s.cp_out = nullptr;
         s.pperm = d_pperm_t;
         s.direct_ids = direct_t;
-        rc = use == CP_PLAN_RESIDENT_WINDOW ? launch_window_sweep(s, cfg_t, stream, launches ? launches + 1 : nullptr)
-                                            : launch_column_sweep(s, stream, launches ? launches + 1 : nullptr);
+        if (fuse_mask) {
+            // the t sweep sets the mask bits itself (tl + b = CP is known when a vertex is published)
+            rc = launch_zero_words(mask_out, (int64_t)batch * (((int64_t)p.n + 63) / 64), stream);
+            if (rc) return rc;
+            s.mask_b = blevel_out;
+            s.mask_cp = cp_out;
+            s.mask_out = mask_out;
+        }
+        rc = use == CP_PLAN_RESIDENT_WINDOW
+                 ? launch_window_sweep(s, fuse_mask ? cfg_tm : cfg_t, stream, launches ? launches + 1 : nullptr)
+                 : launch_column_sweep(s, stream, launches ? launches + 1 : nullptr);
         if (rc) return rc;
         if (via_scratch) {
             rc = launch_transpose_ticks(col_t, tlevel_out, p.n, batch, tick_dtype, stream);
@@ -429,7 +445,7 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
 
     // ---- stage: mask
     CP_MARK(CP_STAGE_MASK);
-    if (mask_out) {
+    if (mask_out && !fuse_mask) {
         rc = launch_mask(blevel_out, tlevel_out, cp_out, p.n, batch, tick_dtype, by_partition, mask_out, stream);
         if (rc) return rc;
     }

@@ -19,6 +19,7 @@ constexpr size_t kLdsBudget = 160 * 1024;   // LDS per workgroup on gfx950
 constexpr int kWindowMaxWaves = 16;      // wavefronts per workgroup (compute + loader)
 constexpr int kWindowTickSlices = 8;     // slices (compute wavefronts) per tick
 constexpr uint64_t kWindowTickBytes = 15 * 1024;   // packet bytes per tick, unless one slice alone is larger
+constexpr int kMaskWords = 72;           // 32-bit mask words one tick's id range may touch (fused mask)
 
 inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
 

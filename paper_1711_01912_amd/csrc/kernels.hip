@@ -59,6 +59,11 @@ __global__ void clear_kernel(int64_t *cp_out, int32_t batch, int32_t *status) {
     if (i == 0) *status = CP_STATUS_OK;
 }
 
+__global__ void zero_words_kernel(uint64_t *dst, int64_t words) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < words; i += (int64_t)gridDim.x * blockDim.x)
+        dst[i] = 0;
+}
+
 __global__ void zero_bytes_kernel(uint8_t *dst, int64_t bytes) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < bytes) dst[i] = 0;
@@ -428,6 +433,13 @@ struct WindowArgs {
     int32_t out32;             // 1 if every output index fits 32 bits
     int64_t out_sq;            // output index of (v, q) = v * out_sv + q * out_sq
     uint32_t out_sv;
+    // t sweep that also writes the critical-vertex mask (partition-major rows only)
+    const void *bvals;         // b [P][n]
+    const int64_t *cp_in;      // [P]
+    uint32_t *mask32;          // mask rows as 32-bit words, zeroed by the caller
+    int64_t mask_row32;        // 32-bit words per mask row
+    int64_t n;                 // vertices (row length of bvals)
+    int32_t bpad;              // bytes a stage slot reserves for the tick's b values (0: no mask)
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // stays in registers when indexed statically
@@ -444,10 +456,12 @@ typedef const uint32_t __attribute__((address_space(4))) *const_u32_ptr;   // un
 // loaders copy packet t+1 (requested DR ticks earlier, held in registers) into
 // the other slot and request packet t+1+DR.  Nothing on the level-to-level
 // dependency touches memory beyond LDS.
-template <typename Tick, bool TSWEEP, bool PACKED, bool ENT4, int NL, int DR>
+template <typename Tick, bool TSWEEP, bool PACKED, bool ENT4, int NL, int DR, bool MASK>
 __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(WindowArgs a) {
     extern __shared__ uint4 lds16[];
     __shared__ long long red[kWindowMaxWaves];
+    // MASK: bits of the tick's critical vertices, by (v - (lo & ~31)) / 32; two ticks in flight
+    __shared__ uint32_t mbits[MASK ? 2 : 1][MASK ? kMaskWords : 1];
     uint8_t *lds = (uint8_t *)lds16;
     const int tid = threadIdx.x, lane = tid & 63, nt = blockDim.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -472,6 +486,8 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
         uint64_t *t64 = (uint64_t *)(lds + etab_off);
         for (int i = tid; i < k * k; i += nt) t64[i] = e[i];
         for (int i = tid; i < k; i += nt) t64[k * k + i] = v[i];
+        if constexpr (MASK)
+            for (int i = tid; i < 2 * kMaskWords; i += nt) (&mbits[0][0])[i] = 0;
         if (tid == 0) {                      // the constant-zero slot padding entries point at
             if (PACKED) {
                 ((uint2 *)lds)[R] = make_uint2(0, 0);
@@ -484,6 +500,8 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
 
     const int Lpad = (L + DR - 1) / DR * DR;
     const int id16 = a.idpad / 16;               // 16-byte chunks of a slot that hold device ids
+    const int b16 = MASK ? a.bpad / 16 : 0;      // ... and the tick's b values
+    const int head = a.idpad + (MASK ? a.bpad : 0);   // bytes of a slot before the packet
     Tick best = 0;
 
     if (wave >= a.nc) {
@@ -494,15 +512,19 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
         // id16 of a slot) or a packet chunk is therefore fixed too
         int cid[NL];
         const uint4 *base[NL];
-        bool is_id[NL];
+        bool is_id[NL], is_b[NL];
         const uint8_t *row = a.ids + (size_t)q * a.ids_row;
         // direct staging starts at the 16-byte boundary below the tick's lowest id
         const uint32_t row_mis = (uint32_t)((uintptr_t)row & 15);
+        const uint8_t *brow = MASK ? (const uint8_t *)a.bvals + (size_t)q * (size_t)a.n * sizeof(Tick) : nullptr;
+        const uint32_t brow_mis = (uint32_t)((uintptr_t)brow & 15);
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             cid[i] = (i * a.nlw + lw) * 64 + lane;
             is_id[i] = cid[i] < id16;
-            base[i] = is_id[i] ? (const uint4 *)(row - row_mis) : a.stream;
+            is_b[i] = MASK && !is_id[i] && cid[i] < id16 + b16;
+            base[i] = is_id[i] ? (const uint4 *)(row - row_mis)
+                               : (is_b[i] ? (const uint4 *)(brow - brow_mis) : a.stream);
         }
         u32x4 buf[DR][NL];
         // every lane always loads: chunks past the end of the ids or of the packet re-read
@@ -520,10 +542,16 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
             id_first_ = s_ * (a.wpad / 16);                                                     \
             id_last_ = a.wpad / 16 - 1;                                                         \
         }                                                                                       \
-        const int pk_last_ = id16 + (int)oc_ - 1, off_pk_ = (int)o0_ - id16;                    \
+        const int pk_last_ = id16 + b16 + (int)oc_ - 1, off_pk_ = (int)o0_ - id16 - b16;        \
+        int b_first_ = 0, b_last_ = 0;                                                          \
+        if (MASK) {                                                                             \
+            b_first_ = (int)((brow_mis + (uint32_t)sizeof(Tick) * lo_) >> 4);                   \
+            b_last_ = (int)((brow_mis + (uint32_t)sizeof(Tick) * (lo_ + span_) - 1) >> 4) - b_first_; \
+        }                                                                                       \
         _Pragma("unroll") for (int i_ = 0; i_ < NL; ++i_) {                                     \
-            const int c_ = is_id[i_] ? min(cid[i_], id_last_) + id_first_                       \
-                                     : min(cid[i_], pk_last_) + off_pk_;                        \
+            int c_ = is_id[i_] ? min(cid[i_], id_last_) + id_first_                             \
+                               : min(cid[i_], pk_last_) + off_pk_;                              \
+            if (MASK && is_b[i_]) c_ = min(cid[i_] - id16, b_last_) + b_first_;                 \
             buf[R_][i_] = *(const u32x4 *)(base[i_] + c_);                                      \
         }                                                                                       \
     } while (0)
@@ -532,6 +560,21 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
         u32x4 *dst_ = (u32x4 *)(stage + (size_t)(SLOT_) * slot_bytes);                          \
         _Pragma("unroll") for (int i_ = 0; i_ < NL; ++i_) dst_[cid[i_]] = buf[R_][i_];          \
     } while (0)
+        // the critical vertices of tick s, collected in LDS while it ran, go to the mask row
+        auto flush_mask = [&](int s_) {
+            const u32x4 tt = *(const u32x4 __attribute__((address_space(4))) *)(tick_tab + 4 * s_);
+            const uint32_t lo = tt.z, span = tt.w;
+            const int words = (int)(((lo & 31u) + span + 31u) >> 5);
+            uint32_t *dst = a.mask32 + (size_t)q * (size_t)a.mask_row32 + (lo >> 5);
+            for (int w = lane; w < words; w += 64) {
+                const uint32_t bits = mbits[MASK ? (s_ & 1) : 0][MASK ? w : 0];
+                if (bits) {
+                    atomicOr(dst + w, bits);
+                    mbits[MASK ? (s_ & 1) : 0][MASK ? w : 0] = 0;
+                }
+            }
+        };
+        (void)flush_mask;
 #pragma unroll
         for (int r = 0; r < DR; ++r) CP_ISSUE(r, r);
         CP_STORE(0, 0);
@@ -545,7 +588,12 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
                 // the compute wavefronts now read slot t&1, which packet t-1 has left
                 CP_STORE((r + 1) % DR, (t + 1) & 1);
                 CP_ISSUE((r + 1) % DR, t + 1 + DR);
+                if (MASK && lw == 0 && t >= 1 && t <= L) flush_mask(t - 1);
             }
+        }
+        if (MASK) {
+            lds_barrier();                   // the last tick's bits are set
+            if (lw == 0 && Lpad == L) flush_mask(L - 1);
         }
 #undef CP_ISSUE
 #undef CP_STORE
@@ -555,7 +603,11 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
         Tick *out = a.out ? (Tick *)a.out + (size_t)q * (size_t)a.out_sq : nullptr;
         const uint32_t out_sv = a.out_sv;
         const uint32_t k8 = 8u * (uint32_t)k;
-        const uint32_t rec_off = (uint32_t)a.idpad + 16u * (uint32_t)a.smax;   // records, from the slot base
+        const uint32_t rec_off = (uint32_t)head + 16u * (uint32_t)a.smax;   // records, from the slot base
+        const uint32_t brow_mis = MASK ? (uint32_t)(((uintptr_t)a.bvals + (size_t)q * (size_t)a.n * sizeof(Tick)) & 15)
+                                       : 0u;
+        const Tick cpq = MASK ? (Tick)a.cp_in[q] : 0;     // tl + b <= CP: no overflow in Tick
+        int cur_tick = 0;
         const uint32_t row_mis = (uint32_t)((uintptr_t)(a.ids + (size_t)q * a.ids_row) & 15);
         uint32_t worst = 0;                  // largest device id seen
 
@@ -588,7 +640,8 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
             return acc;
         };
         // the row's first lane publishes the vertex: ring, output, running maximum
-        auto publish = [&](Tick acc, Tick w, int lsh, int rows, int rbase, uint32_t v, uint32_t pv) {
+        auto publish = [&](Tick acc, Tick w, int lsh, int rows, int rbase, uint32_t v, uint32_t pv, Tick bv,
+                           uint32_t lo) {
             const int row = lane >> lsh;
             const bool first = lsh == 0 || (lane & ((1 << lsh) - 1)) == 0;
             if (row < rows && first) {
@@ -606,13 +659,19 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
                     else out[(size_t)v * out_sv] = TSWEEP ? acc : fin;
                 }
                 best = max(best, fin);
+                if constexpr (MASK) {        // tl(v) + b(v) = CP marks a critical vertex
+                    if ((Tick)(acc + bv) == cpq) {
+                        const uint32_t rel = v - (lo & ~31u);
+                        atomicOr(&mbits[cur_tick & 1][rel >> 5], 1u << (rel & 31u));
+                    }
+                }
             }
         };
         // one slice of the current level out of its stage slot
         auto slice_direct = [&](const uint8_t *st, int j) {
             // the descriptor is the same for all lanes; only what steers control flow
             // (width, lanes per row) is moved to scalars, the rest stays in vector registers
-            const uint4 d = ((const uint4 *)(st + a.idpad))[j];
+            const uint4 d = ((const uint4 *)(st + head))[j];
             const uint32_t ent_off = d.x;
             const int width = __builtin_amdgcn_readfirstlane((int)(d.y & 0xffffu));
             const int lsh = __builtin_amdgcn_readfirstlane((int)(d.y >> 24));
@@ -622,12 +681,14 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
             if (width == 0 && lsh == 0 && __builtin_amdgcn_readfirstlane(rows) == 0) return;
             const int p = j * 64 + (lane >> lsh);
             const uint2 *rec = (const uint2 *)(st + rec_off) + p;
-            const Ent *ent = (const Ent *)(st + a.idpad + ent_off) + lane;
+            const Ent *ent = (const Ent *)(st + head + ent_off) + lane;
             const uint32_t id_bias = a.direct ? ((row_mis + lo) & 15u) - lo : 0u;
             uint2 rc;
             uint32_t pv;
             Magic mv;
-            Tick acc = 0;
+            Tick acc = 0, bv = 0;
+            // byte (v - lo) * sizeof(Tick) of the staged b range, which starts at a 16-byte boundary
+            const uint32_t b_bias = ((brow_mis + (uint32_t)sizeof(Tick) * lo) & 15u) - (uint32_t)sizeof(Tick) * lo;
             // The vertex's own reads (record, then its device id, then its cost-table entry)
             // and the first N relaxations (entries, then ring, then transfer-table entries)
             // are two chains of three dependent LDS reads; issued side by side they cost
@@ -643,6 +704,7 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
         rc = *rec;                                                                              \
         _Pragma("unroll") for (int i_ = 0; i_ < N; ++i_) en_[i_] = ent[i_ * 64];                \
         pv = st[a.direct ? rc.x + id_bias : (uint32_t)p];                                       \
+        if (MASK) bv = *(const Tick *)(st + a.idpad + (uint32_t)sizeof(Tick) * rc.x + b_bias);  \
         _Pragma("unroll") for (int i_ = 0; i_ < N; ++i_) ring_get(ent_field(en_[i_]), vu_[i_], pu8_[i_]); \
         worst = max(worst, pv);                                                                 \
         pv = min(pv, (uint32_t)(k - 1));                                                        \
@@ -693,17 +755,19 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
 #undef CP_BLOCK
 #undef CP_HEAD
             acc = fold(acc, lsh);
-            publish(acc, (Tick)magic_div(rc.y, mv), lsh, rows, rbase, rc.x, pv);
+            publish(acc, (Tick)magic_div(rc.y, mv), lsh, rows, rbase, rc.x, pv, bv, lo);
         };
 
         lds_barrier();                       // packet 0 is staged
         for (int t = 0; t < Lpad; ++t) {
             lds_barrier();
             if (t >= L) continue;
+            cur_tick = t;
             const uint8_t *st = stage + (size_t)(t & 1) * slot_bytes;
             for (int j = wave; j < a.smax; j += a.nc) slice_direct(st, j);
         }
         if (worst >= (uint32_t)k) *a.status = CP_STATUS_BAD_DEVICE_ID;
+        if (MASK) lds_barrier();             // pairs with the loaders' barrier before the last flush
     }
 
     if (a.cp_out) {   // workgroup maximum
@@ -765,7 +829,7 @@ int launch_column_sweep_t(const SweepLaunch &s, hipStream_t st, int32_t *launche
     return hip_ok(hipGetLastError());
 }
 
-template <typename Tick, bool TSWEEP, bool PACKED, bool ENT4, int NL, int DR>
+template <typename Tick, bool TSWEEP, bool PACKED, bool ENT4, int NL, int DR, bool MASK>
 int launch_window_sweep_k(const SweepLaunch &s, const WindowCfg &cfg, hipStream_t st) {
     const WindowDir &dir = *s.win;
     WindowArgs a{};
@@ -786,7 +850,15 @@ int launch_window_sweep_k(const SweepLaunch &s, const WindowCfg &cfg, hipStream_
     a.out_sq = s.out_sq;
     a.out_sv = (uint32_t)s.out_sv;
     a.pgroups = (s.P + 7) / 8;
-    auto kern = window_sweep_kernel<Tick, TSWEEP, PACKED, ENT4, NL, DR>;
+    if (MASK) {
+        a.bvals = s.mask_b;
+        a.cp_in = s.mask_cp;
+        a.mask32 = (uint32_t *)s.mask_out;
+        a.mask_row32 = 2 * (((int64_t)s.n + 63) / 64);
+        a.n = s.n;
+        a.bpad = window_mask_bpad(dir);
+    }
+    auto kern = window_sweep_kernel<Tick, TSWEEP, PACKED, ENT4, NL, DR, MASK>;
     if (cfg.lds_bytes > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)cfg.lds_bytes);
@@ -797,46 +869,57 @@ int launch_window_sweep_k(const SweepLaunch &s, const WindowCfg &cfg, hipStream_
     return hip_ok(hipGetLastError());
 }
 
-template <typename Tick, bool TSWEEP, bool PACKED, bool ENT4>
+template <typename Tick, bool TSWEEP, bool PACKED, bool ENT4, bool MASK>
 int launch_window_sweep_e(const SweepLaunch &s, const WindowCfg &cfg, hipStream_t st) {
     switch (cfg.nl) {   // loads per loader lane per level x levels in flight: 64 registers at most
-        case 1: return launch_window_sweep_k<Tick, TSWEEP, PACKED, ENT4, 1, 8>(s, cfg, st);
-        case 2: return launch_window_sweep_k<Tick, TSWEEP, PACKED, ENT4, 2, 8>(s, cfg, st);
-        case 4: return launch_window_sweep_k<Tick, TSWEEP, PACKED, ENT4, 4, 4>(s, cfg, st);
-        case 8: return launch_window_sweep_k<Tick, TSWEEP, PACKED, ENT4, 8, 2>(s, cfg, st);
+        case 1: return launch_window_sweep_k<Tick, TSWEEP, PACKED, ENT4, 1, 8, MASK>(s, cfg, st);
+        case 2: return launch_window_sweep_k<Tick, TSWEEP, PACKED, ENT4, 2, 8, MASK>(s, cfg, st);
+        case 3: return launch_window_sweep_k<Tick, TSWEEP, PACKED, ENT4, 3, 5, MASK>(s, cfg, st);
+        case 4: return launch_window_sweep_k<Tick, TSWEEP, PACKED, ENT4, 4, 4, MASK>(s, cfg, st);
+        case 8: return launch_window_sweep_k<Tick, TSWEEP, PACKED, ENT4, 8, 2, MASK>(s, cfg, st);
         default: return CP_ERR_ARG;
     }
 }
 
-template <typename Tick, bool TSWEEP, bool PACKED>
+template <typename Tick, bool TSWEEP, bool PACKED, bool MASK>
 int launch_window_sweep_p(const SweepLaunch &s, const WindowCfg &cfg, hipStream_t st) {
-    return s.win->ent4 ? launch_window_sweep_e<Tick, TSWEEP, PACKED, true>(s, cfg, st)
-                       : launch_window_sweep_e<Tick, TSWEEP, PACKED, false>(s, cfg, st);
+    return s.win->ent4 ? launch_window_sweep_e<Tick, TSWEEP, PACKED, true, MASK>(s, cfg, st)
+                       : launch_window_sweep_e<Tick, TSWEEP, PACKED, false, MASK>(s, cfg, st);
 }
 
 template <bool TSWEEP>
 int launch_window_sweep_d(const SweepLaunch &s, const WindowCfg &cfg, hipStream_t st) {
+    if (s.mask_out) {    // the t sweep that also writes the mask: 32-bit ticks in a packed ring only
+        if (!TSWEEP || s.tick_bytes != 4 || !s.win->packed || !s.direct_ids) return CP_ERR_ARG;
+        return launch_window_sweep_p<int32_t, true, true, true>(s, cfg, st);
+    }
     if (s.tick_bytes == 4)
-        return s.win->packed ? launch_window_sweep_p<int32_t, TSWEEP, true>(s, cfg, st)
-                             : launch_window_sweep_p<int32_t, TSWEEP, false>(s, cfg, st);
+        return s.win->packed ? launch_window_sweep_p<int32_t, TSWEEP, true, false>(s, cfg, st)
+                             : launch_window_sweep_p<int32_t, TSWEEP, false, false>(s, cfg, st);
     if (s.win->packed) return CP_ERR_ARG;      // packed rings hold 32-bit ticks only
-    return launch_window_sweep_p<int64_t, TSWEEP, false>(s, cfg, st);
+    return launch_window_sweep_p<int64_t, TSWEEP, false, false>(s, cfg, st);
 }
 
 }  // namespace
 
-bool window_config(const WindowDir &d, int32_t k, size_t tick_bytes, size_t lds_limit, WindowCfg &out) {
+int32_t window_mask_bpad(const WindowDir &d) { return 4 * d.idpad + 16; }
+
+bool window_config(const WindowDir &d, int32_t k, size_t tick_bytes, size_t lds_limit, WindowCfg &out,
+                   bool with_mask) {
     if (d.packed && tick_bytes != 4) return false;
-    const int64_t need = d.idpad / 16 + (int64_t)d.max_chunks;    // 16-byte chunks per stage slot
+    // a tick's id range may touch (31 + span + 31) / 32 mask words
+    if (with_mask && (!d.packed || !d.direct_ok || (d.idpad + 62) / 32 > kMaskWords)) return false;
+    // 16-byte chunks per stage slot: device ids, the tick's b values (mask), the packet
+    const int64_t need = d.idpad / 16 + (with_mask ? window_mask_bpad(d) / 16 : 0) + (int64_t)d.max_chunks;
     const size_t tab = (sizeof(Magic) * ((size_t)k * k + k) + 15) & ~(size_t)15;
     const size_t ring = (((size_t)d.slots + 1) * (d.packed ? 8 : tick_bytes + 1) + 15) & ~(size_t)15;
-    static const int kNl[4] = {1, 2, 4, 8};
+    static const int kNl[5] = {1, 2, 3, 4, 8};
     for (int nl : kNl) {
         const int64_t nlw = (need + 64 * nl - 1) / (64 * nl);
         if (nlw > 8) continue;
         out.nl = nl;
         out.nlw = (int)nlw;
-        out.dr = nl <= 2 ? 8 : (nl == 4 ? 4 : 2);
+        out.dr = nl <= 2 ? 8 : (nl == 3 ? 5 : (nl == 4 ? 4 : 2));
         out.nc = std::max(1, std::min(d.smax, kWindowMaxWaves - (int)nlw));
         out.packed = d.packed;
         out.lds_bytes = ring + tab + (size_t)2 * nl * nlw * 1024;
@@ -866,6 +949,13 @@ int launch_zero_bytes(uint8_t *dst, int64_t bytes, void *stream) {
     if (bytes <= 0) return CP_OK;
     hipLaunchKernelGGL(zero_bytes_kernel, dim3((unsigned)((bytes + 255) / 256)), dim3(256), 0,
                        (hipStream_t)stream, dst, bytes);
+    return hip_ok(hipGetLastError());
+}
+
+int launch_zero_words(uint64_t *dst, int64_t words, void *stream) {
+    if (words <= 0) return CP_OK;
+    const unsigned blocks = (unsigned)std::min<int64_t>((words + 255) / 256, 256 * 16);
+    hipLaunchKernelGGL(zero_words_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, dst, words);
     return hip_ok(hipGetLastError());
 }
 

@@ -29,6 +29,11 @@ struct SweepLaunch {
     const void *edge_tab = nullptr;
     const void *vert_tab = nullptr;
     int32_t *status = nullptr;
+    // resident-window t sweep that also writes the mask rows (partition-major): b, CP and the
+    // zeroed mask; all null otherwise
+    const void *mask_b = nullptr;
+    const int64_t *mask_cp = nullptr;
+    uint64_t *mask_out = nullptr;
 };
 
 // Launch shape of the resident-window kernel for one sweep direction.
@@ -42,7 +47,10 @@ struct WindowCfg {
 };
 
 // False if the direction cannot run under `lds_limit` bytes of LDS.
-bool window_config(const WindowDir &d, int32_t k, size_t tick_bytes, size_t lds_limit, WindowCfg &out);
+// with_mask: the t sweep also stages the tick's b values and writes the mask.
+bool window_config(const WindowDir &d, int32_t k, size_t tick_bytes, size_t lds_limit, WindowCfg &out,
+                   bool with_mask = false);
+int32_t window_mask_bpad(const WindowDir &d);
 int launch_gather_assign(const SweepLaunch &s, uint8_t *out, void *stream);
 
 int launch_clear(int64_t *cp_out, int32_t batch, int32_t *status, void *stream);
@@ -70,6 +78,7 @@ size_t pct_counts_bytes(int32_t n, int32_t P);
 int launch_pct_order(const PctOrderLaunch &s, void *stream);
 
 int launch_zero_bytes(uint8_t *dst, int64_t bytes, void *stream);
+int launch_zero_words(uint64_t *dst, int64_t words, void *stream);
 int launch_ranks(const void *b, const void *tl, const void *c, bool narrow, int tick_bytes, int32_t n,
                  int64_t *up, int64_t *down, int64_t *total, void *stream);
 int launch_critical_path(const SweepLaunch &s, const int32_t *sources, int32_t nsrc, const int64_t *cp,
