@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X, published
 # copy: x2.00 and x1.00).  The figure belongs to one build of the kernel: it is reported only
 # while the sources it was taken on are unchanged, and for the configuration it was taken on.
 MEASURED_TRAFFIC = {
-    "sources_sha256": "39c898868b0e04bc53217c553fe866d54864eadeb56b1e695e854da89cc855b7",
+    "sources_sha256": "b50aa911d77d26bb95120a0cf894d4ea963622fa9f597ed284c07ffce99609f0",
     "workload": "large_sparse", "P": 256, "plan": 2, "out_layout": 1,
     "bytes_per_blevel_launch": (2 * 227701 + 1000002) * 1024,
 }
