@@ -147,7 +147,7 @@ int pct_plan(const cp_graph *g, int32_t batch, int32_t k, int64_t max_b, PctPlan
     out.key_bits = out.b_bits + bit_length((uint64_t)(k - 1));
     if (out.key_bits > 64) return CP_ERR_OVERFLOW;
     out.key_bytes = out.key_bits <= 32 ? 4 : 8;
-    const int64_t tiles = ((int64_t)p.n + 4095) / 4096;
+    const int64_t tiles = pct_sort_tiles(p.n);
     if (tiles * (int64_t)batch >= (int64_t)1 << 31) return CP_ERR_SIZE;
     const size_t items = (size_t)p.n * (size_t)batch;
     out.keys_bytes = align_up(items * (size_t)out.key_bytes);

@@ -75,6 +75,7 @@ struct PctOrderLaunch {
     int32_t *order_out = nullptr, *seg_out = nullptr, *status = nullptr;
 };
 size_t pct_counts_bytes(int32_t n, int32_t P);
+int32_t pct_sort_tiles(int32_t n);
 int launch_pct_order(const PctOrderLaunch &s, void *stream);
 
 int launch_zero_bytes(uint8_t *dst, int64_t bytes, void *stream);

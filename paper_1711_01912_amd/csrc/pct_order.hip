@@ -24,11 +24,13 @@ namespace {
 
 constexpr int kRadixBits = 8;
 constexpr int kRadix = 1 << kRadixBits;
-constexpr int kSortThreads = 256;
-constexpr int kSortWaves = kSortThreads / 64;
 constexpr int kSortRounds = 16;                           // items per thread
-constexpr int kSortTile = kSortThreads * kSortRounds;     // 4096 items per workgroup
-static_assert(kSortThreads == kRadix, "one thread per digit when the tile's digit starts are computed");
+// Items per workgroup = threads x 16.  Long partitions take 1024 threads: 16384 items, so a
+// digit's run in a tile averages 64 items and leaves as full lines; short ones take 256
+// threads (4096 items) so that several workgroups share a partition.
+constexpr int kSortThreadsLong = 1024, kSortThreadsShort = 256;
+constexpr int kSortLongFrom = 65536;                      // vertices from which the long tile is used
+inline int sort_threads(int32_t n) { return n >= kSortLongFrom ? kSortThreadsLong : kSortThreadsShort; }
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? CP_OK : CP_ERR_HIP; }
 
@@ -111,10 +113,12 @@ __device__ __forceinline__ uint32_t digit_of(Key key, int shift) {
 }
 
 // counts[q][digit][tile] = items of the tile with that digit
-template <typename Key>
+template <typename Key, int kSortThreads>
 __global__ __launch_bounds__(kSortThreads) void pct_count_kernel(const Key *__restrict__ keys, int32_t n,
                                                                  int32_t tiles, int shift,
                                                                  uint32_t *__restrict__ counts) {
+    constexpr int kSortWaves = kSortThreads / 64, kSortTile = kSortThreads * kSortRounds;
+    static_assert(kSortThreads >= kRadix, "one thread per digit writes the counts");
     __shared__ uint32_t h[kSortWaves][kRadix];
     const int tid = threadIdx.x, wave = tid >> 6;
     const int32_t tile = (int32_t)(blockIdx.x % (uint32_t)tiles), q = (int32_t)(blockIdx.x / (uint32_t)tiles);
@@ -122,16 +126,33 @@ __global__ __launch_bounds__(kSortThreads) void pct_count_kernel(const Key *__re
     __syncthreads();
     const Key *src = keys + (int64_t)q * n;
     const int64_t base = (int64_t)tile * kSortTile;
+    Key key[kSortRounds];
+#pragma unroll
+    for (int r = 0; r < kSortRounds; ++r) {               // all loads first, then the LDS updates
+        const int64_t i = base + r * kSortThreads + tid;
+        key[r] = i < n ? src[i] : (Key)0;
+    }
 #pragma unroll
     for (int r = 0; r < kSortRounds; ++r) {
         const int64_t i = base + r * kSortThreads + tid;
-        if (i < n) atomicAdd(&h[wave][digit_of(src[i], shift)], 1u);
+        const uint32_t d = digit_of(key[r], shift);
+        // a wavefront whose lanes all hold one digit (the usual case for the leading digit)
+        // adds once instead of 64 times to one counter
+        const uint32_t d0 = __builtin_amdgcn_readfirstlane(d);
+        const unsigned long long live = __ballot(i < n);
+        if (__ballot(i < n && d != d0) == 0) {
+            if ((tid & 63) == 0 && live) h[wave][d0] += (uint32_t)__popcll(live);
+        } else if (i < n) {
+            atomicAdd(&h[wave][d], 1u);
+        }
     }
     __syncthreads();
-    uint32_t c = 0;
+    if (tid < kRadix) {
+        uint32_t c = 0;
 #pragma unroll
-    for (int w = 0; w < kSortWaves; ++w) c += h[w][tid];
-    counts[((int64_t)q * kRadix + tid) * tiles + tile] = c;
+        for (int w = 0; w < kSortWaves; ++w) c += h[w][tid];
+        counts[((int64_t)q * kRadix + tid) * tiles + tile] = c;
+    }
 }
 
 // In place: counts[q][*] becomes its exclusive prefix sum in (digit, tile) order, i.e.
@@ -165,20 +186,24 @@ __global__ __launch_bounds__(1024) void pct_scan_kernel(uint32_t *__restrict__ c
 // and takes them 64 at a time, so item order is (wavefront, round, lane).  Inside a
 // round, lanes with equal digits find each other by ballots; the lowest of them
 // advances the wavefront's counter for that digit.  The tile is then put in digit order
-// in LDS and written out in runs.
-template <typename Key, bool FIRST, bool LAST>
+// in LDS and written out in runs: first the keys, then, through the same LDS buffer,
+// the vertex numbers.
+template <typename Key, int kSortThreads, bool FIRST, bool LAST>
 __global__ __launch_bounds__(kSortThreads) void pct_scatter_kernel(const Key *__restrict__ keys_in,
                                                                    const int32_t *__restrict__ vals_in,
                                                                    Key *__restrict__ keys_out,
                                                                    int32_t *__restrict__ vals_out, int32_t n,
                                                                    int32_t tiles, int shift,
                                                                    const uint32_t *__restrict__ starts) {
+    constexpr int kSortWaves = kSortThreads / 64, kSortTile = kSortThreads * kSortRounds;
+    static_assert(kSortThreads >= kRadix, "one thread per digit when the tile's digit starts are computed");
+    extern __shared__ __align__(16) uint8_t sort_lds[];      // kSortTile keys, later kSortTile vertex numbers
     __shared__ uint32_t cnt[kSortWaves][kRadix];
     __shared__ uint32_t tile_start[kRadix];
     __shared__ int32_t out_base[kRadix];
-    __shared__ uint32_t wave_sum[kSortWaves];
-    __shared__ Key skey[kSortTile];
-    __shared__ int32_t sval[kSortTile];
+    __shared__ uint32_t wave_sum[kRadix / 64];
+    Key *skey = (Key *)sort_lds;
+    int32_t *sval = (int32_t *)sort_lds;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int32_t tile = (int32_t)(blockIdx.x % (uint32_t)tiles), q = (int32_t)(blockIdx.x / (uint32_t)tiles);
     const int64_t seg = (int64_t)q * n;
@@ -189,7 +214,7 @@ __global__ __launch_bounds__(kSortThreads) void pct_scatter_kernel(const Key *__
 
     Key key[kSortRounds];
     int32_t val[kSortRounds];
-    uint32_t loc[kSortRounds];
+    uint32_t loc[kSortRounds];       // rank among equal digits, then position in the sorted tile
 #pragma unroll
     for (int r = 0; r < kSortRounds; ++r) {
         const int32_t t = wave * (kSortRounds * 64) + r * 64 + lane;      // index inside the tile
@@ -222,21 +247,23 @@ __global__ __launch_bounds__(kSortThreads) void pct_scatter_kernel(const Key *__
         loc[r] = old + rank;
     }
     __syncthreads();
-    {   // thread d: wavefront bases and the tile's digit starts
-        uint32_t run = 0;
+    uint32_t run = 0, inc = 0;
+    if (tid < kRadix) {   // thread d: wavefront bases, then the tile's digit starts
 #pragma unroll
         for (int w = 0; w < kSortWaves; ++w) {
             const uint32_t c = cnt[w][tid];
             cnt[w][tid] = run;
             run += c;
         }
-        uint32_t inc = run;
+        inc = run;
         for (int off = 1; off < 64; off <<= 1) {
             const uint32_t up = __shfl_up(inc, off);
             if (lane >= off) inc += up;
         }
         if (lane == 63) wave_sum[wave] = inc;
-        __syncthreads();
+    }
+    __syncthreads();
+    if (tid < kRadix) {
         uint32_t before = 0;
         for (int w = 0; w < wave; ++w) before += wave_sum[w];
         const uint32_t start = before + inc - run;
@@ -249,21 +276,33 @@ __global__ __launch_bounds__(kSortThreads) void pct_scatter_kernel(const Key *__
         const int32_t t = wave * (kSortRounds * 64) + r * 64 + lane;
         if (t < tile_items) {
             const uint32_t d = digit_of(key[r], shift);
-            const uint32_t pos = tile_start[d] + cnt[wave][d] + loc[r];
-            skey[pos] = key[r];
-            sval[pos] = val[r];
+            loc[r] = tile_start[d] + cnt[wave][d] + loc[r];
+            skey[loc[r]] = key[r];
+        }
+    }
+    __syncthreads();
+    int32_t dst[kSortRounds];        // where item i of the sorted tile goes in the partition's output
+#pragma unroll
+    for (int r = 0; r < kSortRounds; ++r) {
+        const int32_t i = r * kSortThreads + tid;
+        dst[r] = 0;
+        if (i < tile_items) {
+            const Key kk = skey[i];
+            dst[r] = out_base[digit_of(kk, shift)] + i;
+            if (!LAST) keys_out[seg + dst[r]] = kk;
         }
     }
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < kSortRounds; ++r) {
+        const int32_t t = wave * (kSortRounds * 64) + r * 64 + lane;
+        if (t < tile_items) sval[loc[r]] = val[r];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < kSortRounds; ++r) {
         const int32_t i = r * kSortThreads + tid;
-        if (i < tile_items) {
-            const Key kk = skey[i];
-            const int64_t dst = seg + out_base[digit_of(kk, shift)] + i;
-            if (!LAST) keys_out[dst] = kk;
-            vals_out[dst] = sval[i];
-        }
+        if (i < tile_items) vals_out[seg + dst[r]] = sval[i];
     }
 }
 
@@ -284,13 +323,24 @@ __global__ void pct_segments_kernel(const int32_t *__restrict__ order, const uin
     seg[i] = lo;
 }
 
-template <typename Key>
+template <typename Key, int THREADS>
 int run_sort(const PctOrderLaunch &s, hipStream_t st) {
+    constexpr int kTile = THREADS * kSortRounds;
     const int32_t n = s.n, P = s.P;
-    const int32_t tiles = (n + kSortTile - 1) / kSortTile;
+    const int32_t tiles = (n + kTile - 1) / kTile;
     Key *ka = (Key *)s.keys_a, *kb = (Key *)s.keys_b;
-    const dim3 grid((unsigned)((int64_t)tiles * P)), block(kSortThreads);     // one workgroup per (partition, tile)
+    const dim3 grid((unsigned)((int64_t)tiles * P)), block(THREADS);     // one workgroup per (partition, tile)
     const int passes = (s.key_bits + kRadixBits - 1) / kRadixBits;
+    const size_t lds = (size_t)kTile * sizeof(Key);
+    if (lds > 64 * 1024) {   // more than 64 KB of dynamic LDS has to be asked for, once per kernel
+        const void *kernels[4] = {(const void *)pct_scatter_kernel<Key, THREADS, true, true>,
+                                  (const void *)pct_scatter_kernel<Key, THREADS, true, false>,
+                                  (const void *)pct_scatter_kernel<Key, THREADS, false, true>,
+                                  (const void *)pct_scatter_kernel<Key, THREADS, false, false>};
+        for (const void *kfn : kernels)
+            if (hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+                return CP_ERR_HIP;
+    }
     // vertex lists alternate between the scratch list and the output so that the last
     // pass writes the output
     for (int p = 0; p < passes; ++p) {
@@ -301,20 +351,16 @@ int run_sort(const PctOrderLaunch &s, hipStream_t st) {
         const bool to_out = ((passes - 1 - p) & 1) == 0;
         int32_t *vout = to_out ? s.order_out : s.vals_tmp;
         const int32_t *vin = to_out ? s.vals_tmp : s.order_out;
-        hipLaunchKernelGGL((pct_count_kernel<Key>), grid, block, 0, st, kin, n, tiles, shift, s.counts);
+        hipLaunchKernelGGL((pct_count_kernel<Key, THREADS>), grid, block, 0, st, kin, n, tiles, shift, s.counts);
         hipLaunchKernelGGL(pct_scan_kernel, dim3((unsigned)P), dim3(1024), 0, st, s.counts, kRadix * tiles);
-        if (first && last)
-            hipLaunchKernelGGL((pct_scatter_kernel<Key, true, true>), grid, block, 0, st, kin, vin, kout, vout, n,
-                               tiles, shift, s.counts);
-        else if (first)
-            hipLaunchKernelGGL((pct_scatter_kernel<Key, true, false>), grid, block, 0, st, kin, vin, kout, vout, n,
-                               tiles, shift, s.counts);
-        else if (last)
-            hipLaunchKernelGGL((pct_scatter_kernel<Key, false, true>), grid, block, 0, st, kin, vin, kout, vout, n,
-                               tiles, shift, s.counts);
-        else
-            hipLaunchKernelGGL((pct_scatter_kernel<Key, false, false>), grid, block, 0, st, kin, vin, kout, vout,
-                               n, tiles, shift, s.counts);
+#define CP_SCATTER(F, L)                                                                               \
+    hipLaunchKernelGGL((pct_scatter_kernel<Key, THREADS, F, L>), grid, block, lds, st, kin, vin, kout, vout, n, \
+                       tiles, shift, s.counts)
+        if (first && last) CP_SCATTER(true, true);
+        else if (first) CP_SCATTER(true, false);
+        else if (last) CP_SCATTER(false, true);
+        else CP_SCATTER(false, false);
+#undef CP_SCATTER
         if (hipGetLastError() != hipSuccess) return CP_ERR_HIP;
     }
     return CP_OK;
@@ -322,7 +368,10 @@ int run_sort(const PctOrderLaunch &s, hipStream_t st) {
 
 }  // namespace
 
-int32_t pct_sort_tiles(int32_t n) { return (n + kSortTile - 1) / kSortTile; }
+int32_t pct_sort_tiles(int32_t n) {
+    const int tile = sort_threads(n) * kSortRounds;
+    return (n + tile - 1) / tile;
+}
 size_t pct_counts_bytes(int32_t n, int32_t P) {
     return align_up((size_t)P * kRadix * (size_t)pct_sort_tiles(n) * sizeof(uint32_t));
 }
@@ -357,7 +406,11 @@ int launch_pct_order(const PctOrderLaunch &s, void *stream) {
     }
 #undef CP_KEYS
     if (hipGetLastError() != hipSuccess) return CP_ERR_HIP;
-    int rc = s.key_bytes == 4 ? run_sort<uint32_t>(s, st) : run_sort<uint64_t>(s, st);
+    int rc;
+    if (sort_threads(s.n) == kSortThreadsLong)
+        rc = s.key_bytes == 4 ? run_sort<uint32_t, kSortThreadsLong>(s, st) : run_sort<uint64_t, kSortThreadsLong>(s, st);
+    else
+        rc = s.key_bytes == 4 ? run_sort<uint32_t, kSortThreadsShort>(s, st) : run_sort<uint64_t, kSortThreadsShort>(s, st);
     if (rc) return rc;
     const int64_t cells = (int64_t)s.P * (s.k + 1);
     hipLaunchKernelGGL(pct_segments_kernel, dim3((unsigned)((cells + 255) / 256)), dim3(256), 0, st,
