@@ -7,8 +7,8 @@
 //   key(v) = device(v) << bb | (max_b - b(v))        bb = bit length of max_b
 //
 // Sorting keys ascending with a stable sort whose input is in vertex order yields the
-// list; the vertex number never enters the key.  Each 8-bit digit takes three
-// launches: per-tile digit counts, an exclusive scan of the counts per partition in
+// list; the vertex number never enters the key.  Each digit (8 bits, or 9 where that
+// saves a pass) takes three launches: per-tile digit counts, an exclusive scan of the counts per partition in
 // (digit, tile) order, and a stable scatter.
 #include <hip/hip_runtime.h>
 
@@ -22,8 +22,7 @@ namespace cpeval {
 
 namespace {
 
-constexpr int kRadixBits = 8;
-constexpr int kRadix = 1 << kRadixBits;
+constexpr int kMaxRadix = 512;
 constexpr int kSortRounds = 16;                           // items per thread
 // Items per workgroup = threads x 16.  Long partitions take 1024 threads: 16384 items, so a
 // digit's run in a tile averages 64 items and leaves as full lines; short ones take 256
@@ -31,6 +30,8 @@ constexpr int kSortRounds = 16;                           // items per thread
 constexpr int kSortThreadsLong = 1024, kSortThreadsShort = 256;
 constexpr int kSortLongFrom = 65536;                      // vertices from which the long tile is used
 inline int sort_threads(int32_t n) { return n >= kSortLongFrom ? kSortThreadsLong : kSortThreadsShort; }
+// Passes over a key of `bits` bits: digits of 8 bits, of up to 9 where allowed.
+inline int pct_passes(int bits, bool wide) { return (bits + (wide ? 9 : 8) - 1) / (wide ? 9 : 8); }
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? CP_OK : CP_ERR_HIP; }
 
@@ -107,17 +108,17 @@ __global__ __launch_bounds__(256) void pct_keys_rows_kernel(KeyArgs a) {
 
 // ---------------------------------------------------------------- one digit pass
 
-template <typename Key>
+template <int RB, typename Key>
 __device__ __forceinline__ uint32_t digit_of(Key key, int shift) {
-    return (uint32_t)(key >> shift) & (kRadix - 1);
+    return (uint32_t)(key >> shift) & ((1u << RB) - 1);
 }
 
 // counts[q][digit][tile] = items of the tile with that digit
-template <typename Key, int kSortThreads>
+template <typename Key, int kSortThreads, int RB>
 __global__ __launch_bounds__(kSortThreads) void pct_count_kernel(const Key *__restrict__ keys, int32_t n,
                                                                  int32_t tiles, int shift,
                                                                  uint32_t *__restrict__ counts) {
-    constexpr int kSortWaves = kSortThreads / 64, kSortTile = kSortThreads * kSortRounds;
+    constexpr int kSortWaves = kSortThreads / 64, kSortTile = kSortThreads * kSortRounds, kRadix = 1 << RB;
     static_assert(kSortThreads >= kRadix, "one thread per digit writes the counts");
     __shared__ uint32_t h[kSortWaves][kRadix];
     const int tid = threadIdx.x, wave = tid >> 6;
@@ -135,7 +136,7 @@ __global__ __launch_bounds__(kSortThreads) void pct_count_kernel(const Key *__re
 #pragma unroll
     for (int r = 0; r < kSortRounds; ++r) {
         const int64_t i = base + r * kSortThreads + tid;
-        const uint32_t d = digit_of(key[r], shift);
+        const uint32_t d = digit_of<RB>(key[r], shift);
         // a wavefront whose lanes all hold one digit (the usual case for the leading digit)
         // adds once instead of 64 times to one counter
         const uint32_t d0 = __builtin_amdgcn_readfirstlane(d);
@@ -188,14 +189,14 @@ __global__ __launch_bounds__(1024) void pct_scan_kernel(uint32_t *__restrict__ c
 // advances the wavefront's counter for that digit.  The tile is then put in digit order
 // in LDS and written out in runs: first the keys, then, through the same LDS buffer,
 // the vertex numbers.
-template <typename Key, int kSortThreads, bool FIRST, bool LAST>
+template <typename Key, int kSortThreads, int RB, bool FIRST, bool LAST>
 __global__ __launch_bounds__(kSortThreads) void pct_scatter_kernel(const Key *__restrict__ keys_in,
                                                                    const int32_t *__restrict__ vals_in,
                                                                    Key *__restrict__ keys_out,
                                                                    int32_t *__restrict__ vals_out, int32_t n,
                                                                    int32_t tiles, int shift,
                                                                    const uint32_t *__restrict__ starts) {
-    constexpr int kSortWaves = kSortThreads / 64, kSortTile = kSortThreads * kSortRounds;
+    constexpr int kSortWaves = kSortThreads / 64, kSortTile = kSortThreads * kSortRounds, kRadix = 1 << RB;
     static_assert(kSortThreads >= kRadix, "one thread per digit when the tile's digit starts are computed");
     extern __shared__ __align__(16) uint8_t sort_lds[];      // kSortTile keys, later kSortTile vertex numbers
     __shared__ uint32_t cnt[kSortWaves][kRadix];
@@ -226,10 +227,10 @@ __global__ __launch_bounds__(kSortThreads) void pct_scatter_kernel(const Key *__
     for (int r = 0; r < kSortRounds; ++r) {
         const int32_t t = wave * (kSortRounds * 64) + r * 64 + lane;
         const bool valid = t < tile_items;
-        const uint32_t d = digit_of(key[r], shift);
+        const uint32_t d = digit_of<RB>(key[r], shift);
         unsigned long long same = __ballot(valid);
 #pragma unroll
-        for (int bit = 0; bit < kRadixBits; ++bit) {
+        for (int bit = 0; bit < RB; ++bit) {
             const bool one = (d >> bit) & 1u;
             const unsigned long long bal = __ballot(one);
             same &= one ? bal : ~bal;
@@ -275,7 +276,7 @@ __global__ __launch_bounds__(kSortThreads) void pct_scatter_kernel(const Key *__
     for (int r = 0; r < kSortRounds; ++r) {
         const int32_t t = wave * (kSortRounds * 64) + r * 64 + lane;
         if (t < tile_items) {
-            const uint32_t d = digit_of(key[r], shift);
+            const uint32_t d = digit_of<RB>(key[r], shift);
             loc[r] = tile_start[d] + cnt[wave][d] + loc[r];
             skey[loc[r]] = key[r];
         }
@@ -288,7 +289,7 @@ __global__ __launch_bounds__(kSortThreads) void pct_scatter_kernel(const Key *__
         dst[r] = 0;
         if (i < tile_items) {
             const Key kk = skey[i];
-            dst[r] = out_base[digit_of(kk, shift)] + i;
+            dst[r] = out_base[digit_of<RB>(kk, shift)] + i;
             if (!LAST) keys_out[seg + dst[r]] = kk;
         }
     }
@@ -323,45 +324,61 @@ __global__ void pct_segments_kernel(const int32_t *__restrict__ order, const uin
     seg[i] = lo;
 }
 
-template <typename Key, int THREADS>
-int run_sort(const PctOrderLaunch &s, hipStream_t st) {
+// One digit pass of RB bits starting at bit `shift`.
+template <typename Key, int THREADS, int RB>
+int run_pass(const PctOrderLaunch &s, hipStream_t st, int shift, bool first, bool last, const Key *kin, Key *kout,
+             const int32_t *vin, int32_t *vout) {
     constexpr int kTile = THREADS * kSortRounds;
     const int32_t n = s.n, P = s.P;
     const int32_t tiles = (n + kTile - 1) / kTile;
-    Key *ka = (Key *)s.keys_a, *kb = (Key *)s.keys_b;
     const dim3 grid((unsigned)((int64_t)tiles * P)), block(THREADS);     // one workgroup per (partition, tile)
-    const int passes = (s.key_bits + kRadixBits - 1) / kRadixBits;
     const size_t lds = (size_t)kTile * sizeof(Key);
-    if (lds > 64 * 1024) {   // more than 64 KB of dynamic LDS has to be asked for, once per kernel
-        const void *kernels[4] = {(const void *)pct_scatter_kernel<Key, THREADS, true, true>,
-                                  (const void *)pct_scatter_kernel<Key, THREADS, true, false>,
-                                  (const void *)pct_scatter_kernel<Key, THREADS, false, true>,
-                                  (const void *)pct_scatter_kernel<Key, THREADS, false, false>};
-        for (const void *kfn : kernels)
-            if (hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-                return CP_ERR_HIP;
-    }
+    hipLaunchKernelGGL((pct_count_kernel<Key, THREADS, RB>), grid, block, 0, st, kin, n, tiles, shift, s.counts);
+    hipLaunchKernelGGL(pct_scan_kernel, dim3((unsigned)P), dim3(1024), 0, st, s.counts, (1 << RB) * tiles);
+#define CP_SCATTER(F, L)                                                                                   \
+    do {                                                                                                   \
+        auto kern = pct_scatter_kernel<Key, THREADS, RB, F, L>;                                            \
+        /* more than 64 KB of dynamic LDS has to be asked for */                                           \
+        if (lds > 64 * 1024 && hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                                   (int)lds) != hipSuccess)                                \
+            return CP_ERR_HIP;                                                                             \
+        hipLaunchKernelGGL(kern, grid, block, lds, st, kin, vin, kout, vout, n, tiles, shift, s.counts);   \
+    } while (0)
+    if (first && last) CP_SCATTER(true, true);
+    else if (first) CP_SCATTER(true, false);
+    else if (last) CP_SCATTER(false, true);
+    else CP_SCATTER(false, false);
+#undef CP_SCATTER
+    return hipGetLastError() == hipSuccess ? CP_OK : CP_ERR_HIP;
+}
+
+// WIDE: 9-bit digits may be used (long tiles of 32-bit keys: the counters of a 64-bit
+// tile's 512 digits would not fit LDS beside the tile).
+template <typename Key, int THREADS, bool WIDE>
+int run_sort(const PctOrderLaunch &s, hipStream_t st) {
+    Key *ka = (Key *)s.keys_a, *kb = (Key *)s.keys_b;
+    const int passes = pct_passes(s.key_bits, WIDE);
+    // 8 bits per pass; where that leaves bits over, the leading passes take 9
+    const int wide_passes = std::max(0, s.key_bits - 8 * passes);
+    int shift = 0;
     // vertex lists alternate between the scratch list and the output so that the last
     // pass writes the output
     for (int p = 0; p < passes; ++p) {
-        const int shift = p * kRadixBits;
         const bool first = p == 0, last = p == passes - 1;
         const Key *kin = (p & 1) ? kb : ka;
         Key *kout = (p & 1) ? ka : kb;
         const bool to_out = ((passes - 1 - p) & 1) == 0;
         int32_t *vout = to_out ? s.order_out : s.vals_tmp;
         const int32_t *vin = to_out ? s.vals_tmp : s.order_out;
-        hipLaunchKernelGGL((pct_count_kernel<Key, THREADS>), grid, block, 0, st, kin, n, tiles, shift, s.counts);
-        hipLaunchKernelGGL(pct_scan_kernel, dim3((unsigned)P), dim3(1024), 0, st, s.counts, kRadix * tiles);
-#define CP_SCATTER(F, L)                                                                               \
-    hipLaunchKernelGGL((pct_scatter_kernel<Key, THREADS, F, L>), grid, block, lds, st, kin, vin, kout, vout, n, \
-                       tiles, shift, s.counts)
-        if (first && last) CP_SCATTER(true, true);
-        else if (first) CP_SCATTER(true, false);
-        else if (last) CP_SCATTER(false, true);
-        else CP_SCATTER(false, false);
-#undef CP_SCATTER
-        if (hipGetLastError() != hipSuccess) return CP_ERR_HIP;
+        int rc;
+        if (WIDE && p < wide_passes) {
+            rc = run_pass<Key, THREADS, WIDE ? 9 : 8>(s, st, shift, first, last, kin, kout, vin, vout);
+            shift += 9;
+        } else {
+            rc = run_pass<Key, THREADS, 8>(s, st, shift, first, last, kin, kout, vin, vout);
+            shift += 8;
+        }
+        if (rc) return rc;
     }
     return CP_OK;
 }
@@ -373,7 +390,7 @@ int32_t pct_sort_tiles(int32_t n) {
     return (n + tile - 1) / tile;
 }
 size_t pct_counts_bytes(int32_t n, int32_t P) {
-    return align_up((size_t)P * kRadix * (size_t)pct_sort_tiles(n) * sizeof(uint32_t));
+    return align_up((size_t)P * kMaxRadix * (size_t)pct_sort_tiles(n) * sizeof(uint32_t));
 }
 
 int launch_pct_order(const PctOrderLaunch &s, void *stream) {
@@ -408,9 +425,11 @@ int launch_pct_order(const PctOrderLaunch &s, void *stream) {
     if (hipGetLastError() != hipSuccess) return CP_ERR_HIP;
     int rc;
     if (sort_threads(s.n) == kSortThreadsLong)
-        rc = s.key_bytes == 4 ? run_sort<uint32_t, kSortThreadsLong>(s, st) : run_sort<uint64_t, kSortThreadsLong>(s, st);
+        rc = s.key_bytes == 4 ? run_sort<uint32_t, kSortThreadsLong, true>(s, st)
+                              : run_sort<uint64_t, kSortThreadsLong, false>(s, st);
     else
-        rc = s.key_bytes == 4 ? run_sort<uint32_t, kSortThreadsShort>(s, st) : run_sort<uint64_t, kSortThreadsShort>(s, st);
+        rc = s.key_bytes == 4 ? run_sort<uint32_t, kSortThreadsShort, false>(s, st)
+                              : run_sort<uint64_t, kSortThreadsShort, false>(s, st);
     if (rc) return rc;
     const int64_t cells = (int64_t)s.P * (s.k + 1);
     hipLaunchKernelGGL(pct_segments_kernel, dim3((unsigned)((cells + 255) / 256)), dim3(256), 0, st,
