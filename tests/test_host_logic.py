@@ -240,3 +240,58 @@ def test_multiply_shift_exhaustive_small_range(lib):
         n_ = a + np.uint64(dm1)
         got = (n_ * np.uint64(mul) + n_) >> np.uint64(32)
         assert (got == (a + np.uint64(d - 1)) // np.uint64(d)).all()
+
+
+def test_consumer_entry_points_check_their_arguments(lib):
+    """cp_critical_path, cp_pct_order and cp_ranks reject bad arguments before touching the GPU."""
+    w = make_workload("tiny")
+    g = cpe.CpGraph.from_workload(w)
+    s = np.array([1, 2], dtype=np.int64)
+    B = np.array([[1, 10], [10, 1]], dtype=np.int64)
+    dummy = C.c_void_p(256)
+    i64p = C.POINTER(C.c_int64)
+    sp, bp = s.ctypes.data_as(i64p), B.ctypes.data_as(i64p)
+
+    def path(batch=4, k=2, assign=dummy, layout=0, b=dummy, cp=dummy, tick=4, b_layout=0, ws=dummy, max_len=8,
+             out=dummy):
+        return lib.cp_critical_path(g._handle, batch, k, assign, layout, sp, bp, b, cp, tick, b_layout, ws, 1 << 20,
+                                    None, max_len, out, dummy, dummy)
+
+    assert path(batch=0) == -2
+    assert path(layout=3) == -12
+    assert path(b_layout=2) == -12
+    assert path(tick=5) == -12
+    assert path(b=C.c_void_p()) == -1
+    assert path() == -11                           # not uploaded
+
+    need = C.c_size_t(0)
+    assert lib.cp_pct_order_workspace_bytes(g._handle, 16, 2, 0, C.byref(need)) == 0
+    # two key arrays and one list of 16 x 64 32-bit items, counts for 512 digits x 1 tile x 16 partitions
+    assert need.value == 3 * 16 * 64 * 4 + 16 * 512 * 4
+    assert lib.cp_pct_order_workspace_bytes(g._handle, 16, 2, -1, C.byref(need)) == -12
+    assert lib.cp_pct_order_workspace_bytes(g._handle, 0, 2, 0, C.byref(need)) == -2
+    assert lib.cp_pct_order_workspace_bytes(g._handle, 16, 2, 0, None) == -1
+    # 62 bits of b plus 8 device bits do not fit one 64-bit key
+    assert lib.cp_pct_order_workspace_bytes(g._handle, 16, 255, 2**62, C.byref(need)) == -8
+    # a bound past 32 bits: 64-bit keys
+    assert lib.cp_pct_order_workspace_bytes(g._handle, 16, 2, 2**40, C.byref(need)) == 0
+    assert need.value == 2 * 16 * 64 * 8 + 16 * 64 * 4 + 16 * 512 * 4
+
+    def order(batch=4, k=2, assign=dummy, layout=0, b=dummy, tick=4, b_layout=0, max_b=0, ws=dummy, out=dummy):
+        return lib.cp_pct_order(g._handle, batch, k, assign, layout, b, tick, b_layout, max_b, ws, 1 << 20, None,
+                                out, dummy, dummy)
+
+    assert order(batch=0) == -2
+    assert order(b_layout=5) == -12
+    assert order(max_b=-3) == -12
+    assert order(out=C.c_void_p()) == -1
+    assert order() == -11
+
+    assert lib.cp_ranks_workspace_bytes(g._handle, C.byref(need)) == 0 and need.value > 0
+    assert lib.cp_ranks(g._handle, dummy, 1 << 20, None, None, None, None) == -1
+    assert lib.cp_ranks(g._handle, dummy, 1 << 20, None, dummy, dummy, dummy) == -11
+    plan = C.c_int(0)
+    assert lib.cp_eval_choose_plan(g._handle, 16, 2, sp, bp, 4, C.byref(plan)) == 0
+    assert plan.value in (cpe.PLAN_WAVE_COLUMN, cpe.PLAN_RESIDENT_WINDOW)
+    assert lib.cp_eval_choose_plan(g._handle, 16, 2, sp, bp, 3, C.byref(plan)) == -12
+    g.close()
