@@ -329,3 +329,32 @@ int cp_oracle_pct_order(int32_t n, int k, int32_t P, const uint8_t *assignments,
     }
     return rc;
 }
+
+/*
+ * Validity of partitions under the two placement constraints of section 2: every
+ * collocation pair (v_i, v_j) must share a device, and every device constraint
+ * (v_i, d_j) must have p(v_i) = d_j.  One pair at a time, one partition at a time.
+ * pairs is [num_pairs][2] vertices, pins is [num_pins][2] = {vertex, device};
+ * valid_out[j] = 1 if partition j meets all of them, violations_out[j] (may be NULL)
+ * counts the constraints it breaks.  Returns 0; -3 an index out of range.
+ */
+int cp_oracle_validate(int32_t n, int k, int32_t P, const uint8_t *assignments,
+                       int64_t num_pairs, const int32_t *pairs, int64_t num_pins, const int32_t *pins,
+                       uint8_t *valid_out, int32_t *violations_out)
+{
+    for (int64_t i = 0; i < num_pairs; ++i)
+        if (pairs[2 * i] < 0 || pairs[2 * i] >= n || pairs[2 * i + 1] < 0 || pairs[2 * i + 1] >= n) return -3;
+    for (int64_t i = 0; i < num_pins; ++i)
+        if (pins[2 * i] < 0 || pins[2 * i] >= n || pins[2 * i + 1] < 0 || pins[2 * i + 1] >= k) return -3;
+    for (int32_t j = 0; j < P; ++j) {
+        const uint8_t *p = assignments + (size_t)j * n;
+        int32_t broken = 0;
+        for (int64_t i = 0; i < num_pairs; ++i)
+            if (p[pairs[2 * i]] != p[pairs[2 * i + 1]]) ++broken;
+        for (int64_t i = 0; i < num_pins; ++i)
+            if (p[pins[2 * i]] != pins[2 * i + 1]) ++broken;
+        valid_out[j] = broken == 0;
+        if (violations_out) violations_out[j] = broken;
+    }
+    return 0;
+}

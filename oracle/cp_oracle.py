@@ -37,6 +37,9 @@ def _load():
         lib.cp_oracle_ranks.argtypes = [C.c_int32, i32p, i32p, i64p, i64p, i64p, i64p]
         lib.cp_oracle_pct_order.restype = C.c_int
         lib.cp_oracle_pct_order.argtypes = [C.c_int32, C.c_int, C.c_int32, u8p, i64p, i32p, i32p, C.c_int]
+        lib.cp_oracle_validate.restype = C.c_int
+        lib.cp_oracle_validate.argtypes = [C.c_int32, C.c_int, C.c_int32, u8p, C.c_int64, i32p, C.c_int64, i32p,
+                                           u8p, i32p]
         _lib = lib
     return _lib
 
@@ -187,3 +190,24 @@ def pct_order(k, assignments, b, threads=0):
     if rc:
         raise ValueError(f"pct_order failed with code {rc}")
     return order, seg
+
+
+def validate(k, assignments, pairs, pins):
+    """Section 2's collocation pairs (each [v_i, v_j]) and device constraints (each
+    [v_i, d_j]) checked for every row of ``assignments``.  Returns (valid uint8 [P],
+    violations int32 [P])."""
+    lib = _load()
+    a = np.ascontiguousarray(assignments, dtype=np.uint8)
+    P, n = a.shape
+    pr = np.ascontiguousarray(np.asarray(pairs, dtype=np.int32).reshape(-1, 2))
+    pn = np.ascontiguousarray(np.asarray(pins, dtype=np.int32).reshape(-1, 2))
+    pr_arg = pr if pr.size else np.zeros((1, 2), dtype=np.int32)
+    pn_arg = pn if pn.size else np.zeros((1, 2), dtype=np.int32)
+    valid = np.zeros(P, dtype=np.uint8)
+    broken = np.zeros(P, dtype=np.int32)
+    rc = lib.cp_oracle_validate(n, int(k), P, _ptr(a, C.c_uint8), pr.shape[0], _ptr(pr_arg, C.c_int32),
+                                pn.shape[0], _ptr(pn_arg, C.c_int32), _ptr(valid, C.c_uint8),
+                                _ptr(broken, C.c_int32))
+    if rc:
+        raise ValueError(f"validate failed with code {rc}")
+    return valid, broken

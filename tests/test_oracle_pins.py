@@ -607,3 +607,48 @@ def test_pct_order_against_lexsort_and_precedence(oracle):
         same = w.assignments[j][src] == w.assignments[j][w.succ_idx]
         assert (pos[src][same] < pos[w.succ_idx][same]).all()
         assert np.array_equal(np.diff(seg[j]), np.bincount(w.assignments[j], minlength=w.k))
+
+
+# ------------------------------------------------------------------ placement constraints (section 2)
+
+def test_validate_hand_example(oracle):
+    # vertices 0 and 3 must share a device, so must 1 and 2; vertex 4 must sit on device 1
+    pairs = [[0, 3], [1, 2]]
+    pins = [[4, 1]]
+    a = np.array([[0, 1, 1, 0, 1],      # all three hold
+                  [0, 1, 1, 0, 0],      # the device constraint is broken
+                  [0, 1, 0, 1, 1],      # both pairs are broken
+                  [2, 2, 2, 2, 1]], dtype=np.uint8)
+    valid, broken = oracle.validate(3, a, pairs, pins)
+    assert valid.tolist() == [1, 0, 0, 1] and broken.tolist() == [0, 1, 2, 0]
+    # no constraints: everything is valid
+    valid, broken = oracle.validate(3, a, [], [])
+    assert valid.tolist() == [1, 1, 1, 1] and broken.tolist() == [0, 0, 0, 0]
+
+
+def test_validate_against_set_formulation(oracle):
+    """The same through the relations as sets: p must be constant on every pair and map
+    every constrained vertex to its device."""
+    rng = np.random.default_rng(500)
+    n, k, P = 40, 4, 60
+    pairs = rng.integers(0, n, size=(12, 2))
+    pins = np.stack([rng.integers(0, n, size=6), rng.integers(0, k, size=6)], axis=1)
+    a = rng.integers(0, k, size=(P, n), dtype=np.uint8)
+    a[:10, pairs[:, 1]] = a[:10, pairs[:, 0]]          # make some partitions satisfy the pairs ...
+    for _ in range(3):                                   # (chains of pairs need a few rounds)
+        a[:10, pairs[:, 1]] = a[:10, pairs[:, 0]]
+    valid, broken = oracle.validate(k, a, pairs, pins)
+    for j in range(P):
+        exp = sum(int(a[j, u] != a[j, v]) for u, v in pairs) + sum(int(a[j, v] != d) for v, d in pins)
+        assert broken[j] == exp and valid[j] == (exp == 0)
+    # symmetric relation: swapping the two ends of every pair changes nothing
+    v2, b2 = oracle.validate(k, a, pairs[:, ::-1], pins)
+    assert np.array_equal(v2, valid) and np.array_equal(b2, broken)
+    # a partition that puts everything on the device every pin names is valid when all pins agree
+    one = np.full((1, n), 2, dtype=np.uint8)
+    assert oracle.validate(k, one, pairs, [[3, 2], [7, 2]])[0].tolist() == [1]
+    assert oracle.validate(k, one, pairs, [[3, 2], [7, 1]])[0].tolist() == [0]
+    with pytest.raises(ValueError):
+        oracle.validate(k, one, [[0, n]], [])
+    with pytest.raises(ValueError):
+        oracle.validate(k, one, [], [[0, k]])
