@@ -58,6 +58,7 @@ extern "C" {
 #define CP_STATUS_OK             0
 #define CP_STATUS_BAD_DEVICE_ID  1   /* some assignments entry is >= k: the call's outputs are meaningless
                                         (the entry was replaced by a valid device so that no access leaves its table) */
+#define CP_STATUS_BAD_CONSTRAINT  4   /* cp_validate: a constraint names a vertex >= n or a device >= k; it was skipped */
 #define CP_STATUS_B_OUT_OF_RANGE 2   /* cp_pct_order: some b lies outside [0, max_b]: the order is meaningless;
                                         status values are bit flags and may be or-ed */
 
@@ -248,6 +249,25 @@ int cp_pct_order(const cp_graph *g, int32_t batch, int32_t k,
                  const void *blevel, int tick_dtype, int b_layout, int64_t max_b,
                  void *workspace, size_t workspace_bytes, void *stream,
                  int32_t *order_out, int32_t *seg_out, int32_t *status_out);
+
+/*
+ * Validity of `batch` partitions under the placement constraints of the problem
+ * statement (paper, section 2, the collocation and the device constraint equations):
+ * every collocation pair (v_i, v_j) must share a device, every device constraint
+ * (v_i, d_j) must have p(v_i) = d_j.  Needs no graph.  Only enqueues work on `stream`.
+ *
+ *   n, k          vertices, devices
+ *   assignments   device uint8, laid out per assign_layout (CP_ASSIGN_*)
+ *   pairs         device int32 [num_pairs][2]; may be NULL when num_pairs = 0
+ *   pins          device int32 [num_pins][2] = {vertex, device}; may be NULL when num_pins = 0
+ *   valid_out     device uint8 [batch]: 1 if the partition meets every constraint
+ *   violations_out  device int32 [batch] or NULL: constraints the partition breaks
+ *   status_out    device int32: CP_STATUS_BAD_CONSTRAINT if an index is out of range
+ * Errors: CP_ERR_NULL, CP_ERR_SIZE (n < 1, batch < 1, k < 1 or > 255, a negative count), CP_ERR_ARG, CP_ERR_HIP.
+ */
+int cp_validate(int32_t n, int32_t batch, int32_t k, const uint8_t *assignments, int assign_layout,
+                int64_t num_pairs, const int32_t *pairs, int64_t num_pins, const int32_t *pins,
+                void *stream, uint8_t *valid_out, int32_t *violations_out, int32_t *status_out);
 
 /*
  * The device-free ranks of section 3.2: upRank (equation for the upward rank), downRank

@@ -27,7 +27,7 @@ STATUS_BAD_DEVICE_ID = 1
 EXPORTS = (
     "cp_graph_create", "cp_graph_get_info", "cp_graph_upload", "cp_graph_destroy",
     "cp_eval_workspace_bytes", "cp_eval_choose_plan", "cp_eval", "cp_critical_path", "cp_ranks_workspace_bytes", "cp_ranks",
-    "cp_pct_order_workspace_bytes", "cp_pct_order",
+    "cp_pct_order_workspace_bytes", "cp_pct_order", "cp_validate",
     "cp_profile_create", "cp_profile_reset",
     "cp_profile_count", "cp_profile_read", "cp_profile_destroy", "cp_cost_magic",
     "cp_error_string",
@@ -95,6 +95,9 @@ def load_library():
     lib.cp_pct_order.restype = C.c_int
     lib.cp_pct_order.argtypes = [vp, C.c_int32, C.c_int32, vp, C.c_int, vp, C.c_int, C.c_int, C.c_int64,
                                  vp, C.c_size_t, vp, vp, vp, vp]
+    lib.cp_validate.restype = C.c_int
+    lib.cp_validate.argtypes = [C.c_int32, C.c_int32, C.c_int32, vp, C.c_int, C.c_int64, vp, C.c_int64, vp, vp,
+                                vp, vp, vp]
     lib.cp_ranks_workspace_bytes.restype = C.c_int
     lib.cp_ranks_workspace_bytes.argtypes = [vp, C.POINTER(C.c_size_t)]
     lib.cp_ranks.restype = C.c_int
@@ -421,6 +424,45 @@ def cp_pct_order(graph: CpGraph, assignments, k: int, b, *, max_b: int = 0,
         if st & STATUS_B_OUT_OF_RANGE:
             raise ValueError("some b lies outside [0, max_b]")
     return out["order"], out["seg"]
+
+
+STATUS_BAD_CONSTRAINT = 4
+
+
+def cp_validate(assignments, k: int, pairs=None, pins=None, *, assign_layout=ASSIGN_PARTITION_MAJOR,
+                stream=None, check_status=True):
+    """cp_validate on torch tensors: ``pairs`` int32 [*][2] vertices that must share a
+    device, ``pins`` int32 [*][2] = {vertex, device}; both on the device of
+    ``assignments`` (or None).  Returns (valid uint8 [batch], violations int32 [batch])."""
+    import torch
+    lib = load_library()
+    dev = assignments.device
+    if assign_layout == ASSIGN_PARTITION_MAJOR:
+        batch, n = (int(x) for x in assignments.shape)
+    else:
+        n, batch = (int(x) for x in assignments.shape)
+
+    def arg(t):
+        if t is None or t.numel() == 0:
+            return 0, C.c_void_p()
+        assert t.is_cuda and t.dtype == torch.int32 and t.is_contiguous() and t.shape[-1] == 2
+        return int(t.numel() // 2), C.c_void_p(t.data_ptr())
+
+    n_pairs, p_pairs = arg(pairs)
+    n_pins, p_pins = arg(pins)
+    valid = torch.empty(batch, dtype=torch.uint8, device=dev)
+    broken = torch.empty(batch, dtype=torch.int32, device=dev)
+    status = torch.empty(1, dtype=torch.int32, device=dev)
+    rc = lib.cp_validate(n, batch, int(k), C.c_void_p(assignments.data_ptr()), int(assign_layout), n_pairs, p_pairs,
+                         n_pins, p_pins, _stream_ptr(stream), C.c_void_p(valid.data_ptr()),
+                         C.c_void_p(broken.data_ptr()), C.c_void_p(status.data_ptr()))
+    if rc:
+        raise CpError(rc, "cp_validate")
+    if check_status:
+        torch.cuda.synchronize(dev)
+        if int(status.item()) & STATUS_BAD_CONSTRAINT:
+            raise ValueError("a constraint names a vertex >= n or a device >= k")
+    return valid, broken
 
 
 def cp_ranks(graph: CpGraph, *, stream=None):

@@ -556,6 +556,21 @@ int cp_pct_order(const cp_graph *g, int32_t batch, int32_t k,
     return launch_pct_order(s, stream);
 }
 
+int cp_validate(int32_t n, int32_t batch, int32_t k, const uint8_t *assignments, int assign_layout,
+                int64_t num_pairs, const int32_t *pairs, int64_t num_pins, const int32_t *pins,
+                void *stream, uint8_t *valid_out, int32_t *violations_out, int32_t *status_out) {
+    if (n < 1 || batch < 1 || k < 1 || k > 255 || num_pairs < 0 || num_pins < 0) return CP_ERR_SIZE;
+    if (assign_layout != CP_ASSIGN_PARTITION_MAJOR && assign_layout != CP_ASSIGN_VERTEX_MAJOR) return CP_ERR_ARG;
+    if (!assignments || !valid_out || !status_out || (num_pairs > 0 && !pairs) || (num_pins > 0 && !pins))
+        return CP_ERR_NULL;
+    int rc = launch_clear(nullptr, 1, status_out, stream);
+    if (rc) return rc;
+    const int64_t sp = assign_layout == CP_ASSIGN_PARTITION_MAJOR ? n : 1;
+    const int64_t sv = assign_layout == CP_ASSIGN_PARTITION_MAJOR ? 1 : batch;
+    return launch_validate(assignments, sp, sv, n, batch, k, num_pairs, pairs, num_pins, pins, valid_out,
+                           violations_out, status_out, stream);
+}
+
 int cp_ranks_workspace_bytes(const cp_graph *g, size_t *out_bytes) {
     if (!g || !out_bytes) return CP_ERR_NULL;
     size_t eval = 0;

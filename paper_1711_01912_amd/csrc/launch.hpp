@@ -78,6 +78,9 @@ size_t pct_counts_bytes(int32_t n, int32_t P);
 int32_t pct_sort_tiles(int32_t n);
 int launch_pct_order(const PctOrderLaunch &s, void *stream);
 
+int launch_validate(const uint8_t *assign, int64_t a_stride_p, int64_t a_stride_v, int32_t n, int32_t P, int32_t k,
+                    int64_t num_pairs, const int32_t *pairs, int64_t num_pins, const int32_t *pins,
+                    uint8_t *valid, int32_t *violations, int32_t *status, void *stream);
 int launch_zero_bytes(uint8_t *dst, int64_t bytes, void *stream);
 int launch_zero_words(uint64_t *dst, int64_t words, void *stream);
 int launch_ranks(const void *b, const void *tl, const void *c, bool narrow, int tick_bytes, int32_t n,

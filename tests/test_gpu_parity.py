@@ -434,3 +434,47 @@ def test_pct_order_reports_a_bound_that_is_too_small(gpu):
     with pytest.raises(ValueError):
         gpu.cp_pct_order(g, a, w.k, out["b"], max_b=int(out["cp"].max().item()) - 1)
     g.close()
+
+
+# ------------------------------------------------------------------ placement constraints (section 2)
+
+@pytest.mark.parametrize("layout", [0, 1])
+def test_validate_against_the_oracle(gpu, oracle, layout):
+    import torch
+    rng = np.random.default_rng(51)
+    w = make_workload("inception", P=300)
+    # constraints that one hidden placement satisfies: pairs inside its device classes, pins to its devices
+    hidden = rng.integers(0, w.k, size=w.n).astype(np.uint8)
+    u = rng.integers(0, w.n, size=1000)
+    v = np.array([rng.choice(np.nonzero(hidden == hidden[x])[0]) for x in u])
+    pairs = np.stack([u, v], axis=1).astype(np.int32)
+    pv = rng.integers(0, w.n, size=700)
+    pins = np.stack([pv, hidden[pv]], axis=1).astype(np.int32)
+    a = w.assignments.copy()
+    a[:20] = hidden                                   # valid
+    for j in range(20, 40):                           # a few constraints broken
+        a[j] = hidden
+        flip = rng.integers(0, w.n, size=j - 19)
+        a[j, flip] = (a[j, flip] + 1) % w.k
+    ref_valid, ref_broken = oracle.validate(w.k, a, pairs, pins)
+    assert 0 < ref_valid.sum() < w.P
+    a_dev = torch.from_numpy(np.ascontiguousarray(a if layout == 0 else a.T)).to("cuda:0")
+    valid, broken = gpu.cp_validate(a_dev, w.k, torch.from_numpy(pairs).to("cuda:0"),
+                                    torch.from_numpy(pins).to("cuda:0"), assign_layout=layout)
+    assert np.array_equal(valid.cpu().numpy(), ref_valid)
+    assert np.array_equal(broken.cpu().numpy(), ref_broken)
+    # no constraints at all; pairs only; pins only
+    for pr, pn in ((None, None), (pairs, None), (None, pins)):
+        rv, rb = oracle.validate(w.k, a, pr if pr is not None else [], pn if pn is not None else [])
+        v, b = gpu.cp_validate(a_dev, w.k, None if pr is None else torch.from_numpy(pr).to("cuda:0"),
+                               None if pn is None else torch.from_numpy(pn).to("cuda:0"), assign_layout=layout)
+        assert np.array_equal(v.cpu().numpy(), rv) and np.array_equal(b.cpu().numpy(), rb)
+
+
+def test_validate_reports_an_index_out_of_range(gpu):
+    import torch
+    a = torch.zeros((3, 10), dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(ValueError):
+        gpu.cp_validate(a, 2, torch.tensor([[0, 10]], dtype=torch.int32, device="cuda:0"))
+    with pytest.raises(ValueError):
+        gpu.cp_validate(a, 2, None, torch.tensor([[0, 2]], dtype=torch.int32, device="cuda:0"))
