@@ -183,8 +183,9 @@ int cp_eval_choose_plan(const cp_graph *g, int32_t batch, int32_t k, const int64
  *   status_out    device int32, required: CP_STATUS_* after the stream has drained
  *   profile       NULL, or a profile whose next slot receives this call's stage timestamps
  *
- * Dependencies between outputs: cp_out needs blevel_out; mask_out needs cp_out,
- * blevel_out and tlevel_out (CP_ERR_ARG otherwise).
+ * Dependencies between outputs: mask_out needs cp_out, blevel_out and tlevel_out; cp_out needs
+ * blevel_out unless the resident-window plan runs (it keeps a running maximum, so CP alone costs
+ * no output traffic; cp_eval_choose_plan tells which plan CP_PLAN_AUTO takes).  CP_ERR_ARG otherwise.
  * Errors: CP_ERR_NULL, CP_ERR_SIZE, CP_ERR_SPEED, CP_ERR_BANDWIDTH, CP_ERR_OVERFLOW
  * (CP_TICK_I32 with a bound >= 2^31), CP_ERR_WORKSPACE, CP_ERR_STATE, CP_ERR_ARG, CP_ERR_HIP.
  */

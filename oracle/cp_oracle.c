@@ -358,3 +358,100 @@ int cp_oracle_validate(int32_t n, int k, int32_t P, const uint8_t *assignments,
     }
     return 0;
 }
+
+/*
+ * Critical-path move search.  The paper's path-based strategies (section 3.2) rest on
+ * one idea: the critical path decides the running time, so its vertices deserve the
+ * best placement.  This is that idea as a local search over partitions, one vertex
+ * move at a time (the paper itself stops at a constructive heuristic):
+ *
+ *   neighbourhood of p = all partitions that differ from p in exactly one vertex of
+ *   p's critical path (the lexicographically smallest one), that vertex placed on any
+ *   other device.  Candidate number j = i * (k-1) + r moves path vertex number i to
+ *   the r-th device other than its own (devices in increasing order).
+ *
+ *   step: evaluate CP of every candidate that meets the placement constraints, take
+ *   the smallest (lowest candidate number on ties); if it is smaller than CP(p), move
+ *   there and repeat, else stop.
+ */
+int cp_oracle_neighbours(int32_t n, int k, const uint8_t *base, int32_t len, const int32_t *path,
+                         uint8_t *out)
+{
+    if (k < 2) return 0;
+    for (int32_t i = 0; i < len; ++i) {
+        int32_t v = path[i];
+        if (v < 0 || v >= n) return -3;
+        for (int r = 0; r < k - 1; ++r) {
+            uint8_t *row = out + ((size_t)i * (k - 1) + r) * n;
+            memcpy(row, base, (size_t)n);
+            row[v] = (uint8_t)(r < base[v] ? r : r + 1);
+        }
+    }
+    return 0;
+}
+
+/* Lowest index with the smallest cp among the entries with valid != 0 (all, if valid is
+ * NULL).  index_out = -1 and value_out untouched when there is none. */
+void cp_oracle_argmin(int32_t P, const int64_t *cp, const uint8_t *valid, int32_t *index_out,
+                      int64_t *value_out)
+{
+    *index_out = -1;
+    for (int32_t j = 0; j < P; ++j) {
+        if (valid && !valid[j]) continue;
+        if (*index_out < 0 || cp[j] < *value_out) { *index_out = j; *value_out = cp[j]; }
+    }
+}
+
+/*
+ * The whole search from `assignment` (in: start, out: result).  cp_trace[0] is the
+ * start's CP, cp_trace[i] the CP after move i; moves_out[i] = {vertex, new device}.
+ * Returns the number of moves made (<= max_moves) or a negative error.
+ */
+int cp_oracle_search(int32_t n, const int32_t *succ_ptr, const int32_t *succ_idx, const int64_t *succ_t,
+                     const int64_t *c, int k, const int64_t *speeds, const int64_t *bandwidth,
+                     uint8_t *assignment, int64_t num_pairs, const int32_t *pairs, int64_t num_pins,
+                     const int32_t *pins, int32_t max_moves, int32_t max_len, int64_t *cp_trace,
+                     int32_t *moves_out, int threads)
+{
+    int32_t *path = (int32_t *)malloc(((size_t)max_len + 1) * sizeof(int32_t));
+    size_t max_cand = (size_t)max_len * (size_t)(k > 1 ? k - 1 : 1);
+    uint8_t *cand = (uint8_t *)malloc(max_cand * (size_t)n + 1);
+    int64_t *cp = (int64_t *)malloc((max_cand + 1) * sizeof(int64_t));
+    uint8_t *valid = (uint8_t *)malloc(max_cand + 1);
+    int moves = 0, rc = 0;
+    if (!path || !cand || !cp || !valid) { rc = -2; goto done; }
+    for (;;) {
+        int64_t cp_base;
+        int32_t len;
+        rc = cp_oracle_eval(n, succ_ptr, succ_idx, succ_t, c, k, speeds, bandwidth, 1, assignment, &cp_base,
+                            NULL, NULL, NULL, 1, NULL);
+        if (rc) goto done;
+        cp_trace[moves] = cp_base;
+        if (moves >= max_moves || k < 2) break;
+        rc = cp_oracle_critical_path(n, succ_ptr, succ_idx, succ_t, c, k, speeds, bandwidth, 1, assignment,
+                                     max_len, path, &len);
+        if (rc) goto done;
+        rc = cp_oracle_neighbours(n, k, assignment, len, path, cand);
+        if (rc) goto done;
+        int32_t ncand = len * (k - 1);
+        rc = cp_oracle_eval(n, succ_ptr, succ_idx, succ_t, c, k, speeds, bandwidth, ncand, cand, cp, NULL,
+                            NULL, NULL, threads, NULL);
+        if (rc) goto done;
+        rc = cp_oracle_validate(n, k, ncand, cand, num_pairs, pairs, num_pins, pins, valid, NULL);
+        if (rc) goto done;
+        int32_t best;
+        int64_t best_cp = 0;
+        cp_oracle_argmin(ncand, cp, valid, &best, &best_cp);
+        if (best < 0 || best_cp >= cp_base) break;
+        int32_t v = path[best / (k - 1)];
+        uint8_t d = cand[(size_t)best * n + v];
+        assignment[v] = d;
+        moves_out[2 * moves] = v;
+        moves_out[2 * moves + 1] = d;
+        ++moves;
+    }
+    rc = moves;
+done:
+    free(path); free(cand); free(cp); free(valid);
+    return rc;
+}

@@ -40,6 +40,13 @@ def _load():
         lib.cp_oracle_validate.restype = C.c_int
         lib.cp_oracle_validate.argtypes = [C.c_int32, C.c_int, C.c_int32, u8p, C.c_int64, i32p, C.c_int64, i32p,
                                            u8p, i32p]
+        lib.cp_oracle_neighbours.restype = C.c_int
+        lib.cp_oracle_neighbours.argtypes = [C.c_int32, C.c_int, u8p, C.c_int32, i32p, u8p]
+        lib.cp_oracle_argmin.restype = None
+        lib.cp_oracle_argmin.argtypes = [C.c_int32, i64p, u8p, i32p, i64p]
+        lib.cp_oracle_search.restype = C.c_int
+        lib.cp_oracle_search.argtypes = [C.c_int32, i32p, i32p, i64p, i64p, C.c_int, i64p, i64p, u8p, C.c_int64,
+                                         i32p, C.c_int64, i32p, C.c_int32, C.c_int32, i64p, i32p, C.c_int]
         _lib = lib
     return _lib
 
@@ -211,3 +218,66 @@ def validate(k, assignments, pairs, pins):
     if rc:
         raise ValueError(f"validate failed with code {rc}")
     return valid, broken
+
+
+def neighbours(k, base, path):
+    """All partitions that differ from ``base`` in exactly one vertex of ``path``:
+    uint8 [len(path) * (k-1)][n], candidate i*(k-1)+r moves path[i] to the r-th device
+    other than its own."""
+    lib = _load()
+    b = np.ascontiguousarray(base, dtype=np.uint8)
+    pth = np.ascontiguousarray(path, dtype=np.int32)
+    out = np.zeros((len(pth) * (k - 1), b.shape[0]), dtype=np.uint8)
+    if out.size:
+        rc = lib.cp_oracle_neighbours(b.shape[0], int(k), _ptr(b, C.c_uint8), len(pth), _ptr(pth, C.c_int32),
+                                      _ptr(out, C.c_uint8))
+        if rc:
+            raise ValueError(f"neighbours failed with code {rc}")
+    return out
+
+
+def argmin(cp, valid=None):
+    """(index, value) of the lowest-index minimum of ``cp`` over the valid entries;
+    (-1, None) when there is none."""
+    lib = _load()
+    c = np.ascontiguousarray(cp, dtype=np.int64)
+    idx = C.c_int32(-1)
+    val = C.c_int64(0)
+    vptr = None
+    if valid is not None:
+        v = np.ascontiguousarray(valid, dtype=np.uint8)
+        vptr = _ptr(v, C.c_uint8)
+    lib.cp_oracle_argmin(len(c), _ptr(c if len(c) else np.zeros(1, dtype=np.int64), C.c_int64), vptr,
+                         C.byref(idx), C.byref(val))
+    return (int(idx.value), int(val.value)) if idx.value >= 0 else (-1, None)
+
+
+def search(n, succ_ptr, succ_idx, succ_t, c, speeds, bandwidth, start, max_len, pairs=(), pins=(),
+           max_moves=1000, threads=1):
+    """Critical-path move search from ``start`` (uint8 [n]).  Returns (assignment,
+    cp_trace int64 [moves+1], moves int32 [moves][2] = {vertex, new device})."""
+    lib = _load()
+    sp = np.ascontiguousarray(succ_ptr, dtype=np.int32)
+    si = np.ascontiguousarray(succ_idx, dtype=np.int32)
+    st = np.ascontiguousarray(succ_t, dtype=np.int64)
+    if si.size == 0:
+        si = np.zeros(1, dtype=np.int32)
+        st = np.zeros(1, dtype=np.int64)
+    cc = np.ascontiguousarray(c, dtype=np.int64)
+    s = np.ascontiguousarray(speeds, dtype=np.int64)
+    bw = np.ascontiguousarray(bandwidth, dtype=np.int64)
+    a = np.array(start, dtype=np.uint8).copy()
+    pr = np.ascontiguousarray(np.asarray(pairs, dtype=np.int32).reshape(-1, 2))
+    pn = np.ascontiguousarray(np.asarray(pins, dtype=np.int32).reshape(-1, 2))
+    pr_arg = pr if pr.size else np.zeros((1, 2), dtype=np.int32)
+    pn_arg = pn if pn.size else np.zeros((1, 2), dtype=np.int32)
+    trace = np.zeros(max_moves + 1, dtype=np.int64)
+    moves = np.zeros((max(max_moves, 1), 2), dtype=np.int32)
+    rc = lib.cp_oracle_search(n, _ptr(sp, C.c_int32), _ptr(si, C.c_int32), _ptr(st, C.c_int64),
+                              _ptr(cc, C.c_int64), int(s.shape[0]), _ptr(s, C.c_int64), _ptr(bw, C.c_int64),
+                              _ptr(a, C.c_uint8), pr.shape[0], _ptr(pr_arg, C.c_int32), pn.shape[0],
+                              _ptr(pn_arg, C.c_int32), int(max_moves), int(max_len), _ptr(trace, C.c_int64),
+                              _ptr(moves, C.c_int32), int(threads))
+    if rc < 0:
+        raise ValueError(f"search failed with code {rc}")
+    return a, trace[:rc + 1].copy(), moves[:rc].copy()

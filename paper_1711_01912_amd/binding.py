@@ -315,8 +315,11 @@ def cp_eval(graph: CpGraph, assignments, speeds, bandwidth, *, want=("cp", "b", 
     want = set(want)
     if "mask" in want:
         want |= {"cp", "b", "tl"}
-    if "cp" in want:
-        want.add("b")
+    if "cp" in want and "b" not in want:
+        # CP alone: the resident-window plan needs no b array for it
+        used = plan if plan != PLAN_AUTO else choose_plan(graph, batch, s, bw, tick_bytes)
+        if used != PLAN_RESIDENT_WINDOW:
+            want.add("b")
     rows, cols = (n, batch) if out_layout == OUT_VERTEX_MAJOR else (batch, n)
     if "cp" in want and "cp" not in out:
         out["cp"] = torch.empty(batch, dtype=torch.int64, device=dev)

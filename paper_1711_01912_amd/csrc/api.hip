@@ -270,7 +270,6 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
     if (!assignments || !speeds || !bandwidth || !workspace || !status_out) return CP_ERR_NULL;
     if (tick_dtype != CP_TICK_I32 && tick_dtype != CP_TICK_I64) return CP_ERR_ARG;
     if (out_layout != CP_OUT_VERTEX_MAJOR && out_layout != CP_OUT_PARTITION_MAJOR) return CP_ERR_ARG;
-    if (cp_out && !blevel_out) return CP_ERR_ARG;
     if (mask_out && (!cp_out || !blevel_out || !tlevel_out)) return CP_ERR_ARG;
     if (!g->device_blob) return CP_ERR_STATE;
     const Packed &p = g->packed;
@@ -295,6 +294,8 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
         use = can_window && window_preferred(p, cfg_b, cfg_t, batch, (size_t)tick_dtype)
                   ? CP_PLAN_RESIDENT_WINDOW : CP_PLAN_WAVE_COLUMN;
     if (use == CP_PLAN_RESIDENT_WINDOW && !can_window) return CP_ERR_ARG;
+    // the wave-column plan reads CP off the stored b-levels; the resident-window sweep keeps a running maximum
+    if (cp_out && !blevel_out && use != CP_PLAN_RESIDENT_WINDOW) return CP_ERR_ARG;
 
     // workspace
     const bool need_pT = use == CP_PLAN_WAVE_COLUMN && assign_layout == CP_ASSIGN_PARTITION_MAJOR;
@@ -374,7 +375,7 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
                            ((uint64_t)p.n * (uint64_t)batch * 4) % 16 == 0 &&
                            window_config(p.win_t, k, (size_t)tick_dtype, device_window_lds_limit(), cfg_tm, true);
     if (use == CP_PLAN_RESIDENT_WINDOW) {
-        if (blevel_out && !direct_b) {
+        if ((blevel_out || cp_out) && !direct_b) {
             s.win = &p.win_b;
             rc = launch_gather_assign(s, d_pperm_b, stream);
             if (rc) return rc;
@@ -388,7 +389,7 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
 
     // ---- stage: b-level sweep
     CP_MARK(CP_STAGE_BLEVEL);
-    if (blevel_out) {
+    if (blevel_out || cp_out) {
         s.tsweep = false;
         s.dir = &p.col_b;
         s.win = &p.win_b;

@@ -271,6 +271,7 @@ def test_partial_outputs_and_determinism(gpu, oracle):
         assert np.array_equal(r1["b"], ref["b"]) and "tl" not in r1
         r2 = run_gpu(w, plan, want=("cp",))
         assert np.array_equal(r2["cp"], ref["cp"])
+        assert ("b" in r2) == (plan == COLUMN)         # the window sweep needs no b array for CP alone
         r3 = run_gpu(w, plan, want=("tl",))
         assert np.array_equal(r3["tl"], ref["tl"])
         r4 = run_gpu(w, plan)

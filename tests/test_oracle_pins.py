@@ -652,3 +652,83 @@ def test_validate_against_set_formulation(oracle):
         oracle.validate(k, one, [[0, n]], [])
     with pytest.raises(ValueError):
         oracle.validate(k, one, [], [[0, k]])
+
+
+# ------------------------------------------------------------------ critical-path move search
+
+def test_neighbours_are_all_single_moves_of_path_vertices(oracle):
+    base = np.array([0, 2, 1, 1, 0], dtype=np.uint8)
+    out = oracle.neighbours(3, base, [3, 0])
+    assert out.tolist() == [[0, 2, 1, 0, 0], [0, 2, 1, 2, 0],        # vertex 3 (on 1) -> 0, 2
+                            [1, 2, 1, 1, 0], [2, 2, 1, 1, 0]]        # vertex 0 (on 0) -> 1, 2
+    rng = np.random.default_rng(600)
+    n, k = 30, 5
+    base = rng.integers(0, k, size=n, dtype=np.uint8)
+    path = rng.permutation(n)[:7]
+    out = oracle.neighbours(k, base, path)
+    seen = set()
+    for row in out:
+        diff = np.nonzero(row != base)[0]
+        assert len(diff) == 1 and diff[0] in path
+        seen.add((int(diff[0]), int(row[diff[0]])))
+    assert seen == {(int(v), d) for v in path for d in range(k) if d != base[v]}
+    assert oracle.neighbours(1, np.zeros(4, dtype=np.uint8), [1, 2]).shape == (0, 4)
+
+
+def test_argmin_takes_the_first_of_the_smallest_valid(oracle):
+    assert oracle.argmin([5, 3, 9, 3]) == (1, 3)
+    assert oracle.argmin([5, 3, 9, 3], [1, 0, 1, 1]) == (3, 3)
+    assert oracle.argmin([5, 3, 9, 3], [1, 0, 1, 0]) == (0, 5)
+    assert oracle.argmin([5, 3], [0, 0]) == (-1, None)
+    assert oracle.argmin([]) == (-1, None)
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_search_descends_to_a_local_optimum(oracle, seed):
+    """Every move lowers CP; at the end no single move of a critical-path vertex does
+    (checked move by move with the brute-force evaluator); the result is never better
+    than the true optimum over all k^n partitions."""
+    rng = np.random.default_rng(700 + seed)
+    n, level, src, dst = random_layered_dag(rng, [2, 3, 2, 2], 1, 2, 2)
+    t = rng.integers(1, 30, size=len(src))
+    c = rng.integers(1, 20, size=n)
+    csr = build_csr(n, src, dst, t, level)
+    s = np.array([1, 3])
+    B = np.array([[1, 2], [4, 1]])
+    start = rng.integers(0, 2, size=n, dtype=np.uint8)
+    final, trace, moves = oracle.search(n, csr["succ_ptr"], csr["succ_idx"], csr["succ_t"], c, s, B, start,
+                                        max_len=csr["L"])
+    assert (np.diff(trace) < 0).all() and len(moves) == len(trace) - 1
+    edges = _edges(csr)
+    replay = start.copy()
+    for (v, d), cp_after in zip(moves, trace[1:]):
+        replay[v] = d
+        assert brute_force.evaluate(n, edges, c, s, B, replay)[0] == cp_after
+    assert np.array_equal(replay, final)
+    best, found = brute_force.critical_paths(n, edges, c, s, B, final)
+    assert best == trace[-1]
+    for v in min(found):
+        other = final.copy()
+        other[v] = 1 - other[v]
+        assert brute_force.evaluate(n, edges, c, s, B, other)[0] >= best
+    optimum = min(brute_force.evaluate(n, edges, c, s, B, np.array([(code >> i) & 1 for i in range(n)]))[0]
+                  for code in range(2 ** n))
+    assert optimum <= trace[-1] <= trace[0]
+
+
+def test_search_respects_constraints_and_the_move_limit(oracle):
+    w = make_workload("tiny")
+    start = w.assignments[0]
+    free, trace_free, moves_free = oracle.search(w.n, w.succ_ptr, w.succ_idx, w.succ_t, w.c, w.speeds,
+                                                 w.bandwidth, start, max_len=w.L)
+    assert len(moves_free) >= 2
+    # pin the first vertex that moved to where it started: that move is no longer allowed
+    v0 = int(moves_free[0][0])
+    pinned, trace_pin, moves_pin = oracle.search(w.n, w.succ_ptr, w.succ_idx, w.succ_t, w.c, w.speeds,
+                                                 w.bandwidth, start, max_len=w.L, pins=[[v0, int(start[v0])]])
+    assert pinned[v0] == start[v0] and all(int(m[0]) != v0 for m in moves_pin)
+    assert trace_pin[0] == trace_free[0]
+    one, trace_one, moves_one = oracle.search(w.n, w.succ_ptr, w.succ_idx, w.succ_t, w.c, w.speeds, w.bandwidth,
+                                              start, max_len=w.L, max_moves=1)
+    assert len(moves_one) == 1 and trace_one.tolist() == trace_free[:2].tolist()
+    assert np.array_equal(moves_one[0], moves_free[0])
