@@ -271,6 +271,35 @@ int cp_validate(int32_t n, int32_t batch, int32_t k, const uint8_t *assignments,
                 void *stream, uint8_t *valid_out, int32_t *violations_out, int32_t *status_out);
 
 /*
+ * Critical-path move search: a descent over partitions built from the paper's own
+ * pieces.  Section 3.2 places the critical path first because it decides the running
+ * time; here, from a start partition, every single move of a vertex of the current
+ * critical path (cp_critical_path's path) to another device is a candidate; candidate
+ * number i * (k-1) + r moves path vertex number i to the r-th device other than its own.
+ * All candidates are evaluated with cp_eval in batches of `chunk`; those that break a
+ * placement constraint (section 2, as in cp_validate) are left out; the candidate with
+ * the smallest CP (lowest number on ties) is taken if it is smaller than the current CP,
+ * and the step repeats; otherwise, or after max_moves moves, the search stops.
+ * The call blocks: it waits on `stream` between steps.
+ *
+ *   assignment   device uint8 [n]: in the start partition, out the result
+ *   pairs, pins  device, as for cp_validate (NULL with a count of 0)
+ *   chunk        candidates per cp_eval call (>= 1)
+ *   workspace    device, 256-byte aligned, >= cp_search_workspace_bytes(g, k, chunk)
+ *   cp_trace     host int64 [max_moves + 1]: CP of the start, then after each move
+ *   moves        host int32 [max_moves][2] = {vertex, new device}, or NULL
+ *   num_moves    host: moves made
+ *   evaluated    host: candidates evaluated, or NULL
+ * Errors: CP_ERR_NULL, CP_ERR_SIZE, CP_ERR_STATE, CP_ERR_WORKSPACE, CP_ERR_ARG (a device id
+ * >= k in the start), CP_ERR_SPEED, CP_ERR_BANDWIDTH, CP_ERR_HIP.
+ */
+int cp_search_workspace_bytes(const cp_graph *g, int32_t k, int32_t chunk, size_t *out_bytes);
+int cp_search(const cp_graph *g, int32_t k, const int64_t *speeds, const int64_t *bandwidth,
+              uint8_t *assignment, int64_t num_pairs, const int32_t *pairs, int64_t num_pins,
+              const int32_t *pins, int32_t max_moves, int32_t chunk, void *workspace, size_t workspace_bytes,
+              void *stream, int64_t *cp_trace, int32_t *moves, int32_t *num_moves, int64_t *evaluated);
+
+/*
  * The device-free ranks of section 3.2: upRank (equation for the upward rank), downRank
  * (equation for the downward rank) and totalRank = upRank + downRank (section 3.2.1).
  * Both rank equations add the vertex's own c, so upRank is the b-level and downRank the

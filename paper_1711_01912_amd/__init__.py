@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     cp_critical_path,
     cp_pct_order,
     cp_ranks,
+    cp_search,
     cp_validate,
     cp_eval,
     error_string,

@@ -28,6 +28,7 @@ EXPORTS = (
     "cp_graph_create", "cp_graph_get_info", "cp_graph_upload", "cp_graph_destroy",
     "cp_eval_workspace_bytes", "cp_eval_choose_plan", "cp_eval", "cp_critical_path", "cp_ranks_workspace_bytes", "cp_ranks",
     "cp_pct_order_workspace_bytes", "cp_pct_order", "cp_validate",
+    "cp_search_workspace_bytes", "cp_search",
     "cp_profile_create", "cp_profile_reset",
     "cp_profile_count", "cp_profile_read", "cp_profile_destroy", "cp_cost_magic",
     "cp_error_string",
@@ -98,6 +99,12 @@ def load_library():
     lib.cp_validate.restype = C.c_int
     lib.cp_validate.argtypes = [C.c_int32, C.c_int32, C.c_int32, vp, C.c_int, C.c_int64, vp, C.c_int64, vp, vp,
                                 vp, vp, vp]
+    lib.cp_search_workspace_bytes.restype = C.c_int
+    lib.cp_search_workspace_bytes.argtypes = [vp, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
+    lib.cp_search.restype = C.c_int
+    lib.cp_search.argtypes = [vp, C.c_int32, i64p, i64p, vp, C.c_int64, vp, C.c_int64, vp, C.c_int32, C.c_int32,
+                              vp, C.c_size_t, vp, i64p, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                              C.POINTER(C.c_int64)]
     lib.cp_ranks_workspace_bytes.restype = C.c_int
     lib.cp_ranks_workspace_bytes.argtypes = [vp, C.POINTER(C.c_size_t)]
     lib.cp_ranks.restype = C.c_int
@@ -466,6 +473,46 @@ def cp_validate(assignments, k: int, pairs=None, pins=None, *, assign_layout=ASS
         if int(status.item()) & STATUS_BAD_CONSTRAINT:
             raise ValueError("a constraint names a vertex >= n or a device >= k")
     return valid, broken
+
+
+def cp_search(graph: CpGraph, start, speeds, bandwidth, *, pairs=None, pins=None, max_moves=1000, chunk=256,
+              stream=None):
+    """cp_search on torch tensors: ``start`` is a uint8 CUDA tensor [n].  Returns a dict
+    with ``assignment`` (new tensor), ``cp_trace`` (int64 numpy, CP of the start and after
+    each move), ``moves`` (int32 numpy [moves][2]) and ``evaluated`` (candidates)."""
+    import torch
+    lib = load_library()
+    dev = start.device
+    s = np.ascontiguousarray(speeds, dtype=np.int64)
+    bw = np.ascontiguousarray(bandwidth, dtype=np.int64)
+    k = int(s.shape[0])
+    a = start.clone().contiguous()
+
+    def arg(t):
+        if t is None or t.numel() == 0:
+            return 0, C.c_void_p()
+        assert t.is_cuda and t.dtype == torch.int32 and t.is_contiguous() and t.shape[-1] == 2
+        return int(t.numel() // 2), C.c_void_p(t.data_ptr())
+
+    n_pairs, p_pairs = arg(pairs)
+    n_pins, p_pins = arg(pins)
+    need = C.c_size_t(0)
+    rc = lib.cp_search_workspace_bytes(graph._handle, k, int(chunk), C.byref(need))
+    if rc:
+        raise CpError(rc, "cp_search_workspace_bytes")
+    ws = torch.empty(need.value, dtype=torch.uint8, device=dev)
+    trace = np.zeros(max_moves + 1, dtype=np.int64)
+    moves = np.zeros((max(max_moves, 1), 2), dtype=np.int32)
+    done = C.c_int32(0)
+    seen = C.c_int64(0)
+    rc = lib.cp_search(graph._handle, k, _np_ptr(s, C.c_int64), _np_ptr(bw, C.c_int64), C.c_void_p(a.data_ptr()),
+                       n_pairs, p_pairs, n_pins, p_pins, int(max_moves), int(chunk), C.c_void_p(ws.data_ptr()),
+                       C.c_size_t(ws.numel()), _stream_ptr(stream), _np_ptr(trace, C.c_int64),
+                       _np_ptr(moves, C.c_int32), C.byref(done), C.byref(seen))
+    if rc:
+        raise CpError(rc, "cp_search")
+    return {"assignment": a, "cp_trace": trace[:done.value + 1].copy(), "moves": moves[:done.value].copy(),
+            "evaluated": int(seen.value)}
 
 
 def cp_ranks(graph: CpGraph, *, stream=None):

@@ -1,0 +1,265 @@
+// Critical-path move search on top of cp_eval.  The paper's path-based strategies
+// (section 3.2) place the critical path first because it decides the running time;
+// this is the same idea as a descent over partitions: all single moves of a vertex of
+// the current critical path to another device are evaluated in batches, the best one
+// that meets the placement constraints (section 2) is taken while it shortens the
+// critical path.  The evaluation is the library's own batched cp_eval; the kernels here
+// only build the candidates, pick the minimum and apply the move.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <climits>
+#include <cstdint>
+
+#include "cpeval_internal.hpp"
+#include "launch.hpp"
+
+namespace cpeval {
+
+namespace {
+
+// Candidate number j = i * (k-1) + r moves path vertex number i to the r-th device other
+// than its own.  Rows first + 0 .. first + count - 1 are written, 16 bytes per thread.
+__global__ __launch_bounds__(256) void neighbours_kernel(const uint8_t *__restrict__ base,
+                                                         const int32_t *__restrict__ path, int32_t n, int32_t k,
+                                                         int32_t first, int32_t count, uint8_t *__restrict__ out,
+                                                         int vector_ok) {
+    const int64_t at = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 16;
+    if (at >= n) return;
+    for (int32_t local = blockIdx.y; local < count; local += gridDim.y) {
+        const int32_t j = first + local;
+        const int32_t v = path[j / (k - 1)];
+        const int32_t r = j % (k - 1);
+        uint8_t *row = out + (int64_t)local * n;
+        if (vector_ok) {
+            uint4 x = *(const uint4 *)(base + at);
+            if (v >= at && v < at + 16) {
+                uint8_t *b8 = (uint8_t *)&x;
+                const int32_t own = b8[v - at];
+                b8[v - at] = (uint8_t)(r < own ? r : r + 1);
+            }
+            *(uint4 *)(row + at) = x;
+        } else {
+            const int64_t end = min((int64_t)n, at + 16);
+            for (int64_t i = at; i < end; ++i) {
+                const int32_t own = base[i];
+                row[i] = i == v ? (uint8_t)(r < own ? r : r + 1) : (uint8_t)own;
+            }
+        }
+    }
+}
+
+struct Best {
+    long long value;    // smallest CP so far, LLONG_MAX = none
+    long long index;    // its candidate number, -1 = none
+};
+
+__global__ void best_reset_kernel(Best *best) {
+    best->value = LLONG_MAX;
+    best->index = -1;
+}
+
+// Lowest-numbered minimum of cp[0..count) over the valid entries, merged into *best.
+// Chunks arrive in increasing candidate order, so a tie keeps the earlier candidate.
+__global__ __launch_bounds__(1024) void argmin_merge_kernel(const int64_t *__restrict__ cp,
+                                                            const uint8_t *__restrict__ valid, int32_t count,
+                                                            int32_t first, Best *best) {
+    __shared__ long long sv[16], si[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    long long v = LLONG_MAX, idx = LLONG_MAX;
+    for (int32_t i = tid; i < count; i += 1024) {
+        if (valid && !valid[i]) continue;
+        const long long c = cp[i];
+        if (c < v) { v = c; idx = i; }          // i grows, so the first minimum stays
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        const long long ov = __shfl_xor(v, off), oi = __shfl_xor(idx, off);
+        if (ov < v || (ov == v && oi < idx)) { v = ov; idx = oi; }
+    }
+    if (lane == 0) { sv[wave] = v; si[wave] = idx; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < 16; ++w)
+            if (sv[w] < v || (sv[w] == v && si[w] < idx)) { v = sv[w]; idx = si[w]; }
+        if (idx != LLONG_MAX && v < best->value) {
+            best->value = v;
+            best->index = (long long)first + idx;
+        }
+    }
+}
+
+// base[path vertex] = its new device; the move is also left in move[0..1] = {vertex, device}.
+__global__ void apply_move_kernel(uint8_t *base, const int32_t *path, int32_t k, const Best *best, int32_t *move) {
+    const int32_t j = (int32_t)best->index;
+    const int32_t v = path[j / (k - 1)];
+    const int32_t r = j % (k - 1);
+    const int32_t own = base[v];
+    const int32_t d = r < own ? r : r + 1;
+    base[v] = (uint8_t)d;
+    move[0] = v;
+    move[1] = d;
+}
+
+struct SearchLayout {
+    size_t eval_ws = 0, cand = 0, b = 0, cp = 0, valid = 0, path = 0, small = 0, total = 0;
+    size_t eval_bytes = 0;
+    int plan_chunk = 0;      // plan that evaluates a chunk of candidates
+    int tick = 4;
+};
+
+int search_layout(const cp_graph *g, int32_t k, int32_t chunk, const int64_t *speeds, const int64_t *bandwidth,
+                  SearchLayout &o) {
+    cp_graph_info info;
+    int rc = cp_graph_get_info(g, &info);
+    if (rc) return rc;
+    o.tick = info.min_tick_bytes;
+    // the plan is not known without the cost model: size for the costlier case (wave-column keeps b)
+    o.plan_chunk = CP_PLAN_WAVE_COLUMN;
+    if (speeds && bandwidth) {
+        rc = cp_eval_choose_plan(g, chunk, k, speeds, bandwidth, o.tick, &o.plan_chunk);
+        if (rc) return rc;
+    }
+    size_t ws_chunk = 0, ws_one = 0;
+    rc = cp_eval_workspace_bytes(g, chunk, k, CP_ASSIGN_PARTITION_MAJOR, CP_PLAN_AUTO, CP_OUT_VERTEX_MAJOR, o.tick,
+                                 &ws_chunk);
+    if (rc) return rc;
+    rc = cp_eval_workspace_bytes(g, 1, k, CP_ASSIGN_PARTITION_MAJOR, CP_PLAN_AUTO, CP_OUT_VERTEX_MAJOR, o.tick,
+                                 &ws_one);
+    if (rc) return rc;
+    const size_t n = (size_t)info.n;
+    o.eval_bytes = align_up(std::max(ws_chunk, ws_one));
+    const size_t b_cols = o.plan_chunk == CP_PLAN_RESIDENT_WINDOW ? 1 : (size_t)chunk;
+    size_t at = 0;
+    o.eval_ws = at; at += o.eval_bytes;
+    o.cand = at;    at += align_up((size_t)chunk * n);
+    o.b = at;       at += align_up(n * b_cols * (size_t)o.tick);
+    o.cp = at;      at += align_up((size_t)chunk * sizeof(int64_t));
+    o.valid = at;   at += align_up((size_t)chunk);
+    o.path = at;    at += align_up((size_t)info.L * sizeof(int32_t));
+    o.small = at;   at += kAlign;        // best (16 B), path length, status, cp of the base, move
+    o.total = at;
+    return CP_OK;
+}
+
+int copy_back(void *host, const void *dev, size_t bytes, hipStream_t st) {
+    if (hipMemcpyAsync(host, dev, bytes, hipMemcpyDeviceToHost, st) != hipSuccess) return CP_ERR_HIP;
+    return hipStreamSynchronize(st) == hipSuccess ? CP_OK : CP_ERR_HIP;
+}
+
+}  // namespace
+
+}  // namespace cpeval
+
+using namespace cpeval;
+
+extern "C" {
+
+int cp_search_workspace_bytes(const cp_graph *g, int32_t k, int32_t chunk, size_t *out_bytes) {
+    if (!g || !out_bytes) return CP_ERR_NULL;
+    if (k < 1 || k > 255 || chunk < 1) return CP_ERR_SIZE;
+    SearchLayout lay;
+    int rc = search_layout(g, k, chunk, nullptr, nullptr, lay);
+    if (rc) return rc;
+    *out_bytes = lay.total;
+    return CP_OK;
+}
+
+int cp_search(const cp_graph *g, int32_t k, const int64_t *speeds, const int64_t *bandwidth,
+              uint8_t *assignment, int64_t num_pairs, const int32_t *pairs, int64_t num_pins,
+              const int32_t *pins, int32_t max_moves, int32_t chunk, void *workspace, size_t workspace_bytes,
+              void *stream, int64_t *cp_trace, int32_t *moves, int32_t *num_moves, int64_t *evaluated) {
+    if (!g || !speeds || !bandwidth || !assignment || !workspace || !cp_trace || !num_moves) return CP_ERR_NULL;
+    if (k < 1 || k > 255 || chunk < 1 || max_moves < 0 || num_pairs < 0 || num_pins < 0) return CP_ERR_SIZE;
+    if ((num_pairs > 0 && !pairs) || (num_pins > 0 && !pins)) return CP_ERR_NULL;
+    SearchLayout lay;
+    int rc = search_layout(g, k, chunk, speeds, bandwidth, lay);
+    if (rc) return rc;
+    if (((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < lay.total) return CP_ERR_WORKSPACE;
+    cp_graph_info info;
+    rc = cp_graph_get_info(g, &info);
+    if (rc) return rc;
+    if (!info.uploaded) return CP_ERR_STATE;
+    const int32_t n = info.n, L = info.L;
+    hipStream_t st = (hipStream_t)stream;
+    uint8_t *ws = (uint8_t *)workspace;
+    uint8_t *d_cand = ws + lay.cand;
+    void *d_b = ws + lay.b;
+    int64_t *d_cp = (int64_t *)(ws + lay.cp);
+    uint8_t *d_valid = ws + lay.valid;
+    int32_t *d_path = (int32_t *)(ws + lay.path);
+    Best *d_best = (Best *)(ws + lay.small);
+    int32_t *d_len = (int32_t *)(ws + lay.small + 16);
+    int32_t *d_status = (int32_t *)(ws + lay.small + 24);
+    int64_t *d_cp_base = (int64_t *)(ws + lay.small + 32);
+    int32_t *d_move = (int32_t *)(ws + lay.small + 40);
+    const bool constrained = num_pairs > 0 || num_pins > 0;
+    const bool vector_ok = n % 16 == 0 && ((uintptr_t)assignment % 16) == 0;     // candidate rows start at j * n
+    int32_t done = 0;
+    int64_t seen = 0;
+    *num_moves = 0;
+    for (;;) {
+        // the current partition: CP, b, one critical path
+        rc = cp_eval(g, 1, k, assignment, CP_ASSIGN_PARTITION_MAJOR, speeds, bandwidth, ws + lay.eval_ws,
+                     lay.eval_bytes, stream, d_cp_base, d_b, nullptr, nullptr, lay.tick, CP_OUT_VERTEX_MAJOR,
+                     CP_PLAN_AUTO, d_status, nullptr);
+        if (rc) return rc;
+        rc = cp_critical_path(g, 1, k, assignment, CP_ASSIGN_PARTITION_MAJOR, speeds, bandwidth, d_b, d_cp_base,
+                              lay.tick, CP_OUT_VERTEX_MAJOR, ws + lay.eval_ws, lay.eval_bytes, stream, L, d_path,
+                              d_len, d_status + 1);
+        if (rc) return rc;
+        struct { int32_t len; int32_t pad; int32_t status[2]; int64_t cp; } head;
+        rc = copy_back(&head, d_len, sizeof(head), st);
+        if (rc) return rc;
+        if (head.status[0] != CP_STATUS_OK || head.status[1] != CP_STATUS_OK) return CP_ERR_ARG;   // bad device id
+        cp_trace[done] = head.cp;
+        if (done >= max_moves || k < 2) break;
+        const int64_t total = (int64_t)head.len * (k - 1);
+        hipLaunchKernelGGL(best_reset_kernel, dim3(1), dim3(1), 0, st, d_best);
+        for (int64_t first = 0; first < total; first += chunk) {
+            const int32_t count = (int32_t)std::min<int64_t>(chunk, total - first);
+            const dim3 grid((unsigned)(((int64_t)n + 16 * 256 - 1) / (16 * 256)), (unsigned)std::min(count, 65535));
+            hipLaunchKernelGGL(neighbours_kernel, grid, dim3(256), 0, st, (const uint8_t *)assignment,
+                               (const int32_t *)d_path, n, k, (int32_t)first, count, d_cand, vector_ok ? 1 : 0);
+            if (hipGetLastError() != hipSuccess) return CP_ERR_HIP;
+            int plan = CP_PLAN_AUTO;
+            rc = cp_eval_choose_plan(g, count, k, speeds, bandwidth, lay.tick, &plan);
+            if (rc) return rc;
+            // a short last chunk may resolve to the other plan: it needs b only if room was made for it
+            void *b_arg = nullptr;
+            if (plan != CP_PLAN_RESIDENT_WINDOW) {
+                if (lay.plan_chunk == CP_PLAN_RESIDENT_WINDOW && count > 1) plan = CP_PLAN_RESIDENT_WINDOW;
+                else b_arg = d_b;
+            }
+            rc = cp_eval(g, count, k, d_cand, CP_ASSIGN_PARTITION_MAJOR, speeds, bandwidth, ws + lay.eval_ws,
+                         lay.eval_bytes, stream, d_cp, b_arg, nullptr, nullptr, lay.tick, CP_OUT_VERTEX_MAJOR, plan,
+                         d_status, nullptr);
+            if (rc) return rc;
+            if (constrained) {
+                rc = cp_validate(n, count, k, d_cand, CP_ASSIGN_PARTITION_MAJOR, num_pairs, pairs, num_pins, pins,
+                                 stream, d_valid, nullptr, d_status + 1);
+                if (rc) return rc;
+            }
+            hipLaunchKernelGGL(argmin_merge_kernel, dim3(1), dim3(1024), 0, st, (const int64_t *)d_cp,
+                               constrained ? (const uint8_t *)d_valid : nullptr, count, (int32_t)first, d_best);
+            if (hipGetLastError() != hipSuccess) return CP_ERR_HIP;
+            seen += count;
+        }
+        Best best;
+        rc = copy_back(&best, d_best, sizeof(best), st);
+        if (rc) return rc;
+        if (best.index < 0 || best.value >= head.cp) break;
+        hipLaunchKernelGGL(apply_move_kernel, dim3(1), dim3(1), 0, st, assignment, (const int32_t *)d_path, k,
+                           (const Best *)d_best, d_move);
+        if (hipGetLastError() != hipSuccess) return CP_ERR_HIP;
+        if (moves) {
+            rc = copy_back(moves + 2 * done, d_move, 2 * sizeof(int32_t), st);
+            if (rc) return rc;
+        }
+        ++done;
+    }
+    *num_moves = done;
+    if (evaluated) *evaluated = seen;
+    return hipStreamSynchronize(st) == hipSuccess ? CP_OK : CP_ERR_HIP;
+}
+
+}  // extern "C"

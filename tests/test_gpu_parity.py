@@ -479,3 +479,39 @@ def test_validate_reports_an_index_out_of_range(gpu):
         gpu.cp_validate(a, 2, torch.tensor([[0, 10]], dtype=torch.int32, device="cuda:0"))
     with pytest.raises(ValueError):
         gpu.cp_validate(a, 2, None, torch.tensor([[0, 2]], dtype=torch.int32, device="cuda:0"))
+
+
+# ------------------------------------------------------------------ critical-path move search
+
+def _check_search(gpu, oracle, w, start, pairs=(), pins=(), max_moves=1000, chunk=256):
+    import torch
+    g = gpu.CpGraph.from_workload(w, device="cuda:0")
+    ref_a, ref_trace, ref_moves = oracle.search(w.n, w.succ_ptr, w.succ_idx, w.succ_t, w.c, w.speeds, w.bandwidth,
+                                                start, max_len=w.L, pairs=pairs, pins=pins, max_moves=max_moves,
+                                                threads=8)
+    to_dev = lambda x: torch.from_numpy(np.asarray(x, dtype=np.int32).reshape(-1, 2)).to("cuda:0") if len(x) else None
+    got = gpu.cp_search(g, torch.from_numpy(np.ascontiguousarray(start)).to("cuda:0"), w.speeds, w.bandwidth,
+                        pairs=to_dev(pairs), pins=to_dev(pins), max_moves=max_moves, chunk=chunk)
+    assert got["cp_trace"].tolist() == ref_trace.tolist()
+    assert got["moves"].tolist() == ref_moves.tolist()
+    assert np.array_equal(got["assignment"].cpu().numpy(), ref_a)
+    g.close()
+    return got
+
+
+def test_search_tiny_and_mlp(gpu, oracle):
+    w = make_workload("tiny")
+    got = _check_search(gpu, oracle, w, w.assignments[0])
+    assert len(got["moves"]) >= 2
+    _check_search(gpu, oracle, w, w.assignments[1], chunk=3)              # many ragged chunks
+    v0 = int(got["moves"][0][0])
+    _check_search(gpu, oracle, w, w.assignments[0], pins=[[v0, int(w.assignments[0][v0])]], pairs=[[0, 1]])
+    _check_search(gpu, oracle, w, w.assignments[0], max_moves=1)
+    w = make_workload("mlp", P=2)                                          # n = 2016: rows are 16-byte multiples
+    _check_search(gpu, oracle, w, w.assignments[0], max_moves=6, chunk=200)
+
+
+def test_search_under_the_wave_column_plan(gpu, oracle):
+    # hub rows rule the window plan out: candidates are evaluated with b kept
+    w = make_workload("comm_heavy", P=2, levels=5, width=300, hub_degree=280)
+    _check_search(gpu, oracle, w, w.assignments[0], max_moves=3, chunk=16)
