@@ -29,11 +29,11 @@ HBM_PEAK_GBS = 8000.0  # MI355X, published
 # copy: x2.00 and x1.00).  The figure belongs to one build of the kernel: it is reported only
 # while the sources it was taken on are unchanged, and for the configuration it was taken on.
 MEASURED_TRAFFIC = {
-    "sources_sha256": "b50aa911d77d26bb95120a0cf894d4ea963622fa9f597ed284c07ffce99609f0",
+    "sources_sha256": "8064dc7e11c704a6a1045d544d2d405cf250cc8fc27b4d83e67bb0b2e7dca75f",
     "workload": "large_sparse", "P": 256, "plan": 2, "out_layout": 1,
     "bytes_per_blevel_launch": (2 * 227701 + 1000002) * 1024,
 }
-TRAFFIC_SOURCES = ("kernels.hip", "graph.cpp", "cpeval_internal.hpp", "launch.hpp")
+TRAFFIC_SOURCES = ("kernels.hip", "graph.cpp", "cpeval_internal.hpp")     # the sweep kernels and the packet layout
 
 
 def measured_traffic(workload, P, plan, out_layout):
