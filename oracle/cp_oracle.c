@@ -455,3 +455,57 @@ done:
     free(path); free(cand); free(cp); free(valid);
     return rc;
 }
+
+/*
+ * The paper's Critical Path partitioning strategy (section 3.2.2), as a start
+ * partition for the search:
+ *   1. the critical path is computed from the ranks, which know no devices: vertex cost
+ *      c(v), no transfer cost (the rank equations of section 3.2 add c only);
+ *   2. it goes to the fastest device (largest s, lowest number on ties) as a whole
+ *      (memory capacities are not modelled, so it always fits);
+ *   3. every other vertex, in increasing vertex number, goes to the device d with the
+ *      smallest  load(d) + w(v, d)  (lowest number on ties), where load(d) is the sum of the
+ *      execution times w(u, d) = ceil(c(u) / s[d]) of the vertices already on d, the
+ *      critical path included (the strategy's load equation, in integer ticks).
+ * assign_out is [n].  Returns 0 or a negative error of the functions it calls.
+ */
+int cp_oracle_seed(int32_t n, const int32_t *succ_ptr, const int32_t *succ_idx, const int64_t *c,
+                   int k, const int64_t *speeds, int32_t max_len, uint8_t *assign_out)
+{
+    int64_t m = n ? succ_ptr[n] : 0;
+    int64_t *zero_t = (int64_t *)calloc((size_t)m + 1, sizeof(int64_t));
+    uint8_t *one_dev = (uint8_t *)calloc((size_t)n + 1, 1);
+    int32_t *path = (int32_t *)malloc(((size_t)max_len + 1) * sizeof(int32_t));
+    uint8_t *on_path = (uint8_t *)calloc((size_t)n + 1, 1);
+    int64_t *load = (int64_t *)calloc((size_t)k + 1, sizeof(int64_t));
+    int rc = -2;
+    if (zero_t && one_dev && path && on_path && load) {
+        const int64_t unit = 1;
+        int32_t len = 0;
+        rc = cp_oracle_critical_path(n, succ_ptr, succ_idx, zero_t, c, 1, &unit, &unit, 1, one_dev, max_len,
+                                     path, &len);
+        if (rc == 0) {
+            int fastest = 0;
+            for (int d = 1; d < k; ++d)
+                if (speeds[d] > speeds[fastest]) fastest = d;
+            for (int32_t i = 0; i < len; ++i) {
+                on_path[path[i]] = 1;
+                assign_out[path[i]] = (uint8_t)fastest;
+                load[fastest] += cp_oracle_vertex_cost(c[path[i]], speeds[fastest]);
+            }
+            for (int32_t v = 0; v < n; ++v) {
+                if (on_path[v]) continue;
+                int best = 0;
+                int64_t best_val = load[0] + cp_oracle_vertex_cost(c[v], speeds[0]);
+                for (int d = 1; d < k; ++d) {
+                    int64_t val = load[d] + cp_oracle_vertex_cost(c[v], speeds[d]);
+                    if (val < best_val) { best = d; best_val = val; }
+                }
+                assign_out[v] = (uint8_t)best;
+                load[best] = best_val;
+            }
+        }
+    }
+    free(zero_t); free(one_dev); free(path); free(on_path); free(load);
+    return rc;
+}

@@ -47,6 +47,8 @@ def _load():
         lib.cp_oracle_search.restype = C.c_int
         lib.cp_oracle_search.argtypes = [C.c_int32, i32p, i32p, i64p, i64p, C.c_int, i64p, i64p, u8p, C.c_int64,
                                          i32p, C.c_int64, i32p, C.c_int32, C.c_int32, i64p, i32p, C.c_int]
+        lib.cp_oracle_seed.restype = C.c_int
+        lib.cp_oracle_seed.argtypes = [C.c_int32, i32p, i32p, i64p, C.c_int, i64p, C.c_int32, u8p]
         _lib = lib
     return _lib
 
@@ -281,3 +283,20 @@ def search(n, succ_ptr, succ_idx, succ_t, c, speeds, bandwidth, start, max_len, 
     if rc < 0:
         raise ValueError(f"search failed with code {rc}")
     return a, trace[:rc + 1].copy(), moves[:rc].copy()
+
+
+def seed(n, succ_ptr, succ_idx, c, speeds, max_len):
+    """The paper's Critical Path partitioning strategy (section 3.2.2): uint8 [n]."""
+    lib = _load()
+    sp = np.ascontiguousarray(succ_ptr, dtype=np.int32)
+    si = np.ascontiguousarray(succ_idx, dtype=np.int32)
+    if si.size == 0:
+        si = np.zeros(1, dtype=np.int32)
+    cc = np.ascontiguousarray(c, dtype=np.int64)
+    s = np.ascontiguousarray(speeds, dtype=np.int64)
+    out = np.zeros(n, dtype=np.uint8)
+    rc = lib.cp_oracle_seed(n, _ptr(sp, C.c_int32), _ptr(si, C.c_int32), _ptr(cc, C.c_int64), int(s.shape[0]),
+                            _ptr(s, C.c_int64), int(max_len), _ptr(out, C.c_uint8))
+    if rc:
+        raise ValueError(f"seed failed with code {rc}")
+    return out

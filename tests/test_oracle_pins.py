@@ -732,3 +732,55 @@ def test_search_respects_constraints_and_the_move_limit(oracle):
                                               start, max_len=w.L, max_moves=1)
     assert len(moves_one) == 1 and trace_one.tolist() == trace_free[:2].tolist()
     assert np.array_equal(moves_one[0], moves_free[0])
+
+
+# ------------------------------------------------------------------ Critical Path partitioning strategy (section 3.2.2)
+
+def test_seed_hand_example(oracle):
+    # 0 -> 1 -> 3 and 0 -> 2 -> 3 with c = 4, 9, 2, 4: the critical path is 0, 1, 3 (4 + 9 + 4);
+    # vertex 4 is isolated with c = 6.  Devices: speeds 2, 4, 4 -> fastest is device 1.
+    csr = build_csr(5, [0, 0, 1, 2], [1, 2, 3, 3], [7, 7, 7, 7])
+    got = oracle.seed(5, csr["succ_ptr"], csr["succ_idx"], [4, 9, 2, 4, 6], [2, 4, 4], max_len=3)
+    # path on device 1: load = ceil(4/4) + ceil(9/4) + ceil(4/4) = 1 + 3 + 1 = 5
+    # vertex 2: device 0: 0 + ceil(2/2) = 1; device 1: 5 + 1 = 6; device 2: 0 + 1 = 1 -> device 0 (lowest number)
+    # vertex 4: device 0: 1 + ceil(6/2) = 4; device 1: 5 + 2 = 7; device 2: 0 + 2 = 2 -> device 2
+    assert got.tolist() == [1, 1, 0, 1, 2]
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_seed_step_by_step(oracle, seed):
+    """The critical path (device-free ranks: the one-device critical path) sits on the fastest
+    device; replaying the remaining vertices in order, the chosen device is a cheapest one
+    for the loads at that moment, and no lower-numbered device is as cheap."""
+    rng = np.random.default_rng(800 + seed)
+    n, level, src, dst = random_layered_dag(rng, [5] * 8, 1, 3, 2)
+    c = rng.integers(1, 40, size=n)
+    csr = build_csr(n, src, dst, rng.integers(1, 9, size=len(src)), level)
+    speeds = np.array([3, 7, 2, 7])
+    got = oracle.seed(n, csr["succ_ptr"], csr["succ_idx"], c, speeds, max_len=csr["L"])
+    paths, lens = oracle.critical_path(n, csr["succ_ptr"], csr["succ_idx"], np.zeros(len(src), dtype=np.int64), c,
+                                       np.array([1]), np.array([[1]]), np.zeros((1, n), dtype=np.uint8), csr["L"])
+    path = paths[0, :lens[0]]
+    up, down, total = oracle.ranks(n, csr["succ_ptr"], csr["succ_idx"], c)
+    assert sum(int(c[v]) for v in path) == up.max()            # it is a longest path of the rank equations
+    assert (got[path] == 1).all()                               # device 1: first of the two fastest
+    load = [0] * 4
+    load[1] = sum(-(-int(c[v]) // 7) for v in path)
+    on_path = set(int(v) for v in path)
+    for v in range(n):
+        if v in on_path:
+            continue
+        cost = [load[d] + -(-int(c[v]) // int(speeds[d])) for d in range(4)]
+        d = int(got[v])
+        assert cost[d] == min(cost) and all(cost[e] > cost[d] for e in range(d))
+        load[d] = cost[d]
+
+
+def test_seed_degenerate_cases(oracle):
+    # one device: everything on it; no edges: the "path" is the costliest vertex alone
+    csr = build_csr(4, [], [], [])
+    assert oracle.seed(4, csr["succ_ptr"], csr["succ_idx"], [3, 9, 9, 1], [5], max_len=1).tolist() == [0, 0, 0, 0]
+    got = oracle.seed(4, csr["succ_ptr"], csr["succ_idx"], [3, 9, 9, 1], [1, 1], max_len=1)
+    # path = vertex 1 (lowest number among the costliest) on device 0 (lowest number among the fastest): load 9
+    # vertex 0 -> device 1 (3 < 12); vertex 2 -> device 1 (3 + 9 = 12 < 18); vertex 3 -> device 0 (10 < 13)
+    assert got.tolist() == [1, 0, 1, 0]
