@@ -271,6 +271,28 @@ int cp_validate(int32_t n, int32_t batch, int32_t k, const uint8_t *assignments,
                 void *stream, uint8_t *valid_out, int32_t *violations_out, int32_t *status_out);
 
 /*
+ * The paper's Critical Path partitioning strategy (section 3.2.2), e.g. as the start of
+ * cp_search: the critical path of the ranks (vertex cost c, no devices, no transfers;
+ * section 3.2's rank equations) goes to the fastest device (largest s, lowest number on
+ * ties); every other vertex, in increasing vertex number, goes to the device d with the
+ * smallest load(d) + ceil(c(v) / s[d]) (lowest number on ties), load(d) being the summed
+ * execution times of the vertices already on d, the path included (the strategy's load
+ * equation in integer ticks).  Memory capacities are not modelled.  The load rule is a
+ * chain of n dependent choices: it runs on one wavefront, about 0.1 us per vertex.
+ * Only enqueues work on `stream`.
+ *
+ *   k <= 64, speeds host int64 [k]
+ *   workspace       device, 256-byte aligned, >= cp_seed_workspace_bytes
+ *   assignment_out  device uint8 [n]
+ *   status_out      device int32 (CP_STATUS_OK unless the inner evaluation reports otherwise)
+ * Errors: CP_ERR_NULL, CP_ERR_SIZE (k < 1 or k > 64), CP_ERR_STATE, CP_ERR_WORKSPACE,
+ * CP_ERR_SPEED, CP_ERR_HIP.
+ */
+int cp_seed_workspace_bytes(const cp_graph *g, size_t *out_bytes);
+int cp_seed_partition(const cp_graph *g, int32_t k, const int64_t *speeds, void *workspace, size_t workspace_bytes,
+                      void *stream, uint8_t *assignment_out, int32_t *status_out);
+
+/*
  * Critical-path move search: a descent over partitions built from the paper's own
  * pieces.  Section 3.2 places the critical path first because it decides the running
  * time; here, from a start partition, every single move of a vertex of the current

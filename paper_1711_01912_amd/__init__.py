@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     cp_pct_order,
     cp_ranks,
     cp_search,
+    cp_seed_partition,
     cp_validate,
     cp_eval,
     error_string,

@@ -28,7 +28,7 @@ EXPORTS = (
     "cp_graph_create", "cp_graph_get_info", "cp_graph_upload", "cp_graph_destroy",
     "cp_eval_workspace_bytes", "cp_eval_choose_plan", "cp_eval", "cp_critical_path", "cp_ranks_workspace_bytes", "cp_ranks",
     "cp_pct_order_workspace_bytes", "cp_pct_order", "cp_validate",
-    "cp_search_workspace_bytes", "cp_search",
+    "cp_search_workspace_bytes", "cp_search", "cp_seed_workspace_bytes", "cp_seed_partition",
     "cp_profile_create", "cp_profile_reset",
     "cp_profile_count", "cp_profile_read", "cp_profile_destroy", "cp_cost_magic",
     "cp_error_string",
@@ -99,6 +99,10 @@ def load_library():
     lib.cp_validate.restype = C.c_int
     lib.cp_validate.argtypes = [C.c_int32, C.c_int32, C.c_int32, vp, C.c_int, C.c_int64, vp, C.c_int64, vp, vp,
                                 vp, vp, vp]
+    lib.cp_seed_workspace_bytes.restype = C.c_int
+    lib.cp_seed_workspace_bytes.argtypes = [vp, C.POINTER(C.c_size_t)]
+    lib.cp_seed_partition.restype = C.c_int
+    lib.cp_seed_partition.argtypes = [vp, C.c_int32, i64p, vp, C.c_size_t, vp, vp, vp]
     lib.cp_search_workspace_bytes.restype = C.c_int
     lib.cp_search_workspace_bytes.argtypes = [vp, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
     lib.cp_search.restype = C.c_int
@@ -473,6 +477,28 @@ def cp_validate(assignments, k: int, pairs=None, pins=None, *, assign_layout=ASS
         if int(status.item()) & STATUS_BAD_CONSTRAINT:
             raise ValueError("a constraint names a vertex >= n or a device >= k")
     return valid, broken
+
+
+def cp_seed_partition(graph: CpGraph, speeds, *, stream=None):
+    """cp_seed_partition on the graph's device: the paper's Critical Path strategy, uint8 [n]."""
+    import torch
+    lib = load_library()
+    dev = graph.blob.device
+    s = np.ascontiguousarray(speeds, dtype=np.int64)
+    need = C.c_size_t(0)
+    rc = lib.cp_seed_workspace_bytes(graph._handle, C.byref(need))
+    if rc:
+        raise CpError(rc, "cp_seed_workspace_bytes")
+    ws = torch.empty(need.value, dtype=torch.uint8, device=dev)
+    out = torch.empty(graph.info["n"], dtype=torch.uint8, device=dev)
+    status = torch.empty(1, dtype=torch.int32, device=dev)
+    rc = lib.cp_seed_partition(graph._handle, int(s.shape[0]), _np_ptr(s, C.c_int64), C.c_void_p(ws.data_ptr()),
+                               C.c_size_t(ws.numel()), _stream_ptr(stream), C.c_void_p(out.data_ptr()),
+                               C.c_void_p(status.data_ptr()))
+    if rc:
+        raise CpError(rc, "cp_seed_partition")
+    torch.cuda.synchronize(dev)          # the workspace is released on return
+    return out
 
 
 def cp_search(graph: CpGraph, start, speeds, bandwidth, *, pairs=None, pins=None, max_moves=1000, chunk=256,

@@ -10,6 +10,8 @@
 #include <algorithm>
 #include <climits>
 #include <cstdint>
+#include <new>
+#include <vector>
 
 #include "cpeval_internal.hpp"
 #include "launch.hpp"
@@ -98,6 +100,79 @@ __global__ void apply_move_kernel(uint8_t *base, const int32_t *path, int32_t k,
     base[v] = (uint8_t)d;
     move[0] = v;
     move[1] = d;
+}
+
+// ---------------------------------------------------------------- Critical Path strategy (section 3.2.2)
+
+constexpr int kSeedMaxK = 64;        // one lane per device
+
+struct SeedArgs {
+    const void *c;            // uint32 or int64 [n]
+    const int32_t *path;      // device-free critical path
+    const int32_t *len;
+    uint8_t *assign;          // [n]
+    int32_t n, k, fastest, magic;
+    Magic mg[kSeedMaxK];
+    int64_t speed[kSeedMaxK];
+};
+
+__global__ void seed_mark_kernel(SeedArgs a) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < a.n) a.assign[i] = 0xff;          // not placed yet
+}
+
+__global__ void seed_path_kernel(SeedArgs a) {
+    const int32_t len = *a.len;
+    for (int32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < len; i += gridDim.x * blockDim.x)
+        a.assign[a.path[i]] = (uint8_t)a.fastest;
+}
+
+// The load rule is a chain: every choice changes the loads the next one sees.  One
+// wavefront walks the vertices in order, lane d keeps load(d); 64 vertices are fetched
+// at a time and handed round with readlane.
+template <typename WT>
+__global__ __launch_bounds__(64) void seed_greedy_kernel(SeedArgs a) {
+    const int lane = threadIdx.x;
+    const WT *c = (const WT *)a.c;
+    const bool mine = lane < a.k;
+    const Magic mg = a.mg[mine ? lane : 0];
+    const uint64_t sp = (uint64_t)a.speed[mine ? lane : 0];
+    auto cost = [&](uint64_t cv) -> long long {
+        return a.magic ? (long long)(uint32_t)((((uint64_t)((uint32_t)cv + mg.dm1)) * mg.mul + ((uint32_t)cv + mg.dm1)) >> 32)
+                       : (long long)((cv + sp - 1) / sp);
+    };
+    // the critical path is placed first: its execution times on the fastest device
+    long long load = 0;
+    {
+        const Magic mf = a.mg[a.fastest];
+        const uint64_t sf = (uint64_t)a.speed[a.fastest];
+        const int32_t len = *a.len;
+        long long part = 0;
+        for (int32_t i = lane; i < len; i += 64) {
+            const uint64_t cv = (uint64_t)c[a.path[i]];
+            part += a.magic ? (long long)(uint32_t)((((uint64_t)((uint32_t)cv + mf.dm1)) * mf.mul + ((uint32_t)cv + mf.dm1)) >> 32)
+                            : (long long)((cv + sf - 1) / sf);
+        }
+        for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
+        if (lane == a.fastest) load = part;
+    }
+    for (int32_t v0 = 0; v0 < a.n; v0 += 64) {
+        const int32_t v = v0 + lane;
+        const uint64_t cv = v < a.n ? (uint64_t)c[v] : 0;
+        int32_t dev = v < a.n ? (int32_t)a.assign[v] : 0;
+        const int32_t cnt = min(64, a.n - v0);
+        for (int j = 0; j < cnt; ++j) {
+            if (__shfl(dev, j) != 0xff) continue;            // on the critical path
+            const uint64_t cj = __shfl(cv, j);
+            const long long val = mine ? load + cost(cj) : LLONG_MAX;
+            long long best = val;
+            for (int off = 32; off > 0; off >>= 1) best = min(best, __shfl_xor(best, off));
+            const int chosen = __ffsll((long long)__ballot(val == best)) - 1;      // lowest device on ties
+            if (lane == chosen) load = val;
+            if (lane == j) dev = chosen;
+        }
+        if (v < a.n) a.assign[v] = (uint8_t)dev;
+    }
 }
 
 struct SearchLayout {
@@ -260,6 +335,87 @@ int cp_search(const cp_graph *g, int32_t k, const int64_t *speeds, const int64_t
     *num_moves = done;
     if (evaluated) *evaluated = seen;
     return hipStreamSynchronize(st) == hipSuccess ? CP_OK : CP_ERR_HIP;
+}
+
+int cp_seed_workspace_bytes(const cp_graph *g, size_t *out_bytes) {
+    if (!g || !out_bytes) return CP_ERR_NULL;
+    cp_graph_info info;
+    int rc = cp_graph_get_info(g, &info);
+    if (rc) return rc;
+    size_t eval = 0;
+    rc = cp_eval_workspace_bytes(g, 1, 1, CP_ASSIGN_PARTITION_MAJOR, CP_PLAN_AUTO, CP_OUT_VERTEX_MAJOR,
+                                 info.min_tick_bytes, &eval);
+    if (rc) return rc;
+    *out_bytes = align_up(eval) + align_up((size_t)info.n) + align_up((size_t)info.n * (size_t)info.min_tick_bytes) +
+                 align_up((size_t)info.L * sizeof(int32_t)) + kAlign;
+    return CP_OK;
+}
+
+int cp_seed_partition(const cp_graph *g, int32_t k, const int64_t *speeds, void *workspace, size_t workspace_bytes,
+                      void *stream, uint8_t *assignment_out, int32_t *status_out) {
+    if (!g || !speeds || !workspace || !assignment_out || !status_out) return CP_ERR_NULL;
+    if (k < 1 || k > kSeedMaxK) return CP_ERR_SIZE;
+    size_t need = 0;
+    int rc = cp_seed_workspace_bytes(g, &need);
+    if (rc) return rc;
+    if (((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < need) return CP_ERR_WORKSPACE;
+    cp_graph_info info;
+    rc = cp_graph_get_info(g, &info);
+    if (rc) return rc;
+    if (!info.uploaded) return CP_ERR_STATE;
+    const Packed &p = g->packed;
+    std::vector<int64_t> ones((size_t)k * k, 1);
+    CostTables tabs;
+    try {
+        rc = build_cost_tables(k, speeds, ones.data(), p.narrow, p.info.max_c, p.info.max_t, tabs);
+    } catch (const std::bad_alloc &) {
+        rc = CP_ERR_ALLOC;
+    }
+    if (rc) return rc;
+    size_t eval = 0;
+    rc = cp_eval_workspace_bytes(g, 1, 1, CP_ASSIGN_PARTITION_MAJOR, CP_PLAN_AUTO, CP_OUT_VERTEX_MAJOR,
+                                 info.min_tick_bytes, &eval);
+    if (rc) return rc;
+    const size_t n = (size_t)info.n;
+    const int T = info.min_tick_bytes;
+    uint8_t *ws = (uint8_t *)workspace;
+    uint8_t *d_one = ws + align_up(eval);
+    void *d_b = d_one + align_up(n);
+    int32_t *d_path = (int32_t *)((uint8_t *)d_b + align_up(n * (size_t)T));
+    uint8_t *d_small = (uint8_t *)d_path + align_up((size_t)info.L * sizeof(int32_t));
+    int64_t *d_cp = (int64_t *)d_small;
+    int32_t *d_len = (int32_t *)(d_small + 8);
+    hipStream_t st = (hipStream_t)stream;
+    // the ranks know no devices: one device of speed 1, nothing is transferred
+    rc = launch_zero_bytes(d_one, (int64_t)n, stream);
+    if (rc) return rc;
+    const int64_t unit = 1;
+    rc = cp_eval(g, 1, 1, d_one, CP_ASSIGN_PARTITION_MAJOR, &unit, &unit, ws, align_up(eval), stream, d_cp, d_b,
+                 nullptr, nullptr, T, CP_OUT_VERTEX_MAJOR, CP_PLAN_AUTO, status_out, nullptr);
+    if (rc) return rc;
+    rc = cp_critical_path(g, 1, 1, d_one, CP_ASSIGN_PARTITION_MAJOR, &unit, &unit, d_b, d_cp, T,
+                          CP_OUT_VERTEX_MAJOR, ws, align_up(eval), stream, info.L, d_path, d_len, status_out);
+    if (rc) return rc;
+    SeedArgs a{};
+    a.c = (const uint8_t *)g->device_blob + p.c_off;
+    a.path = d_path;
+    a.len = d_len;
+    a.assign = assignment_out;
+    a.n = info.n;
+    a.k = k;
+    a.fastest = 0;
+    for (int d = 1; d < k; ++d)
+        if (speeds[d] > speeds[a.fastest]) a.fastest = d;
+    a.magic = tabs.magic_ok ? 1 : 0;
+    for (int d = 0; d < k; ++d) {
+        a.mg[d] = tabs.magic[2 * (size_t)k * k + d];
+        a.speed[d] = speeds[d];
+    }
+    hipLaunchKernelGGL(seed_mark_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(seed_path_kernel, dim3(64), dim3(256), 0, st, a);
+    if (p.narrow) hipLaunchKernelGGL(seed_greedy_kernel<uint32_t>, dim3(1), dim3(64), 0, st, a);
+    else hipLaunchKernelGGL(seed_greedy_kernel<int64_t>, dim3(1), dim3(64), 0, st, a);
+    return hipGetLastError() == hipSuccess ? CP_OK : CP_ERR_HIP;
 }
 
 }  // extern "C"

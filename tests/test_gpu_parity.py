@@ -515,3 +515,49 @@ def test_search_under_the_wave_column_plan(gpu, oracle):
     # hub rows rule the window plan out: candidates are evaluated with b kept
     w = make_workload("comm_heavy", P=2, levels=5, width=300, hub_degree=280)
     _check_search(gpu, oracle, w, w.assignments[0], max_moves=3, chunk=16)
+
+
+# ------------------------------------------------------------------ Critical Path partitioning strategy (section 3.2.2)
+
+@pytest.mark.parametrize("name,kw", [("tiny", {}), ("mlp", {}), ("inception", {}), ("large_sparse", {"levels": 300}),
+                                     ("comm_heavy", {"levels": 6, "width": 900, "hub_degree": 300})])
+def test_seed_partition(gpu, oracle, name, kw):
+    w = make_workload(name, P=1, **kw)
+    g = gpu.CpGraph.from_workload(w, device="cuda:0")
+    got = gpu.cp_seed_partition(g, w.speeds)
+    ref = oracle.seed(w.n, w.succ_ptr, w.succ_idx, w.c, w.speeds, max_len=w.L)
+    assert np.array_equal(got.cpu().numpy(), ref)
+    g.close()
+
+
+def test_seed_partition_wide_weights_and_many_devices(gpu, oracle):
+    rng = np.random.default_rng(61)
+    n, level, src, dst = random_layered_dag(rng, [33] * 7, 1, 3, 2)
+    c = rng.integers(1, 2**40, size=n)
+    w = _custom("wide-seed", n, src, dst, np.ones(len(src), dtype=np.int64), c, [1, 3, 2**33, 2**33, 5],
+                np.ones((5, 5), dtype=np.int64), np.zeros((1, n), dtype=np.uint8), level)
+    g = gpu.CpGraph.from_workload(w, device="cuda:0")
+    got = gpu.cp_seed_partition(g, w.speeds)
+    assert np.array_equal(got.cpu().numpy(), oracle.seed(w.n, w.succ_ptr, w.succ_idx, w.c, w.speeds, max_len=w.L))
+    g.close()
+    # 64 devices with many equal speeds: ties go to the lowest number
+    speeds = np.array([7] * 20 + [9] * 20 + [3] * 24)
+    w = make_workload("mlp", P=1)
+    g = gpu.CpGraph.from_workload(w, device="cuda:0")
+    got = gpu.cp_seed_partition(g, speeds)
+    assert np.array_equal(got.cpu().numpy(), oracle.seed(w.n, w.succ_ptr, w.succ_idx, w.c, speeds, max_len=w.L))
+    g.close()
+
+
+def test_seed_then_search(gpu, oracle):
+    """The strategy's partition as the start of the search, end to end against the oracle."""
+    w = make_workload("mlp", P=1)
+    g = gpu.CpGraph.from_workload(w, device="cuda:0")
+    start = gpu.cp_seed_partition(g, w.speeds)
+    got = gpu.cp_search(g, start, w.speeds, w.bandwidth, max_moves=8, chunk=128)
+    ref_start = oracle.seed(w.n, w.succ_ptr, w.succ_idx, w.c, w.speeds, max_len=w.L)
+    ref_a, ref_trace, ref_moves = oracle.search(w.n, w.succ_ptr, w.succ_idx, w.succ_t, w.c, w.speeds, w.bandwidth,
+                                                ref_start, max_len=w.L, max_moves=8, threads=8)
+    assert got["cp_trace"].tolist() == ref_trace.tolist() and got["moves"].tolist() == ref_moves.tolist()
+    assert np.array_equal(got["assignment"].cpu().numpy(), ref_a)
+    g.close()
