@@ -278,7 +278,7 @@ int cp_validate(int32_t n, int32_t batch, int32_t k, const uint8_t *assignments,
  * smallest load(d) + ceil(c(v) / s[d]) (lowest number on ties), load(d) being the summed
  * execution times of the vertices already on d, the path included (the strategy's load
  * equation in integer ticks).  Memory capacities are not modelled.  The load rule is a
- * chain of n dependent choices: it runs on one wavefront, about 0.1 us per vertex.
+ * chain of n dependent choices: it runs on one wavefront, a few tenths of a microsecond per vertex.
  * Only enqueues work on `stream`.
  *
  *   k <= 64, speeds host int64 [k]

@@ -156,17 +156,21 @@ __global__ __launch_bounds__(64) void seed_greedy_kernel(SeedArgs a) {
         for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
         if (lane == a.fastest) load = part;
     }
+    int span = 1;
+    while (span < a.k) span <<= 1;
     for (int32_t v0 = 0; v0 < a.n; v0 += 64) {
         const int32_t v = v0 + lane;
         const uint64_t cv = v < a.n ? (uint64_t)c[v] : 0;
         int32_t dev = v < a.n ? (int32_t)a.assign[v] : 0;
         const int32_t cnt = min(64, a.n - v0);
         for (int j = 0; j < cnt; ++j) {
-            if (__shfl(dev, j) != 0xff) continue;            // on the critical path
-            const uint64_t cj = __shfl(cv, j);
+            if (__builtin_amdgcn_readlane(dev, j) != 0xff) continue;            // on the critical path
+            const uint64_t cj = (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)cv, j) |
+                                (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(cv >> 32), j) << 32;
             const long long val = mine ? load + cost(cj) : LLONG_MAX;
+            // the devices sit in lanes 0 .. k-1: a butterfly over the next power of two covers them
             long long best = val;
-            for (int off = 32; off > 0; off >>= 1) best = min(best, __shfl_xor(best, off));
+            for (int off = span / 2; off > 0; off >>= 1) best = min(best, __shfl_xor(best, off));
             const int chosen = __ffsll((long long)__ballot(val == best)) - 1;      // lowest device on ties
             if (lane == chosen) load = val;
             if (lane == j) dev = chosen;
