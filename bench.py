@@ -68,7 +68,7 @@ def main():
     ap.add_argument("--out-layout", default="native", choices=("native", "vertex", "partition"),
                     help="layout of b, tl and the mask; native = the one the plan that runs produces directly "
                          "(partition-major for the resident-window plan, vertex-major for wave-column)")
-    ap.add_argument("--cpu-sample", type=int, default=32, help="partitions the oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=128, help="partitions the oracle is timed on (0 = skip)")
     ap.add_argument("--extras", action="store_true",
                     help="after the timed steps also time the consumers of the result (priority lists, one "
                          "critical path per partition) and report them under 'extras'")
