@@ -340,30 +340,62 @@ __global__ __launch_bounds__(64) void critical_path_kernel(PathArgs a) {
     }
     for (int off = 32; off > 0; off >>= 1) v = min(v, __shfl_xor(v, off));
 
+    // What the walk needs of the current vertex: its device, c, b and row bounds.  For the
+    // start they are loaded here; afterwards every lane fetches them for the successor it
+    // examines, together with that successor's b and device, and the winner's copy is
+    // broadcast: two dependent rounds of loads per path vertex instead of three.
+    uint32_t pv = 0;
+    WT cv = 0;
+    Tick bv = 0;
+    int32_t e0 = 0, e1 = 0;
+    if (v != 0x7fffffff) {
+        pv = row[(int64_t)v * a.a_stride_v];
+        cv = cw[v];
+        bv = b[(int64_t)v * bsv];
+        e0 = a.ptr[v];
+        e1 = a.ptr[v + 1];
+    }
+    bool bad_id = false;
     int32_t len = 0;
     while (v != 0x7fffffff && len < a.max_len) {
         if (lane == 0) path[len] = v;
         ++len;
-        uint32_t pv = row[(int64_t)v * a.a_stride_v];
-        if (pv >= (uint32_t)k) { *a.status = CP_STATUS_BAD_DEVICE_ID; pv = 0; }
-        const WT cv = cw[v];
+        if (pv >= (uint32_t)k) { bad_id = true; pv = 0; }
         const Tick wv = MAGIC ? (Tick)magic_div((uint32_t)cv, vtab_m[pv])
                               : (Tick)plain_div((uint64_t)cv, (uint64_t)vtab_g[pv]);
-        const Tick rest = b[(int64_t)v * bsv] - wv;
-        const int32_t e0 = a.ptr[v], e1 = a.ptr[v + 1];
-        int32_t next = 0x7fffffff;
+        const Tick rest = bv - wv;
+        int32_t next = 0x7fffffff;          // this lane's best successor and what it fetched for it
+        uint32_t n_p = 0;
+        WT n_c = 0;
+        Tick n_b = 0;
+        int32_t n_e0 = 0, n_e1 = 0;
         for (int32_t e = e0 + lane; e < e1; e += 64) {
             const int32_t u = a.idx[e];
-            uint32_t pu = row[(int64_t)u * a.a_stride_v];
-            pu = min(pu, (uint32_t)(k - 1));
             const WT te = wt[e];
+            const uint32_t pu_raw = row[(int64_t)u * a.a_stride_v];
+            const Tick bu = b[(int64_t)u * bsv];
+            const WT cu = cw[u];
+            const int32_t u0 = a.ptr[u], u1 = a.ptr[u + 1];
+            const uint32_t pu = min(pu_raw, (uint32_t)(k - 1));
             const Tick x = MAGIC ? (Tick)magic_div((uint32_t)te, etab_m[pv * k + pu])
                                  : (Tick)plain_div((uint64_t)te, (uint64_t)etab_g[pv * k + pu]);
-            if (x + b[(int64_t)u * bsv] == rest) next = min(next, u);
+            if (x + bu == rest && u < next) {
+                next = u; n_p = pu_raw; n_c = cu; n_b = bu; n_e0 = u0; n_e1 = u1;
+            }
         }
-        for (int off = 32; off > 0; off >>= 1) next = min(next, __shfl_xor(next, off));
-        v = next;
+        int32_t best = next;
+        for (int off = 32; off > 0; off >>= 1) best = min(best, __shfl_xor(best, off));
+        if (best != 0x7fffffff) {
+            const int from = __ffsll((long long)__ballot(next == best)) - 1;
+            pv = __shfl(n_p, from);
+            cv = (WT)__shfl(n_c, from);
+            bv = (Tick)__shfl(n_b, from);
+            e0 = __shfl(n_e0, from);
+            e1 = __shfl(n_e1, from);
+        }
+        v = best;
     }
+    if (bad_id) *a.status = CP_STATUS_BAD_DEVICE_ID;
     if (lane == 0) a.len[q] = len;
 }
 
