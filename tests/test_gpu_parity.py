@@ -561,3 +561,29 @@ def test_seed_then_search(gpu, oracle):
     assert got["cp_trace"].tolist() == ref_trace.tolist() and got["moves"].tolist() == ref_moves.tolist()
     assert np.array_equal(got["assignment"].cpu().numpy(), ref_a)
     g.close()
+
+
+# ------------------------------------------------------------------ mask written by the t sweep, and its fallbacks
+
+@pytest.mark.parametrize("width,P", [(7, 3), (8, 5), (8, 4), (25, 64), (16, 1)])
+def test_mask_rows_for_aligned_and_unaligned_sizes(gpu, oracle, width, P):
+    """Partition-major masks under the window plan: with n * P * 4 a multiple of 16 the t sweep
+    writes the bits itself, otherwise the separate pass does; n is not a multiple of 64 in
+    either case, so the last mask word of a row is partly used."""
+    rng = np.random.default_rng(71 + width)
+    n, level, src, dst = random_layered_dag(rng, [width] * 11, 1, 3, 2)
+    w = _custom("mask-rows", n, src, dst, rng.integers(0, 40, size=len(src)), rng.integers(1, 30, size=n), [1, 2, 3],
+                [[1, 2, 3], [2, 1, 2], [4, 3, 1]], rng.integers(0, 3, size=(P, n), dtype=np.uint8), level)
+    _check(gpu, oracle, w, plans=(WINDOW,), out_layouts=(1,))
+
+
+def test_mask_rows_when_ids_are_gathered(gpu, oracle):
+    """Vertices numbered against the level order: the ids of a level are spread over the whole
+    range, so they are gathered first and the t sweep does not write the mask."""
+    rng = np.random.default_rng(72)
+    n, level, src, dst = random_layered_dag(rng, [600] * 12, 1, 3, 2)
+    perm = rng.permutation(n)
+    w = _custom("scrambled", n, perm[src], perm[dst], rng.integers(1, 50, size=len(src)),
+                rng.integers(1, 30, size=n), [1, 2], [[1, 3], [2, 1]],
+                rng.integers(0, 2, size=(16, n), dtype=np.uint8), None)
+    _check(gpu, oracle, w, plans=(WINDOW, COLUMN), out_layouts=(0, 1))
