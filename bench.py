@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X, published
 # copy: x2.00 and x1.00).  The figure belongs to one build of the kernel: it is reported only
 # while the sources it was taken on are unchanged, and for the configuration it was taken on.
 MEASURED_TRAFFIC = {
-    "sources_sha256": "8064dc7e11c704a6a1045d544d2d405cf250cc8fc27b4d83e67bb0b2e7dca75f",
+    "sources_sha256": "a811464c6024c4f7b99eec467edb137f92cc9e86a3de08cc01e6c726c07cfbce",
     "workload": "large_sparse", "P": 256, "plan": 2, "out_layout": 1,
     "bytes_per_blevel_launch": (2 * 227701 + 1000002) * 1024,
 }
