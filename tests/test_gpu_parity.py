@@ -587,3 +587,28 @@ def test_mask_rows_when_ids_are_gathered(gpu, oracle):
                 rng.integers(1, 30, size=n), [1, 2], [[1, 3], [2, 1]],
                 rng.integers(0, 2, size=(16, n), dtype=np.uint8), None)
     _check(gpu, oracle, w, plans=(WINDOW, COLUMN), out_layouts=(0, 1))
+
+
+def test_search_degenerate_calls(gpu, oracle):
+    import torch
+    w = make_workload("tiny")
+    # no moves allowed: the trace is the start's CP alone; a chunk larger than the neighbourhood
+    _check_search(gpu, oracle, w, w.assignments[2], max_moves=0)
+    _check_search(gpu, oracle, w, w.assignments[2], chunk=100000)
+    # one device: nothing can move
+    w1 = _custom("one-device", w.n, np.repeat(np.arange(w.n), np.diff(w.succ_ptr)), w.succ_idx, w.succ_t, w.c, [3],
+                 [[1]], np.zeros((1, w.n), dtype=np.uint8))
+    got = _check_search(gpu, oracle, w1, w1.assignments[0])
+    assert len(got["moves"]) == 0 and got["evaluated"] == 0
+    # every vertex pinned where it is: all candidates are invalid, the search stops at once
+    pins = np.stack([np.arange(w.n), w.assignments[0]], axis=1)
+    got = _check_search(gpu, oracle, w, w.assignments[0], pins=pins.tolist())
+    assert len(got["moves"]) == 0 and got["evaluated"] > 0
+    # a start with a device id out of range is refused
+    g = gpu.CpGraph.from_workload(w, device="cuda:0")
+    bad = torch.from_numpy(w.assignments[0].copy()).to("cuda:0")
+    bad[5] = 7
+    with pytest.raises(gpu.CpError) as e:
+        gpu.cp_search(g, bad, w.speeds, w.bandwidth)
+    assert e.value.code == -12
+    g.close()
