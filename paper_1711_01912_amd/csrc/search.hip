@@ -127,6 +127,27 @@ __global__ void seed_path_kernel(SeedArgs a) {
         a.assign[a.path[i]] = (uint8_t)a.fastest;
 }
 
+// x of the lane a DPP control word names (a permutation inside each row of 16 lanes).
+template <int CTRL>
+__device__ __forceinline__ long long dpp_i64(long long x) {
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)x, CTRL, 0xf, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)((unsigned long long)x >> 32), CTRL, 0xf, 0xf, false);
+    return (long long)(((unsigned long long)(uint32_t)hi << 32) | (uint32_t)lo);
+}
+
+// Minimum over lanes 0 .. span-1 (span a power of two), valid in those lanes: inside a row
+// of 16 by register permutations (swap neighbours, swap pairs, mirror 8, mirror 16), across
+// rows by shuffles.
+__device__ __forceinline__ long long min_over_lanes(long long x, int span) {
+    x = min(x, dpp_i64<0xB1>(x));                     // quad_perm 1,0,3,2
+    if (span > 2) x = min(x, dpp_i64<0x4E>(x));       // quad_perm 2,3,0,1
+    if (span > 4) x = min(x, dpp_i64<0x141>(x));      // row_half_mirror
+    if (span > 8) x = min(x, dpp_i64<0x140>(x));      // row_mirror
+    if (span > 16) x = min(x, __shfl_xor(x, 16));
+    if (span > 32) x = min(x, __shfl_xor(x, 32));
+    return x;
+}
+
 // The load rule is a chain: every choice changes the loads the next one sees.  One
 // wavefront walks the vertices in order, lane d keeps load(d); 64 vertices are fetched
 // at a time and handed round with readlane.
@@ -168,9 +189,8 @@ __global__ __launch_bounds__(64) void seed_greedy_kernel(SeedArgs a) {
             const uint64_t cj = (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)cv, j) |
                                 (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(cv >> 32), j) << 32;
             const long long val = mine ? load + cost(cj) : LLONG_MAX;
-            // the devices sit in lanes 0 .. k-1: a butterfly over the next power of two covers them
-            long long best = val;
-            for (int off = span / 2; off > 0; off >>= 1) best = min(best, __shfl_xor(best, off));
+            // the devices sit in lanes 0 .. k-1: a reduction over the next power of two covers them
+            const long long best = min_over_lanes(val, span);
             const int chosen = __ffsll((long long)__ballot(val == best)) - 1;      // lowest device on ties
             if (lane == chosen) load = val;
             if (lane == j) dev = chosen;
