@@ -97,7 +97,7 @@ bool window_preferred(const Packed &p, const WindowCfg &cb, const WindowCfg &ct,
         const double per_cu = std::max<double>(1.0, std::min<double>(
             (double)(kLdsBudget / std::max<size_t>(c.lds_bytes, 1)), 32.0 / (c.nc + c.nlw)));
         const double rounds = std::ceil((double)batch / (cus * std::floor(per_cu)));
-        return rounds * (double)d.ticks * (0.6 + 0.045 * d.smax);
+        return rounds * (double)d.ticks * (0.58 + 0.03 * d.smax);
     };
     const double window_us = sweep_us(p.win_b, cb) + sweep_us(p.win_t, ct);
     auto column_us = [&](const ColumnDir &d) {
