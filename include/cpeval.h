@@ -105,6 +105,9 @@ typedef struct cp_graph_info {
     int32_t window_slots_t;      /* ... and the t-level sweep */
     int32_t window_packet_bytes_b;   /* largest per-level packet of that plan, b-level sweep */
     int32_t window_packet_bytes_t;   /* ... and t-level sweep */
+    int32_t window_far_b;        /* far reads per tick of that plan's b-level sweep (neighbours too far back for the
+                                    LDS ring are read from the output array); 0 = none */
+    int32_t window_far_t;        /* ... and t-level sweep */
     int32_t auto_plan;           /* plan CP_PLAN_AUTO resolves to for a batch of 256 (the choice is made per call) */
     int32_t uploaded;            /* 1 after cp_graph_upload */
     uint64_t blob_bytes;
@@ -184,8 +187,9 @@ int cp_eval_choose_plan(const cp_graph *g, int32_t batch, int32_t k, const int64
  *   profile       NULL, or a profile whose next slot receives this call's stage timestamps
  *
  * Dependencies between outputs: mask_out needs cp_out, blevel_out and tlevel_out; cp_out needs
- * blevel_out unless the resident-window plan runs (it keeps a running maximum, so CP alone costs
- * no output traffic; cp_eval_choose_plan tells which plan CP_PLAN_AUTO takes).  CP_ERR_ARG otherwise.
+ * blevel_out unless the resident-window plan runs on a graph without far reads (info.window_far_b
+ * == 0): it keeps a running maximum, so CP alone costs no output traffic (cp_eval_choose_plan tells
+ * which plan CP_PLAN_AUTO takes).  CP_ERR_ARG otherwise.
  * Errors: CP_ERR_NULL, CP_ERR_SIZE, CP_ERR_SPEED, CP_ERR_BANDWIDTH, CP_ERR_OVERFLOW
  * (CP_TICK_I32 with a bound >= 2^31), CP_ERR_WORKSPACE, CP_ERR_STATE, CP_ERR_ARG, CP_ERR_HIP.
  */

@@ -44,6 +44,7 @@ class GraphInfo(C.Structure):
         ("min_tick_bytes", C.c_int32), ("window_ok", C.c_int32),
         ("window_slots_b", C.c_int32), ("window_slots_t", C.c_int32),
         ("window_packet_bytes_b", C.c_int32), ("window_packet_bytes_t", C.c_int32),
+        ("window_far_b", C.c_int32), ("window_far_t", C.c_int32),
         ("auto_plan", C.c_int32), ("uploaded", C.c_int32), ("blob_bytes", C.c_uint64),
     ]
 
@@ -329,7 +330,7 @@ def cp_eval(graph: CpGraph, assignments, speeds, bandwidth, *, want=("cp", "b", 
     if "cp" in want and "b" not in want:
         # CP alone: the resident-window plan needs no b array for it
         used = plan if plan != PLAN_AUTO else choose_plan(graph, batch, s, bw, tick_bytes)
-        if used != PLAN_RESIDENT_WINDOW:
+        if used != PLAN_RESIDENT_WINDOW or info["window_far_b"] > 0:
             want.add("b")
     rows, cols = (n, batch) if out_layout == OUT_VERTEX_MAJOR else (batch, n)
     if "cp" in want and "cp" not in out:

@@ -95,7 +95,7 @@ bool window_preferred(const Packed &p, const WindowCfg &cb, const WindowCfg &ct,
     const double cus = 256.0;
     auto sweep_us = [&](const WindowDir &d, const WindowCfg &c) {
         const double per_cu = std::max<double>(1.0, std::min<double>(
-            (double)(kLdsBudget / std::max<size_t>(c.lds_bytes, 1)), 32.0 / (c.nc + c.nlw)));
+            (double)(kLdsBudget / std::max<size_t>(c.lds_bytes, 1)), 32.0 / (c.nc + c.nlw + c.nfw)));
         const double rounds = std::ceil((double)batch / (cus * std::floor(per_cu)));
         return rounds * (double)d.ticks * (0.58 + 0.03 * d.smax);
     };
@@ -295,7 +295,7 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
                   ? CP_PLAN_RESIDENT_WINDOW : CP_PLAN_WAVE_COLUMN;
     if (use == CP_PLAN_RESIDENT_WINDOW && !can_window) return CP_ERR_ARG;
     // the wave-column plan reads CP off the stored b-levels; the resident-window sweep keeps a running maximum
-    if (cp_out && !blevel_out && use != CP_PLAN_RESIDENT_WINDOW) return CP_ERR_ARG;
+    if (cp_out && !blevel_out && (use != CP_PLAN_RESIDENT_WINDOW || p.win_b.far_cap > 0)) return CP_ERR_ARG;
 
     // workspace
     const bool need_pT = use == CP_PLAN_WAVE_COLUMN && assign_layout == CP_ASSIGN_PARTITION_MAJOR;

@@ -19,6 +19,9 @@ constexpr size_t kLdsBudget = 160 * 1024;   // LDS per workgroup on gfx950
 constexpr int kWindowMaxWaves = 16;      // wavefronts per workgroup (compute + loader)
 constexpr int kWindowTickSlices = 8;     // slices (compute wavefronts) per tick
 constexpr uint64_t kWindowTickBytes = 15 * 1024;   // packet bytes per tick, unless one slice alone is larger
+constexpr int kWindowFarTicks = 12;      // a neighbour this many ticks back (or more) is read from the output array
+constexpr int kWindowFarLead = 4;        // ticks a far wavefront runs ahead (twice: read list, then gather)
+constexpr int kWindowMaxFarWaves = 4;    // 64 far reads per tick each
 constexpr int kMaskWords = 72;           // 32-bit mask words one tick's id range may touch (fused mask)
 
 inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
@@ -50,12 +53,18 @@ struct ColumnDir {
 //                of lane l of a slice sits at base + j*64 + l.  The ring field is the
 //                neighbour's slot (times 8 when the ring holds {value, device}
 //                pairs: a byte offset); padding entries point at slot `slots`,
-//                which holds the constant 0, with t = 0.  An entry is two uint32, or
+//                which holds the constant 0, with t = 0.  When the ring cannot hold
+//                every neighbour (far_cap > 0), a neighbour computed far_ticks or more
+//                ticks earlier is a far read: its entry points at a pair behind the ring
+//                (byte offset ring bytes + (tick & 1) * 8 * far_cap + 8 * index) that a far
+//                wavefront fills from the output array before the tick starts.  An entry is two uint32, or
 //                one uint32 (field | t << 16) when both fit 16 bits (ent4).
 struct WindowDir {
     size_t stream_off = 0;   // uint4 [total_chunks]
     size_t tick_off = 0;     // uint32 [ticks+1][4] {first chunk, chunks, lowest id, id span}
     size_t gmap_off = 0;     // int32 [ticks*wpad] original id per padded position, -1 = padding
+    size_t far_off = 0;      // uint32 [ticks][far_cap][2] {vertex, c} of the tick's far reads (padding: vertex 0)
+    int32_t far_cap = 0;     // far reads per tick, a multiple of 64; 0 = every neighbour is in the ring
     int64_t total_chunks = 0;
     int32_t ticks = 0;
     int32_t max_chunks = 0;  // largest packet

@@ -107,25 +107,40 @@ bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int6
         int sh = lanes_per_row_log2(rows);
         return (uint64_t)((deg0 + (1 << sh) - 1) >> sh) * kWave;
     };
-    auto earliest_read = [&](int32_t a, int32_t b) -> int32_t {
-        int32_t jmin = a;
-        for (int32_t i = a; i < b; ++i) {
-            int32_t v = order[i];
-            for (int32_t e = csr.ptr[v]; e < csr.ptr[v + 1]; ++e) jmin = std::min(jmin, pos[csr.idx[e]]);
-        }
-        return jmin;
-    };
-
+    // Far edges: a neighbour computed kWindowFarTicks or more ticks earlier is not kept in
+    // the ring; its value is read back from the output array by a far wavefront (32-bit
+    // ticks only: the far values are staged as {value, device} pairs like the ring's).
+    // Before the ticks are known the level distance stands in for the tick distance (a
+    // level is at least one tick), which can only overestimate the ring.
+    std::vector<int32_t> lvl_of((size_t)n);
+    for (int32_t s = 0; s < L; ++s)
+        for (int32_t i = col.lvl_begin[s]; i < col.lvl_begin[s] + col.lvl_count[s]; ++i) lvl_of[i] = s;
     // An upper bound of the ring capacity (exact value below, once the ticks are known)
     // fixes the entry format: the ring holds {value, device} pairs if that leaves room
     // for two stage slots and small cost tables, else separate arrays.
-    int64_t need_ub = 1;
-    for (int32_t s = 0; s < L; ++s) {
-        int32_t a = col.lvl_begin[s], b = a + col.lvl_count[s];
-        need_ub = std::max<int64_t>(need_ub, (int64_t)b - earliest_read(a, b));
-    }
-    dir.packed = ticks32 && 8 * ((uint64_t)need_ub + 1) + 2 * (kWindowTickBytes + 1024) + 4096 <= kLdsBudget - 512;
-    const uint64_t field_max = dir.packed ? 8 * (uint64_t)need_ub : (uint64_t)need_ub;
+    auto ring_bound = [&](bool skip_far) {
+        int64_t bound = 1;
+        for (int32_t i = 0; i < n; ++i) {
+            int32_t v = order[i];
+            int32_t end = col.lvl_begin[lvl_of[i]] + col.lvl_count[lvl_of[i]];
+            for (int32_t e = csr.ptr[v]; e < csr.ptr[v + 1]; ++e) {
+                int32_t pn = pos[csr.idx[e]];
+                if (skip_far && lvl_of[i] - lvl_of[pn] >= kWindowFarTicks) continue;
+                bound = std::max<int64_t>(bound, (int64_t)end - pn);
+            }
+        }
+        return bound;
+    };
+    auto pairs_fit = [&](int64_t slots, uint64_t far_bytes) {
+        return 8 * ((uint64_t)slots + 1) + far_bytes + 2 * (kWindowTickBytes + 1024) + 4096 <= kLdsBudget - 512;
+    };
+    // far reads only where a ring of pairs for every neighbour does not fit
+    int64_t need_ub = ring_bound(false);
+    const bool far_allowed = ticks32 && !pairs_fit(need_ub, 0);
+    if (far_allowed) need_ub = ring_bound(true);
+    const uint64_t far_bytes_ub = far_allowed ? 2 * 8 * (uint64_t)kWave * kWindowMaxFarWaves : 0;
+    dir.packed = ticks32 && pairs_fit(need_ub, far_bytes_ub);
+    const uint64_t field_max = dir.packed ? 8 * (uint64_t)need_ub + 32 + far_bytes_ub : (uint64_t)need_ub;
     dir.ent4 = field_max < 65536 && max_t < 65536;
     const uint64_t esz = dir.ent4 ? 4 : 8;
 
@@ -157,7 +172,38 @@ bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int6
     const int32_t T = (int32_t)tick_a.size();
     dir.ticks = T;
 
-    int64_t need = 1;
+    std::vector<int32_t> tick_of((size_t)n);
+    for (int32_t s = 0; s < T; ++s)
+        for (int32_t i = tick_a[s]; i < tick_b[s]; ++i) tick_of[i] = s;
+    // A neighbour far_ticks or more ticks back is a far read.  The smallest distance is the
+    // one the far wavefronts' timing needs; it is doubled until the far reads of every tick
+    // fit the far wavefronts (a longer ring for fewer far reads).
+    const bool far_on = far_allowed && dir.packed;
+    int32_t far_ticks = kWindowFarTicks;
+    auto is_far = [&](int32_t s, int32_t pn) { return far_on && s - tick_of[pn] >= far_ticks; };
+    int64_t need = 1, far_max = 0;
+    for (;;) {
+        need = 1;
+        far_max = 0;
+        for (int32_t s = 0; s < T; ++s) {
+            int32_t a = tick_a[s], b = tick_b[s];
+            int64_t far_here = 0;
+            for (int32_t i = a; i < b; ++i) {
+                int32_t v = order[i];
+                for (int32_t e = csr.ptr[v]; e < csr.ptr[v + 1]; ++e) {
+                    int32_t pn = pos[csr.idx[e]];
+                    if (is_far(s, pn)) ++far_here;
+                    else need = std::max<int64_t>(need, (int64_t)b - pn);
+                }
+            }
+            far_max = std::max(far_max, far_here);
+        }
+        if (!far_on || far_max <= (int64_t)kWave * kWindowMaxFarWaves || far_ticks > T) break;
+        far_ticks *= 2;
+    }
+    if (far_on && !pairs_fit(need, 2 * 8 * (uint64_t)((far_max + kWave - 1) / kWave * kWave))) return false;
+    if (dir.ent4 && dir.packed && 8 * ((uint64_t)need + 1) + 32 + far_bytes_ub >= 65536) return false;
+
     int32_t wmax = 1;
     int64_t idspan = 1;
     std::vector<uint32_t> tick_tab(4 * ((size_t)T + 1), 0);   // {first chunk, chunks, lowest id, id span}
@@ -165,7 +211,6 @@ bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int6
     uint32_t max_chunks = 1;
     for (int32_t s = 0; s < T; ++s) {
         int32_t a = tick_a[s], b = tick_b[s];
-        need = std::max<int64_t>(need, (int64_t)b - earliest_read(a, b));
         wmax = std::max(wmax, b - a);
         int32_t lo = order[a], hi = order[a];
         for (int32_t i = a; i < b; ++i) { lo = std::min(lo, order[i]); hi = std::max(hi, order[i]); }
@@ -174,6 +219,8 @@ bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int6
         tick_tab[4 * s + 3] = (uint32_t)(hi - lo + 1);
     }
     dir.slots = (int32_t)need;
+    dir.far_cap = (int32_t)((far_max + kWave - 1) / kWave * kWave);
+    if (dir.far_cap > kWave * kWindowMaxFarWaves) return false;    // too many far reads per tick
     dir.smax = (wmax + kWave - 1) / kWave;
     dir.wpad = dir.smax * kWave;
     if (dir.smax > kWindowMaxWaves - 1) return false;   // only when one slice alone exceeds every limit
@@ -206,10 +253,19 @@ bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int6
     int32_t *gmap = w.at<int32_t>(dir.gmap_off);
     std::fill(gmap, gmap + (size_t)std::max(T, 1) * dir.wpad, -1);
 
+    // far reads of a tick: {vertex, c} per read, padded with vertex 0; the pairs they are
+    // turned into sit behind the ring, one region per tick parity
+    dir.far_off = w.reserve(8 * (size_t)std::max(dir.far_cap, 1) * (size_t)std::max(T, 1));
+    uint32_t *far_list = w.at<uint32_t>(dir.far_off);
+    const uint32_t ring_bytes = (uint32_t)((8 * ((uint64_t)dir.slots + 1) + 15) & ~(uint64_t)15);
+    if (dir.far_cap > 0 && dir.ent4 && ring_bytes + 2 * 8 * (uint64_t)dir.far_cap >= 65536) return false;
+
     const uint32_t pad_field = (uint32_t)(dir.packed ? 8 * (uint64_t)dir.slots : (uint64_t)dir.slots);
     for (int32_t s = 0; s < T; ++s) {
         int32_t a = tick_a[s], b = tick_b[s];
         uint32_t nsl = (uint32_t)(b - a + kWave - 1) / kWave;
+        uint32_t far_next = 0;
+        const uint32_t far_base = ring_bytes + (uint32_t)(s & 1) * 8u * (uint32_t)dir.far_cap;
         uint8_t *pk = w.at<uint8_t>(dir.stream_off + 16 * (size_t)tick_tab[4 * s]);
         uint32_t *desc = (uint32_t *)pk;
         uint32_t *rec = (uint32_t *)(pk + 16 * (size_t)dir.smax);         // nsl*64 x {v, c}
@@ -250,8 +306,17 @@ bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int6
                     uint32_t field = pad_field, te = 0;    // padding: the constant-zero slot
                     if (ei < d) {
                         int64_t e = (int64_t)csr.ptr[v] + ei;
-                        uint32_t slot = (uint32_t)(pos[csr.idx[e]] % dir.slots);
-                        field = dir.packed ? 8 * slot : slot;
+                        int32_t pn = pos[csr.idx[e]];
+                        if (is_far(s, pn)) {
+                            uint32_t *fl = far_list + 2 * ((size_t)s * dir.far_cap + far_next);
+                            fl[0] = (uint32_t)csr.idx[e];
+                            fl[1] = (uint32_t)c[csr.idx[e]];
+                            field = far_base + 8 * far_next;
+                            ++far_next;
+                        } else {
+                            uint32_t slot = (uint32_t)(pn % dir.slots);
+                            field = dir.packed ? 8 * slot : slot;
+                        }
                         te = (uint32_t)csr.wt[e];
                     }
                     if (dir.ent4) {
@@ -409,6 +474,8 @@ int pack_graph(int32_t n, int64_t m, int32_t L,
     info.window_slots_t = P.have_window ? P.win_t.slots : 0;
     info.window_packet_bytes_b = P.have_window ? 16 * P.win_b.max_chunks : 0;
     info.window_packet_bytes_t = P.have_window ? 16 * P.win_t.max_chunks : 0;
+    info.window_far_b = P.have_window ? P.win_b.far_cap : 0;
+    info.window_far_t = P.have_window ? P.win_t.far_cap : 0;
     info.blob_bytes = P.blob.size();
     return CP_OK;
 }

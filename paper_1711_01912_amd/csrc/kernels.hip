@@ -472,6 +472,13 @@ struct WindowArgs {
     int64_t mask_row32;        // 32-bit words per mask row
     int64_t n;                 // vertices (row length of bvals)
     int32_t bpad;              // bytes a stage slot reserves for the tick's b values (0: no mask)
+    // far reads: neighbours computed many ticks earlier are fetched from the output array
+    const uint2 *far_list;     // [ticks][far_cap] {vertex, c}
+    const uint8_t *far_assign; // caller's assignments, device of (v, q) at v * far_a_sv + q * far_a_sp
+    int64_t far_a_sp, far_a_sv;
+    int32_t far_cap;           // far reads per tick (multiple of 64), 0 = none
+    int32_t nfw;               // far wavefronts (after the loaders)
+    int32_t stores_per_tick;   // output stores one compute wavefront issues per tick
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // stays in registers when indexed statically
@@ -488,7 +495,7 @@ typedef const uint32_t __attribute__((address_space(4))) *const_u32_ptr;   // un
 // loaders copy packet t+1 (requested DR ticks earlier, held in registers) into
 // the other slot and request packet t+1+DR.  Nothing on the level-to-level
 // dependency touches memory beyond LDS.
-template <typename Tick, bool TSWEEP, bool PACKED, bool ENT4, int NL, int DR, bool MASK>
+template <typename Tick, bool TSWEEP, bool PACKED, bool ENT4, int NL, int DR, bool MASK, bool FAR>
 __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(WindowArgs a) {
     extern __shared__ uint4 lds16[];
     __shared__ long long red[kWindowMaxWaves];
@@ -509,10 +516,11 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
     const uint32_t tab_bytes = (uint32_t)((sizeof(Magic) * ((size_t)k * k + k) + 15) & ~(size_t)15);
     Tick *ring_val = (Tick *)lds;                                  // split layout
     uint8_t *ring_dev = lds + sizeof(Tick) * ((size_t)R + 1);
-    const uint32_t etab_off = ring_bytes;                          // byte offsets inside LDS
+    const uint32_t far_bytes = FAR ? 8u * (uint32_t)a.far_cap : 0u;   // per tick parity, behind the ring
+    const uint32_t etab_off = ring_bytes + 2u * far_bytes;         // byte offsets inside LDS
     const uint32_t vtab_off = etab_off + 8u * (uint32_t)(k * k);
     const int slot_bytes = NL * a.nlw * 1024;
-    uint8_t *stage = lds + ring_bytes + tab_bytes;
+    uint8_t *stage = lds + etab_off + tab_bytes;
     {
         const uint64_t *e = (const uint64_t *)a.edge_tab, *v = (const uint64_t *)a.vert_tab;
         uint64_t *t64 = (uint64_t *)(lds + etab_off);
@@ -530,13 +538,60 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
         }
     }
 
-    const int Lpad = (L + DR - 1) / DR * DR;
+    // ticks rounded up so that the loaders' and the far wavefronts' unrolled loops end together
+    constexpr int kStep = !FAR ? DR : (DR % kWindowFarLead == 0 ? DR : DR * kWindowFarLead / (DR % 2 == 0 ? 2 : 1));
+    static_assert(kStep % DR == 0 && (!FAR || kStep % kWindowFarLead == 0), "tick padding");
+    const int Lpad = (L + kStep - 1) / kStep * kStep;
     const int id16 = a.idpad / 16;               // 16-byte chunks of a slot that hold device ids
     const int b16 = MASK ? a.bpad / 16 : 0;      // ... and the tick's b values
     const int head = a.idpad + (MASK ? a.bpad : 0);   // bytes of a slot before the packet
     Tick best = 0;
 
-    if (wave >= a.nc) {
+    if (FAR && wave >= a.nc + a.nlw) {
+        // ------------------------------------------------ far wavefronts
+        // Lane f of far wavefront fw owns far read number fw*64 + f of every tick.  For tick
+        // tau its {vertex, c} is loaded 2*X + 1 steps ahead, the value and device of that vertex
+        // X + 1 steps ahead (from the output array: the vertex was published at least
+        // kWindowFarTicks ticks before tau, and the compute wavefronts wait for their older
+        // stores before each barrier), and the pair is written one step ahead.
+        constexpr int X = kWindowFarLead;
+        const int f = (wave - a.nc - a.nlw) * 64 + lane;
+        const Tick *outq = (const Tick *)a.out + (size_t)q * (size_t)a.out_sq;
+        const uint8_t *arow = a.far_assign + (size_t)q * (size_t)a.far_a_sp;
+        const Magic *vtab = (const Magic *)(lds + vtab_off);
+        bool bad = false;
+        auto list_load = [&](int tau) -> uint2 {
+            return a.far_list[(size_t)min(tau, L - 1) * (size_t)a.far_cap + f];
+        };
+        auto fetch = [&](uint2 e) -> uint2 {
+            // the value left this compute unit through its write-through cache: read it from L2
+            Tick val = __hip_atomic_load(outq + (size_t)e.x * a.out_sv, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            uint32_t dev = arow[(size_t)e.x * (size_t)a.far_a_sv];
+            if (dev >= (uint32_t)k) { bad = true; dev = (uint32_t)k - 1; }
+            if (TSWEEP) val += (Tick)magic_div(e.y, vtab[dev]);      // the ring holds tl + w
+            return make_uint2((uint32_t)val, 8u * dev);
+        };
+        uint2 lst[X], got[X];
+#pragma unroll
+        for (int j = 1; j <= X; ++j) {
+            lst[j % X] = list_load(j + X);
+            got[j % X] = make_uint2(0, 0);
+        }
+        lds_barrier();                       // pairs with "packet 0 is staged"
+        for (int t0 = 0; t0 < Lpad; t0 += X) {
+#pragma unroll
+            for (int r = 0; r < X; ++r) {
+                const int t = t0 + r;
+                lds_barrier();
+                const int sl = (r + 1) % X;
+                *(uint2 *)(lds + ring_bytes + (uint32_t)((t + 1) & 1) * far_bytes + 8u * (uint32_t)f) = got[sl];
+                got[sl] = fetch(lst[sl]);                 // for tick t + 1 + X
+                lst[sl] = list_load(t + 1 + 2 * X);
+            }
+        }
+        if (MASK) lds_barrier();
+        if (bad) *a.status = CP_STATUS_BAD_DEVICE_ID;
+    } else if (wave >= a.nc) {
         // ------------------------------------------------ loader wavefronts
         const int lw = wave - a.nc;
         const_u32_ptr tick_tab = (const_u32_ptr)a.tick_tab;
@@ -792,6 +847,13 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
 
         lds_barrier();                       // packet 0 is staged
         for (int t = 0; t < Lpad; ++t) {
+            if constexpr (FAR) {
+                // far reads take values from the output array kWindowFarTicks ticks later:
+                // keep at most two ticks' worth of stores in flight
+                if (a.stores_per_tick == 1) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+                else if (a.stores_per_tick == 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            }
             lds_barrier();
             if (t >= L) continue;
             cur_tick = t;
@@ -861,7 +923,7 @@ int launch_column_sweep_t(const SweepLaunch &s, hipStream_t st, int32_t *launche
     return hip_ok(hipGetLastError());
 }
 
-template <typename Tick, bool TSWEEP, bool PACKED, bool ENT4, int NL, int DR, bool MASK>
+template <typename Tick, bool TSWEEP, bool PACKED, bool ENT4, int NL, int DR, bool MASK, bool FAR>
 int launch_window_sweep_k(const SweepLaunch &s, const WindowCfg &cfg, hipStream_t st) {
     const WindowDir &dir = *s.win;
     WindowArgs a{};
@@ -890,33 +952,43 @@ int launch_window_sweep_k(const SweepLaunch &s, const WindowCfg &cfg, hipStream_
         a.n = s.n;
         a.bpad = window_mask_bpad(dir);
     }
-    auto kern = window_sweep_kernel<Tick, TSWEEP, PACKED, ENT4, NL, DR, MASK>;
+    if (FAR) {
+        if (!s.val) return CP_ERR_ARG;       // far reads come out of the output array
+        a.far_list = (const uint2 *)(s.blob + dir.far_off);
+        a.far_assign = s.assign;
+        a.far_a_sp = s.a_stride_p;
+        a.far_a_sv = s.a_stride_v;
+        a.far_cap = dir.far_cap;
+        a.nfw = cfg.nfw;
+        a.stores_per_tick = (dir.smax + cfg.nc - 1) / cfg.nc;
+    }
+    auto kern = window_sweep_kernel<Tick, TSWEEP, PACKED, ENT4, NL, DR, MASK, FAR>;
     if (cfg.lds_bytes > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)cfg.lds_bytes);
         if (e != hipSuccess) return CP_ERR_HIP;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)(8 * a.pgroups)), dim3((cfg.nc + cfg.nlw) * 64),
+    hipLaunchKernelGGL(kern, dim3((unsigned)(8 * a.pgroups)), dim3((cfg.nc + cfg.nlw + (FAR ? cfg.nfw : 0)) * 64),
                        cfg.lds_bytes, st, a);
     return hip_ok(hipGetLastError());
 }
 
-template <typename Tick, bool TSWEEP, bool PACKED, bool ENT4, bool MASK>
+template <typename Tick, bool TSWEEP, bool PACKED, bool ENT4, bool MASK, bool FAR>
 int launch_window_sweep_e(const SweepLaunch &s, const WindowCfg &cfg, hipStream_t st) {
     switch (cfg.nl) {   // loads per loader lane per level x levels in flight: 64 registers at most
-        case 1: return launch_window_sweep_k<Tick, TSWEEP, PACKED, ENT4, 1, 8, MASK>(s, cfg, st);
-        case 2: return launch_window_sweep_k<Tick, TSWEEP, PACKED, ENT4, 2, 8, MASK>(s, cfg, st);
-        case 3: return launch_window_sweep_k<Tick, TSWEEP, PACKED, ENT4, 3, 5, MASK>(s, cfg, st);
-        case 4: return launch_window_sweep_k<Tick, TSWEEP, PACKED, ENT4, 4, 4, MASK>(s, cfg, st);
-        case 8: return launch_window_sweep_k<Tick, TSWEEP, PACKED, ENT4, 8, 2, MASK>(s, cfg, st);
+        case 1: return launch_window_sweep_k<Tick, TSWEEP, PACKED, ENT4, 1, 8, MASK, FAR>(s, cfg, st);
+        case 2: return launch_window_sweep_k<Tick, TSWEEP, PACKED, ENT4, 2, 8, MASK, FAR>(s, cfg, st);
+        case 3: return launch_window_sweep_k<Tick, TSWEEP, PACKED, ENT4, 3, 5, MASK, FAR>(s, cfg, st);
+        case 4: return launch_window_sweep_k<Tick, TSWEEP, PACKED, ENT4, 4, 4, MASK, FAR>(s, cfg, st);
+        case 8: return launch_window_sweep_k<Tick, TSWEEP, PACKED, ENT4, 8, 2, MASK, FAR>(s, cfg, st);
         default: return CP_ERR_ARG;
     }
 }
 
-template <typename Tick, bool TSWEEP, bool PACKED, bool MASK>
+template <typename Tick, bool TSWEEP, bool PACKED, bool MASK, bool FAR = false>
 int launch_window_sweep_p(const SweepLaunch &s, const WindowCfg &cfg, hipStream_t st) {
-    return s.win->ent4 ? launch_window_sweep_e<Tick, TSWEEP, PACKED, true, MASK>(s, cfg, st)
-                       : launch_window_sweep_e<Tick, TSWEEP, PACKED, false, MASK>(s, cfg, st);
+    return s.win->ent4 ? launch_window_sweep_e<Tick, TSWEEP, PACKED, true, MASK, FAR>(s, cfg, st)
+                       : launch_window_sweep_e<Tick, TSWEEP, PACKED, false, MASK, FAR>(s, cfg, st);
 }
 
 template <bool TSWEEP>
@@ -924,6 +996,10 @@ int launch_window_sweep_d(const SweepLaunch &s, const WindowCfg &cfg, hipStream_
     if (s.mask_out) {    // the t sweep that also writes the mask: 32-bit ticks in a packed ring only
         if (!TSWEEP || s.tick_bytes != 4 || !s.win->packed || !s.direct_ids) return CP_ERR_ARG;
         return launch_window_sweep_p<int32_t, true, true, true>(s, cfg, st);
+    }
+    if (s.win->far_cap > 0) {   // far reads exist only beside a packed ring of 32-bit ticks
+        if (s.tick_bytes != 4 || !s.win->packed) return CP_ERR_ARG;
+        return launch_window_sweep_p<int32_t, TSWEEP, true, false, true>(s, cfg, st);
     }
     if (s.tick_bytes == 4)
         return s.win->packed ? launch_window_sweep_p<int32_t, TSWEEP, true, false>(s, cfg, st)
@@ -939,20 +1015,24 @@ int32_t window_mask_bpad(const WindowDir &d) { return 4 * d.idpad + 16; }
 bool window_config(const WindowDir &d, int32_t k, size_t tick_bytes, size_t lds_limit, WindowCfg &out,
                    bool with_mask) {
     if (d.packed && tick_bytes != 4) return false;
+    if (with_mask && d.far_cap > 0) return false;
+    const int nfw = d.far_cap / kWave;                  // far wavefronts, 64 far reads per tick each
     // a tick's id range may touch (31 + span + 31) / 32 mask words
     if (with_mask && (!d.packed || !d.direct_ok || (d.idpad + 62) / 32 > kMaskWords)) return false;
     // 16-byte chunks per stage slot: device ids, the tick's b values (mask), the packet
     const int64_t need = d.idpad / 16 + (with_mask ? window_mask_bpad(d) / 16 : 0) + (int64_t)d.max_chunks;
     const size_t tab = (sizeof(Magic) * ((size_t)k * k + k) + 15) & ~(size_t)15;
-    const size_t ring = (((size_t)d.slots + 1) * (d.packed ? 8 : tick_bytes + 1) + 15) & ~(size_t)15;
+    const size_t ring = ((((size_t)d.slots + 1) * (d.packed ? 8 : tick_bytes + 1) + 15) & ~(size_t)15) +
+                        2 * 8 * (size_t)d.far_cap;      // the far pairs of two ticks sit behind the ring
     static const int kNl[5] = {1, 2, 3, 4, 8};
     for (int nl : kNl) {
         const int64_t nlw = (need + 64 * nl - 1) / (64 * nl);
-        if (nlw > 8) continue;
+        if (nlw > 8 || nlw + nfw > kWindowMaxWaves - 1) continue;
         out.nl = nl;
         out.nlw = (int)nlw;
+        out.nfw = nfw;
         out.dr = nl <= 2 ? 8 : (nl == 3 ? 5 : (nl == 4 ? 4 : 2));
-        out.nc = std::max(1, std::min(d.smax, kWindowMaxWaves - (int)nlw));
+        out.nc = std::max(1, std::min(d.smax, kWindowMaxWaves - (int)nlw - nfw));
         out.packed = d.packed;
         out.lds_bytes = ring + tab + (size_t)2 * nl * nlw * 1024;
         return out.lds_bytes <= lds_limit;

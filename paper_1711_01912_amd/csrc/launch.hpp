@@ -41,6 +41,7 @@ struct WindowCfg {
     int nl = 0;        // 16-byte loads per loader lane per level
     int nlw = 0;       // loader wavefronts
     int nc = 0;        // compute wavefronts
+    int nfw = 0;       // far wavefronts
     int dr = 0;        // levels a loader runs ahead in registers
     bool packed = false;   // ring holds {value, device} pairs (one LDS read per relaxation)
     size_t lds_bytes = 0;

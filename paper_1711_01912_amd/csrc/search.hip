@@ -203,6 +203,7 @@ struct SearchLayout {
     size_t eval_ws = 0, cand = 0, b = 0, cp = 0, valid = 0, path = 0, small = 0, total = 0;
     size_t eval_bytes = 0;
     int plan_chunk = 0;      // plan that evaluates a chunk of candidates
+    bool cp_only = false;    // ... without a b array
     int tick = 4;
 };
 
@@ -227,7 +228,9 @@ int search_layout(const cp_graph *g, int32_t k, int32_t chunk, const int64_t *sp
     if (rc) return rc;
     const size_t n = (size_t)info.n;
     o.eval_bytes = align_up(std::max(ws_chunk, ws_one));
-    const size_t b_cols = o.plan_chunk == CP_PLAN_RESIDENT_WINDOW ? 1 : (size_t)chunk;
+    // CP alone needs no b array only under the resident-window plan on a graph without far reads
+    o.cp_only = o.plan_chunk == CP_PLAN_RESIDENT_WINDOW && info.window_far_b == 0;
+    const size_t b_cols = o.cp_only ? 1 : (size_t)chunk;
     size_t at = 0;
     o.eval_ws = at; at += o.eval_bytes;
     o.cand = at;    at += align_up((size_t)chunk * n);
@@ -324,9 +327,9 @@ int cp_search(const cp_graph *g, int32_t k, const int64_t *speeds, const int64_t
             rc = cp_eval_choose_plan(g, count, k, speeds, bandwidth, lay.tick, &plan);
             if (rc) return rc;
             // a short last chunk may resolve to the other plan: it needs b only if room was made for it
-            void *b_arg = nullptr;
-            if (plan != CP_PLAN_RESIDENT_WINDOW) {
-                if (lay.plan_chunk == CP_PLAN_RESIDENT_WINDOW && count > 1) plan = CP_PLAN_RESIDENT_WINDOW;
+            void *b_arg = lay.cp_only ? nullptr : d_b;
+            if (lay.cp_only && plan != CP_PLAN_RESIDENT_WINDOW) {
+                if (count > 1) plan = CP_PLAN_RESIDENT_WINDOW;
                 else b_arg = d_b;
             }
             rc = cp_eval(g, count, k, d_cand, CP_ASSIGN_PARTITION_MAJOR, speeds, bandwidth, ws + lay.eval_ws,

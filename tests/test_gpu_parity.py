@@ -612,3 +612,56 @@ def test_search_degenerate_calls(gpu, oracle):
         gpu.cp_search(g, bad, w.speeds, w.bandwidth)
     assert e.value.code == -12
     g.close()
+
+
+# ------------------------------------------------------------------ far reads of the resident-window plan
+
+def _with_long_edges(rng, widths, extra, min_span):
+    n, level, src, dst = random_layered_dag(rng, widths, 1, 4, 6)
+    L = len(widths)
+    off = np.concatenate([[0], np.cumsum(widths)])
+    lo = rng.integers(0, L - min_span, size=extra)
+    hi = rng.integers(lo + min_span, L)                 # uniformly over the levels far enough ahead
+    u = off[lo] + rng.integers(0, np.asarray(widths)[lo])
+    v = off[hi] + rng.integers(0, np.asarray(widths)[hi])
+    pairs = np.unique(np.stack([np.concatenate([src, u]), np.concatenate([dst, v])], axis=1), axis=0)
+    return n, level, pairs[:, 0], pairs[:, 1]
+
+
+def test_long_edges_do_not_rule_the_window_plan_out(gpu, oracle):
+    """A deep narrow graph with edges that span most of its depth: their far ends do not fit an
+    LDS ring, so the window plan reads them back from the output array."""
+    rng = np.random.default_rng(81)
+    n, level, src, dst = _with_long_edges(rng, [700] * 400, extra=6000, min_span=40)
+    w = _custom("long-edges", n, src, dst, rng.integers(1, 3000, size=len(src)), rng.integers(1, 500, size=n),
+                [1, 2, 4, 4], rng.integers(1, 40, size=(4, 4)), rng.integers(0, 4, size=(70, n), dtype=np.uint8), level)
+    g = gpu.CpGraph.from_workload(w)
+    info = g.info
+    g.close()
+    assert info["window_ok"] == 1 and info["window_far_b"] > 0 and info["window_far_t"] > 0
+    _check(gpu, oracle, w, plans=(WINDOW, COLUMN), layouts=(0, 1))
+    # CP alone still needs the b array on such a graph
+    from gpu_util import run_gpu
+    r = run_gpu(w, WINDOW, want=("cp",))
+    assert "b" in r and np.array_equal(r["cp"], _oracle(oracle, w, want=("cp",))["cp"])
+
+
+def test_far_reads_with_few_levels_and_mirror_edges(gpu, oracle):
+    """A forward chain mirrored by a backward chain with an edge from every forward vertex to
+    its twin (the shape of a training graph), deep enough that the twins are far apart."""
+    depth, width = 1500, 20
+    n = 2 * depth * width
+    fwd = np.arange(depth * width).reshape(depth, width)
+    bwd = fwd[::-1] + depth * width
+    src = np.concatenate([fwd[:-1].ravel(), bwd[:-1].ravel(), fwd.ravel(), fwd[-1]])
+    dst = np.concatenate([fwd[1:].ravel(), bwd[1:].ravel(), bwd[::-1].ravel(), bwd[0]])
+    rng = np.random.default_rng(82)
+    level = np.concatenate([np.repeat(np.arange(depth), width), np.repeat(np.arange(2 * depth - 1, depth - 1, -1), width)])
+    w = _custom("mirror", n, src, dst, rng.integers(1, 200, size=len(src)), rng.integers(1, 60, size=n), [2, 3, 5],
+                rng.integers(1, 9, size=(3, 3)), rng.integers(0, 3, size=(130, n), dtype=np.uint8), level)
+    g = gpu.CpGraph.from_workload(w)
+    info = g.info
+    g.close()
+    assert info["window_ok"] == 1 and info["window_far_b"] > 0
+    _check(gpu, oracle, w)
+    _check_paths(gpu, oracle, w)
