@@ -1025,19 +1025,32 @@ bool window_config(const WindowDir &d, int32_t k, size_t tick_bytes, size_t lds_
     const size_t ring = ((((size_t)d.slots + 1) * (d.packed ? 8 : tick_bytes + 1) + 15) & ~(size_t)15) +
                         2 * 8 * (size_t)d.far_cap;      // the far pairs of two ticks sit behind the ring
     static const int kNl[5] = {1, 2, 3, 4, 8};
+    bool found = false;
     for (int nl : kNl) {
         const int64_t nlw = (need + 64 * nl - 1) / (64 * nl);
         if (nlw > 8 || nlw + nfw > kWindowMaxWaves - 1) continue;
-        out.nl = nl;
-        out.nlw = (int)nlw;
-        out.nfw = nfw;
-        out.dr = nl <= 2 ? 8 : (nl == 3 ? 5 : (nl == 4 ? 4 : 2));
-        out.nc = std::max(1, std::min(d.smax, kWindowMaxWaves - (int)nlw - nfw));
-        out.packed = d.packed;
-        out.lds_bytes = ring + tab + (size_t)2 * nl * nlw * 1024;
-        return out.lds_bytes <= lds_limit;
+        WindowCfg c;
+        c.nl = nl;
+        c.nlw = (int)nlw;
+        c.nfw = nfw;
+        c.dr = nl <= 2 ? 8 : (nl == 3 ? 5 : (nl == 4 ? 4 : 2));
+        c.nc = std::max(1, std::min(d.smax, kWindowMaxWaves - (int)nlw - nfw));
+        c.packed = d.packed;
+        c.lds_bytes = ring + tab + (size_t)2 * nl * nlw * 1024;
+        if (c.lds_bytes > lds_limit) continue;
+        // The first shape that fits (most ticks of prefetch) is the one for a workgroup that
+        // fills a compute unit.  A small workgroup shares the unit with others: there fewer
+        // wavefronts per workgroup mean more workgroups, as long as the loaders still run
+        // four ticks ahead.
+        if (!found) {
+            out = c;
+            found = true;
+            if (c.lds_bytes > 40 * 1024) break;
+        } else if (c.lds_bytes <= 40 * 1024 && c.dr >= 4 && c.nc + c.nlw + c.nfw < out.nc + out.nlw + out.nfw) {
+            out = c;
+        }
     }
-    return false;
+    return found;
 }
 
 int launch_gather_assign(const SweepLaunch &s, uint8_t *out, void *stream) {
