@@ -250,13 +250,14 @@ bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int6
     dir.tick_off = w.reserve(sizeof(uint32_t) * tick_tab.size());
     std::memcpy(w.at<uint32_t>(dir.tick_off), tick_tab.data(), sizeof(uint32_t) * tick_tab.size());
     dir.gmap_off = w.reserve(sizeof(int32_t) * (size_t)std::max(T, 1) * dir.wpad);
+    dir.far_off = w.reserve(8 * (size_t)std::max(dir.far_cap, 1) * (size_t)std::max(T, 1));
+    // every reservation is made: the blob does not move any more
     int32_t *gmap = w.at<int32_t>(dir.gmap_off);
+    uint32_t *far_list = w.at<uint32_t>(dir.far_off);
     std::fill(gmap, gmap + (size_t)std::max(T, 1) * dir.wpad, -1);
 
     // far reads of a tick: {vertex, c} per read, padded with vertex 0; the pairs they are
     // turned into sit behind the ring, one region per tick parity
-    dir.far_off = w.reserve(8 * (size_t)std::max(dir.far_cap, 1) * (size_t)std::max(T, 1));
-    uint32_t *far_list = w.at<uint32_t>(dir.far_off);
     const uint32_t ring_bytes = (uint32_t)((8 * ((uint64_t)dir.slots + 1) + 15) & ~(uint64_t)15);
     if (dir.far_cap > 0 && dir.ent4 && ring_bytes + 2 * 8 * (uint64_t)dir.far_cap >= 65536) return false;
 

@@ -665,3 +665,61 @@ def test_far_reads_with_few_levels_and_mirror_edges(gpu, oracle):
     assert info["window_ok"] == 1 and info["window_far_b"] > 0
     _check(gpu, oracle, w)
     _check_paths(gpu, oracle, w)
+
+
+# ------------------------------------------------------------------ many small random shapes
+
+@pytest.mark.parametrize("block", range(4))
+def test_random_shapes(gpu, oracle, block):
+    """Layered DAGs of random depth, width, degree and edge span, with random device counts,
+    batch sizes and weight ranges: every output of every plan that can run them, both layouts."""
+    from gpu_util import assert_equal_to_oracle, run_gpu
+    for seed in range(block * 6, block * 6 + 6):
+        rng = np.random.default_rng(9000 + seed)
+        depth = int(rng.integers(2, 60))
+        widths = rng.integers(1, int(rng.choice([3, 20, 90, 300])) + 1, size=depth)
+        n, level, src, dst = random_layered_dag(rng, widths, int(rng.integers(0, 2)), int(rng.integers(2, 9)),
+                                                int(rng.integers(1, max(2, depth))))
+        k = int(rng.choice([1, 2, 3, 7, 16, 33]))
+        P = int(rng.choice([1, 5, 64, 65, 130]))
+        tmax = int(rng.choice([1, 50, 70000, 2**31]))
+        cmax = int(rng.choice([1, 99, 10**6]))
+        B = rng.integers(1, int(rng.choice([2, 64, 10**5])) + 1, size=(k, k))
+        w = _custom(f"random-{seed}", n, src, dst, rng.integers(0, tmax + 1, size=len(src)),
+                    rng.integers(0, cmax + 1, size=n), rng.integers(1, int(rng.choice([2, 17, 5000])) + 1, size=k), B,
+                    rng.integers(0, k, size=(P, n), dtype=np.uint8), level)
+        ref = _oracle(oracle, w)
+        g = gpu.CpGraph.from_workload(w, device="cuda:0")
+        plans = [COLUMN] + ([WINDOW] if g.info["window_ok"] else [])
+        for plan in plans:
+            for ol in (0, 1):
+                for layout in (0, 1):
+                    try:
+                        res = run_gpu(w, plan, layout=layout, graph=g, out_layout=ol)
+                    except gpu.CpError as e:
+                        # the window plan also needs cost tables in the 32-bit form and room in LDS for k
+                        assert plan == WINDOW and e.code == -12, (seed, plan, e.code)
+                        continue
+                    assert_equal_to_oracle(res, ref, what=f"seed={seed} plan={plan} layout={layout} out={ol} "
+                                                          f"n={n} k={k} P={P}")
+        g.close()
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_deep_shapes_with_long_spans(gpu, oracle, seed):
+    """Deep graphs whose edges may span the whole depth: the window plan runs them with far reads."""
+    rng = np.random.default_rng(9500 + seed)
+    depth = int(rng.integers(250, 600))
+    widths = rng.integers(20, 110, size=depth)
+    n, level, src, dst = random_layered_dag(rng, widths, 1, 3, depth - 1)
+    k = int(rng.choice([2, 5, 16]))
+    P = int(rng.choice([3, 64, 200]))
+    w = _custom(f"deep-{seed}", n, src, dst, rng.integers(0, 3000, size=len(src)), rng.integers(1, 400, size=n),
+                rng.integers(1, 9, size=k), rng.integers(1, 50, size=(k, k)),
+                rng.integers(0, k, size=(P, n), dtype=np.uint8), level)
+    g = gpu.CpGraph.from_workload(w)
+    info = g.info
+    g.close()
+    if info["window_ok"]:
+        assert info["window_far_b"] > 0 or info["window_slots_b"] < 20000
+    _check(gpu, oracle, w, plans=(COLUMN,) + ((WINDOW,) if info["window_ok"] else ()), layouts=(0, 1))

@@ -295,3 +295,30 @@ def test_consumer_entry_points_check_their_arguments(lib):
     assert plan.value in (cpe.PLAN_WAVE_COLUMN, cpe.PLAN_RESIDENT_WINDOW)
     assert lib.cp_eval_choose_plan(g._handle, 16, 2, sp, bp, 3, C.byref(plan)) == -12
     g.close()
+
+
+def test_packing_deep_graphs_with_long_spans(lib):
+    """Deep graphs whose edges span the whole depth are packed for the resident-window plan
+    with far reads: a short ring plus a bounded number of far reads per tick."""
+    from workloads import random_layered_dag
+    from workloads.dags import _finish
+    for seed in range(3):
+        rng = np.random.default_rng(9500 + seed)
+        depth = int(rng.integers(250, 600))
+        widths = rng.integers(20, 110, size=depth)
+        n, level, src, dst = random_layered_dag(rng, widths, 1, 3, depth - 1)
+        csr = build_csr(n, src, dst, rng.integers(0, 3000, size=len(src)), level)
+        w = _finish(f"deep-{seed}", csr, rng.integers(1, 400, size=n), 2, [1, 2], [[1, 3], [3, 1]],
+                    np.zeros((1, n), dtype=np.uint8))
+        g = cpe.CpGraph.from_workload(w)
+        info = g.info
+        assert info["window_ok"] == 1
+        assert 0 < info["window_far_b"] <= 256 and info["window_far_b"] % 64 == 0
+        assert 0 < info["window_far_t"] <= 256
+        assert info["window_slots_b"] < n // 2 and info["window_slots_t"] < n // 2
+        g.close()
+    # without long edges nothing is a far read
+    w = make_workload("large_sparse", P=1, levels=100, width=80)
+    g = cpe.CpGraph.from_workload(w)
+    assert g.info["window_far_b"] == 0 and g.info["window_far_t"] == 0
+    g.close()
