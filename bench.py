@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X, published
 # copy: x2.00 and x1.00).  The figure belongs to one build of the kernel: it is reported only
 # while the sources it was taken on are unchanged, and for the configuration it was taken on.
 MEASURED_TRAFFIC = {
-    "sources_sha256": "257a1d5f0cf884e938e7ef27317a0a91afadd6dab1f0d094a2b6acf0c06f7837",
+    "sources_sha256": "f943be48956ba8c57d71be8236965b654141379c571a53697f4c94e22a1fdcc2",
     "workload": "large_sparse", "P": 256, "plan": 2, "out_layout": 1,
     "bytes_per_blevel_launch": (2 * 227708 + 1000002) * 1024,
 }
