@@ -91,3 +91,56 @@ def critical_paths(n, edges, c, speeds, bandwidth, p):
         elif cost == best:
             found.append(verts)
     return best, found
+
+
+def list_schedule_by_ticks(n, edges, c, speeds, bandwidth, p, policy, b=None, tie=None, horizon=100_000):
+    """Time-stepped list scheduling of one partition p, used only to pin the oracle's event loop.
+
+    The clock advances one tick at a time (no event queue, no ready lists).  At every tick
+    each free device looks at all its unstarted vertices, keeps those whose every input
+    tensor has arrived (paper, section 4, criterion (4)) and starts one at once (criteria
+    (2), (3), (6)): under "pct" the one with the largest b, lowest vertex number among
+    equals (section 4.1); under "fifo" the one that became executable first, the smaller
+    tie value (vertex number if tie is None) among equals (section 5.1).  Returns
+    (makespan, start[n]).  Every vertex must take at least one tick.
+    """
+    k = len(speeds)
+    w = [_w(c, speeds, p, v) for v in range(n)]
+    assert all(x >= 1 for x in w)
+    preds = [[] for _ in range(n)]
+    for (u, v, t) in edges:
+        preds[v].append((u, _x(t, bandwidth, p, u, v)))
+    start = [None] * n
+    free_at = [0] * k
+    now = 0
+    left = n
+    while left:
+        if now > horizon:
+            raise RuntimeError("no progress: cycle or horizon too short")
+        started_now = []
+        for d in range(k):
+            if free_at[d] > now:
+                continue
+            executable = []
+            for v in range(n):
+                if p[v] != d or start[v] is not None:
+                    continue
+                arrivals = [None if start[u] is None else start[u] + w[u] + x for (u, x) in preds[v]]
+                if any(a is None or a > now for a in arrivals):
+                    continue
+                executable.append((v, max(arrivals, default=0)))
+            if not executable:
+                continue
+            if policy == "pct":
+                v = min(executable, key=lambda it: (-b[it[0]], it[0]))[0]
+            else:
+                v = min(executable, key=lambda it: (it[1], it[0] if tie is None else tie[it[0]], it[0]))[0]
+            started_now.append((v, d))
+        # a vertex started at this tick finishes later than this tick, so the devices'
+        # decisions at one tick do not depend on each other: apply them together
+        for (v, d) in started_now:
+            start[v] = now
+            free_at[d] = now + w[v]
+            left -= 1
+        now += 1
+    return max(free_at), start

@@ -509,3 +509,195 @@ int cp_oracle_seed(int32_t n, const int32_t *succ_ptr, const int32_t *succ_idx, 
     free(zero_t); free(one_dev); free(path); free(on_path); free(load);
     return rc;
 }
+
+
+/*
+ * List-scheduling simulation of one iteration (paper, section 4: the scheduling
+ * criteria (1)-(6); section 4.1: PCT scheduling; section 5.1: the FIFO baseline;
+ * section 5: an event-based simulation gives the execution time of one iteration).
+ *
+ * The reading taken here, in integer ticks:
+ *   - every device runs its own vertices one at a time, without interruption; v keeps its
+ *     device busy for w(v) ticks from start(v) to finish(v) = start(v) + w(v);
+ *   - the tensor of an edge e = (u -> v) is at v's device at finish(u) + x(e); transfers
+ *     do not occupy devices and do not compete with each other (the model of section 2
+ *     has a transfer rate per device pair and nothing else);
+ *   - v is executable from ready(v) = max over in-edges of those arrival times, 0 for a
+ *     vertex without predecessors;
+ *   - a device that is free at time T and owns an executable, unstarted vertex starts one
+ *     at T; otherwise it stays idle until the first of its vertices becomes executable
+ *     (criterion (6): idle only when nothing is executable);
+ *   - the choice among the executable vertices at T:
+ *       FIFO (policy 0): the one that became executable first, smallest ready(v); among
+ *                        equals the paper draws at random -- here the caller passes the
+ *                        draw as tie[v] and the smaller tie wins (tie = NULL: the vertex
+ *                        number), equal ties fall back to the smaller vertex number;
+ *       PCT  (policy 1): the largest b(v) (section 4.1's path computation time), among
+ *                        equals the smaller vertex number;
+ *   - makespan = the largest finish time = the start time of the final sink.
+ * Every vertex must cost at least one tick (c(v) >= 1): then a vertex started at T can
+ * influence another device only after T, so the order in which devices that decide at the
+ * same time are served does not matter.  c(v) = 0 is refused.
+ *
+ * How it runs: per device a plain list of the vertices whose predecessors have all
+ * started (so their ready time is final) and that have not started themselves.  Step:
+ * for every device d, T_d = max(free(d), smallest ready time in d's list); the device
+ * with the smallest T_d (lowest number on ties) decides at T_d by a scan of its list.
+ *
+ * b is [P][n] (PCT only), tie [n] (FIFO only, may be NULL), makespan_out [P],
+ * start_out [P][n] (may be NULL).  Returns 0; -1 cycle (a vertex never started);
+ * -2 out of memory; -3 bad argument.
+ */
+static int64_t simulate_one(int32_t n, const int32_t *succ_ptr, const int32_t *succ_idx,
+                            const int64_t *succ_t, const int64_t *c, int k, const int64_t *speeds,
+                            const int64_t *bandwidth, const int32_t *indeg0, const uint8_t *p,
+                            int policy, const int64_t *b, const int32_t *tie,
+                            int64_t *start, int64_t *ready, int32_t *indeg,
+                            int32_t *list, int32_t *list_at, int32_t *list_len,
+                            int64_t *free_at, int64_t *T, uint8_t *stale)
+{
+    const int64_t NEVER = INT64_MAX;
+    /* list of device d occupies list[list_at[d] .. list_at[d] + list_len[d]) */
+    for (int d = 0; d <= k; ++d) list_at[d] = 0;
+    for (int32_t v = 0; v < n; ++v) list_at[p[v] + 1]++;
+    for (int d = 0; d < k; ++d) list_at[d + 1] += list_at[d];
+    for (int d = 0; d < k; ++d) { list_len[d] = 0; free_at[d] = 0; stale[d] = 1; }
+    for (int32_t v = 0; v < n; ++v) {
+        indeg[v] = indeg0[v];
+        ready[v] = 0;
+        start[v] = -1;
+        if (indeg[v] == 0) list[list_at[p[v]] + list_len[p[v]]++] = v;
+    }
+    int32_t started = 0;
+    for (;;) {
+        int who = -1;
+        for (int d = 0; d < k; ++d) {
+            if (stale[d]) {
+                int64_t first = NEVER;
+                for (int32_t i = 0; i < list_len[d]; ++i) {
+                    int64_t r = ready[list[list_at[d] + i]];
+                    if (r < first) first = r;
+                }
+                T[d] = first == NEVER ? NEVER : (first > free_at[d] ? first : free_at[d]);
+                stale[d] = 0;
+            }
+            if (T[d] != NEVER && (who < 0 || T[d] < T[who])) who = d;
+        }
+        if (who < 0) break;
+        const int64_t now = T[who];
+        int32_t *mine = list + list_at[who];
+        int32_t pick = -1;
+        for (int32_t i = 0; i < list_len[who]; ++i) {
+            const int32_t v = mine[i];
+            if (ready[v] > now) continue;                 /* not executable yet */
+            if (pick < 0) { pick = i; continue; }
+            const int32_t u = mine[pick];
+            int better;
+            if (policy == 1) {
+                better = b[v] > b[u] || (b[v] == b[u] && v < u);
+            } else {
+                const int64_t tv = tie ? tie[v] : v, tu = tie ? tie[u] : u;
+                better = ready[v] < ready[u] ||
+                         (ready[v] == ready[u] && (tv < tu || (tv == tu && v < u)));
+            }
+            if (better) pick = i;
+        }
+        const int32_t v = mine[pick];
+        mine[pick] = mine[--list_len[who]];
+        start[v] = now;
+        ++started;
+        const int64_t done = now + cp_oracle_vertex_cost(c[v], speeds[who]);
+        free_at[who] = done;
+        stale[who] = 1;
+        for (int32_t e = succ_ptr[v]; e < succ_ptr[v + 1]; ++e) {
+            const int32_t u = succ_idx[e];
+            const int64_t here = done + cp_oracle_edge_cost(succ_t[e], who, p[u], bandwidth, k);
+            if (here > ready[u]) ready[u] = here;
+            if (--indeg[u] == 0) {
+                list[list_at[p[u]] + list_len[p[u]]++] = u;
+                stale[p[u]] = 1;
+            }
+        }
+    }
+    if (started != n) return -1;
+    int64_t makespan = 0;
+    for (int d = 0; d < k; ++d)
+        if (free_at[d] > makespan) makespan = free_at[d];
+    return makespan;
+}
+
+int cp_oracle_simulate(int32_t n, const int32_t *succ_ptr, const int32_t *succ_idx,
+                       const int64_t *succ_t, const int64_t *c, int k, const int64_t *speeds,
+                       const int64_t *bandwidth, int32_t P, const uint8_t *assignments,
+                       int policy, const int64_t *b, const int32_t *tie,
+                       int64_t *makespan_out, int64_t *start_out, int threads, int *threads_used)
+{
+    if (n < 0 || P < 0 || k < 1 || k > 256 || (policy != 0 && policy != 1)) return -3;
+    if (policy == 1 && !b) return -3;
+    for (int i = 0; i < k; ++i) {
+        if (speeds[i] < 1) return -3;
+        for (int j = 0; j < k; ++j)
+            if (i != j && bandwidth[(size_t)i * k + j] < 1) return -3;
+    }
+    int64_t m = n ? succ_ptr[n] : 0;
+    for (int32_t v = 0; v < n; ++v) if (c[v] < 1) return -3;
+    for (int64_t e = 0; e < m; ++e) if (succ_t[e] < 0) return -3;
+    for (int64_t i = 0; i < (int64_t)P * n; ++i) if (assignments[i] >= k) return -3;
+
+    int32_t *indeg0 = (int32_t *)calloc((size_t)n + 1, sizeof(int32_t));
+    if (!indeg0) return -2;
+    for (int64_t e = 0; e < m; ++e) indeg0[succ_idx[e]]++;
+
+    if (threads < 1) threads = 1;
+    int used = 1, failed = 0, cyclic = 0;
+#ifdef _OPENMP
+#pragma omp parallel num_threads(threads)
+#endif
+    {
+#ifdef _OPENMP
+#pragma omp single
+        used = omp_get_num_threads();
+#endif
+        int64_t *st = start_out ? NULL : (int64_t *)malloc(((size_t)n + 1) * sizeof(int64_t));
+        int64_t *ready = (int64_t *)malloc(((size_t)n + 1) * sizeof(int64_t));
+        int32_t *indeg = (int32_t *)malloc(((size_t)n + 1) * sizeof(int32_t));
+        int32_t *list = (int32_t *)malloc(((size_t)n + 1) * sizeof(int32_t));
+        int32_t *list_at = (int32_t *)malloc(((size_t)k + 2) * sizeof(int32_t));
+        int32_t *list_len = (int32_t *)malloc(((size_t)k + 1) * sizeof(int32_t));
+        int64_t *free_at = (int64_t *)malloc(((size_t)k + 1) * sizeof(int64_t));
+        int64_t *T = (int64_t *)malloc(((size_t)k + 1) * sizeof(int64_t));
+        uint8_t *stale = (uint8_t *)malloc((size_t)k + 1);
+        if ((!start_out && !st) || !ready || !indeg || !list || !list_at || !list_len || !free_at || !T ||
+            !stale) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
+            failed = 1;
+        }
+#ifdef _OPENMP
+#pragma omp barrier
+#pragma omp for schedule(dynamic, 1)
+#endif
+        for (int32_t j = 0; j < P; ++j) {
+            if (failed) continue;
+            int64_t *s = start_out ? start_out + (size_t)j * n : st;
+            int64_t r = simulate_one(n, succ_ptr, succ_idx, succ_t, c, k, speeds, bandwidth, indeg0,
+                                     assignments + (size_t)j * n, policy,
+                                     b ? b + (size_t)j * n : NULL, tie, s, ready, indeg, list, list_at,
+                                     list_len, free_at, T, stale);
+            if (r < 0) {
+#ifdef _OPENMP
+#pragma omp atomic write
+#endif
+                cyclic = 1;
+            }
+            makespan_out[j] = r;
+        }
+        free(st); free(ready); free(indeg); free(list); free(list_at); free(list_len);
+        free(free_at); free(T); free(stale);
+    }
+    free(indeg0);
+    if (threads_used) *threads_used = used;
+    if (failed) return -2;
+    return cyclic ? -1 : 0;
+}

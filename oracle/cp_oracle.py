@@ -49,6 +49,9 @@ def _load():
                                          i32p, C.c_int64, i32p, C.c_int32, C.c_int32, i64p, i32p, C.c_int]
         lib.cp_oracle_seed.restype = C.c_int
         lib.cp_oracle_seed.argtypes = [C.c_int32, i32p, i32p, i64p, C.c_int, i64p, C.c_int32, u8p]
+        lib.cp_oracle_simulate.restype = C.c_int
+        lib.cp_oracle_simulate.argtypes = [C.c_int32, i32p, i32p, i64p, i64p, C.c_int, i64p, i64p, C.c_int32, u8p,
+                                           C.c_int, i64p, i32p, i64p, i64p, C.c_int, C.POINTER(C.c_int)]
         _lib = lib
     return _lib
 
@@ -299,4 +302,58 @@ def seed(n, succ_ptr, succ_idx, c, speeds, max_len):
                             _ptr(s, C.c_int64), int(max_len), _ptr(out, C.c_uint8))
     if rc:
         raise ValueError(f"seed failed with code {rc}")
+    return out
+
+
+FIFO, PCT = 0, 1
+
+
+def simulate(n, succ_ptr, succ_idx, succ_t, c, speeds, bandwidth, assignments, policy, b=None, tie=None,
+             want_start=True, threads=1):
+    """List-scheduling simulation (paper, section 4 criteria, section 4.1 PCT, section 5.1 FIFO) of
+    every row of ``assignments[P][n]``.  ``b`` int64 [P][n] is needed for PCT, ``tie`` int32 [n]
+    (optional) orders FIFO's equal ready times.  Returns {"makespan": int64 [P], "start": int64
+    [P][n] (if asked for), "threads": threads that ran}."""
+    lib = _load()
+    sp = np.ascontiguousarray(succ_ptr, dtype=np.int32)
+    si = np.ascontiguousarray(succ_idx, dtype=np.int32)
+    st = np.ascontiguousarray(succ_t, dtype=np.int64)
+    if si.size == 0:
+        si = np.zeros(1, dtype=np.int32)
+        st = np.zeros(1, dtype=np.int64)
+    cc = np.ascontiguousarray(c, dtype=np.int64)
+    s = np.ascontiguousarray(speeds, dtype=np.int64)
+    bw = np.ascontiguousarray(bandwidth, dtype=np.int64)
+    a = np.ascontiguousarray(assignments, dtype=np.uint8)
+    k = int(s.shape[0])
+    assert bw.shape == (k, k) and a.ndim == 2 and a.shape[1] == n and sp.shape[0] == n + 1
+    P = int(a.shape[0])
+    bb = None
+    if b is not None:
+        bb = np.ascontiguousarray(b, dtype=np.int64)
+        assert bb.shape == (P, n)
+    tt = None
+    if tie is not None:
+        tt = np.ascontiguousarray(tie, dtype=np.int32)
+        assert tt.shape == (n,)
+    makespan = np.zeros(P, dtype=np.int64)
+    start = np.zeros((P, n), dtype=np.int64) if want_start else None
+    used = C.c_int(0)
+    rc = lib.cp_oracle_simulate(
+        n, _ptr(sp, C.c_int32), _ptr(si, C.c_int32), _ptr(st, C.c_int64), _ptr(cc, C.c_int64),
+        k, _ptr(s, C.c_int64), _ptr(bw, C.c_int64), P, _ptr(a, C.c_uint8), int(policy),
+        _ptr(bb, C.c_int64) if bb is not None else C.POINTER(C.c_int64)(),
+        _ptr(tt, C.c_int32) if tt is not None else C.POINTER(C.c_int32)(),
+        _ptr(makespan, C.c_int64),
+        _ptr(start, C.c_int64) if start is not None else C.POINTER(C.c_int64)(),
+        int(threads), C.byref(used))
+    if rc == -1:
+        raise ValueError("graph has a cycle")
+    if rc == -3:
+        raise ValueError("bad argument (see cp_oracle_simulate)")
+    if rc:
+        raise MemoryError("oracle ran out of memory")
+    out = {"makespan": makespan, "threads": int(used.value)}
+    if start is not None:
+        out["start"] = start
     return out
