@@ -61,6 +61,9 @@ extern "C" {
 #define CP_STATUS_BAD_CONSTRAINT  4   /* cp_validate: a constraint names a vertex >= n or a device >= k; it was skipped */
 #define CP_STATUS_B_OUT_OF_RANGE 2   /* cp_pct_order: some b lies outside [0, max_b]: the order is meaningless;
                                         status values are bit flags and may be or-ed */
+#define CP_STATUS_BAD_TIE        8   /* cp_simulate: tie is not a permutation of 0 .. n-1: nothing was simulated */
+#define CP_STATUS_INCOMPLETE     16  /* cp_simulate: a partition ended with vertices that never started (cannot
+                                        happen on a graph that cp_graph_create accepted) */
 
 /* ---- enums ---- */
 #define CP_TICK_I32  4   /* b-level / t-level stored as int32 (only if the graph's bound allows) */
@@ -273,6 +276,57 @@ int cp_pct_order(const cp_graph *g, int32_t batch, int32_t k,
 int cp_validate(int32_t n, int32_t batch, int32_t k, const uint8_t *assignments, int assign_layout,
                 int64_t num_pairs, const int32_t *pairs, int64_t num_pins, const int32_t *pins,
                 void *stream, uint8_t *valid_out, int32_t *violations_out, int32_t *status_out);
+
+/* ---- scheduling policies of cp_simulate ---- */
+#define CP_POLICY_FIFO 0   /* the vertex that became executable first (paper, section 5.1) */
+#define CP_POLICY_PCT  1   /* the vertex with the largest path computation time b (paper, section 4.1) */
+
+/*
+ * List-scheduling simulation of one iteration under each of `batch` partitions: the
+ * execution time the paper's evaluation plots (section 5).  The scheduling criteria of
+ * section 4 are read as follows, in the integer ticks of cp_eval:
+ *   - a device runs its own vertices one at a time, without interruption, w(v) ticks each;
+ *   - the tensor of an edge (u -> v) is at v's device x(u -> v) ticks after u finishes;
+ *     transfers occupy no device and do not compete (section 2 models a rate per device
+ *     pair and nothing else);
+ *   - v is executable once all its input tensors are there (time 0 without inputs);
+ *   - a free device that owns an executable vertex starts one at once, otherwise it waits
+ *     for the first of its vertices to become executable;
+ *   - CP_POLICY_FIFO takes the vertex that became executable first; among equals the paper
+ *     draws at random, here the caller passes the draw: the smaller tie[v] wins;
+ *     CP_POLICY_PCT takes the largest b(v), the smaller vertex number among equals.
+ * Every vertex must cost at least one tick (c(v) >= 1 for all v, else CP_ERR_ARG): then
+ * devices that decide at the same time cannot influence each other and the schedule is
+ * unique.  All times must stay below 2^31: the summed execution times on the slowest device plus
+ * the graph's raw path bound, which no makespan exceeds, else CP_ERR_OVERFLOW.
+ * One wavefront simulates one partition, one lane per device: k <= 64.
+ * Only enqueues work on `stream`.
+ *
+ *   assignments   device uint8, laid out per assign_layout (CP_ASSIGN_*)
+ *   speeds, bandwidth  host, as for cp_eval
+ *   policy        CP_POLICY_*
+ *   blevel        CP_POLICY_PCT: device ticks as cp_eval wrote them for these assignments
+ *                 (tick_dtype, b_layout = CP_OUT_*); values outside [0, 2^31) set
+ *                 CP_STATUS_B_OUT_OF_RANGE.  Ignored (may be NULL) under CP_POLICY_FIFO.
+ *   tie           CP_POLICY_FIFO: device int32 [n], a permutation of 0 .. n-1 (else
+ *                 CP_STATUS_BAD_TIE and makespan -1), or NULL for tie[v] = v.  Ignored under PCT.
+ *   workspace     device, 256-byte aligned, >= cp_simulate_workspace_bytes (28 bytes per
+ *                 vertex and partition under PCT, 20 under FIFO, plus the cost tables)
+ *   makespan_out  device int64 [batch]: the largest finish time; -1 for a partition with a
+ *                 device id >= k (CP_STATUS_BAD_DEVICE_ID)
+ *   start_out     device int32 [batch][n] (partition-major) or NULL: start time of every vertex
+ *   status_out    device int32: CP_STATUS_* flags after the stream has drained
+ * Errors: CP_ERR_NULL, CP_ERR_SIZE (k > 64), CP_ERR_ARG, CP_ERR_STATE, CP_ERR_SPEED,
+ * CP_ERR_BANDWIDTH, CP_ERR_OVERFLOW, CP_ERR_WORKSPACE, CP_ERR_ALLOC, CP_ERR_HIP.
+ */
+int cp_simulate_workspace_bytes(const cp_graph *g, int32_t batch, int32_t k, int policy, int with_tie,
+                                size_t *out_bytes);
+int cp_simulate(const cp_graph *g, int32_t batch, int32_t k,
+                const uint8_t *assignments, int assign_layout,
+                const int64_t *speeds, const int64_t *bandwidth, int policy,
+                const void *blevel, int tick_dtype, int b_layout, const int32_t *tie,
+                void *workspace, size_t workspace_bytes, void *stream,
+                int64_t *makespan_out, int32_t *start_out, int32_t *status_out);
 
 /*
  * The paper's Critical Path partitioning strategy (section 3.2.2), e.g. as the start of

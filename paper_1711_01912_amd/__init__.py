@@ -13,12 +13,15 @@ from .binding import (  # noqa: F401
     PLAN_AUTO,
     PLAN_RESIDENT_WINDOW,
     PLAN_WAVE_COLUMN,
+    POLICY_FIFO,
+    POLICY_PCT,
     cost_magic,
     cp_critical_path,
     cp_pct_order,
     cp_ranks,
     cp_search,
     cp_seed_partition,
+    cp_simulate,
     cp_validate,
     cp_eval,
     error_string,

@@ -29,6 +29,7 @@ EXPORTS = (
     "cp_eval_workspace_bytes", "cp_eval_choose_plan", "cp_eval", "cp_critical_path", "cp_ranks_workspace_bytes", "cp_ranks",
     "cp_pct_order_workspace_bytes", "cp_pct_order", "cp_validate",
     "cp_search_workspace_bytes", "cp_search", "cp_seed_workspace_bytes", "cp_seed_partition",
+    "cp_simulate_workspace_bytes", "cp_simulate",
     "cp_profile_create", "cp_profile_reset",
     "cp_profile_count", "cp_profile_read", "cp_profile_destroy", "cp_cost_magic",
     "cp_error_string",
@@ -110,6 +111,11 @@ def load_library():
     lib.cp_search.argtypes = [vp, C.c_int32, i64p, i64p, vp, C.c_int64, vp, C.c_int64, vp, C.c_int32, C.c_int32,
                               vp, C.c_size_t, vp, i64p, C.POINTER(C.c_int32), C.POINTER(C.c_int32),
                               C.POINTER(C.c_int64)]
+    lib.cp_simulate_workspace_bytes.restype = C.c_int
+    lib.cp_simulate_workspace_bytes.argtypes = [vp, C.c_int32, C.c_int32, C.c_int, C.c_int, C.POINTER(C.c_size_t)]
+    lib.cp_simulate.restype = C.c_int
+    lib.cp_simulate.argtypes = [vp, C.c_int32, C.c_int32, vp, C.c_int, i64p, i64p, C.c_int, vp, C.c_int, C.c_int,
+                                vp, vp, C.c_size_t, vp, vp, vp, vp]
     lib.cp_ranks_workspace_bytes.restype = C.c_int
     lib.cp_ranks_workspace_bytes.argtypes = [vp, C.POINTER(C.c_size_t)]
     lib.cp_ranks.restype = C.c_int
@@ -478,6 +484,61 @@ def cp_validate(assignments, k: int, pairs=None, pins=None, *, assign_layout=ASS
         if int(status.item()) & STATUS_BAD_CONSTRAINT:
             raise ValueError("a constraint names a vertex >= n or a device >= k")
     return valid, broken
+
+
+POLICY_FIFO, POLICY_PCT = 0, 1
+STATUS_BAD_TIE, STATUS_INCOMPLETE = 8, 16
+
+
+def cp_simulate(graph: CpGraph, assignments, speeds, bandwidth, policy, *, b=None, tie=None,
+                assign_layout=ASSIGN_PARTITION_MAJOR, b_layout=OUT_VERTEX_MAJOR, want_start=True,
+                workspace=None, stream=None, check_status=True):
+    """cp_simulate on torch tensors: ``assignments`` uint8 on the GPU, ``b`` cp_eval's b-level
+    output for them (POLICY_PCT), ``tie`` an int32 permutation [n] on the GPU or None
+    (POLICY_FIFO).  Returns (makespan int64 [batch], start int32 [batch][n] or None)."""
+    import torch
+    lib = load_library()
+    dev = assignments.device
+    n = graph.info["n"]
+    batch = int(assignments.shape[0] if assign_layout == ASSIGN_PARTITION_MAJOR else assignments.shape[1])
+    s = np.ascontiguousarray(speeds, dtype=np.int64)
+    bw = np.ascontiguousarray(bandwidth, dtype=np.int64)
+    k = int(s.shape[0])
+    if workspace is None:
+        need = C.c_size_t(0)
+        rc = lib.cp_simulate_workspace_bytes(graph._handle, batch, k, int(policy), int(tie is not None),
+                                             C.byref(need))
+        if rc:
+            raise CpError(rc, "cp_simulate_workspace_bytes")
+        workspace = torch.empty(need.value, dtype=torch.uint8, device=dev)
+    makespan = torch.empty(batch, dtype=torch.int64, device=dev)
+    start = torch.empty((batch, n), dtype=torch.int32, device=dev) if want_start else None
+    status = torch.empty(1, dtype=torch.int32, device=dev)
+    tick = 4
+    if b is not None:
+        tick = 4 if b.dtype == torch.int32 else 8
+    rc = lib.cp_simulate(graph._handle, batch, k, C.c_void_p(assignments.data_ptr()), int(assign_layout),
+                         _np_ptr(s, C.c_int64), _np_ptr(bw, C.c_int64), int(policy),
+                         C.c_void_p(b.data_ptr()) if b is not None else C.c_void_p(), tick, int(b_layout),
+                         C.c_void_p(tie.data_ptr()) if tie is not None else C.c_void_p(),
+                         C.c_void_p(workspace.data_ptr()), C.c_size_t(workspace.numel()), _stream_ptr(stream),
+                         C.c_void_p(makespan.data_ptr()),
+                         C.c_void_p(start.data_ptr()) if start is not None else C.c_void_p(),
+                         C.c_void_p(status.data_ptr()))
+    if rc:
+        raise CpError(rc, "cp_simulate")
+    if check_status:
+        torch.cuda.synchronize(dev)
+        st = int(status.item())
+        if st & STATUS_BAD_DEVICE_ID:
+            raise ValueError("assignments holds a device id >= k")
+        if st & STATUS_B_OUT_OF_RANGE:
+            raise ValueError("some b lies outside [0, 2^31)")
+        if st & STATUS_BAD_TIE:
+            raise ValueError("tie is not a permutation of 0 .. n-1")
+        if st & STATUS_INCOMPLETE:
+            raise RuntimeError("a partition ended with vertices that never started")
+    return makespan, start
 
 
 def cp_seed_partition(graph: CpGraph, speeds, *, stream=None):

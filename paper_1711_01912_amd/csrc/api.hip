@@ -2,7 +2,9 @@
 // cost-table upload and the order in which the stages are enqueued.
 #include <hip/hip_runtime.h>
 
+#include <climits>
 #include <cmath>
+#include <cstdint>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -155,6 +157,45 @@ int pct_plan(const cp_graph *g, int32_t batch, int32_t k, int64_t max_b, PctPlan
     out.counts_bytes = pct_counts_bytes(p.n, batch);
     out.total = 2 * out.keys_bytes + out.vals_bytes + out.counts_bytes;
     return CP_OK;
+}
+
+}  // namespace
+
+namespace {
+
+struct SimPlan {
+    size_t tab = 0, tie_inv = 0, per_i32 = 0, per_u64 = 0, total = 0;
+    bool pct = false, with_tie = false;
+};
+
+int sim_plan(const cp_graph *g, int32_t batch, int32_t k, int policy, bool with_tie, SimPlan &out) {
+    if (!g) return CP_ERR_NULL;
+    if (batch < 1 || k < 1 || k > kWave) return CP_ERR_SIZE;
+    if (policy != CP_POLICY_FIFO && policy != CP_POLICY_PCT) return CP_ERR_ARG;
+    const size_t n = (size_t)g->packed.n;
+    out.pct = policy == CP_POLICY_PCT;
+    out.with_tie = with_tie && !out.pct;
+    out.tab = tables_bytes(k);
+    out.tie_inv = out.with_tie ? align_up(n * 4) : 0;
+    out.per_i32 = align_up(n * (size_t)batch * 4);
+    out.per_u64 = align_up(n * (size_t)batch * 8);
+    out.total = out.tab + out.tie_inv + 3 * out.per_i32 + (out.pct ? 2 : 1) * out.per_u64;
+    return CP_OK;
+}
+
+template <typename WT>
+void min_weights(const Packed &p, uint64_t s_min, uint64_t &min_c, uint64_t &min_t, long double &sum_w) {
+    const WT *c = (const WT *)(p.blob.data() + p.c_off);
+    const WT *t = (const WT *)(p.blob.data() + p.col_b.wt_off);
+    min_c = UINT64_MAX;
+    min_t = UINT64_MAX;
+    sum_w = 0;
+    for (int32_t v = 0; v < p.n; ++v) {
+        const uint64_t cv = (uint64_t)c[v];
+        min_c = std::min<uint64_t>(min_c, cv);
+        sum_w += (long double)(cv / s_min + (cv % s_min != 0));
+    }
+    for (int64_t e = 0; e < p.m; ++e) min_t = std::min<uint64_t>(min_t, (uint64_t)t[e]);
 }
 
 }  // namespace
@@ -570,6 +611,111 @@ int cp_validate(int32_t n, int32_t batch, int32_t k, const uint8_t *assignments,
     const int64_t sv = assign_layout == CP_ASSIGN_PARTITION_MAJOR ? 1 : batch;
     return launch_validate(assignments, sp, sv, n, batch, k, num_pairs, pairs, num_pins, pins, valid_out,
                            violations_out, status_out, stream);
+}
+
+int cp_simulate_workspace_bytes(const cp_graph *g, int32_t batch, int32_t k, int policy, int with_tie,
+                                size_t *out_bytes) {
+    if (!out_bytes) return CP_ERR_NULL;
+    SimPlan plan;
+    int rc = sim_plan(g, batch, k, policy, with_tie != 0, plan);
+    if (rc) return rc;
+    *out_bytes = plan.total;
+    return CP_OK;
+}
+
+int cp_simulate(const cp_graph *g, int32_t batch, int32_t k,
+                const uint8_t *assignments, int assign_layout,
+                const int64_t *speeds, const int64_t *bandwidth, int policy,
+                const void *blevel, int tick_dtype, int b_layout, const int32_t *tie,
+                void *workspace, size_t workspace_bytes, void *stream,
+                int64_t *makespan_out, int32_t *start_out, int32_t *status_out) {
+    SimPlan plan;
+    int rc = sim_plan(g, batch, k, policy, tie != nullptr, plan);
+    if (rc) return rc;
+    if (assign_layout != CP_ASSIGN_PARTITION_MAJOR && assign_layout != CP_ASSIGN_VERTEX_MAJOR) return CP_ERR_ARG;
+    if (!assignments || !speeds || !bandwidth || !workspace || !makespan_out || !status_out) return CP_ERR_NULL;
+    if (plan.pct) {
+        if (!blevel) return CP_ERR_NULL;
+        if (b_layout != CP_OUT_VERTEX_MAJOR && b_layout != CP_OUT_PARTITION_MAJOR) return CP_ERR_ARG;
+        if (tick_dtype != CP_TICK_I32 && tick_dtype != CP_TICK_I64) return CP_ERR_ARG;
+    }
+    if (!g->device_blob) return CP_ERR_STATE;
+    const Packed &p = g->packed;
+    if (((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < plan.total) return CP_ERR_WORKSPACE;
+    CostTables tabs;
+    try {
+        rc = build_cost_tables(k, speeds, bandwidth, p.narrow, p.info.max_c, p.info.max_t, tabs);
+    } catch (const std::bad_alloc &) {
+        rc = CP_ERR_ALLOC;
+    }
+    if (rc) return rc;
+
+    // every vertex takes a tick or more; the shortest execution and transfer times give the
+    // span of decision times that may be served together.  No time may reach 2^31: at every
+    // moment before the end either some device is busy (at most the summed execution times in
+    // all) or every device waits for a transfer on one chain of dependent vertices (at most
+    // the longest path's transfers, which the raw path bound covers).
+    int64_t s_min = speeds[0], s_max = speeds[0], b_max = 1;
+    for (int i = 0; i < k; ++i) {
+        s_min = std::min(s_min, speeds[i]);
+        s_max = std::max(s_max, speeds[i]);
+        for (int j = 0; j < k; ++j)
+            if (i != j) b_max = std::max(b_max, bandwidth[(size_t)i * k + j]);
+    }
+    uint64_t min_c = 0, min_t = 0;
+    long double sum_w = 0;
+    if (p.narrow) min_weights<uint32_t>(p, (uint64_t)s_min, min_c, min_t, sum_w);
+    else min_weights<int64_t>(p, (uint64_t)s_min, min_c, min_t, sum_w);
+    if (min_c < 1) return CP_ERR_ARG;
+    if (sum_w + (long double)p.info.raw_path_bound >= 2147483647.0L) return CP_ERR_OVERFLOW;
+    auto ceil_div = [](uint64_t a, uint64_t d) { return a / d + (a % d != 0); };
+    const uint64_t w_min = ceil_div(min_c, (uint64_t)s_max);
+    const uint64_t x_min = (p.m == 0 || min_t == 0) ? 0 : ceil_div(min_t, (uint64_t)b_max);
+    const uint64_t window = std::min<uint64_t>(w_min + x_min - 1, 1u << 30);
+
+    hipStream_t st = (hipStream_t)stream;
+    rc = launch_clear(nullptr, 1, status_out, stream);
+    if (rc) return rc;
+    uint8_t *ws = (uint8_t *)workspace;
+    const void *tab_src = tabs.magic_ok ? (const void *)tabs.magic.data() : (const void *)tabs.divisor.data();
+    rc = stage_and_copy(tab_src, table_entries(k) * 8, ws, st);
+    if (rc) return rc;
+    SimulateLaunch s;
+    s.blob = (const uint8_t *)g->device_blob;
+    s.succ = &p.col_b;
+    s.pred = &p.col_t;
+    s.c_off = p.c_off;
+    s.magic = tabs.magic_ok;
+    s.narrow = p.narrow;
+    s.pct = plan.pct;
+    s.n = p.n; s.P = batch; s.k = k;
+    s.window = (uint32_t)window;
+    s.assign = assignments;
+    if (assign_layout == CP_ASSIGN_PARTITION_MAJOR) { s.a_stride_p = p.n; s.a_stride_v = 1; }
+    else { s.a_stride_p = 1; s.a_stride_v = batch; }
+    if (plan.pct) {
+        s.b = blevel;
+        s.b_bytes = tick_dtype;
+        if (b_layout == CP_OUT_PARTITION_MAJOR) { s.b_sv = 1; s.b_sq = p.n; }
+        else { s.b_sv = batch; s.b_sq = 1; }
+    }
+    s.edge_tab = ws;
+    s.vert_tab = ws + 2 * (size_t)k * k * 8;
+    uint8_t *at = ws + plan.tab;
+    if (plan.with_tie) {
+        s.tie = tie;
+        s.tie_inv = (int32_t *)at;
+        at += plan.tie_inv;
+    }
+    s.ready = (int32_t *)at; at += plan.per_i32;
+    s.need = (int32_t *)at; at += plan.per_i32;
+    s.inbox = (int32_t *)at; at += plan.per_i32;
+    s.pending = (uint64_t *)at; at += plan.per_u64;
+    if (plan.pct) { s.available = (uint64_t *)at; at += plan.per_u64; }
+    s.makespan = makespan_out;
+    s.start = start_out;
+    s.status = status_out;
+    return launch_simulate(s, stream);
 }
 
 int cp_ranks_workspace_bytes(const cp_graph *g, size_t *out_bytes) {

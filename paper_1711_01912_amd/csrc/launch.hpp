@@ -79,6 +79,31 @@ size_t pct_counts_bytes(int32_t n, int32_t P);
 int32_t pct_sort_tiles(int32_t n);
 int launch_pct_order(const PctOrderLaunch &s, void *stream);
 
+// List-scheduling simulation (sections 4, 4.1, 5.1), one wavefront per partition.
+struct SimulateLaunch {
+    const uint8_t *blob = nullptr;
+    const ColumnDir *succ = nullptr;    // successor CSR
+    const ColumnDir *pred = nullptr;    // predecessor CSR (row bounds only)
+    size_t c_off = 0;
+    bool magic = false, narrow = false, pct = false;
+    int32_t n = 0, P = 0, k = 0;
+    uint32_t window = 0;                // shortest execution time + shortest transfer time - 1
+    const uint8_t *assign = nullptr;
+    int64_t a_stride_p = 0, a_stride_v = 0;
+    const void *b = nullptr;
+    int64_t b_sv = 0, b_sq = 0;
+    int b_bytes = 4;
+    const int32_t *tie = nullptr;
+    int32_t *tie_inv = nullptr;         // [n] scratch when tie is given
+    const void *edge_tab = nullptr, *vert_tab = nullptr;
+    int32_t *ready = nullptr, *need = nullptr, *inbox = nullptr;   // [P][n] each
+    uint64_t *pending = nullptr, *available = nullptr;             // [P][n] each (available: PCT only)
+    int64_t *makespan = nullptr;
+    int32_t *start = nullptr;
+    int32_t *status = nullptr;
+};
+int launch_simulate(const SimulateLaunch &s, void *stream);
+
 int launch_validate(const uint8_t *assign, int64_t a_stride_p, int64_t a_stride_v, int32_t n, int32_t P, int32_t k,
                     int64_t num_pairs, const int32_t *pairs, int64_t num_pins, const int32_t *pins,
                     uint8_t *valid, int32_t *violations, int32_t *status, void *stream);

@@ -1,0 +1,348 @@
+// List-scheduling simulation of one iteration for a batch of partitions: the paper's
+// scheduling criteria (section 4, (1)-(6)) with its PCT rule (section 4.1) or the FIFO
+// baseline (section 5.1), on the cost model of section 2 in integer ticks.  The result is
+// the start time of every vertex and the makespan, the quantity the paper's evaluation
+// plots (section 5).
+//
+// One wavefront simulates one partition; lane d is device d.  A device keeps the vertices
+// whose predecessors have all started -- their ready time is final by then -- in a
+// min-heap keyed by ready time ("pending"); under PCT the ones that are executable at the
+// device's decision time move on to a second heap keyed by descending b ("available").
+// Devices only interact through tensors that arrive: a vertex that starts at time T on
+// one device reaches another device no earlier than T + (shortest execution time) +
+// (shortest transfer time).  So with T_min the earliest decision time over all devices,
+// every device whose decision time lies less than that sum after T_min already knows all
+// it needs, and those lanes decide in the same step.  A lane that starts a vertex lowers
+// the open-input count of each successor and raises its ready time; the lane that takes
+// the last open input hands the successor to its owner's inbox, which the owner drains at
+// the top of its next step.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "cpeval_internal.hpp"
+#include "launch.hpp"
+
+namespace cpeval {
+
+namespace {
+
+constexpr uint32_t kNever = 0xffffffffu;
+
+__device__ __forceinline__ uint32_t sim_magic_div(uint32_t a, Magic mg) {
+    uint32_t nn = a + mg.dm1;
+    return (uint32_t)(((uint64_t)nn * mg.mul + nn) >> 32);
+}
+
+__device__ __forceinline__ uint64_t sim_plain_div(uint64_t a, uint64_t d) {
+    return d ? (a + d - 1) / d : 0;
+}
+
+// All lanes of a partition sit in one wavefront, so everything they exchange passes through
+// one compute unit's vector L1 and one L2; no wider scope is ever needed (a release at device
+// scope would write the L2 back on every step).  Ready times and open-input counts are only
+// touched by read-modify-write atomics, which execute in the L2: a ready time is read back
+// with an atomic too, never through the L1, which those atomics leave stale.  Inbox slots
+// are written once with ordinary stores and read afterwards by another lane of the wavefront.
+__device__ __forceinline__ int32_t l2_read(int32_t *p) {
+    // times are never negative, so the maximum with 0 changes nothing; unlike "add 0" it is
+    // not an operation the compiler may turn into a load
+    return __hip_atomic_fetch_max(p, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+__device__ __forceinline__ int32_t inbox_load(const int32_t *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+}
+__device__ __forceinline__ void inbox_store(int32_t *p, int32_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+}
+// Every memory operation of the wavefront issued so far has completed.
+__device__ __forceinline__ void step_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+}
+
+// Binary min-heaps of 64-bit keys; a lane's heap is touched by that lane only.  A heap
+// never holds more keys than its device has vertices, so 32 levels bound every loop.
+__device__ __forceinline__ void heap_push(uint64_t *h, int32_t &size, uint64_t key) {
+    int32_t i = size++;
+    for (int depth = 0; depth < 32 && i > 0; ++depth) {
+        const int32_t up = (i - 1) >> 1;
+        const uint64_t uk = h[up];
+        if (uk <= key) break;
+        h[i] = uk;
+        i = up;
+    }
+    h[i] = key;
+}
+
+__device__ __forceinline__ uint64_t heap_pop(uint64_t *h, int32_t &size) {
+    const uint64_t top = h[0];
+    const int32_t left = --size;
+    if (left > 0) {
+        const uint64_t last = h[left];
+        int32_t i = 0;
+        for (int depth = 0; depth < 32; ++depth) {
+            int32_t ch = 2 * i + 1;
+            if (ch >= left) break;
+            uint64_t ck = h[ch];
+            if (ch + 1 < left) {
+                const uint64_t c2 = h[ch + 1];
+                if (c2 < ck) { ck = c2; ++ch; }
+            }
+            if (last <= ck) break;
+            h[i] = ck;
+            i = ch;
+        }
+        h[i] = last;
+    }
+    return top;
+}
+
+struct SimArgs {
+    const int32_t *ptr;        // successor CSR over original ids
+    const int32_t *idx;
+    const void *wt;            // t(e) in that order
+    const void *c;
+    const int32_t *pred_ptr;   // predecessor CSR row bounds: the in-degrees
+    const uint8_t *assign;
+    int64_t a_stride_p, a_stride_v;
+    const void *b;             // PCT: ticks, b(v, q) at v * b_sv + q * b_sq
+    int64_t b_sv, b_sq;
+    int32_t b_bytes;
+    const int32_t *tie;        // FIFO: rank of a vertex among equal ready times, null = its number
+    const int32_t *tie_inv;    //       vertex of a rank
+    const void *edge_tab;      // row = device of the edge's source vertex
+    const void *vert_tab;
+    int32_t *ready;            // [P][n] latest arrival so far
+    int32_t *need;             // [P][n] inputs whose producer has not started
+    int32_t *inbox;            // [P][n], one segment per device
+    uint64_t *pending;         // [P][n], one segment per device
+    uint64_t *available;       // [P][n], PCT only
+    long long *makespan;       // [P]
+    int32_t *start;            // [P][n] or null
+    int32_t *status;
+    int32_t n, P, k;
+    uint32_t window;           // lanes with T - T_min <= window decide together
+};
+
+template <typename WT, bool MAGIC, bool PCT>
+__global__ __launch_bounds__(64) void simulate_kernel(SimArgs a) {
+    __shared__ int32_t count[64];      // vertices per device, then vertices handed to the device so far
+    __shared__ int32_t seg[64];        // first slot of the device's segment
+    const int lane = threadIdx.x;
+    const int32_t q = blockIdx.x;
+    const int32_t n = a.n, k = a.k;
+    const uint8_t *row = a.assign + (int64_t)q * a.a_stride_p;
+    const int64_t asv = a.a_stride_v;
+    const WT *wt = (const WT *)a.wt;
+    const WT *cw = (const WT *)a.c;
+    const Magic *etab_m = (const Magic *)a.edge_tab, *vtab_m = (const Magic *)a.vert_tab;
+    const int64_t *etab_g = (const int64_t *)a.edge_tab, *vtab_g = (const int64_t *)a.vert_tab;
+    int32_t *ready = a.ready + (int64_t)q * n;
+    int32_t *need = a.need + (int64_t)q * n;
+    int32_t *start = a.start ? a.start + (int64_t)q * n : nullptr;
+
+    if (*a.status & CP_STATUS_BAD_TIE) {          // set by the check of the tie ranks, same stream
+        if (lane == 0) a.makespan[q] = -1;
+        return;
+    }
+
+    // ---- set-up: vertices per device, state of every vertex
+    count[lane] = 0;
+    __syncthreads();
+    bool bad = false;
+    for (int32_t v = lane; v < n; v += 64) {
+        const uint32_t d = row[(int64_t)v * asv];
+        if (d >= (uint32_t)k) { bad = true; continue; }
+        atomicAdd(&count[d], 1);
+        ready[v] = 0;
+        need[v] = a.pred_ptr[v + 1] - a.pred_ptr[v];
+    }
+    if (__any(bad)) {
+        if (lane == 0) {
+            atomicOr(a.status, CP_STATUS_BAD_DEVICE_ID);
+            a.makespan[q] = -1;
+        }
+        return;
+    }
+    __syncthreads();
+    {
+        const int32_t mine = count[lane];
+        int32_t incl = mine;
+        for (int off = 1; off < 64; off <<= 1) {
+            const int32_t other = __shfl_up(incl, off);
+            if (lane >= off) incl += other;
+        }
+        __syncthreads();
+        seg[lane] = incl - mine;
+        count[lane] = 0;
+    }
+    step_fence();
+    int32_t *inbox = a.inbox + (int64_t)q * n;
+    for (int32_t v = lane; v < n; v += 64) {
+        if (a.pred_ptr[v + 1] == a.pred_ptr[v]) {
+            const uint32_t d = row[(int64_t)v * asv];
+            const int32_t pos = atomicAdd(&count[d], 1);
+            inbox_store(inbox + seg[d] + pos, v);
+        }
+    }
+    step_fence();
+
+    // ---- the event loop
+    const int32_t base = seg[lane];
+    uint64_t *hp = a.pending + (int64_t)q * n + base;
+    uint64_t *ha = PCT ? a.available + (int64_t)q * n + base : nullptr;
+    const int32_t *my_inbox = inbox + base;
+    const int64_t bsv = a.b_sv;
+    const uint8_t *bq = (const uint8_t *)a.b + (PCT ? (int64_t)q * a.b_sq * a.b_bytes : 0);
+    int32_t np = 0, na = 0, taken = 0, done = 0;
+    uint32_t free_at = 0;
+    bool b_bad = false;
+    // every step with work left starts at least one vertex, so n + 1 steps always suffice
+    for (int64_t step = 0; step <= n; ++step) {
+        {   // vertices handed to this device since its last step
+            const int32_t have = count[lane];
+            for (; taken < have; ++taken) {
+                const int32_t z = inbox_load(my_inbox + taken);
+                const uint32_t rz = (uint32_t)l2_read(ready + z);
+                const uint32_t low = PCT ? (uint32_t)z : (a.tie ? (uint32_t)a.tie[z] : (uint32_t)z);
+                heap_push(hp, np, ((uint64_t)rz << 32) | low);
+            }
+        }
+        uint32_t T = kNever;
+        if (PCT && na > 0) T = free_at;
+        else if (np > 0) T = max(free_at, (uint32_t)(hp[0] >> 32));
+        uint32_t tmin = T;
+        for (int off = 32; off > 0; off >>= 1) tmin = min(tmin, (uint32_t)__shfl_xor((int)tmin, off));
+        if (tmin == kNever) break;
+        if (T != kNever && T - tmin <= a.window) {
+            int32_t v;
+            if (PCT) {
+                for (int32_t moved = 0; np > 0 && (uint32_t)(hp[0] >> 32) <= T && moved < n; ++moved) {
+                    const int32_t z = (int32_t)(uint32_t)heap_pop(hp, np);
+                    long long bz = a.b_bytes == 4 ? (long long)*(const int32_t *)(bq + (int64_t)z * bsv * 4)
+                                                  : *(const long long *)(bq + (int64_t)z * bsv * 8);
+                    if (bz < 0 || bz > 0x7fffffffll) { b_bad = true; bz = 0; }
+                    heap_push(ha, na, ((uint64_t)(0x7fffffffu - (uint32_t)bz) << 32) | (uint32_t)z);
+                }
+                v = (int32_t)(uint32_t)heap_pop(ha, na);
+            } else {
+                const uint32_t low = (uint32_t)heap_pop(hp, np);
+                v = a.tie_inv ? a.tie_inv[low] : (int32_t)low;
+            }
+            if (start) start[v] = (int32_t)T;
+            ++done;
+            const WT cv = cw[v];
+            const uint32_t w = MAGIC ? sim_magic_div((uint32_t)cv, vtab_m[lane])
+                                     : (uint32_t)sim_plain_div((uint64_t)cv, (uint64_t)vtab_g[lane]);
+            free_at = T + w;
+            const int32_t e1 = a.ptr[v + 1];
+            for (int32_t e = a.ptr[v]; e < e1; ++e) {
+                const int32_t z = a.idx[e];
+                const WT te = wt[e];
+                const uint32_t dz = row[(int64_t)z * asv];
+                const uint32_t x = MAGIC ? sim_magic_div((uint32_t)te, etab_m[lane * k + dz])
+                                         : (uint32_t)sim_plain_div((uint64_t)te, (uint64_t)etab_g[lane * k + dz]);
+                __hip_atomic_fetch_max(ready + z, (int32_t)(free_at + x), __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_WORKGROUP);
+                const int32_t before = __hip_atomic_fetch_add(need + z, -1, __ATOMIC_RELAXED,
+                                                              __HIP_MEMORY_SCOPE_WORKGROUP);
+                if (before == 1) {
+                    const int32_t pos = atomicAdd(&count[dz], 1);
+                    inbox_store(inbox + seg[dz] + pos, z);
+                }
+            }
+        }
+        step_fence();     // everything this step wrote is in place before the next step reads it
+    }
+    uint32_t last = free_at;
+    int32_t total = done;
+    for (int off = 32; off > 0; off >>= 1) {
+        last = max(last, (uint32_t)__shfl_xor((int)last, off));
+        total += __shfl_xor(total, off);
+    }
+    if (__any(b_bad) && lane == 0) atomicOr(a.status, CP_STATUS_B_OUT_OF_RANGE);
+    if (lane == 0) {
+        if (total != n) {
+            atomicOr(a.status, CP_STATUS_INCOMPLETE);
+            a.makespan[q] = -1;
+        } else {
+            a.makespan[q] = (long long)last;
+        }
+    }
+}
+
+// tie_inv[tie[v]] = v; a rank outside [0, n) is reported.  tie_inv starts at -1.
+__global__ __launch_bounds__(256) void tie_scatter_kernel(const int32_t *tie, int32_t n, int32_t *tie_inv,
+                                                          int32_t *status) {
+    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (v >= n) return;
+    const int32_t r = tie[v];
+    if (r < 0 || r >= n) atomicOr(status, CP_STATUS_BAD_TIE);
+    else tie_inv[r] = (int32_t)v;
+}
+
+// A rank nobody has means another rank was given twice: not a permutation.
+__global__ __launch_bounds__(256) void tie_check_kernel(const int32_t *tie_inv, int32_t n, int32_t *status) {
+    const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (r < n && tie_inv[r] < 0) atomicOr(status, CP_STATUS_BAD_TIE);
+}
+
+__global__ __launch_bounds__(256) void fill_minus_one_kernel(int32_t *dst, int32_t n) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) dst[i] = -1;
+}
+
+}  // namespace
+
+int launch_simulate(const SimulateLaunch &s, void *stream) {
+    hipStream_t st = (hipStream_t)stream;
+    if (s.n < 1 || s.P < 1 || s.k < 1 || s.k > kWave) return CP_ERR_SIZE;
+    if (s.tie) {
+        const dim3 grid((unsigned)((s.n + 255) / 256)), block(256);
+        hipLaunchKernelGGL(fill_minus_one_kernel, grid, block, 0, st, s.tie_inv, s.n);
+        hipLaunchKernelGGL(tie_scatter_kernel, grid, block, 0, st, s.tie, s.n, s.tie_inv, s.status);
+        hipLaunchKernelGGL(tie_check_kernel, grid, block, 0, st, s.tie_inv, s.n, s.status);
+    }
+    SimArgs a{};
+    a.ptr = (const int32_t *)(s.blob + s.succ->ptr_off);
+    a.idx = (const int32_t *)(s.blob + s.succ->idx_off);
+    a.wt = s.blob + s.succ->wt_off;
+    a.c = s.blob + s.c_off;
+    a.pred_ptr = (const int32_t *)(s.blob + s.pred->ptr_off);
+    a.assign = s.assign;
+    a.a_stride_p = s.a_stride_p;
+    a.a_stride_v = s.a_stride_v;
+    a.b = s.b;
+    a.b_sv = s.b_sv;
+    a.b_sq = s.b_sq;
+    a.b_bytes = s.b_bytes;
+    a.tie = s.tie;
+    a.tie_inv = s.tie ? s.tie_inv : nullptr;
+    a.edge_tab = s.edge_tab;
+    a.vert_tab = s.vert_tab;
+    a.ready = s.ready;
+    a.need = s.need;
+    a.inbox = s.inbox;
+    a.pending = s.pending;
+    a.available = s.available;
+    a.makespan = (long long *)s.makespan;
+    a.start = s.start;
+    a.status = s.status;
+    a.n = s.n; a.P = s.P; a.k = s.k;
+    a.window = s.window;
+    const dim3 grid((unsigned)s.P), block(64);
+#define CP_SIM(WT, MAGIC)                                                                      \
+    do {                                                                                       \
+        if (s.pct) hipLaunchKernelGGL((simulate_kernel<WT, MAGIC, true>), grid, block, 0, st, a);  \
+        else hipLaunchKernelGGL((simulate_kernel<WT, MAGIC, false>), grid, block, 0, st, a);       \
+    } while (0)
+    if (s.magic) CP_SIM(uint32_t, true);
+    else if (s.narrow) CP_SIM(uint32_t, false);
+    else CP_SIM(int64_t, false);
+#undef CP_SIM
+    return hipGetLastError() == hipSuccess ? CP_OK : CP_ERR_HIP;
+}
+
+}  // namespace cpeval

@@ -297,6 +297,48 @@ def test_consumer_entry_points_check_their_arguments(lib):
     g.close()
 
 
+def test_simulate_checks_its_arguments(lib):
+    """cp_simulate rejects bad arguments before touching the GPU."""
+    w = make_workload("tiny")
+    g = cpe.CpGraph.from_workload(w)
+    s = np.array([1, 2], dtype=np.int64)
+    B = np.array([[1, 10], [10, 1]], dtype=np.int64)
+    dummy = C.c_void_p(256)
+    null = C.c_void_p()
+    i64p = C.POINTER(C.c_int64)
+    sp, bp = s.ctypes.data_as(i64p), B.ctypes.data_as(i64p)
+    n = w.n
+    need = C.c_size_t(0)
+    assert lib.cp_simulate_workspace_bytes(g._handle, 16, 2, 1, 0, C.byref(need)) == 0
+    per_i32 = -(-16 * n * 4 // 256) * 256
+    per_u64 = -(-16 * n * 8 // 256) * 256
+    tab = -(-(2 * 2 * 2 + 2) * 8 // 256) * 256
+    assert need.value == tab + 3 * per_i32 + 2 * per_u64            # PCT: two heaps
+    assert lib.cp_simulate_workspace_bytes(g._handle, 16, 2, 0, 1, C.byref(need)) == 0
+    assert need.value == tab + -(-n * 4 // 256) * 256 + 3 * per_i32 + per_u64   # FIFO with tie ranks
+    assert lib.cp_simulate_workspace_bytes(g._handle, 16, 65, 0, 0, C.byref(need)) == -2
+    assert lib.cp_simulate_workspace_bytes(g._handle, 0, 2, 0, 0, C.byref(need)) == -2
+    assert lib.cp_simulate_workspace_bytes(g._handle, 16, 2, 2, 0, C.byref(need)) == -12
+    assert lib.cp_simulate_workspace_bytes(g._handle, 16, 2, 0, 0, None) == -1
+
+    def sim(batch=4, k=2, assign=dummy, layout=0, policy=1, b=dummy, tick=4, b_layout=0, tie=null, ws=dummy,
+            out=dummy, status=dummy):
+        return lib.cp_simulate(g._handle, batch, k, assign, layout, sp, bp, policy, b, tick, b_layout, tie, ws,
+                               1 << 24, None, out, null, status)
+
+    assert sim(batch=0) == -2
+    assert sim(k=65) == -2
+    assert sim(policy=7) == -12
+    assert sim(layout=2) == -12
+    assert sim(b=null) == -1                 # PCT needs b
+    assert sim(b_layout=3) == -12
+    assert sim(tick=5) == -12
+    assert sim(out=null) == -1
+    assert sim(policy=0, b=null) == -11      # FIFO needs no b; the graph is not uploaded
+    assert sim() == -11
+    g.close()
+
+
 def test_packing_deep_graphs_with_long_spans(lib):
     """Deep graphs whose edges span the whole depth are packed for the resident-window plan
     with far reads: a short ring plus a bounded number of far reads per tick."""

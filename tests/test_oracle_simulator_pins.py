@@ -312,3 +312,22 @@ def test_paper_like_workload_orders_the_strategies(oracle):
     a = wl.assignments
     w = -(-c[None, :] // wl.speeds[a])
     assert (got["makespan"] <= w.sum(axis=1) + ev["cp"]).all()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_makespan_never_exceeds_busy_time_plus_the_longest_transfer_chain(oracle, seed):
+    """At any moment before the end some device is busy, or all of them wait for a transfer on one
+    chain of dependent vertices: makespan <= sum of w + the largest sum of x along a path."""
+    csr, c, rng = _dag(200 + seed, 12, 9, deg_hi=4, span_hi=4, tmax=5000, cmax=20)
+    n, k = csr["n"], 5
+    s = rng.integers(1, 4, size=k)
+    B = rng.integers(1, 6, size=(k, k))
+    a = rng.integers(0, k, size=(4, n)).astype(np.uint8)
+    ev = _b(oracle, csr, c, s, B, a)
+    chain = oracle.evaluate(n, csr["succ_ptr"], csr["succ_idx"], csr["succ_t"], np.zeros(n, dtype=np.int64), s, B, a,
+                            want=("cp",))["cp"]
+    busy = (-(-c[None, :] // s[a])).sum(axis=1)
+    for policy in (FIFO, PCT):
+        got = _sim(oracle, csr, c, s, B, a, policy, b=ev["b"])["makespan"]
+        assert (got <= busy + chain).all()
+        assert (got >= ev["cp"]).all()
