@@ -71,7 +71,8 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=128, help="partitions the oracle is timed on (0 = skip)")
     ap.add_argument("--extras", action="store_true",
                     help="after the timed steps also time the consumers of the result (priority lists, one "
-                         "critical path per partition) and report them under 'extras'")
+                         "critical path per partition, the list-scheduling simulation) and report them "
+                         "under 'extras'")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB (a known-size kernel to scale "
                          "hardware byte counters against)")
@@ -183,6 +184,35 @@ def main():
         ms = timed(lambda: cpe.cp_critical_path(g, a, w.speeds, w.bandwidth, out["b"], out["cp"],
                                                 b_layout=b_layout, check_status=False))
         extras["critical_path"] = {"ms": ms}
+        if w.k <= 64 and int(w.c.min()) >= 1:
+            # the list-scheduling simulation under both policies, and the oracle's on a few partitions
+            from oracle import cp_oracle
+            sim_ws = {}
+            for policy, name in ((cpe.POLICY_PCT, "pct"), (cpe.POLICY_FIFO, "fifo")):
+                kwargs = dict(b=out["b"], b_layout=b_layout) if policy == cpe.POLICY_PCT else {}
+                res = {}
+
+                def run():
+                    res["makespan"], _ = cpe.cp_simulate(g, a, w.speeds, w.bandwidth, policy, want_start=False,
+                                                         check_status=False, **kwargs)
+                ms = timed(run, reps=1 if n * P > 50_000_000 else 3)
+                sample = min(16, P)
+                b_ref = None
+                if policy == cpe.POLICY_PCT:
+                    rows_b = out["b"][:sample] if b_layout == cpe.OUT_PARTITION_MAJOR else out["b"][:, :sample].T
+                    b_ref = rows_b.cpu().numpy().astype(np.int64)
+                c0 = time.perf_counter()
+                ref = cp_oracle.simulate(w.n, w.succ_ptr, w.succ_idx, w.succ_t, w.c, w.speeds, w.bandwidth,
+                                         w.assignments[:sample], policy, b=b_ref, want_start=False, threads=16)
+                c1 = time.perf_counter()
+                assert np.array_equal(ref["makespan"], res["makespan"][:sample].cpu().numpy()), \
+                    "GPU and oracle disagree on the makespan"
+                extras["simulate_" + name] = {
+                    "ms": ms, "vertex_starts_per_s": n * P / (ms * 1e-3),
+                    "mean_makespan": float(res["makespan"].double().mean().item()),
+                    "mean_cp": float(out["cp"].double().mean().item()),
+                    "oracle_vertex_starts_per_s": n * sample / (c1 - c0), "oracle_threads": ref["threads"],
+                    "oracle_sample": sample}
 
     cpu = None
     if args.cpu_sample > 0:

@@ -412,7 +412,24 @@ def _comm_heavy(seed, P=1024, levels=20, width=10000, hub_fraction=0.01, hub_deg
                    _uniform_assignments(arng, P, n, k), hubs=int(len(hubs)))
 
 
+def _paper_scale(seed, P=4096, levels=251, width=21, k=50):
+    """The size of the largest graph of the paper's evaluation (Table 1: 5,271 vertices, 9,214
+    edges, average degree 1.75) on the simulated cluster of section 5.1: 50 devices, speeds
+    10..100, transfer rates 10..60, tensor sizes 1..100, vertex operations 1..100, all uniform.
+    The graph itself is a random layered DAG, not the paper's network."""
+    rng = np.random.default_rng(seed)
+    n, level, src, dst = random_layered_dag(rng, [width] * levels, 1, 3, 3, overflow="resample")
+    t = rng.integers(1, 101, size=len(src))
+    c = rng.integers(1, 101, size=n)
+    speeds = rng.integers(10, 101, size=k)
+    bandwidth = rng.integers(10, 61, size=(k, k))
+    csr = build_csr(n, src, dst, t, level)
+    arng = np.random.default_rng(seed + 1000)
+    return _finish("paper_scale", csr, c, k, speeds, bandwidth, _uniform_assignments(arng, P, n, k))
+
+
 _BUILDERS = {
+    "paper_scale": (6, _paper_scale),
     "tiny": (1, _tiny),
     "mlp": (2, _mlp),
     "inception": (3, _inception),
@@ -422,7 +439,7 @@ _BUILDERS = {
 
 
 def make_workload(name: str, **overrides) -> Workload:
-    """Build one of the five named workloads.  Keyword overrides (P, levels,
+    """Build one of the five named workloads (or "paper_scale", the scheduling simulation's own size).  Keyword overrides (P, levels,
     width, layers, shards, modules, groups, ...) give scaled-down variants of the
     same recipe for tests; `seed` replaces the default seed."""
     idx, fn = _BUILDERS[name]
