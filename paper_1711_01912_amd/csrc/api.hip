@@ -690,6 +690,9 @@ int cp_simulate(const cp_graph *g, int32_t batch, int32_t k,
     s.pct = plan.pct;
     s.n = p.n; s.P = batch; s.k = k;
     s.window = (uint32_t)window;
+    // One partition per wavefront until the batch alone fills the GPU several times over (8,192
+    // wavefronts are 8 per SIMD); past that, partitions with few devices share a wavefront.
+    s.groups = (int32_t)std::max<int64_t>(1, std::min<int64_t>(kWave / k, batch / 8192));
     s.assign = assignments;
     if (assign_layout == CP_ASSIGN_PARTITION_MAJOR) { s.a_stride_p = p.n; s.a_stride_v = 1; }
     else { s.a_stride_p = 1; s.a_stride_v = batch; }

@@ -88,6 +88,7 @@ struct SimulateLaunch {
     bool magic = false, narrow = false, pct = false;
     int32_t n = 0, P = 0, k = 0;
     uint32_t window = 0;                // shortest execution time + shortest transfer time - 1
+    int32_t groups = 1;                 // partitions per wavefront (at most 64 / k)
     const uint8_t *assign = nullptr;
     int64_t a_stride_p = 0, a_stride_v = 0;
     const void *b = nullptr;

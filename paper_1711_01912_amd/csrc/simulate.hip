@@ -4,7 +4,8 @@
 // the start time of every vertex and the makespan, the quantity the paper's evaluation
 // plots (section 5).
 //
-// One wavefront simulates one partition; lane d is device d.  A device keeps the vertices
+// One wavefront simulates one partition, lane d being device d; with 32 devices or fewer it
+// simulates 64 / k partitions side by side, k lanes each.  A device keeps the vertices
 // whose predecessors have all started -- their ready time is final by then -- in a
 // min-heap keyed by ready time ("pending"); under PCT the ones that are executable at the
 // device's decision time move on to a second heap keyed by descending b ("available").
@@ -18,6 +19,7 @@
 // the top of its next step.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdint>
 
 #include "cpeval_internal.hpp"
@@ -123,6 +125,7 @@ struct SimArgs {
     int32_t *start;            // [P][n] or null
     int32_t *status;
     int32_t n, P, k;
+    int32_t groups;            // partitions per wavefront, <= 64 / k
     uint32_t window;           // lanes with T - T_min <= window decide together
 };
 
@@ -130,78 +133,93 @@ template <typename WT, bool MAGIC, bool PCT>
 __global__ __launch_bounds__(64) void simulate_kernel(SimArgs a) {
     __shared__ int32_t count[64];      // vertices per device, then vertices handed to the device so far
     __shared__ int32_t seg[64];        // first slot of the device's segment
+    __shared__ int32_t gbad[64];       // per group: a device id >= k was seen
     const int lane = threadIdx.x;
-    const int32_t q = blockIdx.x;
     const int32_t n = a.n, k = a.k;
-    const uint8_t *row = a.assign + (int64_t)q * a.a_stride_p;
+    // with k <= 32 devices a wavefront can hold up to 64 / k partitions side by side: group g =
+    // lanes g*k .. g*k + k-1.  Lanes past the last group, and groups past the batch, idle.
+    const int groups = a.groups;
+    const int grp = lane / k, dev = lane - grp * k;
+    const int first = grp * k;
+    const int64_t q = (int64_t)blockIdx.x * groups + grp;
+    bool alive = grp < groups && q < a.P;
+    const int64_t qq = alive ? q : 0;          // idle lanes never load or store, but keep their pointers in range
+    const uint8_t *row = a.assign + qq * a.a_stride_p;
     const int64_t asv = a.a_stride_v;
     const WT *wt = (const WT *)a.wt;
     const WT *cw = (const WT *)a.c;
     const Magic *etab_m = (const Magic *)a.edge_tab, *vtab_m = (const Magic *)a.vert_tab;
     const int64_t *etab_g = (const int64_t *)a.edge_tab, *vtab_g = (const int64_t *)a.vert_tab;
-    int32_t *ready = a.ready + (int64_t)q * n;
-    int32_t *need = a.need + (int64_t)q * n;
-    int32_t *start = a.start ? a.start + (int64_t)q * n : nullptr;
+    int32_t *ready = a.ready + qq * n;
+    int32_t *need = a.need + qq * n;
+    int32_t *start = a.start ? a.start + qq * n : nullptr;
 
     if (*a.status & CP_STATUS_BAD_TIE) {          // set by the check of the tie ranks, same stream
-        if (lane == 0) a.makespan[q] = -1;
+        if (alive && dev == 0) a.makespan[q] = -1;
         return;
     }
 
     // ---- set-up: vertices per device, state of every vertex
     count[lane] = 0;
+    gbad[lane] = 0;
     __syncthreads();
-    bool bad = false;
-    for (int32_t v = lane; v < n; v += 64) {
-        const uint32_t d = row[(int64_t)v * asv];
-        if (d >= (uint32_t)k) { bad = true; continue; }
-        atomicAdd(&count[d], 1);
-        ready[v] = 0;
-        need[v] = a.pred_ptr[v + 1] - a.pred_ptr[v];
+    if (alive) {
+        for (int32_t v = dev; v < n; v += k) {
+            const uint32_t d = row[(int64_t)v * asv];
+            if (d >= (uint32_t)k) { gbad[grp] = 1; continue; }
+            atomicAdd(&count[first + d], 1);
+            ready[v] = 0;
+            need[v] = a.pred_ptr[v + 1] - a.pred_ptr[v];
+        }
     }
-    if (__any(bad)) {
-        if (lane == 0) {
+    __syncthreads();
+    if (alive && gbad[grp]) {
+        alive = false;
+        if (dev == 0) {
             atomicOr(a.status, CP_STATUS_BAD_DEVICE_ID);
             a.makespan[q] = -1;
         }
-        return;
     }
-    __syncthreads();
     {
-        const int32_t mine = count[lane];
+        const int32_t mine = alive ? count[lane] : 0;
         int32_t incl = mine;
         for (int off = 1; off < 64; off <<= 1) {
             const int32_t other = __shfl_up(incl, off);
             if (lane >= off) incl += other;
         }
+        const int32_t below = __shfl(incl, first > 0 ? first - 1 : 0);   // total of the groups before this one
         __syncthreads();
-        seg[lane] = incl - mine;
+        seg[lane] = incl - mine - (first > 0 ? below : 0);
         count[lane] = 0;
     }
     step_fence();
-    int32_t *inbox = a.inbox + (int64_t)q * n;
-    for (int32_t v = lane; v < n; v += 64) {
-        if (a.pred_ptr[v + 1] == a.pred_ptr[v]) {
-            const uint32_t d = row[(int64_t)v * asv];
-            const int32_t pos = atomicAdd(&count[d], 1);
-            inbox_store(inbox + seg[d] + pos, v);
+    int32_t *inbox = a.inbox + qq * n;
+    if (alive) {
+        for (int32_t v = dev; v < n; v += k) {
+            if (a.pred_ptr[v + 1] == a.pred_ptr[v]) {
+                const uint32_t d = row[(int64_t)v * asv];
+                const int32_t pos = atomicAdd(&count[first + d], 1);
+                inbox_store(inbox + seg[first + d] + pos, v);
+            }
         }
     }
     step_fence();
 
     // ---- the event loop
     const int32_t base = seg[lane];
-    uint64_t *hp = a.pending + (int64_t)q * n + base;
-    uint64_t *ha = PCT ? a.available + (int64_t)q * n + base : nullptr;
+    uint64_t *hp = a.pending + qq * n + base;
+    uint64_t *ha = PCT ? a.available + qq * n + base : nullptr;
     const int32_t *my_inbox = inbox + base;
     const int64_t bsv = a.b_sv;
-    const uint8_t *bq = (const uint8_t *)a.b + (PCT ? (int64_t)q * a.b_sq * a.b_bytes : 0);
+    const uint8_t *bq = (const uint8_t *)a.b + (PCT ? qq * a.b_sq * a.b_bytes : 0);
+    const int last_lane = min(first + k - 1, 63);
     int32_t np = 0, na = 0, taken = 0, done = 0;
     uint32_t free_at = 0;
     bool b_bad = false;
-    // every step with work left starts at least one vertex, so n + 1 steps always suffice
+    // every step with work left starts at least one vertex in every unfinished group, so
+    // n + 1 steps always suffice
     for (int64_t step = 0; step <= n; ++step) {
-        {   // vertices handed to this device since its last step
+        if (alive) {   // vertices handed to this device since its last step
             const int32_t have = count[lane];
             for (; taken < have; ++taken) {
                 const int32_t z = inbox_load(my_inbox + taken);
@@ -213,9 +231,15 @@ __global__ __launch_bounds__(64) void simulate_kernel(SimArgs a) {
         uint32_t T = kNever;
         if (PCT && na > 0) T = free_at;
         else if (np > 0) T = max(free_at, (uint32_t)(hp[0] >> 32));
+        // the group's earliest decision time: a running minimum over the group's lanes, read
+        // from its last lane
         uint32_t tmin = T;
-        for (int off = 32; off > 0; off >>= 1) tmin = min(tmin, (uint32_t)__shfl_xor((int)tmin, off));
-        if (tmin == kNever) break;
+        for (int off = 1; off < k; off <<= 1) {
+            const uint32_t other = (uint32_t)__shfl_up((int)tmin, off);
+            if (dev >= off) tmin = min(tmin, other);
+        }
+        tmin = (uint32_t)__shfl((int)tmin, last_lane);
+        if (__all(tmin == kNever)) break;
         if (T != kNever && T - tmin <= a.window) {
             int32_t v;
             if (PCT) {
@@ -234,23 +258,23 @@ __global__ __launch_bounds__(64) void simulate_kernel(SimArgs a) {
             if (start) start[v] = (int32_t)T;
             ++done;
             const WT cv = cw[v];
-            const uint32_t w = MAGIC ? sim_magic_div((uint32_t)cv, vtab_m[lane])
-                                     : (uint32_t)sim_plain_div((uint64_t)cv, (uint64_t)vtab_g[lane]);
+            const uint32_t w = MAGIC ? sim_magic_div((uint32_t)cv, vtab_m[dev])
+                                     : (uint32_t)sim_plain_div((uint64_t)cv, (uint64_t)vtab_g[dev]);
             free_at = T + w;
             const int32_t e1 = a.ptr[v + 1];
             for (int32_t e = a.ptr[v]; e < e1; ++e) {
                 const int32_t z = a.idx[e];
                 const WT te = wt[e];
                 const uint32_t dz = row[(int64_t)z * asv];
-                const uint32_t x = MAGIC ? sim_magic_div((uint32_t)te, etab_m[lane * k + dz])
-                                         : (uint32_t)sim_plain_div((uint64_t)te, (uint64_t)etab_g[lane * k + dz]);
+                const uint32_t x = MAGIC ? sim_magic_div((uint32_t)te, etab_m[dev * k + dz])
+                                         : (uint32_t)sim_plain_div((uint64_t)te, (uint64_t)etab_g[dev * k + dz]);
                 __hip_atomic_fetch_max(ready + z, (int32_t)(free_at + x), __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_WORKGROUP);
                 const int32_t before = __hip_atomic_fetch_add(need + z, -1, __ATOMIC_RELAXED,
                                                               __HIP_MEMORY_SCOPE_WORKGROUP);
                 if (before == 1) {
-                    const int32_t pos = atomicAdd(&count[dz], 1);
-                    inbox_store(inbox + seg[dz] + pos, z);
+                    const int32_t pos = atomicAdd(&count[first + dz], 1);
+                    inbox_store(inbox + seg[first + dz] + pos, z);
                 }
             }
         }
@@ -258,12 +282,16 @@ __global__ __launch_bounds__(64) void simulate_kernel(SimArgs a) {
     }
     uint32_t last = free_at;
     int32_t total = done;
-    for (int off = 32; off > 0; off >>= 1) {
-        last = max(last, (uint32_t)__shfl_xor((int)last, off));
-        total += __shfl_xor(total, off);
+    for (int off = 1; off < k; off <<= 1) {
+        const uint32_t o1 = (uint32_t)__shfl_up((int)last, off);
+        const int32_t o2 = __shfl_up(total, off);
+        if (dev >= off) {
+            last = max(last, o1);
+            total += o2;
+        }
     }
     if (__any(b_bad) && lane == 0) atomicOr(a.status, CP_STATUS_B_OUT_OF_RANGE);
-    if (lane == 0) {
+    if (alive && dev == k - 1) {
         if (total != n) {
             atomicOr(a.status, CP_STATUS_INCOMPLETE);
             a.makespan[q] = -1;
@@ -332,7 +360,9 @@ int launch_simulate(const SimulateLaunch &s, void *stream) {
     a.status = s.status;
     a.n = s.n; a.P = s.P; a.k = s.k;
     a.window = s.window;
-    const dim3 grid((unsigned)s.P), block(64);
+    const int groups = std::max(1, std::min(s.groups, kWave / s.k));      // partitions per wavefront
+    a.groups = groups;
+    const dim3 grid((unsigned)((s.P + groups - 1) / groups)), block(64);
 #define CP_SIM(WT, MAGIC)                                                                      \
     do {                                                                                       \
         if (s.pct) hipLaunchKernelGGL((simulate_kernel<WT, MAGIC, true>), grid, block, 0, st, a);  \

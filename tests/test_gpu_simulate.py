@@ -190,3 +190,29 @@ def test_status_and_errors(gpu, oracle):
         gpu.cp_simulate(g0, d_a, w.speeds, w.bandwidth, FIFO)
     assert e.value.code == -12
     g0.close()
+
+
+def test_partitions_sharing_a_wavefront(gpu, oracle):
+    """A batch large enough that partitions with few devices are simulated several per wavefront
+    (three here: 24,600 partitions of a small graph on 5 devices), with a ragged last wavefront and
+    one partition that names a device that does not exist."""
+    import torch
+    w = _random_workload(21, 9, 6, 5, 24600, deg_hi=3, span_hi=2)
+    a = w.assignments.copy()
+    a[12345, 7] = 5
+    g = gpu.CpGraph.from_workload(w, device="cuda:0")
+    d_a = torch.from_numpy(a).to("cuda:0")
+    ev = gpu.cp_eval(g, torch.from_numpy(w.assignments).to("cuda:0"), w.speeds, w.bandwidth, want=("cp", "b"),
+                     out_layout=1)
+    good = np.delete(np.arange(w.P), 12345)
+    b_ref = oracle.evaluate(w.n, w.succ_ptr, w.succ_idx, w.succ_t, w.c, w.speeds, w.bandwidth, w.assignments[good],
+                            want=("cp", "b"), threads=16)["b"]
+    for policy, kw in ((PCT, dict(b=ev["b"], b_layout=1)), (FIFO, {})):
+        _say(f"cp_simulate shared wavefronts policy={policy}")
+        makespan, start = gpu.cp_simulate(g, d_a, w.speeds, w.bandwidth, policy, check_status=False, **kw)
+        ref = _oracle_sim(oracle, w, w.assignments[good], policy, b=b_ref if policy == PCT else None)
+        got_m = makespan.cpu().numpy()
+        assert got_m[12345] == -1
+        assert np.array_equal(got_m[good], ref["makespan"])
+        assert np.array_equal(start.cpu().numpy()[good], ref["start"])
+    g.close()
