@@ -70,6 +70,9 @@ def load_library():
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(
             f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    # PyTorch first: it brings its own HIP runtime, and device memory handed over by torch must
+    # belong to the runtime this library calls.  The library's dependency then resolves to it.
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     i32p, i64p, u8p = C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_uint8)
     vp = C.c_void_p

@@ -216,3 +216,20 @@ def test_partitions_sharing_a_wavefront(gpu, oracle):
         assert np.array_equal(got_m[good], ref["makespan"])
         assert np.array_equal(start.cpu().numpy()[good], ref["start"])
     g.close()
+
+
+def test_large_sparse_full_size(gpu, oracle):
+    """The bench graph at full size (1,000,000 vertices, 16 devices), a few partitions: every start time."""
+    import torch
+    w = make_workload("large_sparse", P=6)
+    g = gpu.CpGraph.from_workload(w, device="cuda:0")
+    d_a = torch.from_numpy(w.assignments).to("cuda:0")
+    ev = gpu.cp_eval(g, d_a, w.speeds, w.bandwidth, want=("cp", "b"), out_layout=1)
+    b_ref = ev["b"].cpu().numpy().astype(np.int64)      # parity of b itself is test_gpu_parity's subject
+    for policy, kw in ((PCT, dict(b=ev["b"], b_layout=1)), (FIFO, {})):
+        _say(f"cp_simulate large_sparse full size policy={policy}")
+        makespan, start = gpu.cp_simulate(g, d_a, w.speeds, w.bandwidth, policy, **kw)
+        ref = _oracle_sim(oracle, w, w.assignments, policy, b=b_ref if policy == PCT else None)
+        assert np.array_equal(makespan.cpu().numpy(), ref["makespan"])
+        assert np.array_equal(start.cpu().numpy(), ref["start"])
+    g.close()
