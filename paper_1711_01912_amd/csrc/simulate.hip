@@ -101,6 +101,14 @@ __device__ __forceinline__ uint64_t heap_pop(uint64_t *h, int32_t &size) {
     return top;
 }
 
+// b(z) of the lane's partition; a value outside [0, 2^31) is reported and replaced by 0.
+__device__ __forceinline__ long long load_b(const uint8_t *bq, int32_t z, int64_t bsv, int32_t b_bytes, bool &bad) {
+    long long bz = b_bytes == 4 ? (long long)*(const int32_t *)(bq + (int64_t)z * bsv * 4)
+                                : *(const long long *)(bq + (int64_t)z * bsv * 8);
+    if (bz < 0 || bz > 0x7fffffffll) { bad = true; bz = 0; }
+    return bz;
+}
+
 struct SimArgs {
     const int32_t *ptr;        // successor CSR over original ids
     const int32_t *idx;
@@ -219,13 +227,32 @@ __global__ __launch_bounds__(64) void simulate_kernel(SimArgs a) {
     // every step with work left starts at least one vertex in every unfinished group, so
     // n + 1 steps always suffice
     for (int64_t step = 0; step <= n; ++step) {
-        if (alive) {   // vertices handed to this device since its last step
+        if (alive) {   // vertices handed to this device since its last step, four loads in flight at a time
             const int32_t have = count[lane];
-            for (; taken < have; ++taken) {
-                const int32_t z = inbox_load(my_inbox + taken);
-                const uint32_t rz = (uint32_t)l2_read(ready + z);
-                const uint32_t low = PCT ? (uint32_t)z : (a.tie ? (uint32_t)a.tie[z] : (uint32_t)z);
-                heap_push(hp, np, ((uint64_t)rz << 32) | low);
+            while (taken < have) {
+                const int32_t cnt = min(4, have - taken);
+                int32_t z[4];
+                uint32_t rz[4], low[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) z[j] = inbox_load(my_inbox + taken + min(j, cnt - 1));
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    rz[j] = (uint32_t)l2_read(ready + z[j]);
+                    low[j] = PCT ? (uint32_t)z[j] : (a.tie ? (uint32_t)a.tie[z[j]] : (uint32_t)z[j]);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (j < cnt) {
+                        if (PCT && rz[j] <= free_at) {
+                            // executable at every decision this device has still to take
+                            const long long bz = load_b(bq, z[j], bsv, a.b_bytes, b_bad);
+                            heap_push(ha, na, ((uint64_t)(0x7fffffffu - (uint32_t)bz) << 32) | (uint32_t)z[j]);
+                        } else {
+                            heap_push(hp, np, ((uint64_t)rz[j] << 32) | low[j]);
+                        }
+                    }
+                }
+                taken += cnt;
             }
         }
         uint32_t T = kNever;
@@ -245,9 +272,7 @@ __global__ __launch_bounds__(64) void simulate_kernel(SimArgs a) {
             if (PCT) {
                 for (int32_t moved = 0; np > 0 && (uint32_t)(hp[0] >> 32) <= T && moved < n; ++moved) {
                     const int32_t z = (int32_t)(uint32_t)heap_pop(hp, np);
-                    long long bz = a.b_bytes == 4 ? (long long)*(const int32_t *)(bq + (int64_t)z * bsv * 4)
-                                                  : *(const long long *)(bq + (int64_t)z * bsv * 8);
-                    if (bz < 0 || bz > 0x7fffffffll) { b_bad = true; bz = 0; }
+                    const long long bz = load_b(bq, z, bsv, a.b_bytes, b_bad);
                     heap_push(ha, na, ((uint64_t)(0x7fffffffu - (uint32_t)bz) << 32) | (uint32_t)z);
                 }
                 v = (int32_t)(uint32_t)heap_pop(ha, na);
@@ -261,20 +286,48 @@ __global__ __launch_bounds__(64) void simulate_kernel(SimArgs a) {
             const uint32_t w = MAGIC ? sim_magic_div((uint32_t)cv, vtab_m[dev])
                                      : (uint32_t)sim_plain_div((uint64_t)cv, (uint64_t)vtab_g[dev]);
             free_at = T + w;
+            // the out-edges four at a time, so that the dependent loads of four edges (successor,
+            // its device, the table entry) and their atomics overlap; slots past the row's end
+            // repeat its last edge for the loads and take no part in the atomics
             const int32_t e1 = a.ptr[v + 1];
-            for (int32_t e = a.ptr[v]; e < e1; ++e) {
-                const int32_t z = a.idx[e];
-                const WT te = wt[e];
-                const uint32_t dz = row[(int64_t)z * asv];
-                const uint32_t x = MAGIC ? sim_magic_div((uint32_t)te, etab_m[dev * k + dz])
-                                         : (uint32_t)sim_plain_div((uint64_t)te, (uint64_t)etab_g[dev * k + dz]);
-                __hip_atomic_fetch_max(ready + z, (int32_t)(free_at + x), __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_WORKGROUP);
-                const int32_t before = __hip_atomic_fetch_add(need + z, -1, __ATOMIC_RELAXED,
-                                                              __HIP_MEMORY_SCOPE_WORKGROUP);
-                if (before == 1) {
-                    const int32_t pos = atomicAdd(&count[first + dz], 1);
-                    inbox_store(inbox + seg[first + dz] + pos, z);
+            for (int32_t e = a.ptr[v]; e < e1; e += 4) {
+                const int32_t cnt = min(4, e1 - e);
+                int32_t z[4], before[4];
+                WT te[4];
+                uint32_t dz[4], arrive[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int32_t ej = e + min(j, cnt - 1);
+                    z[j] = a.idx[ej];
+                    te[j] = wt[ej];
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) dz[j] = row[(int64_t)z[j] * asv];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t x = MAGIC ? sim_magic_div((uint32_t)te[j], etab_m[dev * k + dz[j]])
+                                             : (uint32_t)sim_plain_div((uint64_t)te[j],
+                                                                       (uint64_t)etab_g[dev * k + dz[j]]);
+                    arrive[j] = free_at + x;
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (j < cnt)
+                        __hip_atomic_fetch_max(ready + z[j], (int32_t)arrive[j], __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_WORKGROUP);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    before[j] = 0;
+                    if (j < cnt)
+                        before[j] = __hip_atomic_fetch_add(need + z[j], -1, __ATOMIC_RELAXED,
+                                                           __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (before[j] == 1) {
+                        const int32_t pos = atomicAdd(&count[first + dz[j]], 1);
+                        inbox_store(inbox + seg[first + dz[j]] + pos, z[j]);
+                    }
                 }
             }
         }
