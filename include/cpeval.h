@@ -298,7 +298,8 @@ int cp_validate(int32_t n, int32_t batch, int32_t k, const uint8_t *assignments,
  * Every vertex must cost at least one tick (c(v) >= 1 for all v, else CP_ERR_ARG): then
  * devices that decide at the same time cannot influence each other and the schedule is
  * unique.  All times must stay below 2^31: the summed execution times on the slowest device plus
- * the graph's raw path bound, which no makespan exceeds, else CP_ERR_OVERFLOW.
+ * the longest chain of transfers (bounded by the graph's raw path bound and by L - 1 transfers
+ * at the lowest rate), which no makespan exceeds, else CP_ERR_OVERFLOW.
  * One wavefront simulates one partition, one lane per device: k <= 64.
  * Only enqueues work on `stream`.
  *

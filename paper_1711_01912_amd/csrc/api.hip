@@ -654,21 +654,30 @@ int cp_simulate(const cp_graph *g, int32_t batch, int32_t k,
     // span of decision times that may be served together.  No time may reach 2^31: at every
     // moment before the end either some device is busy (at most the summed execution times in
     // all) or every device waits for a transfer on one chain of dependent vertices (at most
-    // the longest path's transfers, which the raw path bound covers).
-    int64_t s_min = speeds[0], s_max = speeds[0], b_max = 1;
+    // the longest path's transfers, which the raw path bound covers, and so does L - 1 times the
+    // longest transfer).
+    int64_t s_min = speeds[0], s_max = speeds[0], b_min = INT64_MAX, b_max = 1;
     for (int i = 0; i < k; ++i) {
         s_min = std::min(s_min, speeds[i]);
         s_max = std::max(s_max, speeds[i]);
         for (int j = 0; j < k; ++j)
-            if (i != j) b_max = std::max(b_max, bandwidth[(size_t)i * k + j]);
+            if (i != j) {
+                b_min = std::min(b_min, bandwidth[(size_t)i * k + j]);
+                b_max = std::max(b_max, bandwidth[(size_t)i * k + j]);
+            }
     }
+    if (b_min == INT64_MAX) b_min = 1;
     uint64_t min_c = 0, min_t = 0;
     long double sum_w = 0;
     if (p.narrow) min_weights<uint32_t>(p, (uint64_t)s_min, min_c, min_t, sum_w);
     else min_weights<int64_t>(p, (uint64_t)s_min, min_c, min_t, sum_w);
     if (min_c < 1) return CP_ERR_ARG;
-    if (sum_w + (long double)p.info.raw_path_bound >= 2147483647.0L) return CP_ERR_OVERFLOW;
     auto ceil_div = [](uint64_t a, uint64_t d) { return a / d + (a % d != 0); };
+    // a chain has at most one vertex per level, so L - 1 transfers of at most ceil(max t / min B)
+    const long double chain = std::min<long double>(
+        (long double)p.info.raw_path_bound,
+        (long double)(p.L - 1) * (long double)ceil_div((uint64_t)p.info.max_t, (uint64_t)b_min));
+    if (sum_w + chain >= 2147483647.0L) return CP_ERR_OVERFLOW;
     const uint64_t w_min = ceil_div(min_c, (uint64_t)s_max);
     const uint64_t x_min = (p.m == 0 || min_t == 0) ? 0 : ceil_div(min_t, (uint64_t)b_max);
     const uint64_t window = std::min<uint64_t>(w_min + x_min - 1, 1u << 30);

@@ -190,6 +190,14 @@ def test_status_and_errors(gpu, oracle):
         gpu.cp_simulate(g0, d_a, w.speeds, w.bandwidth, FIFO)
     assert e.value.code == -12
     g0.close()
+    # times that could pass 2^31 are refused: 64 vertices of 2^26 ticks each on a device of speed 1
+    w1 = make_workload("tiny")
+    w1.c = np.full(w1.n, 2**26, dtype=np.int64)
+    g1 = gpu.CpGraph.from_workload(w1, device="cuda:0")
+    with pytest.raises(gpu.CpError) as e:
+        gpu.cp_simulate(g1, d_a, w.speeds, w.bandwidth, FIFO)
+    assert e.value.code == -8
+    g1.close()
 
 
 def test_partitions_sharing_a_wavefront(gpu, oracle):
@@ -233,3 +241,40 @@ def test_large_sparse_full_size(gpu, oracle):
         assert np.array_equal(makespan.cpu().numpy(), ref["makespan"])
         assert np.array_equal(start.cpu().numpy(), ref["start"])
     g.close()
+
+
+def test_other_weight_and_tick_types(gpu, oracle):
+    """b handed over as int64; weights past 32 bits (plain 64-bit division in the kernel); 32-bit
+    weights whose divisors have no exact multiply-shift form."""
+    import torch
+    # (a) int64 b from the wave-column plan
+    w = _random_workload(31, 14, 9, 6, 5)
+    g = gpu.CpGraph.from_workload(w, device="cuda:0")
+    d_a = torch.from_numpy(w.assignments).to("cuda:0")
+    ev = gpu.cp_eval(g, d_a, w.speeds, w.bandwidth, want=("cp", "b"), tick_bytes=8, plan=1)
+    assert ev["b"].dtype == torch.int64
+    ref_b = oracle.evaluate(w.n, w.succ_ptr, w.succ_idx, w.succ_t, w.c, w.speeds, w.bandwidth, w.assignments,
+                            want=("cp", "b"), threads=4)["b"]
+    _say("cp_simulate with int64 b")
+    makespan, start = gpu.cp_simulate(g, d_a, w.speeds, w.bandwidth, PCT, b=ev["b"], b_layout=0)
+    ref = _oracle_sim(oracle, w, w.assignments, PCT, b=ref_b)
+    assert np.array_equal(start.cpu().numpy(), ref["start"]) and np.array_equal(makespan.cpu().numpy(), ref["makespan"])
+    g.close()
+    # (b) weights of 33..35 bits over speeds and rates of ~30 bits: every time stays small
+    rng = np.random.default_rng(32)
+    w = _random_workload(32, 10, 8, 4, 4)
+    w.c = rng.integers(2**32, 2**34, size=w.n)
+    w.succ_t = rng.integers(2**32, 2**35, size=w.succ_t.shape[0])
+    w.speeds = rng.integers(2**28, 2**30, size=4)
+    w.bandwidth = rng.integers(2**28, 2**30, size=(4, 4))
+    g = gpu.CpGraph.from_workload(w, device="cuda:0")
+    assert g.info["max_c"] >= 2**32
+    g.close()
+    _check(gpu, oracle, w, what="wide weights")
+    # (c) 32-bit weights, divisors near 10^9: no exact multiply-shift constant exists for them
+    w = _random_workload(33, 10, 8, 4, 4)
+    w.c = rng.integers(2 * 10**9, 4 * 10**9, size=w.n)
+    w.succ_t = rng.integers(2 * 10**9, 4 * 10**9, size=w.succ_t.shape[0])
+    w.speeds = rng.integers(10**9, 10**9 + 50, size=4)
+    w.bandwidth = rng.integers(10**9, 10**9 + 50, size=(4, 4))
+    _check(gpu, oracle, w, what="no multiply-shift")
