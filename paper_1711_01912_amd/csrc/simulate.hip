@@ -101,6 +101,35 @@ __device__ __forceinline__ uint64_t heap_pop(uint64_t *h, int32_t &size) {
     return top;
 }
 
+// A queue = its smallest key in a register + the heap above in memory for the rest.  Device
+// queues are short most of the time (a handful of executable vertices), so most pushes and
+// pops never touch memory, and the decision time is read from the register.
+struct Queue {
+    uint64_t top = 0;
+    int32_t size = 0;          // keys held, the one in the register included
+};
+
+__device__ __forceinline__ void queue_push(uint64_t *h, Queue &q, uint64_t key) {
+    if (q.size == 0) {
+        q.top = key;
+    } else {
+        const uint64_t keep = min(q.top, key), spill = max(q.top, key);
+        q.top = keep;
+        int32_t in_memory = q.size - 1;
+        heap_push(h, in_memory, spill);
+    }
+    ++q.size;
+}
+
+__device__ __forceinline__ uint64_t queue_pop(uint64_t *h, Queue &q) {
+    const uint64_t out = q.top;
+    if (--q.size > 0) {
+        int32_t in_memory = q.size;
+        q.top = heap_pop(h, in_memory);
+    }
+    return out;
+}
+
 // b(z) of the lane's partition; a value outside [0, 2^31) is reported and replaced by 0.
 __device__ __forceinline__ long long load_b(const uint8_t *bq, int32_t z, int64_t bsv, int32_t b_bytes, bool &bad) {
     long long bz = b_bytes == 4 ? (long long)*(const int32_t *)(bq + (int64_t)z * bsv * 4)
@@ -221,7 +250,8 @@ __global__ __launch_bounds__(64) void simulate_kernel(SimArgs a) {
     const int64_t bsv = a.b_sv;
     const uint8_t *bq = (const uint8_t *)a.b + (PCT ? qq * a.b_sq * a.b_bytes : 0);
     const int last_lane = min(first + k - 1, 63);
-    int32_t np = 0, na = 0, taken = 0, done = 0;
+    Queue pending, available;
+    int32_t taken = 0, done = 0;
     uint32_t free_at = 0;
     bool b_bad = false;
     // every step with work left starts at least one vertex in every unfinished group, so
@@ -246,9 +276,9 @@ __global__ __launch_bounds__(64) void simulate_kernel(SimArgs a) {
                         if (PCT && rz[j] <= free_at) {
                             // executable at every decision this device has still to take
                             const long long bz = load_b(bq, z[j], bsv, a.b_bytes, b_bad);
-                            heap_push(ha, na, ((uint64_t)(0x7fffffffu - (uint32_t)bz) << 32) | (uint32_t)z[j]);
+                            queue_push(ha, available, ((uint64_t)(0x7fffffffu - (uint32_t)bz) << 32) | (uint32_t)z[j]);
                         } else {
-                            heap_push(hp, np, ((uint64_t)rz[j] << 32) | low[j]);
+                            queue_push(hp, pending, ((uint64_t)rz[j] << 32) | low[j]);
                         }
                     }
                 }
@@ -256,8 +286,8 @@ __global__ __launch_bounds__(64) void simulate_kernel(SimArgs a) {
             }
         }
         uint32_t T = kNever;
-        if (PCT && na > 0) T = free_at;
-        else if (np > 0) T = max(free_at, (uint32_t)(hp[0] >> 32));
+        if (PCT && available.size > 0) T = free_at;
+        else if (pending.size > 0) T = max(free_at, (uint32_t)(pending.top >> 32));
         // the group's earliest decision time: a running minimum over the group's lanes, read
         // from its last lane
         uint32_t tmin = T;
@@ -270,14 +300,15 @@ __global__ __launch_bounds__(64) void simulate_kernel(SimArgs a) {
         if (T != kNever && T - tmin <= a.window) {
             int32_t v;
             if (PCT) {
-                for (int32_t moved = 0; np > 0 && (uint32_t)(hp[0] >> 32) <= T && moved < n; ++moved) {
-                    const int32_t z = (int32_t)(uint32_t)heap_pop(hp, np);
+                for (int32_t moved = 0; pending.size > 0 && (uint32_t)(pending.top >> 32) <= T && moved < n;
+                     ++moved) {
+                    const int32_t z = (int32_t)(uint32_t)queue_pop(hp, pending);
                     const long long bz = load_b(bq, z, bsv, a.b_bytes, b_bad);
-                    heap_push(ha, na, ((uint64_t)(0x7fffffffu - (uint32_t)bz) << 32) | (uint32_t)z);
+                    queue_push(ha, available, ((uint64_t)(0x7fffffffu - (uint32_t)bz) << 32) | (uint32_t)z);
                 }
-                v = (int32_t)(uint32_t)heap_pop(ha, na);
+                v = (int32_t)(uint32_t)queue_pop(ha, available);
             } else {
-                const uint32_t low = (uint32_t)heap_pop(hp, np);
+                const uint32_t low = (uint32_t)queue_pop(hp, pending);
                 v = a.tie_inv ? a.tie_inv[low] : (int32_t)low;
             }
             if (start) start[v] = (int32_t)T;
