@@ -121,12 +121,24 @@ __device__ __forceinline__ void queue_push(uint64_t *h, Queue &q, uint64_t key) 
     ++q.size;
 }
 
-__device__ __forceinline__ uint64_t queue_pop(uint64_t *h, Queue &q) {
-    const uint64_t out = q.top;
-    if (--q.size > 0) {
+// Taking the smallest key and bringing the next one into the register are two calls, so that
+// the caller can start the loads that depend on the key before the heap in memory is put in
+// order again.  Nothing else may touch the queue in between.
+__device__ __forceinline__ uint64_t queue_take(Queue &q) {
+    --q.size;
+    return q.top;
+}
+
+__device__ __forceinline__ void queue_refill(uint64_t *h, Queue &q) {
+    if (q.size > 0) {
         int32_t in_memory = q.size;
         q.top = heap_pop(h, in_memory);
     }
+}
+
+__device__ __forceinline__ uint64_t queue_pop(uint64_t *h, Queue &q) {
+    const uint64_t out = queue_take(q);
+    queue_refill(h, q);
     return out;
 }
 
@@ -306,22 +318,25 @@ __global__ __launch_bounds__(64) void simulate_kernel(SimArgs a) {
                     const long long bz = load_b(bq, z, bsv, a.b_bytes, b_bad);
                     queue_push(ha, available, ((uint64_t)(0x7fffffffu - (uint32_t)bz) << 32) | (uint32_t)z);
                 }
-                v = (int32_t)(uint32_t)queue_pop(ha, available);
+                v = (int32_t)(uint32_t)queue_take(available);
             } else {
-                const uint32_t low = (uint32_t)queue_pop(hp, pending);
+                const uint32_t low = (uint32_t)queue_take(pending);
                 v = a.tie_inv ? a.tie_inv[low] : (int32_t)low;
             }
+            // what the vertex needs from the graph is on its way while the queue is put in order
+            const WT cv = cw[v];
+            const int32_t e0 = a.ptr[v], e1 = a.ptr[v + 1];
+            if (PCT) queue_refill(ha, available);
+            else queue_refill(hp, pending);
             if (start) start[v] = (int32_t)T;
             ++done;
-            const WT cv = cw[v];
             const uint32_t w = MAGIC ? sim_magic_div((uint32_t)cv, vtab_m[dev])
                                      : (uint32_t)sim_plain_div((uint64_t)cv, (uint64_t)vtab_g[dev]);
             free_at = T + w;
             // the out-edges four at a time, so that the dependent loads of four edges (successor,
             // its device, the table entry) and their atomics overlap; slots past the row's end
             // repeat its last edge for the loads and take no part in the atomics
-            const int32_t e1 = a.ptr[v + 1];
-            for (int32_t e = a.ptr[v]; e < e1; e += 4) {
+            for (int32_t e = e0; e < e1; e += 4) {
                 const int32_t cnt = min(4, e1 - e);
                 int32_t z[4], before[4];
                 WT te[4];
