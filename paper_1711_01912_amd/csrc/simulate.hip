@@ -30,6 +30,7 @@ namespace cpeval {
 namespace {
 
 constexpr uint32_t kNever = 0xffffffffu;
+constexpr int kWideRow = 32;      // out-edges from which a started vertex's row is shared out over the wavefront
 
 __device__ __forceinline__ uint32_t sim_magic_div(uint32_t a, Magic mg) {
     uint32_t nn = a + mg.dm1;
@@ -309,6 +310,7 @@ __global__ __launch_bounds__(64) void simulate_kernel(SimArgs a) {
         }
         tmin = (uint32_t)__shfl((int)tmin, last_lane);
         if (__all(tmin == kNever)) break;
+        int32_t wide_e0 = 0, wide_e1 = 0;     // a long row is left to the whole wavefront below
         if (T != kNever && T - tmin <= a.window) {
             int32_t v;
             if (PCT) {
@@ -336,8 +338,14 @@ __global__ __launch_bounds__(64) void simulate_kernel(SimArgs a) {
             // the out-edges four at a time, so that the dependent loads of four edges (successor,
             // its device, the table entry) and their atomics overlap; slots past the row's end
             // repeat its last edge for the loads and take no part in the atomics
-            for (int32_t e = e0; e < e1; e += 4) {
-                const int32_t cnt = min(4, e1 - e);
+            int32_t e_end = e1;
+            if (e1 - e0 >= kWideRow) {
+                wide_e0 = e0;
+                wide_e1 = e1;
+                e_end = e0;
+            }
+            for (int32_t e = e0; e < e_end; e += 4) {
+                const int32_t cnt = min(4, e_end - e);
                 int32_t z[4], before[4];
                 WT te[4];
                 uint32_t dz[4], arrive[4];
@@ -374,6 +382,32 @@ __global__ __launch_bounds__(64) void simulate_kernel(SimArgs a) {
                         const int32_t pos = atomicAdd(&count[first + dz[j]], 1);
                         inbox_store(inbox + seg[first + dz[j]] + pos, z[j]);
                     }
+                }
+            }
+        }
+        // long rows (hubs), one after the other, 64 edges at a time: every lane of the wavefront,
+        // whatever its own partition, works for the lane that started the hub
+        for (unsigned long long wide = __ballot(wide_e1 > wide_e0); wide; wide &= wide - 1) {
+            const int src = __ffsll((long long)wide) - 1;
+            const int32_t he0 = __shfl(wide_e0, src), he1 = __shfl(wide_e1, src);
+            const uint32_t hfree = (uint32_t)__shfl((int)free_at, src);
+            const int hdev = __shfl(dev, src), hfirst = __shfl(first, src);
+            const int64_t hq = ((int64_t)__shfl((int)(qq >> 32), src) << 32) | (uint32_t)__shfl((int)(uint32_t)qq, src);
+            const uint8_t *hrow = a.assign + hq * a.a_stride_p;
+            int32_t *hready = a.ready + hq * n, *hneed = a.need + hq * n, *hinbox = a.inbox + hq * n;
+            for (int32_t e = he0 + lane; e < he1; e += 64) {
+                const int32_t z = a.idx[e];
+                const WT te = wt[e];
+                const uint32_t dz = hrow[(int64_t)z * asv];
+                const uint32_t x = MAGIC ? sim_magic_div((uint32_t)te, etab_m[hdev * k + dz])
+                                         : (uint32_t)sim_plain_div((uint64_t)te, (uint64_t)etab_g[hdev * k + dz]);
+                __hip_atomic_fetch_max(hready + z, (int32_t)(hfree + x), __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_WORKGROUP);
+                const int32_t before = __hip_atomic_fetch_add(hneed + z, -1, __ATOMIC_RELAXED,
+                                                              __HIP_MEMORY_SCOPE_WORKGROUP);
+                if (before == 1) {
+                    const int32_t pos = atomicAdd(&count[hfirst + dz], 1);
+                    inbox_store(hinbox + seg[hfirst + dz] + pos, z);
                 }
             }
         }

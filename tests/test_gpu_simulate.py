@@ -278,3 +278,18 @@ def test_other_weight_and_tick_types(gpu, oracle):
     w.speeds = rng.integers(10**9, 10**9 + 50, size=4)
     w.bandwidth = rng.integers(10**9, 10**9 + 50, size=(4, 4))
     _check(gpu, oracle, w, what="no multiply-shift")
+
+
+def test_hub_rows_in_shared_wavefronts(gpu, oracle):
+    """A vertex with 40 successors is shared out over the whole wavefront, here a wavefront that
+    holds two partitions (16,400 partitions on 7 devices)."""
+    rng = np.random.default_rng(41)
+    n = 48
+    src = [0] * 40 + list(range(1, 41)) + [41, 42, 43, 44, 45, 46]
+    dst = list(range(1, 41)) + [41] * 40 + [42, 43, 44, 45, 46, 47]
+    t = rng.integers(1, 200, size=len(src))
+    csr = build_csr(n, np.array(src), np.array(dst), t)
+    k = 7
+    a = rng.integers(0, k, size=(16400, n)).astype(np.uint8)
+    w = _finish("hub", csr, rng.integers(1, 60, size=n), k, rng.integers(1, 9, size=k), rng.integers(1, 9, size=(k, k)), a)
+    _check(gpu, oracle, w, layouts=(0,))
