@@ -65,12 +65,14 @@ __device__ __forceinline__ void step_fence() {
     __syncthreads();
 }
 
-// Binary min-heaps of 64-bit keys; a lane's heap is touched by that lane only.  A heap
-// never holds more keys than its device has vertices, so 32 levels bound every loop.
+// Four-ary min-heaps of 64-bit keys (children of i: 4i+1 .. 4i+4): half the levels of a binary
+// heap, and the four children of a node are loaded together.  A lane's heap is touched by that
+// lane only.  A heap never holds more keys than its device has vertices, so 16 levels bound
+// every loop.
 __device__ __forceinline__ void heap_push(uint64_t *h, int32_t &size, uint64_t key) {
     int32_t i = size++;
-    for (int depth = 0; depth < 32 && i > 0; ++depth) {
-        const int32_t up = (i - 1) >> 1;
+    for (int depth = 0; depth < 16 && i > 0; ++depth) {
+        const int32_t up = (i - 1) >> 2;
         const uint64_t uk = h[up];
         if (uk <= key) break;
         h[i] = uk;
@@ -85,17 +87,24 @@ __device__ __forceinline__ uint64_t heap_pop(uint64_t *h, int32_t &size) {
     if (left > 0) {
         const uint64_t last = h[left];
         int32_t i = 0;
-        for (int depth = 0; depth < 32; ++depth) {
-            int32_t ch = 2 * i + 1;
-            if (ch >= left) break;
-            uint64_t ck = h[ch];
-            if (ch + 1 < left) {
-                const uint64_t c2 = h[ch + 1];
-                if (c2 < ck) { ck = c2; ++ch; }
+        for (int depth = 0; depth < 16; ++depth) {
+            const int32_t c0 = 4 * i + 1;
+            if (c0 >= left) break;
+            uint64_t ck[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) ck[j] = h[min(c0 + j, left - 1)];     // in range; masked below
+            uint64_t best = ck[0];
+            int32_t at = c0;
+#pragma unroll
+            for (int j = 1; j < 4; ++j) {
+                if (c0 + j < left && ck[j] < best) {
+                    best = ck[j];
+                    at = c0 + j;
+                }
             }
-            if (last <= ck) break;
-            h[i] = ck;
-            i = ch;
+            if (last <= best) break;
+            h[i] = best;
+            i = at;
         }
         h[i] = last;
     }
