@@ -37,6 +37,12 @@ __device__ __forceinline__ uint32_t sim_magic_div(uint32_t a, Magic mg) {
     return (uint32_t)(((uint64_t)nn * mg.mul + nn) >> 32);
 }
 
+// x of the lane a DPP control word names (a permutation inside each row of 16 lanes).
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t x) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, false);
+}
+
 __device__ __forceinline__ uint64_t sim_plain_div(uint64_t a, uint64_t d) {
     return d ? (a + d - 1) / d : 0;
 }
@@ -310,14 +316,27 @@ __global__ __launch_bounds__(64) void simulate_kernel(SimArgs a) {
         uint32_t T = kNever;
         if (PCT && available.size > 0) T = free_at;
         else if (pending.size > 0) T = max(free_at, (uint32_t)(pending.top >> 32));
-        // the group's earliest decision time: a running minimum over the group's lanes, read
-        // from its last lane
+        // the group's earliest decision time (several groups: a running minimum over each
+        // group's lanes, read from its last lane)
         uint32_t tmin = T;
-        for (int off = 1; off < k; off <<= 1) {
-            const uint32_t other = (uint32_t)__shfl_up((int)tmin, off);
-            if (dev >= off) tmin = min(tmin, other);
+        if (groups == 1) {
+            // one partition in the wavefront: the minimum of each row of 16 lanes by register
+            // permutations, then the four rows' minima through scalar registers
+            tmin = min(tmin, dpp_u32<0xB1>(tmin));      // swap neighbours
+            tmin = min(tmin, dpp_u32<0x4E>(tmin));      // swap pairs
+            tmin = min(tmin, dpp_u32<0x141>(tmin));     // mirror halves of 8
+            tmin = min(tmin, dpp_u32<0x140>(tmin));     // mirror the row
+            tmin = min(min((uint32_t)__builtin_amdgcn_readlane((int)tmin, 0),
+                           (uint32_t)__builtin_amdgcn_readlane((int)tmin, 16)),
+                       min((uint32_t)__builtin_amdgcn_readlane((int)tmin, 32),
+                           (uint32_t)__builtin_amdgcn_readlane((int)tmin, 48)));
+        } else {
+            for (int off = 1; off < k; off <<= 1) {
+                const uint32_t other = (uint32_t)__shfl_up((int)tmin, off);
+                if (dev >= off) tmin = min(tmin, other);
+            }
+            tmin = (uint32_t)__shfl((int)tmin, last_lane);
         }
-        tmin = (uint32_t)__shfl((int)tmin, last_lane);
         if (__all(tmin == kNever)) break;
         int32_t wide_e0 = 0, wide_e1 = 0;     // a long row is left to the whole wavefront below
         if (T != kNever && T - tmin <= a.window) {
