@@ -54,9 +54,8 @@ __device__ __forceinline__ uint64_t sim_plain_div(uint64_t a, uint64_t d) {
 // with an atomic too, never through the L1, which those atomics leave stale.  Inbox slots
 // are written once with ordinary stores and read afterwards by another lane of the wavefront.
 __device__ __forceinline__ int32_t l2_read(int32_t *p) {
-    // times are never negative, so the maximum with 0 changes nothing; unlike "add 0" it is
-    // not an operation the compiler may turn into a load
-    return __hip_atomic_fetch_max(p, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    // a device-scope load goes past the L1 like the atomics do, and unlike an atomic it writes nothing
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ int32_t inbox_load(const int32_t *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
