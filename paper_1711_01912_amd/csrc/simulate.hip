@@ -48,11 +48,12 @@ __device__ __forceinline__ uint64_t sim_plain_div(uint64_t a, uint64_t d) {
 }
 
 // All lanes of a partition sit in one wavefront, so everything they exchange passes through
-// one compute unit's vector L1 and one L2; no wider scope is ever needed (a release at device
-// scope would write the L2 back on every step).  Ready times and open-input counts are only
-// touched by read-modify-write atomics, which execute in the L2: a ready time is read back
-// with an atomic too, never through the L1, which those atomics leave stale.  Inbox slots
-// are written once with ordinary stores and read afterwards by another lane of the wavefront.
+// one compute unit's vector L1 and one L2; no fence wider than the workgroup is ever needed (a
+// release at device scope would write the L2 back on every step).  Ready times and open-input
+// counts are only changed by read-modify-write atomics, which execute in the L2 and leave the
+// L1 stale: a ready time is read back with a load of device scope, which goes past the L1.
+// Inbox slots are written once with ordinary stores and read afterwards by another lane of
+// the wavefront.
 __device__ __forceinline__ int32_t l2_read(int32_t *p) {
     // a device-scope load goes past the L1 like the atomics do, and unlike an atomic it writes nothing
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
