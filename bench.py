@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X, published
 # copy: x2.00 and x1.00).  The figure belongs to one build of the kernel: it is reported only
 # while the sources it was taken on are unchanged, and for the configuration it was taken on.
 MEASURED_TRAFFIC = {
-    "sources_sha256": "f943be48956ba8c57d71be8236965b654141379c571a53697f4c94e22a1fdcc2",
+    "sources_sha256": "7d812f0406134d5d295dc4081a661d9d454cb87f92326121f0b6594ea22bea40",
     "workload": "large_sparse", "P": 256, "plan": 2, "out_layout": 1,
     "bytes_per_blevel_launch": (2 * 227708 + 1000002) * 1024,
 }
