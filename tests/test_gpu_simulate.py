@@ -293,3 +293,27 @@ def test_hub_rows_in_shared_wavefronts(gpu, oracle):
     a = rng.integers(0, k, size=(16400, n)).astype(np.uint8)
     w = _finish("hub", csr, rng.integers(1, 60, size=n), k, rng.integers(1, 9, size=k), rng.integers(1, 9, size=(k, k)), a)
     _check(gpu, oracle, w, layouts=(0,))
+
+
+def test_many_random_configurations(gpu, oracle):
+    """Sixty graphs with random shape, device count (1 .. 64), batch, weight ranges (zero transfer
+    volumes, equal weights, long minimum times), device models and layouts; all three policies."""
+    import torch
+    rng = np.random.default_rng(51)
+    for it in range(60):
+        layers, width = int(rng.integers(1, 40)), int(rng.integers(1, 50))
+        k = int(rng.choice([1, 2, 3, 5, 8, 13, 16, 21, 32, 33, 50, 64]))
+        P = int(rng.choice([1, 2, 7, 33, 64, 200]))
+        n, level, src, dst = random_layered_dag(rng, [width] * layers, 1, int(rng.integers(1, 9)), int(rng.integers(1, 6)))
+        cmax, tmax = int(rng.choice([1, 5, 100, 5000])), int(rng.choice([0, 1, 100, 20000]))
+        t = rng.integers(int(rng.integers(0, tmax + 1)), tmax + 1, size=len(src))
+        c = rng.integers(int(rng.integers(1, cmax + 1)), cmax + 1, size=n)
+        speeds = rng.integers(1, int(rng.choice([1, 3, 100])) + 1, size=k)
+        bw = rng.integers(1, int(rng.choice([1, 4, 60])) + 1, size=(k, k))
+        a = rng.integers(0, k, size=(P, n)).astype(np.uint8)
+        if rng.random() < 0.2:
+            a[:, :] = a[:, :1]          # one device per partition
+        w = _finish("random", build_csr(n, src, dst, t, level), c, k, speeds, bw, a)
+        if it % 20 == 0:
+            _say(f"cp_simulate random configuration {it}: n={n} k={k} P={P}")
+        _check(gpu, oracle, w, tie_seed=it, layouts=(int(rng.integers(0, 2)),), what=f"random configuration {it}")
