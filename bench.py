@@ -184,6 +184,20 @@ def main():
         ms = timed(lambda: cpe.cp_critical_path(g, a, w.speeds, w.bandwidth, out["b"], out["cp"],
                                                 b_layout=b_layout, check_status=False))
         extras["critical_path"] = {"ms": ms}
+        if w.k <= 64:
+            # the paper's Critical Path partition as a start, then three moves of the search
+            t0 = time.perf_counter()
+            seed = cpe.cp_seed_partition(g, w.speeds)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            found = cpe.cp_search(g, seed, w.speeds, w.bandwidth, max_moves=3, chunk=256)
+            torch.cuda.synchronize()
+            t2 = time.perf_counter()
+            extras["seed_partition"] = {"ms": (t1 - t0) * 1e3}
+            extras["search"] = {"ms": (t2 - t1) * 1e3, "moves": int(len(found["moves"])),
+                                "evaluated": int(found["evaluated"]),
+                                "relaxations_per_s": float(found["evaluated"]) * m / (t2 - t1),
+                                "cp_trace": [int(x) for x in found["cp_trace"]]}
         if w.k <= 64 and int(w.c.min()) >= 1:
             # the list-scheduling simulation under both policies, and the oracle's on a few partitions
             from oracle import cp_oracle
