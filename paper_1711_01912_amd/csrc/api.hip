@@ -96,9 +96,10 @@ bool window_preferred(const Packed &p, const WindowCfg &cb, const WindowCfg &ct,
                       size_t tick_bytes) {
     const double cus = 256.0;
     auto sweep_us = [&](const WindowDir &d, const WindowCfg &c) {
-        const double per_cu = std::max<double>(1.0, std::min<double>(
-            (double)(kLdsBudget / std::max<size_t>(c.lds_bytes, 1)), 32.0 / (c.nc + c.nlw + c.nfw)));
-        const double rounds = std::ceil((double)batch / (cus * std::floor(per_cu)));
+        const int groups = std::max(1, c.groups);         // partitions per workgroup
+        const double wg_per_cu = std::max<double>(1.0, std::floor(std::min<double>(
+            (double)(kLdsBudget / std::max<size_t>(c.lds_bytes, 1)), 32.0 / (groups * (c.nc + c.nlw + c.nfw)))));
+        const double rounds = std::ceil((double)batch / (cus * wg_per_cu * groups));
         return rounds * (double)d.ticks * (0.58 + 0.03 * d.smax);
     };
     const double window_us = sweep_us(p.win_b, cb) + sweep_us(p.win_t, ct);

@@ -22,6 +22,7 @@ constexpr uint64_t kWindowTickBytes = 15 * 1024;   // packet bytes per tick, unl
 constexpr int kWindowFarTicks = 12;      // a neighbour this many ticks back (or more) is read from the output array
 constexpr int kWindowFarLead = 4;        // ticks a far wavefront runs ahead (twice: read list, then gather)
 constexpr int kWindowMaxFarWaves = 4;    // 64 far reads per tick each
+constexpr int kWindowMaxGroups = 8;     // partitions one workgroup may hold
 constexpr int kMaskWords = 72;           // 32-bit mask words one tick's id range may touch (fused mask)
 
 inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }

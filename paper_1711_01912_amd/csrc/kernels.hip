@@ -479,18 +479,26 @@ struct WindowArgs {
     int32_t far_cap;           // far reads per tick (multiple of 64), 0 = none
     int32_t nfw;               // far wavefronts (after the loaders)
     int32_t stores_per_tick;   // output stores one compute wavefront issues per tick
+    // several partitions per workgroup (they share the cost tables in LDS)
+    int32_t groups;            // partitions per workgroup
+    int32_t wgs;               // workgroups that have partitions
+    uint32_t sub_bytes;        // LDS of one partition: ring, far pairs, two stage slots
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // stays in registers when indexed statically
 typedef const uint32_t __attribute__((address_space(4))) *const_u32_ptr;   // uniform reads become scalar loads
 
-// LDS layout: [ring][cost tables][2 stage slots]; a stage slot is
+// LDS layout: per partition of the workgroup [ring][far pairs][2 stage slots], then the cost
+// tables, which the partitions share; a stage slot is
 // [wpad bytes of device ids][packet], NL*nlw*1024 bytes in all.  The ring is
 // either (slots+1) x {value, device*8} (PACKED: one 8-byte read per relaxation, and
 // an entry's ring field is the byte offset itself) or (slots+1) values followed by
 // (slots+1) device bytes.
 //
-// Wavefronts 0..nc-1 compute, wavefronts nc..nc+nlw-1 load.  Tick t: after the
+// Of a partition's wavefronts, 0..nc-1 compute and nc..nc+nlw-1 load.  A workgroup holds
+// `groups` partitions side by side (small workgroups with large cost tables: more partitions
+// per compute unit); they run tick by tick together, which costs nothing since the graph, and
+// so the number of ticks, is the same for all.  Tick t: after the
 // barrier the compute wavefronts relax level t out of stage slot t&1 while the
 // loaders copy packet t+1 (requested DR ticks earlier, held in registers) into
 // the other slot and request packet t+1+DR.  Nothing on the level-to-level
@@ -500,35 +508,43 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
     extern __shared__ uint4 lds16[];
     __shared__ long long red[kWindowMaxWaves];
     // MASK: bits of the tick's critical vertices, by (v - (lo & ~31)) / 32; two ticks in flight
-    __shared__ uint32_t mbits[MASK ? 2 : 1][MASK ? kMaskWords : 1];
-    uint8_t *lds = (uint8_t *)lds16;
+    __shared__ uint32_t mbits[MASK ? kWindowMaxGroups : 1][MASK ? 2 : 1][MASK ? kMaskWords : 1];
     const int tid = threadIdx.x, lane = tid & 63, nt = blockDim.x;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wps = a.nc + a.nlw + a.nfw;                 // wavefronts of one partition
+    const int sub = wave_all / wps;                       // which of the workgroup's partitions
+    const int wave = wave_all - sub * wps;                // role index inside it
+    uint8_t *lds = (uint8_t *)lds16 + (size_t)sub * a.sub_bytes;
     const int k = a.k, L = a.L, R = a.slots;
 
     // blockIdx -> partition: blocks are dealt round-robin to the 8 XCDs; give each
     // XCD a run of consecutive partitions so that the 4-byte stores of one output
     // line meet in one L2
-    const int32_t q = (int32_t)(blockIdx.x % 8) * a.pgroups + (int32_t)(blockIdx.x / 8);
-    if (q >= a.P) return;      // whole workgroup: no barrier has been reached yet
+    const int32_t wg = (int32_t)(blockIdx.x % 8) * a.pgroups + (int32_t)(blockIdx.x / 8);
+    if (wg >= a.wgs) return;   // whole workgroup: no barrier has been reached yet
+    // a last workgroup that is not full repeats its last partition (same values to the same
+    // places) so that every wavefront meets every barrier
+    const int32_t q = min(wg * a.groups + sub, a.P - 1);
 
     const uint32_t ring_bytes = (uint32_t)((((size_t)R + 1) * (PACKED ? 8 : sizeof(Tick) + 1) + 15) & ~(size_t)15);
     const uint32_t tab_bytes = (uint32_t)((sizeof(Magic) * ((size_t)k * k + k) + 15) & ~(size_t)15);
     Tick *ring_val = (Tick *)lds;                                  // split layout
     uint8_t *ring_dev = lds + sizeof(Tick) * ((size_t)R + 1);
     const uint32_t far_bytes = FAR ? 8u * (uint32_t)a.far_cap : 0u;   // per tick parity, behind the ring
-    const uint32_t etab_off = ring_bytes + 2u * far_bytes;         // byte offsets inside LDS
+    // byte offsets from this partition's LDS: the shared tables lie behind the last partition
+    const uint32_t etab_off = (uint32_t)(a.groups - sub) * a.sub_bytes;
     const uint32_t vtab_off = etab_off + 8u * (uint32_t)(k * k);
     const int slot_bytes = NL * a.nlw * 1024;
-    uint8_t *stage = lds + etab_off + tab_bytes;
+    uint8_t *stage = lds + ring_bytes + 2u * far_bytes;
+    (void)tab_bytes;
     {
         const uint64_t *e = (const uint64_t *)a.edge_tab, *v = (const uint64_t *)a.vert_tab;
         uint64_t *t64 = (uint64_t *)(lds + etab_off);
         for (int i = tid; i < k * k; i += nt) t64[i] = e[i];
         for (int i = tid; i < k; i += nt) t64[k * k + i] = v[i];
         if constexpr (MASK)
-            for (int i = tid; i < 2 * kMaskWords; i += nt) (&mbits[0][0])[i] = 0;
-        if (tid == 0) {                      // the constant-zero slot padding entries point at
+            for (int i = tid; i < kWindowMaxGroups * 2 * kMaskWords; i += nt) (&mbits[0][0][0])[i] = 0;
+        if (wave == 0 && lane == 0) {        // the constant-zero slot padding entries point at
             if (PACKED) {
                 ((uint2 *)lds)[R] = make_uint2(0, 0);
             } else {
@@ -654,10 +670,10 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
             const int words = (int)(((lo & 31u) + span + 31u) >> 5);
             uint32_t *dst = a.mask32 + (size_t)q * (size_t)a.mask_row32 + (lo >> 5);
             for (int w = lane; w < words; w += 64) {
-                const uint32_t bits = mbits[MASK ? (s_ & 1) : 0][MASK ? w : 0];
+                const uint32_t bits = mbits[MASK ? sub : 0][MASK ? (s_ & 1) : 0][MASK ? w : 0];
                 if (bits) {
                     atomicOr(dst + w, bits);
-                    mbits[MASK ? (s_ & 1) : 0][MASK ? w : 0] = 0;
+                    mbits[MASK ? sub : 0][MASK ? (s_ & 1) : 0][MASK ? w : 0] = 0;
                 }
             }
         };
@@ -753,7 +769,7 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
                 if constexpr (MASK) {        // tl(v) + b(v) = CP marks a critical vertex
                     if ((Tick)(acc + bv) == cpq) {
                         const uint32_t rel = v - (lo & ~31u);
-                        atomicOr(&mbits[cur_tick & 1][rel >> 5], 1u << (rel & 31u));
+                        atomicOr(&mbits[sub][cur_tick & 1][rel >> 5], 1u << (rel & 31u));
                     }
                 }
             }
@@ -868,13 +884,13 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
         if (MASK) lds_barrier();             // pairs with the loaders' barrier before the last flush
     }
 
-    if (a.cp_out) {   // workgroup maximum
+    if (a.cp_out) {   // the partition's maximum
         long long b64 = (long long)best;
         for (int off = 32; off > 0; off >>= 1) b64 = max(b64, __shfl_xor(b64, off));
-        if (lane == 0) red[wave] = b64;
+        if (lane == 0) red[wave_all] = b64;
         lds_barrier();
-        if (tid == 0) {
-            for (int w2 = 1; w2 < a.nc; ++w2) b64 = max(b64, red[w2]);
+        if (wave == 0 && lane == 0) {
+            for (int w2 = 1; w2 < a.nc; ++w2) b64 = max(b64, red[sub * wps + w2]);
             a.cp_out[q] = b64;
         }
     }
@@ -947,7 +963,11 @@ int launch_window_sweep_k(const SweepLaunch &s, const WindowCfg &cfg, hipStream_
     a.out32 = s.n < (1 << 24) && s.P < (1 << 24) && (uint64_t)s.n * (uint64_t)s.P < (1ull << 31);
     a.out_sq = s.out_sq;
     a.out_sv = (uint32_t)s.out_sv;
-    a.pgroups = (s.P + 7) / 8;
+    a.groups = std::max(1, cfg.groups);
+    a.wgs = (s.P + a.groups - 1) / a.groups;
+    a.pgroups = (a.wgs + 7) / 8;
+    a.sub_bytes = (uint32_t)cfg.sub_bytes;
+    a.nfw = 0;
     if (MASK) {
         a.bvals = s.mask_b;
         a.cp_in = s.mask_cp;
@@ -972,8 +992,8 @@ int launch_window_sweep_k(const SweepLaunch &s, const WindowCfg &cfg, hipStream_
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)cfg.lds_bytes);
         if (e != hipSuccess) return CP_ERR_HIP;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)(8 * a.pgroups)), dim3((cfg.nc + cfg.nlw + (FAR ? cfg.nfw : 0)) * 64),
-                       cfg.lds_bytes, st, a);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(8 * a.pgroups)),
+                       dim3(a.groups * (cfg.nc + cfg.nlw + (FAR ? cfg.nfw : 0)) * 64), cfg.lds_bytes, st, a);
     return hip_ok(hipGetLastError());
 }
 
@@ -1020,6 +1040,10 @@ bool window_config(const WindowDir &d, int32_t k, size_t tick_bytes, size_t lds_
                    bool with_mask) {
     if (d.packed && tick_bytes != 4) return false;
     if (with_mask && d.far_cap > 0) return false;
+    // the mask variant's static LDS: the bits of two ticks for every partition of the workgroup
+    const size_t mask_static = with_mask ? (size_t)kWindowMaxGroups * 2 * kMaskWords * 4 : 0;
+    if (lds_limit <= mask_static) return false;
+    lds_limit -= mask_static;
     const int nfw = d.far_cap / kWave;                  // far wavefronts, 64 far reads per tick each
     // a tick's id range may touch (31 + span + 31) / 32 mask words
     if (with_mask && (!d.packed || !d.direct_ok || (d.idpad + 62) / 32 > kMaskWords)) return false;
@@ -1040,7 +1064,9 @@ bool window_config(const WindowDir &d, int32_t k, size_t tick_bytes, size_t lds_
         c.dr = nl <= 2 ? 8 : (nl == 3 ? 5 : (nl == 4 ? 4 : 2));
         c.nc = std::max(1, std::min(d.smax, kWindowMaxWaves - (int)nlw - nfw));
         c.packed = d.packed;
-        c.lds_bytes = ring + tab + (size_t)2 * nl * nlw * 1024;
+        c.sub_bytes = ring + (size_t)2 * nl * nlw * 1024;
+        c.groups = 1;
+        c.lds_bytes = c.sub_bytes + tab;
         if (c.lds_bytes > lds_limit) continue;
         // The first shape that fits (most ticks of prefetch) is the one for a workgroup that
         // fills a compute unit.  A small workgroup shares the unit with others: there fewer
@@ -1054,7 +1080,27 @@ bool window_config(const WindowDir &d, int32_t k, size_t tick_bytes, size_t lds_
             out = c;
         }
     }
-    return found;
+    if (!found) return false;
+    // Several partitions per workgroup share one copy of the cost tables.  That pays when the
+    // tables are a large part of a small workgroup's LDS (many devices, a narrow graph): more
+    // partitions fit a compute unit.  Taken when it raises that number by a quarter or more.
+    const int wps = out.nc + out.nlw + out.nfw;
+    auto per_cu = [&](int g) {
+        const size_t lds = (size_t)g * out.sub_bytes + tab + mask_static + 512;
+        const size_t by_lds = kLdsBudget / lds, by_waves = (size_t)(32 / (g * wps));
+        return (size_t)g * std::min(by_lds, by_waves);
+    };
+    size_t best = per_cu(1);
+    for (int g = 2; g <= kWindowMaxGroups && g * wps <= kWindowMaxWaves; g *= 2) {
+        if ((size_t)g * out.sub_bytes + tab > lds_limit) break;
+        const size_t here = per_cu(g);
+        if (4 * here >= 5 * best) {
+            best = here;
+            out.groups = g;
+        }
+    }
+    out.lds_bytes = (size_t)out.groups * out.sub_bytes + tab;
+    return true;
 }
 
 int launch_gather_assign(const SweepLaunch &s, uint8_t *out, void *stream) {

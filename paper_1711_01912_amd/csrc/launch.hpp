@@ -44,7 +44,9 @@ struct WindowCfg {
     int nfw = 0;       // far wavefronts
     int dr = 0;        // levels a loader runs ahead in registers
     bool packed = false;   // ring holds {value, device} pairs (one LDS read per relaxation)
-    size_t lds_bytes = 0;
+    int groups = 1;        // partitions per workgroup (they share the cost tables)
+    size_t sub_bytes = 0;  // LDS of one partition: ring, far pairs, two stage slots
+    size_t lds_bytes = 0;  // of the workgroup: groups * sub_bytes + tables
 };
 
 // False if the direction cannot run under `lds_limit` bytes of LDS.
