@@ -92,16 +92,18 @@ size_t device_window_lds_limit() {
 // as many workgroups as fit one unit's LDS at a time (about 0.6 us per tick plus
 // 0.045 us per slice); the wave-column plan pays about 6.3 us per level launch plus
 // its gathers at about 4 TB/s.
+double window_sweep_us(const WindowDir &d, const WindowCfg &c, int32_t batch) {
+    const double cus = 256.0;
+    const int groups = std::max(1, c.groups);         // partitions per workgroup
+    const double wg_per_cu = std::max<double>(1.0, std::floor(std::min<double>(
+        (double)(kLdsBudget / std::max<size_t>(c.lds_bytes, 1)), 32.0 / (groups * (c.nc + c.nlw + c.nfw)))));
+    const double rounds = std::ceil((double)batch / (cus * wg_per_cu * groups));
+    return rounds * (double)d.ticks * (0.58 + 0.03 * d.smax);
+}
+
 bool window_preferred(const Packed &p, const WindowCfg &cb, const WindowCfg &ct, int32_t batch,
                       size_t tick_bytes) {
-    const double cus = 256.0;
-    auto sweep_us = [&](const WindowDir &d, const WindowCfg &c) {
-        const int groups = std::max(1, c.groups);         // partitions per workgroup
-        const double wg_per_cu = std::max<double>(1.0, std::floor(std::min<double>(
-            (double)(kLdsBudget / std::max<size_t>(c.lds_bytes, 1)), 32.0 / (groups * (c.nc + c.nlw + c.nfw)))));
-        const double rounds = std::ceil((double)batch / (cus * wg_per_cu * groups));
-        return rounds * (double)d.ticks * (0.58 + 0.03 * d.smax);
-    };
+    auto sweep_us = [&](const WindowDir &d, const WindowCfg &c) { return window_sweep_us(d, c, batch); };
     const double window_us = sweep_us(p.win_b, cb) + sweep_us(p.win_t, ct);
     auto column_us = [&](const ColumnDir &d) {
         double launches = 0;
@@ -412,10 +414,21 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
     // With rows per partition the t sweep can write the mask as it goes: it needs the tick's b
     // values staged like the device ids (16-byte loads that must stay inside the b array).
     WindowCfg cfg_tm;
-    const bool fuse_mask = use == CP_PLAN_RESIDENT_WINDOW && by_partition && mask_out && direct_t &&
-                           tick_dtype == CP_TICK_I32 && ((uintptr_t)blevel_out % 16) == 0 &&
-                           ((uint64_t)p.n * (uint64_t)batch * 4) % 16 == 0 &&
-                           window_config(p.win_t, k, (size_t)tick_dtype, device_window_lds_limit(), cfg_tm, true);
+    bool fuse_mask = use == CP_PLAN_RESIDENT_WINDOW && by_partition && mask_out && direct_t &&
+                     tick_dtype == CP_TICK_I32 && ((uintptr_t)blevel_out % 16) == 0 &&
+                     ((uint64_t)p.n * (uint64_t)batch * 4) % 16 == 0 &&
+                     window_config(p.win_t, k, (size_t)tick_dtype, device_window_lds_limit(), cfg_tm, true);
+    if (fuse_mask) {
+        // The mask variant costs a little per slice (one more LDS read and a compare) and a fixed
+        // amount per tick.  On wide ticks that is far less than a streaming pass over b and tl
+        // afterwards (large sparse workload: +0.15 ms against 0.51 ms); on ticks of one or two
+        // slices the fixed part outweighs it (5,271 vertices in 251 ticks, 16,384 partitions:
+        // +0.70 ms against 0.25 ms).  The same holds where fewer partitions would fit a compute
+        // unit with it.
+        const double mask_pass_us = 5.0 + (double)p.n * batch * (2.0 * tick_dtype + 0.125) / 3.0e6;
+        fuse_mask = p.win_t.smax >= 4 &&
+                    window_sweep_us(p.win_t, cfg_tm, batch) <= window_sweep_us(p.win_t, cfg_t, batch) + mask_pass_us;
+    }
     if (use == CP_PLAN_RESIDENT_WINDOW) {
         if ((blevel_out || cp_out) && !direct_b) {
             s.win = &p.win_b;
