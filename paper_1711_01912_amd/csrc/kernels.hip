@@ -508,11 +508,13 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
     extern __shared__ uint4 lds16[];
     __shared__ long long red[kWindowMaxWaves];
     // MASK: bits of the tick's critical vertices, by (v - (lo & ~31)) / 32; two ticks in flight
-    __shared__ uint32_t mbits[MASK ? kWindowMaxGroups : 1][MASK ? 2 : 1][MASK ? kMaskWords : 1];
+    __shared__ uint32_t mbits[MASK ? 2 : 1][MASK ? kMaskWords : 1];
     const int tid = threadIdx.x, lane = tid & 63, nt = blockDim.x;
     const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wps = a.nc + a.nlw + a.nfw;                 // wavefronts of one partition
-    const int sub = wave_all / wps;                       // which of the workgroup's partitions
+    // which of the workgroup's partitions (the variant that writes the mask runs one per
+    // workgroup: its addresses stay compile-time constants)
+    const int sub = MASK ? 0 : wave_all / wps;
     const int wave = wave_all - sub * wps;                // role index inside it
     uint8_t *lds = (uint8_t *)lds16 + (size_t)sub * a.sub_bytes;
     const int k = a.k, L = a.L, R = a.slots;
@@ -543,7 +545,7 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
         for (int i = tid; i < k * k; i += nt) t64[i] = e[i];
         for (int i = tid; i < k; i += nt) t64[k * k + i] = v[i];
         if constexpr (MASK)
-            for (int i = tid; i < kWindowMaxGroups * 2 * kMaskWords; i += nt) (&mbits[0][0][0])[i] = 0;
+            for (int i = tid; i < 2 * kMaskWords; i += nt) (&mbits[0][0])[i] = 0;
         if (wave == 0 && lane == 0) {        // the constant-zero slot padding entries point at
             if (PACKED) {
                 ((uint2 *)lds)[R] = make_uint2(0, 0);
@@ -670,10 +672,10 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
             const int words = (int)(((lo & 31u) + span + 31u) >> 5);
             uint32_t *dst = a.mask32 + (size_t)q * (size_t)a.mask_row32 + (lo >> 5);
             for (int w = lane; w < words; w += 64) {
-                const uint32_t bits = mbits[MASK ? sub : 0][MASK ? (s_ & 1) : 0][MASK ? w : 0];
+                const uint32_t bits = mbits[MASK ? (s_ & 1) : 0][MASK ? w : 0];
                 if (bits) {
                     atomicOr(dst + w, bits);
-                    mbits[MASK ? sub : 0][MASK ? (s_ & 1) : 0][MASK ? w : 0] = 0;
+                    mbits[MASK ? (s_ & 1) : 0][MASK ? w : 0] = 0;
                 }
             }
         };
@@ -769,7 +771,7 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
                 if constexpr (MASK) {        // tl(v) + b(v) = CP marks a critical vertex
                     if ((Tick)(acc + bv) == cpq) {
                         const uint32_t rel = v - (lo & ~31u);
-                        atomicOr(&mbits[sub][cur_tick & 1][rel >> 5], 1u << (rel & 31u));
+                        atomicOr(&mbits[cur_tick & 1][rel >> 5], 1u << (rel & 31u));
                     }
                 }
             }
@@ -1040,8 +1042,8 @@ bool window_config(const WindowDir &d, int32_t k, size_t tick_bytes, size_t lds_
                    bool with_mask) {
     if (d.packed && tick_bytes != 4) return false;
     if (with_mask && d.far_cap > 0) return false;
-    // the mask variant's static LDS: the bits of two ticks for every partition of the workgroup
-    const size_t mask_static = with_mask ? (size_t)kWindowMaxGroups * 2 * kMaskWords * 4 : 0;
+    // the mask variant's static LDS: the bits of two ticks
+    const size_t mask_static = with_mask ? (size_t)2 * kMaskWords * 4 : 0;
     if (lds_limit <= mask_static) return false;
     lds_limit -= mask_static;
     const int nfw = d.far_cap / kWave;                  // far wavefronts, 64 far reads per tick each
@@ -1083,7 +1085,8 @@ bool window_config(const WindowDir &d, int32_t k, size_t tick_bytes, size_t lds_
     if (!found) return false;
     // Several partitions per workgroup share one copy of the cost tables.  That pays when the
     // tables are a large part of a small workgroup's LDS (many devices, a narrow graph): more
-    // partitions fit a compute unit.  Taken when it raises that number by a quarter or more.
+    // partitions fit a compute unit.  Taken when it raises that number by a quarter or more
+    // (never by the variant that writes the mask, which is for wide ticks).
     const int wps = out.nc + out.nlw + out.nfw;
     auto per_cu = [&](int g) {
         const size_t lds = (size_t)g * out.sub_bytes + tab + mask_static + 512;
@@ -1091,7 +1094,7 @@ bool window_config(const WindowDir &d, int32_t k, size_t tick_bytes, size_t lds_
         return (size_t)g * std::min(by_lds, by_waves);
     };
     size_t best = per_cu(1);
-    for (int g = 2; g <= kWindowMaxGroups && g * wps <= kWindowMaxWaves; g *= 2) {
+    for (int g = 2; !with_mask && g <= kWindowMaxGroups && g * wps <= kWindowMaxWaves; g *= 2) {
         if ((size_t)g * out.sub_bytes + tab > lds_limit) break;
         const size_t here = per_cu(g);
         if (4 * here >= 5 * best) {
