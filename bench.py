@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X, published
 # copy: x2.00 and x1.00).  The figure belongs to one build of the kernel: it is reported only
 # while the sources it was taken on are unchanged, and for the configuration it was taken on.
 MEASURED_TRAFFIC = {
-    "sources_sha256": "0252dfadec5759453ca2e8ea128ead38afb585c9d64fc65d86ed392f9783344b",
+    "sources_sha256": "c74d24cd7434bc20aa18948b397e2f3c6d4f2df17a1454c7cdfe469598f90825",
     "workload": "large_sparse", "P": 256, "plan": 2, "out_layout": 1,
     "bytes_per_blevel_launch": (2 * 227704 + 1000002) * 1024,
 }
