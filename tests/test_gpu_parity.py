@@ -174,6 +174,14 @@ def test_paper_parameter_ranges_fifty_devices(gpu, oracle):
     _check(gpu, oracle, w)
 
 
+def test_partitions_sharing_a_workgroup(gpu, oracle):
+    """Large cost tables beside a small ring: the window plan puts several partitions into one
+    workgroup.  A batch that does not fill the last workgroup, both layouts, both sweeps."""
+    for P in (37, 130):
+        w = make_workload("paper_scale", P=P)
+        _check(gpu, oracle, w, plans=(WINDOW,), layouts=(0, 1), what=f"paper_scale P={P}")
+
+
 def test_many_devices_take_the_plain_division_path(gpu, oracle):
     """k = 200 exceeds the LDS-table limit: plain divisors from global memory."""
     rng = np.random.default_rng(4)
