@@ -29,11 +29,11 @@ HBM_PEAK_GBS = 8000.0  # MI355X, published
 # copy: x2.00 and x1.00).  The figure belongs to one build of the kernel: it is reported only
 # while the sources it was taken on are unchanged, and for the configuration it was taken on.
 MEASURED_TRAFFIC = {
-    "sources_sha256": "c74d24cd7434bc20aa18948b397e2f3c6d4f2df17a1454c7cdfe469598f90825",
+    "sources_sha256": "c5e7784db85eba3dc4e74d9fb4a2f306a5c9fc3bd2586fe6cb636ee6f82c6f9a",
     "workload": "large_sparse", "P": 256, "plan": 2, "out_layout": 1,
     "bytes_per_blevel_launch": (2 * 227704 + 1000002) * 1024,
 }
-TRAFFIC_SOURCES = ("kernels.hip", "graph.cpp", "cpeval_internal.hpp")     # the sweep kernels and the packet layout
+TRAFFIC_SOURCES = ("kernels.hip", "graph.cpp", "cpeval_internal.hpp", "device_math.hpp")     # the sweep kernels and the packet layout
 
 
 def measured_traffic(workload, P, plan, out_layout):

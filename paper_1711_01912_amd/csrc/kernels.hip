@@ -17,21 +17,13 @@
 
 #include <type_traits>
 
+#include "device_math.hpp"
 #include "launch.hpp"
 
 namespace cpeval {
 namespace {
 
 // ---------------------------------------------------------------- cost policies
-
-__device__ __forceinline__ uint32_t magic_div(uint32_t a, Magic mg) {
-    uint32_t nn = a + mg.dm1;
-    return (uint32_t)(((uint64_t)nn * mg.mul + nn) >> 32);
-}
-
-__device__ __forceinline__ uint64_t plain_div(uint64_t a, uint64_t d) {
-    return d ? (a + d - 1) / d : 0;
-}
 
 template <typename T>
 __device__ __forceinline__ T wave_bcast(T v, int src_lane);

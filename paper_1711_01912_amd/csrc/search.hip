@@ -14,6 +14,7 @@
 #include <vector>
 
 #include "cpeval_internal.hpp"
+#include "device_math.hpp"
 #include "launch.hpp"
 
 namespace cpeval {
@@ -127,14 +128,6 @@ __global__ void seed_path_kernel(SeedArgs a) {
         a.assign[a.path[i]] = (uint8_t)a.fastest;
 }
 
-// x of the lane a DPP control word names (a permutation inside each row of 16 lanes).
-template <int CTRL>
-__device__ __forceinline__ long long dpp_i64(long long x) {
-    const int lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)x, CTRL, 0xf, 0xf, false);
-    const int hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)((unsigned long long)x >> 32), CTRL, 0xf, 0xf, false);
-    return (long long)(((unsigned long long)(uint32_t)hi << 32) | (uint32_t)lo);
-}
-
 // Minimum over lanes 0 .. span-1 (span a power of two), valid in those lanes: inside a row
 // of 16 by register permutations (swap neighbours, swap pairs, mirror 8, mirror 16), across
 // rows by shuffles.
@@ -159,8 +152,7 @@ __global__ __launch_bounds__(64) void seed_greedy_kernel(SeedArgs a) {
     const Magic mg = a.mg[mine ? lane : 0];
     const uint64_t sp = (uint64_t)a.speed[mine ? lane : 0];
     auto cost = [&](uint64_t cv) -> long long {
-        return a.magic ? (long long)(uint32_t)((((uint64_t)((uint32_t)cv + mg.dm1)) * mg.mul + ((uint32_t)cv + mg.dm1)) >> 32)
-                       : (long long)((cv + sp - 1) / sp);
+        return a.magic ? (long long)magic_div((uint32_t)cv, mg) : (long long)plain_div(cv, sp);
     };
     // the critical path is placed first: its execution times on the fastest device
     long long load = 0;
@@ -171,8 +163,7 @@ __global__ __launch_bounds__(64) void seed_greedy_kernel(SeedArgs a) {
         long long part = 0;
         for (int32_t i = lane; i < len; i += 64) {
             const uint64_t cv = (uint64_t)c[a.path[i]];
-            part += a.magic ? (long long)(uint32_t)((((uint64_t)((uint32_t)cv + mf.dm1)) * mf.mul + ((uint32_t)cv + mf.dm1)) >> 32)
-                            : (long long)((cv + sf - 1) / sf);
+            part += a.magic ? (long long)magic_div((uint32_t)cv, mf) : (long long)plain_div(cv, sf);
         }
         for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
         if (lane == a.fastest) load = part;

@@ -23,6 +23,7 @@
 #include <cstdint>
 
 #include "cpeval_internal.hpp"
+#include "device_math.hpp"
 #include "launch.hpp"
 
 namespace cpeval {
@@ -31,21 +32,6 @@ namespace {
 
 constexpr uint32_t kNever = 0xffffffffu;
 constexpr int kWideRow = 32;      // out-edges from which a started vertex's row is shared out over the wavefront
-
-__device__ __forceinline__ uint32_t sim_magic_div(uint32_t a, Magic mg) {
-    uint32_t nn = a + mg.dm1;
-    return (uint32_t)(((uint64_t)nn * mg.mul + nn) >> 32);
-}
-
-// x of the lane a DPP control word names (a permutation inside each row of 16 lanes).
-template <int CTRL>
-__device__ __forceinline__ uint32_t dpp_u32(uint32_t x) {
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, false);
-}
-
-__device__ __forceinline__ uint64_t sim_plain_div(uint64_t a, uint64_t d) {
-    return d ? (a + d - 1) / d : 0;
-}
 
 // All lanes of a partition sit in one wavefront, so everything they exchange passes through
 // one compute unit's vector L1 and one L2; no fence wider than the workgroup is ever needed (a
@@ -360,8 +346,8 @@ __global__ __launch_bounds__(64) void simulate_kernel(SimArgs a) {
             else queue_refill(hp, pending);
             if (start) start[v] = (int32_t)T;
             ++done;
-            const uint32_t w = MAGIC ? sim_magic_div((uint32_t)cv, vtab_m[dev])
-                                     : (uint32_t)sim_plain_div((uint64_t)cv, (uint64_t)vtab_g[dev]);
+            const uint32_t w = MAGIC ? magic_div((uint32_t)cv, vtab_m[dev])
+                                     : (uint32_t)plain_div((uint64_t)cv, (uint64_t)vtab_g[dev]);
             free_at = T + w;
             // the out-edges four at a time, so that the dependent loads of four edges (successor,
             // its device, the table entry) and their atomics overlap; slots past the row's end
@@ -387,8 +373,8 @@ __global__ __launch_bounds__(64) void simulate_kernel(SimArgs a) {
                 for (int j = 0; j < 4; ++j) dz[j] = row[(int64_t)z[j] * asv];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const uint32_t x = MAGIC ? sim_magic_div((uint32_t)te[j], etab_m[dev * k + dz[j]])
-                                             : (uint32_t)sim_plain_div((uint64_t)te[j],
+                    const uint32_t x = MAGIC ? magic_div((uint32_t)te[j], etab_m[dev * k + dz[j]])
+                                             : (uint32_t)plain_div((uint64_t)te[j],
                                                                        (uint64_t)etab_g[dev * k + dz[j]]);
                     arrive[j] = free_at + x;
                 }
@@ -427,8 +413,8 @@ __global__ __launch_bounds__(64) void simulate_kernel(SimArgs a) {
                 const int32_t z = a.idx[e];
                 const WT te = wt[e];
                 const uint32_t dz = hrow[(int64_t)z * asv];
-                const uint32_t x = MAGIC ? sim_magic_div((uint32_t)te, etab_m[hdev * k + dz])
-                                         : (uint32_t)sim_plain_div((uint64_t)te, (uint64_t)etab_g[hdev * k + dz]);
+                const uint32_t x = MAGIC ? magic_div((uint32_t)te, etab_m[hdev * k + dz])
+                                         : (uint32_t)plain_div((uint64_t)te, (uint64_t)etab_g[hdev * k + dz]);
                 __hip_atomic_fetch_max(hready + z, (int32_t)(hfree + x), __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_WORKGROUP);
                 const int32_t before = __hip_atomic_fetch_add(hneed + z, -1, __ATOMIC_RELAXED,
