@@ -204,6 +204,39 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
             int tick_dtype, int out_layout, int plan, int32_t *status_out, cp_profile *profile);
 
 /*
+ * cp_eval for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and errors as cp_eval without `workspace`, `workspace_bytes` and
+ * `profile`.  The scratch memory is a fixed array of CP_STATIC_SCRATCH_BYTES bytes that is
+ * part of the library's device code (every GPU the library runs on holds one until the
+ * process ends), and the cost tables travel as kernel arguments, so the call allocates
+ * nothing, copies nothing through the copy engine and records no memset.  (The array's
+ * device address is looked up on the first call on a device; make that call outside a
+ * capture.)
+ *
+ * Limits: k <= CP_STATIC_MAX_K (CP_ERR_SIZE) and a workspace need of at most
+ * CP_STATIC_SCRATCH_BYTES (CP_ERR_WORKSPACE).  The need is the cost tables
+ * ((2k^2 + k) * 8 bytes) plus, depending on how the call goes: n * batch bytes when the
+ * wave-column plan reads partition-major assignments; 2 * n * batch ticks more when it
+ * writes partition-major outputs; the device ids in sweep order (about n * batch bytes per
+ * sweep) when the resident-window plan cannot read them straight from the caller's rows
+ * (vertex-major assignments, rows not 16-byte aligned, or a graph whose levels are
+ * scattered over the vertex numbers).  A resident-window call on aligned partition-major
+ * rows needs the tables only.
+ *
+ * All calls on one GPU share that GPU's array: calls that may overlap in time on one GPU
+ * (different streams or threads) race; serialise them or use cp_eval with distinct
+ * workspaces.  Nothing in the array has to survive between calls.
+ */
+#define CP_STATIC_SCRATCH_BYTES (32u << 20)
+#define CP_STATIC_MAX_K         64
+int cp_eval_static(const cp_graph *g, int32_t batch, int32_t k,
+                   const uint8_t *assignments, int assign_layout,
+                   const int64_t *speeds, const int64_t *bandwidth, void *stream,
+                   int64_t *cp_out, void *blevel_out, void *tlevel_out, uint64_t *mask_out,
+                   int tick_dtype, int out_layout, int plan, int32_t *status_out);
+
+/*
  * One critical path per partition (paper, section 3.2.2 "compute the critical path";
  * the paper leaves ties open).  Among all source-to-sink paths whose cost equals CP the
  * one with the lexicographically smallest vertex sequence is returned: it starts at the

@@ -24,6 +24,7 @@ from .binding import (  # noqa: F401
     cp_simulate,
     cp_validate,
     cp_eval,
+    cp_eval_static,
     error_string,
     load_library,
 )

@@ -26,7 +26,7 @@ STATUS_BAD_DEVICE_ID = 1
 
 EXPORTS = (
     "cp_graph_create", "cp_graph_get_info", "cp_graph_upload", "cp_graph_destroy",
-    "cp_eval_workspace_bytes", "cp_eval_choose_plan", "cp_eval", "cp_critical_path", "cp_ranks_workspace_bytes", "cp_ranks",
+    "cp_eval_workspace_bytes", "cp_eval_choose_plan", "cp_eval", "cp_eval_static", "cp_critical_path", "cp_ranks_workspace_bytes", "cp_ranks",
     "cp_pct_order_workspace_bytes", "cp_pct_order", "cp_validate",
     "cp_search_workspace_bytes", "cp_search", "cp_seed_workspace_bytes", "cp_seed_partition",
     "cp_simulate_workspace_bytes", "cp_simulate",
@@ -93,6 +93,9 @@ def load_library():
     lib.cp_eval.restype = C.c_int
     lib.cp_eval.argtypes = [vp, C.c_int32, C.c_int32, vp, C.c_int, i64p, i64p, vp, C.c_size_t, vp,
                             vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, vp, vp]
+    lib.cp_eval_static.restype = C.c_int
+    lib.cp_eval_static.argtypes = [vp, C.c_int32, C.c_int32, vp, C.c_int, i64p, i64p, vp,
+                                   vp, vp, vp, vp, C.c_int, C.c_int, C.c_int, vp]
     lib.cp_critical_path.restype = C.c_int
     lib.cp_critical_path.argtypes = [vp, C.c_int32, C.c_int32, vp, C.c_int, i64p, i64p, vp, vp, C.c_int, C.c_int,
                                      vp, C.c_size_t, vp, C.c_int32, vp, vp, vp]
@@ -301,7 +304,7 @@ def choose_plan(graph: CpGraph, batch: int, speeds, bandwidth, tick_bytes=None) 
 def cp_eval(graph: CpGraph, assignments, speeds, bandwidth, *, want=("cp", "b", "tl", "mask"),
             tick_bytes=None, plan=PLAN_AUTO, assign_layout=ASSIGN_PARTITION_MAJOR,
             out_layout=OUT_VERTEX_MAJOR, out=None, workspace=None, profile: CpProfile | None = None,
-            stream=None, check_status=True):
+            stream=None, check_status=True, static=False):
     """cp_eval on torch tensors.
 
     ``assignments``: uint8 CUDA tensor, [batch][n] (or [n][batch] with
@@ -311,7 +314,8 @@ def cp_eval(graph: CpGraph, assignments, speeds, bandwidth, *, want=("cp", "b", 
     ``out_layout=OUT_PARTITION_MAJOR``: [batch][n] and [batch][ceil(n/64)]); plus
     ``status`` (int32 tensor).  ``out`` may carry preallocated tensors under the same keys and
     ``workspace`` a preallocated uint8 tensor.  With ``check_status`` the stream
-    is synchronised and a bad device id raises.
+    is synchronised and a bad device id raises.  ``static=True`` goes through
+    ``cp_eval_static`` (the library's fixed scratch array instead of a workspace).
     """
     import torch
     lib = load_library()
@@ -352,25 +356,42 @@ def cp_eval(graph: CpGraph, assignments, speeds, bandwidth, *, want=("cp", "b", 
         out["mask"] = torch.empty((rows, (cols + 63) // 64), dtype=torch.int64, device=dev)
     if "status" not in out:
         out["status"] = torch.empty(1, dtype=torch.int32, device=dev)
-    if workspace is None:
-        workspace = torch.empty(workspace_bytes(graph, batch, k, assign_layout, plan, out_layout, tick_bytes),
-                                dtype=torch.uint8, device=dev)
     ptr = lambda key: C.c_void_p(out[key].data_ptr()) if key in want else C.c_void_p()
-    rc = lib.cp_eval(graph._handle, batch, k, C.c_void_p(assignments.data_ptr()), int(assign_layout),
-                     _np_ptr(s, C.c_int64), _np_ptr(bw, C.c_int64),
-                     C.c_void_p(workspace.data_ptr()), C.c_size_t(workspace.numel()), _stream_ptr(stream),
-                     ptr("cp"), ptr("b"), ptr("tl"), ptr("mask"), int(tick_bytes), int(out_layout), int(plan),
-                     C.c_void_p(out["status"].data_ptr()),
-                     C.c_void_p(profile._handle.value) if profile is not None else C.c_void_p())
-    if rc:
-        raise CpError(rc, "cp_eval")
-    out["_workspace"] = workspace  # keep it alive until the caller drops the result
+    if static:
+        assert workspace is None and profile is None
+        rc = lib.cp_eval_static(graph._handle, batch, k, C.c_void_p(assignments.data_ptr()), int(assign_layout),
+                                _np_ptr(s, C.c_int64), _np_ptr(bw, C.c_int64), _stream_ptr(stream),
+                                ptr("cp"), ptr("b"), ptr("tl"), ptr("mask"), int(tick_bytes), int(out_layout),
+                                int(plan), C.c_void_p(out["status"].data_ptr()))
+        if rc:
+            raise CpError(rc, "cp_eval_static")
+    else:
+        if workspace is None:
+            workspace = torch.empty(workspace_bytes(graph, batch, k, assign_layout, plan, out_layout, tick_bytes),
+                                    dtype=torch.uint8, device=dev)
+        rc = lib.cp_eval(graph._handle, batch, k, C.c_void_p(assignments.data_ptr()), int(assign_layout),
+                         _np_ptr(s, C.c_int64), _np_ptr(bw, C.c_int64),
+                         C.c_void_p(workspace.data_ptr()), C.c_size_t(workspace.numel()), _stream_ptr(stream),
+                         ptr("cp"), ptr("b"), ptr("tl"), ptr("mask"), int(tick_bytes), int(out_layout), int(plan),
+                         C.c_void_p(out["status"].data_ptr()),
+                         C.c_void_p(profile._handle.value) if profile is not None else C.c_void_p())
+        if rc:
+            raise CpError(rc, "cp_eval")
+        out["_workspace"] = workspace  # keep it alive until the caller drops the result
     if check_status:
         torch.cuda.synchronize(dev)
         st = int(out["status"].item())
         if st == STATUS_BAD_DEVICE_ID:
             raise ValueError("assignments holds a device id >= k")
     return out
+
+
+def cp_eval_static(graph: CpGraph, assignments, speeds, bandwidth, **kw):
+    """cp_eval_static on torch tensors: cp_eval without a workspace (the library's fixed
+    scratch array; the call itself allocates nothing on the device).  Same keywords as
+    cp_eval except ``workspace`` and ``profile``; pass ``out`` to keep torch from allocating
+    the results."""
+    return cp_eval(graph, assignments, speeds, bandwidth, static=True, **kw)
 
 
 def cp_critical_path(graph: CpGraph, assignments, speeds, bandwidth, b, cp, *,

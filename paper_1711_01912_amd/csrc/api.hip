@@ -59,6 +59,49 @@ int stage_and_copy(const void *src, size_t bytes, void *dst, hipStream_t st) {
     return CP_OK;
 }
 
+// Cost tables written by kernels whose arguments carry the values: no staging memory, no
+// copy engine.  One launch moves kTableChunkWords table entries.
+constexpr int kTableChunkWords = 448;                       // 3.5 KB of kernel arguments
+struct TableChunk { uint64_t v[kTableChunkWords]; };
+
+__global__ void table_write_kernel(TableChunk chunk, uint64_t *dst, int32_t count) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) dst[i] = chunk.v[i];
+}
+
+int write_tables_by_kernel(const void *src, size_t entries, void *dst, hipStream_t st) {
+    const uint64_t *from = (const uint64_t *)src;
+    uint64_t *to = (uint64_t *)dst;
+    for (size_t at = 0; at < entries; at += kTableChunkWords) {
+        TableChunk chunk;
+        const int32_t count = (int32_t)std::min<size_t>(kTableChunkWords, entries - at);
+        std::memcpy(chunk.v, from + at, (size_t)count * 8);
+        hipLaunchKernelGGL(table_write_kernel, dim3((count + 255) / 256), dim3(256), 0, st, chunk, to + at, count);
+    }
+    return hipGetLastError() == hipSuccess ? CP_OK : CP_ERR_HIP;
+}
+
+// Scratch memory of cp_eval_static: one array per GPU, part of the loaded code object, never
+// allocated or freed.  In host code the array's name is only a handle: the device address is
+// looked up once per device and kept.
+static __device__ __align__(256) uint8_t scratch[CP_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mu;
+
+int static_scratch(void **out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return CP_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return CP_ERR_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return CP_OK;
+}
+
 constexpr size_t kWindowLdsLimit = kLdsBudget - 256;   // room for the kernel's static LDS
 
 bool window_fits(const Packed &p, int32_t k, size_t tick_bytes, size_t limit = kWindowLdsLimit,
@@ -303,12 +346,15 @@ int cp_eval_choose_plan(const cp_graph *g, int32_t batch, int32_t k, const int64
     return CP_OK;
 }
 
-int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
-            const uint8_t *assignments, int assign_layout,
-            const int64_t *speeds, const int64_t *bandwidth,
-            void *workspace, size_t workspace_bytes, void *stream,
-            int64_t *cp_out, void *blevel_out, void *tlevel_out, uint64_t *mask_out,
-            int tick_dtype, int out_layout, int plan, int32_t *status_out, cp_profile *profile) {
+// Both entry points of the evaluation.  tables_by_kernel: the cost tables reach the device as
+// kernel arguments instead of through the pinned staging ring (nothing is allocated then).
+static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
+                    const uint8_t *assignments, int assign_layout,
+                    const int64_t *speeds, const int64_t *bandwidth,
+                    void *workspace, size_t workspace_bytes, void *stream,
+                    int64_t *cp_out, void *blevel_out, void *tlevel_out, uint64_t *mask_out,
+                    int tick_dtype, int out_layout, int plan, int32_t *status_out, cp_profile *profile,
+                    bool tables_by_kernel) {
     int rc = check_eval_sizes(g, batch, k, assign_layout, plan);
     if (rc) return rc;
     if (!assignments || !speeds || !bandwidth || !workspace || !status_out) return CP_ERR_NULL;
@@ -341,11 +387,22 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
     // the wave-column plan reads CP off the stored b-levels; the resident-window sweep keeps a running maximum
     if (cp_out && !blevel_out && (use != CP_PLAN_RESIDENT_WINDOW || p.win_b.far_cap > 0)) return CP_ERR_ARG;
 
-    // workspace
+    // Device ids reach the resident-window sweep either straight from the caller's rows
+    // (16-byte loads: the rows must be contiguous, and whole-buffer size and base must be
+    // multiples of 16 so that no load leaves the buffer) or gathered into sweep order first.
+    const bool rows_ok = assign_layout == CP_ASSIGN_PARTITION_MAJOR &&
+                         ((uint64_t)p.n * (uint64_t)batch) % 16 == 0 && ((uintptr_t)assignments % 16) == 0;
+    const bool direct_b = rows_ok && p.win_b.direct_ok, direct_t = rows_ok && p.win_t.direct_ok;
+    const bool gather_b = use == CP_PLAN_RESIDENT_WINDOW && (blevel_out || cp_out) && !direct_b;
+    const bool gather_t = use == CP_PLAN_RESIDENT_WINDOW && tlevel_out && !direct_t;
+
+    // workspace: only what this call uses (cp_eval_workspace_bytes is an upper bound over
+    // every way the call may go)
     const bool need_pT = use == CP_PLAN_WAVE_COLUMN && assign_layout == CP_ASSIGN_PARTITION_MAJOR;
     size_t need = tables_bytes(k) + (need_pT ? align_up((size_t)p.n * (size_t)batch) : 0);
-    if (use == CP_PLAN_RESIDENT_WINDOW)
-        need += pperm_bytes(p, p.win_b, batch) + pperm_bytes(p, p.win_t, batch);
+    const size_t pperm_b_bytes = gather_b ? pperm_bytes(p, p.win_b, batch) : 0;
+    const size_t pperm_t_bytes = gather_t ? pperm_bytes(p, p.win_t, batch) : 0;
+    need += pperm_b_bytes + pperm_t_bytes;
     const bool by_partition = out_layout == CP_OUT_PARTITION_MAJOR;
     const bool via_scratch = by_partition && use == CP_PLAN_WAVE_COLUMN;
     const size_t scratch_at = need;
@@ -355,7 +412,7 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
     uint8_t *d_tab = ws;
     uint8_t *d_pT = ws + tables_bytes(k);
     uint8_t *d_pperm_b = ws + tables_bytes(k);
-    uint8_t *d_pperm_t = d_pperm_b + pperm_bytes(p, p.win_b, batch);
+    uint8_t *d_pperm_t = d_pperm_b + pperm_b_bytes;
     // vertex-major sweep results of the wave-column plan when the caller wants rows per partition
     void *col_b = via_scratch && blevel_out ? (void *)(ws + scratch_at) : blevel_out;
     void *col_t = via_scratch && tlevel_out ? (void *)(ws + scratch_at + column_scratch_bytes(p, batch, tick_dtype))
@@ -380,7 +437,8 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
     rc = launch_clear(cp_out, batch, status_out, stream);
     if (rc) return rc;
     const void *tab_src = tabs.magic_ok ? (const void *)tabs.magic.data() : (const void *)tabs.divisor.data();
-    rc = stage_and_copy(tab_src, table_entries(k) * 8, d_tab, st);
+    rc = tables_by_kernel ? write_tables_by_kernel(tab_src, table_entries(k), d_tab, st)
+                          : stage_and_copy(tab_src, table_entries(k) * 8, d_tab, st);
     if (rc) return rc;
     const uint8_t *pT = assignments;
     if (need_pT) {
@@ -405,12 +463,6 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
     s.status = status_out;
     if (by_partition) { s.out_sv = 1; s.out_sq = p.n; }
     else { s.out_sv = batch; s.out_sq = 1; }
-    // Device ids reach the resident-window sweep either straight from the caller's rows
-    // (16-byte loads: the rows must be contiguous, and whole-buffer size and base must be
-    // multiples of 16 so that no load leaves the buffer) or gathered into sweep order first.
-    const bool rows_ok = assign_layout == CP_ASSIGN_PARTITION_MAJOR &&
-                         ((uint64_t)p.n * (uint64_t)batch) % 16 == 0 && ((uintptr_t)assignments % 16) == 0;
-    const bool direct_b = rows_ok && p.win_b.direct_ok, direct_t = rows_ok && p.win_t.direct_ok;
     // With rows per partition the t sweep can write the mask as it goes: it needs the tick's b
     // values staged like the device ids (16-byte loads that must stay inside the b array).
     WindowCfg cfg_tm;
@@ -429,17 +481,15 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
         fuse_mask = p.win_t.smax >= 4 &&
                     window_sweep_us(p.win_t, cfg_tm, batch) <= window_sweep_us(p.win_t, cfg_t, batch) + mask_pass_us;
     }
-    if (use == CP_PLAN_RESIDENT_WINDOW) {
-        if ((blevel_out || cp_out) && !direct_b) {
-            s.win = &p.win_b;
-            rc = launch_gather_assign(s, d_pperm_b, stream);
-            if (rc) return rc;
-        }
-        if (tlevel_out && !direct_t) {
-            s.win = &p.win_t;
-            rc = launch_gather_assign(s, d_pperm_t, stream);
-            if (rc) return rc;
-        }
+    if (gather_b) {
+        s.win = &p.win_b;
+        rc = launch_gather_assign(s, d_pperm_b, stream);
+        if (rc) return rc;
+    }
+    if (gather_t) {
+        s.win = &p.win_t;
+        rc = launch_gather_assign(s, d_pperm_t, stream);
+        if (rc) return rc;
     }
 
     // ---- stage: b-level sweep
@@ -508,6 +558,32 @@ int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
     CP_MARK(CP_NUM_STAGES);
 #undef CP_MARK
     return CP_OK;
+}
+
+int cp_eval(const cp_graph *g, int32_t batch, int32_t k,
+            const uint8_t *assignments, int assign_layout,
+            const int64_t *speeds, const int64_t *bandwidth,
+            void *workspace, size_t workspace_bytes, void *stream,
+            int64_t *cp_out, void *blevel_out, void *tlevel_out, uint64_t *mask_out,
+            int tick_dtype, int out_layout, int plan, int32_t *status_out, cp_profile *profile) {
+    return eval_run(g, batch, k, assignments, assign_layout, speeds, bandwidth, workspace, workspace_bytes, stream,
+                    cp_out, blevel_out, tlevel_out, mask_out, tick_dtype, out_layout, plan, status_out, profile,
+                    /*tables_by_kernel=*/false);
+}
+
+int cp_eval_static(const cp_graph *g, int32_t batch, int32_t k,
+                   const uint8_t *assignments, int assign_layout,
+                   const int64_t *speeds, const int64_t *bandwidth, void *stream,
+                   int64_t *cp_out, void *blevel_out, void *tlevel_out, uint64_t *mask_out,
+                   int tick_dtype, int out_layout, int plan, int32_t *status_out) {
+    if (k > CP_STATIC_MAX_K) return CP_ERR_SIZE;
+    void *ws = nullptr;
+    int rc = static_scratch(&ws);
+    if (rc) return rc;
+    // eval_run answers CP_ERR_WORKSPACE when the call needs more than the array holds
+    return eval_run(g, batch, k, assignments, assign_layout, speeds, bandwidth, ws, (size_t)CP_STATIC_SCRATCH_BYTES,
+                    stream, cp_out, blevel_out, tlevel_out, mask_out, tick_dtype, out_layout, plan, status_out,
+                    nullptr, /*tables_by_kernel=*/true);
 }
 
 int cp_critical_path(const cp_graph *g, int32_t batch, int32_t k,
