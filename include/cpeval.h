@@ -83,6 +83,8 @@ extern "C" {
 #define CP_PLAN_AUTO             0
 #define CP_PLAN_WAVE_COLUMN      1   /* one wavefront = one vertex x 64 partitions; one launch per level */
 #define CP_PLAN_RESIDENT_WINDOW  2   /* one workgroup = one partition; recent levels kept in LDS; one launch per sweep */
+#define CP_PLAN_SHARED_WINDOW_2  3   /* as 2, but one workgroup = 2 partitions behind one graph stream */
+#define CP_PLAN_SHARED_WINDOW_4  4   /* ... 4 partitions */
 
 /* stages of one cp_eval call, in the order they run; also the index into cp_profile_read's output */
 #define CP_STAGE_PREP    0   /* clear outputs, cost tables, assignment transpose */

@@ -12,6 +12,8 @@ from .binding import (  # noqa: F401
     OUT_VERTEX_MAJOR,
     PLAN_AUTO,
     PLAN_RESIDENT_WINDOW,
+    PLAN_SHARED_WINDOW_2,
+    PLAN_SHARED_WINDOW_4,
     PLAN_WAVE_COLUMN,
     POLICY_FIFO,
     POLICY_PCT,

@@ -103,6 +103,7 @@ int static_scratch(void **out) {
 }
 
 constexpr size_t kWindowLdsLimit = kLdsBudget - 256;   // room for the kernel's static LDS
+constexpr size_t kSharedStaticLds = 512;               // the shared-window kernel's static LDS beyond that
 
 bool window_fits(const Packed &p, int32_t k, size_t tick_bytes, size_t limit = kWindowLdsLimit,
                  WindowCfg *cfg_b = nullptr, WindowCfg *cfg_t = nullptr) {
@@ -110,6 +111,18 @@ bool window_fits(const Packed &p, int32_t k, size_t tick_bytes, size_t limit = k
     WindowCfg b, t;
     if (!window_config(p.win_b, k, tick_bytes, limit, b)) return false;
     if (!window_config(p.win_t, k, tick_bytes, limit, t)) return false;
+    if (cfg_b) *cfg_b = b;
+    if (cfg_t) *cfg_t = t;
+    return true;
+}
+
+// The shared-window kernel with `groups` partitions per workgroup, both directions.
+bool shared_fits(const Packed &p, int32_t k, size_t tick_bytes, int groups, size_t limit, SharedCfg *cfg_b,
+                 SharedCfg *cfg_t) {
+    if (!p.have_window || k > kMagicMaxK || tick_bytes != 4 || limit <= kSharedStaticLds) return false;
+    SharedCfg b, t;
+    if (!shared_config(p.win_b, k, groups, limit - kSharedStaticLds, b)) return false;
+    if (!shared_config(p.win_t, k, groups, limit - kSharedStaticLds, t)) return false;
     if (cfg_b) *cfg_b = b;
     if (cfg_t) *cfg_t = t;
     return true;
@@ -168,8 +181,7 @@ int check_eval_sizes(const cp_graph *g, int32_t batch, int32_t k, int assign_lay
     if (batch < 1 || k < 1 || k > 255) return CP_ERR_SIZE;
     if (assign_layout != CP_ASSIGN_PARTITION_MAJOR && assign_layout != CP_ASSIGN_VERTEX_MAJOR)
         return CP_ERR_ARG;
-    if (plan != CP_PLAN_AUTO && plan != CP_PLAN_WAVE_COLUMN && plan != CP_PLAN_RESIDENT_WINDOW)
-        return CP_ERR_ARG;
+    if (plan < CP_PLAN_AUTO || plan > CP_PLAN_SHARED_WINDOW_4) return CP_ERR_ARG;
     return CP_OK;
 }
 
@@ -311,11 +323,12 @@ int cp_eval_workspace_bytes(const cp_graph *g, int32_t batch, int32_t k, int ass
     // the wave-column plan reads device ids vertex-major; under CP_PLAN_AUTO it may be
     // the one that runs, whatever the graph prefers, if the cost model rules the other out
     size_t column = 0, window = 0;
-    if (assign_layout == CP_ASSIGN_PARTITION_MAJOR && plan != CP_PLAN_RESIDENT_WINDOW)
+    const bool may_column = plan == CP_PLAN_AUTO || plan == CP_PLAN_WAVE_COLUMN;
+    if (assign_layout == CP_ASSIGN_PARTITION_MAJOR && may_column)
         column = align_up((size_t)g->packed.n * (size_t)batch);
     // the wave-column plan sweeps vertex-major: partition-major outputs are transposed
     // out of two scratch arrays
-    if (out_layout == CP_OUT_PARTITION_MAJOR && plan != CP_PLAN_RESIDENT_WINDOW)
+    if (out_layout == CP_OUT_PARTITION_MAJOR && may_column)
         column += 2 * column_scratch_bytes(g->packed, batch, tick_dtype);
     // the resident-window plan gathers the device ids into sweep order, once per direction
     if (plan != CP_PLAN_WAVE_COLUMN && g->packed.have_window)
@@ -384,8 +397,16 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
         use = can_window && window_preferred(p, cfg_b, cfg_t, batch, (size_t)tick_dtype)
                   ? CP_PLAN_RESIDENT_WINDOW : CP_PLAN_WAVE_COLUMN;
     if (use == CP_PLAN_RESIDENT_WINDOW && !can_window) return CP_ERR_ARG;
-    // the wave-column plan reads CP off the stored b-levels; the resident-window sweep keeps a running maximum
-    if (cp_out && !blevel_out && (use != CP_PLAN_RESIDENT_WINDOW || p.win_b.far_cap > 0)) return CP_ERR_ARG;
+    // several partitions per workgroup behind one graph stream
+    SharedCfg sh_b, sh_t;
+    const bool shared = use == CP_PLAN_SHARED_WINDOW_2 || use == CP_PLAN_SHARED_WINDOW_4;
+    if (shared && (!tabs.magic_ok ||
+                   !shared_fits(p, k, (size_t)tick_dtype, use == CP_PLAN_SHARED_WINDOW_4 ? 4 : 2,
+                                device_window_lds_limit(), &sh_b, &sh_t)))
+        return CP_ERR_ARG;
+    const bool windowish = use == CP_PLAN_RESIDENT_WINDOW || shared;
+    // the wave-column plan reads CP off the stored b-levels; the window sweeps keep a running maximum
+    if (cp_out && !blevel_out && (!windowish || p.win_b.far_cap > 0)) return CP_ERR_ARG;
 
     // Device ids reach the resident-window sweep either straight from the caller's rows
     // (16-byte loads: the rows must be contiguous, and whole-buffer size and base must be
@@ -393,8 +414,8 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
     const bool rows_ok = assign_layout == CP_ASSIGN_PARTITION_MAJOR &&
                          ((uint64_t)p.n * (uint64_t)batch) % 16 == 0 && ((uintptr_t)assignments % 16) == 0;
     const bool direct_b = rows_ok && p.win_b.direct_ok, direct_t = rows_ok && p.win_t.direct_ok;
-    const bool gather_b = use == CP_PLAN_RESIDENT_WINDOW && (blevel_out || cp_out) && !direct_b;
-    const bool gather_t = use == CP_PLAN_RESIDENT_WINDOW && tlevel_out && !direct_t;
+    const bool gather_b = windowish && (blevel_out || cp_out) && !direct_b;
+    const bool gather_t = windowish && tlevel_out && !direct_t;
 
     // workspace: only what this call uses (cp_eval_workspace_bytes is an upper bound over
     // every way the call may go)
@@ -498,13 +519,18 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
         s.tsweep = false;
         s.dir = &p.col_b;
         s.win = &p.win_b;
-        s.val = use == CP_PLAN_RESIDENT_WINDOW ? blevel_out : col_b;
+        s.val = windowish ? blevel_out : col_b;
         s.edge_tab = d_tab;
-        s.cp_out = use == CP_PLAN_RESIDENT_WINDOW ? cp_out : nullptr;
+        s.cp_out = windowish ? cp_out : nullptr;
         s.pperm = d_pperm_b;
         s.direct_ids = direct_b;
-        rc = use == CP_PLAN_RESIDENT_WINDOW ? launch_window_sweep(s, cfg_b, stream, launches)
-                                            : launch_column_sweep(s, stream, launches);
+        if (shared) {
+            rc = launch_window_shared(s, sh_b, stream);
+            if (launches) launches[0] = 1;
+        } else {
+            rc = use == CP_PLAN_RESIDENT_WINDOW ? launch_window_sweep(s, cfg_b, stream, launches)
+                                                : launch_column_sweep(s, stream, launches);
+        }
         if (rc) return rc;
     }
 
@@ -526,7 +552,7 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
         s.tsweep = true;
         s.dir = &p.col_t;
         s.win = &p.win_t;
-        s.val = use == CP_PLAN_RESIDENT_WINDOW ? tlevel_out : col_t;
+        s.val = windowish ? tlevel_out : col_t;
         s.edge_tab = d_tab + kk * 8;
         s.cp_out = nullptr;
         s.pperm = d_pperm_t;
@@ -539,9 +565,14 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
             s.mask_cp = cp_out;
             s.mask_out = mask_out;
         }
-        rc = use == CP_PLAN_RESIDENT_WINDOW
-                 ? launch_window_sweep(s, fuse_mask ? cfg_tm : cfg_t, stream, launches ? launches + 1 : nullptr)
-                 : launch_column_sweep(s, stream, launches ? launches + 1 : nullptr);
+        if (shared) {
+            rc = launch_window_shared(s, sh_t, stream);
+            if (launches) launches[1] = 1;
+        } else {
+            rc = use == CP_PLAN_RESIDENT_WINDOW
+                     ? launch_window_sweep(s, fuse_mask ? cfg_tm : cfg_t, stream, launches ? launches + 1 : nullptr)
+                     : launch_column_sweep(s, stream, launches ? launches + 1 : nullptr);
+        }
         if (rc) return rc;
         if (via_scratch) {
             rc = launch_transpose_ticks(col_t, tlevel_out, p.n, batch, tick_dtype, stream);

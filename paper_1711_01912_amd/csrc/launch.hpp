@@ -49,6 +49,20 @@ struct WindowCfg {
     size_t lds_bytes = 0;  // of the workgroup: groups * sub_bytes + tables
 };
 
+// Launch shape of the shared-window kernel (several partitions per workgroup behind one
+// loader set and one pair of stage slots) for one sweep direction.
+struct SharedCfg {
+    int groups = 0;    // partitions per workgroup: 2 or 4
+    int nl = 0;        // 16-byte loads per loader lane per tick
+    int nlw = 0;       // loader wavefronts
+    int nc = 0;        // compute wavefronts
+    size_t vals_off = 0, stage_off = 0, tab_off = 0;   // LDS byte offsets: ring values, stage slots, cost tables
+    size_t lds_bytes = 0;
+};
+// False if the direction cannot run that way under `lds_limit` bytes of dynamic LDS.
+bool shared_config(const WindowDir &d, int32_t k, int groups, size_t lds_limit, SharedCfg &out);
+int launch_window_shared(const SweepLaunch &s, const SharedCfg &cfg, void *stream);
+
 // False if the direction cannot run under `lds_limit` bytes of LDS.
 // with_mask: the t sweep also stages the tick's b values and writes the mask.
 bool window_config(const WindowDir &d, int32_t k, size_t tick_bytes, size_t lds_limit, WindowCfg &out,

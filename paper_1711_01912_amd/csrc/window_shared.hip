@@ -1,0 +1,428 @@
+// Shared-window sweep: the resident-window plan for large batches.
+//
+// The resident-window kernel gives every partition a workgroup of its own, and every one of
+// them loads, stages and reads the same tick packets.  Here one workgroup owns G consecutive
+// partitions (G = 2 or 4) and walks the sweep once for all of them: one loader set and one
+// pair of stage slots serve the group, a compute lane reads a packet entry once and relaxes
+// the edge for all G partitions out of one wide ring read.  The recurrences are the same
+// (b-level: the PCT equation of section 4.1; t-level: the downward rank of section 3.2 without
+// the own term).
+//
+// LDS: [device ids of the ring, (R+1) x G bytes][values of the ring, (R+1) x G ticks]
+//      [2 stage slots][cost tables].  A stage slot is [G x idpad bytes of device ids][packet].
+// The packets are the resident-window plan's (WindowDir with a packed ring: an entry's ring
+// field is 8 x slot), read unchanged.
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+
+#include "device_math.hpp"
+#include "launch.hpp"
+
+namespace cpeval {
+namespace {
+
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+struct SharedArgs {
+    const uint4 *stream;       // tick packets
+    const uint32_t *tick_tab;  // [ticks+1][4] {first chunk, chunks, lowest vertex id, id span}
+    const uint8_t *ids;        // direct: the caller's assignments[P][n]; else [P][ticks*wpad] ids in sweep order
+    int64_t ids_row;           // bytes between the rows of two partitions
+    int32_t *out;              // ticks of (v, q) at v * out_sv + q * out_sq, or NULL
+    int64_t *cp_out;           // [P] or NULL
+    const Magic *edge_tab;
+    const Magic *vert_tab;
+    int32_t *status;
+    int64_t out_sq;
+    uint32_t out_sv;
+    int32_t P, L, k, slots, wpad, smax, idpad, direct;   // L counts ticks
+    int32_t nc, nlw;           // compute and loader wavefronts
+    int32_t wgs, per_xcd;      // workgroups with partitions; workgroups per XCD
+    uint32_t vals_off, stage_off, tab_off;   // LDS byte offsets
+    int32_t out32;             // every output index fits 32 bits
+};
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef const uint32_t __attribute__((address_space(4))) *const_u32_ptr;
+
+template <int G> struct GroupVals;
+template <> struct GroupVals<2> { typedef uint2 type; };
+template <> struct GroupVals<4> { typedef uint4 type; };
+
+template <int G>
+__device__ __forceinline__ uint32_t val_of(const typename GroupVals<G>::type &v, int g) {
+    if constexpr (G == 2) return g == 0 ? v.x : v.y;
+    else return g == 0 ? v.x : (g == 1 ? v.y : (g == 2 ? v.z : v.w));
+}
+
+// Wavefronts 0..nc-1 compute, nc..nc+nlw-1 load.  Tick t: after the barrier the compute
+// wavefronts relax the tick out of stage slot t&1 while the loaders copy packet t+1
+// (requested DR ticks earlier, held in registers) into the other slot and request packet
+// t+1+DR.
+template <bool TSWEEP, int G, bool ENT4, int NL, int DR>
+__global__ __launch_bounds__(kWindowMaxWaves * 64) void window_shared_kernel(SharedArgs a) {
+    extern __shared__ uint4 lds16[];
+    __shared__ long long red[G][kWindowMaxWaves];
+    uint8_t *lds = (uint8_t *)lds16;
+    const int tid = threadIdx.x, lane = tid & 63, nt = blockDim.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int k = a.k, L = a.L, R = a.slots;
+    // ring: slot s holds G device bytes at s*G and G ticks at vals_off + s*4G; an entry's
+    // field is 8*s
+    constexpr int kDevShift = G == 4 ? 1 : 2;    // field >> kDevShift = s*G
+    constexpr int kValShift = G == 4 ? 1 : 0;    // field << kValShift = s*4G
+    typedef typename GroupVals<G>::type Vals;
+    typedef typename std::conditional<G == 4, uint32_t, uint16_t>::type Devs;
+
+    // blocks are dealt round-robin to the 8 XCDs; each XCD gets a run of consecutive groups
+    const int32_t wg = (int32_t)(blockIdx.x % 8) * a.per_xcd + (int32_t)(blockIdx.x / 8);
+    if (wg >= a.wgs) return;   // whole workgroup: no barrier has been reached yet
+    // a last group that is not full repeats its last partition (same values to the same places)
+    int32_t q[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) q[g] = min(wg * G + g, a.P - 1);
+
+    const uint32_t etab_off = a.tab_off, vtab_off = a.tab_off + 8u * (uint32_t)(k * k);
+    const int slot_bytes = NL * a.nlw * 1024;
+    uint8_t *stage = lds + a.stage_off;
+    {
+        const uint64_t *e = (const uint64_t *)a.edge_tab, *v = (const uint64_t *)a.vert_tab;
+        uint64_t *t64 = (uint64_t *)(lds + etab_off);
+        for (int i = tid; i < k * k; i += nt) t64[i] = e[i];
+        for (int i = tid; i < k; i += nt) t64[k * k + i] = v[i];
+        if (tid < G) {                           // the constant-zero slot padding entries point at
+            lds[(size_t)R * G + tid] = 0;
+            ((uint32_t *)(lds + a.vals_off))[(size_t)R * G + tid] = 0;
+        }
+    }
+    const int Lpad = (L + DR - 1) / DR * DR;
+    const int id16 = a.idpad / 16;               // 16-byte chunks of device ids per partition and slot
+    const int head = G * a.idpad;                // bytes of a slot before the packet
+    uint32_t best[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) best[g] = 0;
+
+    if (wave >= a.nc) {
+        // ------------------------------------------------ loader wavefronts
+        const int lw = wave - a.nc;
+        const_u32_ptr tick_tab = (const_u32_ptr)a.tick_tab;
+        int cid[NL], cidl[NL];
+        const uint4 *base[NL];
+        bool is_id[NL];
+        uint32_t mis[NL];
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            cid[i] = (i * a.nlw + lw) * 64 + lane;
+            is_id[i] = cid[i] < G * id16;
+            const int g = is_id[i] ? cid[i] / id16 : 0;
+            cidl[i] = cid[i] - g * id16;
+            int32_t qg = q[0];
+#pragma unroll
+            for (int gg = 1; gg < G; ++gg) qg = g == gg ? q[gg] : qg;
+            const uint8_t *row = a.ids + (size_t)qg * a.ids_row;
+            // direct staging starts at the 16-byte boundary below the tick's lowest id
+            mis[i] = a.direct ? (uint32_t)((uintptr_t)row & 15) : 0u;
+            base[i] = is_id[i] ? (const uint4 *)(row - mis[i]) : a.stream;
+        }
+        u32x4 buf[DR][NL];
+        // every lane always loads: chunks past the end of the ids or of the packet re-read
+        // the last chunk of that part
+#define CP_ISSUE(R_, S_)                                                                        \
+    do {                                                                                        \
+        const int s_ = min((S_), L - 1);                                                        \
+        const u32x4 tt_ = *(const u32x4 __attribute__((address_space(4))) *)(tick_tab + 4 * s_); \
+        const uint32_t o0_ = tt_.x, oc_ = tt_.y, lo_ = tt_.z, span_ = tt_.w;                    \
+        const int pk_last_ = G * id16 + (int)oc_ - 1, off_pk_ = (int)o0_ - G * id16;            \
+        _Pragma("unroll") for (int i_ = 0; i_ < NL; ++i_) {                                     \
+            int c_;                                                                             \
+            if (is_id[i_]) {                                                                    \
+                int first_, last_;                                                              \
+                if (a.direct) {                                                                 \
+                    first_ = (int)((mis[i_] + lo_) >> 4);                                       \
+                    last_ = (int)((mis[i_] + lo_ + span_ - 1) >> 4) - first_;                   \
+                } else {                                                                        \
+                    first_ = s_ * (a.wpad / 16);                                                \
+                    last_ = a.wpad / 16 - 1;                                                    \
+                }                                                                               \
+                c_ = min(cidl[i_], last_) + first_;                                             \
+            } else {                                                                            \
+                c_ = min(cid[i_], pk_last_) + off_pk_;                                          \
+            }                                                                                   \
+            buf[R_][i_] = *(const u32x4 *)(base[i_] + c_);                                      \
+        }                                                                                       \
+    } while (0)
+#define CP_STORE(R_, SLOT_)                                                                     \
+    do {                                                                                        \
+        u32x4 *dst_ = (u32x4 *)(stage + (size_t)(SLOT_) * slot_bytes);                          \
+        _Pragma("unroll") for (int i_ = 0; i_ < NL; ++i_) dst_[cid[i_]] = buf[R_][i_];          \
+    } while (0)
+#pragma unroll
+        for (int r = 0; r < DR; ++r) CP_ISSUE(r, r);
+        CP_STORE(0, 0);
+        CP_ISSUE(0, DR);
+        lds_barrier();                       // packet 0 is staged
+        for (int t0 = 0; t0 < Lpad; t0 += DR) {
+#pragma unroll
+            for (int r = 0; r < DR; ++r) {
+                const int t = t0 + r;
+                lds_barrier();
+                // the compute wavefronts now read slot t&1, which packet t-1 has left
+                CP_STORE((r + 1) % DR, (t + 1) & 1);
+                CP_ISSUE((r + 1) % DR, t + 1 + DR);
+            }
+        }
+#undef CP_ISSUE
+#undef CP_STORE
+    } else {
+        // ------------------------------------------------ compute wavefronts
+        __builtin_amdgcn_s_setprio(1);
+        typedef typename std::conditional<ENT4, uint32_t, uint2>::type Ent;
+        const uint32_t out_sv = a.out_sv;
+        const uint32_t k8 = 8u * (uint32_t)k;
+        const uint32_t rec_off = (uint32_t)head + 16u * (uint32_t)a.smax;   // records, from the slot base
+        const uint32_t vals_off = a.vals_off;
+        int32_t *outq[G];
+        uint32_t row_mis[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            outq[g] = a.out ? a.out + (size_t)q[g] * (size_t)a.out_sq : nullptr;
+            row_mis[g] = a.direct ? (uint32_t)((uintptr_t)(a.ids + (size_t)q[g] * a.ids_row) & 15) : 0u;
+        }
+        uint32_t worst = 0;                  // largest device id seen
+
+        auto ent_field = [](Ent e) -> uint32_t {
+            if constexpr (ENT4) return e & 0xffffu; else return e.x;
+        };
+        auto ent_t = [](Ent e) -> uint32_t {
+            if constexpr (ENT4) return e >> 16; else return e.y;
+        };
+        // one slice of the current tick out of its stage slot, for all G partitions
+        auto slice = [&](const uint8_t *st, int j) {
+            const uint4 d = ((const uint4 *)(st + head))[j];
+            const uint32_t ent_off = d.x;
+            const int width = __builtin_amdgcn_readfirstlane((int)(d.y & 0xffffu));
+            const int lsh = __builtin_amdgcn_readfirstlane((int)(d.y >> 24));
+            const int rows = (int)((d.y >> 16) & 0xffu);
+            const uint32_t lo = d.z;
+            const int rbase = (int)d.w;
+            if (width == 0 && lsh == 0 && __builtin_amdgcn_readfirstlane(rows) == 0) return;
+            const int p = j * 64 + (lane >> lsh);
+            const uint2 rc = *((const uint2 *)(st + rec_off) + p);
+            const Ent *ent = (const Ent *)(st + head + ent_off) + lane;
+            uint32_t pv[G], erow[G], acc[G];
+            Magic mv[G];
+            // N relaxations for all G partitions as one straight-line block: N entry reads,
+            // N reads of the G device ids and N of the G values, N*G cost-table reads, then
+            // the arithmetic
+#define CP_BLOCK(N)                                                                             \
+    do {                                                                                        \
+        Ent en_[N];                                                                             \
+        Vals vu_[N];                                                                            \
+        uint32_t du_[N];                                                                        \
+        Magic mg_[N][G];                                                                        \
+        _Pragma("unroll") for (int i_ = 0; i_ < N; ++i_) en_[i_] = ent[(jj + i_) * 64];         \
+        _Pragma("unroll") for (int i_ = 0; i_ < N; ++i_) {                                      \
+            const uint32_t f_ = ent_field(en_[i_]);                                             \
+            du_[i_] = *(const Devs *)(lds + (f_ >> kDevShift));                                 \
+            vu_[i_] = *(const Vals *)(lds + vals_off + (f_ << kValShift));                      \
+        }                                                                                       \
+        _Pragma("unroll") for (int i_ = 0; i_ < N; ++i_)                                        \
+            _Pragma("unroll") for (int g_ = 0; g_ < G; ++g_)                                    \
+                mg_[i_][g_] = *(const Magic *)(lds + erow[g_] + 8u * ((du_[i_] >> (8 * g_)) & 0xffu)); \
+        _Pragma("unroll") for (int i_ = 0; i_ < N; ++i_)                                        \
+            _Pragma("unroll") for (int g_ = 0; g_ < G; ++g_)                                    \
+                acc[g_] = max(acc[g_], val_of<G>(vu_[i_], g_) + magic_div(ent_t(en_[i_]), mg_[i_][g_])); \
+    } while (0)
+            // the vertex's own device ids: position p of the gathered rows, or byte (v - lo) of
+            // the staged id ranges (padding rows carry v = lo, so every lane reads a staged byte)
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const uint32_t at = a.direct ? rc.x - lo + ((row_mis[g] + lo) & 15u) : (uint32_t)p;
+                pv[g] = st[(uint32_t)g * (uint32_t)a.idpad + at];
+            }
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                worst = max(worst, pv[g]);
+                pv[g] = min(pv[g], (uint32_t)(k - 1));
+                erow[g] = etab_off + __umul24(pv[g], k8);
+                mv[g] = *(const Magic *)(lds + vtab_off + 8u * pv[g]);
+                acc[g] = 0;
+            }
+            int jj = 0;
+            for (; jj + 4 <= width; jj += 4) CP_BLOCK(4);
+            switch (width - jj) {
+                case 1: CP_BLOCK(1); break;
+                case 2: CP_BLOCK(2); break;
+                case 3: CP_BLOCK(3); break;
+                default: break;
+            }
+#undef CP_BLOCK
+            // fold the lanes of a row; afterwards the row's first lane holds the row's maxima
+            if (lsh > 0) {
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    uint32_t x = acc[g];
+                    if (lsh >= 1) x = max(x, (uint32_t)__shfl_xor((int)x, 1));
+                    if (lsh >= 2) x = max(x, (uint32_t)__shfl_xor((int)x, 2));
+                    if (lsh >= 3) x = max(x, (uint32_t)__shfl_xor((int)x, 4));
+                    if (lsh >= 4) x = max(x, (uint32_t)__shfl_xor((int)x, 8));
+                    if (lsh >= 5) x = max(x, (uint32_t)__shfl_xor((int)x, 16));
+                    if (lsh >= 6) x = max(x, (uint32_t)__shfl_xor((int)x, 32));
+                    acc[g] = x;
+                }
+            }
+            // the row's first lane publishes the vertex: ring, output, running maxima
+            const int row = lane >> lsh;
+            const bool first = lsh == 0 || (lane & ((1 << lsh) - 1)) == 0;
+            if (row < rows && first) {
+                int rs = rbase + row;
+                if (rs >= R) rs -= R;
+                uint32_t fin[G], devs = 0;
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    fin[g] = acc[g] + magic_div(rc.y, mv[g]);      // b(v), or tl(v) + w(v)
+                    devs |= pv[g] << (8 * g);
+                    best[g] = max(best[g], fin[g]);
+                }
+                *(Devs *)(lds + (size_t)rs * G) = (Devs)devs;
+                Vals fv;
+                if constexpr (G == 2) fv = make_uint2(fin[0], fin[1]);
+                else fv = make_uint4(fin[0], fin[1], fin[2], fin[3]);
+                *(Vals *)(lds + vals_off + (size_t)rs * (4 * G)) = fv;
+                if (a.out) {
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        const int32_t o = (int32_t)(TSWEEP ? acc[g] : fin[g]);
+                        if (a.out32) outq[g][__umul24(rc.x, out_sv)] = o;
+                        else outq[g][(size_t)rc.x * out_sv] = o;
+                    }
+                }
+            }
+        };
+
+        lds_barrier();                       // packet 0 is staged
+        for (int t = 0; t < Lpad; ++t) {
+            lds_barrier();
+            if (t >= L) continue;
+            const uint8_t *st = stage + (size_t)(t & 1) * slot_bytes;
+            for (int j = wave; j < a.smax; j += a.nc) slice(st, j);
+        }
+        if (worst >= (uint32_t)k) *a.status = CP_STATUS_BAD_DEVICE_ID;
+    }
+
+    if (a.cp_out) {   // the partitions' maxima
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            long long b64 = (long long)best[g];
+            for (int off = 32; off > 0; off >>= 1) b64 = max(b64, __shfl_xor(b64, off));
+            if (lane == 0) red[g][wave] = b64;
+        }
+        lds_barrier();
+        if (wave == 0 && lane < G) {
+            long long b64 = 0;
+            for (int w2 = 0; w2 < a.nc; ++w2) b64 = max(b64, red[lane][w2]);
+            a.cp_out[min(wg * G + lane, a.P - 1)] = b64;
+        }
+    }
+}
+
+inline int hip_ok(hipError_t e) { return e == hipSuccess ? CP_OK : CP_ERR_HIP; }
+
+template <bool TSWEEP, int G, bool ENT4, int NL, int DR>
+int launch_shared_k(const SweepLaunch &s, const SharedCfg &cfg, hipStream_t st) {
+    const WindowDir &dir = *s.win;
+    SharedArgs a{};
+    a.stream = (const uint4 *)(s.blob + dir.stream_off);
+    a.tick_tab = (const uint32_t *)(s.blob + dir.tick_off);
+    a.direct = s.direct_ids ? 1 : 0;
+    a.ids = s.direct_ids ? s.assign : s.pperm;
+    a.ids_row = s.direct_ids ? s.a_stride_p : (int64_t)dir.ticks * dir.wpad;
+    a.out = (int32_t *)s.val;
+    a.cp_out = s.cp_out;
+    a.edge_tab = (const Magic *)s.edge_tab;
+    a.vert_tab = (const Magic *)s.vert_tab;
+    a.status = s.status;
+    a.out_sq = s.out_sq;
+    a.out_sv = (uint32_t)s.out_sv;
+    a.P = s.P; a.L = dir.ticks; a.k = s.k; a.slots = dir.slots; a.wpad = dir.wpad; a.smax = dir.smax;
+    a.idpad = dir.idpad;
+    a.nc = cfg.nc; a.nlw = cfg.nlw;
+    a.wgs = (s.P + G - 1) / G;
+    a.per_xcd = (a.wgs + 7) / 8;
+    a.vals_off = (uint32_t)cfg.vals_off;
+    a.stage_off = (uint32_t)cfg.stage_off;
+    a.tab_off = (uint32_t)cfg.tab_off;
+    a.out32 = s.n < (1 << 24) && s.P < (1 << 24) && (uint64_t)s.n * (uint64_t)s.P < (1ull << 31);
+    auto kern = window_shared_kernel<TSWEEP, G, ENT4, NL, DR>;
+    if (cfg.lds_bytes > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)cfg.lds_bytes);
+        if (e != hipSuccess) return CP_ERR_HIP;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)(8 * a.per_xcd)), dim3((cfg.nc + cfg.nlw) * 64), cfg.lds_bytes, st, a);
+    return hip_ok(hipGetLastError());
+}
+
+template <bool TSWEEP, int G, bool ENT4>
+int launch_shared_e(const SweepLaunch &s, const SharedCfg &cfg, hipStream_t st) {
+    switch (cfg.nl) {   // loads per loader lane per tick x ticks in flight: 64 registers at most
+        case 1: return launch_shared_k<TSWEEP, G, ENT4, 1, 8>(s, cfg, st);
+        case 2: return launch_shared_k<TSWEEP, G, ENT4, 2, 8>(s, cfg, st);
+        case 3: return launch_shared_k<TSWEEP, G, ENT4, 3, 5>(s, cfg, st);
+        case 4: return launch_shared_k<TSWEEP, G, ENT4, 4, 4>(s, cfg, st);
+        default: return CP_ERR_ARG;
+    }
+}
+
+template <bool TSWEEP>
+int launch_shared_g(const SweepLaunch &s, const SharedCfg &cfg, hipStream_t st) {
+    if (cfg.groups == 4)
+        return s.win->ent4 ? launch_shared_e<TSWEEP, 4, true>(s, cfg, st) : launch_shared_e<TSWEEP, 4, false>(s, cfg, st);
+    if (cfg.groups == 2)
+        return s.win->ent4 ? launch_shared_e<TSWEEP, 2, true>(s, cfg, st) : launch_shared_e<TSWEEP, 2, false>(s, cfg, st);
+    return CP_ERR_ARG;
+}
+
+}  // namespace
+
+bool shared_config(const WindowDir &d, int32_t k, int groups, size_t lds_limit, SharedCfg &out) {
+    if (!d.packed || d.far_cap > 0 || (groups != 2 && groups != 4)) return false;
+    const size_t G = (size_t)groups;
+    const size_t devs = align_up(((size_t)d.slots + 1) * G, 16);
+    const size_t vals = align_up(((size_t)d.slots + 1) * 4 * G, 16);
+    const size_t tab = align_up(sizeof(Magic) * ((size_t)k * k + k), 16);
+    // the entries' ring fields are read as LDS byte offsets of the device bytes and, doubled
+    // at most, of the values: both regions lie below 2^32 trivially, the fields below 8 * (slots + 1)
+    const int64_t need = (int64_t)G * (d.idpad / 16) + (int64_t)d.max_chunks;    // 16-byte chunks per stage slot
+    static const int kNl[4] = {1, 2, 3, 4};
+    for (int nl : kNl) {
+        const int64_t nlw = (need + 64 * nl - 1) / (64 * nl);
+        if (nlw > 8) continue;
+        SharedCfg c;
+        c.groups = groups;
+        c.nl = nl;
+        c.nlw = (int)nlw;
+        c.nc = std::max(1, std::min(d.smax, kWindowMaxWaves - (int)nlw));
+        c.vals_off = devs;
+        c.stage_off = devs + vals;
+        c.tab_off = c.stage_off + (size_t)2 * nl * nlw * 1024;
+        c.lds_bytes = c.tab_off + tab;
+        if (c.lds_bytes > lds_limit) continue;
+        out = c;
+        return true;
+    }
+    return false;
+}
+
+int launch_window_shared(const SweepLaunch &s, const SharedCfg &cfg, void *stream) {
+    if (s.tick_bytes != 4 || s.mask_out) return CP_ERR_ARG;
+    return s.tsweep ? launch_shared_g<true>(s, cfg, (hipStream_t)stream)
+                    : launch_shared_g<false>(s, cfg, (hipStream_t)stream);
+}
+
+}  // namespace cpeval
