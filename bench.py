@@ -64,7 +64,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="large_sparse")
     ap.add_argument("--plan", type=int, default=0, help="0 auto, 1 wave-column, 2 resident-window, "
-                    "3 / 4 shared window with 2 / 4 partitions per workgroup")
+                    "3 / 4 shared window with 2 / 4 partitions per workgroup, 5 column slices")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
     ap.add_argument("--out-layout", default="native", choices=("native", "vertex", "partition"),
                     help="layout of b, tl and the mask; native = the one the plan that runs produces directly "
@@ -104,7 +104,8 @@ def main():
     tdt = torch.int32 if T == 4 else torch.int64
     plan_used = args.plan if args.plan else binding.choose_plan(g, P, w.speeds, w.bandwidth, T)
     if args.out_layout == "native":
-        out_layout = cpe.OUT_VERTEX_MAJOR if plan_used == cpe.PLAN_WAVE_COLUMN else cpe.OUT_PARTITION_MAJOR
+        out_layout = (cpe.OUT_VERTEX_MAJOR if plan_used in (cpe.PLAN_WAVE_COLUMN, cpe.PLAN_COLUMN_SLICE)
+                      else cpe.OUT_PARTITION_MAJOR)
     else:
         out_layout = cpe.OUT_PARTITION_MAJOR if args.out_layout == "partition" else cpe.OUT_VERTEX_MAJOR
     rows, cols = (n, P) if out_layout == cpe.OUT_VERTEX_MAJOR else (P, n)
@@ -252,7 +253,8 @@ def main():
         "config": {"workload": args.workload, "n": n, "m": m, "L": w.L, "P": P, "k": w.k,
                    "tick_bytes": T, "max_out_degree": info["max_out_degree"],
                    "raw_path_bound": info["raw_path_bound"],
-                   "plan": {1: "wave-column", 2: "resident-window", 3: "shared-window-2", 4: "shared-window-4"}[plan_used],
+                   "plan": {1: "wave-column", 2: "resident-window", 3: "shared-window-2", 4: "shared-window-4",
+                            5: "column-slice"}[plan_used],
                    "out_layout": "vertex-major" if out_layout == cpe.OUT_VERTEX_MAJOR else "partition-major"},
         "stage_ms": stage_ms,
         "blevel_relaxations_per_s": m * P / (b_ms * 1e-3),

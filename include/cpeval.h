@@ -85,6 +85,8 @@ extern "C" {
 #define CP_PLAN_RESIDENT_WINDOW  2   /* one workgroup = one partition; recent levels kept in LDS; one launch per sweep */
 #define CP_PLAN_SHARED_WINDOW_2  3   /* as 2, but one workgroup = 2 partitions behind one graph stream */
 #define CP_PLAN_SHARED_WINDOW_4  4   /* ... 4 partitions */
+#define CP_PLAN_COLUMN_SLICE     5   /* the wave-column layout, but one persistent workgroup owns 64 partitions and
+                                        walks all levels in one launch per sweep (never chosen by CP_PLAN_AUTO) */
 
 /* stages of one cp_eval call, in the order they run; also the index into cp_profile_read's output */
 #define CP_STAGE_PREP    0   /* clear outputs, cost tables, assignment transpose */
@@ -113,6 +115,11 @@ typedef struct cp_graph_info {
     int32_t window_far_b;        /* far reads per tick of that plan's b-level sweep (neighbours too far back for the
                                     LDS ring are read from the output array); 0 = none */
     int32_t window_far_t;        /* ... and t-level sweep */
+    int32_t window_ticks_b;      /* barriers of that plan's b-level sweep: a level is cut into ticks of at most 8 slices
+                                    of 64 vertices */
+    int32_t window_ticks_t;      /* ... and t-level sweep */
+    int32_t window_slices_b;     /* slices of the widest tick, b-level sweep */
+    int32_t window_slices_t;     /* ... and t-level sweep */
     int32_t auto_plan;           /* plan CP_PLAN_AUTO resolves to for a batch of 256 (the choice is made per call) */
     int32_t uploaded;            /* 1 after cp_graph_upload */
     uint64_t blob_bytes;

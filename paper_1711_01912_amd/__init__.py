@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     OUT_PARTITION_MAJOR,
     OUT_VERTEX_MAJOR,
     PLAN_AUTO,
+    PLAN_COLUMN_SLICE,
     PLAN_RESIDENT_WINDOW,
     PLAN_SHARED_WINDOW_2,
     PLAN_SHARED_WINDOW_4,

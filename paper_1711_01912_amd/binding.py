@@ -20,6 +20,7 @@ TICK_I32, TICK_I64 = 4, 8
 ASSIGN_PARTITION_MAJOR, ASSIGN_VERTEX_MAJOR = 0, 1
 OUT_VERTEX_MAJOR, OUT_PARTITION_MAJOR = 0, 1
 PLAN_AUTO, PLAN_WAVE_COLUMN, PLAN_RESIDENT_WINDOW, PLAN_SHARED_WINDOW_2, PLAN_SHARED_WINDOW_4 = 0, 1, 2, 3, 4
+PLAN_COLUMN_SLICE = 5
 NUM_STAGES = 5
 STAGE_NAMES = ("prep", "blevel", "cp", "tlevel", "mask")
 STATUS_BAD_DEVICE_ID = 1
@@ -46,6 +47,8 @@ class GraphInfo(C.Structure):
         ("window_slots_b", C.c_int32), ("window_slots_t", C.c_int32),
         ("window_packet_bytes_b", C.c_int32), ("window_packet_bytes_t", C.c_int32),
         ("window_far_b", C.c_int32), ("window_far_t", C.c_int32),
+        ("window_ticks_b", C.c_int32), ("window_ticks_t", C.c_int32),
+        ("window_slices_b", C.c_int32), ("window_slices_t", C.c_int32),
         ("auto_plan", C.c_int32), ("uploaded", C.c_int32), ("blob_bytes", C.c_uint64),
     ]
 

@@ -148,13 +148,29 @@ size_t device_window_lds_limit() {
 // as many workgroups as fit one unit's LDS at a time (about 0.6 us per tick plus
 // 0.045 us per slice); the wave-column plan pays about 6.3 us per level launch plus
 // its gathers at about 4 TB/s.
+// Workgroups of the resident-window kernel one compute unit holds at a time: LDS, and the
+// wavefronts the register file takes (the loaders keep nl x dr 16-byte loads in registers:
+// about 64 registers per lane with one load per tick, 80 with two or three, more beyond).
+double window_wg_per_cu(const WindowCfg &c) {
+    const int groups = std::max(1, c.groups);
+    const double waves = c.nl <= 1 ? 32.0 : (c.nl <= 3 ? 24.0 : (c.nl == 4 ? 20.0 : 16.0));
+    return std::max<double>(1.0, std::floor(std::min<double>(
+        (double)(kLdsBudget / std::max<size_t>(c.lds_bytes, 1)), waves / (groups * (c.nc + c.nlw + c.nfw)))));
+}
+
 double window_sweep_us(const WindowDir &d, const WindowCfg &c, int32_t batch) {
     const double cus = 256.0;
     const int groups = std::max(1, c.groups);         // partitions per workgroup
-    const double wg_per_cu = std::max<double>(1.0, std::floor(std::min<double>(
-        (double)(kLdsBudget / std::max<size_t>(c.lds_bytes, 1)), 32.0 / (groups * (c.nc + c.nlw + c.nfw)))));
-    const double rounds = std::ceil((double)batch / (cus * wg_per_cu * groups));
+    const double rounds = std::ceil((double)batch / (cus * window_wg_per_cu(c) * groups));
     return rounds * (double)d.ticks * (0.58 + 0.03 * d.smax);
+}
+
+// The shared-window kernel: one workgroup per compute unit, 2 or 4 partitions each.  A tick
+// costs 1.33 (2.03) times the resident-window kernel's (large sparse workload: 0.745 us ->
+// 0.99 us -> 1.51 us per tick for 1, 2, 4 partitions).
+double shared_sweep_us(const WindowDir &d, int groups, int32_t batch) {
+    const double rounds = std::ceil((double)batch / (256.0 * groups));
+    return rounds * (double)d.ticks * (groups == 4 ? 2.03 : 1.33) * (0.58 + 0.03 * d.smax);
 }
 
 bool window_preferred(const Packed &p, const WindowCfg &cb, const WindowCfg &ct, int32_t batch,
@@ -171,6 +187,33 @@ bool window_preferred(const Packed &p, const WindowCfg &cb, const WindowCfg &ct,
     return window_us <= column_us(p.col_b) + column_us(p.col_t);
 }
 
+// CP_PLAN_AUTO among the window plans (the caller has found the resident-window plan runnable
+// and preferable to the wave-column plan).  Sharing a workgroup pays where one workgroup of the
+// resident-window kernel fills a compute unit (wide ticks, a long ring): there the batch can
+// only overlap inside a workgroup.  Narrow graphs, whose workgroups sit several to a unit
+// already, gain nothing from it (measured: 2,016 vertices x 8,192 partitions 0.62 ms per sweep
+// against 0.56 and 0.80 ms; 5,271 vertices x 16,384 partitions 1.08 against 1.31 and 1.05 ms).
+// mask_penalty_us: what the shared plans pay for the mask pass the other plan would not need.
+int choose_window_plan(const Packed &p, int32_t k, size_t tick_bytes, size_t lds_limit, const WindowCfg &cb,
+                       const WindowCfg &ct, int32_t batch, double mask_penalty_us, SharedCfg *sh_b, SharedCfg *sh_t) {
+    int best = CP_PLAN_RESIDENT_WINDOW;
+    if (window_wg_per_cu(cb) > 1.0 || window_wg_per_cu(ct) > 1.0) return best;
+    double best_us = window_sweep_us(p.win_b, cb, batch) + window_sweep_us(p.win_t, ct, batch);
+    for (int groups = 2; groups <= 4; groups += 2) {
+        SharedCfg b, t;
+        if (!shared_fits(p, k, tick_bytes, groups, lds_limit, &b, &t)) continue;
+        const double us = shared_sweep_us(p.win_b, groups, batch) + shared_sweep_us(p.win_t, groups, batch) +
+                          mask_penalty_us;
+        if (us < best_us) {
+            best_us = us;
+            best = groups == 4 ? CP_PLAN_SHARED_WINDOW_4 : CP_PLAN_SHARED_WINDOW_2;
+            if (sh_b) *sh_b = b;
+            if (sh_t) *sh_t = t;
+        }
+    }
+    return best;
+}
+
 size_t tables_bytes(int32_t k) { return align_up(table_entries(k) * 8); }
 size_t column_scratch_bytes(const Packed &p, int32_t batch, int tick_bytes) {
     return align_up((size_t)p.n * (size_t)batch * (size_t)tick_bytes);
@@ -181,7 +224,7 @@ int check_eval_sizes(const cp_graph *g, int32_t batch, int32_t k, int assign_lay
     if (batch < 1 || k < 1 || k > 255) return CP_ERR_SIZE;
     if (assign_layout != CP_ASSIGN_PARTITION_MAJOR && assign_layout != CP_ASSIGN_VERTEX_MAJOR)
         return CP_ERR_ARG;
-    if (plan < CP_PLAN_AUTO || plan > CP_PLAN_SHARED_WINDOW_4) return CP_ERR_ARG;
+    if (plan < CP_PLAN_AUTO || plan > CP_PLAN_COLUMN_SLICE) return CP_ERR_ARG;
     return CP_OK;
 }
 
@@ -285,7 +328,9 @@ int cp_graph_create(int32_t n, int64_t m, int32_t L,
     info.window_ok = window_fits(g->packed, 1, (size_t)info.min_tick_bytes, kWindowLdsLimit, &cb, &ct) ? 1 : 0;
     // the choice is made per call (it depends on the batch); this is the one for 256 partitions
     info.auto_plan = info.window_ok && window_preferred(g->packed, cb, ct, 256, (size_t)info.min_tick_bytes)
-                         ? CP_PLAN_RESIDENT_WINDOW : CP_PLAN_WAVE_COLUMN;
+                         ? choose_window_plan(g->packed, 1, (size_t)info.min_tick_bytes, kWindowLdsLimit, cb, ct, 256,
+                                              0.0, nullptr, nullptr)
+                         : CP_PLAN_WAVE_COLUMN;
     *out = g;
     return CP_OK;
 }
@@ -323,7 +368,7 @@ int cp_eval_workspace_bytes(const cp_graph *g, int32_t batch, int32_t k, int ass
     // the wave-column plan reads device ids vertex-major; under CP_PLAN_AUTO it may be
     // the one that runs, whatever the graph prefers, if the cost model rules the other out
     size_t column = 0, window = 0;
-    const bool may_column = plan == CP_PLAN_AUTO || plan == CP_PLAN_WAVE_COLUMN;
+    const bool may_column = plan == CP_PLAN_AUTO || plan == CP_PLAN_WAVE_COLUMN || plan == CP_PLAN_COLUMN_SLICE;
     if (assign_layout == CP_ASSIGN_PARTITION_MAJOR && may_column)
         column = align_up((size_t)g->packed.n * (size_t)batch);
     // the wave-column plan sweeps vertex-major: partition-major outputs are transposed
@@ -331,7 +376,7 @@ int cp_eval_workspace_bytes(const cp_graph *g, int32_t batch, int32_t k, int ass
     if (out_layout == CP_OUT_PARTITION_MAJOR && may_column)
         column += 2 * column_scratch_bytes(g->packed, batch, tick_dtype);
     // the resident-window plan gathers the device ids into sweep order, once per direction
-    if (plan != CP_PLAN_WAVE_COLUMN && g->packed.have_window)
+    if (plan != CP_PLAN_WAVE_COLUMN && plan != CP_PLAN_COLUMN_SLICE && g->packed.have_window)
         window = pperm_bytes(g->packed, g->packed.win_b, batch) + pperm_bytes(g->packed, g->packed.win_t, batch);
     *out_bytes = bytes + std::max(column, window);
     return CP_OK;
@@ -355,7 +400,9 @@ int cp_eval_choose_plan(const cp_graph *g, int32_t batch, int32_t k, const int64
     const bool can_window = tabs.magic_ok && window_fits(p, k, (size_t)tick_dtype, device_window_lds_limit(),
                                                          &cfg_b, &cfg_t);
     *plan_out = can_window && window_preferred(p, cfg_b, cfg_t, batch, (size_t)tick_dtype)
-                    ? CP_PLAN_RESIDENT_WINDOW : CP_PLAN_WAVE_COLUMN;
+                    ? choose_window_plan(p, k, (size_t)tick_dtype, device_window_lds_limit(), cfg_b, cfg_t, batch, 0.0,
+                                         nullptr, nullptr)
+                    : CP_PLAN_WAVE_COLUMN;
     return CP_OK;
 }
 
@@ -393,18 +440,26 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
     const bool can_window = tabs.magic_ok && window_fits(p, k, (size_t)tick_dtype,
                                                          device_window_lds_limit(), &cfg_b, &cfg_t);
     int use = plan;
-    if (plan == CP_PLAN_AUTO)
-        use = can_window && window_preferred(p, cfg_b, cfg_t, batch, (size_t)tick_dtype)
-                  ? CP_PLAN_RESIDENT_WINDOW : CP_PLAN_WAVE_COLUMN;
+    SharedCfg sh_b, sh_t;
+    if (plan == CP_PLAN_AUTO) {
+        use = CP_PLAN_WAVE_COLUMN;
+        if (can_window && window_preferred(p, cfg_b, cfg_t, batch, (size_t)tick_dtype)) {
+            // with a mask to write, the shared plans pay for a pass of their own over b and tl
+            const double mask_us = mask_out ? 5.0 + (double)p.n * batch * (2.0 * tick_dtype + 0.125) / 4.0e6 : 0.0;
+            use = choose_window_plan(p, k, (size_t)tick_dtype, device_window_lds_limit(), cfg_b, cfg_t, batch, mask_us,
+                                     &sh_b, &sh_t);
+        }
+    }
     if (use == CP_PLAN_RESIDENT_WINDOW && !can_window) return CP_ERR_ARG;
     // several partitions per workgroup behind one graph stream
-    SharedCfg sh_b, sh_t;
     const bool shared = use == CP_PLAN_SHARED_WINDOW_2 || use == CP_PLAN_SHARED_WINDOW_4;
-    if (shared && (!tabs.magic_ok ||
-                   !shared_fits(p, k, (size_t)tick_dtype, use == CP_PLAN_SHARED_WINDOW_4 ? 4 : 2,
-                                device_window_lds_limit(), &sh_b, &sh_t)))
+    if (shared && plan != CP_PLAN_AUTO &&
+        (!tabs.magic_ok || !shared_fits(p, k, (size_t)tick_dtype, use == CP_PLAN_SHARED_WINDOW_4 ? 4 : 2,
+                                        device_window_lds_limit(), &sh_b, &sh_t)))
         return CP_ERR_ARG;
     const bool windowish = use == CP_PLAN_RESIDENT_WINDOW || shared;
+    const bool columnish = !windowish;       // wave-column, or its persistent column-slice form
+    if (use == CP_PLAN_COLUMN_SLICE && (!tabs.magic_ok || k > kMagicMaxK)) return CP_ERR_ARG;
     // the wave-column plan reads CP off the stored b-levels; the window sweeps keep a running maximum
     if (cp_out && !blevel_out && (!windowish || p.win_b.far_cap > 0)) return CP_ERR_ARG;
 
@@ -419,13 +474,13 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
 
     // workspace: only what this call uses (cp_eval_workspace_bytes is an upper bound over
     // every way the call may go)
-    const bool need_pT = use == CP_PLAN_WAVE_COLUMN && assign_layout == CP_ASSIGN_PARTITION_MAJOR;
+    const bool need_pT = columnish && assign_layout == CP_ASSIGN_PARTITION_MAJOR;
     size_t need = tables_bytes(k) + (need_pT ? align_up((size_t)p.n * (size_t)batch) : 0);
     const size_t pperm_b_bytes = gather_b ? pperm_bytes(p, p.win_b, batch) : 0;
     const size_t pperm_t_bytes = gather_t ? pperm_bytes(p, p.win_t, batch) : 0;
     need += pperm_b_bytes + pperm_t_bytes;
     const bool by_partition = out_layout == CP_OUT_PARTITION_MAJOR;
-    const bool via_scratch = by_partition && use == CP_PLAN_WAVE_COLUMN;
+    const bool via_scratch = by_partition && columnish;
     const size_t scratch_at = need;
     if (via_scratch) need += 2 * column_scratch_bytes(p, batch, tick_dtype);
     if (workspace_bytes < need) return CP_ERR_WORKSPACE;
@@ -528,15 +583,20 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
             rc = launch_window_shared(s, sh_b, stream);
             if (launches) launches[0] = 1;
         } else {
-            rc = use == CP_PLAN_RESIDENT_WINDOW ? launch_window_sweep(s, cfg_b, stream, launches)
-                                                : launch_column_sweep(s, stream, launches);
+            if (use == CP_PLAN_COLUMN_SLICE) {
+                rc = launch_column_slice(s, stream);
+                if (launches) launches[0] = 1;
+            } else {
+                rc = use == CP_PLAN_RESIDENT_WINDOW ? launch_window_sweep(s, cfg_b, stream, launches)
+                                                    : launch_column_sweep(s, stream, launches);
+            }
         }
         if (rc) return rc;
     }
 
     // ---- stage: critical-path length
     CP_MARK(CP_STAGE_CP);
-    if (cp_out && use == CP_PLAN_WAVE_COLUMN) {
+    if (cp_out && columnish) {
         rc = launch_cp_sources((const int32_t *)(s.blob + p.sources_off), p.info.num_sources,
                                col_b, batch, tick_dtype, cp_out, stream);
         if (rc) return rc;
@@ -569,9 +629,14 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
             rc = launch_window_shared(s, sh_t, stream);
             if (launches) launches[1] = 1;
         } else {
-            rc = use == CP_PLAN_RESIDENT_WINDOW
-                     ? launch_window_sweep(s, fuse_mask ? cfg_tm : cfg_t, stream, launches ? launches + 1 : nullptr)
-                     : launch_column_sweep(s, stream, launches ? launches + 1 : nullptr);
+            if (use == CP_PLAN_COLUMN_SLICE) {
+                rc = launch_column_slice(s, stream);
+                if (launches) launches[1] = 1;
+            } else {
+                rc = use == CP_PLAN_RESIDENT_WINDOW
+                         ? launch_window_sweep(s, fuse_mask ? cfg_tm : cfg_t, stream, launches ? launches + 1 : nullptr)
+                         : launch_column_sweep(s, stream, launches ? launches + 1 : nullptr);
+            }
         }
         if (rc) return rc;
         if (via_scratch) {

@@ -83,6 +83,15 @@ void pack_column_dir(BlobWriter &w, int32_t n, int64_t m, bool narrow, const Csr
     }
     dir.order_off = w.reserve(sizeof(int32_t) * (size_t)n);
     std::memcpy(w.at<int32_t>(dir.order_off), order.data(), sizeof(int32_t) * (size_t)n);
+    const size_t L = dir.lvl_begin.size();
+    dir.lvl_off = w.reserve(sizeof(int32_t) * 4 * std::max<size_t>(L, 1));
+    int32_t *lvl = w.at<int32_t>(dir.lvl_off);
+    for (size_t l = 0; l < L; ++l) {
+        lvl[4 * l] = dir.lvl_begin[l];
+        lvl[4 * l + 1] = dir.lvl_hubs[l];
+        lvl[4 * l + 2] = dir.lvl_count[l];
+        lvl[4 * l + 3] = 0;
+    }
 }
 
 // A slice with few rows spreads each row over several lanes: log2 of the lanes
@@ -475,6 +484,10 @@ int pack_graph(int32_t n, int64_t m, int32_t L,
     info.window_slots_t = P.have_window ? P.win_t.slots : 0;
     info.window_packet_bytes_b = P.have_window ? 16 * P.win_b.max_chunks : 0;
     info.window_packet_bytes_t = P.have_window ? 16 * P.win_t.max_chunks : 0;
+    info.window_ticks_b = P.have_window ? P.win_b.ticks : 0;
+    info.window_ticks_t = P.have_window ? P.win_t.ticks : 0;
+    info.window_slices_b = P.have_window ? P.win_b.smax : 0;
+    info.window_slices_t = P.have_window ? P.win_t.smax : 0;
     info.window_far_b = P.have_window ? P.win_b.far_cap : 0;
     info.window_far_t = P.have_window ? P.win_t.far_cap : 0;
     info.blob_bytes = P.blob.size();

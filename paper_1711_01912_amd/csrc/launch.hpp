@@ -74,6 +74,7 @@ int launch_clear(int64_t *cp_out, int32_t batch, int32_t *status, void *stream);
 int launch_transpose(const uint8_t *in, uint8_t *out, int32_t n, int32_t P, void *stream);
 int launch_column_sweep(const SweepLaunch &s, void *stream, int32_t *launches);
 int launch_window_sweep(const SweepLaunch &s, const WindowCfg &cfg, void *stream, int32_t *launches);
+int launch_column_slice(const SweepLaunch &s, void *stream);   // CP_ERR_ARG without 32-bit multiply-shift tables
 int launch_cp_sources(const int32_t *sources, int32_t nsrc, const void *b, int32_t P,
                       int tick_bytes, int64_t *cp_out, void *stream);
 // One segmented radix sort per call: the PCT priority lists of section 4.1.

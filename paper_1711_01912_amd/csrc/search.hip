@@ -220,7 +220,7 @@ int search_layout(const cp_graph *g, int32_t k, int32_t chunk, const int64_t *sp
     const size_t n = (size_t)info.n;
     o.eval_bytes = align_up(std::max(ws_chunk, ws_one));
     // CP alone needs no b array only under the resident-window plan on a graph without far reads
-    o.cp_only = o.plan_chunk == CP_PLAN_RESIDENT_WINDOW && info.window_far_b == 0;
+    o.cp_only = o.plan_chunk != CP_PLAN_WAVE_COLUMN && info.window_far_b == 0;
     const size_t b_cols = o.cp_only ? 1 : (size_t)chunk;
     size_t at = 0;
     o.eval_ws = at; at += o.eval_bytes;
@@ -319,7 +319,7 @@ int cp_search(const cp_graph *g, int32_t k, const int64_t *speeds, const int64_t
             if (rc) return rc;
             // a short last chunk may resolve to the other plan: it needs b only if room was made for it
             void *b_arg = lay.cp_only ? nullptr : d_b;
-            if (lay.cp_only && plan != CP_PLAN_RESIDENT_WINDOW) {
+            if (lay.cp_only && plan == CP_PLAN_WAVE_COLUMN) {
                 if (count > 1) plan = CP_PLAN_RESIDENT_WINDOW;
                 else b_arg = d_b;
             }
