@@ -64,7 +64,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="large_sparse")
     ap.add_argument("--plan", type=int, default=0, help="0 auto, 1 wave-column, 2 resident-window, "
-                    "3 / 4 shared window with 2 / 4 partitions per workgroup, 5 column slices")
+                    "3 / 4 shared window with 2 / 4 partitions per workgroup, 5 column slices, 6 streamed window")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
     ap.add_argument("--out-layout", default="native", choices=("native", "vertex", "partition"),
                     help="layout of b, tl and the mask; native = the one the plan that runs produces directly "
@@ -254,7 +254,7 @@ def main():
                    "tick_bytes": T, "max_out_degree": info["max_out_degree"],
                    "raw_path_bound": info["raw_path_bound"],
                    "plan": {1: "wave-column", 2: "resident-window", 3: "shared-window-2", 4: "shared-window-4",
-                            5: "column-slice"}[plan_used],
+                            5: "column-slice", 6: "streamed-window"}[plan_used],
                    "out_layout": "vertex-major" if out_layout == cpe.OUT_VERTEX_MAJOR else "partition-major"},
         "stage_ms": stage_ms,
         "blevel_relaxations_per_s": m * P / (b_ms * 1e-3),

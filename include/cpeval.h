@@ -85,6 +85,8 @@ extern "C" {
 #define CP_PLAN_RESIDENT_WINDOW  2   /* one workgroup = one partition; recent levels kept in LDS; one launch per sweep */
 #define CP_PLAN_SHARED_WINDOW_2  3   /* as 2, but one workgroup = 2 partitions behind one graph stream */
 #define CP_PLAN_SHARED_WINDOW_4  4   /* ... 4 partitions */
+#define CP_PLAN_STREAMED_WINDOW  6   /* as 2, but the compute wavefronts fetch the graph themselves, two ticks ahead, into
+                                        registers; LDS holds only what depends on the partition */
 #define CP_PLAN_COLUMN_SLICE     5   /* the wave-column layout, but one persistent workgroup owns 64 partitions and
                                         walks all levels in one launch per sweep (never chosen by CP_PLAN_AUTO) */
 

@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     PLAN_COLUMN_SLICE,
     PLAN_RESIDENT_WINDOW,
     PLAN_SHARED_WINDOW_2,
+    PLAN_STREAMED_WINDOW,
     PLAN_SHARED_WINDOW_4,
     PLAN_WAVE_COLUMN,
     POLICY_FIFO,

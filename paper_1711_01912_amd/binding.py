@@ -20,7 +20,7 @@ TICK_I32, TICK_I64 = 4, 8
 ASSIGN_PARTITION_MAJOR, ASSIGN_VERTEX_MAJOR = 0, 1
 OUT_VERTEX_MAJOR, OUT_PARTITION_MAJOR = 0, 1
 PLAN_AUTO, PLAN_WAVE_COLUMN, PLAN_RESIDENT_WINDOW, PLAN_SHARED_WINDOW_2, PLAN_SHARED_WINDOW_4 = 0, 1, 2, 3, 4
-PLAN_COLUMN_SLICE = 5
+PLAN_COLUMN_SLICE, PLAN_STREAMED_WINDOW = 5, 6
 NUM_STAGES = 5
 STAGE_NAMES = ("prep", "blevel", "cp", "tlevel", "mask")
 STATUS_BAD_DEVICE_ID = 1
@@ -346,7 +346,7 @@ def cp_eval(graph: CpGraph, assignments, speeds, bandwidth, *, want=("cp", "b", 
     if "cp" in want and "b" not in want:
         # CP alone: the resident-window plan needs no b array for it
         used = plan if plan != PLAN_AUTO else choose_plan(graph, batch, s, bw, tick_bytes)
-        if used not in (PLAN_RESIDENT_WINDOW, PLAN_SHARED_WINDOW_2, PLAN_SHARED_WINDOW_4) or info["window_far_b"] > 0:
+        if used not in (PLAN_RESIDENT_WINDOW, PLAN_SHARED_WINDOW_2, PLAN_SHARED_WINDOW_4, PLAN_STREAMED_WINDOW) or info["window_far_b"] > 0:
             want.add("b")
     rows, cols = (n, batch) if out_layout == OUT_VERTEX_MAJOR else (batch, n)
     if "cp" in want and "cp" not in out:

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcpeval.so")
-SOURCES = ["graph.cpp", "cost.cpp", "api.hip", "kernels.hip", "window_shared.hip", "column_slice.hip", "pct_order.hip", "constraints.hip", "search.hip", "simulate.hip"]
+SOURCES = ["graph.cpp", "cost.cpp", "api.hip", "kernels.hip", "window_shared.hip", "window_stream.hip", "column_slice.hip", "pct_order.hip", "constraints.hip", "search.hip", "simulate.hip"]
 HEADERS = ["cpeval_internal.hpp", "launch.hpp", "device_math.hpp", os.path.join("..", "..", "include", "cpeval.h")]
 
 

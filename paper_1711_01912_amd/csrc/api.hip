@@ -103,7 +103,7 @@ int static_scratch(void **out) {
 }
 
 constexpr size_t kWindowLdsLimit = kLdsBudget - 256;   // room for the kernel's static LDS
-constexpr size_t kSharedStaticLds = 512;               // the shared-window kernel's static LDS beyond that
+constexpr size_t kSharedStaticLds = 512;               // static LDS of the shared-window and streamed kernels beyond that
 
 bool window_fits(const Packed &p, int32_t k, size_t tick_bytes, size_t limit = kWindowLdsLimit,
                  WindowCfg *cfg_b = nullptr, WindowCfg *cfg_t = nullptr) {
@@ -123,6 +123,17 @@ bool shared_fits(const Packed &p, int32_t k, size_t tick_bytes, int groups, size
     SharedCfg b, t;
     if (!shared_config(p.win_b, k, groups, limit - kSharedStaticLds, b)) return false;
     if (!shared_config(p.win_t, k, groups, limit - kSharedStaticLds, t)) return false;
+    if (cfg_b) *cfg_b = b;
+    if (cfg_t) *cfg_t = t;
+    return true;
+}
+
+// The streamed resident-window kernel, both directions.
+bool stream_fits(const Packed &p, int32_t k, size_t tick_bytes, size_t limit, StreamCfg *cfg_b, StreamCfg *cfg_t) {
+    if (!p.have_window || k > kMagicMaxK || tick_bytes != 4 || limit <= kSharedStaticLds) return false;
+    StreamCfg b, t;
+    if (!stream_config(p.win_b, k, limit - kSharedStaticLds, false, b)) return false;
+    if (!stream_config(p.win_t, k, limit - kSharedStaticLds, false, t)) return false;
     if (cfg_b) *cfg_b = b;
     if (cfg_t) *cfg_t = t;
     return true;
@@ -224,7 +235,7 @@ int check_eval_sizes(const cp_graph *g, int32_t batch, int32_t k, int assign_lay
     if (batch < 1 || k < 1 || k > 255) return CP_ERR_SIZE;
     if (assign_layout != CP_ASSIGN_PARTITION_MAJOR && assign_layout != CP_ASSIGN_VERTEX_MAJOR)
         return CP_ERR_ARG;
-    if (plan < CP_PLAN_AUTO || plan > CP_PLAN_COLUMN_SLICE) return CP_ERR_ARG;
+    if (plan < CP_PLAN_AUTO || plan > CP_PLAN_STREAMED_WINDOW) return CP_ERR_ARG;
     return CP_OK;
 }
 
@@ -457,7 +468,11 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
         (!tabs.magic_ok || !shared_fits(p, k, (size_t)tick_dtype, use == CP_PLAN_SHARED_WINDOW_4 ? 4 : 2,
                                         device_window_lds_limit(), &sh_b, &sh_t)))
         return CP_ERR_ARG;
-    const bool windowish = use == CP_PLAN_RESIDENT_WINDOW || shared;
+    StreamCfg st_b, st_t, st_tm;
+    const bool streamed = use == CP_PLAN_STREAMED_WINDOW;
+    if (streamed && (!tabs.magic_ok || !stream_fits(p, k, (size_t)tick_dtype, device_window_lds_limit(), &st_b, &st_t)))
+        return CP_ERR_ARG;
+    const bool windowish = use == CP_PLAN_RESIDENT_WINDOW || shared || streamed;
     const bool columnish = !windowish;       // wave-column, or its persistent column-slice form
     if (use == CP_PLAN_COLUMN_SLICE && (!tabs.magic_ok || k > kMagicMaxK)) return CP_ERR_ARG;
     // the wave-column plan reads CP off the stored b-levels; the window sweeps keep a running maximum
@@ -546,6 +561,10 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
                      tick_dtype == CP_TICK_I32 && ((uintptr_t)blevel_out % 16) == 0 &&
                      ((uint64_t)p.n * (uint64_t)batch * 4) % 16 == 0 &&
                      window_config(p.win_t, k, (size_t)tick_dtype, device_window_lds_limit(), cfg_tm, true);
+    // the streamed kernel: the same rule without the cost model (its workgroups are small either way)
+    const bool fuse_mask_st = streamed && by_partition && mask_out && direct_t && p.win_t.smax >= 4 &&
+                              ((uintptr_t)blevel_out % 16) == 0 && ((uint64_t)p.n * (uint64_t)batch * 4) % 16 == 0 &&
+                              stream_config(p.win_t, k, device_window_lds_limit() - kSharedStaticLds, true, st_tm);
     if (fuse_mask) {
         // The mask variant costs a little per slice (one more LDS read and a compare) and a fixed
         // amount per tick.  On wide ticks that is far less than a streaming pass over b and tl
@@ -557,6 +576,7 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
         fuse_mask = p.win_t.smax >= 4 &&
                     window_sweep_us(p.win_t, cfg_tm, batch) <= window_sweep_us(p.win_t, cfg_t, batch) + mask_pass_us;
     }
+    fuse_mask = fuse_mask || fuse_mask_st;
     if (gather_b) {
         s.win = &p.win_b;
         rc = launch_gather_assign(s, d_pperm_b, stream);
@@ -579,8 +599,8 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
         s.cp_out = windowish ? cp_out : nullptr;
         s.pperm = d_pperm_b;
         s.direct_ids = direct_b;
-        if (shared) {
-            rc = launch_window_shared(s, sh_b, stream);
+        if (shared || streamed) {
+            rc = shared ? launch_window_shared(s, sh_b, stream) : launch_window_stream(s, st_b, stream);
             if (launches) launches[0] = 1;
         } else {
             if (use == CP_PLAN_COLUMN_SLICE) {
@@ -625,8 +645,9 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
             s.mask_cp = cp_out;
             s.mask_out = mask_out;
         }
-        if (shared) {
-            rc = launch_window_shared(s, sh_t, stream);
+        if (shared || streamed) {
+            rc = shared ? launch_window_shared(s, sh_t, stream)
+                        : launch_window_stream(s, fuse_mask ? st_tm : st_t, stream);
             if (launches) launches[1] = 1;
         } else {
             if (use == CP_PLAN_COLUMN_SLICE) {

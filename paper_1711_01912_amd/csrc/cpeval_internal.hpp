@@ -18,6 +18,9 @@ constexpr size_t kAlign = 256;
 constexpr size_t kLdsBudget = 160 * 1024;   // LDS per workgroup on gfx950
 constexpr int kWindowMaxWaves = 16;      // wavefronts per workgroup (compute + loader)
 constexpr int kWindowTickSlices = 8;     // slices (compute wavefronts) per tick
+constexpr int kStreamSlackChunks = 256;  // 16-byte chunks behind the packet stream that a fixed-count entry fetch may touch
+constexpr int kStreamTailTicks = 16;     // empty ticks behind the last one in the slice table (the streaming loop runs on
+                                         // to a multiple of 8 ticks and fetches four ticks ahead)
 constexpr uint64_t kWindowTickBytes = 15 * 1024;   // packet bytes per tick, unless one slice alone is larger
 constexpr int kWindowFarTicks = 12;      // a neighbour this many ticks back (or more) is read from the output array
 constexpr int kWindowFarLead = 4;        // ticks a far wavefront runs ahead (twice: read list, then gather)
@@ -66,6 +69,12 @@ struct WindowDir {
     size_t tick_off = 0;     // uint32 [ticks+1][4] {first chunk, chunks, lowest id, id span}
     size_t gmap_off = 0;     // int32 [ticks*wpad] original id per padded position, -1 = padding
     size_t far_off = 0;      // uint32 [ticks][far_cap][2] {vertex, c} of the tick's far reads (padding: vertex 0)
+    size_t stab_off = 0;     // uint32 [ticks][smax][8] per slice {record chunk, entry chunk, width | rows << 16 | log2 lanes
+                             // per row << 24, lowest id of the tick, ring slot of row 0, 0, 0, 0}: where a compute wavefront
+                             // that streams its own slices finds them (chunks of 16 bytes from the start of the stream;
+                             // slices a tick does not have point at its packet with rows = 0).  0 = not built (only
+                             // for 4-byte entries, a packed ring and no far reads)
+    int32_t max_width = 0;   // entries per lane of the widest slice
     int32_t far_cap = 0;     // far reads per tick, a multiple of 64; 0 = every neighbour is in the ring
     int64_t total_chunks = 0;
     int32_t ticks = 0;

@@ -255,7 +255,12 @@ bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int6
     dir.total_chunks = (int64_t)total;
     dir.max_chunks = (int32_t)max_chunks;
 
-    dir.stream_off = w.reserve(16 * (size_t)std::max<uint64_t>(total, 1));
+    // the stream is followed by slack: a wavefront that streams its own slices always fetches a
+    // fixed number of entry rows, whatever the slice's width
+    dir.stream_off = w.reserve(16 * ((size_t)std::max<uint64_t>(total, 1) + kStreamSlackChunks));
+    const bool with_stab = dir.ent4 && dir.packed && dir.far_cap == 0;
+    // ... and runs kStreamTailTicks ticks past the end with empty slices
+    dir.stab_off = with_stab ? w.reserve(32 * ((size_t)T + kStreamTailTicks) * (size_t)dir.smax) : 0;
     dir.tick_off = w.reserve(sizeof(uint32_t) * tick_tab.size());
     std::memcpy(w.at<uint32_t>(dir.tick_off), tick_tab.data(), sizeof(uint32_t) * tick_tab.size());
     dir.gmap_off = w.reserve(sizeof(int32_t) * (size_t)std::max(T, 1) * dir.wpad);
@@ -263,6 +268,8 @@ bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int6
     // every reservation is made: the blob does not move any more
     int32_t *gmap = w.at<int32_t>(dir.gmap_off);
     uint32_t *far_list = w.at<uint32_t>(dir.far_off);
+    uint32_t *stab = with_stab ? w.at<uint32_t>(dir.stab_off) : nullptr;
+    dir.max_width = 0;
     std::fill(gmap, gmap + (size_t)std::max(T, 1) * dir.wpad, -1);
 
     // far reads of a tick: {vertex, c} per read, padded with vertex 0; the pairs they are
@@ -294,6 +301,15 @@ bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int6
             desc[4 * j + 1] = (uint32_t)width | ((uint32_t)rows << 16) | ((uint32_t)sh << 24);
             desc[4 * j + 2] = tick_tab[4 * s + 2];
             desc[4 * j + 3] = (uint32_t)(p0 % dir.slots);
+            dir.max_width = std::max(dir.max_width, (int32_t)width);
+            if (stab) {
+                uint32_t *e = stab + 8 * ((size_t)s * dir.smax + j);
+                e[0] = tick_tab[4 * s] + (uint32_t)dir.smax + 32u * j;                  // 64 records of 8 bytes per slice
+                e[1] = tick_tab[4 * s] + (ent_start + (uint32_t)esz * ebase) / 16;      // whole chunks: 64 entries a row
+                e[2] = desc[4 * j + 1];
+                e[3] = desc[4 * j + 2];
+                e[4] = desc[4 * j + 3];
+            }
             for (int32_t r = 0; r < kWave; ++r) {       // records: one per row
                 uint32_t *rc = rec + 2 * ((size_t)j * kWave + r);
                 if (r < rows) {
@@ -338,6 +354,11 @@ bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int6
                 }
             }
             ebase += (uint32_t)width * kWave;
+        }
+        for (uint32_t j = nsl; stab && j < (uint32_t)dir.smax; ++j) {   // slices this tick does not have
+            uint32_t *e = stab + 8 * ((size_t)s * dir.smax + j);
+            e[0] = e[1] = tick_tab[4 * s];
+            e[3] = tick_tab[4 * s + 2];
         }
     }
     return true;

@@ -63,6 +63,21 @@ struct SharedCfg {
 bool shared_config(const WindowDir &d, int32_t k, int groups, size_t lds_limit, SharedCfg &out);
 int launch_window_shared(const SweepLaunch &s, const SharedCfg &cfg, void *stream);
 
+// Launch shape of the streamed resident-window kernel (compute wavefronts fetch their own
+// slices; only the per-partition bytes are staged) for one sweep direction.
+struct StreamCfg {
+    bool wide = false; // some slice has more than 8 entries per lane: 16 entry registers instead of 8
+    int nl = 0;        // 16-byte loads per loader lane per tick
+    int nlw = 0;       // loader wavefronts
+    int nc = 0;        // compute wavefronts = slices of the widest tick
+    size_t stage_off = 0, tab_off = 0;   // LDS byte offsets of the stage slots and the cost tables
+    size_t lds_bytes = 0;
+};
+// False if the direction cannot run that way under `lds_limit` bytes of dynamic LDS.
+// with_mask: the t sweep also stages the tick's b values and writes the mask.
+bool stream_config(const WindowDir &d, int32_t k, size_t lds_limit, bool with_mask, StreamCfg &out);
+int launch_window_stream(const SweepLaunch &s, const StreamCfg &cfg, void *stream);
+
 // False if the direction cannot run under `lds_limit` bytes of LDS.
 // with_mask: the t sweep also stages the tick's b values and writes the mask.
 bool window_config(const WindowDir &d, int32_t k, size_t tick_bytes, size_t lds_limit, WindowCfg &out,

@@ -9,7 +9,7 @@ from workloads.dags import _finish
 
 pytestmark = pytest.mark.gpu
 
-PLANS = (1, 2, 3, 4, 5)       # wave-column, resident window, shared window x2 / x4, column slices
+PLANS = (1, 2, 3, 4, 5, 6)    # wave-column, resident window, shared window x2 / x4, column slices, streamed window
 
 
 @pytest.fixture(scope="module")
