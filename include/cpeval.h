@@ -180,7 +180,9 @@ int cp_eval_choose_plan(const cp_graph *g, int32_t batch, int32_t k, const int64
                         const int64_t *bandwidth, int tick_dtype, int *plan_out);
 
 /*
- * Evaluate `batch` partitions.  Only enqueues work on `stream`; it does not wait.
+ * Evaluate `batch` partitions.  Only enqueues work on `stream`; it does not wait (with more
+ * than 64 devices the cost tables, up to 1 MB, go through eight pinned host buffers shared
+ * by the process: the ninth such call in flight waits for the first to have copied its tables).
  *
  *   assignments   device, uint8, [batch][n] or [n][batch] per assign_layout; entries < k
  *   speeds        host, int64 [k], each >= 1
@@ -463,6 +465,15 @@ void cp_profile_destroy(cp_profile *p);
  * is not (the kernels then divide plainly), or a negative CP_ERR_* code.
  */
 int cp_cost_magic(int64_t divisor, int64_t max_dividend, uint32_t *mul, uint32_t *dm1);
+
+/*
+ * Diagnostic: the 4-byte table entry some kernels use instead where every divisor of the
+ * call is at most 256 and every weight below 2^24:
+ *     ceil(a / divisor) == ((a + (e & 0xff)) * (uint64)(e | 0xff) + (a + (e & 0xff))) >> 32.
+ * Returns 1 and fills *entry if that form is exact for 0 <= a <= max_dividend, 0 if not,
+ * or a negative CP_ERR_* code.
+ */
+int cp_cost_compact(int64_t divisor, int64_t max_dividend, uint32_t *entry);
 
 /* Human-readable text for a CP_ERR_* code (static storage). */
 const char *cp_error_string(int code);

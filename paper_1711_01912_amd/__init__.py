@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     PLAN_WAVE_COLUMN,
     POLICY_FIFO,
     POLICY_PCT,
+    cost_compact,
     cost_magic,
     cp_critical_path,
     cp_pct_order,

@@ -33,7 +33,7 @@ EXPORTS = (
     "cp_simulate_workspace_bytes", "cp_simulate",
     "cp_profile_create", "cp_profile_reset",
     "cp_profile_count", "cp_profile_read", "cp_profile_destroy", "cp_cost_magic",
-    "cp_error_string",
+    "cp_error_string", "cp_cost_compact",
 )
 
 
@@ -142,6 +142,8 @@ def load_library():
     lib.cp_cost_magic.restype = C.c_int
     lib.cp_cost_magic.argtypes = [C.c_int64, C.c_int64, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
     lib.cp_error_string.restype = C.c_char_p
+    lib.cp_cost_compact.restype = C.c_int
+    lib.cp_cost_compact.argtypes = [C.c_int64, C.c_int64, C.POINTER(C.c_uint32)]
     lib.cp_error_string.argtypes = [C.c_int]
     _lib = lib
     return lib
@@ -158,6 +160,15 @@ def cost_magic(divisor: int, max_dividend: int):
     if rc < 0:
         raise CpError(rc, "cp_cost_magic")
     return (int(mul.value), int(dm1.value)) if rc == 1 else None
+
+
+def cost_compact(divisor: int, max_dividend: int):
+    """The 4-byte table entry for ceil(a / divisor), 0 <= a <= max_dividend, or None where that form is not exact."""
+    e = C.c_uint32(0)
+    rc = load_library().cp_cost_compact(int(divisor), int(max_dividend), C.byref(e))
+    if rc < 0:
+        raise CpError(rc, "cp_cost_compact")
+    return int(e.value) if rc == 1 else None
 
 
 def _np_ptr(a, ctype):

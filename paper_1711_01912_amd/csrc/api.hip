@@ -21,8 +21,9 @@ struct cp_profile {
 
 namespace {
 
-// Pinned staging slots for the per-call cost tables, reused round-robin; a slot is
-// only rewritten after the copy that last read it has finished.
+// Pinned staging slots for the cost tables of calls with more than 64 devices (up to 1 MB),
+// reused round-robin; a slot is only rewritten after the copy that last read it has finished,
+// so the ninth such call in flight waits for the first.
 struct StageSlot {
     void *host = nullptr;
     size_t cap = 0;
@@ -81,6 +82,14 @@ int write_tables_by_kernel(const void *src, size_t entries, void *dst, hipStream
     return hipGetLastError() == hipSuccess ? CP_OK : CP_ERR_HIP;
 }
 
+// Cost tables of one call into device memory.  Up to 64 devices (66 KB) they travel as kernel
+// arguments: nothing is allocated, nothing waits, and calls on different streams or threads
+// do not meet.  Larger tables go through the pinned staging ring above.
+int upload_tables(const void *src, size_t entries, void *dst, hipStream_t st, bool by_kernel_only = false) {
+    if (by_kernel_only || entries <= table_words(kMagicMaxK)) return write_tables_by_kernel(src, entries, dst, st);
+    return stage_and_copy(src, entries * 8, dst, st);
+}
+
 // Scratch memory of cp_eval_static: one array per GPU, part of the loaded code object, never
 // allocated or freed.  In host code the array's name is only a handle: the device address is
 // looked up once per device and kept.
@@ -106,9 +115,10 @@ constexpr size_t kWindowLdsLimit = kLdsBudget - 256;   // room for the kernel's 
 constexpr size_t kSharedStaticLds = 512;               // static LDS of the shared-window and streamed kernels beyond that
 
 bool window_fits(const Packed &p, int32_t k, size_t tick_bytes, size_t limit = kWindowLdsLimit,
-                 WindowCfg *cfg_b = nullptr, WindowCfg *cfg_t = nullptr) {
+                 WindowCfg *cfg_b = nullptr, WindowCfg *cfg_t = nullptr, bool tab4 = false) {
     if (!p.have_window || k > kMagicMaxK) return false;
     WindowCfg b, t;
+    (void)tab4;
     if (!window_config(p.win_b, k, tick_bytes, limit, b)) return false;
     if (!window_config(p.win_t, k, tick_bytes, limit, t)) return false;
     if (cfg_b) *cfg_b = b;
@@ -118,11 +128,11 @@ bool window_fits(const Packed &p, int32_t k, size_t tick_bytes, size_t limit = k
 
 // The shared-window kernel with `groups` partitions per workgroup, both directions.
 bool shared_fits(const Packed &p, int32_t k, size_t tick_bytes, int groups, size_t limit, SharedCfg *cfg_b,
-                 SharedCfg *cfg_t) {
+                 SharedCfg *cfg_t, bool tab4 = false) {
     if (!p.have_window || k > kMagicMaxK || tick_bytes != 4 || limit <= kSharedStaticLds) return false;
     SharedCfg b, t;
-    if (!shared_config(p.win_b, k, groups, limit - kSharedStaticLds, b)) return false;
-    if (!shared_config(p.win_t, k, groups, limit - kSharedStaticLds, t)) return false;
+    if (!shared_config(p.win_b, k, groups, limit - kSharedStaticLds, b, tab4)) return false;
+    if (!shared_config(p.win_t, k, groups, limit - kSharedStaticLds, t, tab4)) return false;
     if (cfg_b) *cfg_b = b;
     if (cfg_t) *cfg_t = t;
     return true;
@@ -206,13 +216,14 @@ bool window_preferred(const Packed &p, const WindowCfg &cb, const WindowCfg &ct,
 // against 0.56 and 0.80 ms; 5,271 vertices x 16,384 partitions 1.08 against 1.31 and 1.05 ms).
 // mask_penalty_us: what the shared plans pay for the mask pass the other plan would not need.
 int choose_window_plan(const Packed &p, int32_t k, size_t tick_bytes, size_t lds_limit, const WindowCfg &cb,
-                       const WindowCfg &ct, int32_t batch, double mask_penalty_us, SharedCfg *sh_b, SharedCfg *sh_t) {
+                       const WindowCfg &ct, int32_t batch, double mask_penalty_us, SharedCfg *sh_b, SharedCfg *sh_t,
+                       bool tab4 = false) {
     int best = CP_PLAN_RESIDENT_WINDOW;
     if (window_wg_per_cu(cb) > 1.0 || window_wg_per_cu(ct) > 1.0) return best;
     double best_us = window_sweep_us(p.win_b, cb, batch) + window_sweep_us(p.win_t, ct, batch);
     for (int groups = 2; groups <= 4; groups += 2) {
         SharedCfg b, t;
-        if (!shared_fits(p, k, tick_bytes, groups, lds_limit, &b, &t)) continue;
+        if (!shared_fits(p, k, tick_bytes, groups, lds_limit, &b, &t, tab4)) continue;
         const double us = shared_sweep_us(p.win_b, groups, batch) + shared_sweep_us(p.win_t, groups, batch) +
                           mask_penalty_us;
         if (us < best_us) {
@@ -225,7 +236,18 @@ int choose_window_plan(const Packed &p, int32_t k, size_t tick_bytes, size_t lds
     return best;
 }
 
-size_t tables_bytes(int32_t k) { return align_up(table_entries(k) * 8); }
+size_t tables_bytes(int32_t k) { return align_up(table_words(k) * 8); }
+
+// One call's tables as they lie in device memory: the 8-byte entries (multiply-shift constants,
+// or plain divisors), then, where they exist, the 4-byte entries.
+std::vector<uint64_t> table_image(const CostTables &tabs, int32_t k) {
+    std::vector<uint64_t> img(table_words(k), 0);
+    const size_t entries = table_entries(k);
+    std::memcpy(img.data(), tabs.magic_ok ? (const void *)tabs.magic.data() : (const void *)tabs.divisor.data(),
+                entries * 8);
+    if (tabs.tab4_ok) std::memcpy(img.data() + entries, tabs.tab4.data(), entries * 4);
+    return img;
+}
 size_t column_scratch_bytes(const Packed &p, int32_t batch, int tick_bytes) {
     return align_up((size_t)p.n * (size_t)batch * (size_t)tick_bytes);
 }
@@ -449,7 +471,7 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
     // plan
     WindowCfg cfg_b, cfg_t;
     const bool can_window = tabs.magic_ok && window_fits(p, k, (size_t)tick_dtype,
-                                                         device_window_lds_limit(), &cfg_b, &cfg_t);
+                                                         device_window_lds_limit(), &cfg_b, &cfg_t, tabs.tab4_ok);
     int use = plan;
     SharedCfg sh_b, sh_t;
     if (plan == CP_PLAN_AUTO) {
@@ -458,7 +480,7 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
             // with a mask to write, the shared plans pay for a pass of their own over b and tl
             const double mask_us = mask_out ? 5.0 + (double)p.n * batch * (2.0 * tick_dtype + 0.125) / 4.0e6 : 0.0;
             use = choose_window_plan(p, k, (size_t)tick_dtype, device_window_lds_limit(), cfg_b, cfg_t, batch, mask_us,
-                                     &sh_b, &sh_t);
+                                     &sh_b, &sh_t, tabs.tab4_ok);
         }
     }
     if (use == CP_PLAN_RESIDENT_WINDOW && !can_window) return CP_ERR_ARG;
@@ -466,7 +488,7 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
     const bool shared = use == CP_PLAN_SHARED_WINDOW_2 || use == CP_PLAN_SHARED_WINDOW_4;
     if (shared && plan != CP_PLAN_AUTO &&
         (!tabs.magic_ok || !shared_fits(p, k, (size_t)tick_dtype, use == CP_PLAN_SHARED_WINDOW_4 ? 4 : 2,
-                                        device_window_lds_limit(), &sh_b, &sh_t)))
+                                        device_window_lds_limit(), &sh_b, &sh_t, tabs.tab4_ok)))
         return CP_ERR_ARG;
     StreamCfg st_b, st_t, st_tm;
     const bool streamed = use == CP_PLAN_STREAMED_WINDOW;
@@ -527,9 +549,8 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
     CP_MARK(CP_STAGE_PREP);
     rc = launch_clear(cp_out, batch, status_out, stream);
     if (rc) return rc;
-    const void *tab_src = tabs.magic_ok ? (const void *)tabs.magic.data() : (const void *)tabs.divisor.data();
-    rc = tables_by_kernel ? write_tables_by_kernel(tab_src, table_entries(k), d_tab, st)
-                          : stage_and_copy(tab_src, table_entries(k) * 8, d_tab, st);
+    const std::vector<uint64_t> tab_img = table_image(tabs, k);
+    rc = upload_tables(tab_img.data(), tab_img.size(), d_tab, st, tables_by_kernel);
     if (rc) return rc;
     const uint8_t *pT = assignments;
     if (need_pT) {
@@ -546,6 +567,8 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
     s.narrow = p.narrow;
     s.tick_bytes = tick_dtype;
     s.n = p.n; s.P = batch; s.k = k; s.L = p.L; s.max_width = p.max_width;
+    const uint32_t *d_tab4 = tabs.tab4_ok ? (const uint32_t *)(d_tab + table_entries(k) * 8) : nullptr;
+    s.vert_tab4 = d_tab4 ? d_tab4 + 2 * kk : nullptr;
     s.pT = pT;
     s.assign = assignments;
     if (assign_layout == CP_ASSIGN_PARTITION_MAJOR) { s.a_stride_p = p.n; s.a_stride_v = 1; }
@@ -596,6 +619,7 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
         s.win = &p.win_b;
         s.val = windowish ? blevel_out : col_b;
         s.edge_tab = d_tab;
+        s.edge_tab4 = d_tab4;
         s.cp_out = windowish ? cp_out : nullptr;
         s.pperm = d_pperm_b;
         s.direct_ids = direct_b;
@@ -634,6 +658,7 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
         s.win = &p.win_t;
         s.val = windowish ? tlevel_out : col_t;
         s.edge_tab = d_tab + kk * 8;
+        s.edge_tab4 = d_tab4 ? d_tab4 + kk : nullptr;
         s.cp_out = nullptr;
         s.pperm = d_pperm_t;
         s.direct_ids = direct_t;
@@ -733,7 +758,7 @@ int cp_critical_path(const cp_graph *g, int32_t batch, int32_t k,
     if (rc) return rc;
     uint8_t *d_tab = (uint8_t *)workspace;
     const void *tab_src = tabs.magic_ok ? (const void *)tabs.magic.data() : (const void *)tabs.divisor.data();
-    rc = stage_and_copy(tab_src, table_entries(k) * 8, d_tab, st);
+    rc = upload_tables(tab_src, table_entries(k), d_tab, st);
     if (rc) return rc;
     SweepLaunch s;
     s.blob = (const uint8_t *)g->device_blob;
@@ -894,7 +919,7 @@ int cp_simulate(const cp_graph *g, int32_t batch, int32_t k,
     if (rc) return rc;
     uint8_t *ws = (uint8_t *)workspace;
     const void *tab_src = tabs.magic_ok ? (const void *)tabs.magic.data() : (const void *)tabs.divisor.data();
-    rc = stage_and_copy(tab_src, table_entries(k) * 8, ws, st);
+    rc = upload_tables(tab_src, table_entries(k), ws, st);
     if (rc) return rc;
     SimulateLaunch s;
     s.blob = (const uint8_t *)g->device_blob;
@@ -1046,6 +1071,18 @@ int cp_cost_magic(int64_t divisor, int64_t max_dividend, uint32_t *mul, uint32_t
     if (!t.magic_ok) return 0;
     *mul = t.magic[2].mul;
     *dm1 = t.magic[2].dm1;
+    return 1;
+}
+
+int cp_cost_compact(int64_t divisor, int64_t max_dividend, uint32_t *entry) {
+    if (!entry) return CP_ERR_NULL;
+    if (divisor < 1 || max_dividend < 0) return CP_ERR_SIZE;
+    int64_t s = divisor, b[1] = {1};
+    CostTables t;
+    int rc = build_cost_tables(1, &s, b, true, max_dividend, 0, t);
+    if (rc) return rc;
+    if (!t.tab4_ok) return 0;
+    *entry = t.tab4[2];
     return 1;
 }
 

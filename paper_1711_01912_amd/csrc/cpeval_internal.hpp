@@ -122,6 +122,11 @@ struct CostTables {
     std::vector<Magic> magic;           // [k*k edge (row = own device, col = neighbour), b sweep]
                                         // [k*k the same transposed, t sweep] [k vertex]
     std::vector<int64_t> divisor;       // same layout, plain divisors; 0 = free transfer
+    // The compact form: every divisor <= 256 and exact as (d - 1) | (upper 24 bits of the multiplier) << 8
+    // for this graph's weights, which must be below 2^24.  A 4-byte entry can sit in LDS once per
+    // bank, which takes the bank conflicts out of the kernels' table reads.
+    bool tab4_ok = false;
+    std::vector<uint32_t> tab4;         // same layout; 0 = free transfer
 };
 
 // Returns CP_OK, CP_ERR_SPEED or CP_ERR_BANDWIDTH.
@@ -129,6 +134,8 @@ int build_cost_tables(int32_t k, const int64_t *speeds, const int64_t *bandwidth
                       bool narrow, int64_t max_c, int64_t max_t, CostTables &out);
 
 inline size_t table_entries(int32_t k) { return (size_t)2 * k * k + k; }
+// 64-bit words of one call's tables in device memory: the 8-byte entries, then the 4-byte ones
+inline size_t table_words(int32_t k) { return table_entries(k) + (table_entries(k) + 1) / 2; }
 
 }  // namespace cpeval
 

@@ -18,6 +18,14 @@ __device__ __forceinline__ uint32_t magic_div(uint32_t a, Magic mg) {
     return (uint32_t)(((uint64_t)nn * mg.mul + nn) >> 32);
 }
 
+// The same through a 4-byte table entry (d - 1 in the low byte, the upper 24 bits of the
+// multiplier above it; the multiplier's low byte is taken as all ones); 0 (a free transfer)
+// yields 0 for every a < 2^24.  Exact for every a the entry was built for.
+__device__ __forceinline__ uint32_t magic_div(uint32_t a, uint32_t entry) {
+    uint32_t nn = a + (entry & 0xffu);
+    return (uint32_t)(((uint64_t)nn * (entry | 0xffu) + nn) >> 32);
+}
+
 // ceil(a/d) by division; d = 0 marks a free transfer.
 __device__ __forceinline__ uint64_t plain_div(uint64_t a, uint64_t d) {
     return d ? (a + d - 1) / d : 0;

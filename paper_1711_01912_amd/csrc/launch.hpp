@@ -28,6 +28,8 @@ struct SweepLaunch {
     int64_t *cp_out = nullptr;          // resident-window b sweep only
     const void *edge_tab = nullptr;
     const void *vert_tab = nullptr;
+    const uint32_t *edge_tab4 = nullptr;   // the same tables as 4-byte entries, or null
+    const uint32_t *vert_tab4 = nullptr;
     int32_t *status = nullptr;
     // resident-window t sweep that also writes the mask rows (partition-major): b, CP and the
     // zeroed mask; all null otherwise
@@ -58,9 +60,15 @@ struct SharedCfg {
     int nc = 0;        // compute wavefronts
     size_t vals_off = 0, stage_off = 0, tab_off = 0;   // LDS byte offsets: ring values, stage slots, cost tables
     size_t lds_bytes = 0;
+    int tab_rs = -1;   // >= 0: 4-byte cost-table entries, each 2^tab_rs times in LDS
 };
 // False if the direction cannot run that way under `lds_limit` bytes of dynamic LDS.
-bool shared_config(const WindowDir &d, int32_t k, int groups, size_t lds_limit, SharedCfg &out);
+// tab4: the call's cost tables exist as 4-byte entries.
+bool shared_config(const WindowDir &d, int32_t k, int groups, size_t lds_limit, SharedCfg &out, bool tab4 = false);
+// Bytes of the cost tables in LDS as 4-byte entries, every transfer entry 2^rs times.
+inline size_t tab4_lds_bytes(int32_t k, int rs) {
+    return ((((size_t)k * k * 4) << rs) + (size_t)k * 4 + 15) & ~(size_t)15;
+}
 int launch_window_shared(const SweepLaunch &s, const SharedCfg &cfg, void *stream);
 
 // Launch shape of the streamed resident-window kernel (compute wavefronts fetch their own

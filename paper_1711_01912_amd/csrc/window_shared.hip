@@ -37,6 +37,9 @@ struct SharedArgs {
     int64_t *cp_out;           // [P] or NULL
     const Magic *edge_tab;
     const Magic *vert_tab;
+    const uint32_t *edge_tab4; // TAB4: the same tables as 4-byte entries
+    const uint32_t *vert_tab4;
+    int32_t tab_rs;            // TAB4: every transfer entry sits 2^tab_rs times in LDS
     int32_t *status;
     int64_t out_sq;
     uint32_t out_sv;
@@ -64,8 +67,12 @@ __device__ __forceinline__ uint32_t val_of(const typename GroupVals<G>::type &v,
 // wavefronts relax the tick out of stage slot t&1 while the loaders copy packet t+1
 // (requested DR ticks earlier, held in registers) into the other slot and request packet
 // t+1+DR.
-template <bool TSWEEP, int G, bool ENT4, int NL, int DR>
+//
+// TAB4: the cost tables are 4-byte entries and every transfer entry sits 2^tab_rs times in LDS,
+// copy r in bank (r mod 32); lane l reads copy l mod 2^tab_rs: fewer lanes meet in a bank.
+template <bool TSWEEP, int G, bool ENT4, int NL, int DR, bool TAB4>
 __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_shared_kernel(SharedArgs a) {
+    typedef typename std::conditional<TAB4, uint32_t, Magic>::type Tab;
     extern __shared__ uint4 lds16[];
     __shared__ long long red[G][kWindowMaxWaves];
     uint8_t *lds = (uint8_t *)lds16;
@@ -87,14 +94,22 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_shared_kernel(Sha
 #pragma unroll
     for (int g = 0; g < G; ++g) q[g] = min(wg * G + g, a.P - 1);
 
-    const uint32_t etab_off = a.tab_off, vtab_off = a.tab_off + 8u * (uint32_t)(k * k);
+    const int dev_sh = TAB4 ? 2 + a.tab_rs : 3;          // bytes between the entries of two devices, as a shift
+    const uint32_t etab_off = a.tab_off, vtab_off = a.tab_off + ((uint32_t)(k * k) << dev_sh);
     const int slot_bytes = NL * a.nlw * 1024;
     uint8_t *stage = lds + a.stage_off;
     {
-        const uint64_t *e = (const uint64_t *)a.edge_tab, *v = (const uint64_t *)a.vert_tab;
-        uint64_t *t64 = (uint64_t *)(lds + etab_off);
-        for (int i = tid; i < k * k; i += nt) t64[i] = e[i];
-        for (int i = tid; i < k; i += nt) t64[k * k + i] = v[i];
+        if constexpr (TAB4) {
+            uint32_t *t32 = (uint32_t *)(lds + etab_off);
+            const int copies = k * k << a.tab_rs;
+            for (int i = tid; i < copies; i += nt) t32[i] = a.edge_tab4[i >> a.tab_rs];
+            for (int i = tid; i < k; i += nt) t32[copies + i] = a.vert_tab4[i];
+        } else {
+            const uint64_t *e = (const uint64_t *)a.edge_tab, *v = (const uint64_t *)a.vert_tab;
+            uint64_t *t64 = (uint64_t *)(lds + etab_off);
+            for (int i = tid; i < k * k; i += nt) t64[i] = e[i];
+            for (int i = tid; i < k; i += nt) t64[k * k + i] = v[i];
+        }
         if (tid < G) {                           // the constant-zero slot padding entries point at
             lds[(size_t)R * G + tid] = 0;
             ((uint32_t *)(lds + a.vals_off))[(size_t)R * G + tid] = 0;
@@ -183,7 +198,8 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_shared_kernel(Sha
         __builtin_amdgcn_s_setprio(1);
         typedef typename std::conditional<ENT4, uint32_t, uint2>::type Ent;
         const uint32_t out_sv = a.out_sv;
-        const uint32_t k8 = 8u * (uint32_t)k;
+        const uint32_t k8 = (uint32_t)k << dev_sh;        // bytes of one table row
+        const uint32_t copy_off = TAB4 ? 4u * ((uint32_t)lane & ((1u << a.tab_rs) - 1u)) : 0u;   // this lane's copy
         const uint32_t rec_off = (uint32_t)head + 16u * (uint32_t)a.smax;   // records, from the slot base
         const uint32_t vals_off = a.vals_off;
         int32_t *outq[G];
@@ -215,7 +231,7 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_shared_kernel(Sha
             const uint2 rc = *((const uint2 *)(st + rec_off) + p);
             const Ent *ent = (const Ent *)(st + head + ent_off) + lane;
             uint32_t pv[G], erow[G], acc[G];
-            Magic mv[G];
+            Tab mv[G];
             // N relaxations for all G partitions as one straight-line block: N entry reads,
             // N reads of the G device ids and N of the G values, N*G cost-table reads, then
             // the arithmetic
@@ -224,7 +240,7 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_shared_kernel(Sha
         Ent en_[N];                                                                             \
         Vals vu_[N];                                                                            \
         uint32_t du_[N];                                                                        \
-        Magic mg_[N][G];                                                                        \
+        Tab mg_[N][G];                                                                          \
         _Pragma("unroll") for (int i_ = 0; i_ < N; ++i_) en_[i_] = ent[(jj + i_) * 64];         \
         _Pragma("unroll") for (int i_ = 0; i_ < N; ++i_) {                                      \
             const uint32_t f_ = ent_field(en_[i_]);                                             \
@@ -233,7 +249,7 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_shared_kernel(Sha
         }                                                                                       \
         _Pragma("unroll") for (int i_ = 0; i_ < N; ++i_)                                        \
             _Pragma("unroll") for (int g_ = 0; g_ < G; ++g_)                                    \
-                mg_[i_][g_] = *(const Magic *)(lds + erow[g_] + 8u * ((du_[i_] >> (8 * g_)) & 0xffu)); \
+                mg_[i_][g_] = *(const Tab *)(lds + erow[g_] + (((du_[i_] >> (8 * g_)) & 0xffu) << dev_sh)); \
         _Pragma("unroll") for (int i_ = 0; i_ < N; ++i_)                                        \
             _Pragma("unroll") for (int g_ = 0; g_ < G; ++g_)                                    \
                 acc[g_] = max(acc[g_], val_of<G>(vu_[i_], g_) + magic_div(ent_t(en_[i_]), mg_[i_][g_])); \
@@ -249,8 +265,8 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_shared_kernel(Sha
             for (int g = 0; g < G; ++g) {
                 worst = max(worst, pv[g]);
                 pv[g] = min(pv[g], (uint32_t)(k - 1));
-                erow[g] = etab_off + __umul24(pv[g], k8);
-                mv[g] = *(const Magic *)(lds + vtab_off + 8u * pv[g]);
+                erow[g] = etab_off + __umul24(pv[g], k8) + copy_off;
+                mv[g] = *(const Tab *)(lds + vtab_off + (uint32_t)sizeof(Tab) * pv[g]);
                 acc[g] = 0;
             }
             int jj = 0;
@@ -333,7 +349,7 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_shared_kernel(Sha
 
 inline int hip_ok(hipError_t e) { return e == hipSuccess ? CP_OK : CP_ERR_HIP; }
 
-template <bool TSWEEP, int G, bool ENT4, int NL, int DR>
+template <bool TSWEEP, int G, bool ENT4, int NL, int DR, bool TAB4>
 int launch_shared_k(const SweepLaunch &s, const SharedCfg &cfg, hipStream_t st) {
     const WindowDir &dir = *s.win;
     SharedArgs a{};
@@ -346,6 +362,10 @@ int launch_shared_k(const SweepLaunch &s, const SharedCfg &cfg, hipStream_t st) 
     a.cp_out = s.cp_out;
     a.edge_tab = (const Magic *)s.edge_tab;
     a.vert_tab = (const Magic *)s.vert_tab;
+    a.edge_tab4 = s.edge_tab4;
+    a.vert_tab4 = s.vert_tab4;
+    a.tab_rs = cfg.tab_rs;
+    if (TAB4 && (cfg.tab_rs < 0 || cfg.tab_rs > 5 || !s.edge_tab4 || !s.vert_tab4)) return CP_ERR_ARG;
     a.status = s.status;
     a.out_sq = s.out_sq;
     a.out_sv = (uint32_t)s.out_sv;
@@ -358,7 +378,7 @@ int launch_shared_k(const SweepLaunch &s, const SharedCfg &cfg, hipStream_t st) 
     a.stage_off = (uint32_t)cfg.stage_off;
     a.tab_off = (uint32_t)cfg.tab_off;
     a.out32 = s.n < (1 << 24) && s.P < (1 << 24) && (uint64_t)s.n * (uint64_t)s.P < (1ull << 31);
-    auto kern = window_shared_kernel<TSWEEP, G, ENT4, NL, DR>;
+    auto kern = window_shared_kernel<TSWEEP, G, ENT4, NL, DR, TAB4>;
     if (cfg.lds_bytes > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)cfg.lds_bytes);
@@ -368,15 +388,21 @@ int launch_shared_k(const SweepLaunch &s, const SharedCfg &cfg, hipStream_t st) 
     return hip_ok(hipGetLastError());
 }
 
-template <bool TSWEEP, int G, bool ENT4>
-int launch_shared_e(const SweepLaunch &s, const SharedCfg &cfg, hipStream_t st) {
+template <bool TSWEEP, int G, bool ENT4, bool TAB4>
+int launch_shared_t(const SweepLaunch &s, const SharedCfg &cfg, hipStream_t st) {
     switch (cfg.nl) {   // loads per loader lane per tick x ticks in flight: 64 registers at most
-        case 1: return launch_shared_k<TSWEEP, G, ENT4, 1, 8>(s, cfg, st);
-        case 2: return launch_shared_k<TSWEEP, G, ENT4, 2, 8>(s, cfg, st);
-        case 3: return launch_shared_k<TSWEEP, G, ENT4, 3, 5>(s, cfg, st);
-        case 4: return launch_shared_k<TSWEEP, G, ENT4, 4, 4>(s, cfg, st);
+        case 1: return launch_shared_k<TSWEEP, G, ENT4, 1, 8, TAB4>(s, cfg, st);
+        case 2: return launch_shared_k<TSWEEP, G, ENT4, 2, 8, TAB4>(s, cfg, st);
+        case 3: return launch_shared_k<TSWEEP, G, ENT4, 3, 5, TAB4>(s, cfg, st);
+        case 4: return launch_shared_k<TSWEEP, G, ENT4, 4, 4, TAB4>(s, cfg, st);
         default: return CP_ERR_ARG;
     }
+}
+
+template <bool TSWEEP, int G, bool ENT4>
+int launch_shared_e(const SweepLaunch &s, const SharedCfg &cfg, hipStream_t st) {
+    return cfg.tab_rs >= 0 ? launch_shared_t<TSWEEP, G, ENT4, true>(s, cfg, st)
+                           : launch_shared_t<TSWEEP, G, ENT4, false>(s, cfg, st);
 }
 
 template <bool TSWEEP>
@@ -390,7 +416,7 @@ int launch_shared_g(const SweepLaunch &s, const SharedCfg &cfg, hipStream_t st) 
 
 }  // namespace
 
-bool shared_config(const WindowDir &d, int32_t k, int groups, size_t lds_limit, SharedCfg &out) {
+bool shared_config(const WindowDir &d, int32_t k, int groups, size_t lds_limit, SharedCfg &out, bool tab4) {
     if (!d.packed || d.far_cap > 0 || (groups != 2 && groups != 4)) return false;
     const size_t G = (size_t)groups;
     const size_t devs = align_up(((size_t)d.slots + 1) * G, 16);
@@ -413,6 +439,15 @@ bool shared_config(const WindowDir &d, int32_t k, int groups, size_t lds_limit, 
         c.tab_off = c.stage_off + (size_t)2 * nl * nlw * 1024;
         c.lds_bytes = c.tab_off + tab;
         if (c.lds_bytes > lds_limit) continue;
+        // 4-byte cost tables with as many copies of every transfer entry as fit (up to one per
+        // LDS bank): wide ticks only, as for the resident-window kernel
+        for (int rs = 5; tab4 && d.smax >= 4 && rs >= 2; --rs) {
+            if (c.tab_off + tab4_lds_bytes(k, rs) <= lds_limit) {
+                c.tab_rs = rs;
+                c.lds_bytes = c.tab_off + tab4_lds_bytes(k, rs);
+                break;
+            }
+        }
         out = c;
         return true;
     }

@@ -242,6 +242,43 @@ def test_multiply_shift_exhaustive_small_range(lib):
         assert (got == (a + np.uint64(d - 1)) // np.uint64(d)).all()
 
 
+def test_four_byte_table_entries_are_exact(lib):
+    """Every dividend of the range, every divisor up to 256: the 4-byte form equals ceil(a / d)
+    wherever the library offers it, and it is offered for the benchmark's ranges."""
+    offered = 0
+    for amax in (0, 1, 1000, 10_000, 70_000, 2**20, 2**24 - 1):
+        if amax <= 70_000:
+            a = np.arange(0, amax + 1, dtype=np.uint64)
+        else:
+            rng = np.random.default_rng(amax)
+            a = np.unique(np.concatenate([np.arange(0, 3000), np.arange(amax - 3000, amax + 1),
+                                          rng.integers(0, amax + 1, size=20000)])).astype(np.uint64)
+        for d in range(1, 258):
+            e = cpe.cost_compact(d, amax)
+            if e is None:
+                assert d > 256 or (amax + d - 1) * 257 * d >= 2**32, (d, amax)   # only where exactness is not provable
+                continue
+            offered += 1
+            assert e & 0xff == d - 1
+            if amax > 70_000:                       # multiples of d near the top of the range as well
+                top = (np.uint64(amax) // np.uint64(d)) * np.uint64(d)
+                aa = np.unique(np.concatenate([a, top - np.arange(0, 3, dtype=np.uint64) * np.uint64(d),
+                                               top + np.uint64(1) - np.arange(0, 3, dtype=np.uint64) * np.uint64(d)]))
+                aa = aa[aa <= np.uint64(amax)]
+            else:
+                aa = a
+            n_ = aa + np.uint64(e & 0xff)
+            got = (n_ * np.uint64(e | 0xff) + n_) >> np.uint64(32)
+            assert (got == (aa + np.uint64(d - 1)) // np.uint64(d)).all(), (d, amax)
+    assert offered > 1000
+    # the large sparse workload's ranges: volumes up to 10,000 over rates up to 64, work up to 1,000 over speeds up to 16
+    assert all(cpe.cost_compact(d, 10_000) is not None for d in range(1, 65))
+    assert cpe.cost_compact(257, 100) is None and cpe.cost_compact(3, 2**24) is None
+    # a free transfer's entry 0 gives 0 ticks for every volume below 2^24
+    a = np.array([0, 1, 12345, 2**24 - 1], dtype=np.uint64)
+    assert (((a * np.uint64(0xff) + a) >> np.uint64(32)) == 0).all()
+
+
 def test_consumer_entry_points_check_their_arguments(lib):
     """cp_critical_path, cp_pct_order and cp_ranks reject bad arguments before touching the GPU."""
     w = make_workload("tiny")
