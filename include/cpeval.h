@@ -475,6 +475,17 @@ int cp_cost_magic(int64_t divisor, int64_t max_dividend, uint32_t *mul, uint32_t
  */
 int cp_cost_compact(int64_t divisor, int64_t max_dividend, uint32_t *entry);
 
+/*
+ * Diagnostic: the workgroup shape the resident-window plan would launch with for one sweep
+ * (tsweep = 0: b-levels, 1: t-levels) of this graph with k devices, on a compute unit with
+ * 160 KB of LDS.  shape[0..7] = 16-byte loads per loader lane and tick, loader wavefronts, far
+ * wavefronts, compute wavefronts, ticks of prefetch, partitions per workgroup, output stores one
+ * compute wavefront issues per tick (1 or 2: the bound the far reads' ordering rests on), LDS
+ * bytes per workgroup.  Host only.  Returns CP_OK, CP_ERR_NULL, CP_ERR_ARG (no such shape: the
+ * plan does not apply to this graph, device count or tick type).
+ */
+int cp_window_shape(const cp_graph *g, int32_t k, int tick_dtype, int tsweep, int32_t shape[8]);
+
 /* Human-readable text for a CP_ERR_* code (static storage). */
 const char *cp_error_string(int code);
 

@@ -33,7 +33,7 @@ EXPORTS = (
     "cp_simulate_workspace_bytes", "cp_simulate",
     "cp_profile_create", "cp_profile_reset",
     "cp_profile_count", "cp_profile_read", "cp_profile_destroy", "cp_cost_magic",
-    "cp_error_string", "cp_cost_compact",
+    "cp_error_string", "cp_cost_compact", "cp_window_shape",
 )
 
 
@@ -142,6 +142,8 @@ def load_library():
     lib.cp_cost_magic.restype = C.c_int
     lib.cp_cost_magic.argtypes = [C.c_int64, C.c_int64, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
     lib.cp_error_string.restype = C.c_char_p
+    lib.cp_window_shape.restype = C.c_int
+    lib.cp_window_shape.argtypes = [C.c_void_p, C.c_int32, C.c_int, C.c_int, C.POINTER(C.c_int32)]
     lib.cp_cost_compact.restype = C.c_int
     lib.cp_cost_compact.argtypes = [C.c_int64, C.c_int64, C.POINTER(C.c_uint32)]
     lib.cp_error_string.argtypes = [C.c_int]
@@ -223,6 +225,19 @@ class CpGraph:
         if rc:
             raise CpError(rc, "cp_graph_get_info")
         return gi.as_dict()
+
+    def window_shape(self, k: int, tsweep: bool = False, tick_dtype: int = TICK_I32) -> dict:
+        """cp_window_shape: the resident-window plan's workgroup shape for one sweep, or None where the plan
+        does not apply."""
+        out = (C.c_int32 * 8)()
+        rc = self._lib.cp_window_shape(self._handle, int(k), int(tick_dtype), int(bool(tsweep)), out)
+        if rc == -12:
+            return None
+        if rc:
+            raise CpError(rc, "cp_window_shape")
+        names = ("loads_per_lane", "loader_waves", "far_waves", "compute_waves", "prefetch_ticks",
+                 "partitions_per_workgroup", "stores_per_tick", "lds_bytes")
+        return dict(zip(names, (int(v) for v in out)))
 
     def upload(self, device="cuda:0", stream=None):
         import torch

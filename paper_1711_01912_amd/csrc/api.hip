@@ -1086,6 +1086,20 @@ int cp_cost_compact(int64_t divisor, int64_t max_dividend, uint32_t *entry) {
     return 1;
 }
 
+int cp_window_shape(const cp_graph *g, int32_t k, int tick_dtype, int tsweep, int32_t shape[8]) {
+    if (!g || !shape) return CP_ERR_NULL;
+    if (k < 1 || k > kMagicMaxK || (tick_dtype != CP_TICK_I32 && tick_dtype != CP_TICK_I64)) return CP_ERR_ARG;
+    const Packed &p = g->packed;
+    if (!p.have_window) return CP_ERR_ARG;
+    const WindowDir &d = tsweep ? p.win_t : p.win_b;
+    WindowCfg c;
+    if (!window_config(d, k, (size_t)tick_dtype, kWindowLdsLimit, c)) return CP_ERR_ARG;
+    shape[0] = c.nl; shape[1] = c.nlw; shape[2] = c.nfw; shape[3] = c.nc; shape[4] = c.dr; shape[5] = c.groups;
+    shape[6] = (d.smax + c.nc - 1) / c.nc;
+    shape[7] = (int32_t)c.lds_bytes;
+    return CP_OK;
+}
+
 const char *cp_error_string(int code) {
     switch (code) {
         case CP_OK: return "ok";

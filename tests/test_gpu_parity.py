@@ -645,8 +645,12 @@ def test_long_edges_do_not_rule_the_window_plan_out(gpu, oracle):
                 [1, 2, 4, 4], rng.integers(1, 40, size=(4, 4)), rng.integers(0, 4, size=(70, n), dtype=np.uint8), level)
     g = gpu.CpGraph.from_workload(w)
     info = g.info
+    shapes = [g.window_shape(4, tsweep=ts) for ts in (False, True)]
     g.close()
     assert info["window_ok"] == 1 and info["window_far_b"] > 0 and info["window_far_t"] > 0
+    # wide ticks: eight slices on fewer compute wavefronts, two output stores per wavefront and tick,
+    # the larger of the two store counts the far reads' ordering allows for
+    assert all(sh["far_waves"] > 0 and sh["stores_per_tick"] == 2 for sh in shapes), shapes
     _check(gpu, oracle, w, plans=(WINDOW, COLUMN), layouts=(0, 1))
     # CP alone still needs the b array on such a graph
     from gpu_util import run_gpu
@@ -669,8 +673,11 @@ def test_far_reads_with_few_levels_and_mirror_edges(gpu, oracle):
                 rng.integers(1, 9, size=(3, 3)), rng.integers(0, 3, size=(130, n), dtype=np.uint8), level)
     g = gpu.CpGraph.from_workload(w)
     info = g.info
+    shapes = [g.window_shape(3, tsweep=ts) for ts in (False, True)]
     g.close()
     assert info["window_ok"] == 1 and info["window_far_b"] > 0
+    # narrow ticks: one slice, one output store per compute wavefront and tick
+    assert all(sh["far_waves"] > 0 and sh["stores_per_tick"] == 1 for sh in shapes), shapes
     _check(gpu, oracle, w)
     _check_paths(gpu, oracle, w)
 
