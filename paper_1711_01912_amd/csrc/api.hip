@@ -215,17 +215,19 @@ bool window_preferred(const Packed &p, const WindowCfg &cb, const WindowCfg &ct,
 // already, gain nothing from it (measured: 2,016 vertices x 8,192 partitions 0.62 ms per sweep
 // against 0.56 and 0.80 ms; 5,271 vertices x 16,384 partitions 1.08 against 1.31 and 1.05 ms).
 // mask_penalty_us: what the shared plans pay for the mask pass the other plan would not need.
+// mask_penalty_us: what a mask pass of its own would cost the shared plans; mask_t_factor: what
+// writing the mask inside their t sweep costs instead, as a factor on that sweep (measured 1.22).
 int choose_window_plan(const Packed &p, int32_t k, size_t tick_bytes, size_t lds_limit, const WindowCfg &cb,
                        const WindowCfg &ct, int32_t batch, double mask_penalty_us, SharedCfg *sh_b, SharedCfg *sh_t,
-                       bool tab4 = false) {
+                       bool tab4 = false, double mask_t_factor = 1.0) {
     int best = CP_PLAN_RESIDENT_WINDOW;
     if (window_wg_per_cu(cb) > 1.0 || window_wg_per_cu(ct) > 1.0) return best;
     double best_us = window_sweep_us(p.win_b, cb, batch) + window_sweep_us(p.win_t, ct, batch);
     for (int groups = 2; groups <= 4; groups += 2) {
         SharedCfg b, t;
         if (!shared_fits(p, k, tick_bytes, groups, lds_limit, &b, &t, tab4)) continue;
-        const double us = shared_sweep_us(p.win_b, groups, batch) + shared_sweep_us(p.win_t, groups, batch) +
-                          mask_penalty_us;
+        const double us = shared_sweep_us(p.win_b, groups, batch) +
+                          shared_sweep_us(p.win_t, groups, batch) * mask_t_factor + mask_penalty_us;
         if (us < best_us) {
             best_us = us;
             best = groups == 4 ? CP_PLAN_SHARED_WINDOW_4 : CP_PLAN_SHARED_WINDOW_2;
@@ -477,10 +479,12 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
     if (plan == CP_PLAN_AUTO) {
         use = CP_PLAN_WAVE_COLUMN;
         if (can_window && window_preferred(p, cfg_b, cfg_t, batch, (size_t)tick_dtype)) {
-            // with a mask to write, the shared plans pay for a pass of their own over b and tl
-            const double mask_us = mask_out ? 5.0 + (double)p.n * batch * (2.0 * tick_dtype + 0.125) / 4.0e6 : 0.0;
+            // with a mask to write and rows per vertex, the shared plans pay for a pass of their own
+            // over b and tl (with rows per partition their t sweep writes it)
+            const bool sh_mask_pass = mask_out && !(out_layout == CP_OUT_PARTITION_MAJOR && tick_dtype == CP_TICK_I32);
+            const double mask_us = sh_mask_pass ? 5.0 + (double)p.n * batch * (2.0 * tick_dtype + 0.125) / 4.0e6 : 0.0;
             use = choose_window_plan(p, k, (size_t)tick_dtype, device_window_lds_limit(), cfg_b, cfg_t, batch, mask_us,
-                                     &sh_b, &sh_t, tabs.tab4_ok);
+                                     &sh_b, &sh_t, tabs.tab4_ok, mask_out && !sh_mask_pass ? 1.22 : 1.0);
         }
     }
     if (use == CP_PLAN_RESIDENT_WINDOW && !can_window) return CP_ERR_ARG;
@@ -599,7 +603,11 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
         fuse_mask = p.win_t.smax >= 4 &&
                     window_sweep_us(p.win_t, cfg_tm, batch) <= window_sweep_us(p.win_t, cfg_t, batch) + mask_pass_us;
     }
-    fuse_mask = fuse_mask || fuse_mask_st;
+    // the shared-window kernel fetches b(v) from the b rows itself, a tick ahead of the comparison
+    // (one slice per compute wavefront and tick is what that kernel's bookkeeping assumes)
+    const bool fuse_mask_sh = shared && by_partition && mask_out && tick_dtype == CP_TICK_I32 &&
+                              sh_t.nc >= p.win_t.smax && p.n < (1 << 24);
+    fuse_mask = fuse_mask || fuse_mask_st || fuse_mask_sh;
     if (gather_b) {
         s.win = &p.win_b;
         rc = launch_gather_assign(s, d_pperm_b, stream);

@@ -105,14 +105,29 @@ int lanes_per_row_log2(int rows) {
 // Resident-window packing for one direction (layout: see WindowDir).  Returns
 // false if the graph does not suit that plan.
 bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int64_t max_t,
-                     bool ticks32, const Csr &csr, const std::vector<int32_t> &order,
+                     bool ticks32, const Csr &csr, const std::vector<int32_t> &level_order,
                      const ColumnDir &col, WindowDir &dir) {
+    // A slice is 64 consecutive positions of a level in the order the wave-column plan uses
+    // (long rows first).  Inside a slice the order is free: by vertex number, so that the
+    // lanes of an output store (and of the mask's reads of b) walk memory in one direction
+    // and neighbouring lanes share cache lines.
+    std::vector<int32_t> order(level_order);
+    std::vector<int32_t> slice_deg((size_t)n, 0);       // longest row of the slice that starts at this position
+    for (size_t s = 0; s < col.lvl_begin.size(); ++s) {
+        const int32_t a = col.lvl_begin[s], b = a + col.lvl_count[s];
+        for (int32_t p0 = a; p0 < b; p0 += kWave) {
+            const int32_t e = std::min(b, p0 + kWave);
+            int32_t deg = 0;
+            for (int32_t i = p0; i < e; ++i) deg = std::max(deg, csr.ptr[order[i] + 1] - csr.ptr[order[i]]);
+            slice_deg[p0] = deg;
+            std::sort(order.begin() + p0, order.begin() + e);
+        }
+    }
     std::vector<int32_t> pos(n);
     for (int32_t i = 0; i < n; ++i) pos[order[i]] = i;
 
     auto slice_entries = [&](int32_t p0, int32_t rows) -> uint64_t {
-        int32_t v0 = order[p0];
-        int64_t deg0 = csr.ptr[v0 + 1] - csr.ptr[v0];                 // longest row leads
+        int64_t deg0 = slice_deg[p0];
         int sh = lanes_per_row_log2(rows);
         return (uint64_t)((deg0 + (1 << sh) - 1) >> sh) * kWave;
     };
@@ -197,6 +212,9 @@ bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int6
         for (int32_t s = 0; s < T; ++s) {
             int32_t a = tick_a[s], b = tick_b[s];
             int64_t far_here = 0;
+            // a tick's vertices take consecutive slots with at most one wrap, whether or not
+            // anything reads them: the ring is at least as long as the widest tick
+            need = std::max<int64_t>(need, (int64_t)b - a);
             for (int32_t i = a; i < b; ++i) {
                 int32_t v = order[i];
                 for (int32_t e = csr.ptr[v]; e < csr.ptr[v + 1]; ++e) {
@@ -292,10 +310,9 @@ bool pack_window_dir(BlobWriter &w, int32_t n, int32_t L, const int64_t *c, int6
         for (uint32_t j = 0; j < nsl; ++j) {
             int32_t p0 = a + (int32_t)j * kWave;
             int32_t rows = std::min(kWave, b - p0);
-            int32_t v0 = order[p0];
             int sh = lanes_per_row_log2(rows);
             int32_t lpr = 1 << sh;
-            uint64_t width = (uint64_t)((csr.ptr[v0 + 1] - csr.ptr[v0] + lpr - 1) >> sh);
+            uint64_t width = (uint64_t)((slice_deg[p0] + lpr - 1) >> sh);
             if (width >= 65536) return false;
             desc[4 * j] = ent_start + (uint32_t)esz * ebase;
             desc[4 * j + 1] = (uint32_t)width | ((uint32_t)rows << 16) | ((uint32_t)sh << 24);

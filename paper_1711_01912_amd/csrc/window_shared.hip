@@ -48,6 +48,12 @@ struct SharedArgs {
     int32_t wgs, per_xcd;      // workgroups with partitions; workgroups per XCD
     uint32_t vals_off, stage_off, tab_off;   // LDS byte offsets
     int32_t out32;             // every output index fits 32 bits
+    // t sweep that also writes the critical-vertex mask (rows per partition): b with the strides of
+    // `out`, CP per partition, the zeroed mask rows as 32-bit words; all null otherwise
+    const int32_t *mask_b;
+    const int64_t *mask_cp;
+    uint32_t *mask32;
+    int64_t mask_row32;        // 32-bit words per mask row
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -210,6 +216,35 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_shared_kernel(Sha
             row_mis[g] = a.direct ? (uint32_t)((uintptr_t)(a.ids + (size_t)q[g] * a.ids_row) & 15) : 0u;
         }
         uint32_t worst = 0;                  // largest device id seen
+        // Mask (t sweep): tl(v) + b(v) = CP marks a critical vertex.  b(v) comes from the b array in
+        // global memory: the lane that publishes v asks for it right after, and compares two ticks
+        // later, at the start of its slice; even and odd ticks keep their requests apart, so that
+        // the wait for one tick's values leaves the next tick's in flight.
+        const bool with_mask = TSWEEP && a.mask32 != nullptr;
+        struct Pending {
+            bool on = false;                 // this lane published v
+            uint32_t v = 0, tl[G], b[G];
+        } pend_even, pend_odd;
+        uint32_t cpq[G];
+        const int32_t *bq[G];
+        uint32_t *mq[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            pend_even.tl[g] = pend_even.b[g] = pend_odd.tl[g] = pend_odd.b[g] = 0;
+            cpq[g] = with_mask ? (uint32_t)a.mask_cp[q[g]] : 0u;      // tl + b <= CP: no overflow in 32 bits
+            bq[g] = with_mask ? a.mask_b + (size_t)q[g] * (size_t)a.out_sq : nullptr;
+            mq[g] = with_mask ? a.mask32 + (size_t)q[g] * (size_t)a.mask_row32 : nullptr;
+        }
+        auto flush_pending = [&](const Pending &pd) {
+            uint32_t hits = 0;               // critical vertices are rare: one branch for all G
+#pragma unroll
+            for (int g = 0; g < G; ++g) hits |= (uint32_t)(pd.tl[g] + pd.b[g] == cpq[g]) << g;
+            if (pd.on && hits) {
+#pragma unroll
+                for (int g = 0; g < G; ++g)
+                    if ((hits >> g) & 1u) atomicOr(mq[g] + (pd.v >> 5), 1u << (pd.v & 31u));
+            }
+        };
 
         auto ent_field = [](Ent e) -> uint32_t {
             if constexpr (ENT4) return e & 0xffffu; else return e.x;
@@ -218,7 +253,7 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_shared_kernel(Sha
             if constexpr (ENT4) return e >> 16; else return e.y;
         };
         // one slice of the current tick out of its stage slot, for all G partitions
-        auto slice = [&](const uint8_t *st, int j) {
+        auto slice = [&](const uint8_t *st, int j, Pending &pd) {
             const uint4 d = ((const uint4 *)(st + head))[j];
             const uint32_t ent_off = d.x;
             const int width = __builtin_amdgcn_readfirstlane((int)(d.y & 0xffffu));
@@ -226,7 +261,16 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_shared_kernel(Sha
             const int rows = (int)((d.y >> 16) & 0xffu);
             const uint32_t lo = d.z;
             const int rbase = (int)d.w;
-            if (width == 0 && lsh == 0 && __builtin_amdgcn_readfirstlane(rows) == 0) return;
+            if (width == 0 && lsh == 0 && __builtin_amdgcn_readfirstlane(rows) == 0) return;   // (what is pending stays so)
+            // the vertex of this lane's slice two ticks ago.  At the slice's start: the wait for its
+            // b values is a wait for everything older, and must come before this slice's own
+            // stores.  (The cost of the mask is instructions, not latency: comparing after one tick
+            // instead of two costs 2 % more, comparing just before the publication 17 % more,
+            // asking for b at the start of the slice 23 % more; 64-bit address arithmetic per
+            // access instead of one 32-bit offset beside uniform row addresses 7 % more.)
+            if constexpr (TSWEEP) {
+                if (with_mask) flush_pending(pd);
+            }
             const int p = j * 64 + (lane >> lsh);
             const uint2 rc = *((const uint2 *)(st + rec_off) + p);
             const Ent *ent = (const Ent *)(st + head + ent_off) + lane;
@@ -311,22 +355,49 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_shared_kernel(Sha
                 else fv = make_uint4(fin[0], fin[1], fin[2], fin[3]);
                 *(Vals *)(lds + vals_off + (size_t)rs * (4 * G)) = fv;
                 if (a.out) {
+                    if (a.out32) {               // one 32-bit byte offset beside G uniform row addresses
+                        const uint32_t off = __umul24(rc.x, out_sv) << 2;
 #pragma unroll
-                    for (int g = 0; g < G; ++g) {
-                        const int32_t o = (int32_t)(TSWEEP ? acc[g] : fin[g]);
-                        if (a.out32) outq[g][__umul24(rc.x, out_sv)] = o;
-                        else outq[g][(size_t)rc.x * out_sv] = o;
+                        for (int g = 0; g < G; ++g)
+                            *(int32_t *)((char *)outq[g] + off) = (int32_t)(TSWEEP ? acc[g] : fin[g]);
+                    } else {
+#pragma unroll
+                        for (int g = 0; g < G; ++g) outq[g][(size_t)rc.x * out_sv] = (int32_t)(TSWEEP ? acc[g] : fin[g]);
                     }
                 }
             }
+            if constexpr (TSWEEP) {
+                if (with_mask) {
+                    pd.on = row < rows && first;
+                    pd.v = rc.x;                 // padding rows carry a vertex of the tick: a valid index
+#pragma unroll
+                    for (int g = 0; g < G; ++g) pd.tl[g] = acc[g];
+                    const uint32_t off = __umul24(rc.x, out_sv) << 2;      // (the launcher checked that it fits)
+#pragma unroll
+                    for (int g = 0; g < G; ++g) pd.b[g] = (uint32_t) * (const int32_t *)((const char *)bq[g] + off);
+                }
+            }
         };
-
         lds_barrier();                       // packet 0 is staged
-        for (int t = 0; t < Lpad; ++t) {
+        for (int t = 0; t < Lpad; t += 2) {
             lds_barrier();
-            if (t >= L) continue;
-            const uint8_t *st = stage + (size_t)(t & 1) * slot_bytes;
-            for (int j = wave; j < a.smax; j += a.nc) slice(st, j);
+            if (t < L) {
+                const uint8_t *st = stage + (size_t)(t & 1) * slot_bytes;
+                for (int j = wave; j < a.smax; j += a.nc) slice(st, j, pend_even);
+            }
+            if (t + 1 < Lpad) {
+                lds_barrier();
+                if (t + 1 < L) {
+                    const uint8_t *st = stage + (size_t)((t + 1) & 1) * slot_bytes;
+                    for (int j = wave; j < a.smax; j += a.nc) slice(st, j, pend_odd);
+                }
+            }
+        }
+        if constexpr (TSWEEP) {              // the last two ticks' vertices
+            if (with_mask) {
+                flush_pending(pend_even);
+                flush_pending(pend_odd);
+            }
         }
         if (worst >= (uint32_t)k) *a.status = CP_STATUS_BAD_DEVICE_ID;
     }
@@ -377,7 +448,15 @@ int launch_shared_k(const SweepLaunch &s, const SharedCfg &cfg, hipStream_t st) 
     a.vals_off = (uint32_t)cfg.vals_off;
     a.stage_off = (uint32_t)cfg.stage_off;
     a.tab_off = (uint32_t)cfg.tab_off;
-    a.out32 = s.n < (1 << 24) && s.P < (1 << 24) && (uint64_t)s.n * (uint64_t)s.P < (1ull << 31);
+    // every byte offset of a vertex inside a partition's row of outputs fits 32 bits (and both factors 24)
+    a.out32 = s.n < (1 << 24) && s.out_sv < (1 << 24) && (uint64_t)s.n * (uint64_t)s.out_sv * 4 < (1ull << 32);
+    if (s.mask_out) {
+        if (!TSWEEP || !s.mask_b || !s.mask_cp || !s.val || cfg.nc < dir.smax || !a.out32) return CP_ERR_ARG;
+        a.mask_b = (const int32_t *)s.mask_b;
+        a.mask_cp = s.mask_cp;
+        a.mask32 = (uint32_t *)s.mask_out;
+        a.mask_row32 = 2 * (((int64_t)s.n + 63) / 64);
+    }
     auto kern = window_shared_kernel<TSWEEP, G, ENT4, NL, DR, TAB4>;
     if (cfg.lds_bytes > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -455,7 +534,7 @@ bool shared_config(const WindowDir &d, int32_t k, int groups, size_t lds_limit, 
 }
 
 int launch_window_shared(const SweepLaunch &s, const SharedCfg &cfg, void *stream) {
-    if (s.tick_bytes != 4 || s.mask_out) return CP_ERR_ARG;
+    if (s.tick_bytes != 4 || (s.mask_out && !s.tsweep)) return CP_ERR_ARG;
     return s.tsweep ? launch_shared_g<true>(s, cfg, (hipStream_t)stream)
                     : launch_shared_g<false>(s, cfg, (hipStream_t)stream);
 }

@@ -682,6 +682,50 @@ def test_far_reads_with_few_levels_and_mirror_edges(gpu, oracle):
     _check_paths(gpu, oracle, w)
 
 
+def _chain_and_wide_level(width):
+    """A chain of six vertices, one per level, and `width` vertices without edges in a seventh
+    level: the widest tick of either sweep is far wider than any edge's span."""
+    n = 6 + width
+    src, dst = np.arange(5), np.arange(1, 6)
+    level = np.concatenate([np.arange(6), np.full(width, 6)])
+    return n, level, src, dst
+
+
+@pytest.mark.parametrize("shape", ["no-edges", "wide-level"])
+def test_ticks_wider_than_any_edge_span(gpu, oracle, shape):
+    """The ring of the window plans is sized by the edges' spans; a tick whose vertices have no
+    edges still publishes into it and must find room (279 vertices without a single edge once
+    overwrote the staged device ids)."""
+    from gpu_util import assert_equal_to_oracle, run_gpu
+    rng = np.random.default_rng(83)
+    if shape == "no-edges":
+        n, level, src, dst = 279, np.zeros(279, dtype=np.int64), np.zeros(0, dtype=np.int64), np.zeros(0, dtype=np.int64)
+    else:
+        n, level, src, dst = _chain_and_wide_level(300)
+    k = 50
+    w = _custom(shape, n, src, dst, rng.integers(1, 100, size=len(src)), rng.integers(1, 5000, size=n),
+                rng.integers(1, 100, size=k), rng.integers(1, 5, size=(k, k)),
+                rng.integers(0, k, size=(5, n), dtype=np.uint8), level)
+    ref = _oracle(oracle, w)
+    g = gpu.CpGraph.from_workload(w, device="cuda:0")
+    info = g.info
+    assert info["window_ok"] == 1
+    assert min(info["window_slots_b"], info["window_slots_t"]) >= min(info["max_level_width"], 512)
+    ran = 0
+    for plan in (1, 2, 3, 4, 5, 6):
+        for layout in (0, 1):
+            for ol in (0, 1):
+                try:
+                    res = run_gpu(w, plan, layout=layout, graph=g, out_layout=ol)
+                except gpu.CpError as e:
+                    assert plan != 1 and e.code == -12, (plan, e.code)
+                    continue
+                ran += 1
+                assert_equal_to_oracle(res, ref, what=f"{shape} plan={plan} layout={layout} out={ol}")
+    g.close()
+    assert ran >= 12
+
+
 # ------------------------------------------------------------------ many small random shapes
 
 @pytest.mark.parametrize("block", range(4))

@@ -401,3 +401,22 @@ def test_packing_deep_graphs_with_long_spans(lib):
     g = cpe.CpGraph.from_workload(w)
     assert g.info["window_far_b"] == 0 and g.info["window_far_t"] == 0
     g.close()
+
+
+def test_window_ring_holds_the_widest_tick():
+    """Vertices without edges still take ring slots when they are published: the ring is never
+    shorter than the widest tick, whatever the edges' spans."""
+    import paper_1711_01912_amd as cpe
+    from workloads import build_csr
+    from workloads.dags import _finish
+    for width in (70, 279, 600):
+        n = 6 + width                      # a chain of six and a level of `width` vertices without edges
+        src, dst = np.arange(5), np.arange(1, 6)
+        level = np.concatenate([np.arange(6), np.full(width, 6)])
+        w = _finish("wide-level", build_csr(n, src, dst, np.ones(5, dtype=np.int64), level), np.ones(n, dtype=np.int64),
+                    2, [1, 1], [[1, 1], [1, 1]], np.zeros((1, n), dtype=np.uint8))
+        g = cpe.CpGraph.from_workload(w)
+        info = g.info
+        g.close()
+        assert info["window_ok"] == 1
+        assert min(info["window_slots_b"], info["window_slots_t"]) >= min(width, 512), info
