@@ -454,7 +454,7 @@ struct WindowArgs {
     int32_t *status;
     int32_t nc, nlw;           // compute and loader wavefronts per workgroup
     int32_t pgroups;           // partitions per XCD-sized group (blockIdx -> partition map)
-    int32_t out32;             // 1 if every output index fits 32 bits
+    int32_t out32;             // 1 if every byte offset inside a partition's outputs fits 32 bits
     int64_t out_sq;            // output index of (v, q) = v * out_sv + q * out_sq
     uint32_t out_sv;
     // t sweep that also writes the critical-vertex mask (partition-major rows only)
@@ -756,7 +756,8 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_sweep_kernel(Wind
                     ring_dev[rs] = (uint8_t)pv;
                 }
                 if (out) {
-                    if (a.out32) out[__umul24(v, out_sv)] = TSWEEP ? acc : fin;
+                    // (a 32-bit byte offset beside the row's uniform address where that fits)
+                    if (a.out32) *(Tick *)((char *)out + __umul24(v, out_sv) * (uint32_t)sizeof(Tick)) = TSWEEP ? acc : fin;
                     else out[(size_t)v * out_sv] = TSWEEP ? acc : fin;
                 }
                 best = max(best, fin);
@@ -954,7 +955,9 @@ int launch_window_sweep_k(const SweepLaunch &s, const WindowCfg &cfg, hipStream_
     a.vert_tab = (const Magic *)s.vert_tab;
     a.P = s.P; a.L = dir.ticks; a.k = s.k; a.slots = dir.slots; a.wpad = dir.wpad; a.smax = dir.smax;
     a.nc = cfg.nc; a.nlw = cfg.nlw;
-    a.out32 = s.n < (1 << 24) && s.P < (1 << 24) && (uint64_t)s.n * (uint64_t)s.P < (1ull << 31);
+    // every byte offset of a vertex inside a partition's row of outputs fits 32 bits (and both factors 24)
+    a.out32 = s.n < (1 << 24) && s.out_sv < (1 << 24) &&
+              (uint64_t)s.n * (uint64_t)s.out_sv * (uint64_t)s.tick_bytes < (1ull << 32);
     a.out_sq = s.out_sq;
     a.out_sv = (uint32_t)s.out_sv;
     a.groups = std::max(1, cfg.groups);

@@ -43,7 +43,7 @@ struct StreamArgs {
     int32_t *status;
     int64_t out_sq;
     uint32_t out_sv;
-    int32_t out32;             // every output index fits 32 bits
+    int32_t out32;             // every byte offset inside a partition's outputs fits 32 bits
     int32_t P, L, k, slots, wpad, smax, idpad, direct;   // L counts ticks
     int32_t nc, nlw;           // compute and loader wavefronts
     int32_t per_xcd;           // workgroups per XCD
@@ -328,7 +328,7 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_stream_kernel(Str
                 ((uint2 *)lds)[rs] = make_uint2(fin, 8u * pv);
                 if (out) {
                     const int32_t o = (int32_t)(TSWEEP ? acc : fin);
-                    if (a.out32) out[__umul24(rc.x, out_sv)] = o;
+                    if (a.out32) *(int32_t *)((char *)out + (__umul24(rc.x, out_sv) << 2)) = o;
                     else out[(size_t)rc.x * out_sv] = o;
                 }
                 best = max(best, fin);
@@ -399,7 +399,7 @@ int launch_stream_k(const SweepLaunch &s, const StreamCfg &cfg, hipStream_t st) 
     a.status = s.status;
     a.out_sq = s.out_sq;
     a.out_sv = (uint32_t)s.out_sv;
-    a.out32 = s.n < (1 << 24) && s.P < (1 << 24) && (uint64_t)s.n * (uint64_t)s.P < (1ull << 31);
+    a.out32 = s.n < (1 << 24) && s.out_sv < (1 << 24) && (uint64_t)s.n * (uint64_t)s.out_sv * 4 < (1ull << 32);
     a.P = s.P; a.L = dir.ticks; a.k = s.k; a.slots = dir.slots; a.wpad = dir.wpad; a.smax = dir.smax;
     a.idpad = dir.idpad;
     a.nc = cfg.nc; a.nlw = cfg.nlw;
