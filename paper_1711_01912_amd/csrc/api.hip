@@ -194,10 +194,8 @@ double shared_sweep_us(const WindowDir &d, int groups, int32_t batch) {
     return rounds * (double)d.ticks * (groups == 4 ? 2.03 : 1.33) * (0.58 + 0.03 * d.smax);
 }
 
-bool window_preferred(const Packed &p, const WindowCfg &cb, const WindowCfg &ct, int32_t batch,
-                      size_t tick_bytes) {
-    auto sweep_us = [&](const WindowDir &d, const WindowCfg &c) { return window_sweep_us(d, c, batch); };
-    const double window_us = sweep_us(p.win_b, cb) + sweep_us(p.win_t, ct);
+// Both sweeps under the wave-column plan.
+double column_plan_us(const Packed &p, int32_t batch, size_t tick_bytes) {
     auto column_us = [&](const ColumnDir &d) {
         double launches = 0;
         for (size_t l = 0; l < d.lvl_count.size(); ++l)
@@ -205,7 +203,7 @@ bool window_preferred(const Packed &p, const WindowCfg &cb, const WindowCfg &ct,
         const double bytes = ((double)p.n + (double)p.m) * batch * (1.0 + (double)tick_bytes);
         return launches * 6.3 + bytes / 4.0e6;
     };
-    return window_us <= column_us(p.col_b) + column_us(p.col_t);
+    return column_us(p.col_b) + column_us(p.col_t);
 }
 
 // CP_PLAN_AUTO among the window plans (the caller has found the resident-window plan runnable
@@ -219,10 +217,11 @@ bool window_preferred(const Packed &p, const WindowCfg &cb, const WindowCfg &ct,
 // writing the mask inside their t sweep costs instead, as a factor on that sweep (measured 1.22).
 int choose_window_plan(const Packed &p, int32_t k, size_t tick_bytes, size_t lds_limit, const WindowCfg &cb,
                        const WindowCfg &ct, int32_t batch, double mask_penalty_us, SharedCfg *sh_b, SharedCfg *sh_t,
-                       bool tab4 = false, double mask_t_factor = 1.0) {
+                       bool tab4 = false, double mask_t_factor = 1.0, double *us_out = nullptr) {
     int best = CP_PLAN_RESIDENT_WINDOW;
-    if (window_wg_per_cu(cb) > 1.0 || window_wg_per_cu(ct) > 1.0) return best;
     double best_us = window_sweep_us(p.win_b, cb, batch) + window_sweep_us(p.win_t, ct, batch);
+    if (us_out) *us_out = best_us;
+    if (window_wg_per_cu(cb) > 1.0 || window_wg_per_cu(ct) > 1.0) return best;
     for (int groups = 2; groups <= 4; groups += 2) {
         SharedCfg b, t;
         if (!shared_fits(p, k, tick_bytes, groups, lds_limit, &b, &t, tab4)) continue;
@@ -235,6 +234,7 @@ int choose_window_plan(const Packed &p, int32_t k, size_t tick_bytes, size_t lds
             if (sh_t) *sh_t = t;
         }
     }
+    if (us_out) *us_out = best_us;
     return best;
 }
 
@@ -362,10 +362,13 @@ int cp_graph_create(int32_t n, int64_t m, int32_t L,
     WindowCfg cb, ct;
     info.window_ok = window_fits(g->packed, 1, (size_t)info.min_tick_bytes, kWindowLdsLimit, &cb, &ct) ? 1 : 0;
     // the choice is made per call (it depends on the batch); this is the one for 256 partitions
-    info.auto_plan = info.window_ok && window_preferred(g->packed, cb, ct, 256, (size_t)info.min_tick_bytes)
-                         ? choose_window_plan(g->packed, 1, (size_t)info.min_tick_bytes, kWindowLdsLimit, cb, ct, 256,
-                                              0.0, nullptr, nullptr)
-                         : CP_PLAN_WAVE_COLUMN;
+    info.auto_plan = CP_PLAN_WAVE_COLUMN;
+    if (info.window_ok) {
+        double window_us = 0.0;
+        const int wplan = choose_window_plan(g->packed, 1, (size_t)info.min_tick_bytes, kWindowLdsLimit, cb, ct, 256,
+                                             0.0, nullptr, nullptr, false, 1.0, &window_us);
+        if (window_us <= column_plan_us(g->packed, 256, (size_t)info.min_tick_bytes)) info.auto_plan = wplan;
+    }
     *out = g;
     return CP_OK;
 }
@@ -434,10 +437,13 @@ int cp_eval_choose_plan(const cp_graph *g, int32_t batch, int32_t k, const int64
     WindowCfg cfg_b, cfg_t;
     const bool can_window = tabs.magic_ok && window_fits(p, k, (size_t)tick_dtype, device_window_lds_limit(),
                                                          &cfg_b, &cfg_t);
-    *plan_out = can_window && window_preferred(p, cfg_b, cfg_t, batch, (size_t)tick_dtype)
-                    ? choose_window_plan(p, k, (size_t)tick_dtype, device_window_lds_limit(), cfg_b, cfg_t, batch, 0.0,
-                                         nullptr, nullptr)
-                    : CP_PLAN_WAVE_COLUMN;
+    *plan_out = CP_PLAN_WAVE_COLUMN;
+    if (can_window) {
+        double window_us = 0.0;
+        const int wplan = choose_window_plan(p, k, (size_t)tick_dtype, device_window_lds_limit(), cfg_b, cfg_t, batch,
+                                             0.0, nullptr, nullptr, tabs.tab4_ok, 1.0, &window_us);
+        if (window_us <= column_plan_us(p, batch, (size_t)tick_dtype)) *plan_out = wplan;
+    }
     return CP_OK;
 }
 
@@ -478,13 +484,19 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
     SharedCfg sh_b, sh_t;
     if (plan == CP_PLAN_AUTO) {
         use = CP_PLAN_WAVE_COLUMN;
-        if (can_window && window_preferred(p, cfg_b, cfg_t, batch, (size_t)tick_dtype)) {
-            // with a mask to write and rows per vertex, the shared plans pay for a pass of their own
-            // over b and tl (with rows per partition their t sweep writes it)
-            const bool sh_mask_pass = mask_out && !(out_layout == CP_OUT_PARTITION_MAJOR && tick_dtype == CP_TICK_I32);
+        if (can_window) {
+            // with a mask to write and rows per vertex (or far reads), the shared plans pay for a pass
+            // of their own over b and tl (else their t sweep writes it)
+            const bool sh_mask_pass = mask_out && !(out_layout == CP_OUT_PARTITION_MAJOR && tick_dtype == CP_TICK_I32 &&
+                                                    p.win_t.far_cap == 0);
             const double mask_us = sh_mask_pass ? 5.0 + (double)p.n * batch * (2.0 * tick_dtype + 0.125) / 4.0e6 : 0.0;
-            use = choose_window_plan(p, k, (size_t)tick_dtype, device_window_lds_limit(), cfg_b, cfg_t, batch, mask_us,
-                                     &sh_b, &sh_t, tabs.tab4_ok, mask_out && !sh_mask_pass ? 1.22 : 1.0);
+            double window_us = 0.0;
+            const int wplan = choose_window_plan(p, k, (size_t)tick_dtype, device_window_lds_limit(), cfg_b, cfg_t, batch,
+                                                 mask_us, &sh_b, &sh_t, tabs.tab4_ok,
+                                                 mask_out && !sh_mask_pass ? 1.22 : 1.0, &window_us);
+            // (the mask's cost is left out of the comparison with the wave-column plan, which pays
+            // for a pass of its own as well)
+            if (window_us - mask_us <= column_plan_us(p, batch, (size_t)tick_dtype)) use = wplan;
         }
     }
     if (use == CP_PLAN_RESIDENT_WINDOW && !can_window) return CP_ERR_ARG;
@@ -606,7 +618,7 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
     // the shared-window kernel fetches b(v) from the b rows itself, a tick ahead of the comparison
     // (one slice per compute wavefront and tick is what that kernel's bookkeeping assumes)
     const bool fuse_mask_sh = shared && by_partition && mask_out && tick_dtype == CP_TICK_I32 &&
-                              sh_t.nc >= p.win_t.smax && p.n < (1 << 24);
+                              sh_t.nc >= p.win_t.smax && p.n < (1 << 24) && p.win_t.far_cap == 0;
     fuse_mask = fuse_mask || fuse_mask_st || fuse_mask_sh;
     if (gather_b) {
         s.win = &p.win_b;

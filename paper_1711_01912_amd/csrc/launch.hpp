@@ -58,6 +58,7 @@ struct SharedCfg {
     int nl = 0;        // 16-byte loads per loader lane per tick
     int nlw = 0;       // loader wavefronts
     int nc = 0;        // compute wavefronts
+    int nfw = 0;       // far wavefronts
     size_t vals_off = 0, stage_off = 0, tab_off = 0;   // LDS byte offsets: ring values, stage slots, cost tables
     size_t lds_bytes = 0;
     int tab_rs = -1;   // >= 0: 4-byte cost-table entries, each 2^tab_rs times in LDS

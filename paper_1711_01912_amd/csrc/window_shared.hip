@@ -10,6 +10,10 @@
 //
 // LDS: [device ids of the ring, (R+1) x G bytes][values of the ring, (R+1) x G ticks]
 //      [2 stage slots][cost tables].  A stage slot is [G x idpad bytes of device ids][packet].
+// With far reads (neighbours computed too long ago to be kept in the ring: see the resident-window
+// kernel) both ring regions go on behind slot R with two sets of far_cap slots, one per tick
+// parity, which far wavefronts fill from the output rows: an entry's field / 8 is a slot number
+// either way.
 // The packets are the resident-window plan's (WindowDir with a packed ring: an entry's ring
 // field is 8 x slot), read unchanged.
 #include <hip/hip_runtime.h>
@@ -54,6 +58,13 @@ struct SharedArgs {
     const int64_t *mask_cp;
     uint32_t *mask32;
     int64_t mask_row32;        // 32-bit words per mask row
+    // far reads: {vertex, c} per tick and read; the caller's assignments, device of (v, q) at
+    // v * far_a_sv + q * far_a_sp; reads per tick (a multiple of 64); far wavefronts (after the
+    // loaders); output stores a compute wavefront issues per tick
+    const uint2 *far_list;
+    const uint8_t *far_assign;
+    int64_t far_a_sp, far_a_sv;
+    int32_t far_cap, nfw, stores_per_tick;
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -76,7 +87,7 @@ __device__ __forceinline__ uint32_t val_of(const typename GroupVals<G>::type &v,
 //
 // TAB4: the cost tables are 4-byte entries and every transfer entry sits 2^tab_rs times in LDS,
 // copy r in bank (r mod 32); lane l reads copy l mod 2^tab_rs: fewer lanes meet in a bank.
-template <bool TSWEEP, int G, bool ENT4, int NL, int DR, bool TAB4>
+template <bool TSWEEP, int G, bool ENT4, int NL, int DR, bool TAB4, bool FAR>
 __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_shared_kernel(SharedArgs a) {
     typedef typename std::conditional<TAB4, uint32_t, Magic>::type Tab;
     extern __shared__ uint4 lds16[];
@@ -121,14 +132,84 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_shared_kernel(Sha
             ((uint32_t *)(lds + a.vals_off))[(size_t)R * G + tid] = 0;
         }
     }
-    const int Lpad = (L + DR - 1) / DR * DR;
+    // ticks rounded up so that the loaders' and the far wavefronts' unrolled loops end together
+    constexpr int kStep = !FAR ? DR : (DR % kWindowFarLead == 0 ? DR : DR * kWindowFarLead / (DR % 2 == 0 ? 2 : 1));
+    static_assert(kStep % DR == 0 && (!FAR || kStep % kWindowFarLead == 0), "tick padding");
+    const int Lpad = (L + kStep - 1) / kStep * kStep;
+    // first far slot: behind the ring as the packer laid it out (pairs of 8 bytes, 16-byte aligned)
+    const uint32_t far0 = (uint32_t)((((size_t)R + 1) * 8 + 15) / 16 * 2);
     const int id16 = a.idpad / 16;               // 16-byte chunks of device ids per partition and slot
     const int head = G * a.idpad;                // bytes of a slot before the packet
     uint32_t best[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) best[g] = 0;
 
-    if (wave >= a.nc) {
+    if (FAR && wave >= a.nc + a.nlw) {
+        // ------------------------------------------------ far wavefronts
+        // Lane f of far wavefront fw owns far read number fw*64 + f of every tick, for all G
+        // partitions.  For tick tau its {vertex, c} is loaded 2*X + 1 steps ahead, the values and
+        // devices of that vertex X + 1 steps ahead (from the output rows: the vertex was published
+        // at least kWindowFarTicks ticks before tau, and the compute wavefronts wait for their
+        // older stores before each barrier), and the slot is written one step ahead.
+        constexpr int X = kWindowFarLead;
+        const int f = (wave - a.nc - a.nlw) * 64 + lane;
+        const int32_t *outq[G];
+        const uint8_t *arow[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            outq[g] = a.out + (size_t)q[g] * (size_t)a.out_sq;
+            arow[g] = a.far_assign + (size_t)q[g] * (size_t)a.far_a_sp;
+        }
+        const Tab *vtab = (const Tab *)(lds + vtab_off);
+        bool bad = false;
+        struct Got { uint32_t val[G], devs; };
+        auto list_load = [&](int tau) -> uint2 {
+            return a.far_list[(size_t)min(tau, L - 1) * (size_t)a.far_cap + f];
+        };
+        auto fetch = [&](uint2 e) -> Got {
+            Got r;
+            r.devs = 0;
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                // the value left this compute unit through its write-through cache: read it from L2
+                uint32_t val = (uint32_t)__hip_atomic_load(outq[g] + (size_t)e.x * a.out_sv, __ATOMIC_RELAXED,
+                                                           __HIP_MEMORY_SCOPE_AGENT);
+                uint32_t dev = arow[g][(size_t)e.x * (size_t)a.far_a_sv];
+                if (dev >= (uint32_t)k) { bad = true; dev = (uint32_t)k - 1; }
+                if (TSWEEP) val += magic_div(e.y, vtab[dev]);       // the ring holds tl + w
+                r.val[g] = val;
+                r.devs |= dev << (8 * g);
+            }
+            return r;
+        };
+        uint2 lst[X];
+        Got got[X];
+#pragma unroll
+        for (int j = 1; j <= X; ++j) {
+            lst[j % X] = list_load(j + X);
+            got[j % X].devs = 0;
+#pragma unroll
+            for (int g = 0; g < G; ++g) got[j % X].val[g] = 0;
+        }
+        lds_barrier();                       // pairs with "packet 0 is staged"
+        for (int t0 = 0; t0 < Lpad; t0 += X) {
+#pragma unroll
+            for (int r = 0; r < X; ++r) {
+                const int t = t0 + r;
+                lds_barrier();
+                const int sl = (r + 1) % X;
+                const uint32_t slot = far0 + (uint32_t)((t + 1) & 1) * (uint32_t)a.far_cap + (uint32_t)f;
+                *(Devs *)(lds + (size_t)slot * G) = (Devs)got[sl].devs;
+                Vals fv;
+                if constexpr (G == 2) fv = make_uint2(got[sl].val[0], got[sl].val[1]);
+                else fv = make_uint4(got[sl].val[0], got[sl].val[1], got[sl].val[2], got[sl].val[3]);
+                *(Vals *)(lds + a.vals_off + (size_t)slot * (4 * G)) = fv;
+                got[sl] = fetch(lst[sl]);                 // for tick t + 1 + X
+                lst[sl] = list_load(t + 1 + 2 * X);
+            }
+        }
+        if (bad) *a.status = CP_STATUS_BAD_DEVICE_ID;
+    } else if (wave >= a.nc) {
         // ------------------------------------------------ loader wavefronts
         const int lw = wave - a.nc;
         const_u32_ptr tick_tab = (const_u32_ptr)a.tick_tab;
@@ -378,14 +459,27 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_shared_kernel(Sha
                 }
             }
         };
+        // far reads take values from the output rows kWindowFarTicks ticks later: keep at most
+        // two ticks' worth of stores in flight
+        auto far_wait = [&]() {
+            if constexpr (FAR) {
+                const int pending = 2 * G * a.stores_per_tick;
+                if (pending == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+                else if (pending == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+                else if (pending == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            }
+        };
         lds_barrier();                       // packet 0 is staged
         for (int t = 0; t < Lpad; t += 2) {
+            far_wait();
             lds_barrier();
             if (t < L) {
                 const uint8_t *st = stage + (size_t)(t & 1) * slot_bytes;
                 for (int j = wave; j < a.smax; j += a.nc) slice(st, j, pend_even);
             }
             if (t + 1 < Lpad) {
+                far_wait();
                 lds_barrier();
                 if (t + 1 < L) {
                     const uint8_t *st = stage + (size_t)((t + 1) & 1) * slot_bytes;
@@ -420,7 +514,7 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_shared_kernel(Sha
 
 inline int hip_ok(hipError_t e) { return e == hipSuccess ? CP_OK : CP_ERR_HIP; }
 
-template <bool TSWEEP, int G, bool ENT4, int NL, int DR, bool TAB4>
+template <bool TSWEEP, int G, bool ENT4, int NL, int DR, bool TAB4, bool FAR>
 int launch_shared_k(const SweepLaunch &s, const SharedCfg &cfg, hipStream_t st) {
     const WindowDir &dir = *s.win;
     SharedArgs a{};
@@ -457,31 +551,44 @@ int launch_shared_k(const SweepLaunch &s, const SharedCfg &cfg, hipStream_t st) 
         a.mask32 = (uint32_t *)s.mask_out;
         a.mask_row32 = 2 * (((int64_t)s.n + 63) / 64);
     }
-    auto kern = window_shared_kernel<TSWEEP, G, ENT4, NL, DR, TAB4>;
+    if (FAR != (dir.far_cap > 0) || cfg.nfw != dir.far_cap / kWave) return CP_ERR_ARG;
+    if (FAR) {
+        if (!s.val || s.mask_out) return CP_ERR_ARG;     // far reads come out of the output rows
+        a.far_list = (const uint2 *)(s.blob + dir.far_off);
+        a.far_assign = s.assign;
+        a.far_a_sp = s.a_stride_p;
+        a.far_a_sv = s.a_stride_v;
+        a.far_cap = dir.far_cap;
+        a.nfw = cfg.nfw;
+        a.stores_per_tick = (dir.smax + cfg.nc - 1) / cfg.nc;
+    }
+    auto kern = window_shared_kernel<TSWEEP, G, ENT4, NL, DR, TAB4, FAR>;
     if (cfg.lds_bytes > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)cfg.lds_bytes);
         if (e != hipSuccess) return CP_ERR_HIP;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)(8 * a.per_xcd)), dim3((cfg.nc + cfg.nlw) * 64), cfg.lds_bytes, st, a);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(8 * a.per_xcd)), dim3((cfg.nc + cfg.nlw + cfg.nfw) * 64), cfg.lds_bytes, st, a);
     return hip_ok(hipGetLastError());
 }
 
-template <bool TSWEEP, int G, bool ENT4, bool TAB4>
+template <bool TSWEEP, int G, bool ENT4, bool TAB4, bool FAR>
 int launch_shared_t(const SweepLaunch &s, const SharedCfg &cfg, hipStream_t st) {
     switch (cfg.nl) {   // loads per loader lane per tick x ticks in flight: 64 registers at most
-        case 1: return launch_shared_k<TSWEEP, G, ENT4, 1, 8, TAB4>(s, cfg, st);
-        case 2: return launch_shared_k<TSWEEP, G, ENT4, 2, 8, TAB4>(s, cfg, st);
-        case 3: return launch_shared_k<TSWEEP, G, ENT4, 3, 5, TAB4>(s, cfg, st);
-        case 4: return launch_shared_k<TSWEEP, G, ENT4, 4, 4, TAB4>(s, cfg, st);
+        case 1: return launch_shared_k<TSWEEP, G, ENT4, 1, 8, TAB4, FAR>(s, cfg, st);
+        case 2: return launch_shared_k<TSWEEP, G, ENT4, 2, 8, TAB4, FAR>(s, cfg, st);
+        case 3: return launch_shared_k<TSWEEP, G, ENT4, 3, 5, TAB4, FAR>(s, cfg, st);
+        case 4: return launch_shared_k<TSWEEP, G, ENT4, 4, 4, TAB4, FAR>(s, cfg, st);
         default: return CP_ERR_ARG;
     }
 }
 
 template <bool TSWEEP, int G, bool ENT4>
 int launch_shared_e(const SweepLaunch &s, const SharedCfg &cfg, hipStream_t st) {
-    return cfg.tab_rs >= 0 ? launch_shared_t<TSWEEP, G, ENT4, true>(s, cfg, st)
-                           : launch_shared_t<TSWEEP, G, ENT4, false>(s, cfg, st);
+    if (s.win->far_cap > 0)                  // (far reads go with the 8-byte tables only)
+        return cfg.tab_rs >= 0 ? CP_ERR_ARG : launch_shared_t<TSWEEP, G, ENT4, false, true>(s, cfg, st);
+    return cfg.tab_rs >= 0 ? launch_shared_t<TSWEEP, G, ENT4, true, false>(s, cfg, st)
+                           : launch_shared_t<TSWEEP, G, ENT4, false, false>(s, cfg, st);
 }
 
 template <bool TSWEEP>
@@ -496,10 +603,15 @@ int launch_shared_g(const SweepLaunch &s, const SharedCfg &cfg, hipStream_t st) 
 }  // namespace
 
 bool shared_config(const WindowDir &d, int32_t k, int groups, size_t lds_limit, SharedCfg &out, bool tab4) {
-    if (!d.packed || d.far_cap > 0 || (groups != 2 && groups != 4)) return false;
+    if (!d.packed || (groups != 2 && groups != 4)) return false;
     const size_t G = (size_t)groups;
-    const size_t devs = align_up(((size_t)d.slots + 1) * G, 16);
-    const size_t vals = align_up(((size_t)d.slots + 1) * 4 * G, 16);
+    // slots of either ring region: the ring and its constant-zero slot, then, with far reads, from
+    // the 16-byte boundary behind them two sets of far_cap slots
+    const int nfw = d.far_cap / kWave;
+    const size_t nslots = d.far_cap > 0 ? (((size_t)d.slots + 1) * 8 + 15) / 16 * 2 + 2 * (size_t)d.far_cap
+                                        : (size_t)d.slots + 1;
+    const size_t devs = align_up(nslots * G, 16);
+    const size_t vals = align_up(nslots * 4 * G, 16);
     const size_t tab = align_up(sizeof(Magic) * ((size_t)k * k + k), 16);
     // the entries' ring fields are read as LDS byte offsets of the device bytes and, doubled
     // at most, of the values: both regions lie below 2^32 trivially, the fields below 8 * (slots + 1)
@@ -507,12 +619,13 @@ bool shared_config(const WindowDir &d, int32_t k, int groups, size_t lds_limit, 
     static const int kNl[4] = {1, 2, 3, 4};
     for (int nl : kNl) {
         const int64_t nlw = (need + 64 * nl - 1) / (64 * nl);
-        if (nlw > 8) continue;
+        if (nlw > 8 || nlw + nfw > kWindowMaxWaves - 1) continue;
         SharedCfg c;
         c.groups = groups;
         c.nl = nl;
         c.nlw = (int)nlw;
-        c.nc = std::max(1, std::min(d.smax, kWindowMaxWaves - (int)nlw));
+        c.nfw = nfw;
+        c.nc = std::max(1, std::min(d.smax, kWindowMaxWaves - (int)nlw - nfw));
         c.vals_off = devs;
         c.stage_off = devs + vals;
         c.tab_off = c.stage_off + (size_t)2 * nl * nlw * 1024;
@@ -520,7 +633,7 @@ bool shared_config(const WindowDir &d, int32_t k, int groups, size_t lds_limit, 
         if (c.lds_bytes > lds_limit) continue;
         // 4-byte cost tables with as many copies of every transfer entry as fit (up to one per
         // LDS bank): wide ticks only, as for the resident-window kernel
-        for (int rs = 5; tab4 && d.smax >= 4 && rs >= 2; --rs) {
+        for (int rs = 5; tab4 && d.far_cap == 0 && d.smax >= 4 && rs >= 2; --rs) {
             if (c.tab_off + tab4_lds_bytes(k, rs) <= lds_limit) {
                 c.tab_rs = rs;
                 c.lds_bytes = c.tab_off + tab4_lds_bytes(k, rs);

@@ -54,16 +54,30 @@ def test_comm_heavy_scaled_rows_of_forty_edges(gpu, oracle):
     _check(gpu, oracle, w, plans=(SHARED2, SHARED4))
 
 
-def test_graphs_with_far_reads_are_refused(gpu):
-    from gpu_util import run_gpu
-    w = make_workload("inception", P=8)
+def test_graphs_with_far_reads(gpu, oracle):
+    """Neighbours too old for the ring come back from the output rows, for all partitions of a
+    workgroup at once: the inception workload (one far wavefront), a batch that leaves the last
+    workgroup short, both layouts."""
+    w = make_workload("inception", P=22)
     g = gpu.CpGraph.from_workload(w, device="cuda:0")
-    assert g.info["window_far_b"] > 0
-    for plan in (SHARED2, SHARED4):
-        with pytest.raises(gpu.CpError) as e:
-            run_gpu(w, plan, graph=g)
-        assert e.value.code == -12
+    assert g.info["window_far_b"] > 0 and g.info["window_far_t"] > 0
     g.close()
+    _check(gpu, oracle, w, plans=(SHARED2, SHARED4), layouts=(0, 1))
+
+
+def test_far_reads_on_wide_ticks(gpu, oracle):
+    """Far reads beside ticks of eight slices (several far wavefronts, two stores per compute
+    wavefront and tick in some shapes)."""
+    import test_gpu_parity as T
+    rng = np.random.default_rng(84)
+    n, level, src, dst = T._with_long_edges(rng, [600] * 300, extra=5000, min_span=40)
+    w = T._custom("long-edges", n, src, dst, rng.integers(1, 3000, size=len(src)), rng.integers(1, 500, size=n),
+                  [1, 2, 4, 4], rng.integers(1, 40, size=(4, 4)), rng.integers(0, 4, size=(37, n), dtype=np.uint8), level)
+    g = gpu.CpGraph.from_workload(w, device="cuda:0")
+    info = g.info
+    g.close()
+    assert info["window_ok"] == 1 and info["window_far_b"] > 0 and info["window_far_t"] > 0
+    _check(gpu, oracle, w, plans=(SHARED2, SHARED4), layouts=(0, 1))
 
 
 def test_cp_alone_and_b_alone(gpu, oracle):
