@@ -91,6 +91,12 @@ int launch_window_stream(const SweepLaunch &s, const StreamCfg &cfg, void *strea
 // with_mask: the t sweep also stages the tick's b values and writes the mask.
 bool window_config(const WindowDir &d, int32_t k, size_t tick_bytes, size_t lds_limit, WindowCfg &out,
                    bool with_mask = false);
+// The two sweeps side by side in one launch (window_pair_kernel): shapes for both, or false
+// where that form does not apply.
+bool window_pair_config(const WindowDir &db, const WindowDir &dt, int32_t k, size_t lds_limit, WindowCfg &out_b,
+                        WindowCfg &out_t);
+int launch_window_pair(const SweepLaunch &sb, const SweepLaunch &st, const WindowCfg &cfg_b, const WindowCfg &cfg_t,
+                       void *stream);
 int32_t window_mask_bpad(const WindowDir &d);
 int launch_gather_assign(const SweepLaunch &s, uint8_t *out, void *stream);
 
