@@ -30,13 +30,17 @@ HBM_PEAK_GBS = 8000.0  # MI355X, published
 # a figure belongs to one build of the kernels and one configuration, and is reported only
 # while the sources it was taken on are unchanged and the configuration matches.
 MEASURED_TRAFFIC = {
-    "sources_sha256": "unset",
+    "sources_sha256": "aebd59549fa48d9939534609778afb9c44b5b280c2f2450e3c5a99230fb7d9da",
     "runs": [
-        # (workload, P, plan, out_layout) -> bytes per b-level launch
+        # (workload, P, plan, out_layout) -> HBM bytes per launch of the dominant kernel: FETCH_SIZE x 2.00 +
+        # WRITE_SIZE x 1.00 (KiB per dispatch, scaled by what the same counters read for a 1 GiB copy and fill)
+        (("large_sparse", 256, 2, 1), (2 * 454582.1 + 2000005.1) * 1024),        # both sweeps in one launch
+        (("large_sparse", 1024, 4, 1), (2 * 602781.3 + 4000023.6) * 1024),       # b-level sweep
+        (("large_sparse", 16384, 4, 1), (2 * 9642987.4 + 64000470.1) * 1024),    # b-level sweep
     ],
 }
-TRAFFIC_SOURCES = ("kernels.hip", "window_shared.hip", "graph.cpp", "cpeval_internal.hpp",
-                   "device_math.hpp")     # the sweep kernels and the packet layout
+TRAFFIC_SOURCES = ("kernels.hip", "window_shared.hip", "graph.cpp", "api.hip", "launch.hpp", "cpeval_internal.hpp",
+                   "device_math.hpp")     # the sweep kernels, the packet layout, the choice of plan and shape
 
 
 def sources_digest():
@@ -76,6 +80,8 @@ def main():
     ap.add_argument("--plan", type=int, default=0, help="0 auto, 1 wave-column, 2 resident-window, "
                     "3 / 4 shared window with 2 / 4 partitions per workgroup, 5 column slices, 6 streamed window")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
+    ap.add_argument("--print-sources-digest", action="store_true",
+                    help="print the digest MEASURED_TRAFFIC is keyed by (after taking the HBM counters anew) and exit")
     ap.add_argument("--out-layout", default="native", choices=("native", "vertex", "partition"),
                     help="layout of b, tl and the mask; native = the one the plan that runs produces directly "
                          "(partition-major for the resident-window plan, vertex-major for wave-column)")
@@ -88,6 +94,9 @@ def main():
                     help="also run a plain device copy of this many MiB (a known-size kernel to scale "
                          "hardware byte counters against)")
     args = ap.parse_args()
+    if args.print_sources_digest:
+        print(sources_digest())
+        return
     if args.gpus != 1:
         print("bench.py measures one GPU: the path has no multi-GPU part; run with --gpus 1", file=sys.stderr)
         sys.exit(2)

@@ -417,9 +417,22 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_shared_kernel(Sha
                     acc[g] = x;
                 }
             }
-            // the row's first lane publishes the vertex: ring, output, running maxima
             const int row = lane >> lsh;
             const bool first = lsh == 0 || (lane & ((1 << lsh) - 1)) == 0;
+            // (the requests for b go out before this slice's stores: the wait for them, two ticks on,
+            // then leaves the stores issued since in flight, whatever their number)
+            if constexpr (TSWEEP) {
+                if (with_mask) {
+                    pd.on = row < rows && first;
+                    pd.v = rc.x;                 // padding rows carry a vertex of the tick: a valid index
+#pragma unroll
+                    for (int g = 0; g < G; ++g) pd.tl[g] = acc[g];
+                    const uint32_t off = __umul24(rc.x, out_sv) << 2;      // (the launcher checked that it fits)
+#pragma unroll
+                    for (int g = 0; g < G; ++g) pd.b[g] = (uint32_t) * (const int32_t *)((const char *)bq[g] + off);
+                }
+            }
+            // the row's first lane publishes the vertex: ring, output, running maxima
             if (row < rows && first) {
                 int rs = rbase + row;
                 if (rs >= R) rs -= R;
@@ -445,17 +458,6 @@ __global__ __launch_bounds__(kWindowMaxWaves * 64) void window_shared_kernel(Sha
 #pragma unroll
                         for (int g = 0; g < G; ++g) outq[g][(size_t)rc.x * out_sv] = (int32_t)(TSWEEP ? acc[g] : fin[g]);
                     }
-                }
-            }
-            if constexpr (TSWEEP) {
-                if (with_mask) {
-                    pd.on = row < rows && first;
-                    pd.v = rc.x;                 // padding rows carry a vertex of the tick: a valid index
-#pragma unroll
-                    for (int g = 0; g < G; ++g) pd.tl[g] = acc[g];
-                    const uint32_t off = __umul24(rc.x, out_sv) << 2;      // (the launcher checked that it fits)
-#pragma unroll
-                    for (int g = 0; g < G; ++g) pd.b[g] = (uint32_t) * (const int32_t *)((const char *)bq[g] + off);
                 }
             }
         };
