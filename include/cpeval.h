@@ -82,7 +82,8 @@ extern "C" {
 
 #define CP_PLAN_AUTO             0
 #define CP_PLAN_WAVE_COLUMN      1   /* one wavefront = one vertex x 64 partitions; one launch per level */
-#define CP_PLAN_RESIDENT_WINDOW  2   /* one workgroup = one partition; recent levels kept in LDS; one launch per sweep */
+#define CP_PLAN_RESIDENT_WINDOW  2   /* one workgroup = one partition; recent levels kept in LDS; one launch per sweep, or
+                                        one for both sweeps where a workgroup of each fits a compute unit side by side */
 #define CP_PLAN_SHARED_WINDOW_2  3   /* as 2, but one workgroup = 2 partitions behind one graph stream */
 #define CP_PLAN_SHARED_WINDOW_4  4   /* ... 4 partitions */
 #define CP_PLAN_STREAMED_WINDOW  6   /* as 2, but the compute wavefronts fetch the graph themselves, two ticks ahead, into
@@ -452,7 +453,8 @@ int cp_profile_reset(cp_profile *p);                       /* next call fills sl
 int cp_profile_count(const cp_profile *p, int32_t *out);   /* slots filled so far */
 /* Milliseconds per stage for one filled slot; the stream must have drained.
  * sweep_launches[0], [1] (may be NULL) receive the number of kernel launches the
- * b-level and t-level stages made. */
+ * b-level and t-level stages made; {1, 0} for a call that asked for both sweeps means one
+ * launch ran both (its time is the b-level stage's). */
 int cp_profile_read(const cp_profile *p, int32_t slot, float ms_out[CP_NUM_STAGES],
                     int32_t sweep_launches[2]);
 void cp_profile_destroy(cp_profile *p);
