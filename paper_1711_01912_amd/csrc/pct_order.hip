@@ -10,6 +10,13 @@
 // list; the vertex number never enters the key.  Each digit (8 bits, or 9 where that
 // saves a pass) takes three launches: per-tile digit counts, an exclusive scan of the counts per partition in
 // (digit, tile) order, and a stable scatter.
+//
+// Long partitions of 32-bit keys take a shorter way where they can: one such pass on the
+// LEADING 9 bits cuts a partition into 512 buckets, and a bucket of at most 4,096 or 8,192 items is
+// then sorted on the remaining bits entirely inside LDS by one workgroup (the same ranking,
+// LDS to LDS) and leaves as the finished list: every item crosses HBM twice less.  Whether
+// every bucket fits is only known on the device, so both continuations are launched and a flag
+// the bucket check sets lets one of them return at once.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -33,6 +40,9 @@ inline int sort_threads(int32_t n) { return n >= kSortLongFrom ? kSortThreadsLon
 // Passes over a key of `bits` bits: digits of 8 bits, of up to 9 where allowed.
 inline int pct_passes(int bits, bool wide) { return (bits + (wide ? 9 : 8) - 1) / (wide ? 9 : 8); }
 
+// the bucket path cuts a partition by its leading kBucketBits bits
+constexpr int kBucketBits = 9, kBuckets = 1 << kBucketBits;
+
 inline int hip_status(hipError_t e) { return e == hipSuccess ? CP_OK : CP_ERR_HIP; }
 
 // ---------------------------------------------------------------- keys
@@ -45,6 +55,14 @@ struct KeyArgs {
     int32_t *status;
     int64_t max_b;
     int32_t n, P, k, bb;
+};
+
+// A kernel launched for one of two continuations returns at once when the device-side flag
+// says the other one runs (flag == nullptr: always runs).  Uniform for the whole grid.
+struct Gate {
+    const uint32_t *flag;
+    uint32_t want;
+    __device__ __forceinline__ bool closed() const { return flag != nullptr && *flag != want; }
 };
 
 // b is vertex-major, the sort wants one contiguous key array per partition: 64 x 64
@@ -108,22 +126,44 @@ __global__ __launch_bounds__(256) void pct_keys_rows_kernel(KeyArgs a) {
 
 // ---------------------------------------------------------------- one digit pass
 
+
 template <int RB, typename Key>
 __device__ __forceinline__ uint32_t digit_of(Key key, int shift) {
     return (uint32_t)(key >> shift) & ((1u << RB) - 1);
 }
 
+// The counting kernels keep several copies of the histogram in LDS, a lane adding to copy
+// (lane mod copies): the vertices of a wavefront often share a handful of leading digits, and
+// adds to one counter queue up behind each other.  A copy's row is one word longer than the
+// radix, so that equal digits in different copies fall into different banks.
+template <int kThreads, int kRadix>
+struct Histogram {
+    static constexpr int kCopies = kThreads >= 1024 ? 8192 / kRadix : 8;      // 16 or 32; 8 for the short tile
+    uint32_t h[kCopies][kRadix + 1];
+    __device__ __forceinline__ void clear(int tid) {
+        for (int i = tid; i < kCopies * (kRadix + 1); i += kThreads) (&h[0][0])[i] = 0;
+    }
+    __device__ __forceinline__ void add(int tid, uint32_t d) { atomicAdd(&h[tid & (kCopies - 1)][d], 1u); }
+    __device__ __forceinline__ uint32_t total(uint32_t d) const {
+        uint32_t c = 0;
+#pragma unroll
+        for (int w = 0; w < kCopies; ++w) c += h[w][d];
+        return c;
+    }
+};
+
 // counts[q][digit][tile] = items of the tile with that digit
 template <typename Key, int kSortThreads, int RB>
 __global__ __launch_bounds__(kSortThreads) void pct_count_kernel(const Key *__restrict__ keys, int32_t n,
                                                                  int32_t tiles, int shift,
-                                                                 uint32_t *__restrict__ counts) {
-    constexpr int kSortWaves = kSortThreads / 64, kSortTile = kSortThreads * kSortRounds, kRadix = 1 << RB;
+                                                                 uint32_t *__restrict__ counts, Gate gate) {
+    constexpr int kSortTile = kSortThreads * kSortRounds, kRadix = 1 << RB;
     static_assert(kSortThreads >= kRadix, "one thread per digit writes the counts");
-    __shared__ uint32_t h[kSortWaves][kRadix];
-    const int tid = threadIdx.x, wave = tid >> 6;
+    if (gate.closed()) return;
+    __shared__ Histogram<kSortThreads, kRadix> hist;
+    const int tid = threadIdx.x;
     const int32_t tile = (int32_t)(blockIdx.x % (uint32_t)tiles), q = (int32_t)(blockIdx.x / (uint32_t)tiles);
-    for (int i = tid; i < kSortWaves * kRadix; i += kSortThreads) (&h[0][0])[i] = 0;
+    hist.clear(tid);
     __syncthreads();
     const Key *src = keys + (int64_t)q * n;
     const int64_t base = (int64_t)tile * kSortTile;
@@ -136,30 +176,86 @@ __global__ __launch_bounds__(kSortThreads) void pct_count_kernel(const Key *__re
 #pragma unroll
     for (int r = 0; r < kSortRounds; ++r) {
         const int64_t i = base + r * kSortThreads + tid;
-        const uint32_t d = digit_of<RB>(key[r], shift);
-        // a wavefront whose lanes all hold one digit (the usual case for the leading digit)
-        // adds once instead of 64 times to one counter
-        const uint32_t d0 = __builtin_amdgcn_readfirstlane(d);
-        const unsigned long long live = __ballot(i < n);
-        if (__ballot(i < n && d != d0) == 0) {
-            if ((tid & 63) == 0 && live) h[wave][d0] += (uint32_t)__popcll(live);
-        } else if (i < n) {
-            atomicAdd(&h[wave][d], 1u);
-        }
+        if (i < n) hist.add(tid, digit_of<RB>(key[r], shift));
     }
     __syncthreads();
-    if (tid < kRadix) {
-        uint32_t c = 0;
+    if (tid < kRadix) counts[((int64_t)q * kRadix + tid) * tiles + tile] = hist.total(tid);
+}
+
+// Keys from rows of b ([P][n]) and, in the same pass, the counts of their leading digit: what
+// pct_keys_rows_kernel and the first pct_count_kernel do, with one read of b.  A thread takes four
+// consecutive vertices per round (VEC: as one 16-byte load of b, one 4-byte load of device ids, one
+// 16-byte store of keys; needs n % 4 == 0, unit stride between a partition's ids and aligned rows).
+struct alignas(16) Keys4 { uint32_t x[4]; };
+template <typename Tick> struct alignas(16) Ticks4 { Tick x[4]; };
+template <typename Tick, bool VEC>
+__global__ __launch_bounds__(kSortThreadsLong) void pct_keys_count_kernel(KeyArgs a, int32_t tiles, int shift,
+                                                                          uint32_t *__restrict__ counts) {
+    constexpr int kRadix = 1 << kBucketBits, kTile = kSortThreadsLong * kSortRounds;
+    constexpr int kQuadRounds = kSortRounds / 4;
+    __shared__ Histogram<kSortThreadsLong, kRadix> hist;
+    const int tid = threadIdx.x;
+    const int32_t tile = (int32_t)(blockIdx.x % (uint32_t)tiles), q = (int32_t)(blockIdx.x / (uint32_t)tiles);
+    hist.clear(tid);
+    __syncthreads();
+    const Tick *b = (const Tick *)a.b + (int64_t)q * a.n;
+    const uint8_t *ids = a.assign + q * a.a_stride_p;
+    uint32_t *keys = (uint32_t *)a.keys + (int64_t)q * a.n;
+    const int32_t base = tile * kTile;
+    uint32_t key[kQuadRounds][4];
+    bool bad_b = false, bad_id = false;
 #pragma unroll
-        for (int w = 0; w < kSortWaves; ++w) c += h[w][tid];
-        counts[((int64_t)q * kRadix + tid) * tiles + tile] = c;
+    for (int r = 0; r < kQuadRounds; ++r) {
+        const int32_t i0 = base + (r * kSortThreadsLong + tid) * 4;
+        Ticks4<Tick> bv{};
+        uint32_t dv = 0;
+        if (VEC) {
+            if (i0 < a.n) {
+                bv = *(const Ticks4<Tick> *)(b + i0);
+                dv = *(const uint32_t *)(ids + i0);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (i0 + j < a.n) {
+                    bv.x[j] = b[i0 + j];
+                    dv |= (uint32_t)ids[(int64_t)(i0 + j) * a.a_stride_v] << (8 * j);
+                }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            long long t = (long long)bv.x[j];
+            if (t < 0 || t > a.max_b) { bad_b = true; t = t < 0 ? 0 : a.max_b; }
+            uint32_t dev = (dv >> (8 * j)) & 0xffu;
+            if (dev >= (uint32_t)a.k) { bad_id = true; dev = (uint32_t)a.k - 1; }
+            key[r][j] = (uint32_t)(a.max_b - t) | dev << a.bb;
+        }
+        if (VEC) {
+            if (i0 < a.n) *(Keys4 *)(keys + i0) = Keys4{{key[r][0], key[r][1], key[r][2], key[r][3]}};
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (i0 + j < a.n) keys[i0 + j] = key[r][j];
+        }
     }
+    if (bad_id) atomicOr(a.status, CP_STATUS_BAD_DEVICE_ID);
+    if (bad_b) atomicOr(a.status, CP_STATUS_B_OUT_OF_RANGE);
+#pragma unroll
+    for (int r = 0; r < kQuadRounds; ++r) {
+        const int32_t i0 = base + (r * kSortThreadsLong + tid) * 4;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (i0 + j < a.n) hist.add(tid, digit_of<kBucketBits>(key[r][j], shift));
+    }
+    __syncthreads();
+    if (tid < kRadix) counts[((int64_t)q * kRadix + tid) * tiles + tile] = hist.total(tid);
 }
 
 // In place: counts[q][*] becomes its exclusive prefix sum in (digit, tile) order, i.e.
 // where the tile's run of that digit starts in the partition's output.
-__global__ __launch_bounds__(1024) void pct_scan_kernel(uint32_t *__restrict__ counts, int32_t entries) {
+__global__ __launch_bounds__(1024) void pct_scan_kernel(uint32_t *__restrict__ counts, int32_t entries, Gate gate) {
     __shared__ uint32_t wave_sum[16];
+    if (gate.closed()) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     uint32_t *c = counts + (int64_t)blockIdx.x * entries;
     const int32_t per = (entries + 1023) / 1024;
@@ -183,9 +279,44 @@ __global__ __launch_bounds__(1024) void pct_scan_kernel(uint32_t *__restrict__ c
     }
 }
 
+// The lanes of the wavefront whose item is valid and has the same RB-bit digit as this lane's
+// (for a lane with a valid item).  One ballot per bit; a lane collects, per half of the
+// wavefront, the lanes whose bit differs from its own.
+template <int RB>
+__device__ __forceinline__ unsigned long long lanes_with_same_digit(uint32_t d, bool valid) {
+    uint32_t diff_lo = 0, diff_hi = 0;
+#pragma unroll
+    for (int bit = 0; bit < RB; ++bit) {
+        const uint32_t mine = (uint32_t)((int32_t)(d << (31 - bit)) >> 31);      // all ones where the bit is set
+        const unsigned long long bal = __ballot(mine != 0);
+        diff_lo |= (uint32_t)bal ^ mine;
+        diff_hi |= (uint32_t)(bal >> 32) ^ mine;
+    }
+    const unsigned long long live = __ballot(valid);
+    return live & ~((unsigned long long)diff_hi << 32 | diff_lo);
+}
+
+// Rank of a valid lane's item among the wavefront's earlier items with its digit: the digit's
+// counter (one row of counters per wavefront) plus the lane's place among the lanes of this
+// round that share the digit; the last of them moves the counter on.  LDS reads and writes of
+// one wavefront keep their order, so every lane has read before one writes.
+template <int RB>
+__device__ __forceinline__ uint32_t rank_in_wavefront(uint32_t *counters, uint32_t d, bool valid) {
+    const unsigned long long same = lanes_with_same_digit<RB>(d, valid);
+    const uint32_t place = __builtin_amdgcn_mbcnt_hi((uint32_t)(same >> 32),
+                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)same, 0u));
+    const uint32_t together = (uint32_t)__popcll(same);
+    uint32_t before = 0;
+    if (valid) {
+        before = counters[d];
+        if (place + 1 == together) counters[d] = before + together;
+    }
+    return before + place;
+}
+
 // Stable scatter of one tile.  Wavefront w owns items [w*1024, (w+1)*1024) of the tile
 // and takes them 64 at a time, so item order is (wavefront, round, lane).  Inside a
-// round, lanes with equal digits find each other by ballots; the lowest of them
+// round, lanes with equal digits find each other by ballots; the last of them
 // advances the wavefront's counter for that digit.  The tile is then put in digit order
 // in LDS and written out in runs: first the keys, then, through the same LDS buffer,
 // the vertex numbers.
@@ -195,9 +326,10 @@ __global__ __launch_bounds__(kSortThreads) void pct_scatter_kernel(const Key *__
                                                                    Key *__restrict__ keys_out,
                                                                    int32_t *__restrict__ vals_out, int32_t n,
                                                                    int32_t tiles, int shift,
-                                                                   const uint32_t *__restrict__ starts) {
+                                                                   const uint32_t *__restrict__ starts, Gate gate) {
     constexpr int kSortWaves = kSortThreads / 64, kSortTile = kSortThreads * kSortRounds, kRadix = 1 << RB;
     static_assert(kSortThreads >= kRadix, "one thread per digit when the tile's digit starts are computed");
+    if (gate.closed()) return;
     extern __shared__ __align__(16) uint8_t sort_lds[];      // kSortTile keys, later kSortTile vertex numbers
     __shared__ uint32_t cnt[kSortWaves][kRadix];
     __shared__ uint32_t tile_start[kRadix];
@@ -227,25 +359,7 @@ __global__ __launch_bounds__(kSortThreads) void pct_scatter_kernel(const Key *__
     for (int r = 0; r < kSortRounds; ++r) {
         const int32_t t = wave * (kSortRounds * 64) + r * 64 + lane;
         const bool valid = t < tile_items;
-        const uint32_t d = digit_of<RB>(key[r], shift);
-        unsigned long long same = __ballot(valid);
-#pragma unroll
-        for (int bit = 0; bit < RB; ++bit) {
-            const bool one = (d >> bit) & 1u;
-            const unsigned long long bal = __ballot(one);
-            same &= one ? bal : ~bal;
-        }
-        if (!valid) same = 1ull << lane;
-        const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(same >> 32),
-                                                        __builtin_amdgcn_mbcnt_lo((uint32_t)same, 0u));
-        const int leader = __ffsll((long long)same) - 1;
-        uint32_t old = 0;
-        if (valid && lane == leader) {
-            old = cnt[wave][d];
-            cnt[wave][d] = old + (uint32_t)__popcll(same);
-        }
-        old = __shfl(old, leader);
-        loc[r] = old + rank;
+        loc[r] = rank_in_wavefront<RB>(cnt[wave], digit_of<RB>(key[r], shift), valid);
     }
     __syncthreads();
     uint32_t run = 0, inc = 0;
@@ -307,6 +421,130 @@ __global__ __launch_bounds__(kSortThreads) void pct_scatter_kernel(const Key *__
     }
 }
 
+// ---------------------------------------------------------------- buckets of the leading digit
+
+// a bucket is sorted by a workgroup of 256 or 512 threads, 16 items per thread at most
+constexpr int kBucketCapSmall = 256 * kSortRounds, kBucketCapLarge = 512 * kSortRounds;     // 4,096 / 8,192 items
+
+__global__ void pct_flag_clear_kernel(uint32_t *flag) { *flag = 0; }
+
+// After the scan of the leading digit's counts, bucket d of partition q starts where tile 0's
+// run of digit d starts.  flag |= 1 if some bucket holds more than `cap` items.
+__global__ __launch_bounds__(kBuckets) void pct_bucket_check_kernel(const uint32_t *__restrict__ starts, int32_t n,
+                                                                    int32_t tiles, int32_t cap, uint32_t *flag) {
+    const int32_t q = blockIdx.x, d = threadIdx.x;
+    const uint32_t lo = starts[((int64_t)q * kBuckets + d) * tiles];
+    const uint32_t hi = d + 1 < kBuckets ? starts[((int64_t)q * kBuckets + d + 1) * tiles] : (uint32_t)n;
+    if (hi - lo > (uint32_t)cap) atomicOr(flag, 1u);
+}
+
+// One bucket, sorted on the low `bits` bits inside LDS: stable passes of 8 bits, each ranking
+// the items as the scatter kernel does (wavefront w owns items [w*1024, (w+1)*1024) of the
+// bucket in (round, lane) order) and moving keys and vertex numbers through one LDS buffer;
+// the vertex numbers of the last pass go straight out.
+template <int kBucketThreads>
+__global__ __launch_bounds__(kBucketThreads) void pct_bucket_sort_kernel(const uint32_t *__restrict__ keys_in,
+                                                                         const int32_t *__restrict__ vals_in,
+                                                                         int32_t *__restrict__ vals_out, int32_t n,
+                                                                         int32_t tiles, int bits,
+                                                                         const uint32_t *__restrict__ starts, Gate gate) {
+    constexpr int kWaves = kBucketThreads / 64, kRadix = 256, kBucketCap = kBucketThreads * kSortRounds;
+    __shared__ uint32_t slot[kBucketCap];                 // keys, then vertex numbers, in sorted order
+    __shared__ uint32_t cnt[kWaves][kRadix];
+    __shared__ uint32_t digit_start[kRadix];
+    __shared__ uint32_t wave_sum[kRadix / 64];
+    if (gate.closed()) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int32_t q = (int32_t)(blockIdx.x / kBuckets), d = (int32_t)(blockIdx.x % kBuckets);
+    const uint32_t lo = starts[((int64_t)q * kBuckets + d) * tiles];
+    const uint32_t hi = d + 1 < kBuckets ? starts[((int64_t)q * kBuckets + d + 1) * tiles] : (uint32_t)n;
+    const int32_t items = (int32_t)(hi - lo);
+    if (items <= 0 || items > kBucketCap) return;         // (larger buckets: the other continuation runs)
+    const int64_t at = (int64_t)q * n + lo;
+    // rounds this bucket needs (the same for every wavefront: wavefront w owns items
+    // [w * nr * 64, (w + 1) * nr * 64) of the bucket)
+    const int nr = (items + kBucketThreads - 1) / kBucketThreads;
+
+    uint32_t key[kSortRounds], loc[kSortRounds];
+    int32_t val[kSortRounds];
+#pragma unroll
+    for (int r = 0; r < kSortRounds; ++r) {
+        const int32_t t = wave * (nr * 64) + r * 64 + lane;
+        const bool valid = r < nr && t < items;
+        key[r] = valid ? keys_in[at + t] : 0u;
+        val[r] = valid ? vals_in[at + t] : 0;
+    }
+    for (int shift = 0; shift < bits; shift += 8) {
+        const bool last = shift + 8 >= bits;
+        for (int i = tid; i < kWaves * kRadix; i += kBucketThreads) (&cnt[0][0])[i] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < kSortRounds; ++r) {
+            if (r >= nr) continue;           // (uniform)
+            const int32_t t = wave * (nr * 64) + r * 64 + lane;
+            const bool valid = t < items;
+            loc[r] = rank_in_wavefront<8>(cnt[wave], digit_of<8>(key[r], shift), valid);
+        }
+        __syncthreads();
+        uint32_t run = 0, inc = 0;
+        if (tid < kRadix) {   // thread dg: wavefront bases, then the bucket's digit starts
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                const uint32_t c = cnt[w][tid];
+                cnt[w][tid] = run;
+                run += c;
+            }
+            inc = run;
+            for (int off = 1; off < 64; off <<= 1) {
+                const uint32_t up = __shfl_up(inc, off);
+                if (lane >= off) inc += up;
+            }
+            if (lane == 63) wave_sum[wave] = inc;
+        }
+        __syncthreads();
+        if (tid < kRadix) {
+            uint32_t before = 0;
+            for (int w = 0; w < wave; ++w) before += wave_sum[w];
+            digit_start[tid] = before + inc - run;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < kSortRounds; ++r) {
+            const int32_t t = wave * (nr * 64) + r * 64 + lane;
+            if (r < nr && t < items) {
+                const uint32_t dg = digit_of<8>(key[r], shift);
+                loc[r] = digit_start[dg] + cnt[wave][dg] + loc[r];
+                if (!last) slot[loc[r]] = key[r];
+            }
+        }
+        if (!last) {          // the keys come back in sorted order, then the vertex numbers the same way
+            __syncthreads();
+#pragma unroll
+            for (int r = 0; r < kSortRounds; ++r) {
+                const int32_t t = wave * (nr * 64) + r * 64 + lane;
+                if (r < nr && t < items) key[r] = slot[t];
+            }
+            __syncthreads();
+        }
+#pragma unroll
+        for (int r = 0; r < kSortRounds; ++r) {
+            const int32_t t = wave * (nr * 64) + r * 64 + lane;
+            if (r < nr && t < items) slot[loc[r]] = (uint32_t)val[r];
+        }
+        __syncthreads();
+        if (last) {
+            for (int32_t i = tid; i < items; i += kBucketThreads) vals_out[at + i] = (int32_t)slot[i];
+        } else {
+#pragma unroll
+            for (int r = 0; r < kSortRounds; ++r) {
+                const int32_t t = wave * (nr * 64) + r * 64 + lane;
+                if (r < nr && t < items) val[r] = (int32_t)slot[t];
+            }
+            __syncthreads();
+        }
+    }
+}
+
 // seg[q][d] = first position of the sorted list whose vertex sits on a device >= d
 __global__ void pct_segments_kernel(const int32_t *__restrict__ order, const uint8_t *__restrict__ assign,
                                     int64_t a_stride_p, int64_t a_stride_v, int32_t n, int32_t P, int32_t k,
@@ -324,17 +562,19 @@ __global__ void pct_segments_kernel(const int32_t *__restrict__ order, const uin
     seg[i] = lo;
 }
 
-// One digit pass of RB bits starting at bit `shift`.
+// One digit pass of RB bits starting at bit `shift`.  counted: the counts are there already.
 template <typename Key, int THREADS, int RB>
 int run_pass(const PctOrderLaunch &s, hipStream_t st, int shift, bool first, bool last, const Key *kin, Key *kout,
-             const int32_t *vin, int32_t *vout) {
+             const int32_t *vin, int32_t *vout, Gate gate = Gate{nullptr, 0}, bool counted = false) {
     constexpr int kTile = THREADS * kSortRounds;
     const int32_t n = s.n, P = s.P;
     const int32_t tiles = (n + kTile - 1) / kTile;
     const dim3 grid((unsigned)((int64_t)tiles * P)), block(THREADS);     // one workgroup per (partition, tile)
     const size_t lds = (size_t)kTile * sizeof(Key);
-    hipLaunchKernelGGL((pct_count_kernel<Key, THREADS, RB>), grid, block, 0, st, kin, n, tiles, shift, s.counts);
-    hipLaunchKernelGGL(pct_scan_kernel, dim3((unsigned)P), dim3(1024), 0, st, s.counts, (1 << RB) * tiles);
+    if (!counted)
+        hipLaunchKernelGGL((pct_count_kernel<Key, THREADS, RB>), grid, block, 0, st, kin, n, tiles, shift, s.counts,
+                           gate);
+    hipLaunchKernelGGL(pct_scan_kernel, dim3((unsigned)P), dim3(1024), 0, st, s.counts, (1 << RB) * tiles, gate);
 #define CP_SCATTER(F, L)                                                                                   \
     do {                                                                                                   \
         auto kern = pct_scatter_kernel<Key, THREADS, RB, F, L>;                                            \
@@ -342,7 +582,7 @@ int run_pass(const PctOrderLaunch &s, hipStream_t st, int shift, bool first, boo
         if (lds > 64 * 1024 && hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
                                                    (int)lds) != hipSuccess)                                \
             return CP_ERR_HIP;                                                                             \
-        hipLaunchKernelGGL(kern, grid, block, lds, st, kin, vin, kout, vout, n, tiles, shift, s.counts);   \
+        hipLaunchKernelGGL(kern, grid, block, lds, st, kin, vin, kout, vout, n, tiles, shift, s.counts, gate); \
     } while (0)
     if (first && last) CP_SCATTER(true, true);
     else if (first) CP_SCATTER(true, false);
@@ -355,7 +595,7 @@ int run_pass(const PctOrderLaunch &s, hipStream_t st, int shift, bool first, boo
 // WIDE: 9-bit digits may be used (long tiles of 32-bit keys: the counters of a 64-bit
 // tile's 512 digits would not fit LDS beside the tile).
 template <typename Key, int THREADS, bool WIDE>
-int run_sort(const PctOrderLaunch &s, hipStream_t st) {
+int run_sort(const PctOrderLaunch &s, hipStream_t st, Gate gate = Gate{nullptr, 0}) {
     Key *ka = (Key *)s.keys_a, *kb = (Key *)s.keys_b;
     const int passes = pct_passes(s.key_bits, WIDE);
     // 8 bits per pass; where that leaves bits over, the leading passes take 9
@@ -372,10 +612,10 @@ int run_sort(const PctOrderLaunch &s, hipStream_t st) {
         const int32_t *vin = to_out ? s.vals_tmp : s.order_out;
         int rc;
         if (WIDE && p < wide_passes) {
-            rc = run_pass<Key, THREADS, WIDE ? 9 : 8>(s, st, shift, first, last, kin, kout, vin, vout);
+            rc = run_pass<Key, THREADS, WIDE ? 9 : 8>(s, st, shift, first, last, kin, kout, vin, vout, gate);
             shift += 9;
         } else {
-            rc = run_pass<Key, THREADS, 8>(s, st, shift, first, last, kin, kout, vin, vout);
+            rc = run_pass<Key, THREADS, 8>(s, st, shift, first, last, kin, kout, vin, vout, gate);
             shift += 8;
         }
         if (rc) return rc;
@@ -383,27 +623,8 @@ int run_sort(const PctOrderLaunch &s, hipStream_t st) {
     return CP_OK;
 }
 
-}  // namespace
-
-int32_t pct_sort_tiles(int32_t n) {
-    const int tile = sort_threads(n) * kSortRounds;
-    return (n + tile - 1) / tile;
-}
-size_t pct_counts_bytes(int32_t n, int32_t P) {
-    return align_up((size_t)P * kMaxRadix * (size_t)pct_sort_tiles(n) * sizeof(uint32_t));
-}
-
-int launch_pct_order(const PctOrderLaunch &s, void *stream) {
-    hipStream_t st = (hipStream_t)stream;
-    KeyArgs a{};
-    a.b = s.b;
-    a.assign = s.assign;
-    a.a_stride_p = s.a_stride_p;
-    a.a_stride_v = s.a_stride_v;
-    a.keys = s.keys_a;
-    a.status = s.status;
-    a.max_b = s.max_b;
-    a.n = s.n; a.P = s.P; a.k = s.k; a.bb = s.b_bits;
+// The key kernels, for all four (tick, key) widths.
+void launch_keys(const PctOrderLaunch &s, const KeyArgs &a, hipStream_t st) {
 #define CP_KEYS(KERNEL, GRID)                                                                         \
     do {                                                                                              \
         if (s.key_bytes == 4) {                                                                       \
@@ -422,9 +643,88 @@ int launch_pct_order(const PctOrderLaunch &s, void *stream) {
         CP_KEYS(pct_keys_kernel, kgrid);
     }
 #undef CP_KEYS
+}
+
+// The leading digit's pass, the bucket check, and both continuations: buckets sorted inside
+// LDS (flag 0), or the ordinary passes from the untouched keys (flag 1).  With rows of b per
+// partition one kernel writes the keys and counts their leading digit.
+int run_bucket_sort(const PctOrderLaunch &s, const KeyArgs &a, hipStream_t st) {
+    constexpr int kTile = kSortThreadsLong * kSortRounds;
+    const int32_t tiles = (s.n + kTile - 1) / kTile;
+    uint32_t *flag = s.counts + (size_t)s.P * kMaxRadix * (size_t)tiles;     // behind the counts
+    hipLaunchKernelGGL(pct_flag_clear_kernel, dim3(1), dim3(1), 0, st, flag);
+    const int rem = s.key_bits - kBucketBits;
+    if (s.b_by_partition) {
+        const dim3 grid((unsigned)((int64_t)tiles * s.P)), block(kSortThreadsLong);
+        const bool vec = s.n % 4 == 0 && s.a_stride_v == 1 && s.a_stride_p % 4 == 0 && (uintptr_t)s.assign % 4 == 0 &&
+                         (uintptr_t)s.b % 16 == 0 && (uintptr_t)s.keys_a % 16 == 0;
+        if (s.tick_bytes == 4) {
+            if (vec) hipLaunchKernelGGL((pct_keys_count_kernel<int32_t, true>), grid, block, 0, st, a, tiles, rem, s.counts);
+            else hipLaunchKernelGGL((pct_keys_count_kernel<int32_t, false>), grid, block, 0, st, a, tiles, rem, s.counts);
+        } else {
+            if (vec) hipLaunchKernelGGL((pct_keys_count_kernel<int64_t, true>), grid, block, 0, st, a, tiles, rem, s.counts);
+            else hipLaunchKernelGGL((pct_keys_count_kernel<int64_t, false>), grid, block, 0, st, a, tiles, rem, s.counts);
+        }
+    } else {
+        launch_keys(s, a, st);
+    }
     if (hipGetLastError() != hipSuccess) return CP_ERR_HIP;
+    int rc = run_pass<uint32_t, kSortThreadsLong, kBucketBits>(s, st, rem, /*first=*/true, /*last=*/false,
+                                                               (const uint32_t *)s.keys_a, (uint32_t *)s.keys_b, nullptr,
+                                                               s.vals_tmp, Gate{nullptr, 0u},
+                                                               /*counted=*/s.b_by_partition);
+    if (rc) return rc;
+    // the smaller workgroup (more of them per compute unit) where buckets of twice the average size fit it
+    const bool small = 2 * ((int64_t)s.n / kBuckets + 1) <= kBucketCapSmall;
+    hipLaunchKernelGGL(pct_bucket_check_kernel, dim3((unsigned)s.P), dim3(kBuckets), 0, st, s.counts, s.n, tiles,
+                       small ? kBucketCapSmall : kBucketCapLarge, flag);
+    const dim3 bgrid((unsigned)((int64_t)s.P * kBuckets));
+    if (small)
+        hipLaunchKernelGGL(pct_bucket_sort_kernel<256>, bgrid, dim3(256), 0, st, (const uint32_t *)s.keys_b,
+                           (const int32_t *)s.vals_tmp, s.order_out, s.n, tiles, rem, (const uint32_t *)s.counts,
+                           Gate{flag, 0u});
+    else
+        hipLaunchKernelGGL(pct_bucket_sort_kernel<512>, bgrid, dim3(512), 0, st, (const uint32_t *)s.keys_b,
+                           (const int32_t *)s.vals_tmp, s.order_out, s.n, tiles, rem, (const uint32_t *)s.counts,
+                           Gate{flag, 0u});
+    if (hipGetLastError() != hipSuccess) return CP_ERR_HIP;
+    return run_sort<uint32_t, kSortThreadsLong, true>(s, st, Gate{flag, 1u});
+}
+
+}  // namespace
+
+int32_t pct_sort_tiles(int32_t n) {
+    const int tile = sort_threads(n) * kSortRounds;
+    return (n + tile - 1) / tile;
+}
+size_t pct_counts_bytes(int32_t n, int32_t P) {
+    // (and the flag of the bucket path behind them)
+    return align_up((size_t)P * kMaxRadix * (size_t)pct_sort_tiles(n) * sizeof(uint32_t) + 256);
+}
+
+int launch_pct_order(const PctOrderLaunch &s, void *stream) {
+    hipStream_t st = (hipStream_t)stream;
+    KeyArgs a{};
+    a.b = s.b;
+    a.assign = s.assign;
+    a.a_stride_p = s.a_stride_p;
+    a.a_stride_v = s.a_stride_v;
+    a.keys = s.keys_a;
+    a.status = s.status;
+    a.max_b = s.max_b;
+    a.n = s.n; a.P = s.P; a.k = s.k; a.bb = s.b_bits;
     int rc;
-    if (sort_threads(s.n) == kSortThreadsLong)
+    // the bucket path: long partitions of 32-bit keys whose buckets hold a quarter of their
+    // capacity on average (so that an uneven spread still fits), at least two passes to save
+    const bool buckets = sort_threads(s.n) == kSortThreadsLong && s.key_bytes == 4 && s.key_bits > kBucketBits + 8 &&
+                         (int64_t)s.n <= (int64_t)kBuckets * kBucketCapLarge / 4 && (int64_t)s.P * kBuckets < (1ll << 31);
+    if (!buckets) {
+        launch_keys(s, a, st);
+        if (hipGetLastError() != hipSuccess) return CP_ERR_HIP;
+    }
+    if (buckets)
+        rc = run_bucket_sort(s, a, st);
+    else if (sort_threads(s.n) == kSortThreadsLong)
         rc = s.key_bytes == 4 ? run_sort<uint32_t, kSortThreadsLong, true>(s, st)
                               : run_sort<uint64_t, kSortThreadsLong, false>(s, st);
     else

@@ -434,6 +434,56 @@ def test_pct_order_large_sparse_full(gpu, oracle):
     _check_pct_order(gpu, oracle, make_workload("large_sparse"), sample=24)
 
 
+def test_pct_order_buckets_of_the_leading_digit(gpu, oracle):
+    """Partitions of 65,536 vertices or more with keys of more than 17 bits: one pass on the
+    leading 9 bits, then every bucket sorted inside LDS."""
+    _check_pct_order(gpu, oracle, make_workload("large_sparse", P=5, levels=300, width=300))
+    _check_pct_order(gpu, oracle, make_workload("large_sparse", P=3, levels=300, width=300), layout=1)
+    _check_pct_order(gpu, oracle, make_workload("comm_heavy", P=3, levels=20, width=4000))
+    w = make_workload("large_sparse", P=3, levels=299, width=301)         # rows that are not 16-byte aligned
+    assert w.n % 4 != 0
+    _check_pct_order(gpu, oracle, w)
+
+
+def test_pct_order_buckets_too_large_for_lds(gpu, oracle):
+    """70,000 vertices without edges on one device and a generous bound: every key has the same
+    leading bits, one bucket holds the whole partition, and the ordinary passes take over."""
+    rng = np.random.default_rng(43)
+    n = 70000
+    w = _custom("one-bucket", n, np.zeros(0, dtype=np.int64), np.zeros(0, dtype=np.int64), np.zeros(0, dtype=np.int64),
+                rng.integers(1, 200, size=n), [1], [[1]], np.zeros((2, n), dtype=np.uint8),
+                np.zeros(n, dtype=np.int64))
+    _check_pct_order(gpu, oracle, w, max_b=2**24)
+    # ... and two devices with everything but a handful of vertices on one of them
+    a = np.zeros((2, n), dtype=np.uint8)
+    a[:, ::1000] = 1
+    w2 = _custom("lopsided", n, np.zeros(0, dtype=np.int64), np.zeros(0, dtype=np.int64), np.zeros(0, dtype=np.int64),
+                 rng.integers(1, 200, size=n), [1, 2], [[1, 1], [1, 1]], a, np.zeros(n, dtype=np.int64))
+    _check_pct_order(gpu, oracle, w2, max_b=2**23)
+
+
+def test_pct_order_buckets_from_rows_of_b(gpu, oracle):
+    """Rows of b per partition on the bucket path: the leading pass builds its keys from b and
+    the device ids directly.  64-bit ticks give the same lists; a bound that is too small and a
+    device id >= k are still reported."""
+    import torch
+    w = make_workload("large_sparse", P=4, levels=300, width=300)
+    g = gpu.CpGraph.from_workload(w, device="cuda:0")
+    a = torch.from_numpy(w.assignments).to("cuda:0")
+    out = gpu.cp_eval(g, a, w.speeds, w.bandwidth, want=("cp", "b"), out_layout=1)
+    bound = int(out["cp"].max().item())
+    ref_order, ref_seg = oracle.pct_order(w.k, w.assignments, out["b"].cpu().numpy().astype(np.int64), threads=8)
+    order, seg = gpu.cp_pct_order(g, a, w.k, out["b"].to(torch.int64), max_b=bound, b_layout=1)
+    assert np.array_equal(order.cpu().numpy(), ref_order) and np.array_equal(seg.cpu().numpy(), ref_seg)
+    with pytest.raises(ValueError):
+        gpu.cp_pct_order(g, a, w.k, out["b"], max_b=bound - 1, b_layout=1)
+    bad = a.clone()
+    bad[2, w.n - 5] = w.k
+    with pytest.raises(ValueError):
+        gpu.cp_pct_order(g, bad, w.k, out["b"], max_b=bound, b_layout=1)
+    g.close()
+
+
 def test_pct_order_reports_a_bound_that_is_too_small(gpu):
     import torch
     w = make_workload("tiny")

@@ -303,8 +303,9 @@ def test_consumer_entry_points_check_their_arguments(lib):
 
     need = C.c_size_t(0)
     assert lib.cp_pct_order_workspace_bytes(g._handle, 16, 2, 0, C.byref(need)) == 0
-    # two key arrays and one list of 16 x 64 32-bit items, counts for 512 digits x 1 tile x 16 partitions
-    assert need.value == 3 * 16 * 64 * 4 + 16 * 512 * 4
+    # two key arrays and one list of 16 x 64 32-bit items, counts for 512 digits x 1 tile x 16 partitions,
+    # one aligned slot for the flag of the bucket path
+    assert need.value == 3 * 16 * 64 * 4 + 16 * 512 * 4 + 256
     assert lib.cp_pct_order_workspace_bytes(g._handle, 16, 2, -1, C.byref(need)) == -12
     assert lib.cp_pct_order_workspace_bytes(g._handle, 0, 2, 0, C.byref(need)) == -2
     assert lib.cp_pct_order_workspace_bytes(g._handle, 16, 2, 0, None) == -1
@@ -312,7 +313,7 @@ def test_consumer_entry_points_check_their_arguments(lib):
     assert lib.cp_pct_order_workspace_bytes(g._handle, 16, 255, 2**62, C.byref(need)) == -8
     # a bound past 32 bits: 64-bit keys
     assert lib.cp_pct_order_workspace_bytes(g._handle, 16, 2, 2**40, C.byref(need)) == 0
-    assert need.value == 2 * 16 * 64 * 8 + 16 * 64 * 4 + 16 * 512 * 4
+    assert need.value == 2 * 16 * 64 * 8 + 16 * 64 * 4 + 16 * 512 * 4 + 256
 
     def order(batch=4, k=2, assign=dummy, layout=0, b=dummy, tick=4, b_layout=0, max_b=0, ws=dummy, out=dummy):
         return lib.cp_pct_order(g._handle, batch, k, assign, layout, b, tick, b_layout, max_b, ws, 1 << 20, None,
