@@ -252,30 +252,44 @@ __global__ __launch_bounds__(kSortThreadsLong) void pct_keys_count_kernel(KeyArg
 }
 
 // In place: counts[q][*] becomes its exclusive prefix sum in (digit, tile) order, i.e.
-// where the tile's run of that digit starts in the partition's output.
+// where the tile's run of that digit starts in the partition's output.  One workgroup per
+// partition walks the entries 4,096 at a time, four neighbours per thread (entries is a
+// multiple of the radix, so of four, and every partition's row is 16-byte aligned).
+struct alignas(16) Counts4 { uint32_t x[4]; };
 __global__ __launch_bounds__(1024) void pct_scan_kernel(uint32_t *__restrict__ counts, int32_t entries, Gate gate) {
-    __shared__ uint32_t wave_sum[16];
+    __shared__ uint32_t wave_sum[2][16];                  // (two sets: one barrier per step)
     if (gate.closed()) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     uint32_t *c = counts + (int64_t)blockIdx.x * entries;
-    const int32_t per = (entries + 1023) / 1024;
-    const int32_t lo = min(tid * per, entries), hi = min(lo + per, entries);
-    uint32_t sum = 0;
-    for (int32_t i = lo; i < hi; ++i) sum += c[i];
-    uint32_t inc = sum;                                   // inclusive scan over the wavefront
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t up = __shfl_up(inc, off);
-        if (lane >= off) inc += up;
-    }
-    if (lane == 63) wave_sum[wave] = inc;
-    __syncthreads();
-    uint32_t before = 0;
-    for (int w = 0; w < wave; ++w) before += wave_sum[w];
-    uint32_t run = before + inc - sum;
-    for (int32_t i = lo; i < hi; ++i) {
-        const uint32_t x = c[i];
-        c[i] = run;
-        run += x;
+    uint32_t carry = 0;
+    int set = 0;
+    for (int32_t base = 0; base < entries; base += 4096, set ^= 1) {
+        const int32_t i = base + tid * 4;
+        Counts4 v{};
+        if (i < entries) v = *(const Counts4 *)(c + i);
+        const uint32_t sum = v.x[0] + v.x[1] + v.x[2] + v.x[3];
+        uint32_t inc = sum;                               // inclusive scan over the wavefront
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t up = __shfl_up(inc, off);
+            if (lane >= off) inc += up;
+        }
+        if (lane == 63) wave_sum[set][wave] = inc;
+        __syncthreads();
+        uint32_t before = carry;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            const uint32_t ws = wave_sum[set][w];
+            if (w < wave) before += ws;
+            carry += ws;
+        }
+        uint32_t run = before + inc - sum;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t x = v.x[j];
+            v.x[j] = run;
+            run += x;
+        }
+        if (i < entries) *(Counts4 *)(c + i) = v;
     }
 }
 
@@ -314,6 +328,11 @@ __device__ __forceinline__ uint32_t rank_in_wavefront(uint32_t *counters, uint32
     return before + place;
 }
 
+// Where the scatter kernel keeps what belongs to digit d in its LDS tables: a permutation of
+// the digits that moves digits 32, 64, ... apart into different banks (the device id sits in
+// the upper bits of the leading digit, so the digits of one wavefront often differ by that).
+__device__ __forceinline__ uint32_t cell_of(uint32_t d) { return d ^ (d >> 5); }
+
 // Stable scatter of one tile.  Wavefront w owns items [w*1024, (w+1)*1024) of the tile
 // and takes them 64 at a time, so item order is (wavefront, round, lane).  Inside a
 // round, lanes with equal digits find each other by ballots; the last of them
@@ -332,7 +351,6 @@ __global__ __launch_bounds__(kSortThreads) void pct_scatter_kernel(const Key *__
     if (gate.closed()) return;
     extern __shared__ __align__(16) uint8_t sort_lds[];      // kSortTile keys, later kSortTile vertex numbers
     __shared__ uint32_t cnt[kSortWaves][kRadix];
-    __shared__ uint32_t tile_start[kRadix];
     __shared__ int32_t out_base[kRadix];
     __shared__ uint32_t wave_sum[kRadix / 64];
     Key *skey = (Key *)sort_lds;
@@ -359,15 +377,15 @@ __global__ __launch_bounds__(kSortThreads) void pct_scatter_kernel(const Key *__
     for (int r = 0; r < kSortRounds; ++r) {
         const int32_t t = wave * (kSortRounds * 64) + r * 64 + lane;
         const bool valid = t < tile_items;
-        loc[r] = rank_in_wavefront<RB>(cnt[wave], digit_of<RB>(key[r], shift), valid);
+        loc[r] = rank_in_wavefront<RB>(cnt[wave], cell_of(digit_of<RB>(key[r], shift)), valid);
     }
     __syncthreads();
     uint32_t run = 0, inc = 0;
     if (tid < kRadix) {   // thread d: wavefront bases, then the tile's digit starts
 #pragma unroll
         for (int w = 0; w < kSortWaves; ++w) {
-            const uint32_t c = cnt[w][tid];
-            cnt[w][tid] = run;
+            const uint32_t c = cnt[w][cell_of(tid)];
+            cnt[w][cell_of(tid)] = run;
             run += c;
         }
         inc = run;
@@ -382,16 +400,17 @@ __global__ __launch_bounds__(kSortThreads) void pct_scatter_kernel(const Key *__
         uint32_t before = 0;
         for (int w = 0; w < wave; ++w) before += wave_sum[w];
         const uint32_t start = before + inc - run;
-        tile_start[tid] = start;
-        out_base[tid] = (int32_t)starts[((int64_t)q * kRadix + tid) * tiles + tile] - (int32_t)start;
+        out_base[cell_of(tid)] = (int32_t)starts[((int64_t)q * kRadix + tid) * tiles + tile] - (int32_t)start;
+#pragma unroll
+        for (int w = 0; w < kSortWaves; ++w) cnt[w][cell_of(tid)] += start;   // now positions in the sorted tile
     }
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < kSortRounds; ++r) {
         const int32_t t = wave * (kSortRounds * 64) + r * 64 + lane;
         if (t < tile_items) {
-            const uint32_t d = digit_of<RB>(key[r], shift);
-            loc[r] = tile_start[d] + cnt[wave][d] + loc[r];
+            const uint32_t d = cell_of(digit_of<RB>(key[r], shift));
+            loc[r] = cnt[wave][d] + loc[r];
             skey[loc[r]] = key[r];
         }
     }
@@ -403,7 +422,7 @@ __global__ __launch_bounds__(kSortThreads) void pct_scatter_kernel(const Key *__
         dst[r] = 0;
         if (i < tile_items) {
             const Key kk = skey[i];
-            dst[r] = out_base[digit_of<RB>(kk, shift)] + i;
+            dst[r] = out_base[cell_of(digit_of<RB>(kk, shift))] + i;
             if (!LAST) keys_out[seg + dst[r]] = kk;
         }
     }
@@ -435,7 +454,9 @@ __global__ __launch_bounds__(kBuckets) void pct_bucket_check_kernel(const uint32
     const int32_t q = blockIdx.x, d = threadIdx.x;
     const uint32_t lo = starts[((int64_t)q * kBuckets + d) * tiles];
     const uint32_t hi = d + 1 < kBuckets ? starts[((int64_t)q * kBuckets + d + 1) * tiles] : (uint32_t)n;
-    if (hi - lo > (uint32_t)cap) atomicOr(flag, 1u);
+    // (one atomic per partition at most, none once the flag is up: they queue up on the one word)
+    const int any = __syncthreads_or(hi - lo > (uint32_t)cap);
+    if (any && threadIdx.x == 0 && *(volatile const uint32_t *)flag == 0) atomicOr(flag, 1u);
 }
 
 // One bucket, sorted on the low `bits` bits inside LDS: stable passes of 8 bits, each ranking
@@ -451,7 +472,6 @@ __global__ __launch_bounds__(kBucketThreads) void pct_bucket_sort_kernel(const u
     constexpr int kWaves = kBucketThreads / 64, kRadix = 256, kBucketCap = kBucketThreads * kSortRounds;
     __shared__ uint32_t slot[kBucketCap];                 // keys, then vertex numbers, in sorted order
     __shared__ uint32_t cnt[kWaves][kRadix];
-    __shared__ uint32_t digit_start[kRadix];
     __shared__ uint32_t wave_sum[kRadix / 64];
     if (gate.closed()) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -486,13 +506,14 @@ __global__ __launch_bounds__(kBucketThreads) void pct_bucket_sort_kernel(const u
             loc[r] = rank_in_wavefront<8>(cnt[wave], digit_of<8>(key[r], shift), valid);
         }
         __syncthreads();
-        uint32_t run = 0, inc = 0;
-        if (tid < kRadix) {   // thread dg: wavefront bases, then the bucket's digit starts
+        // thread dg: the digit's items per wavefront, the bucket's digit starts, then every
+        // wavefront's first position for the digit
+        uint32_t per_wave[kWaves], run = 0, inc = 0;
+        if (tid < kRadix) {
 #pragma unroll
             for (int w = 0; w < kWaves; ++w) {
-                const uint32_t c = cnt[w][tid];
-                cnt[w][tid] = run;
-                run += c;
+                per_wave[w] = cnt[w][tid];
+                run += per_wave[w];
             }
             inc = run;
             for (int off = 1; off < 64; off <<= 1) {
@@ -503,9 +524,13 @@ __global__ __launch_bounds__(kBucketThreads) void pct_bucket_sort_kernel(const u
         }
         __syncthreads();
         if (tid < kRadix) {
-            uint32_t before = 0;
-            for (int w = 0; w < wave; ++w) before += wave_sum[w];
-            digit_start[tid] = before + inc - run;
+            uint32_t first = inc - run;
+            for (int w = 0; w < wave; ++w) first += wave_sum[w];
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                cnt[w][tid] = first;
+                first += per_wave[w];
+            }
         }
         __syncthreads();
 #pragma unroll
@@ -513,7 +538,7 @@ __global__ __launch_bounds__(kBucketThreads) void pct_bucket_sort_kernel(const u
             const int32_t t = wave * (nr * 64) + r * 64 + lane;
             if (r < nr && t < items) {
                 const uint32_t dg = digit_of<8>(key[r], shift);
-                loc[r] = digit_start[dg] + cnt[wave][dg] + loc[r];
+                loc[r] = cnt[wave][dg] + loc[r];
                 if (!last) slot[loc[r]] = key[r];
             }
         }
@@ -562,19 +587,25 @@ __global__ void pct_segments_kernel(const int32_t *__restrict__ order, const uin
     seg[i] = lo;
 }
 
-// One digit pass of RB bits starting at bit `shift`.  counted: the counts are there already.
+// The launches of one digit pass of RB bits starting at bit `shift`: counts, scan, scatter.
 template <typename Key, int THREADS, int RB>
-int run_pass(const PctOrderLaunch &s, hipStream_t st, int shift, bool first, bool last, const Key *kin, Key *kout,
-             const int32_t *vin, int32_t *vout, Gate gate = Gate{nullptr, 0}, bool counted = false) {
-    constexpr int kTile = THREADS * kSortRounds;
-    const int32_t n = s.n, P = s.P;
-    const int32_t tiles = (n + kTile - 1) / kTile;
-    const dim3 grid((unsigned)((int64_t)tiles * P)), block(THREADS);     // one workgroup per (partition, tile)
-    const size_t lds = (size_t)kTile * sizeof(Key);
-    if (!counted)
-        hipLaunchKernelGGL((pct_count_kernel<Key, THREADS, RB>), grid, block, 0, st, kin, n, tiles, shift, s.counts,
-                           gate);
-    hipLaunchKernelGGL(pct_scan_kernel, dim3((unsigned)P), dim3(1024), 0, st, s.counts, (1 << RB) * tiles, gate);
+struct DigitPass {
+    static constexpr int kTile = THREADS * kSortRounds;
+    const PctOrderLaunch &s;
+    hipStream_t st;
+    int shift;
+    Gate gate;
+    int32_t tiles() const { return (s.n + kTile - 1) / kTile; }
+    dim3 grid() const { return dim3((unsigned)((int64_t)tiles() * s.P)); }     // one workgroup per (partition, tile)
+    void count(const Key *kin) const {
+        hipLaunchKernelGGL((pct_count_kernel<Key, THREADS, RB>), grid(), dim3(THREADS), 0, st, kin, s.n, tiles(), shift,
+                           s.counts, gate);
+    }
+    void scan() const {
+        hipLaunchKernelGGL(pct_scan_kernel, dim3((unsigned)s.P), dim3(1024), 0, st, s.counts, (1 << RB) * tiles(), gate);
+    }
+    int scatter(bool first, bool last, const Key *kin, Key *kout, const int32_t *vin, int32_t *vout) const {
+        const size_t lds = (size_t)kTile * sizeof(Key);
 #define CP_SCATTER(F, L)                                                                                   \
     do {                                                                                                   \
         auto kern = pct_scatter_kernel<Key, THREADS, RB, F, L>;                                            \
@@ -582,14 +613,25 @@ int run_pass(const PctOrderLaunch &s, hipStream_t st, int shift, bool first, boo
         if (lds > 64 * 1024 && hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
                                                    (int)lds) != hipSuccess)                                \
             return CP_ERR_HIP;                                                                             \
-        hipLaunchKernelGGL(kern, grid, block, lds, st, kin, vin, kout, vout, n, tiles, shift, s.counts, gate); \
+        hipLaunchKernelGGL(kern, grid(), dim3(THREADS), lds, st, kin, vin, kout, vout, s.n, tiles(), shift, s.counts, \
+                           gate);                                                                          \
     } while (0)
-    if (first && last) CP_SCATTER(true, true);
-    else if (first) CP_SCATTER(true, false);
-    else if (last) CP_SCATTER(false, true);
-    else CP_SCATTER(false, false);
+        if (first && last) CP_SCATTER(true, true);
+        else if (first) CP_SCATTER(true, false);
+        else if (last) CP_SCATTER(false, true);
+        else CP_SCATTER(false, false);
 #undef CP_SCATTER
-    return hipGetLastError() == hipSuccess ? CP_OK : CP_ERR_HIP;
+        return hipGetLastError() == hipSuccess ? CP_OK : CP_ERR_HIP;
+    }
+};
+
+template <typename Key, int THREADS, int RB>
+int run_pass(const PctOrderLaunch &s, hipStream_t st, int shift, bool first, bool last, const Key *kin, Key *kout,
+             const int32_t *vin, int32_t *vout, Gate gate) {
+    const DigitPass<Key, THREADS, RB> pass{s, st, shift, gate};
+    pass.count(kin);
+    pass.scan();
+    return pass.scatter(first, last, kin, kout, vin, vout);
 }
 
 // WIDE: 9-bit digits may be used (long tiles of 32-bit keys: the counters of a 64-bit
@@ -645,9 +687,10 @@ void launch_keys(const PctOrderLaunch &s, const KeyArgs &a, hipStream_t st) {
 #undef CP_KEYS
 }
 
-// The leading digit's pass, the bucket check, and both continuations: buckets sorted inside
-// LDS (flag 0), or the ordinary passes from the untouched keys (flag 1).  With rows of b per
-// partition one kernel writes the keys and counts their leading digit.
+// The leading digit's counts, the bucket check on their scan, and both continuations: the
+// leading digit's scatter and the buckets sorted inside LDS (flag 0), or the ordinary passes
+// from the untouched keys (flag 1).  With rows of b per partition one kernel writes the keys
+// and counts their leading digit.
 int run_bucket_sort(const PctOrderLaunch &s, const KeyArgs &a, hipStream_t st) {
     constexpr int kTile = kSortThreadsLong * kSortRounds;
     const int32_t tiles = (s.n + kTile - 1) / kTile;
@@ -668,16 +711,18 @@ int run_bucket_sort(const PctOrderLaunch &s, const KeyArgs &a, hipStream_t st) {
     } else {
         launch_keys(s, a, st);
     }
-    if (hipGetLastError() != hipSuccess) return CP_ERR_HIP;
-    int rc = run_pass<uint32_t, kSortThreadsLong, kBucketBits>(s, st, rem, /*first=*/true, /*last=*/false,
-                                                               (const uint32_t *)s.keys_a, (uint32_t *)s.keys_b, nullptr,
-                                                               s.vals_tmp, Gate{nullptr, 0u},
-                                                               /*counted=*/s.b_by_partition);
-    if (rc) return rc;
+    const DigitPass<uint32_t, kSortThreadsLong, kBucketBits> lead{s, st, rem, Gate{nullptr, 0u}};
+    if (!s.b_by_partition) lead.count((const uint32_t *)s.keys_a);
+    lead.scan();
     // the smaller workgroup (more of them per compute unit) where buckets of twice the average size fit it
     const bool small = 2 * ((int64_t)s.n / kBuckets + 1) <= kBucketCapSmall;
     hipLaunchKernelGGL(pct_bucket_check_kernel, dim3((unsigned)s.P), dim3(kBuckets), 0, st, s.counts, s.n, tiles,
                        small ? kBucketCapSmall : kBucketCapLarge, flag);
+    if (hipGetLastError() != hipSuccess) return CP_ERR_HIP;
+    const DigitPass<uint32_t, kSortThreadsLong, kBucketBits> lead_if_fit{s, st, rem, Gate{flag, 0u}};
+    const int rc = lead_if_fit.scatter(/*first=*/true, /*last=*/false, (const uint32_t *)s.keys_a, (uint32_t *)s.keys_b,
+                                       nullptr, s.vals_tmp);
+    if (rc) return rc;
     const dim3 bgrid((unsigned)((int64_t)s.P * kBuckets));
     if (small)
         hipLaunchKernelGGL(pct_bucket_sort_kernel<256>, bgrid, dim3(256), 0, st, (const uint32_t *)s.keys_b,

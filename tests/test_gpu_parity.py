@@ -443,6 +443,13 @@ def test_pct_order_buckets_of_the_leading_digit(gpu, oracle):
     w = make_workload("large_sparse", P=3, levels=299, width=301)         # rows that are not 16-byte aligned
     assert w.n % 4 != 0
     _check_pct_order(gpu, oracle, w)
+    # 31-bit keys (a path bound near 2^28, 8 devices): three passes inside a bucket, the first of
+    # them with too many key bits left to travel in one word with the vertex number
+    rng = np.random.default_rng(44)
+    n, level, src, dst = random_layered_dag(rng, [700] * 100, 1, 3, 2)
+    wide = _custom("wide-keys", n, src, dst, rng.integers(0, 2**20, size=len(src)), rng.integers(1, 2**21, size=n),
+                   [1] * 8, np.ones((8, 8), dtype=np.int64), rng.integers(0, 8, size=(3, n), dtype=np.uint8), level)
+    _check_pct_order(gpu, oracle, wide)
 
 
 def test_pct_order_buckets_too_large_for_lds(gpu, oracle):
