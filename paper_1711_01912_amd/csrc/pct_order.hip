@@ -11,12 +11,19 @@
 // saves a pass) takes three launches: per-tile digit counts, an exclusive scan of the counts per partition in
 // (digit, tile) order, and a stable scatter.
 //
-// Long partitions of 32-bit keys take a shorter way where they can: one such pass on the
-// LEADING 9 bits cuts a partition into 512 buckets, and a bucket of at most 4,096 or 8,192 items is
-// then sorted on the remaining bits entirely inside LDS by one workgroup (the same ranking,
-// LDS to LDS) and leaves as the finished list: every item crosses HBM twice less.  Whether
-// every bucket fits is only known on the device, so both continuations are launched and a flag
-// the bucket check sets lets one of them return at once.
+// Ranking inside a wavefront is done by ballots (one per key bit): lanes with equal digits
+// find each other, every lane reads its digit's counter, the last lane of a group moves it on.
+//
+// Long partitions of 32-bit keys take a shorter way where they can: a pass on the LEADING 9
+// bits cuts a partition into 512 buckets, and a bucket of at most 4,096 or 8,192 items is then
+// sorted on the remaining bits entirely inside LDS by one workgroup (the same ranking, LDS to
+// LDS) and leaves as the finished list: an item crosses HBM three times (keys written, the
+// leading digit's scatter, the bucket sort) whatever the key length.  Whether every bucket fits
+// is only known on the device, after the scan of the leading digit's counts.  So both
+// continuations are launched -- the leading digit's scatter and the bucket sort, or the
+// ordinary passes from the low digit up -- and a flag the bucket check sets lets the kernels of
+// one of them return at once.  With rows of b per partition, one kernel writes the keys and
+// counts their leading digit.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
