@@ -141,9 +141,51 @@ __device__ __forceinline__ long long min_over_lanes(long long x, int span) {
     return x;
 }
 
+// The same on 32-bit numbers over the first 16 lanes (WIDE: all 64), every step taken: lanes
+// past the devices hold the largest number and never win.
+template <bool WIDE>
+__device__ __forceinline__ uint32_t min_over_lanes_u32(uint32_t x) {
+    x = min(x, dpp_u32<0xB1>(x));
+    x = min(x, dpp_u32<0x4E>(x));
+    x = min(x, dpp_u32<0x141>(x));
+    x = min(x, dpp_u32<0x140>(x));
+    if (WIDE) {
+        x = min(x, (uint32_t)__shfl_xor((int)x, 16));
+        x = min(x, (uint32_t)__shfl_xor((int)x, 32));
+    }
+    return x;
+}
+
+// One batch of up to 64 vertices on relative 32-bit loads (see seed_greedy_kernel): lane j of
+// `dev` holds vertex j's device (0xff: not placed yet), of `cv` its c.  No branch but the one
+// that skips a placed vertex.
+template <bool MAGIC, bool WIDE>
+__device__ __forceinline__ void seed_batch_u32(uint32_t &rel, int32_t &dev, uint32_t cv, int cnt, bool mine,
+                                               const Magic &mg, uint64_t sp, int lane) {
+    for (int j = 0; j < cnt; ++j) {
+        if (__builtin_amdgcn_readlane(dev, j) != 0xff) continue;            // on the critical path
+        const uint32_t cj = (uint32_t)__builtin_amdgcn_readlane((int)cv, j);
+        const uint32_t w = MAGIC ? magic_div(cj, mg) : (uint32_t)plain_div((uint64_t)cj, sp);
+        const uint32_t val = mine ? rel + w : 0xffffffffu;
+        const uint32_t best = min_over_lanes_u32<WIDE>(val);
+        const int chosen = __ffsll((long long)__ballot(val == best)) - 1;  // lowest device on ties
+        rel = lane == chosen ? val : rel;
+        dev = lane == j ? chosen : dev;
+    }
+}
+
+__device__ __forceinline__ long long lane0_i64(long long x) {
+    return (long long)((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)x) |
+                       (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)x >> 32)) << 32);
+}
+
 // The load rule is a chain: every choice changes the loads the next one sees.  One
 // wavefront walks the vertices in order, lane d keeps load(d); 64 vertices are fetched
-// at a time and handed round with readlane.
+// at a time and handed round with readlane.  The chain is the wavefront's own instruction
+// latency, so a batch of 64 vertices runs on 32-bit numbers where it can: loads relative
+// to the smallest one, which stay below 2^32 - 1 through the batch when (largest - smallest
+// load) + 64 * (largest c of the batch) does -- an execution time is at most c.  The choices
+// are the same, a minimum and its ties do not move when every load loses the same amount.
 template <typename WT>
 __global__ __launch_bounds__(64) void seed_greedy_kernel(SeedArgs a) {
     const int lane = threadIdx.x;
@@ -175,16 +217,34 @@ __global__ __launch_bounds__(64) void seed_greedy_kernel(SeedArgs a) {
         const uint64_t cv = v < a.n ? (uint64_t)c[v] : 0;
         int32_t dev = v < a.n ? (int32_t)a.assign[v] : 0;
         const int32_t cnt = min(64, a.n - v0);
-        for (int j = 0; j < cnt; ++j) {
-            if (__builtin_amdgcn_readlane(dev, j) != 0xff) continue;            // on the critical path
-            const uint64_t cj = (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)cv, j) |
-                                (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(cv >> 32), j) << 32;
-            const long long val = mine ? load + cost(cj) : LLONG_MAX;
-            // the devices sit in lanes 0 .. k-1: a reduction over the next power of two covers them
-            const long long best = min_over_lanes(val, span);
-            const int chosen = __ffsll((long long)__ballot(val == best)) - 1;      // lowest device on ties
-            if (lane == chosen) load = val;
-            if (lane == j) dev = chosen;
+        // smallest and largest load, largest c of the batch (the same in every lane)
+        const long long low = lane0_i64(min_over_lanes(mine ? load : LLONG_MAX, span));
+        const long long high = -lane0_i64(min_over_lanes(mine ? -load : LLONG_MAX, span));
+        unsigned long long cmax = cv;
+        for (int off = 32; off > 0; off >>= 1) cmax = max(cmax, (unsigned long long)__shfl_xor((long long)cmax, off));
+        const bool narrow = cmax < (1ull << 32) && (unsigned long long)(high - low) + 64 * cmax < 0xffffffffull;
+        if (narrow) {
+            uint32_t rel = mine ? (uint32_t)(load - low) : 0xffffffffu;
+            if (a.magic) {
+                if (span <= 16) seed_batch_u32<true, false>(rel, dev, (uint32_t)cv, cnt, mine, mg, sp, lane);
+                else seed_batch_u32<true, true>(rel, dev, (uint32_t)cv, cnt, mine, mg, sp, lane);
+            } else {
+                if (span <= 16) seed_batch_u32<false, false>(rel, dev, (uint32_t)cv, cnt, mine, mg, sp, lane);
+                else seed_batch_u32<false, true>(rel, dev, (uint32_t)cv, cnt, mine, mg, sp, lane);
+            }
+            if (mine) load = low + (long long)rel;
+        } else {
+            for (int j = 0; j < cnt; ++j) {
+                if (__builtin_amdgcn_readlane(dev, j) != 0xff) continue;
+                const uint64_t cj = (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)cv, j) |
+                                    (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(cv >> 32), j) << 32;
+                const long long val = mine ? load + cost(cj) : LLONG_MAX;
+                // the devices sit in lanes 0 .. k-1: a reduction over the next power of two covers them
+                const long long best = min_over_lanes(val, span);
+                const int chosen = __ffsll((long long)__ballot(val == best)) - 1;
+                if (lane == chosen) load = val;
+                if (lane == j) dev = chosen;
+            }
         }
         if (v < a.n) a.assign[v] = (uint8_t)dev;
     }
