@@ -225,7 +225,7 @@ def main():
             seed = cpe.cp_seed_partition(g, w.speeds)
             torch.cuda.synchronize()
             t1 = time.perf_counter()
-            found = cpe.cp_search(g, seed, w.speeds, w.bandwidth, max_moves=3, chunk=256)
+            found = cpe.cp_search(g, seed, w.speeds, w.bandwidth, max_moves=3, chunk=1024)
             torch.cuda.synchronize()
             t2 = time.perf_counter()
             extras["seed_partition"] = {"ms": (t1 - t0) * 1e3}

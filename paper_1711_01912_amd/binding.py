@@ -616,7 +616,7 @@ def cp_seed_partition(graph: CpGraph, speeds, *, stream=None):
     return out
 
 
-def cp_search(graph: CpGraph, start, speeds, bandwidth, *, pairs=None, pins=None, max_moves=1000, chunk=256,
+def cp_search(graph: CpGraph, start, speeds, bandwidth, *, pairs=None, pins=None, max_moves=1000, chunk=1024,
               stream=None):
     """cp_search on torch tensors: ``start`` is a uint8 CUDA tensor [n].  Returns a dict
     with ``assignment`` (new tensor), ``cp_trace`` (int64 numpy, CP of the start and after
