@@ -450,6 +450,13 @@ def test_pct_order_buckets_of_the_leading_digit(gpu, oracle):
     wide = _custom("wide-keys", n, src, dst, rng.integers(0, 2**20, size=len(src)), rng.integers(1, 2**21, size=n),
                    [1] * 8, np.ones((8, 8), dtype=np.int64), rng.integers(0, 8, size=(3, n), dtype=np.uint8), level)
     _check_pct_order(gpu, oracle, wide)
+    # 18-bit keys (two devices, a path bound of 17 bits): the shortest keys on the bucket path,
+    # nine bits left for the buckets, the second pass inside a bucket sorts on one bit
+    rng = np.random.default_rng(45)
+    n, level, src, dst = random_layered_dag(rng, [700] * 100, 1, 3, 2)
+    narrow = _custom("narrow-keys", n, src, dst, rng.integers(0, 600, size=len(src)), rng.integers(1, 1200, size=n),
+                     [1, 2], np.ones((2, 2), dtype=np.int64), rng.integers(0, 2, size=(3, n), dtype=np.uint8), level)
+    _check_pct_order(gpu, oracle, narrow)
 
 
 def test_pct_order_buckets_too_large_for_lds(gpu, oracle):
