@@ -93,6 +93,33 @@ __global__ __launch_bounds__(256) void transpose_kernel(const uint8_t *__restric
     }
 }
 
+// The same with four ids per load and per store, for n and P multiples of four and 4-byte
+// aligned arrays: a tile of 64 partitions x 256 vertices, a row of it read as 64 words, a
+// vertex's 64 ids written as 16 words, each put together from four rows of the tile.
+__global__ __launch_bounds__(256) void transpose4_kernel(const uint8_t *__restrict__ in, uint8_t *__restrict__ out,
+                                                         int32_t n, int32_t P) {
+    __shared__ uint32_t tile[64][65];
+    const int64_t v0 = (int64_t)blockIdx.x * 256, p0 = (int64_t)blockIdx.y * 64;
+    const int lane = threadIdx.x & 63, row0 = threadIdx.x >> 6;
+    for (int r = row0; r < 64; r += 4) {
+        const int64_t p = p0 + r, v = v0 + 4 * lane;
+        if (p < P && v < n) tile[r][lane] = *(const uint32_t *)(in + p * n + v);
+    }
+    __syncthreads();
+    const uint8_t *bytes = (const uint8_t *)&tile[0][0];
+    for (int it = 0; it < 16; ++it) {
+        const int idx = it * 256 + threadIdx.x;
+        const int vl = idx >> 4, pq = idx & 15;
+        const int64_t v = v0 + vl, p = p0 + 4 * pq;
+        if (v < n && p < P) {
+            const uint32_t w = (uint32_t)bytes[(4 * pq + 0) * 260 + vl] | (uint32_t)bytes[(4 * pq + 1) * 260 + vl] << 8 |
+                               (uint32_t)bytes[(4 * pq + 2) * 260 + vl] << 16 |
+                               (uint32_t)bytes[(4 * pq + 3) * 260 + vl] << 24;
+            *(uint32_t *)(out + v * P + p) = w;
+        }
+    }
+}
+
 // ---------------------------------------------------------------- wave-column sweep
 
 struct ColumnArgs {
@@ -244,8 +271,8 @@ __global__ __launch_bounds__(256) void mask_kernel(const Tick *__restrict__ b,
             vb[u] = 0; vt[u] = 0; c[u] = -1;
             if (live[u]) {
                 const size_t at = (size_t)r * cols + i;
-                vt[u] = tl[at];
-                vb[u] = b[at];
+                vt[u] = __builtin_nontemporal_load(tl + at);      // read once, far larger than the caches
+                vb[u] = __builtin_nontemporal_load(b + at);
                 c[u] = cp[BY_PARTITION ? r : (int64_t)i];
             }
         }
@@ -489,6 +516,53 @@ __global__ __launch_bounds__(256) void gather_assign_kernel(const int32_t *__res
     }
     if (worst >= (uint32_t)k) *status = CP_STATUS_BAD_DEVICE_ID;
     *(uint4 *)(out + q * row_len + i16) = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// The same for rows of at most kGatherLdsRow device ids that lie one byte apart: a workgroup
+// copies its partition's row into LDS once and gathers from there (64 scattered one-byte
+// loads from memory per instruction are what bounds the kernel above).
+constexpr int32_t kGatherLdsRow = 60 * 1024;
+__global__ __launch_bounds__(256) void gather_assign_lds_kernel(const int32_t *__restrict__ gmap, int64_t row_len,
+                                                                const uint8_t *__restrict__ assign,
+                                                                int64_t a_stride_p, int32_t n, int32_t k,
+                                                                uint8_t *__restrict__ out, int32_t *status) {
+    extern __shared__ __align__(16) uint8_t ids_lds[];
+    const int64_t q = blockIdx.x;
+    const uint8_t *row = assign + q * a_stride_p;
+    const int tid = threadIdx.x;
+    if (((uintptr_t)row & 15) == 0) {
+        const int32_t n16 = n / 16;
+        for (int32_t i = tid; i < n16; i += 256) ((uint4 *)ids_lds)[i] = ((const uint4 *)row)[i];
+        for (int32_t i = n16 * 16 + tid; i < n; i += 256) ids_lds[i] = row[i];
+    } else {
+        for (int32_t i = tid; i < n; i += 256) ids_lds[i] = row[i];
+    }
+    __syncthreads();
+    uint32_t worst = 0;
+    for (int64_t i16 = (int64_t)tid * 16; i16 < row_len; i16 += 256 * 16) {     // row_len is a multiple of 64
+        int4 v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = *(const int4 *)(gmap + i16 + 4 * j);
+        uint32_t w[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t p0 = v[j].x >= 0 ? ids_lds[v[j].x] : 0;
+            uint32_t p1 = v[j].y >= 0 ? ids_lds[v[j].y] : 0;
+            uint32_t p2 = v[j].z >= 0 ? ids_lds[v[j].z] : 0;
+            uint32_t p3 = v[j].w >= 0 ? ids_lds[v[j].w] : 0;
+            const uint32_t m = max(max(p0, p1), max(p2, p3));
+            if (m >= (uint32_t)k) {
+                if (p0 >= (uint32_t)k) p0 = 0;
+                if (p1 >= (uint32_t)k) p1 = 0;
+                if (p2 >= (uint32_t)k) p2 = 0;
+                if (p3 >= (uint32_t)k) p3 = 0;
+            }
+            worst = max(worst, m);
+            w[j] = p0 | (p1 << 8) | (p2 << 16) | (p3 << 24);
+        }
+        *(uint4 *)(out + q * row_len + i16) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    if (worst >= (uint32_t)k) *status = CP_STATUS_BAD_DEVICE_ID;
 }
 
 struct WindowArgs {
@@ -1188,6 +1262,12 @@ bool window_config(const WindowDir &d, int32_t k, size_t tick_bytes, size_t lds_
 int launch_gather_assign(const SweepLaunch &s, uint8_t *out, void *stream) {
     const WindowDir &dir = *s.win;
     const int64_t row_len = (int64_t)dir.ticks * dir.wpad;
+    if (s.a_stride_v == 1 && s.n <= kGatherLdsRow) {
+        hipLaunchKernelGGL(gather_assign_lds_kernel, dim3((unsigned)s.P), dim3(256), (size_t)((s.n + 15) & ~15),
+                           (hipStream_t)stream, (const int32_t *)(s.blob + dir.gmap_off), row_len, s.assign,
+                           s.a_stride_p, s.n, s.k, out, s.status);
+        return hip_ok(hipGetLastError());
+    }
     const int64_t chunks = (row_len + 4095) / 4096;
     if (chunks > 65535) return CP_ERR_SIZE;
     hipLaunchKernelGGL(gather_assign_kernel, dim3((unsigned)s.P, (unsigned)chunks), dim3(256), 0,
@@ -1233,6 +1313,11 @@ int launch_ranks(const void *b, const void *tl, const void *c, bool narrow, int 
 }
 
 int launch_transpose(const uint8_t *in, uint8_t *out, int32_t n, int32_t P, void *stream) {
+    if (n % 4 == 0 && P % 4 == 0 && ((uintptr_t)in & 3) == 0 && ((uintptr_t)out & 3) == 0) {
+        const dim3 grid4((unsigned)((n + 255) / 256), (unsigned)((P + 63) / 64));
+        hipLaunchKernelGGL(transpose4_kernel, grid4, dim3(256), 0, (hipStream_t)stream, in, out, n, P);
+        return hip_ok(hipGetLastError());
+    }
     dim3 grid((unsigned)((n + 63) / 64), (unsigned)((P + 63) / 64));
     hipLaunchKernelGGL(transpose_kernel, grid, dim3(256), 0, (hipStream_t)stream, in, out, n, P);
     return hip_ok(hipGetLastError());
