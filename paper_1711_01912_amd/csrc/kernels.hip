@@ -136,6 +136,7 @@ struct ColumnArgs {
     int32_t P, ncol, k, count;
 };
 
+constexpr int kColumnUnroll = 4;      // neighbours whose loads are in flight together
 template <typename Tick, typename WT, bool MAGIC, bool TSWEEP, bool HUB>
 __global__ __launch_bounds__(HUB ? kHubWaves * 64 : 256) void column_level_kernel(ColumnArgs a) {
     extern __shared__ uint64_t lds[];
@@ -188,21 +189,38 @@ __global__ __launch_bounds__(HUB ? kHubWaves * 64 : 256) void column_level_kerne
         int32_t my_u = 0;
         WT my_t = 0;
         if (lane < cnt) { my_u = a.idx[base + lane]; my_t = wt[base + lane]; }
-        for (int j = 0; j < cnt; ++j) {
-            const int32_t u = wave_bcast<int32_t>(my_u, j);
-            const WT te = wave_bcast<WT>(my_t, j);
+        // four neighbours at a time: their device ids and values are four independent pairs of
+        // loads in flight per lane (one pair at a time leaves the memory system a third busy);
+        // slots past the row's end repeat its last neighbour and are left out of the maximum
+        for (int j = 0; j < cnt; j += kColumnUnroll) {
+            int32_t u[kColumnUnroll];
+            WT te[kColumnUnroll], cu[kColumnUnroll];
+            uint32_t pu[kColumnUnroll];
+            Tick vu[kColumnUnroll];
+#pragma unroll
+            for (int i = 0; i < kColumnUnroll; ++i) {
+                const int jj = min(j + i, cnt - 1);
+                u[i] = wave_bcast<int32_t>(my_u, jj);
+                te[i] = wave_bcast<WT>(my_t, jj);
+            }
             if (live) {
-                uint32_t pu = pT[(size_t)u * P];
-                pu = min(pu, (uint32_t)(k - 1));
-                Tick vu = val[(size_t)u * P];
-                if (TSWEEP) {   // neighbour is a predecessor: its finish time is tl(u) + w(u)
-                    const WT cu = cw[u];
-                    vu += MAGIC ? (Tick)magic_div((uint32_t)cu, vtab_m[pu])
-                                : (Tick)plain_div((uint64_t)cu, (uint64_t)vtab_g[pu]);
+#pragma unroll
+                for (int i = 0; i < kColumnUnroll; ++i) {
+                    pu[i] = pT[(size_t)u[i] * P];
+                    vu[i] = val[(size_t)u[i] * P];
+                    if (TSWEEP) cu[i] = cw[u[i]];
                 }
-                const Tick x = MAGIC ? (Tick)magic_div((uint32_t)te, etab_m[pv * k + pu])
-                                     : (Tick)plain_div((uint64_t)te, (uint64_t)etab_g[pv * k + pu]);
-                acc = max(acc, (Tick)(vu + x));
+#pragma unroll
+                for (int i = 0; i < kColumnUnroll; ++i) {
+                    const uint32_t pd = min(pu[i], (uint32_t)(k - 1));
+                    Tick t = vu[i];
+                    if (TSWEEP)   // neighbour is a predecessor: its finish time is tl(u) + w(u)
+                        t += MAGIC ? (Tick)magic_div((uint32_t)cu[i], vtab_m[pd])
+                                   : (Tick)plain_div((uint64_t)cu[i], (uint64_t)vtab_g[pd]);
+                    const Tick x = MAGIC ? (Tick)magic_div((uint32_t)te[i], etab_m[pv * k + pd])
+                                         : (Tick)plain_div((uint64_t)te[i], (uint64_t)etab_g[pv * k + pd]);
+                    if (j + i < cnt) acc = max(acc, (Tick)(t + x));
+                }
             }
         }
     }
