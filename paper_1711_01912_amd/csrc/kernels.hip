@@ -302,36 +302,46 @@ __global__ __launch_bounds__(256) void mask_kernel(const Tick *__restrict__ b,
     }
 }
 
-// The same for rows per partition of 32-bit ticks whose rows start on 16-byte boundaries
-// (n a multiple of 4): blockIdx.y is the partition, a lane takes four consecutive vertices with
-// one 16-byte load from either array, a wavefront kMaskTrips x 256 vertices.  The four match
+// The same for rows of 32-bit ticks that start on 16-byte boundaries (a row length that is a
+// multiple of 4), rows per partition or per vertex: a lane takes four consecutive columns with
+// one 16-byte load from either array, a wavefront kMaskTrips x 256 columns.  The four match
 // bits of a lane are bits 4 (lane mod 16) .. +3 of mask word (lane / 16) of the trip's four
 // words; the sixteen lanes of a word fold with shuffles.  Both arrays are read once and far
 // exceed the caches: the loads carry the non-temporal hint, and a wavefront takes one trip
 // (6.2 TB/s on the large sparse batch; 5.1 TB/s with plain loads and four trips).
 constexpr int kMaskTrips = 1;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+template <bool BY_PARTITION>
 __global__ __launch_bounds__(256) void mask_rows_kernel(const int32_t *__restrict__ b, const int32_t *__restrict__ tl,
                                                         const int64_t *__restrict__ cp, int32_t n, int32_t ncol,
                                                         uint64_t *mask) {
+    // n: the length of a row (vertices with rows per partition, else partitions).  The row's
+    // number sits in whichever grid dimension takes it: there may be millions of vertices.
     const int lane = threadIdx.x & 63;
-    const int32_t r = blockIdx.y;
-    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int64_t v0 = wave * (256 * kMaskTrips);                    // first vertex of this wavefront
+    const int32_t r = BY_PARTITION ? blockIdx.y : blockIdx.x;
+    const int64_t wave = (int64_t)(BY_PARTITION ? blockIdx.x : blockIdx.y) * 4 + (threadIdx.x >> 6);
+    const int64_t v0 = wave * (256 * kMaskTrips);                    // first column of this wavefront
     if (v0 >= n) return;
-    const int64_t c = cp[r];
+    const int64_t c_row = BY_PARTITION ? cp[r] : 0;
     const uint4 *b4 = (const uint4 *)(b + (size_t)r * n), *t4 = (const uint4 *)(tl + (size_t)r * n);
     uint4 vb[kMaskTrips], vt[kMaskTrips];
+    int64_t c[kMaskTrips][4];
 #pragma unroll
     for (int u = 0; u < kMaskTrips; ++u) {
         const int64_t v = v0 + 256 * u + 4 * lane;
         vb[u] = make_uint4(0, 0, 0, 0);
         vt[u] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) c[u][j] = c_row;
         if (v < n) {                                                 // n is a multiple of 4: all four or none
             const u32x4 xt = __builtin_nontemporal_load((const u32x4 *)t4 + (v >> 2));
             const u32x4 xb = __builtin_nontemporal_load((const u32x4 *)b4 + (v >> 2));
             vt[u] = make_uint4(xt.x, xt.y, xt.z, xt.w);
             vb[u] = make_uint4(xb.x, xb.y, xb.z, xb.w);
+            if (!BY_PARTITION) {                                     // a column is a partition: its own CP
+#pragma unroll
+                for (int j = 0; j < 4; ++j) c[u][j] = cp[v + j];
+            }
         }
     }
 #pragma unroll
@@ -339,10 +349,10 @@ __global__ __launch_bounds__(256) void mask_rows_kernel(const int32_t *__restric
         const int64_t v = v0 + 256 * u + 4 * lane;
         uint32_t nib = 0;
         if (v < n) {
-            nib = (uint32_t)((int64_t)(int32_t)vt[u].x + (int32_t)vb[u].x == c) |
-                  (uint32_t)((int64_t)(int32_t)vt[u].y + (int32_t)vb[u].y == c) << 1 |
-                  (uint32_t)((int64_t)(int32_t)vt[u].z + (int32_t)vb[u].z == c) << 2 |
-                  (uint32_t)((int64_t)(int32_t)vt[u].w + (int32_t)vb[u].w == c) << 3;
+            nib = (uint32_t)((int64_t)(int32_t)vt[u].x + (int32_t)vb[u].x == c[u][0]) |
+                  (uint32_t)((int64_t)(int32_t)vt[u].y + (int32_t)vb[u].y == c[u][1]) << 1 |
+                  (uint32_t)((int64_t)(int32_t)vt[u].z + (int32_t)vb[u].z == c[u][2]) << 2 |
+                  (uint32_t)((int64_t)(int32_t)vt[u].w + (int32_t)vb[u].w == c[u][3]) << 3;
         }
         uint64_t word = (uint64_t)nib << (4 * (lane & 15));
         word |= __shfl_xor(word, 1);
@@ -1492,12 +1502,20 @@ int launch_mask(const void *b, const void *tl, const int64_t *cp, int32_t n, int
     const int64_t tasks = (int64_t)rows * ncol;
     const dim3 grid((unsigned)std::max<int64_t>(1, std::min<int64_t>((tasks + 15) / 16, 256 * 32))), block(256);
     hipStream_t st = (hipStream_t)stream;
-    if (by_partition && tick_bytes == 4 && n % 4 == 0 && ((uintptr_t)b % 16) == 0 && ((uintptr_t)tl % 16) == 0 &&
-        P <= 65535) {
+    // rows of 32-bit ticks that start on 16-byte boundaries: 16 bytes per load
+    if (tick_bytes == 4 && cols % 4 == 0 && ((uintptr_t)b % 16) == 0 && ((uintptr_t)tl % 16) == 0) {
         const int64_t per_block = 4 * 256 * kMaskTrips;
-        const dim3 g2((unsigned)((n + per_block - 1) / per_block), (unsigned)P);
-        hipLaunchKernelGGL(mask_rows_kernel, g2, block, 0, st, (const int32_t *)b, (const int32_t *)tl, cp, n, ncol, mask);
-        return hip_ok(hipGetLastError());
+        const int64_t chunks = (cols + per_block - 1) / per_block;
+        if (by_partition && rows <= 65535) {
+            hipLaunchKernelGGL(mask_rows_kernel<true>, dim3((unsigned)chunks, (unsigned)rows), block, 0, st,
+                               (const int32_t *)b, (const int32_t *)tl, cp, cols, ncol, mask);
+            return hip_ok(hipGetLastError());
+        }
+        if (!by_partition && cols >= 256 && chunks <= 65535) {      // (a wavefront per 256 partitions of a vertex)
+            hipLaunchKernelGGL(mask_rows_kernel<false>, dim3((unsigned)rows, (unsigned)chunks), block, 0, st,
+                               (const int32_t *)b, (const int32_t *)tl, cp, cols, ncol, mask);
+            return hip_ok(hipGetLastError());
+        }
     }
 #define CP_MASK(TICK, BYP)                                                                              \
     hipLaunchKernelGGL((mask_kernel<TICK, BYP>), grid, block, 0, st, (const TICK *)b, (const TICK *)tl, cp, \
