@@ -14,6 +14,9 @@
 // Ranking inside a wavefront is done by ballots (one per key bit): lanes with equal digits
 // find each other, every lane reads its digit's counter, the last lane of a group moves it on.
 //
+// Partitions of at most 20,480 vertices with 32-bit keys are sorted by one workgroup each, entirely
+// inside LDS (the bucket kernel below with the whole partition as its bucket).
+//
 // Long partitions of 32-bit keys take a shorter way where they can: a pass on the LEADING 9
 // bits cuts a partition into 512 buckets, and a bucket of at most 4,096 or 8,192 items is then
 // sorted on the remaining bits entirely inside LDS by one workgroup (the same ranking, LDS to
@@ -466,25 +469,29 @@ __global__ __launch_bounds__(kBuckets) void pct_bucket_check_kernel(const uint32
     if (any && threadIdx.x == 0 && *(volatile const uint32_t *)flag == 0) atomicOr(flag, 1u);
 }
 
+// WHOLE: the "bucket" is a whole partition (at most kBucketThreads * kRounds vertices), its keys
+// in vertex order in keys_in, sorted on all `bits` key bits: short partitions need no pass over
+// HBM at all.
 // One bucket, sorted on the low `bits` bits inside LDS: stable passes of 8 bits, each ranking
 // the items as the scatter kernel does (wavefront w owns items [w*1024, (w+1)*1024) of the
 // bucket in (round, lane) order) and moving keys and vertex numbers through one LDS buffer;
 // the vertex numbers of the last pass go straight out.
-template <int kBucketThreads>
+template <int kBucketThreads, int kRounds, bool WHOLE>
 __global__ __launch_bounds__(kBucketThreads) void pct_bucket_sort_kernel(const uint32_t *__restrict__ keys_in,
                                                                          const int32_t *__restrict__ vals_in,
                                                                          int32_t *__restrict__ vals_out, int32_t n,
                                                                          int32_t tiles, int bits,
                                                                          const uint32_t *__restrict__ starts, Gate gate) {
-    constexpr int kWaves = kBucketThreads / 64, kRadix = 256, kBucketCap = kBucketThreads * kSortRounds;
-    __shared__ uint32_t slot[kBucketCap];                 // keys, then vertex numbers, in sorted order
+    constexpr int kWaves = kBucketThreads / 64, kRadix = 256, kBucketCap = kBucketThreads * kRounds;
+    extern __shared__ __align__(16) uint32_t slot[];      // kBucketCap keys, then vertex numbers, in sorted order
     __shared__ uint32_t cnt[kWaves][kRadix];
     __shared__ uint32_t wave_sum[kRadix / 64];
     if (gate.closed()) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int32_t q = (int32_t)(blockIdx.x / kBuckets), d = (int32_t)(blockIdx.x % kBuckets);
-    const uint32_t lo = starts[((int64_t)q * kBuckets + d) * tiles];
-    const uint32_t hi = d + 1 < kBuckets ? starts[((int64_t)q * kBuckets + d + 1) * tiles] : (uint32_t)n;
+    const int32_t q = WHOLE ? (int32_t)blockIdx.x : (int32_t)(blockIdx.x / kBuckets);
+    const int32_t d = WHOLE ? 0 : (int32_t)(blockIdx.x % kBuckets);
+    const uint32_t lo = WHOLE ? 0u : starts[((int64_t)q * kBuckets + d) * tiles];
+    const uint32_t hi = WHOLE || d + 1 == kBuckets ? (uint32_t)n : starts[((int64_t)q * kBuckets + d + 1) * tiles];
     const int32_t items = (int32_t)(hi - lo);
     if (items <= 0 || items > kBucketCap) return;         // (larger buckets: the other continuation runs)
     const int64_t at = (int64_t)q * n + lo;
@@ -492,21 +499,21 @@ __global__ __launch_bounds__(kBucketThreads) void pct_bucket_sort_kernel(const u
     // [w * nr * 64, (w + 1) * nr * 64) of the bucket)
     const int nr = (items + kBucketThreads - 1) / kBucketThreads;
 
-    uint32_t key[kSortRounds], loc[kSortRounds];
-    int32_t val[kSortRounds];
+    uint32_t key[kRounds], loc[kRounds];
+    int32_t val[kRounds];
 #pragma unroll
-    for (int r = 0; r < kSortRounds; ++r) {
+    for (int r = 0; r < kRounds; ++r) {
         const int32_t t = wave * (nr * 64) + r * 64 + lane;
         const bool valid = r < nr && t < items;
         key[r] = valid ? keys_in[at + t] : 0u;
-        val[r] = valid ? vals_in[at + t] : 0;
+        val[r] = WHOLE ? t : (valid ? vals_in[at + t] : 0);       // WHOLE: the keys come in vertex order
     }
     for (int shift = 0; shift < bits; shift += 8) {
         const bool last = shift + 8 >= bits;
         for (int i = tid; i < kWaves * kRadix; i += kBucketThreads) (&cnt[0][0])[i] = 0;
         __syncthreads();
 #pragma unroll
-        for (int r = 0; r < kSortRounds; ++r) {
+        for (int r = 0; r < kRounds; ++r) {
             if (r >= nr) continue;           // (uniform)
             const int32_t t = wave * (nr * 64) + r * 64 + lane;
             const bool valid = t < items;
@@ -541,7 +548,7 @@ __global__ __launch_bounds__(kBucketThreads) void pct_bucket_sort_kernel(const u
         }
         __syncthreads();
 #pragma unroll
-        for (int r = 0; r < kSortRounds; ++r) {
+        for (int r = 0; r < kRounds; ++r) {
             const int32_t t = wave * (nr * 64) + r * 64 + lane;
             if (r < nr && t < items) {
                 const uint32_t dg = digit_of<8>(key[r], shift);
@@ -552,14 +559,14 @@ __global__ __launch_bounds__(kBucketThreads) void pct_bucket_sort_kernel(const u
         if (!last) {          // the keys come back in sorted order, then the vertex numbers the same way
             __syncthreads();
 #pragma unroll
-            for (int r = 0; r < kSortRounds; ++r) {
+            for (int r = 0; r < kRounds; ++r) {
                 const int32_t t = wave * (nr * 64) + r * 64 + lane;
                 if (r < nr && t < items) key[r] = slot[t];
             }
             __syncthreads();
         }
 #pragma unroll
-        for (int r = 0; r < kSortRounds; ++r) {
+        for (int r = 0; r < kRounds; ++r) {
             const int32_t t = wave * (nr * 64) + r * 64 + lane;
             if (r < nr && t < items) slot[loc[r]] = (uint32_t)val[r];
         }
@@ -568,7 +575,7 @@ __global__ __launch_bounds__(kBucketThreads) void pct_bucket_sort_kernel(const u
             for (int32_t i = tid; i < items; i += kBucketThreads) vals_out[at + i] = (int32_t)slot[i];
         } else {
 #pragma unroll
-            for (int r = 0; r < kSortRounds; ++r) {
+            for (int r = 0; r < kRounds; ++r) {
                 const int32_t t = wave * (nr * 64) + r * 64 + lane;
                 if (r < nr && t < items) val[r] = (int32_t)slot[t];
             }
@@ -732,15 +739,40 @@ int run_bucket_sort(const PctOrderLaunch &s, const KeyArgs &a, hipStream_t st) {
     if (rc) return rc;
     const dim3 bgrid((unsigned)((int64_t)s.P * kBuckets));
     if (small)
-        hipLaunchKernelGGL(pct_bucket_sort_kernel<256>, bgrid, dim3(256), 0, st, (const uint32_t *)s.keys_b,
+        hipLaunchKernelGGL((pct_bucket_sort_kernel<256, kSortRounds, false>), bgrid, dim3(256),
+                           (size_t)kBucketCapSmall * 4, st, (const uint32_t *)s.keys_b,
                            (const int32_t *)s.vals_tmp, s.order_out, s.n, tiles, rem, (const uint32_t *)s.counts,
                            Gate{flag, 0u});
     else
-        hipLaunchKernelGGL(pct_bucket_sort_kernel<512>, bgrid, dim3(512), 0, st, (const uint32_t *)s.keys_b,
+        hipLaunchKernelGGL((pct_bucket_sort_kernel<512, kSortRounds, false>), bgrid, dim3(512),
+                           (size_t)kBucketCapLarge * 4, st, (const uint32_t *)s.keys_b,
                            (const int32_t *)s.vals_tmp, s.order_out, s.n, tiles, rem, (const uint32_t *)s.counts,
                            Gate{flag, 0u});
     if (hipGetLastError() != hipSuccess) return CP_ERR_HIP;
     return run_sort<uint32_t, kSortThreadsLong, true>(s, st, Gate{flag, 1u});
+}
+
+// Partitions of at most 20,480 vertices with 32-bit keys: one workgroup sorts a whole partition
+// inside LDS.
+constexpr int kWholeRoundsMax = 20, kWholeMax = kSortThreadsLong * kWholeRoundsMax;
+template <int THREADS, int ROUNDS>
+int launch_whole(const PctOrderLaunch &s, hipStream_t st) {
+    auto kern = pct_bucket_sort_kernel<THREADS, ROUNDS, true>;
+    const size_t lds = (size_t)THREADS * ROUNDS * 4;
+    // more than 64 KB of dynamic LDS has to be asked for
+    if (lds > 64 * 1024 &&
+        hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        return CP_ERR_HIP;
+    hipLaunchKernelGGL(kern, dim3((unsigned)s.P), dim3(THREADS), lds, st, (const uint32_t *)s.keys_a,
+                       (const int32_t *)nullptr, s.order_out, s.n, 0, s.key_bits, (const uint32_t *)nullptr,
+                       Gate{nullptr, 0u});
+    return hip_status(hipGetLastError());
+}
+int run_whole_sort(const PctOrderLaunch &s, hipStream_t st) {
+    if (s.n <= 256 * kSortRounds) return launch_whole<256, kSortRounds>(s, st);
+    if (s.n <= 512 * kSortRounds) return launch_whole<512, kSortRounds>(s, st);
+    if (s.n <= 1024 * kSortRounds) return launch_whole<1024, kSortRounds>(s, st);
+    return launch_whole<1024, kWholeRoundsMax>(s, st);
 }
 
 }  // namespace
@@ -770,11 +802,14 @@ int launch_pct_order(const PctOrderLaunch &s, void *stream) {
     // capacity on average (so that an uneven spread still fits), at least two passes to save
     const bool buckets = sort_threads(s.n) == kSortThreadsLong && s.key_bytes == 4 && s.key_bits > kBucketBits + 8 &&
                          (int64_t)s.n <= (int64_t)kBuckets * kBucketCapLarge / 4 && (int64_t)s.P * kBuckets < (1ll << 31);
+    const bool whole = s.key_bytes == 4 && s.n <= kWholeMax;
     if (!buckets) {
         launch_keys(s, a, st);
         if (hipGetLastError() != hipSuccess) return CP_ERR_HIP;
     }
-    if (buckets)
+    if (whole)
+        rc = run_whole_sort(s, st);
+    else if (buckets)
         rc = run_bucket_sort(s, a, st);
     else if (sort_threads(s.n) == kSortThreadsLong)
         rc = s.key_bytes == 4 ? run_sort<uint32_t, kSortThreadsLong, true>(s, st)

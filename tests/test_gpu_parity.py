@@ -405,8 +405,15 @@ def test_pct_order_small(gpu, oracle):
 
 
 def test_pct_order_several_tiles_and_a_ragged_tail(gpu, oracle):
-    _check_pct_order(gpu, oracle, make_workload("inception", P=33))          # 19,772 = 4 tiles + 3,388
+    # partitions of up to 20,480 vertices are sorted inside LDS by one workgroup: 19,772 takes 20
+    # items per thread, 8,196 takes 9 of 16
+    _check_pct_order(gpu, oracle, make_workload("inception", P=33))
     _check_pct_order(gpu, oracle, make_workload("comm_heavy", P=9, levels=4, width=2049))
+    # above that and below 65,536 vertices: digit passes over tiles of 4,096 items, here 6 + 3,424
+    w = make_workload("comm_heavy", P=5, levels=4, width=7000)
+    assert 20480 < w.n < 65536
+    _check_pct_order(gpu, oracle, w)
+    _check_pct_order(gpu, oracle, w, layout=1)
 
 
 def test_pct_order_many_ties_and_one_device(gpu, oracle):
