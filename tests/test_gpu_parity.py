@@ -58,6 +58,14 @@ def test_tiny_all_variants(gpu, oracle):
     assert e.value.code == -12
 
 
+@pytest.mark.parametrize("P", [300, 258, 1028])
+def test_batches_that_end_inside_a_mask_word(gpu, oracle, P):
+    """Batches that are a multiple of four but not of 64 (the 16-byte mask kernel's last word of a
+    vertex-major row holds 44 / 2 / 4 partitions; the assignments are transposed four ids at a
+    time) and one that is not a multiple of four (258: the plain kernels), both plans and layouts."""
+    _check(gpu, oracle, make_workload("mlp", P=P), layouts=(0, 1))
+
+
 def test_window_plan_with_64_bit_ticks(gpu, oracle):
     """A raw path bound past 2^31 with 32-bit weights: the window plan runs on int64 ticks."""
     w = make_workload("large_sparse", P=40, levels=300, width=40)
