@@ -36,6 +36,8 @@ struct ColumnDir {
     size_t idx_off = 0;     // int32 [m]     neighbour vertex (head for the b sweep, tail for the t sweep)
     size_t wt_off = 0;      // uint32 or int64 [m]  t(e) in this CSR's order
     size_t order_off = 0;   // int32 [n]     vertices in sweep order, long rows first inside a level
+    size_t rows_off = 0;    // int32 [n][4]  {vertex, first edge, end of its edges, 0} in sweep order: what a
+                            //               wavefront of the wave-column plan needs to start, in one load
     size_t lvl_off = 0;     // int32 [L][4]  {first position, hub rows, rows, 0} per level in sweep order
     // per level, in sweep order
     std::vector<int32_t> lvl_begin, lvl_hubs, lvl_count;

@@ -83,6 +83,15 @@ void pack_column_dir(BlobWriter &w, int32_t n, int64_t m, bool narrow, const Csr
     }
     dir.order_off = w.reserve(sizeof(int32_t) * (size_t)n);
     std::memcpy(w.at<int32_t>(dir.order_off), order.data(), sizeof(int32_t) * (size_t)n);
+    dir.rows_off = w.reserve(sizeof(int32_t) * 4 * (size_t)n);
+    int32_t *rows = w.at<int32_t>(dir.rows_off);
+    for (int32_t i = 0; i < n; ++i) {
+        const int32_t v = order[i];
+        rows[4 * (size_t)i] = v;
+        rows[4 * (size_t)i + 1] = csr.ptr[v];
+        rows[4 * (size_t)i + 2] = csr.ptr[v + 1];
+        rows[4 * (size_t)i + 3] = 0;
+    }
     const size_t L = dir.lvl_begin.size();
     dir.lvl_off = w.reserve(sizeof(int32_t) * 4 * std::max<size_t>(L, 1));
     int32_t *lvl = w.at<int32_t>(dir.lvl_off);

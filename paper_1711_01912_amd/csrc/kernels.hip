@@ -123,11 +123,10 @@ __global__ __launch_bounds__(256) void transpose4_kernel(const uint8_t *__restri
 // ---------------------------------------------------------------- wave-column sweep
 
 struct ColumnArgs {
-    const int32_t *ptr;
     const int32_t *idx;
     const void *wt;
     const void *c;
-    const int32_t *order;   // already offset to the first vertex of this launch
+    const int4 *rows;       // {vertex, first edge, end of edges, 0} per position, offset to this launch's first
     const uint8_t *pT;      // [n][P]
     void *val;              // [n][P] ticks: b (b sweep) or tl (t sweep)
     const void *edge_tab;   // Magic[k*k] or int64[k*k] for this sweep
@@ -144,23 +143,21 @@ __global__ __launch_bounds__(HUB ? kHubWaves * 64 : 256) void column_level_kerne
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int k = a.k;
     const int ntab = MAGIC ? k * k + k : 0;
-    if (MAGIC) {
-        const uint64_t *e = (const uint64_t *)a.edge_tab, *v = (const uint64_t *)a.vert_tab;
-        for (int i = tid; i < k * k; i += blockDim.x) lds[i] = e[i];
-        for (int i = tid; i < k; i += blockDim.x) lds[k * k + i] = v[i];
-        __syncthreads();
-    }
     const Magic *etab_m = (const Magic *)lds;
     const Magic *vtab_m = etab_m + k * k;
     const int64_t *etab_g = (const int64_t *)a.edge_tab;
     const int64_t *vtab_g = (const int64_t *)a.vert_tab;
 
+    // What the wavefront needs to start (its row's record, its vertex's device ids, the first 64
+    // neighbours) is asked for before the cost tables are copied into LDS, so that the copy and
+    // its barrier overlap those round trips instead of preceding them.
     const int64_t task = HUB ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * 4 + wave;
     const int64_t ntasks = (int64_t)a.count * a.ncol;
     const bool task_live = task < ntasks;
     const int32_t vi = task_live ? (int32_t)(task / a.ncol) : 0;
     const int32_t col = task_live ? (int32_t)(task % a.ncol) : 0;
-    const int32_t v = a.order[vi];
+    const int4 rec = a.rows[vi];          // one load instead of the vertex number and then its row bounds
+    const int32_t v = rec.x;
     const int32_t q = col * 64 + lane;
     const int32_t P = a.P;
     const bool live = task_live && q < P;
@@ -170,25 +167,37 @@ __global__ __launch_bounds__(HUB ? kHubWaves * 64 : 256) void column_level_kerne
     const WT *cw = (const WT *)a.c;
 
     uint32_t pv = 0;
-    if (live) {
-        pv = pT[(size_t)v * P];
-        if (pv >= (uint32_t)k) { *a.status = CP_STATUS_BAD_DEVICE_ID; pv = 0; }
-    }
+    if (live) pv = pT[(size_t)v * P];
 
-    int32_t e0 = a.ptr[v], e1 = a.ptr[v + 1];
+    int32_t e0 = rec.y, e1 = rec.z;
     if (HUB) {  // this wavefront's share of the row
         int32_t len = e1 - e0, chunk = (len + kHubWaves - 1) / kHubWaves;
         e0 = min(e1, e0 + wave * chunk);
         e1 = min(e1, e0 + chunk);
     }
     if (!task_live) e1 = e0;
+    int32_t first_u = 0;
+    WT first_t = 0;
+    if (e0 + lane < e1) { first_u = a.idx[e0 + lane]; first_t = wt[e0 + lane]; }
+
+    if (MAGIC) {
+        const uint64_t *e = (const uint64_t *)a.edge_tab, *vt = (const uint64_t *)a.vert_tab;
+        for (int i = tid; i < k * k; i += blockDim.x) lds[i] = e[i];
+        for (int i = tid; i < k; i += blockDim.x) lds[k * k + i] = vt[i];
+        __syncthreads();
+    }
+    if (live && pv >= (uint32_t)k) { *a.status = CP_STATUS_BAD_DEVICE_ID; pv = 0; }
 
     Tick acc = 0;
     for (int32_t base = e0; base < e1; base += 64) {
         const int32_t cnt = min(64, e1 - base);
-        int32_t my_u = 0;
-        WT my_t = 0;
-        if (lane < cnt) { my_u = a.idx[base + lane]; my_t = wt[base + lane]; }
+        int32_t my_u = first_u;
+        WT my_t = first_t;
+        if (base != e0) {
+            my_u = 0;
+            my_t = 0;
+            if (lane < cnt) { my_u = a.idx[base + lane]; my_t = wt[base + lane]; }
+        }
         // four neighbours at a time: their device ids and values are four independent pairs of
         // loads in flight per lane (one pair at a time leaves the memory system a third busy);
         // slots past the row's end repeat its last neighbour and are left out of the maximum
@@ -1081,7 +1090,6 @@ int launch_column_sweep_t(const SweepLaunch &s, hipStream_t st, int32_t *launche
     const int ncol = (s.P + 63) / 64;
     const size_t tab_bytes = MAGIC ? sizeof(Magic) * ((size_t)s.k * s.k + s.k) : 0;
     ColumnArgs a{};
-    a.ptr = (const int32_t *)(s.blob + dir.ptr_off);
     a.idx = (const int32_t *)(s.blob + dir.idx_off);
     a.wt = s.blob + dir.wt_off;
     a.c = s.blob + s.c_off;
@@ -1091,12 +1099,12 @@ int launch_column_sweep_t(const SweepLaunch &s, hipStream_t st, int32_t *launche
     a.vert_tab = s.vert_tab;
     a.status = s.status;
     a.P = s.P; a.ncol = ncol; a.k = s.k;
-    const int32_t *order = (const int32_t *)(s.blob + dir.order_off);
+    const int4 *rows = (const int4 *)(s.blob + dir.rows_off);
     int32_t count = 0;
     for (int l = 0; l < L; ++l) {
         const int32_t hubs = dir.lvl_hubs[l], total = dir.lvl_count[l];
         if (hubs > 0) {
-            a.order = order + dir.lvl_begin[l];
+            a.rows = rows + dir.lvl_begin[l];
             a.count = hubs;
             const int64_t blocks = (int64_t)hubs * ncol;
             const size_t lds_bytes = tab_bytes + sizeof(Tick) * 64 * kHubWaves;
@@ -1105,7 +1113,7 @@ int launch_column_sweep_t(const SweepLaunch &s, hipStream_t st, int32_t *launche
             ++count;
         }
         if (total > hubs) {
-            a.order = order + dir.lvl_begin[l] + hubs;
+            a.rows = rows + dir.lvl_begin[l] + hubs;
             a.count = total - hubs;
             const int64_t tasks = (int64_t)(total - hubs) * ncol;
             hipLaunchKernelGGL((column_level_kernel<Tick, WT, MAGIC, TSWEEP, false>),
