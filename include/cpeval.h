@@ -83,7 +83,8 @@ extern "C" {
 #define CP_PLAN_AUTO             0
 #define CP_PLAN_WAVE_COLUMN      1   /* one wavefront = one vertex x 64 partitions; one launch per level */
 #define CP_PLAN_RESIDENT_WINDOW  2   /* one workgroup = one partition; recent levels kept in LDS; one launch per sweep, or
-                                        one for both sweeps where a workgroup of each fits a compute unit side by side */
+                                        one for both sweeps where a workgroup of each fits a compute unit side by side
+                                        or all workgroups of both sweeps find room on the chip at once */
 #define CP_PLAN_SHARED_WINDOW_2  3   /* as 2, but one workgroup = 2 partitions behind one graph stream */
 #define CP_PLAN_SHARED_WINDOW_4  4   /* ... 4 partitions */
 #define CP_PLAN_STREAMED_WINDOW  6   /* as 2, but the compute wavefronts fetch the graph themselves, two ticks ahead, into

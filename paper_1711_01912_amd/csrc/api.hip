@@ -630,9 +630,19 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
     // more than the overlap gains, 4.9 against 3.8 ms)
     bool paired = use == CP_PLAN_RESIDENT_WINDOW && (blevel_out || cp_out) && tlevel_out && tick_dtype == CP_TICK_I32 &&
                   by_partition &&
-                  window_wg_per_cu(cfg_b) == 1.0 && window_wg_per_cu(cfg_t) == 1.0 &&
                   window_pair_config(p.win_b, p.win_t, k, device_window_lds_limit(), pr_b, pr_t);
-    if (paired) {
+    // ... or where every workgroup of both sweeps finds room on the chip at once (small graphs,
+    // moderate batches): then the two chains simply run side by side
+    const bool alone = window_wg_per_cu(cfg_b) == 1.0 && window_wg_per_cu(cfg_t) == 1.0;
+    const bool roomy = paired && !alone &&
+                       2.0 * std::ceil((double)batch / 256.0) <= std::min(window_wg_per_cu(pr_b), window_wg_per_cu(pr_t));
+    paired = paired && (alone || roomy);
+    if (paired && roomy) {
+        const double mask_pass_us = mask_out ? 5.0 + (double)p.n * batch * (2.0 * tick_dtype + 0.125) / 4.0e6 : 0.0;
+        const double b_us = window_sweep_us(p.win_b, cfg_b, batch), t_us = window_sweep_us(p.win_t, cfg_t, batch);
+        const double seq_us = b_us + (fuse_mask ? window_sweep_us(p.win_t, cfg_tm, batch) * 1.06 : t_us + mask_pass_us);
+        paired = 1.2 * std::max(b_us, t_us) + mask_pass_us < seq_us;
+    } else if (paired) {
         const double mask_pass_us = mask_out ? 5.0 + (double)p.n * batch * (2.0 * tick_dtype + 0.125) / 4.0e6 : 0.0;
         const double b_us = window_sweep_us(p.win_b, cfg_b, batch), t_us = window_sweep_us(p.win_t, cfg_t, batch);
         const double seq_us = b_us + (fuse_mask ? window_sweep_us(p.win_t, cfg_tm, batch) * 1.06 : t_us + mask_pass_us);
