@@ -50,8 +50,11 @@ inline int sort_threads(int32_t n) { return n >= kSortLongFrom ? kSortThreadsLon
 // Passes over a key of `bits` bits: digits of 8 bits, of up to 9 where allowed.
 inline int pct_passes(int bits, bool wide) { return (bits + (wide ? 9 : 8) - 1) / (wide ? 9 : 8); }
 
-// the bucket path cuts a partition by its leading kBucketBits bits
+// the bucket path cuts a partition by its leading kBucketBits bits, in tiles of kLeadThreads x 16
+// items: half the long tile, so that two workgroups of the leading scatter share a compute unit
+// and one's ranking overlaps the other's loads and stores
 constexpr int kBucketBits = 9, kBuckets = 1 << kBucketBits;
+constexpr int kLeadThreads = 512;
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? CP_OK : CP_ERR_HIP; }
 
@@ -199,11 +202,11 @@ __global__ __launch_bounds__(kSortThreads) void pct_count_kernel(const Key *__re
 struct alignas(16) Keys4 { uint32_t x[4]; };
 template <typename Tick> struct alignas(16) Ticks4 { Tick x[4]; };
 template <typename Tick, bool VEC>
-__global__ __launch_bounds__(kSortThreadsLong) void pct_keys_count_kernel(KeyArgs a, int32_t tiles, int shift,
+__global__ __launch_bounds__(kLeadThreads) void pct_keys_count_kernel(KeyArgs a, int32_t tiles, int shift,
                                                                           uint32_t *__restrict__ counts) {
-    constexpr int kRadix = 1 << kBucketBits, kTile = kSortThreadsLong * kSortRounds;
+    constexpr int kRadix = 1 << kBucketBits, kTile = kLeadThreads * kSortRounds;
     constexpr int kQuadRounds = kSortRounds / 4;
-    __shared__ Histogram<kSortThreadsLong, kRadix> hist;
+    __shared__ Histogram<kLeadThreads, kRadix> hist;
     const int tid = threadIdx.x;
     const int32_t tile = (int32_t)(blockIdx.x % (uint32_t)tiles), q = (int32_t)(blockIdx.x / (uint32_t)tiles);
     hist.clear(tid);
@@ -216,7 +219,7 @@ __global__ __launch_bounds__(kSortThreadsLong) void pct_keys_count_kernel(KeyArg
     bool bad_b = false, bad_id = false;
 #pragma unroll
     for (int r = 0; r < kQuadRounds; ++r) {
-        const int32_t i0 = base + (r * kSortThreadsLong + tid) * 4;
+        const int32_t i0 = base + (r * kLeadThreads + tid) * 4;
         Ticks4<Tick> bv{};
         uint32_t dv = 0;
         if (VEC) {
@@ -252,7 +255,7 @@ __global__ __launch_bounds__(kSortThreadsLong) void pct_keys_count_kernel(KeyArg
     if (bad_b) atomicOr(a.status, CP_STATUS_B_OUT_OF_RANGE);
 #pragma unroll
     for (int r = 0; r < kQuadRounds; ++r) {
-        const int32_t i0 = base + (r * kSortThreadsLong + tid) * 4;
+        const int32_t i0 = base + (r * kLeadThreads + tid) * 4;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             if (i0 + j < a.n) hist.add(tid, digit_of<kBucketBits>(key[r][j], shift));
@@ -706,13 +709,13 @@ void launch_keys(const PctOrderLaunch &s, const KeyArgs &a, hipStream_t st) {
 // from the untouched keys (flag 1).  With rows of b per partition one kernel writes the keys
 // and counts their leading digit.
 int run_bucket_sort(const PctOrderLaunch &s, const KeyArgs &a, hipStream_t st) {
-    constexpr int kTile = kSortThreadsLong * kSortRounds;
+    constexpr int kTile = kLeadThreads * kSortRounds;
     const int32_t tiles = (s.n + kTile - 1) / kTile;
     uint32_t *flag = s.counts + (size_t)s.P * kMaxRadix * (size_t)tiles;     // behind the counts
     hipLaunchKernelGGL(pct_flag_clear_kernel, dim3(1), dim3(1), 0, st, flag);
     const int rem = s.key_bits - kBucketBits;
     if (s.b_by_partition) {
-        const dim3 grid((unsigned)((int64_t)tiles * s.P)), block(kSortThreadsLong);
+        const dim3 grid((unsigned)((int64_t)tiles * s.P)), block(kLeadThreads);
         const bool vec = s.n % 4 == 0 && s.a_stride_v == 1 && s.a_stride_p % 4 == 0 && (uintptr_t)s.assign % 4 == 0 &&
                          (uintptr_t)s.b % 16 == 0 && (uintptr_t)s.keys_a % 16 == 0;
         if (s.tick_bytes == 4) {
@@ -725,7 +728,7 @@ int run_bucket_sort(const PctOrderLaunch &s, const KeyArgs &a, hipStream_t st) {
     } else {
         launch_keys(s, a, st);
     }
-    const DigitPass<uint32_t, kSortThreadsLong, kBucketBits> lead{s, st, rem, Gate{nullptr, 0u}};
+    const DigitPass<uint32_t, kLeadThreads, kBucketBits> lead{s, st, rem, Gate{nullptr, 0u}};
     if (!s.b_by_partition) lead.count((const uint32_t *)s.keys_a);
     lead.scan();
     // the smaller workgroup (more of them per compute unit) where buckets of twice the average size fit it
@@ -733,7 +736,7 @@ int run_bucket_sort(const PctOrderLaunch &s, const KeyArgs &a, hipStream_t st) {
     hipLaunchKernelGGL(pct_bucket_check_kernel, dim3((unsigned)s.P), dim3(kBuckets), 0, st, s.counts, s.n, tiles,
                        small ? kBucketCapSmall : kBucketCapLarge, flag);
     if (hipGetLastError() != hipSuccess) return CP_ERR_HIP;
-    const DigitPass<uint32_t, kSortThreadsLong, kBucketBits> lead_if_fit{s, st, rem, Gate{flag, 0u}};
+    const DigitPass<uint32_t, kLeadThreads, kBucketBits> lead_if_fit{s, st, rem, Gate{flag, 0u}};
     const int rc = lead_if_fit.scatter(/*first=*/true, /*last=*/false, (const uint32_t *)s.keys_a, (uint32_t *)s.keys_b,
                                        nullptr, s.vals_tmp);
     if (rc) return rc;
@@ -778,7 +781,8 @@ int run_whole_sort(const PctOrderLaunch &s, hipStream_t st) {
 }  // namespace
 
 int32_t pct_sort_tiles(int32_t n) {
-    const int tile = sort_threads(n) * kSortRounds;
+    // (long partitions: the leading pass of the bucket path has the most tiles)
+    const int tile = (n >= kSortLongFrom ? kLeadThreads : kSortThreadsShort) * kSortRounds;
     return (n + tile - 1) / tile;
 }
 size_t pct_counts_bytes(int32_t n, int32_t P) {
