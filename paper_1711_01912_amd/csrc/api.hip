@@ -194,6 +194,10 @@ double shared_sweep_us(const WindowDir &d, int groups, int32_t batch) {
     return rounds * (double)d.ticks * (groups == 4 ? 2.03 : 1.33) * (0.58 + 0.03 * d.smax);
 }
 
+// A mask pass of its own streams b and tl once: 6.2 - 6.5 TB/s for 32-bit ticks in aligned rows
+// (measured), 4.4 for the plain kernel.
+constexpr double kMaskPassBytesPerUs = 6.0e6;
+
 // Both sweeps under the wave-column plan.
 double column_plan_us(const Packed &p, int32_t batch, size_t tick_bytes) {
     auto column_us = [&](const ColumnDir &d) {
@@ -201,9 +205,9 @@ double column_plan_us(const Packed &p, int32_t batch, size_t tick_bytes) {
         for (size_t l = 0; l < d.lvl_count.size(); ++l)
             launches += (d.lvl_hubs[l] > 0) + (d.lvl_count[l] > d.lvl_hubs[l]);
         const double bytes = ((double)p.n + (double)p.m) * batch * (1.0 + (double)tick_bytes);
-        // (measured: 6.3 us per launch; the gathers of a sweep at 5.4 - 6.3 TB/s with four
+        // (measured: 6.3 us per launch; the gathers of a sweep at 6.0 - 7.0 TB/s with four
         // neighbours' loads in flight per lane)
-        return launches * 6.3 + bytes / 6.0e6;
+        return launches * 6.3 + bytes / 6.5e6;
     };
     return column_us(p.col_b) + column_us(p.col_t);
 }
@@ -491,7 +495,7 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
             // of their own over b and tl (else their t sweep writes it)
             const bool sh_mask_pass = mask_out && !(out_layout == CP_OUT_PARTITION_MAJOR && tick_dtype == CP_TICK_I32 &&
                                                     p.win_t.far_cap == 0);
-            const double mask_us = sh_mask_pass ? 5.0 + (double)p.n * batch * (2.0 * tick_dtype + 0.125) / 4.0e6 : 0.0;
+            const double mask_us = sh_mask_pass ? 5.0 + (double)p.n * batch * (2.0 * tick_dtype + 0.125) / kMaskPassBytesPerUs : 0.0;
             double window_us = 0.0;
             const int wplan = choose_window_plan(p, k, (size_t)tick_dtype, device_window_lds_limit(), cfg_b, cfg_t, batch,
                                                  mask_us, &sh_b, &sh_t, tabs.tab4_ok,
@@ -613,7 +617,7 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
         // slices the fixed part outweighs it (5,271 vertices in 251 ticks, 16,384 partitions:
         // +0.70 ms against 0.25 ms).  The same holds where fewer partitions would fit a compute
         // unit with it.
-        const double mask_pass_us = 5.0 + (double)p.n * batch * (2.0 * tick_dtype + 0.125) / 3.0e6;
+        const double mask_pass_us = 5.0 + (double)p.n * batch * (2.0 * tick_dtype + 0.125) / kMaskPassBytesPerUs;
         fuse_mask = p.win_t.smax >= 4 &&
                     window_sweep_us(p.win_t, cfg_tm, batch) <= window_sweep_us(p.win_t, cfg_t, batch) + mask_pass_us;
     }
@@ -638,12 +642,12 @@ static int eval_run(const cp_graph *g, int32_t batch, int32_t k,
                        2.0 * std::ceil((double)batch / 256.0) <= std::min(window_wg_per_cu(pr_b), window_wg_per_cu(pr_t));
     paired = paired && (alone || roomy);
     if (paired && roomy) {
-        const double mask_pass_us = mask_out ? 5.0 + (double)p.n * batch * (2.0 * tick_dtype + 0.125) / 4.0e6 : 0.0;
+        const double mask_pass_us = mask_out ? 5.0 + (double)p.n * batch * (2.0 * tick_dtype + 0.125) / kMaskPassBytesPerUs : 0.0;
         const double b_us = window_sweep_us(p.win_b, cfg_b, batch), t_us = window_sweep_us(p.win_t, cfg_t, batch);
         const double seq_us = b_us + (fuse_mask ? window_sweep_us(p.win_t, cfg_tm, batch) * 1.06 : t_us + mask_pass_us);
         paired = 1.2 * std::max(b_us, t_us) + mask_pass_us < seq_us;
     } else if (paired) {
-        const double mask_pass_us = mask_out ? 5.0 + (double)p.n * batch * (2.0 * tick_dtype + 0.125) / 4.0e6 : 0.0;
+        const double mask_pass_us = mask_out ? 5.0 + (double)p.n * batch * (2.0 * tick_dtype + 0.125) / kMaskPassBytesPerUs : 0.0;
         const double b_us = window_sweep_us(p.win_b, cfg_b, batch), t_us = window_sweep_us(p.win_t, cfg_t, batch);
         const double seq_us = b_us + (fuse_mask ? window_sweep_us(p.win_t, cfg_tm, batch) * 1.06 : t_us + mask_pass_us);
         paired = 0.66 * (b_us + t_us) + mask_pass_us < seq_us;
